@@ -1,0 +1,175 @@
+/*
+ * modulora.h -- C ABI of the MI355X (gfx950) ModuLoRA linear-layer library.
+ *
+ * The layer (ModuLoRA, arXiv 2309.16119, Section 3.1 eq. (3) and Figure 1) is a
+ * frozen low-precision base weight plus a high-precision low-rank adapter:
+ *
+ *     forward          Y  = X What^T + s (X A) B
+ *     backward, input  dX = dY What  + s (dY B^T) A^T
+ *     backward, LoRA   dA = s X^T (dY B^T),   dB = s (X A)^T dY
+ *
+ * What [d_out][d_in] is never stored in high precision.  It is re-materialized
+ * tile by tile inside the kernels, in the forward and again in the backward pass
+ * (Section 3.1.2: recompute instead of save), from b-bit codes with a per-group
+ * scale and zero point (Section 2.2 eq. (2), in integer-zero-point form):
+ *
+ *     What[n][k] = bf16_rne( (q[n][k] - zeros[k/g][n]) * scales[k/g][n] )
+ *
+ * Naming: K = d_in, N = d_out, M = tokens, r = LoRA rank, g = group_size,
+ * s = lora_scale (alpha / r).  The paper's adapter factors B, A^T are called
+ * A [K][r] and B [r][N] here.
+ *
+ * General rules for every entry point
+ *   - Every data pointer is a DEVICE pointer (HIP global memory) unless it says
+ *     "host".  The caller owns all buffers; the library never allocates, frees or
+ *     keeps device memory and holds no per-layer state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is
+ *     only enqueued on that stream; no call synchronizes with the host.
+ *   - Inputs are read-only.  Outputs are fully overwritten unless stated.
+ *   - Arguments are validated on the host before any HIP call, so every
+ *     MODULORA_ERR_* below except MODULORA_ERR_HIP can be produced without a GPU.
+ *     Nothing aborts and nothing throws across this boundary.
+ *   - 16-bit floats travel as uint16_t bit patterns: X, dY, Y, dX, What are
+ *     bfloat16; scales are IEEE binary16.
+ *   - `workspace` is scratch device memory of at least modulora_workspace_bytes()
+ *     bytes, 256-byte aligned, contents irrelevant on entry and undefined on exit.
+ *     Two calls that share a workspace must be ordered on one stream.
+ */
+#ifndef MODULORA_H
+#define MODULORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MODULORA_OK = 0,
+    MODULORA_ERR_NULL = 1,      /* a required pointer is NULL                          */
+    MODULORA_ERR_SHAPE = 2,     /* d_in / d_out / M out of range or not divisible      */
+    MODULORA_ERR_BITS = 3,      /* bits not in {2, 3, 4}                               */
+    MODULORA_ERR_GROUP = 4,     /* group_size not a multiple of 32 dividing d_in       */
+    MODULORA_ERR_ALIGN = 5,     /* a pointer is not 16-byte aligned                    */
+    MODULORA_ERR_RANK = 6,      /* r < 0, r > 64, or r > 0 with A or B NULL            */
+    MODULORA_ERR_WORKSPACE = 7, /* workspace NULL, misaligned or too small             */
+    MODULORA_ERR_HIP = 8        /* a HIP call failed (launch error, wrong device, ...) */
+} modulora_status;
+
+/*
+ * The frozen quantized base weight of one linear layer (Section 2.2 eq. (2): codes,
+ * zeros and scales as produced by a black-box quantizer).  All pointers are device
+ * pointers, borrowed for the duration of a call, never written.
+ *
+ *   qweight [d_in*bits/32][d_out] uint32, d_out contiguous.  The codes of output
+ *           column n form one bitstream along d_in: code k occupies stream bits
+ *           [k*bits, k*bits+bits); stream bit j is bit (j mod 32), LSB = bit 0, of
+ *           word qweight[j / 32][n].  (3-bit: 32 codes per 3 words; codes 10 and 21
+ *           of each 32 straddle a word boundary.)
+ *   scales  [d_in/group_size][d_out] binary16 bit patterns (finite, normal).
+ *   zeros   [d_in/group_size][d_out] uint8 integer zero points, used as stored.
+ *
+ * Requirements: bits in {2,3,4}; group_size a multiple of 32 that divides d_in
+ * (group_size == d_in is the one-scale-per-row case of the paper); d_out a
+ * multiple of 8; 32 <= d_in, 8 <= d_out, both <= 2^20.
+ */
+typedef struct {
+    int32_t d_in;
+    int32_t d_out;
+    int32_t bits;
+    int32_t group_size;
+    const uint32_t *qweight;
+    const uint16_t *scales;
+    const uint8_t *zeros;
+} modulora_qweight;
+
+/* Human-readable name of a status code (static storage, host pointer). */
+const char *modulora_status_string(int status);
+
+/*
+ * Bytes of workspace that modulora_fwd / modulora_bwd_input / modulora_bwd_lora need
+ * for this layer at M tokens and rank r (the maximum over the three).  Returns 0 when
+ * the arguments are invalid.  Never touches the GPU.
+ */
+size_t modulora_workspace_bytes(const modulora_qweight *w, int32_t M, int32_t r);
+
+/*
+ * Test-only: materialize the whole weight, What[n][k] as defined above, into
+ * What_bf16 [d_out][d_in] (bfloat16 bits, d_in contiguous).  This is the paper's
+ * "weight materialization" (Figure 1, hatW = dequantize(hatWq, z, s)); the product
+ * path never calls it -- it exists so that unpacking and dequantization can be
+ * checked bit for bit.
+ */
+int modulora_dequant(const modulora_qweight *w, uint16_t *What_bf16, void *stream);
+
+/*
+ * Forward (Section 3.1 eq. (3), Figure 1 ModuLoRALinear.forward, without bias):
+ *     Y[m][n] = sum_k X[m][k] What[n][k] + lora_scale * sum_j XA[m][j] B[j][n],
+ *     XA = X A.
+ *   X  [M][d_in] bfloat16          A [d_in][r] float32      B [r][d_out] float32
+ *   Y  [M][d_out] bfloat16 (out)   XA [M][r] float32 (out, may be NULL)
+ * r == 0 (A, B ignored) is the plain low-precision linear map LPLinear.forward.
+ * fp32 accumulation; one round-to-nearest-even to bfloat16 at the end.
+ */
+int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M,
+                 const float *A, const float *B, int32_t r, float lora_scale,
+                 uint16_t *Y, float *XA,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward with respect to the input (Figure 1 LPLinear.backward: the weight is
+ * re-materialized, grad_input = grad_output What; plus the adapter path of
+ * Section 3.1.1, d y~/d y = What^T + B A^T in the paper's naming):
+ *     dX[m][k] = sum_n dY[m][n] What[n][k] + lora_scale * sum_j dYBt[m][j] A[k][j],
+ *     dYBt = dY B^T.
+ *   dY [M][d_out] bfloat16          dX [M][d_in] bfloat16 (out)
+ *   dYBt [M][r] float32 (out, may be NULL)
+ * No gradient flows to qweight, scales or zeros.
+ */
+int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M,
+                       const float *A, const float *B, int32_t r, float lora_scale,
+                       uint16_t *dX, float *dYBt,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Adapter gradients (Section 3.1.1: they do not involve the quantized weight):
+ *     dA[k][j] = lora_scale * sum_m X[m][k] dYBt[m][j]
+ *     dB[j][n] = lora_scale * sum_m XA[m][j] dY[m][n]
+ *   XA, dYBt [M][r] float32: the hand-offs written by modulora_fwd and
+ *       modulora_bwd_input; either may be NULL and is then recomputed here from
+ *       (X, A) or (dY, B).
+ *   dA [d_in][r], dB [r][d_out] float32.  accumulate == 0 overwrites them,
+ *       accumulate != 0 adds to their current contents (gradient accumulation over
+ *       micro-batches).  The reduction over tokens uses fp32 atomic adds, so the
+ *       low-order bits may differ from run to run.
+ * r must be >= 1.
+ */
+int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float lora_scale,
+                      const uint16_t *X, const uint16_t *dY, const float *A, const float *B,
+                      const float *XA, const float *dYBt,
+                      float *dA, float *dB, int32_t accumulate,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Per-kernel timing for benchmarks.  Between modulora_profile_begin() and
+ * modulora_profile_end() every kernel the library launches is bracketed by HIP
+ * events on the stream it is launched on.  modulora_profile_end() waits for those
+ * events (it synchronizes with the device -- the only call that does), writes one
+ * record per distinct kernel name into `out` (host memory, at most `capacity`
+ * records) and stores the number of records in *count.  Not thread-safe; meant for
+ * a benchmark's timed loop, not for production use.
+ */
+typedef struct {
+    char name[64];      /* kernel family and tile variant, NUL-terminated */
+    int32_t launches;   /* launches seen since modulora_profile_begin()   */
+    float total_ms;     /* sum of their durations in milliseconds         */
+} modulora_kernel_time;
+
+int modulora_profile_begin(void);
+int modulora_profile_end(modulora_kernel_time *out, int32_t capacity, int32_t *count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MODULORA_H */

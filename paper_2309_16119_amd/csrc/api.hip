@@ -1,0 +1,312 @@
+// The C ABI of the library: argument validation (host only, before any HIP call),
+// workspace carving, kernel selection, and the benchmark timing hook.
+// Declarations and the contract of every entry point are in include/modulora.h.
+#include "modulora.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "launch.h"
+
+namespace {
+
+constexpr int32_t kMaxDim = 1 << 20;
+constexpr int32_t kMaxTokens = 1 << 22;
+constexpr int32_t kMaxRank = 64;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align256(size_t v) { return (v + 255) & ~static_cast<size_t>(255); }
+
+int check_layer_shape(const modulora_qweight *w) {
+    if (!w) return MODULORA_ERR_NULL;
+    if (w->bits != 2 && w->bits != 3 && w->bits != 4) return MODULORA_ERR_BITS;
+    if (w->d_in < 32 || w->d_in > kMaxDim || w->d_out < 8 || w->d_out > kMaxDim) return MODULORA_ERR_SHAPE;
+    if (w->d_in % 32 != 0 || w->d_out % 8 != 0) return MODULORA_ERR_SHAPE;
+    if (w->group_size <= 0 || w->group_size % 32 != 0 || w->d_in % w->group_size != 0) return MODULORA_ERR_GROUP;
+    return MODULORA_OK;
+}
+
+int check_layer(const modulora_qweight *w) {
+    const int s = check_layer_shape(w);
+    if (s != MODULORA_OK) return s;
+    if (!w->qweight || !w->scales || !w->zeros) return MODULORA_ERR_NULL;
+    if (!aligned16(w->qweight) || !aligned16(w->scales) || !aligned16(w->zeros)) return MODULORA_ERR_ALIGN;
+    return MODULORA_OK;
+}
+
+int check_rank(int32_t r, const float *A, const float *B, bool allow_zero) {
+    if (r < (allow_zero ? 0 : 1) || r > kMaxRank) return MODULORA_ERR_RANK;
+    if (r > 0) {
+        if (!A || !B) return MODULORA_ERR_RANK;
+        if (!aligned16(A) || !aligned16(B)) return MODULORA_ERR_ALIGN;
+    }
+    return MODULORA_OK;
+}
+
+mlr::LayerView view_of(const modulora_qweight *w) {
+    mlr::LayerView v;
+    v.K = w->d_in;
+    v.N = w->d_out;
+    v.bits = w->bits;
+    v.group = w->group_size;
+    v.qweight = w->qweight;
+    v.scales = w->scales;
+    v.zeros = w->zeros;
+    return v;
+}
+
+// Workspace carving, shared by the size query and the entry points.
+struct WsLayout {
+    size_t act_ext, w_ext, p0, p1, total;
+};
+
+WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
+    WsLayout l{};
+    if (r <= 0) return l;
+    const size_t RE = (size_t)mlr::lora_ext_len(r);
+    const size_t maxdim = (size_t)(K > N ? K : N);
+    size_t off = 0;
+    l.act_ext = off; off += align256((size_t)M * RE * 2);
+    l.w_ext = off;   off += align256(maxdim * RE * 2);
+    l.p0 = off;      off += align256((size_t)M * r * 4);
+    l.p1 = off;      off += align256((size_t)M * r * 4);
+    l.total = off;
+    return l;
+}
+
+int check_workspace(const WsLayout &l, const void *ws, size_t bytes) {
+    if (l.total == 0) return MODULORA_OK;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || bytes < l.total) return MODULORA_ERR_WORKSPACE;
+    return MODULORA_OK;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? MODULORA_OK : MODULORA_ERR_HIP; }
+
+// ---- profiling state ------------------------------------------------------------
+struct ProfRecord {
+    const char *name;
+    hipEvent_t start, stop;
+};
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof;
+
+}  // namespace
+
+namespace mlr {
+
+void prof_before(const char *kernel_name, hipStream_t stream) {
+    if (!g_prof_on) return;
+    ProfRecord rec{kernel_name, nullptr, nullptr};
+    if (hipEventCreate(&rec.start) != hipSuccess) return;
+    if (hipEventCreate(&rec.stop) != hipSuccess) {
+        (void)hipEventDestroy(rec.start);
+        return;
+    }
+    (void)hipEventRecord(rec.start, stream);
+    g_prof.push_back(rec);
+}
+
+void prof_after(hipStream_t stream) {
+    if (!g_prof_on || g_prof.empty()) return;
+    (void)hipEventRecord(g_prof.back().stop, stream);
+}
+
+}  // namespace mlr
+
+extern "C" {
+
+const char *modulora_status_string(int status) {
+    switch (status) {
+        case MODULORA_OK: return "ok";
+        case MODULORA_ERR_NULL: return "a required pointer is NULL";
+        case MODULORA_ERR_SHAPE: return "d_in, d_out or M out of range or not divisible as required";
+        case MODULORA_ERR_BITS: return "bits must be 2, 3 or 4";
+        case MODULORA_ERR_GROUP: return "group_size must be a multiple of 32 that divides d_in";
+        case MODULORA_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+        case MODULORA_ERR_RANK: return "LoRA rank out of range, or A/B missing";
+        case MODULORA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case MODULORA_ERR_HIP: return "a HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+size_t modulora_workspace_bytes(const modulora_qweight *w, int32_t M, int32_t r) {
+    if (check_layer_shape(w) != MODULORA_OK) return 0;
+    if (M < 1 || M > kMaxTokens || r < 0 || r > kMaxRank) return 0;
+    return ws_layout(w->d_in, w->d_out, M, r).total;
+}
+
+int modulora_dequant(const modulora_qweight *w, uint16_t *What_bf16, void *stream) {
+    const int s = check_layer(w);
+    if (s != MODULORA_OK) return s;
+    if (!What_bf16) return MODULORA_ERR_NULL;
+    if (!aligned16(What_bf16)) return MODULORA_ERR_ALIGN;
+    return hip_status(mlr::launch_dequant(view_of(w), What_bf16, static_cast<hipStream_t>(stream)));
+}
+
+int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M, const float *A, const float *B,
+                 int32_t r, float lora_scale, uint16_t *Y, float *XA, void *workspace,
+                 size_t workspace_bytes, void *stream) {
+    int s = check_layer(w);
+    if (s != MODULORA_OK) return s;
+    if (!X || !Y) return MODULORA_ERR_NULL;
+    if (M < 1 || M > kMaxTokens) return MODULORA_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Y) || (XA && !aligned16(XA))) return MODULORA_ERR_ALIGN;
+    if ((s = check_rank(r, A, B, true)) != MODULORA_OK) return s;
+    const WsLayout l = ws_layout(w->d_in, w->d_out, M, r);
+    if ((s = check_workspace(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    mlr::GemmArgs g{};
+    g.w = view_of(w);
+    g.backward = false;
+    g.act = X;
+    g.M = M;
+    g.out = Y;
+    if (r > 0) {
+        mlr::DownArgs d{};
+        d.act = X; d.M = M; d.C = w->d_in; d.r = r;
+        d.Fm = A; d.f_is_A = true;
+        d.P = XA ? XA : reinterpret_cast<float *>(ws + l.p0);
+        d.lora_scale = lora_scale;
+        d.act_ext = reinterpret_cast<uint16_t *>(ws + l.act_ext);
+        d.RE = mlr::lora_ext_len(r);
+        d.w_ext = reinterpret_cast<uint16_t *>(ws + l.w_ext);
+        d.Wsrc = B; d.w_from_A = false; d.Cw = w->d_out;
+        if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
+        g.act_ext = d.act_ext;
+        g.w_ext = d.w_ext;
+        g.RE = d.RE;
+    }
+    return hip_status(mlr::launch_gemm(g, st));
+}
+
+int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M, const float *A,
+                       const float *B, int32_t r, float lora_scale, uint16_t *dX, float *dYBt,
+                       void *workspace, size_t workspace_bytes, void *stream) {
+    int s = check_layer(w);
+    if (s != MODULORA_OK) return s;
+    if (!dY || !dX) return MODULORA_ERR_NULL;
+    if (M < 1 || M > kMaxTokens) return MODULORA_ERR_SHAPE;
+    if (!aligned16(dY) || !aligned16(dX) || (dYBt && !aligned16(dYBt))) return MODULORA_ERR_ALIGN;
+    if ((s = check_rank(r, A, B, true)) != MODULORA_OK) return s;
+    const WsLayout l = ws_layout(w->d_in, w->d_out, M, r);
+    if ((s = check_workspace(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    mlr::GemmArgs g{};
+    g.w = view_of(w);
+    g.backward = true;
+    g.act = dY;
+    g.M = M;
+    g.out = dX;
+    if (r > 0) {
+        mlr::DownArgs d{};
+        d.act = dY; d.M = M; d.C = w->d_out; d.r = r;
+        d.Fm = B; d.f_is_A = false;
+        d.P = dYBt ? dYBt : reinterpret_cast<float *>(ws + l.p0);
+        d.lora_scale = lora_scale;
+        d.act_ext = reinterpret_cast<uint16_t *>(ws + l.act_ext);
+        d.RE = mlr::lora_ext_len(r);
+        d.w_ext = reinterpret_cast<uint16_t *>(ws + l.w_ext);
+        d.Wsrc = A; d.w_from_A = true; d.Cw = w->d_in;
+        if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
+        g.act_ext = d.act_ext;
+        g.w_ext = d.w_ext;
+        g.RE = d.RE;
+    }
+    return hip_status(mlr::launch_gemm(g, st));
+}
+
+int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float lora_scale,
+                      const uint16_t *X, const uint16_t *dY, const float *A, const float *B,
+                      const float *XA, const float *dYBt, float *dA, float *dB, int32_t accumulate,
+                      void *workspace, size_t workspace_bytes, void *stream) {
+    if (d_in < 32 || d_in > kMaxDim || d_out < 8 || d_out > kMaxDim || d_in % 32 != 0 || d_out % 8 != 0)
+        return MODULORA_ERR_SHAPE;
+    if (M < 1 || M > kMaxTokens) return MODULORA_ERR_SHAPE;
+    if (!X || !dY || !dA || !dB) return MODULORA_ERR_NULL;
+    int s = check_rank(r, A, B, false);
+    if (s != MODULORA_OK) return s;
+    if (!aligned16(X) || !aligned16(dY) || !aligned16(dA) || !aligned16(dB) || (XA && !aligned16(XA)) ||
+        (dYBt && !aligned16(dYBt)))
+        return MODULORA_ERR_ALIGN;
+    const WsLayout l = ws_layout(d_in, d_out, M, r);
+    if ((s = check_workspace(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    if (!XA) {
+        mlr::DownArgs d{};
+        d.act = X; d.M = M; d.C = d_in; d.r = r; d.Fm = A; d.f_is_A = true;
+        d.P = reinterpret_cast<float *>(ws + l.p0);
+        d.lora_scale = lora_scale;
+        if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
+        XA = d.P;
+    }
+    if (!dYBt) {
+        mlr::DownArgs d{};
+        d.act = dY; d.M = M; d.C = d_out; d.r = r; d.Fm = B; d.f_is_A = false;
+        d.P = reinterpret_cast<float *>(ws + l.p1);
+        d.lora_scale = lora_scale;
+        if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
+        dYBt = d.P;
+    }
+    if (!accumulate) {
+        if ((s = hip_status(mlr::launch_fill_zero(dA, (size_t)d_in * r, st))) != MODULORA_OK) return s;
+        if ((s = hip_status(mlr::launch_fill_zero(dB, (size_t)d_out * r, st))) != MODULORA_OK) return s;
+    }
+    mlr::GradArgs ga{};
+    ga.act = X; ga.M = M; ga.C = d_in; ga.r = r; ga.P = dYBt; ga.lora_scale = lora_scale;
+    ga.out = dA; ga.out_is_A = true;
+    if ((s = hip_status(mlr::launch_lora_grad(ga, st))) != MODULORA_OK) return s;
+    mlr::GradArgs gb{};
+    gb.act = dY; gb.M = M; gb.C = d_out; gb.r = r; gb.P = XA; gb.lora_scale = lora_scale;
+    gb.out = dB; gb.out_is_A = false;
+    return hip_status(mlr::launch_lora_grad(gb, st));
+}
+
+int modulora_profile_begin(void) {
+    for (auto &rec : g_prof) {
+        (void)hipEventDestroy(rec.start);
+        (void)hipEventDestroy(rec.stop);
+    }
+    g_prof.clear();
+    g_prof_on = true;
+    return MODULORA_OK;
+}
+
+int modulora_profile_end(modulora_kernel_time *out, int32_t capacity, int32_t *count) {
+    g_prof_on = false;
+    if (!count || (capacity > 0 && !out)) return MODULORA_ERR_NULL;
+    int32_t n = 0;
+    int status = MODULORA_OK;
+    for (auto &rec : g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(rec.stop) != hipSuccess || hipEventElapsedTime(&ms, rec.start, rec.stop) != hipSuccess)
+            status = MODULORA_ERR_HIP;
+        (void)hipEventDestroy(rec.start);
+        (void)hipEventDestroy(rec.stop);
+        int32_t slot = -1;
+        for (int32_t i = 0; i < n; ++i)
+            if (std::strncmp(out[i].name, rec.name, sizeof(out[i].name)) == 0) { slot = i; break; }
+        if (slot < 0) {
+            if (n >= capacity) continue;
+            slot = n++;
+            std::memset(&out[slot], 0, sizeof(out[slot]));
+            std::strncpy(out[slot].name, rec.name, sizeof(out[slot].name) - 1);
+        }
+        out[slot].launches += 1;
+        out[slot].total_ms += ms;
+    }
+    g_prof.clear();
+    *count = n;
+    return status;
+}
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Device-side building blocks shared by every kernel of the library:
+// bit-stream unpacking and the exact dequantization of one code.
+//
+// Dequantization follows Section 2.2 eq. (2) of the ModuLoRA paper in its
+// integer-zero-point form,  w = (q - zero) * scale, materialized in bfloat16
+// (Section 3.2 materializes in a 16-bit float).  The product is formed exactly
+// in binary32 and rounded once, to nearest even, to bfloat16.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mlr {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+__device__ __forceinline__ float half_bits_to_float(uint16_t h) {
+    _Float16 x;
+    __builtin_memcpy(&x, &h, sizeof x);
+    return (float)x;   // exact
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t h) {
+    return __uint_as_float(((uint32_t)h) << 16);
+}
+
+// Two floats -> two bfloat16 (round to nearest even) packed in one register,
+// `lo` in bits 0..15.  Compiles to v_cvt_pk_bf16_f32.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    bf16x2 p = {(__bf16)lo, (__bf16)hi};
+    uint32_t u;
+    __builtin_memcpy(&u, &p, sizeof u);
+    return u;
+}
+
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+    return (uint16_t)(pack_bf16x2(f, 0.0f) & 0xFFFFu);
+}
+
+// Per-(group, column) dequantization constants: w = fma(q, scale, bias) with
+// bias = -zero * scale.  zero <= 255 and scale has an 11-bit significand, so
+// bias is exact; q * scale is exact inside the fma and the sum (q - zero) * scale
+// is representable, so the fma returns the exact product.
+struct DqConst {
+    float scale;
+    float bias;
+};
+
+__device__ __forceinline__ DqConst make_dq(uint16_t scale_bits, uint8_t zero) {
+    DqConst c;
+    c.scale = half_bits_to_float(scale_bits);
+    c.bias = -(float)zero * c.scale;
+    return c;
+}
+
+__device__ __forceinline__ float dq_value(uint32_t q, const DqConst &c) {
+    return __builtin_fmaf((float)q, c.scale, c.bias);
+}
+
+// Code i (0..7) of an 8-code chunk: chunk bits [i*BITS, i*BITS + BITS).
+template <int BITS>
+__device__ __forceinline__ uint32_t chunk_code(uint32_t chunk, int i) {
+    return (chunk >> (i * BITS)) & ((1u << BITS) - 1u);
+}
+
+// The 8-code chunk number j (0..3) of a 32-code block held in BITS words
+// (w[0] first): stream bits [8*BITS*j, 8*BITS*(j+1)) of the block, in the low
+// 8*BITS bits of the result (higher bits are junk for BITS == 3 and are masked
+// by chunk_code).
+template <int BITS>
+__device__ __forceinline__ uint32_t block_chunk(const uint32_t *w, int j) {
+    if (BITS == 4) return w[j];
+    if (BITS == 2) return (j & 1) ? (w[j >> 1] >> 16) : w[j >> 1];
+    // BITS == 3: 24-bit chunks at stream bits 0, 24, 48, 72
+    switch (j) {
+        case 0: return w[0];
+        case 1: return (w[0] >> 24) | (w[1] << 8);
+        case 2: return (w[1] >> 16) | (w[2] << 16);
+        default: return w[2] >> 8;
+    }
+}
+
+// Dequantize the 8 codes of one chunk with one (scale, bias): 8 bfloat16 in
+// 4 registers, code 0 in the low half of out[0].
+template <int BITS>
+__device__ __forceinline__ void dequant_chunk(uint32_t chunk, const DqConst &c, uint32_t out[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float lo = dq_value(chunk_code<BITS>(chunk, 2 * i), c);
+        float hi = dq_value(chunk_code<BITS>(chunk, 2 * i + 1), c);
+        out[i] = pack_bf16x2(lo, hi);
+    }
+}
+
+}  // namespace mlr

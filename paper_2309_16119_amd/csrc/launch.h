@@ -1,0 +1,87 @@
+// Internal host-side interface between the C-ABI layer (api.hip) and the kernel
+// translation units.  Not installed; nothing outside csrc/ includes it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mlr {
+
+// The frozen quantized weight (same fields as modulora_qweight, device pointers).
+struct LayerView {
+    int K, N, bits, group;
+    const uint32_t *qweight;
+    const uint16_t *scales;
+    const uint8_t *zeros;
+};
+
+// Length of the extended contraction that carries the rank-r adapter through the
+// MFMA pipeline: three bfloat16 segments of r (hi*hi, hi*lo, lo*hi), padded to
+// the MFMA K-step of 16.
+inline int lora_ext_len(int r) { return r > 0 ? ((3 * r + 15) / 16) * 16 : 0; }
+
+// ---- profiling hook (api.hip owns the state) -------------------------------
+// launch wrappers call these around every kernel launch; they are no-ops unless
+// modulora_profile_begin() is active.
+void prof_before(const char *kernel_name, hipStream_t stream);
+void prof_after(hipStream_t stream);
+
+// ---- dequant_kernel.hip ------------------------------------------------------
+hipError_t launch_dequant(const LayerView &w, uint16_t *What, hipStream_t stream);
+
+// ---- gemm_tile.hip -----------------------------------------------------------
+// out[M][Cout] = act[M][C] (x) What  (+ act_ext[M][RE] . w_ext[Cout][RE]^T)
+//   forward : C = K, Cout = N, out[m][n] = sum_k act[m][k] What[n][k]
+//   backward: C = N, Cout = K, out[m][k] = sum_n act[m][n] What[n][k]
+struct GemmArgs {
+    LayerView w;
+    bool backward;
+    const uint16_t *act;      // bf16 [M][C]
+    int M;
+    uint16_t *out;            // bf16 [M][Cout]
+    const uint16_t *act_ext;  // bf16 [M][RE]    (NULL when RE == 0)
+    const uint16_t *w_ext;    // bf16 [Cout][RE] (NULL when RE == 0)
+    int RE;                   // multiple of 16
+};
+hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
+
+// ---- lora_kernels.hip ----------------------------------------------------------
+// P[m][j] = sum_c act[m][c] * F(c, j)  and the extended operands for launch_gemm.
+//   f_is_A: F(c, j) = Fm[c * r + j]  (A [K][r], projection of X)
+//   else  : F(c, j) = Fm[j * C + c]  (B [r][N], projection of dY onto B^T)
+// Writes P (fp32 [M][r]); if act_ext != NULL also the split of lora_scale * P into
+// act_ext [M][RE]; if w_ext != NULL also w_ext [Cw][RE] from Wsrc:
+//   w_from_A: w_ext[c][.] from Wsrc[c * r + j] (A, for the backward pass)
+//   else    : w_ext[c][.] from Wsrc[j * Cw + c] (B, for the forward pass)
+struct DownArgs {
+    const uint16_t *act;  // bf16 [M][C]
+    int M, C, r;
+    const float *Fm;
+    bool f_is_A;
+    float *P;             // fp32 [M][r]
+    float lora_scale;
+    uint16_t *act_ext;    // may be NULL
+    int RE;
+    uint16_t *w_ext;      // may be NULL
+    const float *Wsrc;
+    bool w_from_A;
+    int Cw;
+};
+hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream);
+
+// out(c, j) (+)= lora_scale * sum_m act[m][c] * P[m][j]
+//   out_is_A: out index c * r + j (dA [K][r]);  else j * C + c (dB [r][N]).
+// `out` must already hold the value to accumulate onto (zeros for overwrite).
+struct GradArgs {
+    const uint16_t *act;  // bf16 [M][C]
+    int M, C, r;
+    const float *P;       // fp32 [M][r]
+    float lora_scale;
+    float *out;
+    bool out_is_A;
+};
+hipError_t launch_lora_grad(const GradArgs &a, hipStream_t stream);
+
+// dst[0..n) = 0.0f   (a fill kernel, so that callers may capture it in a HIP graph)
+hipError_t launch_fill_zero(float *dst, size_t n, hipStream_t stream);
+
+}  // namespace mlr

@@ -1,0 +1,119 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before any HIP call is made.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2309_16119_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "modulora.h")
+
+FAKE = 0x10000          # a non-NULL, 256-byte aligned address that is never dereferenced
+ODD = FAKE + 4          # misaligned
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(modulora_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for required in ("modulora_fwd", "modulora_bwd_input", "modulora_bwd_lora", "modulora_dequant",
+                     "modulora_workspace_bytes", "modulora_status_string"):
+        assert required in names
+
+
+@pytest.mark.parametrize("name", declared_functions())
+def test_library_exports_symbol(name):
+    assert hasattr(b.lib, name), name
+
+
+def qw(d_in=4096, d_out=4096, bits=3, group=128, q=FAKE, s=FAKE, z=FAKE):
+    return b.modulora_qweight(d_in, d_out, bits, group, q, s, z)
+
+
+def fwd(w, X=FAKE, M=16, A=FAKE, B=FAKE, r=8, Y=FAKE, XA=0, ws=FAKE, wsb=1 << 30):
+    return b.lib.modulora_fwd(ctypes.byref(w), X, M, A, B, r, 2.0, Y, XA, ws, wsb, None)
+
+
+def bwd(w, dY=FAKE, M=16, A=FAKE, B=FAKE, r=8, dX=FAKE, T=0, ws=FAKE, wsb=1 << 30):
+    return b.lib.modulora_bwd_input(ctypes.byref(w), dY, M, A, B, r, 2.0, dX, T, ws, wsb, None)
+
+
+def test_status_strings():
+    for code in range(0, 9):
+        assert b.modulora_status_string(code)
+    assert "unknown" in b.modulora_status_string(99)
+
+
+@pytest.mark.parametrize("call", [fwd, bwd])
+def test_rejections_fwd_and_bwd_input(call):
+    assert call(qw(bits=5)) == 3
+    assert call(qw(bits=1)) == 3
+    assert call(qw(group=100)) == 4           # not a multiple of 32
+    assert call(qw(group=96)) == 4            # multiple of 32 that does not divide d_in
+    assert call(qw(group=0)) == 4
+    assert call(qw(d_in=4100)) == 2           # not a multiple of 32
+    assert call(qw(d_out=4100)) == 2          # not a multiple of 8
+    assert call(qw(d_in=0)) == 2
+    assert call(qw(q=0)) == 1
+    assert call(qw(s=0)) == 1
+    assert call(qw(z=ODD)) == 5
+    assert call(qw(), M=0) == 2
+    assert call(qw(), M=-3) == 2
+    assert call(qw(), r=65) == 6
+    assert call(qw(), r=-1) == 6
+    assert call(qw(), A=0) == 6               # r > 0 needs A and B
+    assert call(qw(), B=ODD) == 5
+    assert call(qw(), ws=0) == 7
+    assert call(qw(), ws=FAKE + 16) == 7      # workspace must be 256-byte aligned
+    assert call(qw(), wsb=16) == 7
+    if call is fwd:
+        assert call(qw(), X=0) == 1 and call(qw(), Y=0) == 1 and call(qw(), X=ODD) == 5
+    else:
+        assert call(qw(), dY=0) == 1 and call(qw(), dX=0) == 1 and call(qw(), dX=ODD) == 5
+
+
+def test_null_layer_pointer():
+    assert b.lib.modulora_fwd(None, FAKE, 1, None, None, 0, 1.0, FAKE, None, None, 0, None) == 1
+    assert b.lib.modulora_dequant(None, FAKE, None) == 1
+    assert b.lib.modulora_dequant(ctypes.byref(qw()), None, None) == 1
+    assert b.lib.modulora_dequant(ctypes.byref(qw(bits=7)), FAKE, None) == 3
+
+
+def test_rejections_bwd_lora():
+    def call(d_in=4096, d_out=4096, M=16, r=8, X=FAKE, dY=FAKE, A=FAKE, B=FAKE, dA=FAKE, dB=FAKE,
+             ws=FAKE, wsb=1 << 30):
+        return b.lib.modulora_bwd_lora(d_in, d_out, M, r, 2.0, X, dY, A, B, None, None, dA, dB, 0, ws, wsb, None)
+    assert call(d_in=33) == 2
+    assert call(d_out=12) == 2
+    assert call(M=0) == 2
+    assert call(r=0) == 6                      # the adapter gradients need r >= 1
+    assert call(r=70) == 6
+    assert call(X=0) == 1 and call(dA=0) == 1 and call(dB=0) == 1
+    assert call(dY=ODD) == 5
+    assert call(A=0) == 6
+    assert call(ws=0) == 7
+    assert call(wsb=100) == 7
+
+
+def test_workspace_bytes():
+    w = qw()
+    assert b.lib.modulora_workspace_bytes(ctypes.byref(w), 512, 0) == 0       # r = 0 needs none
+    n8 = b.lib.modulora_workspace_bytes(ctypes.byref(w), 512, 8)
+    n16 = b.lib.modulora_workspace_bytes(ctypes.byref(w), 512, 16)
+    assert 0 < n8 < n16 and n8 % 256 == 0
+    assert b.lib.modulora_workspace_bytes(ctypes.byref(qw(bits=9)), 512, 8) == 0
+    assert b.lib.modulora_workspace_bytes(ctypes.byref(w), 0, 8) == 0
+    assert b.lib.modulora_workspace_bytes(None, 1, 1) == 0
+
+
+def test_profile_api_without_launches():
+    b.modulora_profile_begin()
+    assert b.modulora_profile_end() == {}
