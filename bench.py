@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-LoRA linear layer on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extra]
+
+A "step" is one pass of the whole hot path over one batch of synthetic tokens:
+modulora_fwd + modulora_bwd_input + modulora_bwd_lora of one layer, inputs already
+resident in HBM.  The headline workload is the LLaMA-7B attention projection
+(4096x4096, 3-bit, group 128, M = 512, r = 8); `--workload` picks another one.
+The timed region replays the K steps from one HIP graph (no host launch overhead);
+weights rotate over enough distinct copies (>= 512 MB) that no step finds its
+packed weights in the last-level cache.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor peak
+ROTATE_BYTES = 512 << 20        # distinct packed weights touched before one is reused
+
+
+def parse_args():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=10)
+    p.add_argument("--workload", default="c2_7b_attn")
+    p.add_argument("--M", type=int, default=None, help="override the token count of the workload")
+    p.add_argument("--no-extra", action="store_true", help="skip the additional workloads")
+    p.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return p.parse_args()
+
+
+class Workload:
+    """Device buffers and prebuilt C-ABI argument lists for one layer configuration."""
+
+    def __init__(self, cfg, host_layer=None, seed=0):
+        import numpy as np
+        import torch
+        from paper_2309_16119_amd import binding as b
+
+        self.cfg, self.b, self.torch = cfg, b, torch
+        K, N, M, r, bits, g = cfg.K, cfg.N, cfg.M, cfg.r, cfg.bits, cfg.group
+        G = K // g
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed)
+        n_copies = max(1, math.ceil(ROTATE_BYTES / cfg.packed_weight_bytes))
+        self.n_copies = n_copies
+        self.weights = []
+        for i in range(n_copies):
+            if i == 0 and host_layer is not None:
+                w = b.QWeight.from_numpy(host_layer["qweight"], host_layer["scales"], host_layer["zeros"],
+                                         K, N, bits, g)
+            else:
+                # uniformly random words are exactly uniformly random codes
+                q = torch.randint(-2 ** 31, 2 ** 31, (K * bits // 32, N), dtype=torch.int64, device="cuda",
+                                  generator=gen).to(torch.int32)
+                sc = (torch.rand((G, N), device="cuda", generator=gen) * (cfg.scale_hi - cfg.scale_lo)
+                      + cfg.scale_lo).to(torch.float16)
+                z = torch.randint(0, 1 << bits, (G, N), dtype=torch.uint8, device="cuda", generator=gen)
+                w = b.QWeight(q, sc, z, K, N, bits, g)
+            self.weights.append(w)
+        if host_layer is not None:
+            def dev16(a):
+                return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+            self.X, self.dY = dev16(host_layer["X"]), dev16(host_layer["dY"])
+            self.A, self.B = torch.from_numpy(host_layer["A"]).cuda(), torch.from_numpy(host_layer["B"]).cuda()
+        else:
+            self.X = torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16)
+            self.dY = torch.randn((M, N), device="cuda", generator=gen).to(torch.bfloat16)
+            self.A = torch.randn((K, r), device="cuda", generator=gen) * 0.02
+            self.B = torch.randn((r, N), device="cuda", generator=gen) * 0.02
+        self.Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        self.dX = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+        self.XA = torch.empty((M, r), dtype=torch.float32, device="cuda")
+        self.dYBt = torch.empty((M, r), dtype=torch.float32, device="cuda")
+        self.dA = torch.empty((K, r), dtype=torch.float32, device="cuda")
+        self.dB = torch.empty((r, N), dtype=torch.float32, device="cuda")
+        nbytes = b.modulora_workspace_bytes(self.weights[0], M, r)
+        self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        self.ws_bytes = nbytes
+        self.structs = [w.c_struct() for w in self.weights]
+
+    def step(self, i: int):
+        b, cfg = self.b, self.cfg
+        st = ctypes.byref(self.structs[i % self.n_copies])
+        stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
+        p = lambda t: ctypes.c_void_p(t.data_ptr())
+        s = float(cfg.lora_scale)
+        rc = b.lib.modulora_fwd(st, p(self.X), cfg.M, p(self.A), p(self.B), cfg.r, s, p(self.Y), p(self.XA),
+                                p(self.ws), self.ws_bytes, stream)
+        rc |= b.lib.modulora_bwd_input(st, p(self.dY), cfg.M, p(self.A), p(self.B), cfg.r, s, p(self.dX),
+                                       p(self.dYBt), p(self.ws), self.ws_bytes, stream)
+        rc |= b.lib.modulora_bwd_lora(cfg.K, cfg.N, cfg.M, cfg.r, s, p(self.X), p(self.dY), p(self.A), p(self.B),
+                                      p(self.XA), p(self.dYBt), p(self.dA), p(self.dB), 0, p(self.ws),
+                                      self.ws_bytes, stream)
+        if rc != 0:
+            raise RuntimeError("library call failed with status %d" % rc)
+
+
+def time_steps(wl: Workload, steps: int, warmup: int, use_graph: bool) -> float:
+    """Milliseconds per step over exactly `steps` steps (after `warmup` untimed ones)."""
+    torch = wl.torch
+    for i in range(warmup):
+        wl.step(i)
+    torch.cuda.synchronize()
+    if use_graph:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for i in range(steps):
+                    wl.step(i)
+        torch.cuda.synchronize()
+        graph.replay()          # untimed: uploads the graph
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        t0 = time.perf_counter()
+        for i in range(steps):
+            wl.step(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps
+
+
+def kernel_profile(wl: Workload, steps: int) -> dict:
+    """{kernel: (launches, total_ms)} over `steps` eager steps, from HIP events recorded by the
+    library around each of its kernel launches (on the stream they are launched on)."""
+    b, torch = wl.b, wl.torch
+    torch.cuda.synchronize()
+    b.modulora_profile_begin()
+    for i in range(steps):
+        wl.step(i)
+    prof = b.modulora_profile_end(capacity=64)
+    torch.cuda.synchronize()
+    return prof
+
+
+def roofline_of(cfg, prof: dict) -> dict:
+    """Roofline entry for the kernel that takes the most time in `prof`."""
+    name, (launches, total_ms) = max(prof.items(), key=lambda kv: kv[1][1])
+    avg_s = total_ms / launches * 1e-3
+    K, N, M, r = cfg.K, cfg.N, cfg.M, cfg.r
+    if name.startswith("gemm_") and M > 16:
+        # one product with the frozen weight plus the rank-r up-projection it carries
+        cout = N if "fwd" in name else K
+        flops = 2.0 * M * K * N + 2.0 * M * r * cout
+        ach = flops / avg_s / 1e12
+        return {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "avg_kernel_us": round(avg_s * 1e6, 2), "launches": launches}
+    if name.startswith("gemm_") or name.startswith("stream_"):
+        nbytes = float(cfg.packed_weight_bytes)            # one pass over codes + scales + zeros
+    else:
+        # adapter kernels stream the activations once
+        nbytes = 2.0 * M * (K if ("down" in name) else max(K, N))
+    ach = nbytes / avg_s / 1e9
+    return {"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "avg_kernel_us": round(avg_s * 1e6, 2),
+            "launches": launches}
+
+
+def per_call_ms(prof: dict) -> dict:
+    out = {}
+    for name, (launches, total_ms) in prof.items():
+        out[name] = round(total_ms / launches * 1e3, 2)   # microseconds per launch
+    return out
+
+
+def cpu_baseline(host_layer, cfg) -> dict:
+    """The oracle, as it stands, timed on the host cores on one full step of the workload."""
+    import oracle
+
+    L = host_layer
+    args = (L["qweight"], L["scales"], L["zeros"], L["K"], L["N"], L["bits"], L["group"])
+    t0 = time.perf_counter()
+    oracle.fwd(*args, L["X"], L["A"], L["B"], L["lora_scale"])
+    oracle.bwd_input(*args, L["dY"], L["A"], L["B"], L["lora_scale"])
+    oracle.bwd_lora(L["K"], L["N"], L["X"], L["dY"], L["A"], L["B"], L["lora_scale"])
+    dt = time.perf_counter() - t0
+    return {"value": round(cfg.flops_fwd_bwd / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": "one full step (fwd + bwd_input + bwd_lora) of %s, all %d tokens" % (cfg.name, cfg.M)}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding). "
+              "Run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2309_16119_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    if args.M is not None:
+        cfg = cfg.with_M(args.M)
+    use_graph = not args.no_graph
+
+    host_layer = synth.make_layer(cfg)
+    wl = Workload(cfg, host_layer)
+    ms = time_steps(wl, args.steps, args.warmup, use_graph)
+    prof = kernel_profile(wl, args.steps)
+    tflops = cfg.flops_fwd_bwd / (ms * 1e-3) / 1e12
+
+    line = {
+        "metric": "fwd+bwd TFLOP/s per quantized LoRA layer",
+        "value": round(tflops, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: d_in=%d d_out=%d %d-bit group %d, M=%d tokens, r=%d, lora_scale=%g" % (
+            cfg.name, cfg.K, cfg.N, cfg.bits, cfg.group, cfg.M, cfg.r, cfg.lora_scale),
+            "weight_copies_rotated": wl.n_copies, "hip_graph": use_graph},
+        "roofline": roofline_of(cfg, prof),
+        "kernel_us": per_call_ms(prof),
+    }
+    if not args.no_cpu:
+        line["cpu_baseline"] = cpu_baseline(host_layer, cfg)
+    del wl, host_layer
+    torch.cuda.empty_cache()
+
+    if not args.no_extra:
+        extra = []
+        others = [synth.CONFIGS["c3_7b_gate_up"], synth.CONFIGS["c5_65b_attn"].with_M(16),
+                  synth.CONFIGS["c5_65b_attn"].with_M(1)]
+        for ocfg in others:
+            if ocfg.name == cfg.name:
+                continue
+            w2 = Workload(ocfg)
+            steps = max(5, min(args.steps, 20))
+            ms2 = time_steps(w2, steps, 3, use_graph)
+            prof2 = kernel_profile(w2, steps)
+            entry = {"workload": ocfg.name, "ms_per_step": round(ms2, 5),
+                     "tflops": round(ocfg.flops_fwd_bwd / (ms2 * 1e-3) / 1e12, 3),
+                     "roofline": roofline_of(ocfg, prof2), "kernel_us": per_call_ms(prof2)}
+            if ocfg.M <= 16:
+                gemm = {k: v for k, v in prof2.items() if k.startswith(("gemm_", "stream_"))}
+                entry["packed_weight_GBps"] = {
+                    k: round(ocfg.packed_weight_bytes / (v[1] / v[0] * 1e-3) / 1e9, 1) for k, v in gemm.items()}
+            extra.append(entry)
+            del w2
+            torch.cuda.empty_cache()
+        line["extra"] = extra
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -286,9 +286,18 @@ static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_
     const int blocks = (tiles_m * tiles_c + 7) / 8 * 8;
     const size_t lds_bytes = (size_t)(MT + CT) * LROW * sizeof(uint16_t);
     auto kern = gemm_tile_kernel<BITS, BWD, MT, CT, WM, WN>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    // raise the dynamic-LDS limit once per variant and device (not a stream operation,
+    // but keep it out of the steady state and out of graph captures after the first call)
+    static bool configured[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64 || !configured[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) configured[dev] = true;
+    }
     prof_before(name, stream);
     kern<<<blocks, THREADS, lds_bytes, stream>>>(a, tiles_m, tiles_c);
     prof_after(stream);
