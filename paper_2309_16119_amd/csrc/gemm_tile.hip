@@ -17,8 +17,24 @@
 //   - forward: one packed word holds codes along k for one column n -> a lane that
 //     loads the words of column n writes 8 consecutive k of row n of the W tile.
 //   - backward: the contraction runs over n, and qweight is n-contiguous, so a lane
-//     that loads the words of 8 adjacent columns holds, for each k of the chunk, the
-//     8 consecutive n the MFMA operand wants; no transpose through LDS is needed.
+//     that loads the words of 4 adjacent columns holds, for each k of the chunk, 4
+//     consecutive n of the MFMA operand; no transpose through LDS is needed.
+//
+// Scheduling.  One VALU instruction costs a SIMD 4 cycles and one 32x32x16 MFMA 32;
+// they overlap when they come from different waves of the same SIMD.  The large
+// variant therefore runs 8 waves (2 per SIMD) on a double-buffered LDS tile pair and
+// lets the two waves of a SIMD take the two halves of a step in opposite order: one
+// issues the MFMAs of tile t while the other dequantizes tile t+1, then they swap.
+// The mid variant runs 4 waves with one LDS buffer and relies on two workgroups per
+// CU to fill each other's gaps.
+//
+// The steady-state loop is branch-free: rows past M and columns past the matrix are
+// clamped to valid addresses (their results are never stored), uniform address parts
+// live in scalar registers, and only a ragged last contraction tile and the adapter
+// extension take the predicated path.
+#include <cstdlib>
+#include <cstring>
+
 #include "device_common.h"
 #include "launch.h"
 
@@ -27,15 +43,14 @@ namespace mlr {
 constexpr int RT = 64;         // contraction elements per LDS tile
 constexpr int LDS_PAD = 8;     // bf16 elements of row padding (row stride 144 B: conflict-free 16-B accesses)
 constexpr int LROW = RT + LDS_PAD;
-constexpr int THREADS = 256;
 
 struct TileCoord {
     int tm, tc;
 };
 
 // XCD-aware tile order: consecutive workgroup ids go round-robin over the 8 XCDs, so
-// give each XCD a contiguous run of tiles, and walk tiles column-major inside a run
-// so that neighbours on one XCD share the weight tile (and its L2 lines).
+// give each XCD a contiguous run of tiles, and walk tiles row-block-fastest inside a
+// run so that neighbours on one XCD share the weight tile (and its L2 lines).
 __device__ __forceinline__ TileCoord tile_of_block(int bid, int tiles_m, int tiles_c) {
     const int total = tiles_m * tiles_c;
     const int per_xcd = (total + 7) / 8;
@@ -47,127 +62,217 @@ __device__ __forceinline__ TileCoord tile_of_block(int bid, int tiles_m, int til
     return tc;
 }
 
-template <int BITS, bool BWD, int MT, int CT, int WM, int WN>
-__global__ __launch_bounds__(THREADS) void gemm_tile_kernel(GemmArgs a, int tiles_m, int tiles_c) {
-    static_assert((MT / WM) * (CT / WN) == THREADS / 64, "4 waves");
-    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA tiles");
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-    uint16_t *As = lds;                 // [MT][LROW]
-    uint16_t *Ws = lds + MT * LROW;     // [CT][LROW]
+struct GemmDev {
+    GemmArgs a;
+    int tiles_m, tiles_c;
+    // group index of a 32-code block: blk / (group/32), as one multiply-high with
+    // magic = floor(2^32 / d) + 1 (exact for blk, d < 2^15); d == 1 is passed through
+    uint32_t blocks_per_group, blocks_per_group_magic;
+    __device__ __forceinline__ uint32_t group_of_block(uint32_t blk) const {
+        return blocks_per_group == 1 ? blk : __umulhi(blk, blocks_per_group_magic);
+    }
+};
 
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+template <typename T>
+__device__ __forceinline__ T load_at(const void *base, uint32_t byte_off) {
+    return *reinterpret_cast<const T *>(static_cast<const char *>(base) + byte_off);
+}
+
+template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, bool DB, int OCC>
+__global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
+    constexpr int NWAVES = THREADS / 64;
+    static_assert((MT / WM) * (CT / WN) == NWAVES, "wave grid covers the tile");
+    static_assert(WM % 32 == 0 && WN == 64, "wave tile: rows in 32s, two 32-column MFMA tiles");
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
+    constexpr int BUF = (MT + CT) * LROW;   // elements per buffer: As [MT][LROW] then Ws [CT][LROW]
+
+    const GemmArgs &a = d.a;
     // grid is padded up to a multiple of 8 blocks; surplus blocks leave here
-    const TileCoord tcoord = tile_of_block(blockIdx.x, tiles_m, tiles_c);
+    const TileCoord tcoord = tile_of_block(blockIdx.x, d.tiles_m, d.tiles_c);
     if (tcoord.tm < 0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int m0 = tcoord.tm * MT, c0 = tcoord.tc * CT;
     const int K = a.w.K, N = a.w.N;
     const int C = BWD ? N : K;          // contraction length
     const int Cout = BWD ? K : N;       // output columns
+    const int n_full = C / RT;          // tiles that need no predicate
     const int n_main = (C + RT - 1) / RT;
     const int n_ext = (a.RE + RT - 1) / RT;
     const int n_tiles = n_main + n_ext;
 
-    // ---- register staging for one tile -------------------------------------
+    // ---- per-thread constants of the staging pattern ---------------------------
     constexpr int A_CH = MT * (RT / 8) / THREADS;            // 16-byte activation chunks per thread
     constexpr int FW_UNITS = CT * (RT / 32) / THREADS;       // forward: (column, 32-code block) units
-    constexpr int BW_UNITS = (CT / 8) * (RT / 8) / THREADS;  // backward: (8 columns n, 8 codes k) units
+    constexpr int BW_UNITS = (CT / 8) * (RT / 4) / THREADS;  // backward: (4 columns n, 8 codes k) units
+    constexpr int W_CH = CT * (RT / 8) / THREADS;            // 16-byte chunks of an extension W tile
     static_assert(A_CH >= 1 && (MT * (RT / 8)) % THREADS == 0, "activation tile divides");
-    static_assert(CT * (RT / 32) % THREADS == 0 && FW_UNITS >= 1, "forward units divide");
-    static_assert(BWD ? ((CT / 8) * (RT / 8) % THREADS == 0 && BW_UNITS >= 1) : true, "backward units divide");
-    constexpr int W_CH = CT * (RT / 8) / THREADS;             // 16-byte chunks of an extension W tile
+    static_assert(FW_UNITS >= 1 && (CT * (RT / 32)) % THREADS == 0, "forward units divide");
+    static_assert(BW_UNITS >= 1 && ((CT / 8) * (RT / 4)) % THREADS == 0, "backward units divide");
+    static_assert(W_CH >= 1, "extension tile divides");
+    static_assert(THREADS % CT == 0 || CT % THREADS == 0, "forward unit -> k-block is wave-uniform");
 
+    // activations: uniform base (row block, tile) + per-thread byte offset
+    uint32_t a_off[A_CH];       // bytes from act + m0*C: clamped row * C + chunk
+    int a_col[A_CH];            // contraction offset of the chunk inside the tile
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+        const int idx = tid + i * THREADS;
+        const int row = idx / (RT / 8), ch = idx % (RT / 8);
+        int m = m0 + row;
+        if (m > a.M - 1) m = a.M - 1;
+        a_off[i] = (uint32_t)(((size_t)(m - m0) * C + ch * 8) * 2);
+        a_col[i] = ch * 8;
+    }
+    const uint16_t *act_rowblock = a.act + (size_t)m0 * C;
+
+    // forward weight units
+    uint32_t fw_off[BWD ? 1 : FW_UNITS];   // bytes: clamped column * 4
+    uint32_t fw_n[BWD ? 1 : FW_UNITS];     // clamped column
+    int fw_kb[BWD ? 1 : FW_UNITS];         // 32-code block inside the tile (wave-uniform)
+    // backward weight units
+    uint32_t bw_off[BWD ? BW_UNITS : 1];   // bytes from qweight row of c0: (drow * N + no*4) * 4
+    uint32_t bw_offhi[BWD ? BW_UNITS : 1];
+    uint32_t bw_soff[BWD ? BW_UNITS : 1];  // elements from scales/zeros row of c0's group: dgroup * N + no*4
+    int bw_shift[BWD ? BW_UNITS : 1];
+    bool bw_kok[BWD ? BW_UNITS : 1];
+    int bw_row0 = 0, bw_g0 = 0;
+    if (!BWD) {
+#pragma unroll
+        for (int u = 0; u < FW_UNITS; ++u) {
+            const int idx = tid + u * THREADS;
+            int n = c0 + idx % CT;
+            if (n > N - 1) n = N - 1;
+            fw_n[u] = (uint32_t)n;
+            fw_off[u] = (uint32_t)n * 4u;
+            fw_kb[u] = uniform(idx / CT);
+        }
+    } else {
+        bw_row0 = (c0 * BITS) >> 5;
+        bw_g0 = (int)d.group_of_block((uint32_t)(c0 >> 5));
+        const int last_row = K * BITS / 32 - 1;
+#pragma unroll
+        for (int u = 0; u < BW_UNITS; ++u) {
+            const int idx = tid + u * THREADS;
+            const int no = idx % (RT / 4), ko = idx / (RT / 4);
+            int k = c0 + ko * 8;
+            bw_kok[u] = k < K;
+            if (k > K - 8) k = K - 8;
+            const int bit = k * BITS;
+            const int row = bit >> 5;
+            const int row_hi = row + 1 > last_row ? last_row : row + 1;
+            bw_shift[u] = bit & 31;
+            bw_off[u] = (uint32_t)(((size_t)(row - bw_row0) * N + no * 4) * 4);
+            bw_offhi[u] = (uint32_t)(((size_t)(row_hi - bw_row0) * N + no * 4) * 4);
+            const int g = (int)d.group_of_block((uint32_t)(k >> 5));
+            bw_soff[u] = (uint32_t)((size_t)(g - bw_g0) * N + no * 4);
+        }
+    }
+
+    // ---- register staging for one tile -------------------------------------
     uint4 a_reg[A_CH];
     uint32_t fw_words[BWD ? 1 : FW_UNITS][BITS];
-    DqConst fw_dq[BWD ? 1 : FW_UNITS];
-    uint32_t bw_lo[BWD ? BW_UNITS : 1][8], bw_hi[BWD ? BW_UNITS : 1][8];
-    uint32_t bw_scale[BWD ? BW_UNITS : 1][4];   // 8 binary16
-    uint32_t bw_zero[BWD ? BW_UNITS : 1][2];    // 8 uint8
-    int bw_shift[BWD ? BW_UNITS : 1];
+    uint32_t fw_sz[BWD ? 1 : FW_UNITS];          // scale bits | zero << 16
+    uint4 bw_lo[BWD ? BW_UNITS : 1], bw_hi[BWD ? BW_UNITS : 1];
+    uint2 bw_scale[BWD ? BW_UNITS : 1];          // 4 binary16
+    uint32_t bw_zero[BWD ? BW_UNITS : 1];        // 4 uint8
     uint4 w_reg[W_CH];                           // extension tiles only
 
-    auto load_tile = [&](int t) {
+    // full main tile t: no predicates at all
+    auto load_main = [&](int t) {
+        const uint16_t *abase = act_rowblock + (size_t)t * RT;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) a_reg[i] = load_at<uint4>(abase, a_off[i]);
+        if (!BWD) {
+#pragma unroll
+            for (int u = 0; u < FW_UNITS; ++u) {
+                const int blk = t * (RT / 32) + fw_kb[u];
+                const uint32_t *wbase = a.w.qweight + (size_t)blk * BITS * N;
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) fw_words[u][j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off[u]);
+                const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
+                fw_sz[u] = (uint32_t)a.w.scales[grow + fw_n[u]] | ((uint32_t)a.w.zeros[grow + fw_n[u]] << 16);
+            }
+        } else {
+            const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
+            const uint16_t *sbase = a.w.scales + (size_t)bw_g0 * N + (size_t)t * RT;
+            const uint8_t *zbase = a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT;
+#pragma unroll
+            for (int u = 0; u < BW_UNITS; ++u) {
+                bw_lo[u] = load_at<uint4>(wbase, bw_off[u]);
+                if (BITS == 3) bw_hi[u] = load_at<uint4>(wbase, bw_offhi[u]);
+                bw_scale[u] = load_at<uint2>(sbase, bw_soff[u] * 2);
+                bw_zero[u] = load_at<uint32_t>(zbase, bw_soff[u]);
+            }
+        }
+    };
+
+    // ragged last main tile (C % 64 != 0) and extension tiles: predicated
+    auto load_edge = [&](int t) {
         const bool ext = t >= n_main;
-        const int r0 = ext ? (t - n_main) * RT : t * RT;       // first contraction index
-        const uint16_t *src = ext ? a.act_ext : a.act;
+        const int r0 = ext ? (t - n_main) * RT : t * RT;
         const int ld = ext ? a.RE : C;
+        const uint16_t *abase = (ext ? a.act_ext + (size_t)m0 * ld : act_rowblock) + r0;
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int idx = tid + i * THREADS;
-            const int row = idx / (RT / 8), ch = idx % (RT / 8);
-            const int m = m0 + row, cc = r0 + ch * 8;
+            const int row = idx / (RT / 8);
+            int m = m0 + row;
+            if (m > a.M - 1) m = a.M - 1;
             a_reg[i] = make_uint4(0, 0, 0, 0);
-            if (m < a.M && cc < ld) a_reg[i] = *reinterpret_cast<const uint4 *>(src + (size_t)m * ld + cc);
+            if (r0 + a_col[i] < ld) a_reg[i] = load_at<uint4>(abase, (uint32_t)(((size_t)(m - m0) * ld + a_col[i]) * 2));
         }
         if (ext) {
 #pragma unroll
             for (int i = 0; i < W_CH; ++i) {
                 const int idx = tid + i * THREADS;
                 const int row = idx / (RT / 8), ch = idx % (RT / 8);
-                const int c = c0 + row, cc = r0 + ch * 8;
+                int c = c0 + row;
+                if (c > Cout - 1) c = Cout - 1;
+                const int cc = r0 + ch * 8;
                 w_reg[i] = make_uint4(0, 0, 0, 0);
-                if (c < Cout && cc < a.RE) w_reg[i] = *reinterpret_cast<const uint4 *>(a.w_ext + (size_t)c * a.RE + cc);
+                if (cc < a.RE) w_reg[i] = *reinterpret_cast<const uint4 *>(a.w_ext + (size_t)c * a.RE + cc);
             }
             return;
         }
         if (!BWD) {
 #pragma unroll
             for (int u = 0; u < FW_UNITS; ++u) {
-                const int idx = tid + u * THREADS;
-                const int nl = idx % CT, kb = idx / CT;
-                const int n = c0 + nl, k = r0 + kb * 32;
-                const bool ok = n < N && k < K;
+                const int blk = t * (RT / 32) + fw_kb[u];
+                const bool ok = blk * 32 < K;
+                const int blk_c = ok ? blk : 0;
+                const uint32_t *wbase = a.w.qweight + (size_t)blk_c * BITS * N;
 #pragma unroll
-                for (int j = 0; j < BITS; ++j)
-                    fw_words[u][j] = ok ? a.w.qweight[(size_t)((k / 32) * BITS + j) * N + n] : 0u;
-                if (ok) {
-                    const size_t gi = (size_t)(k / a.w.group) * N + n;
-                    fw_dq[u] = make_dq(a.w.scales[gi], a.w.zeros[gi]);
-                } else {
-                    fw_dq[u].scale = 0.f;
-                    fw_dq[u].bias = 0.f;
-                }
+                for (int j = 0; j < BITS; ++j) fw_words[u][j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off[u]);
+                const size_t grow = (size_t)d.group_of_block((uint32_t)blk_c) * N;
+                // scale bits 0 -> every weight of the block dequantizes to +0
+                fw_sz[u] = ok ? (uint32_t)a.w.scales[grow + fw_n[u]] | ((uint32_t)a.w.zeros[grow + fw_n[u]] << 16) : 0u;
             }
         } else {
+            const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + r0;
+            const uint16_t *sbase = a.w.scales + (size_t)bw_g0 * N + r0;
+            const uint8_t *zbase = a.w.zeros + (size_t)bw_g0 * N + r0;
 #pragma unroll
             for (int u = 0; u < BW_UNITS; ++u) {
                 const int idx = tid + u * THREADS;
-                const int no = idx % (RT / 8), ko = idx / (RT / 8);
-                const int n = r0 + no * 8, k = c0 + ko * 8;
-                const bool ok = n < N && k < K;
-                const int bit = k * BITS;                 // first stream bit of the 8-code chunk
-                const int row = bit >> 5;
-                bw_shift[u] = bit & 31;
-                const int last_row = K * BITS / 32 - 1;
-                const int row_hi = row + 1 > last_row ? last_row : row + 1;
+                const int no = idx % (RT / 4);
+                const bool ok = r0 + no * 4 < N;
+                bw_lo[u] = make_uint4(0, 0, 0, 0);
+                bw_hi[u] = make_uint4(0, 0, 0, 0);
+                bw_scale[u] = make_uint2(0, 0);
+                bw_zero[u] = 0;
                 if (ok) {
-                    const uint4 *p = reinterpret_cast<const uint4 *>(a.w.qweight + (size_t)row * N + n);
-                    const uint4 l0 = p[0], l1 = p[1];
-                    bw_lo[u][0] = l0.x; bw_lo[u][1] = l0.y; bw_lo[u][2] = l0.z; bw_lo[u][3] = l0.w;
-                    bw_lo[u][4] = l1.x; bw_lo[u][5] = l1.y; bw_lo[u][6] = l1.z; bw_lo[u][7] = l1.w;
-                    if (BITS == 3) {
-                        const uint4 *ph = reinterpret_cast<const uint4 *>(a.w.qweight + (size_t)row_hi * N + n);
-                        const uint4 h0 = ph[0], h1 = ph[1];
-                        bw_hi[u][0] = h0.x; bw_hi[u][1] = h0.y; bw_hi[u][2] = h0.z; bw_hi[u][3] = h0.w;
-                        bw_hi[u][4] = h1.x; bw_hi[u][5] = h1.y; bw_hi[u][6] = h1.z; bw_hi[u][7] = h1.w;
-                    }
-                    const size_t gi = (size_t)(k / a.w.group) * N + n;
-                    const uint4 sc = *reinterpret_cast<const uint4 *>(a.w.scales + gi);
-                    bw_scale[u][0] = sc.x; bw_scale[u][1] = sc.y; bw_scale[u][2] = sc.z; bw_scale[u][3] = sc.w;
-                    const uint2 zz = *reinterpret_cast<const uint2 *>(a.w.zeros + gi);
-                    bw_zero[u][0] = zz.x; bw_zero[u][1] = zz.y;
-                } else {
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) { bw_lo[u][i] = 0; bw_hi[u][i] = 0; }
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) bw_scale[u][i] = 0;   // scale 0 -> weight 0
-                    bw_zero[u][0] = bw_zero[u][1] = 0;
+                    bw_lo[u] = load_at<uint4>(wbase, bw_off[u]);
+                    if (BITS == 3) bw_hi[u] = load_at<uint4>(wbase, bw_offhi[u]);
+                    bw_scale[u] = load_at<uint2>(sbase, bw_soff[u] * 2);
+                    bw_zero[u] = load_at<uint32_t>(zbase, bw_soff[u]);
                 }
             }
         }
     };
 
-    auto store_tile = [&](int t) {
-        const bool ext = t >= n_main;
+    auto store_tile = [&](bool ext, uint16_t *As, uint16_t *Ws) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int idx = tid + i * THREADS;
@@ -187,39 +292,43 @@ __global__ __launch_bounds__(THREADS) void gemm_tile_kernel(GemmArgs a, int tile
 #pragma unroll
             for (int u = 0; u < FW_UNITS; ++u) {
                 const int idx = tid + u * THREADS;
-                const int nl = idx % CT, kb = idx / CT;
+                const int nl = idx % CT;
+                const DqConst dq = make_dq((uint16_t)(fw_sz[u] & 0xFFFFu), (uint8_t)(fw_sz[u] >> 16));
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     uint32_t o[4];
-                    dequant_chunk<BITS>(block_chunk<BITS>(fw_words[u], j), fw_dq[u], o);
-                    *reinterpret_cast<uint4 *>(Ws + nl * LROW + kb * 32 + j * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+                    dequant_chunk<BITS>(block_chunk<BITS>(fw_words[u], j), dq, o);
+                    *reinterpret_cast<uint4 *>(Ws + nl * LROW + fw_kb[u] * 32 + j * 8) = make_uint4(o[0], o[1], o[2], o[3]);
                 }
             }
         } else {
 #pragma unroll
             for (int u = 0; u < BW_UNITS; ++u) {
                 const int idx = tid + u * THREADS;
-                const int no = idx % (RT / 8), ko = idx / (RT / 8);
-                uint32_t chunk[8];
-                DqConst dq[8];
+                const int no = idx % (RT / 4), ko = idx / (RT / 4);
+                const uint32_t lo[4] = {bw_lo[u].x, bw_lo[u].y, bw_lo[u].z, bw_lo[u].w};
+                const uint32_t hi[4] = {bw_hi[u].x, bw_hi[u].y, bw_hi[u].z, bw_hi[u].w};
+                const uint32_t sc[2] = {bw_scale[u].x, bw_scale[u].y};
+                uint32_t chunk[4];
+                DqConst dq[4];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
+                for (int i = 0; i < 4; ++i) {
                     if (BITS == 3)
-                        chunk[i] = __builtin_amdgcn_alignbit(bw_hi[u][i], bw_lo[u][i], bw_shift[u]);
+                        chunk[i] = __builtin_amdgcn_alignbit(hi[i], lo[i], bw_shift[u]);
                     else
-                        chunk[i] = bw_lo[u][i] >> bw_shift[u];
-                    const uint16_t sb = (uint16_t)(bw_scale[u][i >> 1] >> ((i & 1) * 16));
-                    const uint8_t zb = (uint8_t)(bw_zero[u][i >> 2] >> ((i & 3) * 8));
+                        chunk[i] = lo[i] >> bw_shift[u];
+                    const uint16_t sb = bw_kok[u] ? (uint16_t)(sc[i >> 1] >> ((i & 1) * 16)) : (uint16_t)0;
+                    const uint8_t zb = (uint8_t)(bw_zero[u] >> (i * 8));
                     dq[i] = make_dq(sb, zb);
                 }
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) {
-                    uint32_t o[4];
+                    uint32_t o[2];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                    for (int i = 0; i < 2; ++i)
                         o[i] = pack_bf16x2(dq_value(chunk_code<BITS>(chunk[2 * i], kk), dq[2 * i]),
                                            dq_value(chunk_code<BITS>(chunk[2 * i + 1], kk), dq[2 * i + 1]));
-                    *reinterpret_cast<uint4 *>(Ws + (ko * 8 + kk) * LROW + no * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+                    *reinterpret_cast<uint2 *>(Ws + (ko * 8 + kk) * LROW + no * 4) = make_uint2(o[0], o[1]);
                 }
             }
         }
@@ -237,55 +346,145 @@ __global__ __launch_bounds__(THREADS) void gemm_tile_kernel(GemmArgs a, int tile
 
     const int wm = wave / (CT / WN), wn = wave % (CT / WN);
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
+    const int a_frag_off = (wm * WM + frag_row) * LROW + frag_k;
+    const int w_frag_off = (wn * WN + frag_row) * LROW + frag_k;
 
-    load_tile(0);
-    for (int t = 0; t < n_tiles; ++t) {
-        store_tile(t);
-        __syncthreads();
-        if (t + 1 < n_tiles) load_tile(t + 1);
-        int ksteps = RT / 16;
-        if (t >= n_main) {
-            const int left = a.RE - (t - n_main) * RT;
-            if (left < RT) ksteps = left / 16;
-        }
-        for (int ks = 0; ks < ksteps; ++ks) {
-            bf16x8 af[TI], bf[TJ];
+    struct Frags {
+        bf16x8 af[TI], bf[TJ];
+    };
+    auto load_frags = [&](Frags &f, const uint16_t *As, const uint16_t *Ws, int ks) {
 #pragma unroll
-            for (int i = 0; i < TI; ++i)
-                af[i] = *reinterpret_cast<const bf16x8 *>(As + (wm * WM + i * 32 + frag_row) * LROW + ks * 16 + frag_k);
+        for (int i = 0; i < TI; ++i)
+            f.af[i] = *reinterpret_cast<const bf16x8 *>(As + a_frag_off + i * 32 * LROW + ks * 16);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+            f.bf[j] = *reinterpret_cast<const bf16x8 *>(Ws + w_frag_off + j * 32 * LROW + ks * 16);
+    };
+    auto mfma_frags = [&](const Frags &f) {
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
 #pragma unroll
             for (int j = 0; j < TJ; ++j)
-                bf[j] = *reinterpret_cast<const bf16x8 *>(Ws + (wn * WN + j * 32 + frag_row) * LROW + ks * 16 + frag_k);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
+    };
+
+    // a full 64-deep tile: fragments of step ks+1 are fetched from LDS while the MFMAs of
+    // step ks run; the scheduling barriers keep the compiler from hoisting every fetch
+    auto mfma_full = [&](const uint16_t *As, const uint16_t *Ws) {
+        Frags f[2];
+        load_frags(f[0], As, Ws, 0);
 #pragma unroll
-            for (int i = 0; i < TI; ++i)
-#pragma unroll
-                for (int j = 0; j < TJ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        for (int ks = 0; ks < RT / 16; ++ks) {
+            if (ks + 1 < RT / 16) load_frags(f[(ks + 1) & 1], As, Ws, ks + 1);
+            mfma_frags(f[ks & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // ---- steady state: full main tiles only, no predicates -----------------------
+    uint16_t *const As0 = lds, *const Ws0 = lds + MT * LROW;
+    if (n_full > 0) {
+        if (DB) {
+            // Two LDS buffers.  In step t the MFMAs read tile t from one buffer while tile
+            // t+1 is dequantized into the other and the raw words of tile t+2 are fetched
+            // into registers.  Loads and stores past the last full tile are clamped
+            // repeats: they keep the loop body unconditional and are never consumed.
+            load_main(0);
+            store_tile(false, As0, Ws0);
+            __syncthreads();
+            load_main(n_full > 1 ? 1 : 0);
+            if (wave < NWAVES / 2) {
+                // waves w and w + NWAVES/2 share a SIMD and take the two halves of a step
+                // in opposite order, so that one's MFMAs cover the other's VALU work
+                for (int t = 0; t < n_full; ++t) {
+                    uint16_t *cur = lds + (t & 1) * BUF, *nxt = lds + ((t + 1) & 1) * BUF;
+                    mfma_full(cur, cur + MT * LROW);
+                    store_tile(false, nxt, nxt + MT * LROW);
+                    load_main(t + 2 < n_full ? t + 2 : n_full - 1);
+                    __syncthreads();
+                }
+            } else {
+                for (int t = 0; t < n_full; ++t) {
+                    uint16_t *cur = lds + (t & 1) * BUF, *nxt = lds + ((t + 1) & 1) * BUF;
+                    store_tile(false, nxt, nxt + MT * LROW);
+                    load_main(t + 2 < n_full ? t + 2 : n_full - 1);
+                    mfma_full(cur, cur + MT * LROW);
+                    __syncthreads();
+                }
+            }
+        } else {
+            load_main(0);
+            for (int t = 0; t < n_full; ++t) {
+                store_tile(false, As0, Ws0);
+                __syncthreads();
+                load_main(t + 1 < n_full ? t + 1 : n_full - 1);
+                mfma_full(As0, Ws0);
+                __syncthreads();
+            }
+        }
+    }
+
+    // ---- tail: a ragged last main tile and the adapter extension, one at a time ----
+    for (int t = n_full; t < n_tiles; ++t) {
+        const bool ext = t >= n_main;
+        load_edge(t);
+        store_tile(ext, As0, Ws0);
+        __syncthreads();
+        int ksteps = RT / 16;
+        if (ext) {
+            ksteps = (a.RE - (t - n_main) * RT) / 16;
+            if (ksteps > RT / 16) ksteps = RT / 16;
+        }
+        for (int ks = 0; ks < ksteps; ++ks) {
+            Frags f;
+            load_frags(f, As0, Ws0, ks);
+            mfma_frags(f);
         }
         __syncthreads();
     }
 
-    // ---- epilogue: one RNE to bfloat16, guarded stores --------------------------
+    // ---- epilogue: one RNE to bfloat16; 32x64 patches go through LDS so that the
+    // global stores are 16 bytes per lane and 128 contiguous bytes per row ----------
+    uint16_t *patch = lds + wave * (32 * LROW);        // per-wave [32][LROW]
 #pragma unroll
-    for (int i = 0; i < TI; ++i)
+    for (int i = 0; i < TI; ++i) {
 #pragma unroll
-        for (int j = 0; j < TJ; ++j) {
-            const int col = c0 + wn * WN + j * 32 + (lane & 31);
+        for (int j = 0; j < TJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * WM + i * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-                if (row < a.M && col < Cout) a.out[(size_t)row * Cout + col] = float_to_bf16_bits(acc[i][j][v]);
+                const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+                patch[prow * LROW + j * 32 + (lane & 31)] = float_to_bf16_bits(acc[i][j][v]);
             }
+        // the patch is private to the wave: a wave-level wait is enough
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int idx = lane + q * 64;            // 256 chunks of 16 bytes: 32 rows x 8
+            const int prow = idx / 8, ch = idx % 8;
+            const uint4 v = *reinterpret_cast<const uint4 *>(patch + prow * LROW + ch * 8);
+            const int row = m0 + wm * WM + i * 32 + prow;
+            const int col = c0 + wn * WN + ch * 8;
+            if (row < a.M && col < Cout) *reinterpret_cast<uint4 *>(a.out + (size_t)row * Cout + col) = v;
         }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
-template <int BITS, bool BWD, int MT, int CT, int WM, int WN>
+template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, bool DB, int OCC>
 static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_t stream) {
     const int Cout = BWD ? a.w.K : a.w.N;
-    const int tiles_m = (a.M + MT - 1) / MT, tiles_c = (Cout + CT - 1) / CT;
-    const int blocks = (tiles_m * tiles_c + 7) / 8 * 8;
-    const size_t lds_bytes = (size_t)(MT + CT) * LROW * sizeof(uint16_t);
-    auto kern = gemm_tile_kernel<BITS, BWD, MT, CT, WM, WN>;
+    GemmDev d;
+    d.a = a;
+    d.tiles_m = (a.M + MT - 1) / MT;
+    d.tiles_c = (Cout + CT - 1) / CT;
+    d.blocks_per_group = (uint32_t)(a.w.group / 32);
+    d.blocks_per_group_magic = d.blocks_per_group > 1 ? (uint32_t)((1ull << 32) / d.blocks_per_group) + 1u : 0u;
+    const int blocks = (d.tiles_m * d.tiles_c + 7) / 8 * 8;
+    const size_t lds_bytes = (size_t)(MT + CT) * LROW * sizeof(uint16_t) * (DB ? 2 : 1);
+    static_assert((size_t)(MT + CT) * (DB ? 2 : 1) >= (size_t)(THREADS / 64) * 32, "epilogue patches fit");
+    auto kern = gemm_tile_kernel<BITS, BWD, THREADS, MT, CT, WM, WN, DB, OCC>;
     // raise the dynamic-LDS limit once per variant and device (not a stream operation,
     // but keep it out of the steady state and out of graph captures after the first call)
     static bool configured[64] = {};
@@ -299,20 +498,55 @@ static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_
         if (dev >= 0 && dev < 64) configured[dev] = true;
     }
     prof_before(name, stream);
-    kern<<<blocks, THREADS, lds_bytes, stream>>>(a, tiles_m, tiles_c);
+    kern<<<blocks, THREADS, lds_bytes, stream>>>(d);
     prof_after(stream);
     return hipGetLastError();
+}
+
+// Tile variants.  `pick` may be forced with the environment variable MODULORA_TILE
+// (big | mid | small), a tuning knob for benchmarks.
+enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_SMALL };
+
+static TilePick forced_pick() {
+    static int cached = -1;
+    if (cached < 0) {
+        const char *e = std::getenv("MODULORA_TILE");
+        cached = PICK_AUTO;
+        if (e) {
+            if (!std::strcmp(e, "big")) cached = PICK_BIG;
+            else if (!std::strcmp(e, "mid")) cached = PICK_MID;
+            else if (!std::strcmp(e, "small")) cached = PICK_SMALL;
+        }
+    }
+    return (TilePick)cached;
 }
 
 template <int BITS, bool BWD>
 static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
     const int Cout = BWD ? a.w.K : a.w.N;
-    const long tiles_large = (long)((a.M + 255) / 256) * ((Cout + 255) / 256);
-    if (a.M <= 32)
-        return launch_variant<BITS, BWD, 32, 256, 32, 64>(a, BWD ? "gemm_bwd_32x256" : "gemm_fwd_32x256", stream);
-    if (a.M <= 128 || tiles_large < 192)
-        return launch_variant<BITS, BWD, 128, 256, 64, 128>(a, BWD ? "gemm_bwd_128x256" : "gemm_fwd_128x256", stream);
-    return launch_variant<BITS, BWD, 256, 256, 128, 128>(a, BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", stream);
+    TilePick pick = forced_pick();
+    if (pick == PICK_AUTO) {
+        const long tiles_big = (long)((a.M + 255) / 256) * ((Cout + 255) / 256);
+        const long tiles_mid = (long)((a.M + 255) / 256) * ((Cout + 127) / 128);
+        if (a.M <= 32) pick = PICK_SMALL;
+        else {
+            // rounds of 256 CUs; a mid tile costs about half a big one
+            const double cost_big = (double)((tiles_big + 255) / 256);
+            const double cost_mid = 0.5 * (double)((tiles_mid + 255) / 256) * 1.1;
+            pick = cost_big <= cost_mid ? PICK_BIG : PICK_MID;
+        }
+    }
+    switch (pick) {
+        case PICK_SMALL:
+            return launch_variant<BITS, BWD, 256, 32, 256, 32, 64, false, 1>(
+                a, BWD ? "gemm_bwd_32x256" : "gemm_fwd_32x256", stream);
+        case PICK_MID:
+            return launch_variant<BITS, BWD, 256, 256, 128, 128, 64, false, 2>(
+                a, BWD ? "gemm_bwd_256x128" : "gemm_fwd_256x128", stream);
+        default:
+            return launch_variant<BITS, BWD, 512, 256, 256, 128, 64, true, 2>(
+                a, BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", stream);
+    }
 }
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream) {
