@@ -16,7 +16,8 @@ from typing import Optional
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libmodulora.so")
+# MODULORA_LIB may point at another build of the same library (e.g. one compiled with other flags)
+LIB_PATH = os.environ.get("MODULORA_LIB") or os.path.join(_PKG, "libmodulora.so")
 
 OK = 0
 STATUS_NAMES = {

@@ -94,4 +94,37 @@ __device__ __forceinline__ void dequant_chunk(uint32_t chunk, const DqConst &c, 
     }
 }
 
+// Dequantize a whole 32-code block (BITS words, one scale and zero): 32 bfloat16 in 16
+// registers, code 0 in the low half of out[0].  For 4- and 2-bit codes the fields are
+// first spread to one code per byte with a few AND/shift operations, so that each code
+// then costs one byte->float conversion (v_cvt_f32_ubyteN) instead of extract + convert.
+template <int BITS>
+__device__ __forceinline__ void dequant_block(const uint32_t *w, const DqConst &c, uint32_t out[16]) {
+    if (BITS == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)   // codes 2i (lo byte i) and 2i+1 (hi byte i)
+                out[j * 4 + i] = pack_bf16x2(dq_value((lo >> (8 * i)) & 0xFFu, c), dq_value((hi >> (8 * i)) & 0xFFu, c));
+        }
+    } else if (BITS == 2) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {     // word h holds codes 16h .. 16h+15
+            uint32_t m[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) m[t] = (w[h] >> (2 * t)) & 0x03030303u;   // byte b of m[t] = code 4b + t
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { // codes 2i, 2i+1 of the word
+                const int c0 = 2 * i, c1 = 2 * i + 1;
+                out[h * 8 + i] = pack_bf16x2(dq_value((m[c0 & 3] >> (8 * (c0 >> 2))) & 0xFFu, c),
+                                             dq_value((m[c1 & 3] >> (8 * (c1 >> 2))) & 0xFFu, c));
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dequant_chunk<BITS>(block_chunk<BITS>(w, j), c, out + 4 * j);
+    }
+}
+
 }  // namespace mlr

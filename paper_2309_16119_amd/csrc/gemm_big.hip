@@ -1,0 +1,434 @@
+// The large-M variant of the fused dequantize + bf16 MFMA tile kernel: a 256 x 256
+// output tile per workgroup, 8 waves (two per SIMD) of 128 x 64 each, 64-deep steps on
+// two LDS buffers.  Same mathematics as gemm_tile.hip (ModuLoRA Figure 1: forward
+// X What^T and backward dY What with What re-materialized from the packed codes, plus
+// the adapter term of eq. (3) as an extended contraction); what differs is the data path,
+// chosen from what was measured on MI355X:
+//
+//   - LDS stores from registers (ds_write_b128) sustain only ~70 B/clk per CU while
+//     LDS reads sustain ~200: the activation tile therefore never passes through
+//     registers -- it is fetched with direct global->LDS loads (16 B per lane), and only
+//     the dequantized weight tile is written with ds_write.
+//   - Direct loads place lane i's 16 bytes at LDS base + 16 i, so rows cannot be padded.
+//     Rows are 128 B and the 16-byte chunk index is XOR-swizzled with (row >> 1) & 7;
+//     the 16 lanes that hit the banks together (rows r..r+15, same logical chunk) then
+//     fall on 16 different 4-bank groups for both tiles, for reads and for writes.
+//   - The two waves of a SIMD run the halves of a step in opposite order (MFMA of tile t
+//     first / dequantization of tile t+1 first), so that VALU and MFMA overlap.
+//   - The direct loads are issued from inline assembly and awaited with an explicit
+//     s_waitcnt before the step's barrier; the compiler's own (in-order) vmcnt
+//     bookkeeping for the weight-word loads stays valid, only more conservative.
+#include "gemm_common.h"
+
+namespace mlr {
+
+namespace big {
+constexpr int THREADS = 512, NWAVES = 8;
+constexpr int MT = 256, CT = 256, WM = 128, WN = 64, RT = 64;
+constexpr int TI = WM / 32, TJ = WN / 32;
+constexpr int ROW_BYTES = RT * 2;                 // 128
+constexpr int A_BYTES = MT * ROW_BYTES;           // 32 KB
+constexpr int BUF_BYTES = (MT + CT) * ROW_BYTES;  // 64 KB
+constexpr int A_CH = MT * 8 / THREADS;            // 16-byte activation chunks per thread = 4
+constexpr int W_CH = CT * 8 / THREADS;            // 16-byte chunks of an extension W tile per thread
+constexpr int FW_UNITS = CT * 2 / THREADS;        // (column, 32-code block) units per thread = 1
+constexpr int BW_UNITS = (CT / 8) * (RT / 4) / THREADS;   // (4 n, 8 k) units per thread = 1
+constexpr int PATCH_ROW = 72;                     // epilogue patch row stride (elements)
+
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+// byte offset of logical 16-byte chunk `c` of row `row` inside a tile
+__device__ __forceinline__ int tile_off(int row, int c) { return row * ROW_BYTES + ((c ^ swz(row)) << 4); }
+}  // namespace big
+
+// One direct global->LDS load of 16 bytes per lane: lane i's data lands at
+// lds_base + 16 i (lds_base wave-uniform, in M0).
+__device__ __forceinline__ void load_to_lds_16(const void *gbase_uniform, uint32_t voff_bytes, uint32_t lds_base_uniform) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base_uniform), "v"(voff_bytes), "s"(gbase_uniform)
+                 : "memory");
+}
+
+// Register loads issued from inline assembly (uniform base + per-lane byte offset).  The
+// compiler does not know that they are in flight: every consumer must sit behind
+// wait_loads(), which also ties the destination registers so that no use can be moved
+// ahead of the wait.  This keeps the compiler from sprinkling conservative vmcnt waits
+// (which would also wait for the direct loads) through the MFMA phase.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void aload_b32(uint32_t &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void aload_u16(uint32_t &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_ushort %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void aload_u8(uint32_t &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_ubyte %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void aload_b64(u32x2 &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void aload_b128(u32x4 &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+
+template <int BITS, bool BWD>
+__global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d) {
+    using namespace big;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const GemmArgs &a = d.a;
+    const TileCoord tcoord = tile_of_block(blockIdx.x, d.tiles_m, d.tiles_c);
+    if (tcoord.tm < 0) return;   // grid padded to a multiple of 8
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
+    const int m0 = tcoord.tm * MT, c0 = tcoord.tc * CT;
+    const int K = a.w.K, N = a.w.N;
+    const int C = BWD ? N : K;
+    const int Cout = BWD ? K : N;
+    const int n_full = C / RT;
+    const int n_main = (C + RT - 1) / RT;
+    const int n_ext = (a.RE + RT - 1) / RT;
+    const int n_tiles = n_main + n_ext;
+    // LDS byte address of the dynamic segment (what M0 wants)
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+
+    // ---- activation tile: direct loads ------------------------------------------
+    // chunk idx = i*512 + tid sits at byte 16*idx of the tile: row idx/8, physical chunk
+    // idx%8, which holds logical chunk (idx%8) ^ swz(row).
+    uint32_t a_voff[A_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+        const int idx = i * THREADS + tid;
+        const int row = idx >> 3, lc = (idx & 7) ^ swz(idx >> 3);
+        int m = m0 + row;
+        if (m > a.M - 1) m = a.M - 1;
+        a_voff[i] = (uint32_t)(((size_t)(m - m0) * C + lc * 8) * 2);
+    }
+    const uint16_t *act_rowblock = a.act + (size_t)m0 * C;
+    auto issue_a = [&](int t, int buf) {
+        const uint16_t *g = act_rowblock + (size_t)t * RT;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i)
+            load_to_lds_16(g, a_voff[i], lds0 + buf * BUF_BYTES + i * (THREADS * 16) + wave * 1024);
+    };
+
+    // ---- weight units -------------------------------------------------------------
+    uint32_t fw_off = 0, fw_n = 0;
+    int fw_kb = 0;
+    uint32_t bw_off = 0, bw_offhi = 0, bw_soff = 0;
+    int bw_shift = 0, bw_row0 = 0, bw_g0 = 0;
+    bool bw_kok = true;
+    if (!BWD) {
+        int n = c0 + (tid & (CT - 1));
+        if (n > N - 1) n = N - 1;
+        fw_n = (uint32_t)n;
+        fw_off = (uint32_t)n * 4u;
+        fw_kb = uniform(tid >> 8);
+    } else {
+        bw_row0 = (c0 * BITS) >> 5;
+        bw_g0 = (int)d.group_of_block((uint32_t)(c0 >> 5));
+        const int last_row = K * BITS / 32 - 1;
+        const int no = tid & 15, ko = tid >> 4;
+        int k = c0 + ko * 8;
+        bw_kok = k < K;
+        if (k > K - 8) k = K - 8;
+        const int bit = k * BITS, row = bit >> 5;
+        const int row_hi = row + 1 > last_row ? last_row : row + 1;
+        bw_shift = bit & 31;
+        bw_off = (uint32_t)(((size_t)(row - bw_row0) * N + no * 4) * 4);
+        bw_offhi = (uint32_t)(((size_t)(row_hi - bw_row0) * N + no * 4) * 4);
+        bw_soff = (uint32_t)((size_t)((int)d.group_of_block((uint32_t)(k >> 5)) - bw_g0) * N + no * 4);
+    }
+
+    // staging registers of the asm loads
+    uint32_t fw_words[BITS] = {};
+    uint32_t fw_scale = 0, fw_zero = 0;
+    u32x4 bw_lo = {0, 0, 0, 0}, bw_hi = {0, 0, 0, 0};
+    u32x2 bw_scale = {0, 0};
+    uint32_t bw_zero = 0;
+
+    auto load_w = [&](int t) {     // raw words, scales and zeros of full main tile t -> registers (async)
+        if (!BWD) {
+            const int blk = t * 2 + fw_kb;
+            const uint32_t *wbase = a.w.qweight + (size_t)blk * BITS * N;
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) aload_b32(fw_words[j], wbase + (size_t)j * N, fw_off);
+            const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
+            aload_u16(fw_scale, a.w.scales + grow, fw_n * 2);
+            aload_u8(fw_zero, a.w.zeros + grow, fw_n);
+        } else {
+            const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
+            aload_b128(bw_lo, wbase, bw_off);
+            if (BITS == 3) aload_b128(bw_hi, wbase, bw_offhi);
+            aload_b64(bw_scale, a.w.scales + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff * 2);
+            aload_b32(bw_zero, a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff);
+        }
+    };
+    // wait for every outstanding load of this wave (direct and staged) and pin the staged
+    // registers behind the wait
+    auto wait_loads = [&]() {
+        if (!BWD) {
+            if (BITS == 2)
+                asm volatile("s_waitcnt vmcnt(0)" : "+v"(fw_words[0]), "+v"(fw_words[1]), "+v"(fw_scale), "+v"(fw_zero)::"memory");
+            else if (BITS == 3)
+                asm volatile("s_waitcnt vmcnt(0)" : "+v"(fw_words[0]), "+v"(fw_words[1]), "+v"(fw_words[2 % BITS]), "+v"(fw_scale), "+v"(fw_zero)::"memory");
+            else
+                asm volatile("s_waitcnt vmcnt(0)" : "+v"(fw_words[0]), "+v"(fw_words[1]), "+v"(fw_words[2 % BITS]), "+v"(fw_words[3 % BITS]), "+v"(fw_scale), "+v"(fw_zero)::"memory");
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(bw_lo), "+v"(bw_hi), "+v"(bw_scale), "+v"(bw_zero)::"memory");
+        }
+    };
+
+    auto store_w = [&](int buf) {  // dequantize the staged words into the W tile of buffer buf
+        unsigned char *Ws = smem + buf * BUF_BYTES + A_BYTES;
+        if (!BWD) {
+            const int nl = tid & (CT - 1);
+            const DqConst dq = make_dq((uint16_t)fw_scale, (uint8_t)fw_zero);
+            uint32_t o[16];
+            dequant_block<BITS>(fw_words, dq, o);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<uint4 *>(Ws + tile_off(nl, fw_kb * 4 + j)) =
+                    make_uint4(o[4 * j], o[4 * j + 1], o[4 * j + 2], o[4 * j + 3]);
+        } else {
+            const int no = tid & 15, ko = tid >> 4;
+            const uint32_t lo[4] = {bw_lo[0], bw_lo[1], bw_lo[2], bw_lo[3]};
+            const uint32_t hi[4] = {bw_hi[0], bw_hi[1], bw_hi[2], bw_hi[3]};
+            const uint32_t sc[2] = {bw_scale[0], bw_scale[1]};
+            uint32_t chunk[4];
+            DqConst dq[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                chunk[i] = BITS == 3 ? __builtin_amdgcn_alignbit(hi[i], lo[i], bw_shift) : lo[i] >> bw_shift;
+                const uint16_t sb = bw_kok ? (uint16_t)(sc[i >> 1] >> ((i & 1) * 16)) : (uint16_t)0;
+                dq[i] = make_dq(sb, (uint8_t)(bw_zero >> (i * 8)));
+            }
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                uint32_t o[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    o[i] = pack_bf16x2(dq_value(chunk_code<BITS>(chunk[2 * i], kk), dq[2 * i]),
+                                       dq_value(chunk_code<BITS>(chunk[2 * i + 1], kk), dq[2 * i + 1]));
+                *reinterpret_cast<uint2 *>(Ws + tile_off(ko * 8 + kk, no >> 1) + (no & 1) * 8) = make_uint2(o[0], o[1]);
+            }
+        }
+    };
+
+    // ---- accumulators and fragment addressing ------------------------------------
+    f32x16 acc[TI][TJ];
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int wm = wave >> 2, wn = wave & 3;
+    const int rowA = wm * WM + (lane & 31), rowW = wn * WN + (lane & 31);
+    // +32 rows leaves the swizzle unchanged, so one offset per 16-deep step serves all i / j
+    int offA[RT / 16], offW[RT / 16];
+#pragma unroll
+    for (int ks = 0; ks < RT / 16; ++ks) {
+        offA[ks] = tile_off(rowA, 2 * ks + (lane >> 5));
+        offW[ks] = A_BYTES + tile_off(rowW, 2 * ks + (lane >> 5));
+    }
+
+    struct Frags {
+        bf16x8 af[TI], bf[TJ];
+    };
+    auto load_frags = [&](Frags &f, const unsigned char *buf, int ks) {
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+            f.af[i] = *reinterpret_cast<const bf16x8 *>(buf + offA[ks] + i * 32 * ROW_BYTES);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+            f.bf[j] = *reinterpret_cast<const bf16x8 *>(buf + offW[ks] + j * 32 * ROW_BYTES);
+    };
+    auto mfma_frags = [&](const Frags &f) {
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
+    };
+    auto mfma_full = [&](const unsigned char *buf) {
+        Frags f[2];
+        load_frags(f[0], buf, 0);
+#pragma unroll
+        for (int ks = 0; ks < RT / 16; ++ks) {
+            // fetch the next step's fragments first, then run this step's 8 MFMAs over them
+            if (ks + 1 < RT / 16) load_frags(f[(ks + 1) & 1], buf, ks + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_frags(f[ks & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    auto wait_direct_loads_and_sync = [&]() {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    };
+
+    // ---- steady state: full main tiles -------------------------------------------
+    if (n_full > 0) {
+        issue_a(0, 0);
+        load_w(0);
+        wait_loads();
+        store_w(0);
+        __syncthreads();
+        if (wave < NWAVES / 2) {
+            // this half of the waves: fetch t+1, MFMA tile t, then dequantize t+1
+            for (int t = 0; t < n_full; ++t) {
+                const int cur = t & 1, nxt = cur ^ 1;
+                const int tn = t + 1 < n_full ? t + 1 : n_full - 1;   // clamped repeat, never consumed
+                issue_a(tn, nxt);
+                load_w(tn);
+                mfma_full(smem + cur * BUF_BYTES);
+                wait_loads();
+                store_w(nxt);
+                __syncthreads();
+            }
+        } else {
+            // the other half: dequantize t+1 (fetched a step earlier), fetch t+2, MFMA tile t
+            load_w(n_full > 1 ? 1 : 0);
+            wait_loads();
+            for (int t = 0; t < n_full; ++t) {
+                const int cur = t & 1, nxt = cur ^ 1;
+                issue_a(t + 1 < n_full ? t + 1 : n_full - 1, nxt);
+                store_w(nxt);
+                load_w(t + 2 < n_full ? t + 2 : n_full - 1);
+                mfma_full(smem + cur * BUF_BYTES);
+                wait_loads();
+                __syncthreads();
+            }
+        }
+    }
+
+    // ---- tail: ragged last main tile and the adapter extension, one at a time, through
+    // registers into buffer 0 (predicated; a handful of tiles at most) ---------------
+    for (int t = n_full; t < n_tiles; ++t) {
+        const bool ext = t >= n_main;
+        const int r0 = ext ? (t - n_main) * RT : t * RT;
+        const int ld = ext ? a.RE : C;
+        const uint16_t *abase = (ext ? a.act_ext + (size_t)m0 * ld : act_rowblock) + r0;
+        unsigned char *As = smem, *Ws = smem + A_BYTES;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            const int idx = i * THREADS + tid;
+            const int row = idx >> 3, ch = idx & 7;
+            int m = m0 + row;
+            if (m > a.M - 1) m = a.M - 1;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (r0 + ch * 8 < ld) v = load_at<uint4>(abase, (uint32_t)(((size_t)(m - m0) * ld + ch * 8) * 2));
+            *reinterpret_cast<uint4 *>(As + tile_off(row, ch)) = v;
+        }
+        if (ext) {
+#pragma unroll
+            for (int i = 0; i < W_CH; ++i) {
+                const int idx = i * THREADS + tid;
+                const int row = idx >> 3, ch = idx & 7;
+                int c = c0 + row;
+                if (c > Cout - 1) c = Cout - 1;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (r0 + ch * 8 < a.RE) v = *reinterpret_cast<const uint4 *>(a.w_ext + (size_t)c * a.RE + r0 + ch * 8);
+                *reinterpret_cast<uint4 *>(Ws + tile_off(row, ch)) = v;
+            }
+        } else if (!BWD) {
+            const int blk = t * 2 + fw_kb;
+            const bool ok = blk * 32 < K;
+            const int blk_c = ok ? blk : 0;
+            const uint32_t *wbase = a.w.qweight + (size_t)blk_c * BITS * N;
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) fw_words[j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off);
+            const size_t grow = (size_t)d.group_of_block((uint32_t)blk_c) * N;
+            fw_scale = ok ? (uint32_t)load_at<uint16_t>(a.w.scales + grow, fw_n * 2) : 0u;   // 0 -> weights +0
+            fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
+            store_w(0);
+        } else {
+            const bool ok = r0 + (tid & 15) * 4 < N;
+            bw_lo = u32x4{0, 0, 0, 0};
+            bw_hi = u32x4{0, 0, 0, 0};
+            bw_scale = u32x2{0, 0};
+            bw_zero = 0;
+            if (ok) {
+                const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + r0;
+                bw_lo = load_at<u32x4>(wbase, bw_off);
+                if (BITS == 3) bw_hi = load_at<u32x4>(wbase, bw_offhi);
+                bw_scale = load_at<u32x2>(a.w.scales + (size_t)bw_g0 * N + r0, bw_soff * 2);
+                bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
+            }
+            store_w(0);
+        }
+        __syncthreads();
+        int ksteps = RT / 16;
+        if (ext) {
+            ksteps = (a.RE - r0) / 16;
+            if (ksteps > RT / 16) ksteps = RT / 16;
+        }
+        for (int ks = 0; ks < ksteps; ++ks) {
+            Frags f;
+            // offA/offW are indexed with a runtime step here: recompute instead
+            const int c = 2 * ks + (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+                f.af[i] = *reinterpret_cast<const bf16x8 *>(smem + tile_off(rowA, c) + i * 32 * ROW_BYTES);
+#pragma unroll
+            for (int j = 0; j < TJ; ++j)
+                f.bf[j] = *reinterpret_cast<const bf16x8 *>(smem + A_BYTES + tile_off(rowW, c) + j * 32 * ROW_BYTES);
+            mfma_frags(f);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: one RNE to bfloat16; 32x64 patches go through LDS so that the global
+    // stores are 16 bytes per lane and 128 contiguous bytes per row ---------------------
+    uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + wave * (32 * PATCH_ROW);
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+                patch[prow * PATCH_ROW + j * 32 + (lane & 31)] = float_to_bf16_bits(acc[i][j][v]);
+            }
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the patch is private to the wave
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int idx = lane + q * 64;    // 256 chunks of 16 bytes: 32 rows x 8
+            const int prow = idx / 8, ch = idx % 8;
+            const uint4 v = *reinterpret_cast<const uint4 *>(patch + prow * PATCH_ROW + ch * 8);
+            const int row = m0 + wm * WM + i * 32 + prow;
+            const int col = c0 + wn * WN + ch * 8;
+            if (row < a.M && col < Cout) *reinterpret_cast<uint4 *>(a.out + (size_t)row * Cout + col) = v;
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <int BITS, bool BWD>
+static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
+    const GemmDev d = make_gemm_dev(a, big::MT, big::CT);
+    const int blocks = (d.tiles_m * d.tiles_c + 7) / 8 * 8;
+    const size_t lds_bytes = 2 * (size_t)big::BUF_BYTES;
+    auto kern = gemm_big_kernel<BITS, BWD>;
+    static bool configured[64] = {};
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
+    if (e != hipSuccess) return e;
+    prof_before(BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", stream);
+    kern<<<blocks, big::THREADS, lds_bytes, stream>>>(d);
+    prof_after(stream);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_big(const GemmArgs &a, hipStream_t stream) {
+    switch (a.w.bits) {
+        case 2: return a.backward ? launch_big<2, true>(a, stream) : launch_big<2, false>(a, stream);
+        case 3: return a.backward ? launch_big<3, true>(a, stream) : launch_big<3, false>(a, stream);
+        default: return a.backward ? launch_big<4, true>(a, stream) : launch_big<4, false>(a, stream);
+    }
+}
+
+}  // namespace mlr

@@ -35,8 +35,7 @@
 #include <cstdlib>
 #include <cstring>
 
-#include "device_common.h"
-#include "launch.h"
+#include "gemm_common.h"
 
 namespace mlr {
 
@@ -44,49 +43,12 @@ constexpr int RT = 64;         // contraction elements per LDS tile
 constexpr int LDS_PAD = 8;     // bf16 elements of row padding (row stride 144 B: conflict-free 16-B accesses)
 constexpr int LROW = RT + LDS_PAD;
 
-struct TileCoord {
-    int tm, tc;
-};
-
-// XCD-aware tile order: consecutive workgroup ids go round-robin over the 8 XCDs, so
-// give each XCD a contiguous run of tiles, and walk tiles row-block-fastest inside a
-// run so that neighbours on one XCD share the weight tile (and its L2 lines).
-__device__ __forceinline__ TileCoord tile_of_block(int bid, int tiles_m, int tiles_c) {
-    const int total = tiles_m * tiles_c;
-    const int per_xcd = (total + 7) / 8;
-    int t = (bid % 8) * per_xcd + bid / 8;
-    TileCoord tc;
-    if (t >= total) { tc.tm = -1; tc.tc = -1; return tc; }
-    tc.tc = t / tiles_m;
-    tc.tm = t % tiles_m;
-    return tc;
-}
-
-struct GemmDev {
-    GemmArgs a;
-    int tiles_m, tiles_c;
-    // group index of a 32-code block: blk / (group/32), as one multiply-high with
-    // magic = floor(2^32 / d) + 1 (exact for blk, d < 2^15); d == 1 is passed through
-    uint32_t blocks_per_group, blocks_per_group_magic;
-    __device__ __forceinline__ uint32_t group_of_block(uint32_t blk) const {
-        return blocks_per_group == 1 ? blk : __umulhi(blk, blocks_per_group_magic);
-    }
-};
-
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-template <typename T>
-__device__ __forceinline__ T load_at(const void *base, uint32_t byte_off) {
-    return *reinterpret_cast<const T *>(static_cast<const char *>(base) + byte_off);
-}
-
-template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, bool DB, int OCC>
+template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, int OCC>
 __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     constexpr int NWAVES = THREADS / 64;
     static_assert((MT / WM) * (CT / WN) == NWAVES, "wave grid covers the tile");
     static_assert(WM % 32 == 0 && WN == 64, "wave tile: rows in 32s, two 32-column MFMA tiles");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
-    constexpr int BUF = (MT + CT) * LROW;   // elements per buffer: As [MT][LROW] then Ws [CT][LROW]
 
     const GemmArgs &a = d.a;
     // grid is padded up to a multiple of 8 blocks; surplus blocks leave here
@@ -173,7 +135,8 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     // ---- register staging for one tile -------------------------------------
     uint4 a_reg[A_CH];
     uint32_t fw_words[BWD ? 1 : FW_UNITS][BITS];
-    uint32_t fw_sz[BWD ? 1 : FW_UNITS];          // scale bits | zero << 16
+    uint16_t fw_scale[BWD ? 1 : FW_UNITS];       // binary16 bits (0: block dequantizes to +0)
+    uint8_t fw_zero[BWD ? 1 : FW_UNITS];
     uint4 bw_lo[BWD ? BW_UNITS : 1], bw_hi[BWD ? BW_UNITS : 1];
     uint2 bw_scale[BWD ? BW_UNITS : 1];          // 4 binary16
     uint32_t bw_zero[BWD ? BW_UNITS : 1];        // 4 uint8
@@ -192,7 +155,8 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
 #pragma unroll
                 for (int j = 0; j < BITS; ++j) fw_words[u][j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off[u]);
                 const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
-                fw_sz[u] = (uint32_t)a.w.scales[grow + fw_n[u]] | ((uint32_t)a.w.zeros[grow + fw_n[u]] << 16);
+                fw_scale[u] = load_at<uint16_t>(a.w.scales + grow, fw_n[u] * 2);
+                fw_zero[u] = load_at<uint8_t>(a.w.zeros + grow, fw_n[u]);
             }
         } else {
             const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
@@ -247,7 +211,8 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
                 for (int j = 0; j < BITS; ++j) fw_words[u][j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off[u]);
                 const size_t grow = (size_t)d.group_of_block((uint32_t)blk_c) * N;
                 // scale bits 0 -> every weight of the block dequantizes to +0
-                fw_sz[u] = ok ? (uint32_t)a.w.scales[grow + fw_n[u]] | ((uint32_t)a.w.zeros[grow + fw_n[u]] << 16) : 0u;
+                fw_scale[u] = ok ? load_at<uint16_t>(a.w.scales + grow, fw_n[u] * 2) : (uint16_t)0;
+                fw_zero[u] = load_at<uint8_t>(a.w.zeros + grow, fw_n[u]);
             }
         } else {
             const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + r0;
@@ -293,7 +258,7 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
             for (int u = 0; u < FW_UNITS; ++u) {
                 const int idx = tid + u * THREADS;
                 const int nl = idx % CT;
-                const DqConst dq = make_dq((uint16_t)(fw_sz[u] & 0xFFFFu), (uint8_t)(fw_sz[u] >> 16));
+                const DqConst dq = make_dq(fw_scale[u], fw_zero[u]);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     uint32_t o[4];
@@ -368,15 +333,15 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
     };
 
-    // a full 64-deep tile: fragments of step ks+1 are fetched from LDS while the MFMAs of
-    // step ks run; the scheduling barriers keep the compiler from hoisting every fetch
+    // a full 64-deep tile.  Fragments are fetched per 16-deep step; the second wave of
+    // the SIMD covers the LDS latency, and keeping one set of fragments live (instead of
+    // prefetching the next) keeps the kernel under 256 registers without live-range splits.
     auto mfma_full = [&](const uint16_t *As, const uint16_t *Ws) {
-        Frags f[2];
-        load_frags(f[0], As, Ws, 0);
 #pragma unroll
         for (int ks = 0; ks < RT / 16; ++ks) {
-            if (ks + 1 < RT / 16) load_frags(f[(ks + 1) & 1], As, Ws, ks + 1);
-            mfma_frags(f[ks & 1]);
+            Frags f;
+            load_frags(f, As, Ws, ks);
+            mfma_frags(f);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -384,43 +349,13 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     // ---- steady state: full main tiles only, no predicates -----------------------
     uint16_t *const As0 = lds, *const Ws0 = lds + MT * LROW;
     if (n_full > 0) {
-        if (DB) {
-            // Two LDS buffers.  In step t the MFMAs read tile t from one buffer while tile
-            // t+1 is dequantized into the other and the raw words of tile t+2 are fetched
-            // into registers.  Loads and stores past the last full tile are clamped
-            // repeats: they keep the loop body unconditional and are never consumed.
-            load_main(0);
+        load_main(0);
+        for (int t = 0; t < n_full; ++t) {
             store_tile(false, As0, Ws0);
             __syncthreads();
-            load_main(n_full > 1 ? 1 : 0);
-            if (wave < NWAVES / 2) {
-                // waves w and w + NWAVES/2 share a SIMD and take the two halves of a step
-                // in opposite order, so that one's MFMAs cover the other's VALU work
-                for (int t = 0; t < n_full; ++t) {
-                    uint16_t *cur = lds + (t & 1) * BUF, *nxt = lds + ((t + 1) & 1) * BUF;
-                    mfma_full(cur, cur + MT * LROW);
-                    store_tile(false, nxt, nxt + MT * LROW);
-                    load_main(t + 2 < n_full ? t + 2 : n_full - 1);
-                    __syncthreads();
-                }
-            } else {
-                for (int t = 0; t < n_full; ++t) {
-                    uint16_t *cur = lds + (t & 1) * BUF, *nxt = lds + ((t + 1) & 1) * BUF;
-                    store_tile(false, nxt, nxt + MT * LROW);
-                    load_main(t + 2 < n_full ? t + 2 : n_full - 1);
-                    mfma_full(cur, cur + MT * LROW);
-                    __syncthreads();
-                }
-            }
-        } else {
-            load_main(0);
-            for (int t = 0; t < n_full; ++t) {
-                store_tile(false, As0, Ws0);
-                __syncthreads();
-                load_main(t + 1 < n_full ? t + 1 : n_full - 1);
-                mfma_full(As0, Ws0);
-                __syncthreads();
-            }
+            load_main(t + 1 < n_full ? t + 1 : n_full - 1);
+            mfma_full(As0, Ws0);
+            __syncthreads();
         }
     }
 
@@ -472,31 +407,16 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     }
 }
 
-template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, bool DB, int OCC>
+template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, int OCC>
 static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_t stream) {
-    const int Cout = BWD ? a.w.K : a.w.N;
-    GemmDev d;
-    d.a = a;
-    d.tiles_m = (a.M + MT - 1) / MT;
-    d.tiles_c = (Cout + CT - 1) / CT;
-    d.blocks_per_group = (uint32_t)(a.w.group / 32);
-    d.blocks_per_group_magic = d.blocks_per_group > 1 ? (uint32_t)((1ull << 32) / d.blocks_per_group) + 1u : 0u;
+    const GemmDev d = make_gemm_dev(a, MT, CT);
     const int blocks = (d.tiles_m * d.tiles_c + 7) / 8 * 8;
-    const size_t lds_bytes = (size_t)(MT + CT) * LROW * sizeof(uint16_t) * (DB ? 2 : 1);
-    static_assert((size_t)(MT + CT) * (DB ? 2 : 1) >= (size_t)(THREADS / 64) * 32, "epilogue patches fit");
-    auto kern = gemm_tile_kernel<BITS, BWD, THREADS, MT, CT, WM, WN, DB, OCC>;
-    // raise the dynamic-LDS limit once per variant and device (not a stream operation,
-    // but keep it out of the steady state and out of graph captures after the first call)
+    const size_t lds_bytes = (size_t)(MT + CT) * LROW * sizeof(uint16_t);
+    static_assert((size_t)(MT + CT) >= (size_t)(THREADS / 64) * 32, "epilogue patches fit");
+    auto kern = gemm_tile_kernel<BITS, BWD, THREADS, MT, CT, WM, WN, OCC>;
     static bool configured[64] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64 || !configured[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        if (dev >= 0 && dev < 64) configured[dev] = true;
-    }
     prof_before(name, stream);
     kern<<<blocks, THREADS, lds_bytes, stream>>>(d);
     prof_after(stream);
@@ -538,14 +458,13 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
     }
     switch (pick) {
         case PICK_SMALL:
-            return launch_variant<BITS, BWD, 256, 32, 256, 32, 64, false, 1>(
+            return launch_variant<BITS, BWD, 256, 32, 256, 32, 64, 1>(
                 a, BWD ? "gemm_bwd_32x256" : "gemm_fwd_32x256", stream);
         case PICK_MID:
-            return launch_variant<BITS, BWD, 256, 256, 128, 128, 64, false, 2>(
+            return launch_variant<BITS, BWD, 256, 256, 128, 128, 64, 2>(
                 a, BWD ? "gemm_bwd_256x128" : "gemm_fwd_256x128", stream);
         default:
-            return launch_variant<BITS, BWD, 512, 256, 256, 128, 64, true, 2>(
-                a, BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", stream);
+            return launch_gemm_big(a, stream);
     }
 }
 
