@@ -65,7 +65,13 @@ struct WsLayout {
 
 WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     WsLayout l{};
-    if (r <= 0) return l;
+    // the M <= 16 streaming kernels keep a re-ordered copy of the activations and the
+    // adapter partial sums in the workspace (also when r == 0)
+    const size_t small = M <= 16 ? mlr::smallm_ws_bytes(K, N, r) : 0;
+    if (r <= 0) {
+        l.total = small;
+        return l;
+    }
     const size_t RE = (size_t)mlr::lora_ext_len(r);
     const size_t maxdim = (size_t)(K > N ? K : N);
     size_t off = 0;
@@ -73,7 +79,7 @@ WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     l.w_ext = off;   off += align256(maxdim * RE * 2);
     l.p0 = off;      off += align256((size_t)M * r * 4);
     l.p1 = off;      off += align256((size_t)M * r * 4);
-    l.total = off;
+    l.total = off > small ? off : small;
     return l;
 }
 
@@ -161,6 +167,14 @@ int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M, const 
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
+    if (mlr::smallm_fwd_supported(view_of(w), M)) {
+        mlr::SmallArgs sa{};
+        sa.w = view_of(w);
+        sa.act = X; sa.M = M; sa.out = Y;
+        sa.A = A; sa.B = B; sa.r = r; sa.lora_scale = lora_scale;
+        sa.P_out = XA; sa.ws = ws;
+        return hip_status(mlr::launch_smallm_fwd(sa, st));
+    }
     mlr::GemmArgs g{};
     g.w = view_of(w);
     g.backward = false;

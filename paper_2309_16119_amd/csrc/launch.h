@@ -81,6 +81,22 @@ struct GradArgs {
 };
 hipError_t launch_lora_grad(const GradArgs &a, hipStream_t stream);
 
+// ---- smallm.hip: M <= 16 streaming kernels ------------------------------------
+struct SmallArgs {
+    LayerView w;
+    const uint16_t *act;  // bf16 [M][K] (forward) or [M][N] (backward)
+    int M;
+    uint16_t *out;        // bf16 [M][N] (forward) or [M][K] (backward)
+    const float *A, *B;   // adapter factors (ignored when r == 0)
+    int r;
+    float lora_scale;
+    float *P_out;         // XA / dYBt hand-off [M][r], may be NULL
+    void *ws;             // at least smallm_ws_bytes() bytes
+};
+bool smallm_fwd_supported(const LayerView &w, int M);
+size_t smallm_ws_bytes(int K, int N, int r);
+hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream);
+
 // dst[0..n) = 0.0f   (a fill kernel, so that callers may capture it in a HIP graph)
 hipError_t launch_fill_zero(float *dst, size_t n, hipStream_t stream);
 

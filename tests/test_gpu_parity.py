@@ -73,6 +73,14 @@ SHAPES = [
     (3, 736, 776, 300, 64, 736),     # one scale per row (g = K), maximum rank
     (2, 512, 2056, 515, 5, 128),
     (4, 2048, 512, 64, 0, 128),      # r = 0: the plain low-precision linear map
+    # M <= 16 with group sizes the streaming kernels accept (ragged last column block too)
+    (3, 1024, 808, 16, 8, 128),
+    (3, 2560, 264, 3, 5, 256),
+    (2, 768, 296, 5, 4, 64),
+    (2, 1024, 1032, 16, 16, 128),
+    (4, 512, 1304, 1, 16, 32),
+    (4, 1152, 520, 13, 40, 128),
+    (3, 1536, 512, 9, 0, 1536),      # one scale per row, no adapter
 ]
 
 
@@ -83,15 +91,24 @@ def test_forward_backward_against_oracle(bits, K, N, M, r, group):
     s = L["lora_scale"]
     A, B = (L["A"], L["B"]) if r else (None, None)
 
+    # At M <= 16 the library may multiply by the codes directly, i.e. without the oracle's
+    # intermediate rounding of What to bfloat16 (at most 2^-9 relative per weight): allow
+    # exactly that much, as the rigorous bound 2^-9 * |act| |What|^T.
+    extra_Y = extra_dX = 0.0
+    if M <= 16:
+        Wabs = np.abs(oracle.dequant_f32(*oracle_args(L)).astype(np.float64))      # [N][K]
+        extra_Y = 2.0 ** -9 * (np.abs(synth.bf16_bits_to_f64(L["X"])) @ Wabs.T)
+        extra_dX = 2.0 ** -9 * (np.abs(synth.bf16_bits_to_f64(L["dY"])) @ Wabs)
+
     Y, XA = b.modulora_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], s)
     Yr, Ur = oracle.fwd(*oracle_args(L), L["X"], A, B, s)
     assert_bar("Y", f64(Y), Yr)
-    assert_tight("Y", f64(Y), Yr, True, K)
+    assert_tight("Y", f64(Y), Yr, True, K, extra_Y)
 
     dX, T = b.modulora_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], s)
     dXr, Tr = oracle.bwd_input(*oracle_args(L), L["dY"], A, B, s)
     assert_bar("dX", f64(dX), dXr)
-    assert_tight("dX", f64(dX), dXr, True, N)
+    assert_tight("dX", f64(dX), dXr, True, N, extra_dX)
 
     if r == 0:
         assert XA is None and T is None
@@ -107,6 +124,26 @@ def test_forward_backward_against_oracle(bits, K, N, M, r, group):
         assert_bar("dB", f64(dB), dBr)
         assert_tight("dA", f64(dA), dAr, False, M * N)
         assert_tight("dB", f64(dB), dBr, False, M * K)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_streaming_kernels_pick_out_single_weights(bits):
+    """One-hot rows through the M <= 16 streaming kernels: a single nonzero term, so the
+    code-domain arithmetic must land on the same bfloat16 as the materialized weight."""
+    K, N, group = 512, 296, 128
+    L = layer(bits, K, N, 1, 0, group, seed=6)
+    D = to_device(L)
+    What = oracle.dequant_bf16(*oracle_args(L))
+    eyeK = torch.eye(K, dtype=torch.bfloat16, device="cuda")
+    for lo in (0, 100, 497):
+        rows = eyeK[lo:lo + 15].contiguous()
+        Y, _ = b.modulora_fwd(D["w"], rows, None, None, 1.0)
+        assert np.array_equal(bits16(Y), What.T[lo:lo + 15])
+    eyeN = torch.eye(N, dtype=torch.bfloat16, device="cuda")
+    for lo in (0, 280):
+        rows = eyeN[lo:lo + 16].contiguous()
+        dX, _ = b.modulora_bwd_input(D["w"], rows, None, None, 1.0)
+        assert np.array_equal(bits16(dX), What[lo:lo + 16])
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
