@@ -16,6 +16,16 @@ typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
+// Make a value provably wave-uniform (it then lives in a scalar register).
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Load from a wave-uniform base plus a per-lane 32-bit byte offset: the form that maps
+// onto "scalar base + vector offset" addressing and needs no per-lane 64-bit arithmetic.
+template <typename T>
+__device__ __forceinline__ T load_at(const void *base, uint32_t byte_off) {
+    return *reinterpret_cast<const T *>(static_cast<const char *>(base) + byte_off);
+}
+
 __device__ __forceinline__ float half_bits_to_float(uint16_t h) {
     _Float16 x;
     __builtin_memcpy(&x, &h, sizeof x);

@@ -35,12 +35,6 @@ struct GemmDev {
     }
 };
 
-__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
-
-template <typename T>
-__device__ __forceinline__ T load_at(const void *base, uint32_t byte_off) {
-    return *reinterpret_cast<const T *>(static_cast<const char *>(base) + byte_off);
-}
 
 
 inline GemmDev make_gemm_dev(const GemmArgs &a, int MT, int CT) {

@@ -31,9 +31,10 @@
 namespace mlr {
 
 namespace sm {
-constexpr int WG_WAVES = 16, WG_THREADS = WG_WAVES * 64;
+constexpr int WG_WAVES = 4, WG_THREADS = WG_WAVES * 64;
 constexpr int COLS = 32;               // columns per workgroup (2 per lane of a 16-lane group)
 constexpr int PREP_K = 128;            // contraction elements per prep workgroup
+constexpr int MAX_KSPLIT = 8;          // workgroups that may share a column block
 constexpr uint32_t MAGIC = 0x43004300u;   // two bfloat16 128.0
 constexpr uint32_t ONES = 0x3F803F80u;    // two bfloat16 1.0
 
@@ -48,6 +49,26 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 q) {
     return v;
 }
 
+// (x & mask) | magic.  A VOP3 instruction of this ISA takes no literal, so with literal
+// constants the compiler emits v_and + v_or; callers pass mask and magic as opaque
+// register values (see opaque_sgpr / opaque_vgpr) and get one v_and_or_b32.  The
+// instruction itself is left to the compiler: hand-written VALU assembly next to MFMAs is
+// not covered by the compiler's hazard handling.
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) {
+    return (x & mask) | magic;
+}
+__device__ __forceinline__ uint32_t opaque_sgpr(uint32_t v) {
+    asm volatile("" : "+s"(v));
+    return v;
+}
+__device__ __forceinline__ uint32_t opaque_vgpr(uint32_t v) {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+struct CodeMasks {
+    uint32_t field, top, magic;   // field mask of a register pair, mask of 3-bit code 4, 2 x 128.0
+};
+
 // chunks (8 codes) per step of a lane group, and codes per wave step
 template <int BITS> struct Geo {
     static constexpr int NC = BITS == 4 ? 1 : (BITS == 2 ? 2 : 4);   // MFMA calls per wave step
@@ -55,25 +76,34 @@ template <int BITS> struct Geo {
     static constexpr int KSTEP = 32 * NC;                             // codes per wave step
 };
 
+template <int BITS>
+__device__ __forceinline__ CodeMasks make_masks() {
+    CodeMasks m;
+    m.field = opaque_sgpr(BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x0007000Eu));
+    m.top = opaque_sgpr(0x00070000u);
+    m.magic = opaque_vgpr(MAGIC);
+    return m;
+}
+
 // The 8 operand values (4 registers) of call c from the words of one lane-group step.
 template <int BITS>
-__device__ __forceinline__ void codes_to_operand(const uint32_t *w, int c, uint32_t o[4]) {
+__device__ __forceinline__ void codes_to_operand(const uint32_t *w, int c, const CodeMasks &m, uint32_t o[4]) {
     if (BITS == 4) {
         // reg p = (code p, code p+4)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) o[p] = ((w[0] >> (4 * p)) & 0x000F000Fu) | MAGIC;
+        for (int p = 0; p < 4; ++p) o[p] = and_or(w[0] >> (4 * p), m.field, m.magic);
     } else if (BITS == 2) {
         // word of 16 codes; call c, reg p = (code 4c+p, code 4c+p+8)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) o[p] = ((w[0] >> (2 * (4 * c + p))) & 0x00030003u) | MAGIC;
+        for (int p = 0; p < 4; ++p) o[p] = and_or(w[0] >> (2 * (4 * c + p)), m.field, m.magic);
     } else {
         // 24-bit chunk c of the 96-bit block; regs (2*q0, q5) (2*q1, q6) (2*q2, q7) (q3, q4)
         const uint32_t ch = block_chunk<3>(w, c);
-        o[0] = ((ch << 1) & 0x0007000Eu) | MAGIC;
-        o[1] = ((ch >> 2) & 0x0007000Eu) | MAGIC;
-        o[2] = ((ch >> 5) & 0x0007000Eu) | MAGIC;
-        const uint32_t t = ch >> 9;                       // code 3 at bits 0-2, code 4 at bits 3-5
-        o[3] = (t & 7u) | (((t << 13) & 0x00070000u) | MAGIC);
+        o[0] = and_or(ch << 1, m.field, m.magic);
+        o[1] = and_or(ch >> 2, m.field, m.magic);
+        o[2] = and_or(ch >> 5, m.field, m.magic);
+        // code 3 (bits 9-11) low, code 4 (bits 12-14) high
+        o[3] = ((ch >> 9) & 7u) | and_or(ch << 4, m.top, m.magic);
     }
 }
 
@@ -94,13 +124,14 @@ __device__ __forceinline__ int perm_src(int bits, int pos, float *scale) {
 }  // namespace sm
 
 // ---------------------------------------------------------------------------------
-// prep (forward): Xp = X in operand order (rows >= M zero), and per-128-k partial sums of
+// prep (forward): Xp = X in operand order, stored [K/8][16][8] (rows >= M zero), and per-128-k partial sums of
 // XA = X A.  One workgroup per 128 contraction elements; thread (m, chunk of 8).
 // ---------------------------------------------------------------------------------
 template <int RP>
 __global__ __launch_bounds__(256) void smallm_prep_fwd_kernel(const uint16_t *__restrict__ X, int M, int K, int bits,
                                                               const float *__restrict__ A, int r,
-                                                              uint16_t *__restrict__ Xp, float *__restrict__ Upart) {
+                                                              uint16_t *__restrict__ Xp, float *__restrict__ Upart,
+                                                              int n_kparts) {
     __shared__ uint16_t Xs[16][sm::PREP_K + 8];
     const int t = threadIdx.x, m = t >> 4, ch = t & 15;
     const int k0 = blockIdx.x * sm::PREP_K;
@@ -162,7 +193,9 @@ __global__ __launch_bounds__(256) void smallm_prep_fwd_kernel(const uint16_t *__
     ov.y = o[2] | ((uint32_t)o[3] << 16);
     ov.z = o[4] | ((uint32_t)o[5] << 16);
     ov.w = o[6] | ((uint32_t)o[7] << 16);
-    *reinterpret_cast<uint4 *>(Xp + (size_t)m * K + kc) = ov;
+    // operand layout [chunk of 8][row m][8]: the 16 rows of one chunk are 256 contiguous bytes,
+    // which is what the 16 lanes of a lane group fetch together
+    *reinterpret_cast<uint4 *>(Xp + ((size_t)(kc >> 3) * 16 + m) * 8) = ov;
 }
 
 // ---------------------------------------------------------------------------------
@@ -174,45 +207,73 @@ __global__ __launch_bounds__(256) void smallm_prep_fwd_kernel(const uint16_t *__
 // ---------------------------------------------------------------------------------
 struct SmallFwdDev {
     LayerView w;
-    const uint16_t *Xp;     // [16][K] operand order
+    const uint16_t *Xp;     // [K/8][16][8] operand order
     const float *Upart;     // [K/128][16][r]
     const float *B;         // [r][N]
     int M, r, n_kparts;
+    int ksplit;             // workgroups that share one column block (split of the groups along K)
     float lora_scale;
     uint16_t *Y;            // [M][N]
     float *XA;              // [M][r] or NULL
+    float *Yacc;            // [ksplit][16][N] fp32 partial tiles (used when ksplit > 1)
 };
 
+// Epilogue shared by the stream kernel (no K split) and the finish kernel: thread tid holds
+// outputs tid and tid + WG_THREADS of the 16 x 32 tile of column block cb in y[]; adds the
+// adapter term and stores bfloat16.  XA = sum of the prep kernel's partials: element t of the
+// 16 x r tile is summed by WG_THREADS / (16 r) threads over interleaved slices of the
+// partials, eight independent loads at a time, and the slices meet in LDS (Us, 16 * 64 floats).
+__device__ __forceinline__ void smallm_fwd_epilogue(const SmallFwdDev &d, int cb, const float y[2], float *Us) {
+    const int tid = threadIdx.x, N = d.w.N, n0 = cb * sm::COLS;
+    const int ur = 16 * d.r;
+    for (int t = tid; t < ur; t += sm::WG_THREADS) Us[t] = 0.f;
+    __syncthreads();
+    if (d.r > 0) {
+        const int slices = sm::WG_THREADS >= ur ? sm::WG_THREADS / ur : 1;
+        for (int t = tid; t < slices * ur; t += sm::WG_THREADS) {
+            const int mj = t % ur, slice = t / ur;
+            float acc8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            int kb = slice;
+            for (; kb + 7 * slices < d.n_kparts; kb += 8 * slices) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc8[u] += d.Upart[(size_t)(kb + u * slices) * ur + mj];
+            }
+            for (; kb < d.n_kparts; kb += slices) acc8[0] += d.Upart[(size_t)kb * ur + mj];
+            atomicAdd(&Us[mj], ((acc8[0] + acc8[1]) + (acc8[2] + acc8[3])) + ((acc8[4] + acc8[5]) + (acc8[6] + acc8[7])));
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int idx = tid + e * sm::WG_THREADS, m = idx / sm::COLS, col = n0 + idx % sm::COLS;
+        if (m < d.M && col < N) {
+            float lora = 0.f;
+            for (int jj = 0; jj < d.r; ++jj) lora = __builtin_fmaf(Us[m * d.r + jj], d.B[(size_t)jj * N + col], lora);
+            d.Y[(size_t)m * N + col] = float_to_bf16_bits(__builtin_fmaf(d.lora_scale, lora, y[e]));
+        }
+    }
+    if (cb == 0 && d.XA != nullptr)
+        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
+}
+
 template <int BITS>
-__global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_kernel(SmallFwdDev d) {
+__global__ __launch_bounds__(sm::WG_THREADS, 4) void smallm_fwd_kernel(SmallFwdDev d) {
     using G = sm::Geo<BITS>;
     __shared__ float red[sm::WG_WAVES][16][sm::COLS + 1];
     __shared__ float Us[16 * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 15, j = lane >> 4;
     const int K = d.w.K, N = d.w.N, group = d.w.group;
-    const int n0 = blockIdx.x * sm::COLS;
+    const int cb = blockIdx.x / d.ksplit, ks = blockIdx.x % d.ksplit;   // column block, K split
+    const int n0 = cb * sm::COLS;
     int n = n0 + 2 * i;
     if (n > N - 2) n = N - 2;                       // clamped pair, masked at the store
 
-    // adapter: XA = sum of the prep kernel's partials, gathered while the stream starts
-    const int ur = 16 * d.r;
-    for (int t = tid; t < ur; t += sm::WG_THREADS) Us[t] = 0.f;
-    __syncthreads();
-    if (d.r > 0) {
-        const int parts = sm::WG_THREADS / ur > 0 ? sm::WG_THREADS / ur : 1;
-        const int mj = tid % ur, part = tid / ur;
-        if (part < parts) {
-            float s = 0.f;
-            for (int kb = part; kb < d.n_kparts; kb += parts) s += d.Upart[(size_t)kb * ur + mj];
-            atomicAdd(&Us[mj], s);
-        }
-    }
-
     // this wave's share of the quantization groups
     const int n_groups = K / group;
-    const int g_begin = (int)((long)n_groups * wave / sm::WG_WAVES);
-    const int g_end = (int)((long)n_groups * (wave + 1) / sm::WG_WAVES);
+    const int parts = d.ksplit * sm::WG_WAVES, part = ks * sm::WG_WAVES + wave;
+    const int g_begin = (int)((long)n_groups * part / parts);
+    const int g_end = (int)((long)n_groups * (part + 1) / parts);
     const int steps_per_group = group / G::KSTEP;
 
     f32x4 yacc[2];
@@ -225,54 +286,58 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_kernel(SmallFwdDev 
     const uint32_t invf4[4] = {0x3F804000u, 0x3F804000u, 0x3F804000u, sm::ONES};   // (2,1)(2,1)(2,1)(1,1)
     const bf16x8 ones = sm::as_bf16x8(ones4), invf = sm::as_bf16x8(invf4);
 
-    // The wave's work is a run of steps (KSTEP codes each); a group's affine part is
-    // applied after its last step.  Loads run DEPTH steps ahead of the MFMAs in a rotating
-    // set of register buffers (the loop is unrolled by DEPTH so the buffer index is static).
-    constexpr int DEPTH = 4;
+    // The wave's work is a run of steps (KSTEP codes each), group after group; a group's
+    // affine part is applied after its last step.  Loads run DEPTH steps ahead of the MFMAs
+    // in a rotating set of register buffers (the loop is unrolled by DEPTH so the buffer
+    // index is static).  Every address is a wave-uniform base plus a per-lane constant.
+    // deep enough that a CU keeps ~64-96 KB of packed words in flight (16 waves x DEPTH steps)
+    constexpr int DEPTH = BITS == 3 ? 3 : (BITS == 2 ? 6 : 8);
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
     struct Step {
-        uint32_t w[2][G::WORDS];
+        u32x2 w[G::WORDS];
         uint4 xa[G::NC];
-        uint32_t sbits, zbits;
+        uint32_t sbits;
+        uint16_t zbits;
     };
-    auto load_step = [&](Step &sd, int s) {
-        const int g = s / steps_per_group;
-        // lane group j takes chunks [cidx, cidx + NC) of 8 codes
-        const int cidx = s * (G::KSTEP / 8) + j * G::NC;
-        const int row0 = BITS == 4 ? cidx : (BITS == 2 ? cidx / 2 : (cidx / 4) * 3);
+    // lane group j reads packed rows (4 s + j) * WORDS + q, columns n, n + 1
+    const uint32_t w_voff = (uint32_t)(((size_t)j * G::WORDS * N + n) * 4);
+    // and operand chunks 4 NC s + NC j + c, row i:  element ((chunk) * 16 + i) * 8
+    const uint32_t x_voff = (uint32_t)(((j * G::NC) * 16 + i) * 16);
+    const uint32_t s_voff = (uint32_t)n * 2u, z_voff = (uint32_t)n;
+    auto load_step = [&](Step &sd, int s, int g) {
+        const uint32_t *wbase = d.w.qweight + (size_t)s * (4 * G::WORDS) * N;
 #pragma unroll
-        for (int q = 0; q < G::WORDS; ++q) {
-            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-            // streamed once: keep the packed words from displacing X and the adapter in cache
-            const u32x2 pw = __builtin_nontemporal_load(
-                reinterpret_cast<const u32x2 *>(d.w.qweight + (size_t)(row0 + q) * N + n));
-            sd.w[0][q] = pw[0];
-            sd.w[1][q] = pw[1];
-        }
+        for (int q = 0; q < G::WORDS; ++q)   // streamed once: non-temporal
+            sd.w[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(
+                reinterpret_cast<const char *>(wbase + (size_t)q * N) + w_voff));
+        const uint16_t *xbase = d.Xp + (size_t)s * (4 * G::NC * 128);
 #pragma unroll
-        for (int c = 0; c < G::NC; ++c)
-            sd.xa[c] = *reinterpret_cast<const uint4 *>(d.Xp + (size_t)i * K + (size_t)(cidx + c) * 8);
-        sd.sbits = *reinterpret_cast<const uint32_t *>(d.w.scales + (size_t)g * N + n);
-        sd.zbits = *reinterpret_cast<const uint16_t *>(d.w.zeros + (size_t)g * N + n);
+        for (int c = 0; c < G::NC; ++c) sd.xa[c] = load_at<uint4>(xbase + c * 128, x_voff);
+        sd.sbits = load_at<uint32_t>(d.w.scales + (size_t)g * N, s_voff);
+        sd.zbits = load_at<uint16_t>(d.w.zeros + (size_t)g * N, z_voff);
     };
 
+    const sm::CodeMasks masks = sm::make_masks<BITS>();
     f32x4 tmp[2], s1, s2;
 #pragma unroll
     for (int v = 0; v < 4; ++v) { tmp[0][v] = 0.f; tmp[1][v] = 0.f; s1[v] = 0.f; s2[v] = 0.f; }
 
-    auto compute_step = [&](const Step &sd, int s) {
+    auto compute_step = [&](const Step &sd, bool group_ends) {
+        uint32_t w0[G::WORDS], w1[G::WORDS];
+#pragma unroll
+        for (int q = 0; q < G::WORDS; ++q) { w0[q] = sd.w[q][0]; w1[q] = sd.w[q][1]; }
 #pragma unroll
         for (int c = 0; c < G::NC; ++c) {
             const bf16x8 a = sm::as_bf16x8(sd.xa[c]);
-#pragma unroll
-            for (int cs = 0; cs < 2; ++cs) {
-                uint32_t o[4];
-                sm::codes_to_operand<BITS>(sd.w[cs], c, o);
-                tmp[cs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), tmp[cs], 0, 0, 0);
-            }
+            uint32_t o[4];
+            sm::codes_to_operand<BITS>(w0, c, masks, o);
+            tmp[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), tmp[0], 0, 0, 0);
+            sm::codes_to_operand<BITS>(w1, c, masks, o);
+            tmp[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), tmp[1], 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, s1, 0, 0, 0);
             if (BITS == 3) s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, invf, s2, 0, 0, 0);
         }
-        if ((s + 1) % steps_per_group != 0) return;
+        if (!group_ends) return;
         // end of a group: tmp = sum a (128 + q/f);  s1 = sum a;  s2 = sum a/f = sum X
         // (f == 1 unless 3-bit)
 #pragma unroll
@@ -292,15 +357,29 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_kernel(SmallFwdDev 
 
     const int s_begin = g_begin * steps_per_group, s_end = g_end * steps_per_group;
     Step buf[DEPTH];
+    // (step, group, position in group) of the next step to load and of the next to compute
+    int ls = s_begin, lg = g_begin, lp = 0;
 #pragma unroll
     for (int dd = 0; dd < DEPTH; ++dd)
-        if (s_begin + dd < s_end) load_step(buf[dd], s_begin + dd);
+        if (ls < s_end) {
+            load_step(buf[dd], ls, lg);
+            ++ls;
+            if (++lp == steps_per_group) { lp = 0; ++lg; }
+        }
+
+    int cp = 0;
     for (int s = s_begin; s < s_end; s += DEPTH) {
 #pragma unroll
         for (int dd = 0; dd < DEPTH; ++dd) {
             if (s + dd < s_end) {
-                compute_step(buf[dd], s + dd);
-                if (s + dd + DEPTH < s_end) load_step(buf[dd], s + dd + DEPTH);
+                const bool ends = ++cp == steps_per_group;
+                if (ends) cp = 0;
+                compute_step(buf[dd], ends);
+                if (ls < s_end) {
+                    load_step(buf[dd], ls, lg);
+                    ++ls;
+                    if (++lp == steps_per_group) { lp = 0; ++lg; }
+                }
             }
         }
     }
@@ -312,20 +391,43 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_kernel(SmallFwdDev 
         for (int v = 0; v < 4; ++v) red[wave][4 * j + v][2 * i + cs] = yacc[cs][v];
     __syncthreads();
 
-    if (tid < 16 * sm::COLS) {
-        const int m = tid / sm::COLS, c = tid % sm::COLS;
-        float y = 0.f;
+    // each thread owns two of the 16 x 32 outputs of the column block
+    float y[2];
 #pragma unroll
-        for (int w = 0; w < sm::WG_WAVES; ++w) y += red[w][m][c];
-        const int col = n0 + c;
-        if (m < d.M && col < N) {
-            float lora = 0.f;
-            for (int jj = 0; jj < d.r; ++jj) lora = __builtin_fmaf(Us[m * d.r + jj], d.B[(size_t)jj * N + col], lora);
-            d.Y[(size_t)m * N + col] = float_to_bf16_bits(__builtin_fmaf(d.lora_scale, lora, y));
-        }
+    for (int e = 0; e < 2; ++e) {
+        const int idx = tid + e * sm::WG_THREADS, m = idx / sm::COLS, c = idx % sm::COLS;
+        y[e] = 0.f;
+#pragma unroll
+        for (int w = 0; w < sm::WG_WAVES; ++w) y[e] += red[w][m][c];
     }
-    if (blockIdx.x == 0 && d.XA != nullptr)
-        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
+    if (d.ksplit > 1) {
+        // each K split leaves its fp32 partial tile; the finish kernel (next launch on the
+        // stream) adds them up.  No cross-workgroup traffic inside this kernel, hence no fences.
+        float *mine = d.Yacc + (size_t)ks * 16 * N;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int idx = tid + e * sm::WG_THREADS, m = idx / sm::COLS, col = n0 + idx % sm::COLS;
+            if (col < N) mine[(size_t)m * N + col] = y[e];
+        }
+        return;
+    }
+    smallm_fwd_epilogue(d, cb, y, Us);
+}
+
+// Sum of the K splits' partial tiles, then the common epilogue.  One workgroup per column block.
+__global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(SmallFwdDev d) {
+    __shared__ float Us[16 * 64];
+    const int tid = threadIdx.x, cb = blockIdx.x, n0 = cb * sm::COLS, N = d.w.N;
+    float y[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int idx = tid + e * sm::WG_THREADS, m = idx / sm::COLS, col = n0 + idx % sm::COLS;
+        float sum = 0.f;
+        if (col < N)
+            for (int q = 0; q < d.ksplit; ++q) sum += d.Yacc[((size_t)q * 16 + m) * N + col];
+        y[e] = sum;
+    }
+    smallm_fwd_epilogue(d, cb, y, Us);
 }
 
 bool smallm_fwd_supported(const LayerView &w, int M) {
@@ -334,27 +436,49 @@ bool smallm_fwd_supported(const LayerView &w, int M) {
     return w.group % kstep == 0 && w.K % sm::PREP_K == 0 && w.N >= 2;
 }
 
-size_t smallm_ws_bytes(int K, int N, int r) {
+namespace {
+struct SmallWs {
+    size_t xp, upart, yacc, total;
+};
+SmallWs small_ws(int K, int N, int r) {
     const size_t kmax = (size_t)(K > N ? K : N);
-    const size_t xp = ((size_t)16 * kmax * 2 + 255) & ~(size_t)255;
-    const size_t up = (((kmax + sm::PREP_K - 1) / sm::PREP_K) * 16 * (size_t)(r > 0 ? r : 1) * 4 + 255) & ~(size_t)255;
-    return xp + up;
+    auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    SmallWs l;
+    size_t off = 0;
+    l.xp = off;      off += al((size_t)16 * kmax * 2);
+    l.upart = off;   off += al(((kmax + sm::PREP_K - 1) / sm::PREP_K) * 16 * (size_t)(r > 0 ? r : 1) * 4);
+    l.yacc = off;    off += al((size_t)sm::MAX_KSPLIT * 16 * kmax * 4);
+    l.total = off;
+    return l;
 }
+}  // namespace
+
+size_t smallm_ws_bytes(int K, int N, int r) { return small_ws(K, N, r).total; }
 
 hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     const int K = a.w.K, N = a.w.N;
-    uint16_t *Xp = static_cast<uint16_t *>(a.ws);
-    const size_t xp_bytes = ((size_t)16 * (K > N ? K : N) * 2 + 255) & ~(size_t)255;
-    float *Upart = reinterpret_cast<float *>(static_cast<char *>(a.ws) + xp_bytes);
+    const SmallWs l = small_ws(K, N, a.r);
+    char *ws = static_cast<char *>(a.ws);
+    uint16_t *Xp = reinterpret_cast<uint16_t *>(ws + l.xp);
+    float *Upart = reinterpret_cast<float *>(ws + l.upart);
+    float *Yacc = reinterpret_cast<float *>(ws + l.yacc);
     const int n_kparts = K / sm::PREP_K;
+    const int col_blocks = (N + sm::COLS - 1) / sm::COLS;
+
+    // enough workgroups (4 waves each) for ~4 per CU; a split never gets less than one group per wave
+    int ksplit = (1024 + col_blocks - 1) / col_blocks;
+    const int max_split = (K / a.w.group) / sm::WG_WAVES;
+    if (ksplit > max_split) ksplit = max_split;
+    if (ksplit > sm::MAX_KSPLIT) ksplit = sm::MAX_KSPLIT;
+    if (ksplit < 1) ksplit = 1;
 
     prof_before("smallm_prep_fwd", stream);
     if (a.r <= 8)
-        smallm_prep_fwd_kernel<8><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart);
+        smallm_prep_fwd_kernel<8><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart, n_kparts);
     else if (a.r <= 16)
-        smallm_prep_fwd_kernel<16><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart);
+        smallm_prep_fwd_kernel<16><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart, n_kparts);
     else
-        smallm_prep_fwd_kernel<64><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart);
+        smallm_prep_fwd_kernel<64><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart, n_kparts);
     prof_after(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -367,16 +491,22 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     d.M = a.M;
     d.r = a.r;
     d.n_kparts = n_kparts;
+    d.ksplit = ksplit;
     d.lora_scale = a.lora_scale;
     d.Y = a.out;
     d.XA = a.P_out;
-    const int blocks = (N + sm::COLS - 1) / sm::COLS;
+    d.Yacc = Yacc;
     prof_before("stream_fwd", stream);
     switch (a.w.bits) {
-        case 2: smallm_fwd_kernel<2><<<blocks, sm::WG_THREADS, 0, stream>>>(d); break;
-        case 3: smallm_fwd_kernel<3><<<blocks, sm::WG_THREADS, 0, stream>>>(d); break;
-        default: smallm_fwd_kernel<4><<<blocks, sm::WG_THREADS, 0, stream>>>(d); break;
+        case 2: smallm_fwd_kernel<2><<<col_blocks * ksplit, sm::WG_THREADS, 0, stream>>>(d); break;
+        case 3: smallm_fwd_kernel<3><<<col_blocks * ksplit, sm::WG_THREADS, 0, stream>>>(d); break;
+        default: smallm_fwd_kernel<4><<<col_blocks * ksplit, sm::WG_THREADS, 0, stream>>>(d); break;
     }
+    prof_after(stream);
+    e = hipGetLastError();
+    if (e != hipSuccess || ksplit == 1) return e;
+    prof_before("stream_fwd_finish", stream);
+    smallm_fwd_finish_kernel<<<col_blocks, sm::WG_THREADS, 0, stream>>>(d);
     prof_after(stream);
     return hipGetLastError();
 }
