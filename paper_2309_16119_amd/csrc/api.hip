@@ -60,7 +60,7 @@ mlr::LayerView view_of(const modulora_qweight *w) {
 
 // Workspace carving, shared by the size query and the entry points.
 struct WsLayout {
-    size_t act_ext, w_ext, p0, p1, total;
+    size_t act_ext, w_ext, p0, p1, gpart, total;
 };
 
 WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
@@ -79,6 +79,7 @@ WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     l.w_ext = off;   off += align256(maxdim * RE * 2);
     l.p0 = off;      off += align256((size_t)M * r * 4);
     l.p1 = off;      off += align256((size_t)M * r * 4);
+    l.gpart = off;   off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
     l.total = off > small ? off : small;
     return l;
 }
@@ -271,18 +272,12 @@ int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float l
         if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
         dYBt = d.P;
     }
-    if (!accumulate) {
-        if ((s = hip_status(mlr::launch_fill_zero(dA, (size_t)d_in * r, st))) != MODULORA_OK) return s;
-        if ((s = hip_status(mlr::launch_fill_zero(dB, (size_t)d_out * r, st))) != MODULORA_OK) return s;
-    }
-    mlr::GradArgs ga{};
-    ga.act = X; ga.M = M; ga.C = d_in; ga.r = r; ga.P = dYBt; ga.lora_scale = lora_scale;
-    ga.out = dA; ga.out_is_A = true;
-    if ((s = hip_status(mlr::launch_lora_grad(ga, st))) != MODULORA_OK) return s;
-    mlr::GradArgs gb{};
-    gb.act = dY; gb.M = M; gb.C = d_out; gb.r = r; gb.P = XA; gb.lora_scale = lora_scale;
-    gb.out = dB; gb.out_is_A = false;
-    return hip_status(mlr::launch_lora_grad(gb, st));
+    mlr::GradPairArgs ga{};
+    ga.X = X; ga.dY = dY; ga.M = M; ga.K = d_in; ga.N = d_out; ga.r = r;
+    ga.XA = XA; ga.dYBt = dYBt; ga.lora_scale = lora_scale;
+    ga.dA = dA; ga.dB = dB; ga.accumulate = accumulate ? 1 : 0;
+    ga.partials = reinterpret_cast<float *>(ws + l.gpart);
+    return hip_status(mlr::launch_lora_grad_pair(ga, st));
 }
 
 int modulora_profile_begin(void) {

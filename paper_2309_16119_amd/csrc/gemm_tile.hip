@@ -39,14 +39,54 @@
 
 namespace mlr {
 
-constexpr int RT = 64;         // contraction elements per LDS tile
-constexpr int LDS_PAD = 8;     // bf16 elements of row padding (row stride 144 B: conflict-free 16-B accesses)
-constexpr int LROW = RT + LDS_PAD;
+constexpr int LDS_PAD = 8;     // bf16 elements of row padding (row stride 144 or 272 B: conflict-free 16-B accesses)
 
-template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, int OCC>
+typedef uint32_t tu32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t tu32x4 __attribute__((ext_vector_type(4)));
+
+// Loads issued from inline assembly (wave-uniform base + per-lane byte offset) for the
+// pipelined variants.  The compiler does not track them: a consumer must sit behind
+// wait_vm<N>() followed by tie() of every destination register.  Loads return in order,
+// so waiting until at most N remain outstanding completes everything issued before the
+// N most recent ones.
+namespace tl {
+__device__ __forceinline__ void ld(uint32_t &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void ld_u16(uint32_t &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_ushort %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void ld_u8(uint32_t &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_ubyte %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void ld(tu32x2 &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void ld(tu32x4 &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <typename T>
+__device__ __forceinline__ void tie(T &x) {
+    asm volatile("" : "+v"(x)::"memory");
+}
+}  // namespace tl
+
+// RT: contraction elements per LDS tile (64 or 128).  KG: wave groups that split the 16-deep
+// steps of every tile between them (their accumulators are added through LDS at the end).
+template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, int OCC, int PF, int RT, int KG>
 __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
+    constexpr int LROW = RT + LDS_PAD;
     constexpr int NWAVES = THREADS / 64;
-    static_assert((MT / WM) * (CT / WN) == NWAVES, "wave grid covers the tile");
+    constexpr int GWAVES = NWAVES / KG;      // waves of one k-group: they tile the MT x CT output
+    static_assert((MT / WM) * (CT / WN) == GWAVES && GWAVES * KG == NWAVES, "wave grid covers the tile");
+    constexpr int KS_LOCAL = (RT / 16) / KG;   // 16-deep steps of a tile that one wave takes: ks = i * KG + kg
+    static_assert((KG == 1 || KG == 2) && (RT / 16) % KG == 0 && (KS_LOCAL == 2 || KS_LOCAL == 4 || KS_LOCAL == 8),
+                  "k-steps divide between the groups");
     static_assert(WM % 32 == 0 && WN == 64, "wave tile: rows in 32s, two 32-column MFMA tiles");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
 
@@ -133,30 +173,34 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     }
 
     // ---- register staging for one tile -------------------------------------
-    uint4 a_reg[A_CH];
-    uint32_t fw_words[BWD ? 1 : FW_UNITS][BITS];
-    uint16_t fw_scale[BWD ? 1 : FW_UNITS];       // binary16 bits (0: block dequantizes to +0)
-    uint8_t fw_zero[BWD ? 1 : FW_UNITS];
-    uint4 bw_lo[BWD ? BW_UNITS : 1], bw_hi[BWD ? BW_UNITS : 1];
-    uint2 bw_scale[BWD ? BW_UNITS : 1];          // 4 binary16
-    uint32_t bw_zero[BWD ? BW_UNITS : 1];        // 4 uint8
-    uint4 w_reg[W_CH];                           // extension tiles only
+    struct Stage {
+        tu32x4 a_reg[A_CH];
+        uint32_t fw_words[BWD ? 1 : FW_UNITS][BITS];
+        uint32_t fw_scale[BWD ? 1 : FW_UNITS];       // binary16 bits (0: block dequantizes to +0)
+        uint32_t fw_zero[BWD ? 1 : FW_UNITS];
+        tu32x4 bw_lo[BWD ? BW_UNITS : 1], bw_hi[BWD ? BW_UNITS : 1];
+        tu32x2 bw_scale[BWD ? BW_UNITS : 1];         // 4 binary16
+        uint32_t bw_zero[BWD ? BW_UNITS : 1];        // 4 uint8
+    };
+    // load instructions one stage issues through load_main_async
+    constexpr int STAGE_LOADS = A_CH + (BWD ? BW_UNITS * (BITS == 3 ? 4 : 3) : FW_UNITS * (BITS + 2));
+    uint4 w_reg[W_CH];                               // extension tiles only
 
     // full main tile t: no predicates at all
-    auto load_main = [&](int t) {
+    auto load_main = [&](Stage &st, int t) {
         const uint16_t *abase = act_rowblock + (size_t)t * RT;
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) a_reg[i] = load_at<uint4>(abase, a_off[i]);
+        for (int i = 0; i < A_CH; ++i) st.a_reg[i] = load_at<tu32x4>(abase, a_off[i]);
         if (!BWD) {
 #pragma unroll
             for (int u = 0; u < FW_UNITS; ++u) {
                 const int blk = t * (RT / 32) + fw_kb[u];
                 const uint32_t *wbase = a.w.qweight + (size_t)blk * BITS * N;
 #pragma unroll
-                for (int j = 0; j < BITS; ++j) fw_words[u][j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off[u]);
+                for (int j = 0; j < BITS; ++j) st.fw_words[u][j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off[u]);
                 const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
-                fw_scale[u] = load_at<uint16_t>(a.w.scales + grow, fw_n[u] * 2);
-                fw_zero[u] = load_at<uint8_t>(a.w.zeros + grow, fw_n[u]);
+                st.fw_scale[u] = load_at<uint16_t>(a.w.scales + grow, fw_n[u] * 2);
+                st.fw_zero[u] = load_at<uint8_t>(a.w.zeros + grow, fw_n[u]);
             }
         } else {
             const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
@@ -164,16 +208,68 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
             const uint8_t *zbase = a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT;
 #pragma unroll
             for (int u = 0; u < BW_UNITS; ++u) {
-                bw_lo[u] = load_at<uint4>(wbase, bw_off[u]);
-                if (BITS == 3) bw_hi[u] = load_at<uint4>(wbase, bw_offhi[u]);
-                bw_scale[u] = load_at<uint2>(sbase, bw_soff[u] * 2);
-                bw_zero[u] = load_at<uint32_t>(zbase, bw_soff[u]);
+                st.bw_lo[u] = load_at<tu32x4>(wbase, bw_off[u]);
+                if (BITS == 3) st.bw_hi[u] = load_at<tu32x4>(wbase, bw_offhi[u]);
+                st.bw_scale[u] = load_at<tu32x2>(sbase, bw_soff[u] * 2);
+                st.bw_zero[u] = load_at<uint32_t>(zbase, bw_soff[u]);
+            }
+        }
+    };
+
+    // the same loads, issued from assembly (exactly STAGE_LOADS instructions) and left in flight
+    auto load_main_async = [&](Stage &st, int t) {
+        const uint16_t *abase = act_rowblock + (size_t)t * RT;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) tl::ld(st.a_reg[i], abase, a_off[i]);
+        if (!BWD) {
+#pragma unroll
+            for (int u = 0; u < FW_UNITS; ++u) {
+                const int blk = t * (RT / 32) + fw_kb[u];
+                const uint32_t *wbase = a.w.qweight + (size_t)blk * BITS * N;
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) tl::ld(st.fw_words[u][j], wbase + (size_t)j * N, fw_off[u]);
+                const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
+                tl::ld_u16(st.fw_scale[u], a.w.scales + grow, fw_n[u] * 2);
+                tl::ld_u8(st.fw_zero[u], a.w.zeros + grow, fw_n[u]);
+            }
+        } else {
+            const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
+            const uint16_t *sbase = a.w.scales + (size_t)bw_g0 * N + (size_t)t * RT;
+            const uint8_t *zbase = a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT;
+#pragma unroll
+            for (int u = 0; u < BW_UNITS; ++u) {
+                tl::ld(st.bw_lo[u], wbase, bw_off[u]);
+                if (BITS == 3) tl::ld(st.bw_hi[u], wbase, bw_offhi[u]);
+                tl::ld(st.bw_scale[u], sbase, bw_soff[u] * 2);
+                tl::ld(st.bw_zero[u], zbase, bw_soff[u]);
+            }
+        }
+    };
+    // make every register of a stage depend on the wait that precedes this call
+    auto tie_stage = [&](Stage &st) {
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) tl::tie(st.a_reg[i]);
+        if (!BWD) {
+#pragma unroll
+            for (int u = 0; u < FW_UNITS; ++u) {
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) tl::tie(st.fw_words[u][j]);
+                tl::tie(st.fw_scale[u]);
+                tl::tie(st.fw_zero[u]);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < BW_UNITS; ++u) {
+                tl::tie(st.bw_lo[u]);
+                if (BITS == 3) tl::tie(st.bw_hi[u]);
+                tl::tie(st.bw_scale[u]);
+                tl::tie(st.bw_zero[u]);
             }
         }
     };
 
     // ragged last main tile (C % 64 != 0) and extension tiles: predicated
-    auto load_edge = [&](int t) {
+    auto load_edge = [&](Stage &st, int t) {
         const bool ext = t >= n_main;
         const int r0 = ext ? (t - n_main) * RT : t * RT;
         const int ld = ext ? a.RE : C;
@@ -184,8 +280,8 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
             const int row = idx / (RT / 8);
             int m = m0 + row;
             if (m > a.M - 1) m = a.M - 1;
-            a_reg[i] = make_uint4(0, 0, 0, 0);
-            if (r0 + a_col[i] < ld) a_reg[i] = load_at<uint4>(abase, (uint32_t)(((size_t)(m - m0) * ld + a_col[i]) * 2));
+            st.a_reg[i] = tu32x4{0, 0, 0, 0};
+            if (r0 + a_col[i] < ld) st.a_reg[i] = load_at<tu32x4>(abase, (uint32_t)(((size_t)(m - m0) * ld + a_col[i]) * 2));
         }
         if (ext) {
 #pragma unroll
@@ -208,11 +304,11 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
                 const int blk_c = ok ? blk : 0;
                 const uint32_t *wbase = a.w.qweight + (size_t)blk_c * BITS * N;
 #pragma unroll
-                for (int j = 0; j < BITS; ++j) fw_words[u][j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off[u]);
+                for (int j = 0; j < BITS; ++j) st.fw_words[u][j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off[u]);
                 const size_t grow = (size_t)d.group_of_block((uint32_t)blk_c) * N;
                 // scale bits 0 -> every weight of the block dequantizes to +0
-                fw_scale[u] = ok ? load_at<uint16_t>(a.w.scales + grow, fw_n[u] * 2) : (uint16_t)0;
-                fw_zero[u] = load_at<uint8_t>(a.w.zeros + grow, fw_n[u]);
+                st.fw_scale[u] = ok ? (uint32_t)load_at<uint16_t>(a.w.scales + grow, fw_n[u] * 2) : 0u;
+                st.fw_zero[u] = load_at<uint8_t>(a.w.zeros + grow, fw_n[u]);
             }
         } else {
             const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + r0;
@@ -223,28 +319,32 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
                 const int idx = tid + u * THREADS;
                 const int no = idx % (RT / 4);
                 const bool ok = r0 + no * 4 < N;
-                bw_lo[u] = make_uint4(0, 0, 0, 0);
-                bw_hi[u] = make_uint4(0, 0, 0, 0);
-                bw_scale[u] = make_uint2(0, 0);
-                bw_zero[u] = 0;
+                st.bw_lo[u] = tu32x4{0, 0, 0, 0};
+                st.bw_hi[u] = tu32x4{0, 0, 0, 0};
+                st.bw_scale[u] = tu32x2{0, 0};
+                st.bw_zero[u] = 0;
                 if (ok) {
-                    bw_lo[u] = load_at<uint4>(wbase, bw_off[u]);
-                    if (BITS == 3) bw_hi[u] = load_at<uint4>(wbase, bw_offhi[u]);
-                    bw_scale[u] = load_at<uint2>(sbase, bw_soff[u] * 2);
-                    bw_zero[u] = load_at<uint32_t>(zbase, bw_soff[u]);
+                    st.bw_lo[u] = load_at<tu32x4>(wbase, bw_off[u]);
+                    if (BITS == 3) st.bw_hi[u] = load_at<tu32x4>(wbase, bw_offhi[u]);
+                    st.bw_scale[u] = load_at<tu32x2>(sbase, bw_soff[u] * 2);
+                    st.bw_zero[u] = load_at<uint32_t>(zbase, bw_soff[u]);
                 }
             }
         }
     };
 
-    auto store_tile = [&](bool ext, uint16_t *As, uint16_t *Ws) {
+    // Store one staged tile into LDS in four parts (part 0..3), so that the parts can be
+    // interleaved with the MFMA steps of the tile before it.  part < 0 stores everything.
+    auto store_tile = [&](const Stage &st, bool ext, uint16_t *As, uint16_t *Ws, int part) {
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
+            if (part >= 0 && (A_CH >= 4 ? i / (A_CH / 4) : (i == 0 ? 0 : 2 * i)) != part) continue;
             const int idx = tid + i * THREADS;
             const int row = idx / (RT / 8), ch = idx % (RT / 8);
-            *reinterpret_cast<uint4 *>(As + row * LROW + ch * 8) = a_reg[i];
+            *reinterpret_cast<tu32x4 *>(As + row * LROW + ch * 8) = st.a_reg[i];
         }
         if (ext) {
+            if (part > 0) return;
 #pragma unroll
             for (int i = 0; i < W_CH; ++i) {
                 const int idx = tid + i * THREADS;
@@ -258,11 +358,12 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
             for (int u = 0; u < FW_UNITS; ++u) {
                 const int idx = tid + u * THREADS;
                 const int nl = idx % CT;
-                const DqConst dq = make_dq(fw_scale[u], fw_zero[u]);
+                const DqConst dq = make_dq((uint16_t)st.fw_scale[u], (uint8_t)st.fw_zero[u]);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
+                    if (part >= 0 && j != part) continue;
                     uint32_t o[4];
-                    dequant_chunk<BITS>(block_chunk<BITS>(fw_words[u], j), dq, o);
+                    dequant_chunk<BITS>(block_chunk<BITS>(st.fw_words[u], j), dq, o);
                     *reinterpret_cast<uint4 *>(Ws + nl * LROW + fw_kb[u] * 32 + j * 8) = make_uint4(o[0], o[1], o[2], o[3]);
                 }
             }
@@ -271,9 +372,9 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
             for (int u = 0; u < BW_UNITS; ++u) {
                 const int idx = tid + u * THREADS;
                 const int no = idx % (RT / 4), ko = idx / (RT / 4);
-                const uint32_t lo[4] = {bw_lo[u].x, bw_lo[u].y, bw_lo[u].z, bw_lo[u].w};
-                const uint32_t hi[4] = {bw_hi[u].x, bw_hi[u].y, bw_hi[u].z, bw_hi[u].w};
-                const uint32_t sc[2] = {bw_scale[u].x, bw_scale[u].y};
+                const uint32_t lo[4] = {st.bw_lo[u][0], st.bw_lo[u][1], st.bw_lo[u][2], st.bw_lo[u][3]};
+                const uint32_t hi[4] = {st.bw_hi[u][0], st.bw_hi[u][1], st.bw_hi[u][2], st.bw_hi[u][3]};
+                const uint32_t sc[2] = {st.bw_scale[u][0], st.bw_scale[u][1]};
                 uint32_t chunk[4];
                 DqConst dq[4];
 #pragma unroll
@@ -283,11 +384,12 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
                     else
                         chunk[i] = lo[i] >> bw_shift[u];
                     const uint16_t sb = bw_kok[u] ? (uint16_t)(sc[i >> 1] >> ((i & 1) * 16)) : (uint16_t)0;
-                    const uint8_t zb = (uint8_t)(bw_zero[u] >> (i * 8));
+                    const uint8_t zb = (uint8_t)(st.bw_zero[u] >> (i * 8));
                     dq[i] = make_dq(sb, zb);
                 }
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) {
+                    if (part >= 0 && kk / 2 != part) continue;
                     uint32_t o[2];
 #pragma unroll
                     for (int i = 0; i < 2; ++i)
@@ -309,7 +411,8 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int wm = wave / (CT / WN), wn = wave % (CT / WN);
+    const int kg = wave / GWAVES, gw = wave % GWAVES;   // k-group, wave inside the group
+    const int wm = gw / (CT / WN), wn = gw % (CT / WN);
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
     const int a_frag_off = (wm * WM + frag_row) * LROW + frag_k;
     const int w_frag_off = (wn * WN + frag_row) * LROW + frag_k;
@@ -338,9 +441,9 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     // prefetching the next) keeps the kernel under 256 registers without live-range splits.
     auto mfma_full = [&](const uint16_t *As, const uint16_t *Ws) {
 #pragma unroll
-        for (int ks = 0; ks < RT / 16; ++ks) {
+        for (int i = 0; i < KS_LOCAL; ++i) {
             Frags f;
-            load_frags(f, As, Ws, ks);
+            load_frags(f, As, Ws, i * KG + kg);
             mfma_frags(f);
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -348,29 +451,93 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
 
     // ---- steady state: full main tiles only, no predicates -----------------------
     uint16_t *const As0 = lds, *const Ws0 = lds + MT * LROW;
-    if (n_full > 0) {
-        load_main(0);
-        for (int t = 0; t < n_full; ++t) {
-            store_tile(false, As0, Ws0);
-            __syncthreads();
-            load_main(t + 1 < n_full ? t + 1 : n_full - 1);
-            mfma_full(As0, Ws0);
-            __syncthreads();
+    constexpr int NST = PF > 0 ? PF : 1;
+    Stage stg[NST];
+    if (PF == 0) {
+        // single LDS buffer, loads one tile ahead
+        if (n_full > 0) {
+            load_main(stg[0], 0);
+            for (int t = 0; t < n_full; ++t) {
+                store_tile(stg[0], false, As0, Ws0, -1);
+                __syncthreads();
+                load_main(stg[0], t + 1 < n_full ? t + 1 : n_full - 1);
+                mfma_full(As0, Ws0);
+                __syncthreads();
+            }
+        }
+    } else if (n_full > 0) {
+        // Two LDS buffers and PF register stages: global loads run PF tiles ahead (issued from
+        // assembly, awaited with exact counts), and the dequantization of tile t+1 into the
+        // other LDS buffer is issued in four parts between the MFMA steps of tile t (the matrix
+        // cores work while the wave issues VALU work).  One barrier per tile: before it,
+        // everyone has read buffer t&1 and written the other.
+        static_assert(PF == 0 || (PF >= 2 && PF <= 4), "pipelined variants keep 2..4 stages");
+        constexpr int BUF = (MT + CT) * LROW;
+        constexpr int SL = STAGE_LOADS;
+        // wait until the stage that was followed by `later` younger stages has landed
+        auto wait_stage = [&](Stage &st, int later) {
+            if (NST >= 4 && later >= 3) tl::wait_vm<(3 * SL < 64 ? 3 * SL : 0)>();
+            else if (NST >= 3 && later == 2) tl::wait_vm<(2 * SL < 64 ? 2 * SL : 0)>();
+            else if (later == 1) tl::wait_vm<(SL < 64 ? SL : 0)>();
+            else tl::wait_vm<0>();
+            tie_stage(st);
+        };
+#pragma unroll
+        for (int dd = 0; dd < NST; ++dd)
+            if (dd < n_full) load_main_async(stg[dd], dd);
+        wait_stage(stg[0], n_full - 1 < NST - 1 ? n_full - 1 : NST - 1);
+        store_tile(stg[0], false, As0, Ws0, -1);
+        __syncthreads();
+        for (int t = 0; t < n_full; t += NST) {
+#pragma unroll
+            for (int dd = 0; dd < NST; ++dd) {
+                const int tt = t + dd;
+                if (tt < n_full) {
+                    const uint16_t *Ac = As0 + (tt & 1) * BUF, *Wc = Ws0 + (tt & 1) * BUF;
+                    uint16_t *An = As0 + ((tt + 1) & 1) * BUF, *Wn = Ws0 + ((tt + 1) & 1) * BUF;
+                    const bool has_next = tt + 1 < n_full;
+                    // tile tt already sits in LDS: its stage takes the loads of tile tt + PF
+                    if (tt + NST < n_full) load_main_async(stg[dd], tt + NST);
+                    Frags f[2];
+                    load_frags(f[0], Ac, Wc, kg);
+#pragma unroll
+                    for (int i = 0; i < KS_LOCAL; ++i) {
+                        if (i + 1 < KS_LOCAL) load_frags(f[(i + 1) & 1], Ac, Wc, (i + 1) * KG + kg);
+                        mfma_frags(f[i & 1]);
+                        if (has_next) {
+                            Stage &nx = stg[(dd + 1) % NST];
+                            if (i == 0) {
+                                const int younger = n_full - tt - 2;   // stages issued after nx
+                                wait_stage(nx, younger < NST - 1 ? younger : NST - 1);
+                            }
+                            // the four parts of the next tile, spread over this wave's steps
+                            if (KS_LOCAL >= 4) {
+                                if (i % (KS_LOCAL / 4) == 0) store_tile(nx, false, An, Wn, i / (KS_LOCAL / 4));
+                            } else {
+#pragma unroll
+                                for (int pp = 0; pp < 4 / KS_LOCAL; ++pp) store_tile(nx, false, An, Wn, i * (4 / KS_LOCAL) + pp);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    __syncthreads();
+                }
+            }
         }
     }
 
     // ---- tail: a ragged last main tile and the adapter extension, one at a time ----
     for (int t = n_full; t < n_tiles; ++t) {
         const bool ext = t >= n_main;
-        load_edge(t);
-        store_tile(ext, As0, Ws0);
+        load_edge(stg[0], t);
+        store_tile(stg[0], ext, As0, Ws0, -1);
         __syncthreads();
         int ksteps = RT / 16;
         if (ext) {
             ksteps = (a.RE - (t - n_main) * RT) / 16;
             if (ksteps > RT / 16) ksteps = RT / 16;
         }
-        for (int ks = 0; ks < ksteps; ++ks) {
+        for (int ks = kg; ks < ksteps; ks += KG) {
             Frags f;
             load_frags(f, As0, Ws0, ks);
             mfma_frags(f);
@@ -378,9 +545,32 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
         __syncthreads();
     }
 
+    // ---- the k-groups' accumulators meet in LDS; group 0 carries on alone -------------
+    if (KG > 1) {
+        float *redbuf = reinterpret_cast<float *>(lds);      // [gw][i][j][v][lane]
+        if (kg == 1) {
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
+#pragma unroll
+                for (int j = 0; j < TJ; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) redbuf[(((gw * TI + i) * TJ + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (kg != 0) return;
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] += redbuf[(((gw * TI + i) * TJ + j) * 16 + v) * 64 + lane];
+        // group 0's waves now reuse the same LDS for their patches: wait for each other's reads
+        __syncthreads();
+    }
+
     // ---- epilogue: one RNE to bfloat16; 32x64 patches go through LDS so that the
     // global stores are 16 bytes per lane and 128 contiguous bytes per row ----------
-    uint16_t *patch = lds + wave * (32 * LROW);        // per-wave [32][LROW]
+    uint16_t *patch = lds + gw * (32 * LROW);          // per-wave [32][LROW]
 #pragma unroll
     for (int i = 0; i < TI; ++i) {
 #pragma unroll
@@ -407,13 +597,18 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     }
 }
 
-template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, int OCC>
+template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, int OCC, int PF, int RT = 64, int KG = 1>
 static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_t stream) {
+    constexpr int LROW = RT + LDS_PAD;
+    static_assert(KG == 1 || (size_t)MT * CT * 4 <= (size_t)(PF > 0 ? 2 : 1) * (MT + CT) * LROW * 2, "k-group partials fit");
     const GemmDev d = make_gemm_dev(a, MT, CT);
     const int blocks = (d.tiles_m * d.tiles_c + 7) / 8 * 8;
-    const size_t lds_bytes = (size_t)(MT + CT) * LROW * sizeof(uint16_t);
-    static_assert((size_t)(MT + CT) >= (size_t)(THREADS / 64) * 32, "epilogue patches fit");
-    auto kern = gemm_tile_kernel<BITS, BWD, THREADS, MT, CT, WM, WN, OCC>;
+    size_t lds_bytes = (size_t)(PF > 0 ? 2 : 1) * (MT + CT) * LROW * sizeof(uint16_t);
+    // With no more workgroups than CUs, ask for more than half of a CU's 160 KB of LDS: the
+    // dispatcher then cannot put two workgroups on one CU while another CU stays empty.
+    if (blocks <= 256 && lds_bytes < 81 * 1024) lds_bytes = 81 * 1024;
+    static_assert((size_t)(MT + CT) >= (size_t)(THREADS / 64 / KG) * 32, "epilogue patches fit");
+    auto kern = gemm_tile_kernel<BITS, BWD, THREADS, MT, CT, WM, WN, OCC, PF, RT, KG>;
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
     if (e != hipSuccess) return e;
@@ -424,8 +619,8 @@ static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_
 }
 
 // Tile variants.  `pick` may be forced with the environment variable MODULORA_TILE
-// (big | mid | small), a tuning knob for benchmarks.
-enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_SMALL };
+// (big | mid | m128 | m64 | small), a tuning knob for benchmarks.
+enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128, PICK_SMALL };
 
 static TilePick forced_pick() {
     static int cached = -1;
@@ -435,6 +630,10 @@ static TilePick forced_pick() {
         if (e) {
             if (!std::strcmp(e, "big")) cached = PICK_BIG;
             else if (!std::strcmp(e, "mid")) cached = PICK_MID;
+            else if (!std::strcmp(e, "m128")) cached = PICK_M128;
+            else if (!std::strcmp(e, "m64")) cached = PICK_M64;
+            else if (!std::strcmp(e, "m64k")) cached = PICK_M64K;
+            else if (!std::strcmp(e, "t128")) cached = PICK_T128;
             else if (!std::strcmp(e, "small")) cached = PICK_SMALL;
         }
     }
@@ -446,23 +645,44 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
     const int Cout = BWD ? a.w.K : a.w.N;
     TilePick pick = forced_pick();
     if (pick == PICK_AUTO) {
-        const long tiles_big = (long)((a.M + 255) / 256) * ((Cout + 255) / 256);
-        const long tiles_mid = (long)((a.M + 255) / 256) * ((Cout + 127) / 128);
         if (a.M <= 32) pick = PICK_SMALL;
         else {
-            // rounds of 256 CUs; a mid tile costs about half a big one
-            const double cost_big = (double)((tiles_big + 255) / 256);
-            const double cost_mid = 0.5 * (double)((tiles_mid + 255) / 256) * 1.1;
-            pick = cost_big <= cost_mid ? PICK_BIG : PICK_MID;
+            // Cost of one 64-deep contraction step of the whole grid, in microseconds, from
+            // measured per-step times of each variant: alone on a CU (t1) and sharing it with a
+            // second workgroup (t2).  rounds = how often the 256 CUs (x occupancy) are refilled.
+            struct Variant { TilePick pick; int mt, ct, occ; double t1, t2; };
+            const Variant vs[5] = {{PICK_BIG, 256, 256, 1, 1.83, 1.83},
+                                   {PICK_MID, 256, 128, 2, 1.46, 1.95},
+                                   {PICK_M128, 128, 128, 2, 0.97, 1.40},
+                                   {PICK_M64, 64, 128, 2, 0.75, 1.10},
+                                   {PICK_M64K, 64, 128, 1, 0.62, 0.62}};
+            double best = 1e30;
+            for (const Variant &v : vs) {
+                const long tiles = (long)((a.M + v.mt - 1) / v.mt) * ((Cout + v.ct - 1) / v.ct);
+                const double cost = tiles <= 256 ? v.t1 : (double)((tiles + 256 * v.occ - 1) / (256 * v.occ)) * v.t2;
+                if (cost < best) { best = cost; pick = v.pick; }
+            }
         }
     }
     switch (pick) {
         case PICK_SMALL:
-            return launch_variant<BITS, BWD, 256, 32, 256, 32, 64, 1>(
+            return launch_variant<BITS, BWD, 256, 32, 256, 32, 64, 1, 0>(
                 a, BWD ? "gemm_bwd_32x256" : "gemm_fwd_32x256", stream);
         case PICK_MID:
-            return launch_variant<BITS, BWD, 256, 256, 128, 128, 64, 2>(
+            return launch_variant<BITS, BWD, 256, 256, 128, 128, 64, 2, 0>(
                 a, BWD ? "gemm_bwd_256x128" : "gemm_fwd_256x128", stream);
+        case PICK_M128:
+            return launch_variant<BITS, BWD, 256, 128, 128, 64, 64, 2, 2>(
+                a, BWD ? "gemm_bwd_128x128" : "gemm_fwd_128x128", stream);
+        case PICK_M64:
+            return launch_variant<BITS, BWD, 256, 64, 128, 32, 64, 2, 3>(
+                a, BWD ? "gemm_bwd_64x128" : "gemm_fwd_64x128", stream);
+        case PICK_M64K:   // 8 waves: two k-groups of 4 share every 128-deep tile
+            return launch_variant<BITS, BWD, 512, 64, 128, 32, 64, 1, 3, 128, 2>(
+                a, BWD ? "gemm_bwd_64x128k" : "gemm_fwd_64x128k", stream);
+        case PICK_T128:   // tall tile: half the dequantization work per output of the 64-row tile
+            return launch_variant<BITS, BWD, 256, 128, 64, 32, 64, 1, 2, 128, 1>(
+                a, BWD ? "gemm_bwd_128x64" : "gemm_fwd_128x64", stream);
         default:
             return launch_gemm_big(a, stream);
     }

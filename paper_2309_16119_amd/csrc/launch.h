@@ -68,18 +68,25 @@ struct DownArgs {
 };
 hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream);
 
-// out(c, j) (+)= lora_scale * sum_m act[m][c] * P[m][j]
-//   out_is_A: out index c * r + j (dA [K][r]);  else j * C + c (dB [r][N]).
-// `out` must already hold the value to accumulate onto (zeros for overwrite).
-struct GradArgs {
-    const uint16_t *act;  // bf16 [M][C]
-    int M, C, r;
-    const float *P;       // fp32 [M][r]
+// dA[k][j] (+)= lora_scale * sum_m X[m][k] dYBt[m][j]   and
+// dB[j][n] (+)= lora_scale * sum_m XA[m][j] dY[m][n],  in two launches (partials, reduce).
+struct GradPairArgs {
+    const uint16_t *X, *dY;      // bf16 [M][K], [M][N]
+    int M, K, N, r;              // r >= 1
+    const float *XA, *dYBt;      // fp32 [M][r]
     float lora_scale;
-    float *out;
-    bool out_is_A;
+    float *dA, *dB;              // fp32 [K][r], [r][N]
+    int accumulate;              // 0: overwrite, 1: add onto the outputs
+    float *partials;             // scratch, grad_geom().partial_floats floats
 };
-hipError_t launch_lora_grad(const GradArgs &a, hipStream_t stream);
+struct GradGeom {
+    int cols_a, cols_b;          // 128-column blocks of X and of dY
+    int chunks, rows_per_block;  // row chunks (one partial each)
+    int passes;                  // rank passes of 32 (r > 32)
+    size_t partial_floats;
+};
+GradGeom grad_geom(int M, int K, int N, int r);
+hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream);
 
 // ---- smallm.hip: M <= 16 streaming kernels ------------------------------------
 struct SmallArgs {

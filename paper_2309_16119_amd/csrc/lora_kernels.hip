@@ -177,39 +177,75 @@ hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream) {
 }
 
 // ---------------------------------------------------------------------------
-// Adapter gradient: out(c, j) += s * sum_m act[m][c] P[m][j].
-// A workgroup owns 128 columns and a chunk of rows; each lane owns 2 adjacent
-// columns (one 4-byte load per row), the 4 waves take rows round-robin.  P[m][:] is
-// wave-uniform.  Partial sums meet in LDS, then one fp32 atomic add per element.
+// Adapter gradients (Section 3.1.1), both in one launch plus one reduction launch:
+//   dA[k][j] = s * sum_m X[m][k]  dYBt[m][j]      dB[j][n] = s * sum_m XA[m][j] dY[m][n]
+// Stage 1: a workgroup owns 128 columns of X (or dY) and a chunk of rows; each lane owns 2
+// adjacent columns (one 4-byte load per row), the 4 waves take rows round-robin, P[m][:] is
+// wave-uniform.  The 4 waves' sums meet in LDS and go out as one partial per row chunk, laid
+// out like the outputs ([chunk][dA | dB]).  Stage 2 adds the chunks, applies s and the
+// accumulate flag.  No atomics (device-scope fp32 atomics bypass the per-XCD L2 and are slow)
+// and no zero-fill of the outputs.
 // ---------------------------------------------------------------------------
-template <int RP, bool OUT_IS_A>
-__global__ __launch_bounds__(256) void lora_grad_kernel(GradArgs a, int rows_per_block, int j0) {
+GradGeom grad_geom(int M, int K, int N, int r) {
+    GradGeom g;
+    g.cols_a = (K + 127) / 128;
+    g.cols_b = (N + 127) / 128;
+    const int col_blocks = g.cols_a + g.cols_b;
+    // enough row chunks to give the chip ~1024 workgroups, at least 32 rows each
+    int chunks = (1024 + col_blocks - 1) / col_blocks;
+    const int max_chunks = (M + 31) / 32;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    int rows = (M + chunks - 1) / chunks;
+    rows = (rows + 3) / 4 * 4;
+    g.rows_per_block = rows;
+    g.chunks = (M + rows - 1) / rows;
+    g.passes = r > 32 ? 2 : 1;
+    g.partial_floats = (size_t)g.chunks * (size_t)(K + N) * (size_t)(r > 0 ? r : 0);
+    return g;
+}
+
+template <int RP>
+__global__ __launch_bounds__(256) void lora_grad_partial_kernel(GradPairArgs a, GradGeom g) {
     __shared__ float red[3][64][2 * RP + 1];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c = blockIdx.x * 128 + 2 * lane;
-    const int r = a.r;
-    const int m_begin = blockIdx.y * rows_per_block;
-    int m_end = m_begin + rows_per_block;
+    const bool is_a = (int)blockIdx.x < g.cols_a;
+    const uint16_t *act = is_a ? a.X : a.dY;
+    const float *P = is_a ? a.dYBt : a.XA;
+    const int C = is_a ? a.K : a.N;
+    const int c = (is_a ? blockIdx.x : blockIdx.x - g.cols_a) * 128 + 2 * lane;
+    const int r = a.r, j0 = blockIdx.z * RP;
+    const int m_begin = blockIdx.y * g.rows_per_block;
+    int m_end = m_begin + g.rows_per_block;
     if (m_end > a.M) m_end = a.M;
-    const bool col_ok = c < a.C;   // C is even, so c + 1 < C too
+    const bool col_ok = c < C;   // C is even, so c + 1 < C too
 
     float acc[2][RP];
 #pragma unroll
     for (int j = 0; j < RP; ++j) acc[0][j] = acc[1][j] = 0.f;
 
-    for (int m = m_begin + wave; m < m_end; m += 4) {
-        uint32_t v = 0;
-        if (col_ok) v = *reinterpret_cast<const uint32_t *>(a.act + (size_t)m * a.C + c);
+    auto row_fma = [&](uint32_t v, int m) {
         const float x0 = __uint_as_float(v << 16), x1 = __uint_as_float(v & 0xFFFF0000u);
-        const float *p = a.P + (size_t)m * r + j0;
+        const float *p = P + (size_t)m * r + j0;
 #pragma unroll
         for (int j = 0; j < RP; ++j) {
             const float pj = j0 + j < r ? p[j] : 0.f;
             acc[0][j] = __builtin_fmaf(x0, pj, acc[0][j]);
             acc[1][j] = __builtin_fmaf(x1, pj, acc[1][j]);
         }
+    };
+    const uint16_t *col = act + (col_ok ? c : 0);
+    int m = m_begin + wave;
+    for (; m + 12 < m_end; m += 16) {     // four rows in flight per wave
+        uint32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint32_t *>(col + (size_t)(m + 4 * u) * C);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) row_fma(v[u], m + 4 * u);
     }
+    for (; m < m_end; m += 4) row_fma(*reinterpret_cast<const uint32_t *>(col + (size_t)m * C), m);
+
     if (wave > 0) {
 #pragma unroll
         for (int j = 0; j < RP; ++j) {
@@ -219,49 +255,77 @@ __global__ __launch_bounds__(256) void lora_grad_kernel(GradArgs a, int rows_per
     }
     __syncthreads();
     if (wave != 0 || !col_ok) return;
+    float *part = a.partials + (size_t)blockIdx.y * ((size_t)(a.K + a.N) * r);
 #pragma unroll
-    for (int j = 0; j < RP; ++j) {
-        if (j0 + j >= r) break;
+    for (int t = 0; t < 2; ++t) {
+        float v[RP];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const float v = acc[t][j] + red[0][lane][t * RP + j] + red[1][lane][t * RP + j] +
-                            red[2][lane][t * RP + j];
-            float *dst = OUT_IS_A ? a.out + (size_t)(c + t) * r + (j0 + j)
-                                  : a.out + (size_t)(j0 + j) * a.C + (c + t);
-            atomicAdd(dst, a.lora_scale * v);
+        for (int j = 0; j < RP; ++j)
+            v[j] = acc[t][j] + red[0][lane][t * RP + j] + red[1][lane][t * RP + j] + red[2][lane][t * RP + j];
+        if (is_a) {
+            float *dst = part + (size_t)(c + t) * r + j0;
+            if ((r & 3) == 0) {
+#pragma unroll
+                for (int j = 0; j < RP; j += 4)
+                    if (j0 + j < r) *reinterpret_cast<float4 *>(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < RP; ++j)
+                    if (j0 + j < r) dst[j] = v[j];
+            }
+        } else {
+            float *dst = part + (size_t)a.K * r + (size_t)j0 * a.N + (c + t);
+#pragma unroll
+            for (int j = 0; j < RP; ++j)
+                if (j0 + j < r) dst[(size_t)j * a.N] = v[j];
         }
     }
 }
 
-template <int RP>
-static hipError_t launch_grad_rp(const GradArgs &a, int j0, hipStream_t stream) {
-    const int col_blocks = (a.C + 127) / 128;
-    // enough row chunks to give the chip ~1024 workgroups, at least 32 rows each
-    int chunks = (1024 + col_blocks - 1) / col_blocks;
-    const int max_chunks = (a.M + 31) / 32;
-    if (chunks > max_chunks) chunks = max_chunks;
-    if (chunks < 1) chunks = 1;
-    int rows_per_block = (a.M + chunks - 1) / chunks;
-    rows_per_block = (rows_per_block + 3) / 4 * 4;
-    chunks = (a.M + rows_per_block - 1) / rows_per_block;
-    dim3 grid(col_blocks, chunks);
-    prof_before("lora_grad", stream);
-    if (a.out_is_A)
-        lora_grad_kernel<RP, true><<<grid, 256, 0, stream>>>(a, rows_per_block, j0);
-    else
-        lora_grad_kernel<RP, false><<<grid, 256, 0, stream>>>(a, rows_per_block, j0);
-    prof_after(stream);
-    return hipGetLastError();
+// out = (accumulate ? out : 0) + s * sum over chunks; 4 consecutive elements per thread.
+__global__ __launch_bounds__(256) void lora_grad_reduce_kernel(GradPairArgs a, int chunks) {
+    const size_t n_a = (size_t)a.K * a.r, n = n_a + (size_t)a.N * a.r;
+    const size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (e >= n) return;
+    float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float *p = a.partials + e;
+    int q = 0;
+    for (; q + 4 <= chunks; q += 4) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4 *>(p + (size_t)(q + u) * n);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { sum.x += v[u].x; sum.y += v[u].y; sum.z += v[u].z; sum.w += v[u].w; }
+    }
+    for (; q < chunks; ++q) {
+        const float4 v = *reinterpret_cast<const float4 *>(p + (size_t)q * n);
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    float4 *dst = reinterpret_cast<float4 *>(e < n_a ? a.dA + e : a.dB + (e - n_a));
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (a.accumulate) o = *dst;
+    o.x = __builtin_fmaf(a.lora_scale, sum.x, o.x);
+    o.y = __builtin_fmaf(a.lora_scale, sum.y, o.y);
+    o.z = __builtin_fmaf(a.lora_scale, sum.z, o.z);
+    o.w = __builtin_fmaf(a.lora_scale, sum.w, o.w);
+    *dst = o;
 }
 
-hipError_t launch_lora_grad(const GradArgs &a, hipStream_t stream) {
-    if (a.r <= 8) return launch_grad_rp<8>(a, 0, stream);
-    if (a.r <= 16) return launch_grad_rp<16>(a, 0, stream);
-    if (a.r <= 32) return launch_grad_rp<32>(a, 0, stream);
-    // ranks 33..64: two passes of 32 ranks each (keeps the LDS partials under 64 KB)
-    const hipError_t e = launch_grad_rp<32>(a, 0, stream);
+hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream) {
+    const GradGeom g = grad_geom(a.M, a.K, a.N, a.r);
+    dim3 grid(g.cols_a + g.cols_b, g.chunks, g.passes);
+    prof_before("lora_grad", stream);
+    if (a.r <= 8) lora_grad_partial_kernel<8><<<grid, 256, 0, stream>>>(a, g);
+    else if (a.r <= 16) lora_grad_partial_kernel<16><<<grid, 256, 0, stream>>>(a, g);
+    else lora_grad_partial_kernel<32><<<grid, 256, 0, stream>>>(a, g);
+    prof_after(stream);
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_grad_rp<32>(a, 32, stream);
+    const size_t n = (size_t)(a.K + a.N) * a.r;
+    prof_before("lora_grad_reduce", stream);
+    lora_grad_reduce_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, stream>>>(a, g.chunks);
+    prof_after(stream);
+    return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float *dst, size_t n) {
