@@ -85,7 +85,7 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     constexpr int GWAVES = NWAVES / KG;      // waves of one k-group: they tile the MT x CT output
     static_assert((MT / WM) * (CT / WN) == GWAVES && GWAVES * KG == NWAVES, "wave grid covers the tile");
     constexpr int KS_LOCAL = (RT / 16) / KG;   // 16-deep steps of a tile that one wave takes: ks = i * KG + kg
-    static_assert((KG == 1 || KG == 2) && (RT / 16) % KG == 0 && (KS_LOCAL == 2 || KS_LOCAL == 4 || KS_LOCAL == 8),
+    static_assert((KG == 1 || KG == 2 || KG == 4) && (RT / 16) % KG == 0 && (KS_LOCAL == 2 || KS_LOCAL == 4 || KS_LOCAL == 8),
                   "k-steps divide between the groups");
     static_assert(WM % 32 == 0 && WN == 64, "wave tile: rows in 32s, two 32-column MFMA tiles");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -106,12 +106,19 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
 
     // ---- per-thread constants of the staging pattern ---------------------------
     constexpr int A_CH = MT * (RT / 8) / THREADS;            // 16-byte activation chunks per thread
-    constexpr int FW_UNITS = CT * (RT / 32) / THREADS;       // forward: (column, 32-code block) units
-    constexpr int BW_UNITS = (CT / 8) * (RT / 4) / THREADS;  // backward: (4 columns n, 8 codes k) units
+    // Weight staging units of a tile: forward (column, 32-code block), backward (4 columns n,
+    // 8 codes k).  With fewer units than threads only the first FW_N (BW_N) threads dequantize
+    // and store; the others issue the same loads again (so that every wave has the same
+    // number of loads in flight) and drop them.
+    constexpr int FW_N = CT * (RT / 32), BW_N = (CT / 8) * (RT / 4);
+    constexpr int FW_UNITS = FW_N >= THREADS ? FW_N / THREADS : 1;
+    constexpr int BW_UNITS = BW_N >= THREADS ? BW_N / THREADS : 1;
+    const bool w_active = tid < (BWD ? BW_N : FW_N);
     constexpr int W_CH = CT * (RT / 8) / THREADS;            // 16-byte chunks of an extension W tile
     static_assert(A_CH >= 1 && (MT * (RT / 8)) % THREADS == 0, "activation tile divides");
-    static_assert(FW_UNITS >= 1 && (CT * (RT / 32)) % THREADS == 0, "forward units divide");
-    static_assert(BW_UNITS >= 1 && ((CT / 8) * (RT / 4)) % THREADS == 0, "backward units divide");
+    static_assert(FW_N % THREADS == 0 || THREADS % FW_N == 0, "forward units divide");
+    static_assert(BW_N % THREADS == 0 || THREADS % BW_N == 0, "backward units divide");
+    static_assert(FW_N % 64 == 0 && BW_N % 64 == 0, "the staging threads are whole waves");
     static_assert(W_CH >= 1, "extension tile divides");
     static_assert(THREADS % CT == 0 || CT % THREADS == 0, "forward unit -> k-block is wave-uniform");
 
@@ -143,7 +150,7 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     if (!BWD) {
 #pragma unroll
         for (int u = 0; u < FW_UNITS; ++u) {
-            const int idx = tid + u * THREADS;
+            const int idx = (tid + u * THREADS) % FW_N;
             int n = c0 + idx % CT;
             if (n > N - 1) n = N - 1;
             fw_n[u] = (uint32_t)n;
@@ -156,7 +163,7 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
         const int last_row = K * BITS / 32 - 1;
 #pragma unroll
         for (int u = 0; u < BW_UNITS; ++u) {
-            const int idx = tid + u * THREADS;
+            const int idx = (tid + u * THREADS) % BW_N;
             const int no = idx % (RT / 4), ko = idx / (RT / 4);
             int k = c0 + ko * 8;
             bw_kok[u] = k < K;
@@ -316,7 +323,7 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
             const uint8_t *zbase = a.w.zeros + (size_t)bw_g0 * N + r0;
 #pragma unroll
             for (int u = 0; u < BW_UNITS; ++u) {
-                const int idx = tid + u * THREADS;
+                const int idx = (tid + u * THREADS) % BW_N;
                 const int no = idx % (RT / 4);
                 const bool ok = r0 + no * 4 < N;
                 st.bw_lo[u] = tu32x4{0, 0, 0, 0};
@@ -353,10 +360,11 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
             }
             return;
         }
+        if (!w_active) return;
         if (!BWD) {
 #pragma unroll
             for (int u = 0; u < FW_UNITS; ++u) {
-                const int idx = tid + u * THREADS;
+                const int idx = (tid + u * THREADS) % FW_N;
                 const int nl = idx % CT;
                 const DqConst dq = make_dq((uint16_t)st.fw_scale[u], (uint8_t)st.fw_zero[u]);
 #pragma unroll
@@ -370,7 +378,7 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
         } else {
 #pragma unroll
             for (int u = 0; u < BW_UNITS; ++u) {
-                const int idx = tid + u * THREADS;
+                const int idx = (tid + u * THREADS) % BW_N;
                 const int no = idx % (RT / 4), ko = idx / (RT / 4);
                 const uint32_t lo[4] = {st.bw_lo[u][0], st.bw_lo[u][1], st.bw_lo[u][2], st.bw_lo[u][3]};
                 const uint32_t hi[4] = {st.bw_hi[u][0], st.bw_hi[u][1], st.bw_hi[u][2], st.bw_hi[u][3]};
@@ -547,23 +555,28 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
 
     // ---- the k-groups' accumulators meet in LDS; group 0 carries on alone -------------
     if (KG > 1) {
-        float *redbuf = reinterpret_cast<float *>(lds);      // [gw][i][j][v][lane]
-        if (kg == 1) {
+        float *redbuf = reinterpret_cast<float *>(lds);      // [kg - 1][gw][i][j][v][lane]
+        constexpr int GROUP_FLOATS = GWAVES * TI * TJ * 16 * 64;   // = MT * CT
+        if (kg > 0) {
 #pragma unroll
             for (int i = 0; i < TI; ++i)
 #pragma unroll
                 for (int j = 0; j < TJ; ++j)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) redbuf[(((gw * TI + i) * TJ + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+                    for (int v = 0; v < 16; ++v)
+                        redbuf[(kg - 1) * GROUP_FLOATS + (((gw * TI + i) * TJ + j) * 16 + v) * 64 + lane] = acc[i][j][v];
         }
         __syncthreads();
         if (kg != 0) return;
 #pragma unroll
-        for (int i = 0; i < TI; ++i)
+        for (int g = 0; g < KG - 1; ++g)
 #pragma unroll
-            for (int j = 0; j < TJ; ++j)
+            for (int i = 0; i < TI; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] += redbuf[(((gw * TI + i) * TJ + j) * 16 + v) * 64 + lane];
+                for (int j = 0; j < TJ; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[i][j][v] += redbuf[g * GROUP_FLOATS + (((gw * TI + i) * TJ + j) * 16 + v) * 64 + lane];
         // group 0's waves now reuse the same LDS for their patches: wait for each other's reads
         __syncthreads();
     }
@@ -600,7 +613,7 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
 template <int BITS, bool BWD, int THREADS, int MT, int CT, int WM, int WN, int OCC, int PF, int RT = 64, int KG = 1>
 static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_t stream) {
     constexpr int LROW = RT + LDS_PAD;
-    static_assert(KG == 1 || (size_t)MT * CT * 4 <= (size_t)(PF > 0 ? 2 : 1) * (MT + CT) * LROW * 2, "k-group partials fit");
+    static_assert(KG == 1 || (size_t)(KG - 1) * MT * CT * 4 <= (size_t)(PF > 0 ? 2 : 1) * (MT + CT) * LROW * 2, "k-group partials fit");
     const GemmDev d = make_gemm_dev(a, MT, CT);
     const int blocks = (d.tiles_m * d.tiles_c + 7) / 8 * 8;
     size_t lds_bytes = (size_t)(PF > 0 ? 2 : 1) * (MT + CT) * LROW * sizeof(uint16_t);
@@ -620,7 +633,7 @@ static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_
 
 // Tile variants.  `pick` may be forced with the environment variable MODULORA_TILE
 // (big | mid | m128 | m64 | small), a tuning knob for benchmarks.
-enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128, PICK_SMALL };
+enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128, PICK_T128K, PICK_SMALL };
 
 static TilePick forced_pick() {
     static int cached = -1;
@@ -634,6 +647,7 @@ static TilePick forced_pick() {
             else if (!std::strcmp(e, "m64")) cached = PICK_M64;
             else if (!std::strcmp(e, "m64k")) cached = PICK_M64K;
             else if (!std::strcmp(e, "t128")) cached = PICK_T128;
+            else if (!std::strcmp(e, "t128k")) cached = PICK_T128K;
             else if (!std::strcmp(e, "small")) cached = PICK_SMALL;
         }
     }
@@ -651,11 +665,12 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
             // measured per-step times of each variant: alone on a CU (t1) and sharing it with a
             // second workgroup (t2).  rounds = how often the 256 CUs (x occupancy) are refilled.
             struct Variant { TilePick pick; int mt, ct, occ; double t1, t2; };
-            const Variant vs[5] = {{PICK_BIG, 256, 256, 1, 1.83, 1.83},
+            const Variant vs[6] = {{PICK_BIG, 256, 256, 1, 1.83, 1.83},
                                    {PICK_MID, 256, 128, 2, 1.46, 1.95},
                                    {PICK_M128, 128, 128, 2, 0.97, 1.40},
                                    {PICK_M64, 64, 128, 2, 0.75, 1.10},
-                                   {PICK_M64K, 64, 128, 1, 0.62, 0.62}};
+                                   {PICK_M64K, 64, 128, 1, 0.62, 0.62},
+                                   {PICK_T128K, 128, 64, 1, 0.57, 0.57}};
             double best = 1e30;
             for (const Variant &v : vs) {
                 const long tiles = (long)((a.M + v.mt - 1) / v.mt) * ((Cout + v.ct - 1) / v.ct);
@@ -683,6 +698,9 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
         case PICK_T128:   // tall tile: half the dequantization work per output of the 64-row tile
             return launch_variant<BITS, BWD, 256, 128, 64, 32, 64, 1, 2, 128, 1>(
                 a, BWD ? "gemm_bwd_128x64" : "gemm_fwd_128x64", stream);
+        case PICK_T128K:  // 8 waves: four k-groups of two 64x64 wave tiles
+            return launch_variant<BITS, BWD, 512, 128, 64, 64, 64, 1, 3, 128, 4>(
+                a, BWD ? "gemm_bwd_128x64k" : "gemm_fwd_128x64k", stream);
         default:
             return launch_gemm_big(a, stream);
     }
