@@ -22,19 +22,19 @@
 // help of one extra MFMA per step against a vector of ones (it yields sum_k X[m][k], which
 // the zero point needs anyway).  Which two codes share a register is fixed by the bit
 // layout, so the X operand is pre-permuted to the same order by a small prep kernel
-// (which also forms the partial sums of X A for the adapter term).  For 3-bit codes a
-// field that lands one bit high (128 + 2q) is compensated by halving the matching X
-// element -- powers of two, exact.
+// (which also forms the partial sums of X A for the adapter term).  For 3-bit codes the
+// low field of a register lands four bits high (128 + 16q), compensated by the matching X
+// element divided by 16 -- a power of two, exact.
 #include "device_common.h"
+#include "gemm_common.h"
 #include "launch.h"
 
 namespace mlr {
 
 namespace sm {
 constexpr int WG_WAVES = 4, WG_THREADS = WG_WAVES * 64;
-constexpr int COLS = 32;               // columns per workgroup (2 per lane of a 16-lane group)
 constexpr int PREP_K = 128;            // contraction elements per prep workgroup
-constexpr int MAX_KSPLIT = 8;          // workgroups that may share a column block
+constexpr int MAX_KSPLIT = 32;         // workgroups that may share a column block
 constexpr uint32_t MAGIC = 0x43004300u;   // two bfloat16 128.0
 constexpr uint32_t ONES = 0x3F803F80u;    // two bfloat16 1.0
 
@@ -66,7 +66,7 @@ __device__ __forceinline__ uint32_t opaque_vgpr(uint32_t v) {
     return v;
 }
 struct CodeMasks {
-    uint32_t field, top, magic;   // field mask of a register pair, mask of 3-bit code 4, 2 x 128.0
+    uint32_t field, magic;        // field mask of a register pair, 2 x 128.0
 };
 
 // chunks (8 codes) per step of a lane group, and codes per wave step
@@ -79,8 +79,7 @@ template <int BITS> struct Geo {
 template <int BITS>
 __device__ __forceinline__ CodeMasks make_masks() {
     CodeMasks m;
-    m.field = opaque_sgpr(BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x0007000Eu));
-    m.top = opaque_sgpr(0x00070000u);
+    m.field = opaque_sgpr(BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x00070070u));
     m.magic = opaque_vgpr(MAGIC);
     return m;
 }
@@ -97,13 +96,20 @@ __device__ __forceinline__ void codes_to_operand(const uint32_t *w, int c, const
 #pragma unroll
         for (int p = 0; p < 4; ++p) o[p] = and_or(w[0] >> (2 * (4 * c + p)), m.field, m.magic);
     } else {
-        // 24-bit chunk c of the 96-bit block; regs (2*q0, q5) (2*q1, q6) (2*q2, q7) (q3, q4)
-        const uint32_t ch = block_chunk<3>(w, c);
-        o[0] = and_or(ch << 1, m.field, m.magic);
-        o[1] = and_or(ch >> 2, m.field, m.magic);
-        o[2] = and_or(ch >> 5, m.field, m.magic);
-        // code 3 (bits 9-11) low, code 4 (bits 12-14) high
-        o[3] = ((ch >> 9) & 7u) | and_or(ch << 4, m.top, m.magic);
+        // 24-bit chunk c of the 96-bit block (stream bits 24c .. 24c+23); reg p = (16 * code p,
+        // code p+4): code p must land at bits 4-6, i.e. the chunk shifted right by 3p - 4, and
+        // code p+4 (12 bits further up) then sits at bits 16-18.  The shift is folded into the
+        // extraction of the chunk from the words (one funnel shift or plain shift per register).
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int sh = 24 * c + 3 * p - 4;       // stream bit that lands at register bit 0
+            uint32_t x;
+            if (sh < 0) x = w[0] << (-sh);
+            else if ((sh & 31) == 0) x = w[sh >> 5];
+            else if ((sh >> 5) == 2) x = w[2] >> (sh & 31);
+            else x = __builtin_amdgcn_alignbit(w[(sh >> 5) + 1], w[sh >> 5], sh & 31);
+            o[p] = and_or(x, m.field, m.magic);
+        }
     }
 }
 
@@ -116,10 +122,9 @@ __device__ __forceinline__ int perm_src(int bits, int pos, float *scale) {
         const int c = pos >> 3, p = (pos >> 1) & 3, h = pos & 1;
         return 4 * c + p + 8 * h;
     }
-    // 3-bit: (X0/2, X5, X1/2, X6, X2/2, X7, X3, X4)
-    const int src[8] = {0, 5, 1, 6, 2, 7, 3, 4};
-    if (pos == 0 || pos == 2 || pos == 4) *scale = 0.5f;
-    return src[pos];
+    // 3-bit: (X0/16, X4, X1/16, X5, X2/16, X6, X3/16, X7)
+    if ((pos & 1) == 0) *scale = 0.0625f;
+    return (pos >> 1) + 4 * (pos & 1);
 }
 }  // namespace sm
 
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(256) void smallm_prep_fwd_kernel(const uint16_t *__
     }
     __syncthreads();
     if (kc >= K) return;
-    // permuted (and for 3-bit partly halved) copy of this thread's chunk
+    // permuted (and for 3-bit partly scaled) copy of this thread's chunk
     const int unit = bits == 2 ? 16 : 8;
     uint16_t o[8];
 #pragma unroll
@@ -199,11 +204,16 @@ __global__ __launch_bounds__(256) void smallm_prep_fwd_kernel(const uint16_t *__
 }
 
 // ---------------------------------------------------------------------------------
-// forward stream kernel.  A workgroup owns 32 output columns; its 16 waves split the
-// quantization groups along K; each wave keeps a 16 x 32 fp32 partial in registers; the
-// partials meet in LDS; the epilogue adds the adapter term and stores bfloat16.
-// Inside a wave, lane l = 16 j + i holds columns n0 + 2i, n0 + 2i + 1 (one 8-byte load per
-// packed word row) and the k-slice j of each MFMA call.
+// forward stream kernel.  A workgroup of 4 waves owns 256 output columns and one slice of K
+// (a run of whole quantization groups); each wave owns 64 of the columns.  The slice of the
+// re-ordered activations sits in LDS, shared by the four waves.  Inside a wave, lane
+// l = 16 j + i holds columns n0 + 4i .. 4i+3 (one 16-byte load per packed word row, 256
+// contiguous bytes per 16-lane group) and the k-slice j of each MFMA call.  Packed words,
+// scales and zeros are loaded DEPTH steps ahead by loads issued from assembly and awaited
+// with an exact count; loads past the end of the slice are clamped to its last step, so the
+// number in flight never changes and the loop needs no predicates.  The 16 x 64 fp32 result
+// of a wave is final for the slice: with one slice it goes through the epilogue, else it is
+// stored as a partial tile for the finish kernel.
 // ---------------------------------------------------------------------------------
 struct SmallFwdDev {
     LayerView w;
@@ -218,13 +228,45 @@ struct SmallFwdDev {
     float *Yacc;            // [ksplit][16][N] fp32 partial tiles (used when ksplit > 1)
 };
 
-// Epilogue shared by the stream kernel (no K split) and the finish kernel: thread tid holds
-// outputs tid and tid + WG_THREADS of the 16 x 32 tile of column block cb in y[]; adds the
-// adapter term and stores bfloat16.  XA = sum of the prep kernel's partials: element t of the
-// 16 x r tile is summed by WG_THREADS / (16 r) threads over interleaved slices of the
-// partials, eight independent loads at a time, and the slices meet in LDS (Us, 16 * 64 floats).
-__device__ __forceinline__ void smallm_fwd_epilogue(const SmallFwdDev &d, int cb, const float y[2], float *Us) {
-    const int tid = threadIdx.x, N = d.w.N, n0 = cb * sm::COLS;
+namespace sm {
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void ald(u32x4 &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void ald(u32x2 &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+__device__ __forceinline__ void ald(uint32_t &dst, const void *base, uint32_t voff) {
+    asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base
+// wave-uniform, passed in M0); counted in vmcnt like a register load.
+__device__ __forceinline__ void ald_lds(const void *gbase_uniform, uint32_t voff_bytes, uint32_t lds_base_uniform) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base_uniform), "v"(voff_bytes), "s"(gbase_uniform)
+                 : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <typename T>
+__device__ __forceinline__ void tie(T &x) {
+    asm volatile("" : "+v"(x)::"memory");
+}
+constexpr int WCOLS = 64;                 // columns per wave (4 per lane of a 16-lane group)
+constexpr int BCOLS = WG_WAVES * WCOLS;   // columns per workgroup
+constexpr int MAX_RANGE = 2048;           // contraction elements of one K slice (64 KB of LDS)
+}  // namespace sm
+
+// XA = sum of the prep kernel's partials into Us (16 x r floats in LDS): element t of the tile
+// is summed by WG_THREADS / (16 r) threads over interleaved slices of the partials, eight
+// independent loads at a time, and the slices meet through LDS atomics.
+__device__ __forceinline__ void smallm_gather_xa(const SmallFwdDev &d, float *Us) {
+    const int tid = threadIdx.x;
     const int ur = 16 * d.r;
     for (int t = tid; t < ur; t += sm::WG_THREADS) Us[t] = 0.f;
     __syncthreads();
@@ -243,97 +285,111 @@ __device__ __forceinline__ void smallm_fwd_epilogue(const SmallFwdDev &d, int cb
         }
     }
     __syncthreads();
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int idx = tid + e * sm::WG_THREADS, m = idx / sm::COLS, col = n0 + idx % sm::COLS;
-        if (m < d.M && col < N) {
-            float lora = 0.f;
-            for (int jj = 0; jj < d.r; ++jj) lora = __builtin_fmaf(Us[m * d.r + jj], d.B[(size_t)jj * N + col], lora);
-            d.Y[(size_t)m * N + col] = float_to_bf16_bits(__builtin_fmaf(d.lora_scale, lora, y[e]));
-        }
+}
+
+// Adds the adapter term to the four adjacent outputs y[0..3] of row m, columns col..col+3
+// (col a multiple of 4, col + 3 < N) and stores them as bfloat16.
+__device__ __forceinline__ void smallm_store4(const SmallFwdDev &d, const float *Us, int m, int col, const float y[4]) {
+    float l[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int jj = 0; jj < d.r; ++jj) {
+        const float u = Us[m * d.r + jj];
+        const float4 b = *reinterpret_cast<const float4 *>(d.B + (size_t)jj * d.w.N + col);
+        l[0] = __builtin_fmaf(u, b.x, l[0]);
+        l[1] = __builtin_fmaf(u, b.y, l[1]);
+        l[2] = __builtin_fmaf(u, b.z, l[2]);
+        l[3] = __builtin_fmaf(u, b.w, l[3]);
     }
-    if (cb == 0 && d.XA != nullptr)
-        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
+    uint2 o;
+    o.x = pack_bf16x2(__builtin_fmaf(d.lora_scale, l[0], y[0]), __builtin_fmaf(d.lora_scale, l[1], y[1]));
+    o.y = pack_bf16x2(__builtin_fmaf(d.lora_scale, l[2], y[2]), __builtin_fmaf(d.lora_scale, l[3], y[3]));
+    *reinterpret_cast<uint2 *>(d.Y + (size_t)m * d.w.N + col) = o;
 }
 
 template <int BITS>
-__global__ __launch_bounds__(sm::WG_THREADS, 4) void smallm_fwd_kernel(SmallFwdDev d) {
+__global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdDev d) {
     using G = sm::Geo<BITS>;
-    __shared__ float red[sm::WG_WAVES][16][sm::COLS + 1];
+    extern __shared__ __attribute__((aligned(16))) uint4 xs[];   // [chunks of the slice][16 rows]
     __shared__ float Us[16 * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 15, j = lane >> 4;
-    const int K = d.w.K, N = d.w.N, group = d.w.group;
-    const int cb = blockIdx.x / d.ksplit, ks = blockIdx.x % d.ksplit;   // column block, K split
-    const int n0 = cb * sm::COLS;
-    int n = n0 + 2 * i;
-    if (n > N - 2) n = N - 2;                       // clamped pair, masked at the store
+    const int N = d.w.N, group = d.w.group;
+    const int cb = blockIdx.x / d.ksplit, ks = blockIdx.x % d.ksplit;   // column block, K slice
+    const int nw = cb * sm::BCOLS + wave * sm::WCOLS;   // first column of the wave
+    int n = nw + 4 * i;
+    const bool col_ok = n < N;                      // N is a multiple of 8: all four columns or none
+    if (n > N - 4) n = N - 4;                       // clamped loads, masked at the store
 
-    // this wave's share of the quantization groups
-    const int n_groups = K / group;
-    const int parts = d.ksplit * sm::WG_WAVES, part = ks * sm::WG_WAVES + wave;
-    const int g_begin = (int)((long)n_groups * part / parts);
-    const int g_end = (int)((long)n_groups * (part + 1) / parts);
-    const int steps_per_group = group / G::KSTEP;
+    // this workgroup's run of quantization groups, as a run of steps (KSTEP codes each)
+    const int n_groups = d.w.K / group;
+    const int g_begin = (int)((long)n_groups * ks / d.ksplit);
+    const int g_end = (int)((long)n_groups * (ks + 1) / d.ksplit);
+    const int spg = group / G::KSTEP;               // steps per group
+    const int s_begin = g_begin * spg, s_end = g_end * spg;
 
-    f32x4 yacc[2];
-#pragma unroll
-    for (int cs = 0; cs < 2; ++cs)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) yacc[cs][v] = 0.f;
-
-    const uint32_t ones4[4] = {sm::ONES, sm::ONES, sm::ONES, sm::ONES};
-    const uint32_t invf4[4] = {0x3F804000u, 0x3F804000u, 0x3F804000u, sm::ONES};   // (2,1)(2,1)(2,1)(1,1)
-    const bf16x8 ones = sm::as_bf16x8(ones4), invf = sm::as_bf16x8(invf4);
-
-    // The wave's work is a run of steps (KSTEP codes each), group after group; a group's
-    // affine part is applied after its last step.  Loads run DEPTH steps ahead of the MFMAs
-    // in a rotating set of register buffers (the loop is unrolled by DEPTH so the buffer
-    // index is static).  Every address is a wave-uniform base plus a per-lane constant.
-    // deep enough that a CU keeps ~64-96 KB of packed words in flight (16 waves x DEPTH steps)
-    constexpr int DEPTH = BITS == 3 ? 3 : (BITS == 2 ? 6 : 8);
-    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-    struct Step {
-        u32x2 w[G::WORDS];
-        uint4 xa[G::NC];
-        uint32_t sbits;
-        uint16_t zbits;
+    constexpr int DEPTH = BITS == 3 ? 4 : 8;
+    constexpr int SL = G::WORDS + 2;                // loads per stage
+    struct Stage {
+        sm::u32x4 w[G::WORDS];
+        sm::u32x2 sc;      // 4 binary16 scales
+        uint32_t z;        // 4 zero points
     };
-    // lane group j reads packed rows (4 s + j) * WORDS + q, columns n, n + 1
+    Stage st[DEPTH];
+    // lane group j reads packed rows (4 s + j) * WORDS + q, columns n .. n + 3
     const uint32_t w_voff = (uint32_t)(((size_t)j * G::WORDS * N + n) * 4);
-    // and operand chunks 4 NC s + NC j + c, row i:  element ((chunk) * 16 + i) * 8
-    const uint32_t x_voff = (uint32_t)(((j * G::NC) * 16 + i) * 16);
     const uint32_t s_voff = (uint32_t)n * 2u, z_voff = (uint32_t)n;
-    auto load_step = [&](Step &sd, int s, int g) {
+    auto issue = [&](Stage &sd, int s) {            // s: any step of the slice (clamped by the caller)
         const uint32_t *wbase = d.w.qweight + (size_t)s * (4 * G::WORDS) * N;
 #pragma unroll
-        for (int q = 0; q < G::WORDS; ++q)   // streamed once: non-temporal
-            sd.w[q] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(
-                reinterpret_cast<const char *>(wbase + (size_t)q * N) + w_voff));
-        const uint16_t *xbase = d.Xp + (size_t)s * (4 * G::NC * 128);
-#pragma unroll
-        for (int c = 0; c < G::NC; ++c) sd.xa[c] = load_at<uint4>(xbase + c * 128, x_voff);
-        sd.sbits = load_at<uint32_t>(d.w.scales + (size_t)g * N, s_voff);
-        sd.zbits = load_at<uint16_t>(d.w.zeros + (size_t)g * N, z_voff);
+        for (int q = 0; q < G::WORDS; ++q) sm::ald(sd.w[q], wbase + (size_t)q * N, w_voff);
+        const int g = s / spg;
+        sm::ald(sd.sc, d.w.scales + (size_t)g * N, s_voff);
+        sm::ald(sd.z, d.w.zeros + (size_t)g * N, z_voff);
     };
+    // The slice of the re-ordered activations, a contiguous run of 16-byte operand rows, goes
+    // straight from global memory into LDS: 1 KB per wave and load, the waves take turns.
+    // (A slice is a multiple of 32 contraction elements, i.e. of 1 KB.)  These loads are
+    // issued first, so they are the oldest ones in flight.
+    {
+        const char *src = reinterpret_cast<const char *>(d.Xp) + (size_t)s_begin * (G::KSTEP / 8) * 256;
+        const int n_kb = (s_end - s_begin) * (G::KSTEP / 8) / 4;          // 1 KB units
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)xs;
+        for (int u = wave; u < n_kb; u += sm::WG_WAVES) sm::ald_lds(src + (size_t)u * 1024, (uint32_t)lane * 16u, lds0 + (uint32_t)u * 1024u);
+    }
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd) issue(st[dd], s_begin + dd < s_end ? s_begin + dd : s_end - 1);
+    // everything older than the DEPTH stages has landed: this wave's part of the slice is in LDS
+    sm::wait_vm<DEPTH * SL>();
+    __syncthreads();
 
+    f32x4 yacc[4], tmp[4], s1, s2;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+        for (int cs = 0; cs < 4; ++cs) { yacc[cs][v] = 0.f; tmp[cs][v] = 0.f; }
+        s1[v] = 0.f; s2[v] = 0.f;
+    }
+    const uint32_t ones4[4] = {sm::ONES, sm::ONES, sm::ONES, sm::ONES};
+    const uint32_t invf4[4] = {0x3F804180u, 0x3F804180u, 0x3F804180u, 0x3F804180u};   // (16, 1) pairs
+    const bf16x8 ones = sm::as_bf16x8(ones4), invf = sm::as_bf16x8(invf4);
     const sm::CodeMasks masks = sm::make_masks<BITS>();
-    f32x4 tmp[2], s1, s2;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) { tmp[0][v] = 0.f; tmp[1][v] = 0.f; s1[v] = 0.f; s2[v] = 0.f; }
 
-    auto compute_step = [&](const Step &sd, bool group_ends) {
-        uint32_t w0[G::WORDS], w1[G::WORDS];
+    auto compute = [&](Stage &sd, int srel, bool group_ends) {
+        // operand chunks 4 NC srel + NC j + c of the slice, row i
+        const uint4 *xrow = xs + ((size_t)srel * 4 * G::NC + G::NC * j) * 16 + i;
+        uint4 xa[G::NC];
 #pragma unroll
-        for (int q = 0; q < G::WORDS; ++q) { w0[q] = sd.w[q][0]; w1[q] = sd.w[q][1]; }
+        for (int c = 0; c < G::NC; ++c) xa[c] = xrow[c * 16];
 #pragma unroll
         for (int c = 0; c < G::NC; ++c) {
-            const bf16x8 a = sm::as_bf16x8(sd.xa[c]);
-            uint32_t o[4];
-            sm::codes_to_operand<BITS>(w0, c, masks, o);
-            tmp[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), tmp[0], 0, 0, 0);
-            sm::codes_to_operand<BITS>(w1, c, masks, o);
-            tmp[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), tmp[1], 0, 0, 0);
+            const bf16x8 a = sm::as_bf16x8(xa[c]);
+#pragma unroll
+            for (int cs = 0; cs < 4; ++cs) {
+                uint32_t wq[G::WORDS], o[4];
+#pragma unroll
+                for (int q = 0; q < G::WORDS; ++q) wq[q] = sd.w[q][cs];
+                sm::codes_to_operand<BITS>(wq, c, masks, o);
+                tmp[cs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), tmp[cs], 0, 0, 0);
+            }
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, s1, 0, 0, 0);
             if (BITS == 3) s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, invf, s2, 0, 0, 0);
         }
@@ -341,99 +397,121 @@ __global__ __launch_bounds__(sm::WG_THREADS, 4) void smallm_fwd_kernel(SmallFwdD
         // end of a group: tmp = sum a (128 + q/f);  s1 = sum a;  s2 = sum a/f = sum X
         // (f == 1 unless 3-bit)
 #pragma unroll
-        for (int cs = 0; cs < 2; ++cs) {
-            const float scale = half_bits_to_float((uint16_t)(sd.sbits >> (16 * cs)));
-            const float zero = (float)((sd.zbits >> (8 * cs)) & 0xFFu);
+        for (int cs = 0; cs < 4; ++cs) {
+            const float scale = half_bits_to_float((uint16_t)(sd.sc[cs >> 1] >> (16 * (cs & 1))));
+            const float zero = (float)((sd.z >> (8 * cs)) & 0xFFu);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float xsum = BITS == 3 ? s2[v] : s1[v];
                 const float qx = __builtin_fmaf(-128.0f, s1[v], tmp[cs][v]);       // sum X q
                 yacc[cs][v] = __builtin_fmaf(scale, __builtin_fmaf(-zero, xsum, qx), yacc[cs][v]);
+                tmp[cs][v] = 0.f;
             }
         }
 #pragma unroll
-        for (int v = 0; v < 4; ++v) { tmp[0][v] = 0.f; tmp[1][v] = 0.f; s1[v] = 0.f; s2[v] = 0.f; }
+        for (int v = 0; v < 4; ++v) { s1[v] = 0.f; s2[v] = 0.f; }
     };
 
-    const int s_begin = g_begin * steps_per_group, s_end = g_end * steps_per_group;
-    Step buf[DEPTH];
-    // (step, group, position in group) of the next step to load and of the next to compute
-    int ls = s_begin, lg = g_begin, lp = 0;
-#pragma unroll
-    for (int dd = 0; dd < DEPTH; ++dd)
-        if (ls < s_end) {
-            load_step(buf[dd], ls, lg);
-            ++ls;
-            if (++lp == steps_per_group) { lp = 0; ++lg; }
-        }
-
-    int cp = 0;
+    int cp = 0;   // position of the next step inside its group
     for (int s = s_begin; s < s_end; s += DEPTH) {
 #pragma unroll
         for (int dd = 0; dd < DEPTH; ++dd) {
             if (s + dd < s_end) {
-                const bool ends = ++cp == steps_per_group;
+                // DEPTH - 1 younger stages stay in flight
+                sm::wait_vm<(DEPTH - 1) * SL>();
+#pragma unroll
+                for (int q = 0; q < G::WORDS; ++q) sm::tie(st[dd].w[q]);
+                sm::tie(st[dd].sc);
+                sm::tie(st[dd].z);
+                const bool ends = ++cp == spg;
                 if (ends) cp = 0;
-                compute_step(buf[dd], ends);
-                if (ls < s_end) {
-                    load_step(buf[dd], ls, lg);
-                    ++ls;
-                    if (++lp == steps_per_group) { lp = 0; ++lg; }
-                }
+                compute(st[dd], s + dd - s_begin, ends);
+                const int sn = s + dd + DEPTH;
+                issue(st[dd], sn < s_end ? sn : s_end - 1);
             }
         }
     }
+    sm::wait_vm<0>();
 
-    // meet in LDS: D register v of lane (i, j) is row 4j + v, column i of the call's column set
-#pragma unroll
-    for (int cs = 0; cs < 2; ++cs)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) red[wave][4 * j + v][2 * i + cs] = yacc[cs][v];
-    __syncthreads();
-
-    // each thread owns two of the 16 x 32 outputs of the column block
-    float y[2];
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int idx = tid + e * sm::WG_THREADS, m = idx / sm::COLS, c = idx % sm::COLS;
-        y[e] = 0.f;
-#pragma unroll
-        for (int w = 0; w < sm::WG_WAVES; ++w) y[e] += red[w][m][c];
-    }
+    // D register v of lane (i, j): row 4j + v, columns n + cs
     if (d.ksplit > 1) {
-        // each K split leaves its fp32 partial tile; the finish kernel (next launch on the
-        // stream) adds them up.  No cross-workgroup traffic inside this kernel, hence no fences.
+        // the finish kernel (next launch on the stream) adds the slices' partial tiles
         float *mine = d.Yacc + (size_t)ks * 16 * N;
+        if (col_ok) {
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int idx = tid + e * sm::WG_THREADS, m = idx / sm::COLS, col = n0 + idx % sm::COLS;
-            if (col < N) mine[(size_t)m * N + col] = y[e];
+            for (int v = 0; v < 4; ++v)
+                if (4 * j + v < d.M)
+                    *reinterpret_cast<float4 *>(mine + (size_t)(4 * j + v) * N + n) =
+                        make_float4(yacc[0][v], yacc[1][v], yacc[2][v], yacc[3][v]);
         }
         return;
     }
-    smallm_fwd_epilogue(d, cb, y, Us);
+    smallm_gather_xa(d, Us);
+    if (col_ok) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (4 * j + v < d.M) {
+                const float y[4] = {yacc[0][v], yacc[1][v], yacc[2][v], yacc[3][v]};
+                smallm_store4(d, Us, 4 * j + v, n, y);
+            }
+    }
+    if (cb == 0 && d.XA != nullptr)
+        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
 }
 
-// Sum of the K splits' partial tiles, then the common epilogue.  One workgroup per column block.
+// Sum of the K slices' partial tiles, then the adapter term and the bfloat16 store.  One
+// workgroup per 64 columns: thread t owns row t / 16, columns 4 (t % 16) .. + 3.
 __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(SmallFwdDev d) {
     __shared__ float Us[16 * 64];
-    const int tid = threadIdx.x, cb = blockIdx.x, n0 = cb * sm::COLS, N = d.w.N;
-    float y[2];
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-        const int idx = tid + e * sm::WG_THREADS, m = idx / sm::COLS, col = n0 + idx % sm::COLS;
-        float sum = 0.f;
-        if (col < N)
-            for (int q = 0; q < d.ksplit; ++q) sum += d.Yacc[((size_t)q * 16 + m) * N + col];
-        y[e] = sum;
+    const int tid = threadIdx.x, N = d.w.N;
+    const int m = tid >> 4, col = blockIdx.x * 64 + 4 * (tid & 15);
+    float y[4] = {0.f, 0.f, 0.f, 0.f};
+    if (m < d.M && col < N) {
+        for (int q = 0; q < d.ksplit; ++q) {
+            const float4 v = *reinterpret_cast<const float4 *>(d.Yacc + ((size_t)q * 16 + m) * N + col);
+            y[0] += v.x; y[1] += v.y; y[2] += v.z; y[3] += v.w;
+        }
     }
-    smallm_fwd_epilogue(d, cb, y, Us);
+    smallm_gather_xa(d, Us);
+    if (m < d.M && col < N) smallm_store4(d, Us, m, col, y);
+    if (blockIdx.x == 0 && d.XA != nullptr)
+        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
 }
+
+namespace {
+// K slices for a product with contraction length Kc (groups of `group`) and Nout outputs:
+// enough workgroups to fill the chip, slices of whole groups that fit the LDS, at most
+// MAX_KSPLIT.  Returns 0 when no such split exists.
+int pick_ksplit(int Kc, int Nout, int group) {
+    if (group > sm::MAX_RANGE) return 0;
+    const int n_groups = Kc / group;
+    const int gmax = sm::MAX_RANGE / group;                    // groups per slice that fit the LDS
+    const int need = (n_groups + gmax - 1) / gmax;
+    const int col_blocks = (Nout + sm::BCOLS - 1) / sm::BCOLS;
+    int ksplit = (512 + col_blocks - 1) / col_blocks;
+    if (ksplit < need) ksplit = need;
+    if (ksplit > n_groups) ksplit = n_groups;
+    if (ksplit > sm::MAX_KSPLIT) ksplit = sm::MAX_KSPLIT;
+    if (ksplit < need) return 0;
+    // every slice holds at most ceil(n_groups / ksplit) groups
+    if ((long)((n_groups + ksplit - 1) / ksplit) * group > sm::MAX_RANGE) return 0;
+    return ksplit;
+}
+// upper bound of pick_ksplit over all group sizes (for the workspace query)
+int ksplit_bound(int Kc, int Nout) {
+    const int col_blocks = (Nout + sm::BCOLS - 1) / sm::BCOLS;
+    int b = (512 + col_blocks - 1) / col_blocks;
+    const int need = (Kc + 1023) / 1024;
+    if (b < need) b = need;
+    if (b > sm::MAX_KSPLIT) b = sm::MAX_KSPLIT;
+    return b;
+}
+}  // namespace
 
 bool smallm_fwd_supported(const LayerView &w, int M) {
     if (M > 16) return false;
     const int kstep = w.bits == 4 ? 32 : (w.bits == 2 ? 64 : 128);
-    return w.group % kstep == 0 && w.K % sm::PREP_K == 0 && w.N >= 2;
+    return w.group % kstep == 0 && w.K % sm::PREP_K == 0 && pick_ksplit(w.K, w.N, w.group) > 0;
 }
 
 namespace {
@@ -447,13 +525,24 @@ SmallWs small_ws(int K, int N, int r) {
     size_t off = 0;
     l.xp = off;      off += al((size_t)16 * kmax * 2);
     l.upart = off;   off += al(((kmax + sm::PREP_K - 1) / sm::PREP_K) * 16 * (size_t)(r > 0 ? r : 1) * 4);
-    l.yacc = off;    off += al((size_t)sm::MAX_KSPLIT * 16 * kmax * 4);
+    const size_t yf = (size_t)ksplit_bound(K, N) * 16 * N, yb = (size_t)ksplit_bound(N, K) * 16 * K;
+    l.yacc = off;    off += al((yf > yb ? yf : yb) * 4);
     l.total = off;
     return l;
 }
 }  // namespace
 
 size_t smallm_ws_bytes(int K, int N, int r) { return small_ws(K, N, r).total; }
+
+template <int BITS>
+static hipError_t launch_fwd_bits(const SmallFwdDev &d, int col_blocks, size_t lds_bytes, hipStream_t stream) {
+    auto kern = smallm_fwd_kernel<BITS>;
+    static bool configured[64] = {};
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
+    if (e != hipSuccess) return e;
+    kern<<<col_blocks * d.ksplit, sm::WG_THREADS, lds_bytes, stream>>>(d);
+    return hipGetLastError();
+}
 
 hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     const int K = a.w.K, N = a.w.N;
@@ -463,14 +552,9 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     float *Upart = reinterpret_cast<float *>(ws + l.upart);
     float *Yacc = reinterpret_cast<float *>(ws + l.yacc);
     const int n_kparts = K / sm::PREP_K;
-    const int col_blocks = (N + sm::COLS - 1) / sm::COLS;
-
-    // enough workgroups (4 waves each) for ~4 per CU; a split never gets less than one group per wave
-    int ksplit = (1024 + col_blocks - 1) / col_blocks;
-    const int max_split = (K / a.w.group) / sm::WG_WAVES;
-    if (ksplit > max_split) ksplit = max_split;
-    if (ksplit > sm::MAX_KSPLIT) ksplit = sm::MAX_KSPLIT;
-    if (ksplit < 1) ksplit = 1;
+    const int col_blocks = (N + sm::BCOLS - 1) / sm::BCOLS;
+    const int ksplit = pick_ksplit(K, N, a.w.group);
+    if (ksplit < 1) return hipErrorInvalidValue;     // callers check smallm_fwd_supported first
 
     prof_before("smallm_prep_fwd", stream);
     if (a.r <= 8)
@@ -496,17 +580,19 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     d.Y = a.out;
     d.XA = a.P_out;
     d.Yacc = Yacc;
+    // LDS for the largest slice: ceil(groups / ksplit) groups of 32 bytes per contraction element
+    const int n_groups = K / a.w.group;
+    const size_t lds_bytes = (size_t)((n_groups + ksplit - 1) / ksplit) * a.w.group * 32;
     prof_before("stream_fwd", stream);
     switch (a.w.bits) {
-        case 2: smallm_fwd_kernel<2><<<col_blocks * ksplit, sm::WG_THREADS, 0, stream>>>(d); break;
-        case 3: smallm_fwd_kernel<3><<<col_blocks * ksplit, sm::WG_THREADS, 0, stream>>>(d); break;
-        default: smallm_fwd_kernel<4><<<col_blocks * ksplit, sm::WG_THREADS, 0, stream>>>(d); break;
+        case 2: e = launch_fwd_bits<2>(d, col_blocks, lds_bytes, stream); break;
+        case 3: e = launch_fwd_bits<3>(d, col_blocks, lds_bytes, stream); break;
+        default: e = launch_fwd_bits<4>(d, col_blocks, lds_bytes, stream); break;
     }
     prof_after(stream);
-    e = hipGetLastError();
     if (e != hipSuccess || ksplit == 1) return e;
     prof_before("stream_fwd_finish", stream);
-    smallm_fwd_finish_kernel<<<col_blocks, sm::WG_THREADS, 0, stream>>>(d);
+    smallm_fwd_finish_kernel<<<(N + 63) / 64, sm::WG_THREADS, 0, stream>>>(d);
     prof_after(stream);
     return hipGetLastError();
 }
