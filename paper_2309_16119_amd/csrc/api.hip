@@ -214,6 +214,14 @@ int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M,
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
+    if (mlr::smallm_bwd_supported(view_of(w), M)) {
+        mlr::SmallArgs sa{};
+        sa.w = view_of(w);
+        sa.act = dY; sa.M = M; sa.out = dX;
+        sa.A = A; sa.B = B; sa.r = r; sa.lora_scale = lora_scale;
+        sa.P_out = dYBt; sa.ws = ws;
+        return hip_status(mlr::launch_smallm_bwd(sa, st));
+    }
     mlr::GemmArgs g{};
     g.w = view_of(w);
     g.backward = true;

@@ -212,8 +212,7 @@ __global__ __launch_bounds__(256) void smallm_prep_fwd_kernel(const uint16_t *__
 // scales and zeros are loaded DEPTH steps ahead by loads issued from assembly and awaited
 // with an exact count; loads past the end of the slice are clamped to its last step, so the
 // number in flight never changes and the loop needs no predicates.  The 16 x 64 fp32 result
-// of a wave is final for the slice: with one slice it goes through the epilogue, else it is
-// stored as a partial tile for the finish kernel.
+// of a wave is final for the slice and is stored as a partial tile for the finish kernel.
 // ---------------------------------------------------------------------------------
 struct SmallFwdDev {
     LayerView w;
@@ -225,7 +224,7 @@ struct SmallFwdDev {
     float lora_scale;
     uint16_t *Y;            // [M][N]
     float *XA;              // [M][r] or NULL
-    float *Yacc;            // [ksplit][16][N] fp32 partial tiles (used when ksplit > 1)
+    float *Yacc;            // [ksplit][16][N] fp32 partial tiles
 };
 
 namespace sm {
@@ -262,25 +261,25 @@ constexpr int BCOLS = WG_WAVES * WCOLS;   // columns per workgroup
 constexpr int MAX_RANGE = 2048;           // contraction elements of one K slice (64 KB of LDS)
 }  // namespace sm
 
-// XA = sum of the prep kernel's partials into Us (16 x r floats in LDS): element t of the tile
+// Sum of a prep kernel's partials [n_parts][16][r] into Us (16 x r floats in LDS): element t of the tile
 // is summed by WG_THREADS / (16 r) threads over interleaved slices of the partials, eight
 // independent loads at a time, and the slices meet through LDS atomics.
-__device__ __forceinline__ void smallm_gather_xa(const SmallFwdDev &d, float *Us) {
+__device__ __forceinline__ void smallm_gather_parts(const float *parts, int n_parts, int r, float *Us) {
     const int tid = threadIdx.x;
-    const int ur = 16 * d.r;
+    const int ur = 16 * r;
     for (int t = tid; t < ur; t += sm::WG_THREADS) Us[t] = 0.f;
     __syncthreads();
-    if (d.r > 0) {
+    if (r > 0) {
         const int slices = sm::WG_THREADS >= ur ? sm::WG_THREADS / ur : 1;
         for (int t = tid; t < slices * ur; t += sm::WG_THREADS) {
             const int mj = t % ur, slice = t / ur;
             float acc8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             int kb = slice;
-            for (; kb + 7 * slices < d.n_kparts; kb += 8 * slices) {
+            for (; kb + 7 * slices < n_parts; kb += 8 * slices) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc8[u] += d.Upart[(size_t)(kb + u * slices) * ur + mj];
+                for (int u = 0; u < 8; ++u) acc8[u] += parts[(size_t)(kb + u * slices) * ur + mj];
             }
-            for (; kb < d.n_kparts; kb += slices) acc8[0] += d.Upart[(size_t)kb * ur + mj];
+            for (; kb < n_parts; kb += slices) acc8[0] += parts[(size_t)kb * ur + mj];
             atomicAdd(&Us[mj], ((acc8[0] + acc8[1]) + (acc8[2] + acc8[3])) + ((acc8[4] + acc8[5]) + (acc8[6] + acc8[7])));
         }
     }
@@ -309,7 +308,6 @@ template <int BITS>
 __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdDev d) {
     using G = sm::Geo<BITS>;
     extern __shared__ __attribute__((aligned(16))) uint4 xs[];   // [chunks of the slice][16 rows]
-    __shared__ float Us[16 * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 15, j = lane >> 4;
     const int N = d.w.N, group = d.w.group;
@@ -431,32 +429,28 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdD
             }
         }
     }
+    // Loads past the end of the slice are still in flight.  Their destination registers must
+    // stay allocated until they have landed: tie every stage after the wait, so that on no path
+    // the compiler hands those registers to other values first.
     sm::wait_vm<0>();
-
-    // D register v of lane (i, j): row 4j + v, columns n + cs
-    if (d.ksplit > 1) {
-        // the finish kernel (next launch on the stream) adds the slices' partial tiles
-        float *mine = d.Yacc + (size_t)ks * 16 * N;
-        if (col_ok) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (4 * j + v < d.M)
-                    *reinterpret_cast<float4 *>(mine + (size_t)(4 * j + v) * N + n) =
-                        make_float4(yacc[0][v], yacc[1][v], yacc[2][v], yacc[3][v]);
-        }
-        return;
+    for (int dd = 0; dd < DEPTH; ++dd) {
+#pragma unroll
+        for (int q = 0; q < G::WORDS; ++q) sm::tie(st[dd].w[q]);
+        sm::tie(st[dd].sc);
+        sm::tie(st[dd].z);
     }
-    smallm_gather_xa(d, Us);
+
+    // D register v of lane (i, j): row 4j + v, columns n + cs.  The finish kernel (next launch
+    // on the stream) adds the slices' partial tiles.
+    float *mine = d.Yacc + (size_t)ks * 16 * N;
     if (col_ok) {
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-            if (4 * j + v < d.M) {
-                const float y[4] = {yacc[0][v], yacc[1][v], yacc[2][v], yacc[3][v]};
-                smallm_store4(d, Us, 4 * j + v, n, y);
-            }
+            if (4 * j + v < d.M)
+                *reinterpret_cast<float4 *>(mine + (size_t)(4 * j + v) * N + n) =
+                    make_float4(yacc[0][v], yacc[1][v], yacc[2][v], yacc[3][v]);
     }
-    if (cb == 0 && d.XA != nullptr)
-        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
 }
 
 // Sum of the K slices' partial tiles, then the adapter term and the bfloat16 store.  One
@@ -472,10 +466,301 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
             y[0] += v.x; y[1] += v.y; y[2] += v.z; y[3] += v.w;
         }
     }
-    smallm_gather_xa(d, Us);
+    smallm_gather_parts(d.Upart, d.n_kparts, d.r, Us);
     if (m < d.M && col < N) smallm_store4(d, Us, m, col, y);
     if (blockIdx.x == 0 && d.XA != nullptr)
         for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
+}
+
+// ---------------------------------------------------------------------------------
+// Backward (input gradient) at M <= 16:  dX[m][k] = sum_n dY[m][n] What[n][k]  (Figure 1,
+// LPLinear.backward, with What never materialized).  With g the group of k,
+//
+//   dX[m][k] = sum_n (dY[m][n] scale[g][n]) q[n][k]  -  sum_n (dY[m][n] scale[g][n]) zero[g][n]
+//
+// so a tile of 128 output columns k inside ONE quantization group (group % 128 == 0) is a
+// plain product of the scaled activations dYs = bf16(dY * scale[g]) with the codes, minus a
+// per-row constant.  Codes enter the matrix cores as 128 + q as in the forward kernel; the
+// zero points as exact bfloat16 in one extra MFMA per step, and one more against ones
+// removes the 128:  dX = D_codes - 128 * D_ones - D_zeros, applied once at the end.
+// Rounding dY * scale to bfloat16 moves the result by at most 2^-9 sum_n |dY| |What|, the
+// same size as the rounding of What in the materialized form.
+//
+// prep: dYp = dY stored [N/8][16][8] (rows >= M zero) and per-128-n partial sums of
+// dYBt = dY B^T.  One workgroup per 128 contraction elements; thread (m, chunk of 8).
+// ---------------------------------------------------------------------------------
+template <int RP>
+__global__ __launch_bounds__(256) void smallm_prep_bwd_kernel(const uint16_t *__restrict__ dY, int M, int N,
+                                                              const float *__restrict__ B, int r,
+                                                              uint16_t *__restrict__ dYp, float *__restrict__ Tpart) {
+    const int t = threadIdx.x, m = t >> 4, ch = t & 15;
+    const int nc = blockIdx.x * sm::PREP_K + ch * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (m < M) v = *reinterpret_cast<const uint4 *>(dY + (size_t)m * N + nc);
+    *reinterpret_cast<uint4 *>(dYp + ((size_t)(nc >> 3) * 16 + m) * 8) = v;
+    if (r <= 0) return;
+    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = (e & 1) ? __uint_as_float(u[e >> 1] & 0xFFFF0000u) : __uint_as_float(u[e >> 1] << 16);
+#pragma unroll
+    for (int jj = 0; jj < RP; ++jj) {
+        float s = 0.f;
+        if (jj < r) {
+            const float4 b0 = *reinterpret_cast<const float4 *>(B + (size_t)jj * N + nc);
+            const float4 b1 = *reinterpret_cast<const float4 *>(B + (size_t)jj * N + nc + 4);
+            s = x[0] * b0.x + x[1] * b0.y + x[2] * b0.z + x[3] * b0.w + x[4] * b1.x + x[5] * b1.y + x[6] * b1.z + x[7] * b1.w;
+        }
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (ch == 0 && jj < r) Tpart[((size_t)blockIdx.x * 16 + m) * r + jj] = s;
+    }
+}
+
+struct SmallBwdDev {
+    LayerView w;
+    const uint16_t *dYp;    // [N/8][16][8]
+    const float *Tpart;     // [N/128][16][r]
+    const float *A;         // [K][r]
+    int M, r, n_parts;
+    int nsplit;             // workgroups that share one 128-column tile (split of N)
+    float lora_scale;
+    uint16_t *dX;           // [M][K]
+    float *T_out;           // dYBt [M][r] or NULL
+    float *acc;             // [nsplit][16][K] fp32 partial tiles
+};
+
+namespace smb {
+constexpr int KT = 128;      // output columns per workgroup: four 32-code blocks
+constexpr int NSTEP = 32;    // contraction elements per step (8 per lane group)
+}
+
+// adapter term and bfloat16 store of 8 adjacent outputs dX[m][k0 .. k0+7]
+__device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const float *Ts, int m, int k0, const float y[8]) {
+    float o[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        float l = 0.f;
+        const float *arow = d.A + (size_t)(k0 + c) * d.r;
+        for (int jj = 0; jj < d.r; ++jj) l = __builtin_fmaf(Ts[m * d.r + jj], arow[jj], l);
+        o[c] = __builtin_fmaf(d.lora_scale, l, y[c]);
+    }
+    uint4 v;
+    v.x = pack_bf16x2(o[0], o[1]);
+    v.y = pack_bf16x2(o[2], o[3]);
+    v.z = pack_bf16x2(o[4], o[5]);
+    v.w = pack_bf16x2(o[6], o[7]);
+    *reinterpret_cast<uint4 *>(d.dX + (size_t)m * d.w.K + k0) = v;
+}
+
+// A workgroup owns 128 output columns k (one quantization group's scales and zeros) and a
+// slice of N; its four waves split the slice and add their results through LDS.  Lane
+// l = 16 j + i: i = 4 u + b picks the 32-code block b of the tile and the 8 codes 8u .. 8u+7
+// of it (MFMA call c handles code 8u + c, so the lane's outputs are 8 adjacent k), j picks
+// 8 adjacent n of the step.  A lane therefore loads, per step, the packed words that hold
+// its 8 codes for 8 adjacent n (32 contiguous bytes per word row).
+template <int BITS>
+__global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdDev d) {
+    extern __shared__ __attribute__((aligned(16))) uint4 ys[];   // [chunks of 8 n of the slice][16 rows]
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 15, j = lane >> 4, b = i & 3, u = i >> 2;
+    const int N = d.w.N, K = d.w.K;
+    const int kb = blockIdx.x / d.nsplit, ns = blockIdx.x % d.nsplit;
+    const int kt = kb * smb::KT;
+    const int n_steps = N / smb::NSTEP;
+    const int S0 = (int)((long)n_steps * ns / d.nsplit), S1 = (int)((long)n_steps * (ns + 1) / d.nsplit);
+    const int W0 = S0 + (int)((long)(S1 - S0) * wave / sm::WG_WAVES);
+    const int W1 = S0 + (int)((long)(S1 - S0) * (wave + 1) / sm::WG_WAVES);
+    const int g = kt / d.w.group;
+
+    // word rows of this lane, relative to the first word row of the tile
+    constexpr int NROWS = BITS == 3 ? 2 : 1;
+    int row0, row1 = 0;
+    uint32_t bitsh = 0;                  // right shift that brings the lane's 8 codes to bit 0
+    if (BITS == 4) row0 = b * 4 + u;
+    else if (BITS == 2) { row0 = b * 2 + (u >> 1); bitsh = 16u * (u & 1); }
+    else {
+        const int lo = (24 * u) >> 5;
+        row0 = b * 3 + lo;
+        row1 = b * 3 + (lo + 1 > 2 ? 2 : lo + 1);
+        bitsh = (24u * u) & 31u;
+    }
+    const uint32_t voff0 = (uint32_t)(((size_t)row0 * N + 8 * j) * 4);
+    const uint32_t voff1 = (uint32_t)(((size_t)row1 * N + 8 * j) * 4);
+    const uint32_t s_voff = 16u * j, z_voff = 8u * j;
+    const uint32_t *wtile = d.w.qweight + (size_t)(kt / 32) * BITS * N;
+    const uint16_t *stile = d.w.scales + (size_t)g * N;
+    const uint8_t *ztile = d.w.zeros + (size_t)g * N;
+
+    constexpr int DEPTH = 4;
+    constexpr int SL = NROWS * 2 + 2;               // loads per stage
+    struct Stage {
+        sm::u32x4 w[NROWS][2];   // 8 adjacent n of each word row
+        sm::u32x4 sc;            // 8 binary16 scales
+        sm::u32x2 z;             // 8 zero points
+    };
+    Stage st[DEPTH];
+    auto issue = [&](Stage &sd, int step) {         // step: any step of the workgroup's slice
+        const uint32_t *wbase = wtile + (size_t)step * smb::NSTEP;
+        sm::ald(sd.w[0][0], wbase, voff0);
+        sm::ald(sd.w[0][1], wbase + 4, voff0);
+        if (NROWS == 2) {
+            sm::ald(sd.w[NROWS - 1][0], wbase, voff1);
+            sm::ald(sd.w[NROWS - 1][1], wbase + 4, voff1);
+        }
+        sm::ald(sd.sc, stile + (size_t)step * smb::NSTEP, s_voff);
+        sm::ald(sd.z, ztile + (size_t)step * smb::NSTEP, z_voff);
+    };
+    auto clamp_step = [&](int s) { return s < S1 ? s : S1 - 1; };
+
+    // the slice of dY goes straight into LDS, 1 KB (one step) per wave and load
+    {
+        const char *src = reinterpret_cast<const char *>(d.dYp) + (size_t)S0 * 1024;
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)ys;
+        for (int q = wave; q < S1 - S0; q += sm::WG_WAVES) sm::ald_lds(src + (size_t)q * 1024, (uint32_t)lane * 16u, lds0 + (uint32_t)q * 1024u);
+    }
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd) issue(st[dd], clamp_step(W0 + dd));
+    sm::wait_vm<DEPTH * SL>();
+    __syncthreads();
+
+    f32x4 acc[8], accz, accs;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) acc[c][v] = 0.f;
+        accz[v] = 0.f;
+        accs[v] = 0.f;
+    }
+    const uint32_t ones4[4] = {sm::ONES, sm::ONES, sm::ONES, sm::ONES};
+    const bf16x8 ones = sm::as_bf16x8(ones4);
+    const uint32_t fmask = sm::opaque_sgpr(BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x00070007u));
+    const uint32_t magic = sm::opaque_vgpr(sm::MAGIC);
+
+    auto compute = [&](Stage &sd, int srel) {       // srel: step relative to S0
+        // A operand: dY[i][8 n] * scale[g][8 n], rounded to bfloat16
+        const uint4 yv = ys[((size_t)srel * 4 + j) * 16 + i];
+        const uint32_t yw[4] = {yv.x, yv.y, yv.z, yv.w};
+        uint32_t areg[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const float y0 = __uint_as_float(yw[p] << 16), y1 = __uint_as_float(yw[p] & 0xFFFF0000u);
+            const float s0 = half_bits_to_float((uint16_t)(sd.sc[p] & 0xFFFFu)), s1 = half_bits_to_float((uint16_t)(sd.sc[p] >> 16));
+            areg[p] = pack_bf16x2(y0 * s0, y1 * s1);
+        }
+        const bf16x8 a = sm::as_bf16x8(areg);
+        // the lane's 8 codes of each of its 8 n, at bit 0 of ch[e]
+        uint32_t ch[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t lo = sd.w[0][e >> 2][e & 3];
+            if (BITS == 4) ch[e] = lo;
+            else if (BITS == 2) ch[e] = lo >> bitsh;
+            else ch[e] = __builtin_amdgcn_alignbit(sd.w[NROWS - 1][e >> 2][e & 3], lo, bitsh);
+        }
+        // pairs of n side by side: low halves (bits 0-15) and, where codes reach further, a second view
+        uint32_t plo[4], phi[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            plo[p] = __builtin_amdgcn_perm(ch[2 * p + 1], ch[2 * p], 0x05040100u);
+            if (BITS == 4) phi[p] = __builtin_amdgcn_perm(ch[2 * p + 1], ch[2 * p], 0x07060302u);        // bits 16-31
+            else if (BITS == 3) phi[p] = __builtin_amdgcn_perm(ch[2 * p + 1], ch[2 * p], 0x06050201u);   // bits 8-23
+            else phi[p] = 0;
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            uint32_t o[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                uint32_t x;
+                if (BITS == 4) x = c < 4 ? plo[p] >> (4 * c) : phi[p] >> (4 * (c - 4));
+                else if (BITS == 2) x = plo[p] >> (2 * c);
+                else x = c < 5 ? plo[p] >> (3 * c) : phi[p] >> (3 * c - 8);
+                o[p] = sm::and_or(x, fmask, magic);
+            }
+            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), acc[c], 0, 0, 0);
+        }
+        // zero points as exact bfloat16
+        uint32_t zo[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const uint32_t zw = sd.z[p >> 1] >> (16 * (p & 1));
+            zo[p] = pack_bf16x2((float)(zw & 0xFFu), (float)((zw >> 8) & 0xFFu));
+        }
+        accz = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(zo), accz, 0, 0, 0);
+        accs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, accs, 0, 0, 0);
+    };
+
+    for (int s = W0; s < W1; s += DEPTH) {
+#pragma unroll
+        for (int dd = 0; dd < DEPTH; ++dd) {
+            if (s + dd < W1) {
+                sm::wait_vm<(DEPTH - 1) * SL>();
+#pragma unroll
+                for (int rr = 0; rr < NROWS; ++rr) { sm::tie(st[dd].w[rr][0]); sm::tie(st[dd].w[rr][1]); }
+                sm::tie(st[dd].sc);
+                sm::tie(st[dd].z);
+                compute(st[dd], s + dd - S0);
+                issue(st[dd], clamp_step(s + dd + DEPTH));
+            }
+        }
+    }
+    // loads past the end of the slice are still in flight: keep their registers allocated
+    // until they have landed (see the forward kernel)
+    sm::wait_vm<0>();
+#pragma unroll
+    for (int dd = 0; dd < DEPTH; ++dd) {
+#pragma unroll
+        for (int rr = 0; rr < NROWS; ++rr) { sm::tie(st[dd].w[rr][0]); sm::tie(st[dd].w[rr][1]); }
+        sm::tie(st[dd].sc);
+        sm::tie(st[dd].z);
+    }
+    __syncthreads();                                 // every wave is done with the dY slice
+
+    // the four waves' tiles meet in LDS: red[wave][c * 4 + v][lane]
+    float *red = reinterpret_cast<float *>(ys);
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            red[(wave * 32 + c * 4 + v) * 64 + lane] = acc[c][v] - 128.0f * accs[v] - accz[v];
+    __syncthreads();
+    // thread (wave, lane) finishes D register v = wave of lane's position: row 4j + wave, 8 adjacent k
+    float y[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        float sum = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < sm::WG_WAVES; ++wv) sum += red[(wv * 32 + c * 4 + wave) * 64 + lane];
+        y[c] = sum;
+    }
+    const int m = 4 * j + wave, k0 = kt + 32 * b + 8 * u;
+    if (m < d.M) {
+        float *dst = d.acc + ((size_t)ns * 16 + m) * K + k0;
+        *reinterpret_cast<float4 *>(dst) = make_float4(y[0], y[1], y[2], y[3]);
+        *reinterpret_cast<float4 *>(dst + 4) = make_float4(y[4], y[5], y[6], y[7]);
+    }
+}
+
+// Sum of the N slices' partial tiles, adapter term, bfloat16 store.  One workgroup per 128
+// columns: thread t owns row t / 16, columns 8 (t % 16) .. + 7.
+__global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(SmallBwdDev d) {
+    __shared__ float Ts[16 * 64];
+    const int tid = threadIdx.x, K = d.w.K;
+    const int m = tid >> 4, k0 = blockIdx.x * 128 + 8 * (tid & 15);
+    float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (m < d.M) {
+        for (int q = 0; q < d.nsplit; ++q) {
+            const float *src = d.acc + ((size_t)q * 16 + m) * K + k0;
+            const float4 v0 = *reinterpret_cast<const float4 *>(src), v1 = *reinterpret_cast<const float4 *>(src + 4);
+            y[0] += v0.x; y[1] += v0.y; y[2] += v0.z; y[3] += v0.w;
+            y[4] += v1.x; y[5] += v1.y; y[6] += v1.z; y[7] += v1.w;
+        }
+    }
+    smallm_gather_parts(d.Tpart, d.n_parts, d.r, Ts);
+    if (m < d.M) smallm_bwd_store8(d, Ts, m, k0, y);
+    if (blockIdx.x == 0 && d.T_out != nullptr)
+        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.T_out[t] = Ts[t];
 }
 
 namespace {
@@ -506,7 +791,25 @@ int ksplit_bound(int Kc, int Nout) {
     if (b > sm::MAX_KSPLIT) b = sm::MAX_KSPLIT;
     return b;
 }
+// N slices of the backward product (contraction length N, K outputs in tiles of 128)
+int pick_nsplit(int N, int K) {
+    const int n_steps = N / smb::NSTEP;
+    const int k_blocks = K / smb::KT;
+    const int max_steps = sm::MAX_RANGE / smb::NSTEP;          // steps of one slice that fit the LDS
+    const int need = (n_steps + max_steps - 1) / max_steps;
+    int nsplit = (512 + k_blocks - 1) / k_blocks;
+    if (nsplit < need) nsplit = need;
+    if (nsplit > n_steps) nsplit = n_steps;
+    if (nsplit > sm::MAX_KSPLIT) nsplit = sm::MAX_KSPLIT;
+    if (nsplit < need || nsplit < 1) return 0;
+    return nsplit;
+}
 }  // namespace
+
+bool smallm_bwd_supported(const LayerView &w, int M) {
+    if (M > 16) return false;
+    return w.group % smb::KT == 0 && w.N % sm::PREP_K == 0 && pick_nsplit(w.N, w.K) > 0;
+}
 
 bool smallm_fwd_supported(const LayerView &w, int M) {
     if (M > 16) return false;
@@ -525,7 +828,7 @@ SmallWs small_ws(int K, int N, int r) {
     size_t off = 0;
     l.xp = off;      off += al((size_t)16 * kmax * 2);
     l.upart = off;   off += al(((kmax + sm::PREP_K - 1) / sm::PREP_K) * 16 * (size_t)(r > 0 ? r : 1) * 4);
-    const size_t yf = (size_t)ksplit_bound(K, N) * 16 * N, yb = (size_t)ksplit_bound(N, K) * 16 * K;
+    const size_t yf = (size_t)ksplit_bound(K, N) * 16 * N, yb = (size_t)sm::MAX_KSPLIT * 16 * K;
     l.yacc = off;    off += al((yf > yb ? yf : yb) * 4);
     l.total = off;
     return l;
@@ -590,9 +893,69 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
         default: e = launch_fwd_bits<4>(d, col_blocks, lds_bytes, stream); break;
     }
     prof_after(stream);
-    if (e != hipSuccess || ksplit == 1) return e;
+    if (e != hipSuccess) return e;
     prof_before("stream_fwd_finish", stream);
     smallm_fwd_finish_kernel<<<(N + 63) / 64, sm::WG_THREADS, 0, stream>>>(d);
+    prof_after(stream);
+    return hipGetLastError();
+}
+
+template <int BITS>
+static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, size_t lds_bytes, hipStream_t stream) {
+    auto kern = smallm_bwd_kernel<BITS>;
+    static bool configured[64] = {};
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
+    if (e != hipSuccess) return e;
+    kern<<<k_blocks * d.nsplit, sm::WG_THREADS, lds_bytes, stream>>>(d);
+    return hipGetLastError();
+}
+
+hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
+    const int K = a.w.K, N = a.w.N;
+    const SmallWs l = small_ws(K, N, a.r);
+    char *ws = static_cast<char *>(a.ws);
+    uint16_t *dYp = reinterpret_cast<uint16_t *>(ws + l.xp);
+    float *Tpart = reinterpret_cast<float *>(ws + l.upart);
+    const int n_parts = N / sm::PREP_K;
+    const int k_blocks = K / smb::KT;
+    const int nsplit = pick_nsplit(N, K);
+    if (nsplit < 1) return hipErrorInvalidValue;     // callers check smallm_bwd_supported first
+
+    prof_before("smallm_prep_bwd", stream);
+    if (a.r <= 8) smallm_prep_bwd_kernel<8><<<n_parts, 256, 0, stream>>>(a.act, a.M, N, a.B, a.r, dYp, Tpart);
+    else if (a.r <= 16) smallm_prep_bwd_kernel<16><<<n_parts, 256, 0, stream>>>(a.act, a.M, N, a.B, a.r, dYp, Tpart);
+    else smallm_prep_bwd_kernel<64><<<n_parts, 256, 0, stream>>>(a.act, a.M, N, a.B, a.r, dYp, Tpart);
+    prof_after(stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    SmallBwdDev d;
+    d.w = a.w;
+    d.dYp = dYp;
+    d.Tpart = Tpart;
+    d.A = a.A;
+    d.M = a.M;
+    d.r = a.r;
+    d.n_parts = n_parts;
+    d.nsplit = nsplit;
+    d.lora_scale = a.lora_scale;
+    d.dX = a.out;
+    d.T_out = a.P_out;
+    d.acc = reinterpret_cast<float *>(ws + l.yacc);
+    // LDS: the largest slice of dY (1 KB per step), and at least the 32 KB of the wave reduction
+    const int n_steps = N / smb::NSTEP;
+    size_t lds_bytes = (size_t)((n_steps + nsplit - 1) / nsplit) * 1024;
+    if (lds_bytes < 32 * 1024) lds_bytes = 32 * 1024;
+    prof_before("stream_bwd", stream);
+    switch (a.w.bits) {
+        case 2: e = launch_bwd_bits<2>(d, k_blocks, lds_bytes, stream); break;
+        case 3: e = launch_bwd_bits<3>(d, k_blocks, lds_bytes, stream); break;
+        default: e = launch_bwd_bits<4>(d, k_blocks, lds_bytes, stream); break;
+    }
+    prof_after(stream);
+    if (e != hipSuccess) return e;
+    prof_before("stream_bwd_finish", stream);
+    smallm_bwd_finish_kernel<<<k_blocks, sm::WG_THREADS, 0, stream>>>(d);
     prof_after(stream);
     return hipGetLastError();
 }
