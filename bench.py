@@ -28,6 +28,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor peak
 ROTATE_BYTES = 512 << 20        # distinct packed weights touched before one is reused
+COPY_CAL_BYTES = 1 << 30        # size of the copy that calibrates the rocprofv3 byte counters
 
 
 def parse_args():
@@ -40,6 +41,10 @@ def parse_args():
     p.add_argument("--no-extra", action="store_true", help="skip the additional workloads")
     p.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    p.add_argument("--no-traffic", action="store_true",
+                   help="skip the two rocprofv3 --pmc child runs that measure the HBM traffic of the dominant kernel")
+    p.add_argument("--pmc-child", action="store_true",
+                   help="(internal) run a few eager steps and a plain copy of known size, print nothing")
     return p.parse_args()
 
 
@@ -165,8 +170,11 @@ def roofline_of(cfg, prof: dict) -> dict:
         return {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                 "avg_kernel_us": round(avg_s * 1e6, 2), "launches": launches}
-    if name.startswith("gemm_") or name.startswith("stream_"):
+    if name.startswith("gemm_") or name in ("stream_fwd", "stream_bwd"):
         nbytes = float(cfg.packed_weight_bytes)            # one pass over codes + scales + zeros
+    elif name.startswith("stream_"):
+        # finish kernels: the partial tiles (not known here) -- report against the output only
+        nbytes = 2.0 * M * max(K, N)
     else:
         # adapter kernels stream the activations once
         nbytes = 2.0 * M * (K if ("down" in name) else max(K, N))
@@ -199,12 +207,87 @@ def cpu_baseline(host_layer, cfg) -> dict:
             "sample": "one full step (fwd + bwd_input + bwd_lora) of %s, all %d tokens" % (cfg.name, cfg.M)}
 
 
+def rocprof_kernel_pattern(lib_name: str) -> str:
+    """Substring of the rocprofv3 kernel name that belongs to a library profile name."""
+    if lib_name.startswith("gemm_fwd_256x256"):
+        return "gemm_big_kernel<%d, false"
+    if lib_name.startswith("gemm_bwd_256x256"):
+        return "gemm_big_kernel<%d, true"
+    if lib_name.startswith("gemm_fwd"):
+        return "gemm_tile_kernel<%d, false"
+    if lib_name.startswith("gemm_bwd"):
+        return "gemm_tile_kernel<%d, true"
+    return {"stream_fwd": "smallm_fwd_kernel<%d", "stream_bwd": "smallm_bwd_kernel<%d",
+            "stream_fwd_finish": "smallm_fwd_finish_kernel", "stream_bwd_finish": "smallm_bwd_finish_kernel",
+            "smallm_prep_fwd": "smallm_prep_fwd_kernel", "smallm_prep_bwd": "smallm_prep_bwd_kernel",
+            "lora_down": "lora_down_kernel", "lora_grad": "lora_grad_partial_kernel",
+            "lora_grad_reduce": "lora_grad_reduce_kernel"}.get(lib_name, lib_name)
+
+
+def pmc_child_run(counter: str, workload_args: list) -> dict:
+    """Run `rocprofv3 --pmc <counter>` on a child `bench.py --pmc-child` and return
+    {kernel name: mean counter value per dispatch}.  The child is started before this process
+    touches the GPU.  Any failure returns {}."""
+    import csv
+    import glob
+    import shutil
+    import subprocess
+    import tempfile
+
+    exe = shutil.which("rocprofv3")
+    if exe is None:
+        return {}
+    out = tempfile.mkdtemp(prefix="modulora_pmc_", dir="/tmp")
+    env = dict(os.environ, TMPDIR="/tmp")
+    cmd = [exe, "--pmc", counter, "--output-format", "csv", "-d", out, "-o", "pmc", "--", sys.executable,
+           os.path.abspath(__file__), "--pmc-child", "--steps", "4", "--warmup", "2"] + workload_args
+    try:
+        subprocess.run(cmd, cwd="/tmp", env=env, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL, timeout=240)
+        files = glob.glob(os.path.join(out, "**", "*counter_collection.csv"), recursive=True)
+        acc = {}
+        for f in files:
+            with open(f) as fh:
+                for row in csv.DictReader(fh):
+                    if row.get("Counter_Name") != counter:
+                        continue
+                    acc.setdefault(row["Kernel_Name"], []).append(float(row["Counter_Value"]))
+        return {k: sum(v) / len(v) for k, v in acc.items()}
+    except Exception:
+        return {}
+    finally:
+        shutil.rmtree(out, ignore_errors=True)
+
+
+def traffic_of(kernel_pattern: str, fetch: dict, write: dict):
+    """HBM bytes per launch of the kernel matching `kernel_pattern`: FETCH_SIZE + WRITE_SIZE, each
+    scaled by the reading of the plain copy kernel (COPY_CAL_BYTES read, COPY_CAL_BYTES written)."""
+    def pick(d, pat):
+        hits = [v for k, v in d.items() if pat in k]
+        return max(hits) if hits else None
+    cal_f, cal_w = pick(fetch, "CUDAFunctorOnSelf_add"), pick(write, "CUDAFunctorOnSelf_add")
+    if cal_f is None or cal_w is None:     # name of the torch.add kernel, else the largest elementwise one
+        cal_f = cal_f or pick(fetch, "elementwise")
+        cal_w = cal_w or pick(write, "elementwise")
+    f, w = pick(fetch, kernel_pattern), pick(write, kernel_pattern)
+    if not cal_f or not cal_w or f is None or w is None:
+        return None
+    return {"read_bytes": round(f * COPY_CAL_BYTES / cal_f), "write_bytes": round(w * COPY_CAL_BYTES / cal_w),
+            "bytes": round(f * COPY_CAL_BYTES / cal_f + w * COPY_CAL_BYTES / cal_w),
+            "copy_kernel_scale": {"FETCH_SIZE_per_GiB": round(cal_f, 1), "WRITE_SIZE_per_GiB": round(cal_w, 1)}}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding). "
               "Run with --gpus 1." % args.gpus, file=sys.stderr)
         sys.exit(2)
+    fetch = write = {}
+    if not (args.no_traffic or args.pmc_child):
+        # before this process touches the GPU: two counter runs in child processes
+        wargs = ["--workload", args.workload] + (["--M", str(args.M)] if args.M is not None else [])
+        fetch = pmc_child_run("FETCH_SIZE", wargs)
+        write = pmc_child_run("WRITE_SIZE", wargs) if fetch else {}
     import torch
 
     from paper_2309_16119_amd import synth
@@ -215,6 +298,22 @@ def main():
     if args.M is not None:
         cfg = cfg.with_M(args.M)
     use_graph = not args.no_graph
+
+    if args.pmc_child:
+        # a plain elementwise copy of known size: its FETCH_SIZE / WRITE_SIZE readings turn the
+        # counters of the other kernels into bytes
+        src = torch.ones(COPY_CAL_BYTES // 4, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
+        wl = Workload(cfg, synth.make_layer(cfg))
+        for i in range(args.warmup + args.steps):
+            wl.step(i)
+        torch.cuda.synchronize()
+        return
 
     host_layer = synth.make_layer(cfg)
     wl = Workload(cfg, host_layer)
@@ -233,6 +332,9 @@ def main():
         "roofline": roofline_of(cfg, prof),
         "kernel_us": per_call_ms(prof),
     }
+    if fetch and write:
+        pat = rocprof_kernel_pattern(line["roofline"]["kernel"])
+        line["roofline"]["traffic"] = traffic_of(pat % cfg.bits if "%d" in pat else pat, fetch, write)
     if not args.no_cpu:
         line["cpu_baseline"] = cpu_baseline(host_layer, cfg)
     del wl, host_layer
@@ -240,7 +342,8 @@ def main():
 
     if not args.no_extra:
         extra = []
-        others = [synth.CONFIGS["c3_7b_gate_up"], synth.CONFIGS["c5_65b_attn"].with_M(16),
+        others = [synth.CONFIGS["c3_7b_gate_up"], synth.CONFIGS["c5_65b_up"].with_M(4096),
+                  synth.CONFIGS["c5_65b_attn"].with_M(16), synth.CONFIGS["c5_65b_up"].with_M(16),
                   synth.CONFIGS["c5_65b_attn"].with_M(1)]
         for ocfg in others:
             if ocfg.name == cfg.name:
@@ -253,7 +356,7 @@ def main():
                      "tflops": round(ocfg.flops_fwd_bwd / (ms2 * 1e-3) / 1e12, 3),
                      "roofline": roofline_of(ocfg, prof2), "kernel_us": per_call_ms(prof2)}
             if ocfg.M <= 16:
-                gemm = {k: v for k, v in prof2.items() if k.startswith(("gemm_", "stream_"))}
+                gemm = {k: v for k, v in prof2.items() if k.startswith("gemm_") or k in ("stream_fwd", "stream_bwd")}
                 entry["packed_weight_GBps"] = {
                     k: round(ocfg.packed_weight_bytes / (v[1] / v[0] * 1e-3) / 1e9, 1) for k, v in gemm.items()}
             extra.append(entry)
