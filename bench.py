@@ -55,27 +55,24 @@ class Workload:
         import numpy as np
         import torch
         from paper_2309_16119_amd import binding as b
+        from paper_2309_16119_amd import synth as synth_mod
 
         self.cfg, self.b, self.torch = cfg, b, torch
         K, N, M, r, bits, g = cfg.K, cfg.N, cfg.M, cfg.r, cfg.bits, cfg.group
         G = K // g
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(seed)
         n_copies = max(1, math.ceil(ROTATE_BYTES / cfg.packed_weight_bytes))
         self.n_copies = n_copies
         self.weights = []
+        first = None
         for i in range(n_copies):
             if i == 0 and host_layer is not None:
                 w = b.QWeight.from_numpy(host_layer["qweight"], host_layer["scales"], host_layer["zeros"],
                                          K, N, bits, g)
             else:
-                # uniformly random words are exactly uniformly random codes
-                q = torch.randint(-2 ** 31, 2 ** 31, (K * bits // 32, N), dtype=torch.int64, device="cuda",
-                                  generator=gen).to(torch.int32)
-                sc = (torch.rand((G, N), device="cuda", generator=gen) * (cfg.scale_hi - cfg.scale_lo)
-                      + cfg.scale_lo).to(torch.float16)
-                z = torch.randint(0, 1 << bits, (G, N), dtype=torch.uint8, device="cuda", generator=gen)
-                w = b.QWeight(q, sc, z, K, N, bits, g)
+                # the same distributions, drawn on the device (uniform words = uniform codes)
+                T = synth_mod.make_layer_torch(cfg, "cuda", seed=seed + 1000 + i)
+                first = first or T
+                w = b.QWeight(T["qweight"], T["scales"], T["zeros"], K, N, bits, g)
             self.weights.append(w)
         if host_layer is not None:
             def dev16(a):
@@ -83,10 +80,7 @@ class Workload:
             self.X, self.dY = dev16(host_layer["X"]), dev16(host_layer["dY"])
             self.A, self.B = torch.from_numpy(host_layer["A"]).cuda(), torch.from_numpy(host_layer["B"]).cuda()
         else:
-            self.X = torch.randn((M, K), device="cuda", generator=gen).to(torch.bfloat16)
-            self.dY = torch.randn((M, N), device="cuda", generator=gen).to(torch.bfloat16)
-            self.A = torch.randn((K, r), device="cuda", generator=gen) * 0.02
-            self.B = torch.randn((r, N), device="cuda", generator=gen) * 0.02
+            self.X, self.dY, self.A, self.B = first["X"], first["dY"], first["A"], first["B"]
         self.Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
         self.dX = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
         self.XA = torch.empty((M, r), dtype=torch.float32, device="cuda")

@@ -135,3 +135,28 @@ def make_layer(cfg: LayerConfig, *, zero_B: bool = False, zero_A: bool = False) 
         codes=codes, qweight=pack_codes(codes, b), zeros=zeros, scales=scales,
         X=X, dY=dY, A=np.ascontiguousarray(A), B=np.ascontiguousarray(B),
     )
+
+
+def make_layer_torch(cfg: LayerConfig, device: str = "cuda", seed: int = 0) -> dict:
+    """The same distributions as make_layer, drawn with torch's generator on `device` (fast at
+    the full benchmark sizes, where the bit-by-bit packer would take minutes).  Uniformly random
+    32-bit words are exactly uniformly random codes.  Returns torch tensors: qweight int32,
+    scales float16, zeros uint8, X / dY bfloat16, A / B float32."""
+    import torch
+
+    K, N, M, r, bits, g = cfg.K, cfg.N, cfg.M, cfg.r, cfg.bits, cfg.group
+    G = K // g
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    q = torch.randint(-2 ** 31, 2 ** 31, (K * bits // 32, N), dtype=torch.int64, device=device,
+                      generator=gen).to(torch.int32)
+    sc = (torch.rand((G, N), device=device, generator=gen) * (cfg.scale_hi - cfg.scale_lo)
+          + cfg.scale_lo).to(torch.float16)
+    z = torch.randint(0, 1 << bits, (G, N), dtype=torch.uint8, device=device, generator=gen)
+    out = {"qweight": q, "scales": sc, "zeros": z, "K": K, "N": N, "M": M, "r": r, "bits": bits, "group": g,
+           "lora_scale": cfg.lora_scale}
+    out["X"] = torch.randn((M, K), device=device, generator=gen).to(torch.bfloat16)
+    out["dY"] = torch.randn((M, N), device=device, generator=gen).to(torch.bfloat16)
+    out["A"] = torch.randn((K, max(r, 1)), device=device, generator=gen)[:, :r].contiguous() * 0.02
+    out["B"] = torch.randn((max(r, 1), N), device=device, generator=gen)[:r].contiguous() * 0.02
+    return out
