@@ -218,6 +218,7 @@ struct SmallFwdDev {
     LayerView w;
     const uint16_t *Xp;     // [K/8][16][8] operand order
     const float *Upart;     // [K/128][16][r]
+    float *Ufinal;          // [16][r]: XA, summed by the reducer block of the stream kernel
     const float *B;         // [r][N]
     int M, r, n_kparts;
     int ksplit;             // workgroups that share one column block (split of the groups along K)
@@ -308,10 +309,21 @@ template <int BITS>
 __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdDev d) {
     using G = sm::Geo<BITS>;
     extern __shared__ __attribute__((aligned(16))) uint4 xs[];   // [chunks of the slice][16 rows]
+    __shared__ float Us[16 * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (blockIdx.x == 0) {
+        // reducer block: XA = sum of the prep kernel's partials, for the finish kernel and the
+        // caller; it runs beside the streaming blocks, so its latency-bound gather costs nothing
+        smallm_gather_parts(d.Upart, d.n_kparts, d.r, Us);
+        for (int t = tid; t < 16 * d.r; t += sm::WG_THREADS) d.Ufinal[t] = Us[t];
+        if (d.XA != nullptr)
+            for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
+        return;
+    }
+    const int bid = blockIdx.x - 1;
     const int i = lane & 15, j = lane >> 4;
     const int N = d.w.N, group = d.w.group;
-    const int cb = blockIdx.x / d.ksplit, ks = blockIdx.x % d.ksplit;   // column block, K slice
+    const int cb = bid / d.ksplit, ks = bid % d.ksplit;   // column block, K slice
     const int nw = cb * sm::BCOLS + wave * sm::WCOLS;   // first column of the wave
     int n = nw + 4 * i;
     const bool col_ok = n < N;                      // N is a multiple of 8: all four columns or none
@@ -466,10 +478,9 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
             y[0] += v.x; y[1] += v.y; y[2] += v.z; y[3] += v.w;
         }
     }
-    smallm_gather_parts(d.Upart, d.n_kparts, d.r, Us);
+    for (int t = tid; t < 16 * d.r; t += sm::WG_THREADS) Us[t] = d.Ufinal[t];
+    __syncthreads();
     if (m < d.M && col < N) smallm_store4(d, Us, m, col, y);
-    if (blockIdx.x == 0 && d.XA != nullptr)
-        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
 }
 
 // ---------------------------------------------------------------------------------
@@ -521,6 +532,7 @@ struct SmallBwdDev {
     LayerView w;
     const uint16_t *dYp;    // [N/8][16][8]
     const float *Tpart;     // [N/128][16][r]
+    float *Tfinal;          // [16][r]: dYBt, summed by the reducer block of the stream kernel
     const float *A;         // [K][r]
     int M, r, n_parts;
     int nsplit;             // workgroups that share one 128-column tile (split of N)
@@ -562,10 +574,20 @@ __device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const fl
 template <int BITS>
 __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdDev d) {
     extern __shared__ __attribute__((aligned(16))) uint4 ys[];   // [chunks of 8 n of the slice][16 rows]
+    __shared__ float Ts[16 * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (blockIdx.x == 0) {
+        // reducer block: dYBt = sum of the prep kernel's partials (see the forward kernel)
+        smallm_gather_parts(d.Tpart, d.n_parts, d.r, Ts);
+        for (int t = tid; t < 16 * d.r; t += sm::WG_THREADS) d.Tfinal[t] = Ts[t];
+        if (d.T_out != nullptr)
+            for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.T_out[t] = Ts[t];
+        return;
+    }
+    const int bid = blockIdx.x - 1;
     const int i = lane & 15, j = lane >> 4, b = i & 3, u = i >> 2;
     const int N = d.w.N, K = d.w.K;
-    const int kb = blockIdx.x / d.nsplit, ns = blockIdx.x % d.nsplit;
+    const int kb = bid / d.nsplit, ns = bid % d.nsplit;
     const int kt = kb * smb::KT;
     const int n_steps = N / smb::NSTEP;
     const int S0 = (int)((long)n_steps * ns / d.nsplit), S1 = (int)((long)n_steps * (ns + 1) / d.nsplit);
@@ -757,10 +779,9 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(Small
             y[4] += v1.x; y[5] += v1.y; y[6] += v1.z; y[7] += v1.w;
         }
     }
-    smallm_gather_parts(d.Tpart, d.n_parts, d.r, Ts);
+    for (int t = tid; t < 16 * d.r; t += sm::WG_THREADS) Ts[t] = d.Tfinal[t];
+    __syncthreads();
     if (m < d.M) smallm_bwd_store8(d, Ts, m, k0, y);
-    if (blockIdx.x == 0 && d.T_out != nullptr)
-        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.T_out[t] = Ts[t];
 }
 
 namespace {
@@ -819,7 +840,7 @@ bool smallm_fwd_supported(const LayerView &w, int M) {
 
 namespace {
 struct SmallWs {
-    size_t xp, upart, yacc, total;
+    size_t xp, upart, ufinal, yacc, total;
 };
 SmallWs small_ws(int K, int N, int r) {
     const size_t kmax = (size_t)(K > N ? K : N);
@@ -828,6 +849,7 @@ SmallWs small_ws(int K, int N, int r) {
     size_t off = 0;
     l.xp = off;      off += al((size_t)16 * kmax * 2);
     l.upart = off;   off += al(((kmax + sm::PREP_K - 1) / sm::PREP_K) * 16 * (size_t)(r > 0 ? r : 1) * 4);
+    l.ufinal = off;  off += al((size_t)16 * 64 * 4);
     const size_t yf = (size_t)ksplit_bound(K, N) * 16 * N, yb = (size_t)sm::MAX_KSPLIT * 16 * K;
     l.yacc = off;    off += al((yf > yb ? yf : yb) * 4);
     l.total = off;
@@ -843,7 +865,7 @@ static hipError_t launch_fwd_bits(const SmallFwdDev &d, int col_blocks, size_t l
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
     if (e != hipSuccess) return e;
-    kern<<<col_blocks * d.ksplit, sm::WG_THREADS, lds_bytes, stream>>>(d);
+    kern<<<col_blocks * d.ksplit + 1, sm::WG_THREADS, lds_bytes, stream>>>(d);   // + the reducer block
     return hipGetLastError();
 }
 
@@ -874,6 +896,7 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     d.w = a.w;
     d.Xp = Xp;
     d.Upart = Upart;
+    d.Ufinal = reinterpret_cast<float *>(ws + l.ufinal);
     d.B = a.B;
     d.M = a.M;
     d.r = a.r;
@@ -906,7 +929,7 @@ static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, size_t lds
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
     if (e != hipSuccess) return e;
-    kern<<<k_blocks * d.nsplit, sm::WG_THREADS, lds_bytes, stream>>>(d);
+    kern<<<k_blocks * d.nsplit + 1, sm::WG_THREADS, lds_bytes, stream>>>(d);   // + the reducer block
     return hipGetLastError();
 }
 
@@ -933,6 +956,7 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     d.w = a.w;
     d.dYp = dYp;
     d.Tpart = Tpart;
+    d.Tfinal = reinterpret_cast<float *>(ws + l.ufinal);
     d.A = a.A;
     d.M = a.M;
     d.r = a.r;
