@@ -4,8 +4,9 @@
 // "extended contraction" operands with which the tile GEMM adds the adapter term
 // s (X A) B inside its MFMA loop.
 //
-// All of these are bound by one streaming pass over X or dY; the arithmetic is plain
-// fp32 FMA with coalesced 16-byte (projection) or 4-byte (gradient) loads per lane.
+// All of these are bound by one streaming pass over X or dY.  The projections run on the
+// matrix cores (the fp32 factor split into three bfloat16 terms); the gradients are plain
+// fp32 FMA with coalesced 4-byte loads per lane.
 #include "device_common.h"
 #include "launch.h"
 
@@ -22,22 +23,46 @@ __device__ __forceinline__ uint16_t split_part(float v, bool want_lo) {
 }
 
 // ---------------------------------------------------------------------------
-// Projection: P[m][j] = sum_c act[m][c] F(c, j); one workgroup owns ROWS rows and
-// walks the whole contraction; lanes own 8-column chunks (16-byte loads).
-// Extra workgroups (blockIdx.x >= row blocks) write the weight-side extension.
+// Projection: P[m][j] = sum_c act[m][c] F(c, j) on the matrix cores.  A workgroup owns 16 rows;
+// its waves split the contraction and meet in LDS.  act is bfloat16 already; the fp32 factor is
+// split on the fly into three bfloat16 terms (hi + mid + lo carry all 24 significand bits), so
+// three 16x16x32 MFMAs per step give the fp32-exact products, accumulated in fp32.
+// Lane l = 16 cs + i: activation row i / factor column i, contraction elements 8 cs .. 8 cs + 7
+// of the step.  Extra workgroups (blockIdx.x >= row blocks) write the weight-side extension.
 // ---------------------------------------------------------------------------
-template <int RP, int ROWS, bool F_IS_A>
-__global__ __launch_bounds__(256) void lora_down_kernel(DownArgs a, int row_blocks) {
-    __shared__ float red[4][ROWS * RP];
-    __shared__ float Ps[ROWS * RP];
-    const int tid = threadIdx.x;
+__device__ __forceinline__ void split3(const float x[8], uint32_t hi[4], uint32_t mid[4], uint32_t lo[4]) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const float x0 = x[2 * p], x1 = x[2 * p + 1];
+        hi[p] = pack_bf16x2(x0, x1);
+        const float r0 = x0 - __uint_as_float(hi[p] << 16), r1 = x1 - __uint_as_float(hi[p] & 0xFFFF0000u);
+        mid[p] = pack_bf16x2(r0, r1);
+        const float s0 = r0 - __uint_as_float(mid[p] << 16), s1 = r1 - __uint_as_float(mid[p] & 0xFFFF0000u);
+        lo[p] = pack_bf16x2(s0, s1);
+    }
+}
+
+__device__ __forceinline__ bf16x8 regs_to_bf16x8(const uint32_t r[4]) {
+    bf16x8 v;
+    __builtin_memcpy(&v, r, 16);
+    return v;
+}
+
+// ROWT: 16-row tiles per workgroup (they share every factor operand); UNR: steps whose loads
+// are issued together before any of them is used.
+template <int RG, int ROWT, bool F_IS_A>
+__global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blocks) {
+    extern __shared__ __attribute__((aligned(16))) float lds_f[];   // [waves][ROWT][RG][256] partial tiles, then Ps
+    constexpr int UNR = RG == 1 ? 4 : (RG == 2 ? 2 : 1);
+    constexpr int ROWS = 16 * ROWT;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
     const int r = a.r;
 
     if ((int)blockIdx.x >= row_blocks) {
         // weight-side extension: w_ext[c][e]
         const size_t total = (size_t)a.Cw * a.RE;
-        size_t idx = (size_t)(blockIdx.x - row_blocks) * 256 + tid;
-        const size_t stride = (size_t)(gridDim.x - row_blocks) * 256;
+        size_t idx = (size_t)(blockIdx.x - row_blocks) * nthreads + tid;
+        const size_t stride = (size_t)(gridDim.x - row_blocks) * nthreads;
         for (; idx < total; idx += stride) {
             const int c = (int)(idx / a.RE), e = (int)(idx % a.RE);
             uint16_t v = 0;
@@ -51,129 +76,138 @@ __global__ __launch_bounds__(256) void lora_down_kernel(DownArgs a, int row_bloc
         return;
     }
 
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthreads >> 6;
+    const int i = lane & 15, cs = lane >> 4;
     const int m0 = blockIdx.x * ROWS;
-    float acc[ROWS][RP];
+    const uint16_t *arow[ROWT];
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i)
-#pragma unroll
-        for (int j = 0; j < RP; ++j) acc[i][j] = 0.f;
+    for (int t = 0; t < ROWT; ++t) {
+        int row = m0 + 16 * t + i;
+        if (row > a.M - 1) row = a.M - 1;
+        arow[t] = a.act + (size_t)row * a.C;
+    }
+    const int steps = (a.C + 31) / 32;
+    const int s_begin = (int)((long)steps * wave / nwaves), s_end = (int)((long)steps * (wave + 1) / nwaves);
 
-    for (int c = tid * 8; c < a.C; c += 256 * 8) {
-        float x[ROWS][8];
+    f32x4 acc[ROWT][RG];
 #pragma unroll
-        for (int i = 0; i < ROWS; ++i) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (m0 + i < a.M) v = *reinterpret_cast<const uint4 *>(a.act + (size_t)(m0 + i) * a.C + c);
-            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+    for (int t = 0; t < ROWT; ++t)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                x[i][2 * t] = __uint_as_float(u[t] << 16);
-                x[i][2 * t + 1] = __uint_as_float(u[t] & 0xFFFF0000u);
+        for (int g = 0; g < RG; ++g) acc[t][g] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int st = s_begin; st < s_end; st += UNR) {
+        uint4 av[UNR][ROWT];
+        float f[UNR][RG][8];
+        // all loads of UNR steps first
+#pragma unroll
+        for (int q = 0; q < UNR; ++q) {
+            const int c = (st + q) * 32 + cs * 8;       // C is a multiple of 8: the chunk is all in or all out
+            const bool c_ok = st + q < s_end && c < a.C;
+#pragma unroll
+            for (int t = 0; t < ROWT; ++t) {
+                av[q][t] = make_uint4(0, 0, 0, 0);
+                if (c_ok) av[q][t] = *reinterpret_cast<const uint4 *>(arow[t] + c);
             }
-        }
-        if (F_IS_A) {
 #pragma unroll
-            for (int cc = 0; cc < 8; ++cc) {
-                float f[RP];
-                const float *src = a.Fm + (size_t)(c + cc) * r;
-                if (r == RP) {
+            for (int g = 0; g < RG; ++g) {
+                const int j = g * 16 + i;
 #pragma unroll
-                    for (int j = 0; j < RP; j += 4) {
-                        const float4 q = *reinterpret_cast<const float4 *>(src + j);
-                        f[j] = q.x; f[j + 1] = q.y; f[j + 2] = q.z; f[j + 3] = q.w;
+                for (int e = 0; e < 8; ++e) f[q][g][e] = 0.f;
+                if (c_ok && j < r) {
+                    if (F_IS_A) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) f[q][g][e] = a.Fm[(size_t)(c + e) * r + j];
+                    } else {
+                        const float4 q0 = *reinterpret_cast<const float4 *>(a.Fm + (size_t)j * a.C + c);
+                        const float4 q1 = *reinterpret_cast<const float4 *>(a.Fm + (size_t)j * a.C + c + 4);
+                        f[q][g][0] = q0.x; f[q][g][1] = q0.y; f[q][g][2] = q0.z; f[q][g][3] = q0.w;
+                        f[q][g][4] = q1.x; f[q][g][5] = q1.y; f[q][g][6] = q1.z; f[q][g][7] = q1.w;
                     }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < RP; ++j) f[j] = j < r ? src[j] : 0.f;
                 }
-#pragma unroll
-                for (int i = 0; i < ROWS; ++i)
-#pragma unroll
-                    for (int j = 0; j < RP; ++j) acc[i][j] = __builtin_fmaf(x[i][cc], f[j], acc[i][j]);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < RP; ++j) {
-                float f[8];
-                if (j < r) {
-                    const float4 q0 = *reinterpret_cast<const float4 *>(a.Fm + (size_t)j * a.C + c);
-                    const float4 q1 = *reinterpret_cast<const float4 *>(a.Fm + (size_t)j * a.C + c + 4);
-                    f[0] = q0.x; f[1] = q0.y; f[2] = q0.z; f[3] = q0.w;
-                    f[4] = q1.x; f[5] = q1.y; f[6] = q1.z; f[7] = q1.w;
-                } else {
-#pragma unroll
-                    for (int cc = 0; cc < 8; ++cc) f[cc] = 0.f;
-                }
-#pragma unroll
-                for (int i = 0; i < ROWS; ++i)
-#pragma unroll
-                    for (int cc = 0; cc < 8; ++cc) acc[i][j] = __builtin_fmaf(x[i][cc], f[cc], acc[i][j]);
             }
         }
+#pragma unroll
+        for (int q = 0; q < UNR; ++q)
+#pragma unroll
+            for (int g = 0; g < RG; ++g) {
+                uint32_t hi[4], mid[4], lo[4];
+                split3(f[q][g], hi, mid, lo);
+                const bf16x8 bh = regs_to_bf16x8(hi), bm = regs_to_bf16x8(mid), bl = regs_to_bf16x8(lo);
+#pragma unroll
+                for (int t = 0; t < ROWT; ++t) {
+                    const uint32_t ar[4] = {av[q][t].x, av[q][t].y, av[q][t].z, av[q][t].w};
+                    const bf16x8 aop = regs_to_bf16x8(ar);
+                    acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bh, acc[t][g], 0, 0, 0);
+                    acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bm, acc[t][g], 0, 0, 0);
+                    acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bl, acc[t][g], 0, 0, 0);
+                }
+            }
     }
 
-    // reduce over the 64 lanes of each wave, then over the 4 waves through LDS
+    // D register v of lane (i, cs): row 4 cs + v, column i.  Partial tiles -> LDS -> sum over the waves.
+    constexpr int TILES = ROWT * RG;
 #pragma unroll
-    for (int i = 0; i < ROWS; ++i)
+    for (int t = 0; t < ROWT; ++t)
 #pragma unroll
-        for (int j = 0; j < RP; ++j) {
-            float v = acc[i][j];
+        for (int g = 0; g < RG; ++g)
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-            acc[i][j] = v;
-        }
-    const int wave = tid >> 6, lane = tid & 63;
-    if (lane == 0) {
-#pragma unroll
-        for (int i = 0; i < ROWS; ++i)
-#pragma unroll
-            for (int j = 0; j < RP; ++j) red[wave][i * RP + j] = acc[i][j];
-    }
+            for (int v = 0; v < 4; ++v) lds_f[((wave * TILES + t * RG + g) * 4 + v) * 64 + lane] = acc[t][g][v];
     __syncthreads();
-    for (int t = tid; t < ROWS * RP; t += 256) {
-        const float v = red[0][t] + red[1][t] + red[2][t] + red[3][t];
-        Ps[t] = v;
-        const int i = t / RP, j = t % RP;
-        if (m0 + i < a.M && j < r) a.P[(size_t)(m0 + i) * r + j] = v;
+    float *Ps = lds_f + nwaves * TILES * 256;               // [ROWS][16 * RG]
+    for (int x = tid; x < TILES * 256; x += nthreads) {
+        const int tile = x >> 8, v = (x >> 6) & 3, l = x & 63;
+        float sum = 0.f;
+        for (int w = 0; w < nwaves; ++w) sum += lds_f[((w * TILES + tile) * 4 + v) * 64 + l];
+        const int prow = 16 * (tile / RG) + 4 * (l >> 4) + v, j = (tile % RG) * 16 + (l & 15);
+        Ps[prow * (16 * RG) + j] = sum;
+        if (m0 + prow < a.M && j < r) a.P[(size_t)(m0 + prow) * r + j] = sum;
     }
     if (a.act_ext == nullptr) return;
     __syncthreads();
-    for (int t = tid; t < ROWS * a.RE; t += 256) {
-        const int i = t / a.RE, e = t % a.RE;
-        if (m0 + i >= a.M) continue;
+    for (int x = tid; x < ROWS * a.RE; x += nthreads) {
+        const int pr = x / a.RE, e = x % a.RE;
+        if (m0 + pr >= a.M) continue;
         uint16_t v = 0;
         if (e < 3 * r) {
             const int seg = e / r, j = e % r;
-            v = split_part(a.lora_scale * Ps[i * RP + j], seg == 2);
+            v = split_part(a.lora_scale * Ps[pr * (16 * RG) + j], seg == 2);
         }
-        a.act_ext[(size_t)(m0 + i) * a.RE + e] = v;
+        a.act_ext[(size_t)(m0 + pr) * a.RE + e] = v;
     }
 }
 
-template <int RP, int ROWS>
-static hipError_t launch_down_rp(const DownArgs &a, hipStream_t stream) {
+template <int RG, int ROWT>
+static hipError_t launch_down_rg(const DownArgs &a, hipStream_t stream) {
+    constexpr int ROWS = 16 * ROWT;
     const int row_blocks = (a.M + ROWS - 1) / ROWS;
+    // enough waves to fill the chip (~2048: the loads are 64-byte pieces of 16 rows, so it takes
+    // many waves to keep HBM busy), at most 32 partial tiles per workgroup
+    int nwaves = 4;
+    while (nwaves < 16 && row_blocks * nwaves < 2048 && nwaves * 2 * RG * ROWT <= 32) nwaves *= 2;
+    const int nthreads = nwaves * 64;
     int w_blocks = 0;
     if (a.w_ext) {
         const size_t total = (size_t)a.Cw * a.RE;
-        w_blocks = (int)((total + 256 * 8 - 1) / (256 * 8));
+        w_blocks = (int)((total + (size_t)nthreads * 8 - 1) / ((size_t)nthreads * 8));
         if (w_blocks > 512) w_blocks = 512;
         if (w_blocks < 1) w_blocks = 1;
     }
+    const size_t lds = (size_t)(nwaves * RG * ROWT * 256 + ROWS * 16 * RG) * sizeof(float);
     prof_before("lora_down", stream);
     if (a.f_is_A)
-        lora_down_kernel<RP, ROWS, true><<<row_blocks + w_blocks, 256, 0, stream>>>(a, row_blocks);
+        lora_down_kernel<RG, ROWT, true><<<row_blocks + w_blocks, nthreads, lds, stream>>>(a, row_blocks);
     else
-        lora_down_kernel<RP, ROWS, false><<<row_blocks + w_blocks, 256, 0, stream>>>(a, row_blocks);
+        lora_down_kernel<RG, ROWT, false><<<row_blocks + w_blocks, nthreads, lds, stream>>>(a, row_blocks);
     prof_after(stream);
     return hipGetLastError();
 }
 
 hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream) {
-    if (a.r <= 8) return launch_down_rp<8, 4>(a, stream);
-    if (a.r <= 16) return launch_down_rp<16, 4>(a, stream);
-    if (a.r <= 32) return launch_down_rp<32, 2>(a, stream);
-    return launch_down_rp<64, 1>(a, stream);
+    // many tokens: four row tiles per workgroup share each split factor operand
+    if (a.r <= 16) return launch_down_rg<1, 1>(a, stream);
+    if (a.r <= 32) return launch_down_rg<2, 1>(a, stream);
+    if (a.r <= 48) return launch_down_rg<3, 1>(a, stream);
+    return launch_down_rg<4, 1>(a, stream);
 }
 
 // ---------------------------------------------------------------------------
