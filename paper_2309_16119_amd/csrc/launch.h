@@ -80,7 +80,8 @@ struct GradPairArgs {
     float *partials;             // scratch, grad_geom().partial_floats floats
 };
 struct GradGeom {
-    int cols_a, cols_b;          // 128-column blocks of X and of dY
+    int cpl;                     // columns per lane (2 or 4)
+    int cols_a, cols_b;          // column blocks (64 * cpl columns) of X and of dY
     int chunks, rows_per_block;  // row chunks (one partial each)
     int passes;                  // rank passes of 32 (r > 32)
     size_t partial_floats;

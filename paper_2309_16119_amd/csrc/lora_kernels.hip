@@ -213,8 +213,8 @@ hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream) {
 // ---------------------------------------------------------------------------
 // Adapter gradients (Section 3.1.1), both in one launch plus one reduction launch:
 //   dA[k][j] = s * sum_m X[m][k]  dYBt[m][j]      dB[j][n] = s * sum_m XA[m][j] dY[m][n]
-// Stage 1: a workgroup owns 128 columns of X (or dY) and a chunk of rows; each lane owns 2
-// adjacent columns (one 4-byte load per row), the 4 waves take rows round-robin, P[m][:] is
+// Stage 1: a workgroup owns 128 or 256 columns of X (or dY) and a chunk of rows; each lane owns 2
+// or 4 adjacent columns (one 4- or 8-byte load per row), the 4 waves take rows round-robin, P[m][:] is
 // wave-uniform.  The 4 waves' sums meet in LDS and go out as one partial per row chunk, laid
 // out like the outputs ([chunk][dA | dB]).  Stage 2 adds the chunks, applies s and the
 // accumulate flag.  No atomics (device-scope fp32 atomics bypass the per-XCD L2 and are slow)
@@ -222,8 +222,10 @@ hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream) {
 // ---------------------------------------------------------------------------
 GradGeom grad_geom(int M, int K, int N, int r) {
     GradGeom g;
-    g.cols_a = (K + 127) / 128;
-    g.cols_b = (N + 127) / 128;
+    g.cpl = r <= 16 ? 4 : 2;                        // columns per lane (8- or 4-byte loads)
+    const int wcols = 64 * g.cpl;                   // columns per workgroup
+    g.cols_a = (K + wcols - 1) / wcols;
+    g.cols_b = (N + wcols - 1) / wcols;
     const int col_blocks = g.cols_a + g.cols_b;
     // enough row chunks to give the chip ~1024 workgroups, at least 32 rows each
     int chunks = (1024 + col_blocks - 1) / col_blocks;
@@ -239,59 +241,68 @@ GradGeom grad_geom(int M, int K, int N, int r) {
     return g;
 }
 
-template <int RP>
+template <int RP, int CPL>
 __global__ __launch_bounds__(256) void lora_grad_partial_kernel(GradPairArgs a, GradGeom g) {
-    __shared__ float red[3][64][2 * RP + 1];
+    __shared__ float red[3][64][CPL * RP + 1];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool is_a = (int)blockIdx.x < g.cols_a;
     const uint16_t *act = is_a ? a.X : a.dY;
     const float *P = is_a ? a.dYBt : a.XA;
     const int C = is_a ? a.K : a.N;
-    const int c = (is_a ? blockIdx.x : blockIdx.x - g.cols_a) * 128 + 2 * lane;
+    const int c = (is_a ? blockIdx.x : blockIdx.x - g.cols_a) * (64 * CPL) + CPL * lane;
     const int r = a.r, j0 = blockIdx.z * RP;
     const int m_begin = blockIdx.y * g.rows_per_block;
     int m_end = m_begin + g.rows_per_block;
     if (m_end > a.M) m_end = a.M;
-    const bool col_ok = c < C;   // C is even, so c + 1 < C too
+    const bool col_ok = c < C;   // C is a multiple of 8 >= CPL, so c + CPL - 1 < C too
 
-    float acc[2][RP];
+    float acc[CPL][RP];
 #pragma unroll
-    for (int j = 0; j < RP; ++j) acc[0][j] = acc[1][j] = 0.f;
+    for (int t = 0; t < CPL; ++t)
+#pragma unroll
+        for (int j = 0; j < RP; ++j) acc[t][j] = 0.f;
 
-    auto row_fma = [&](uint32_t v, int m) {
-        const float x0 = __uint_as_float(v << 16), x1 = __uint_as_float(v & 0xFFFF0000u);
+    typedef uint32_t words_t __attribute__((ext_vector_type(CPL / 2)));
+    auto row_fma = [&](words_t v, int m) {
+        float x[CPL];
+#pragma unroll
+        for (int q = 0; q < CPL / 2; ++q) {
+            uint32_t wq;
+            wq = v[q];
+            x[2 * q] = __uint_as_float(wq << 16);
+            x[2 * q + 1] = __uint_as_float(wq & 0xFFFF0000u);
+        }
         const float *p = P + (size_t)m * r + j0;
 #pragma unroll
         for (int j = 0; j < RP; ++j) {
             const float pj = j0 + j < r ? p[j] : 0.f;
-            acc[0][j] = __builtin_fmaf(x0, pj, acc[0][j]);
-            acc[1][j] = __builtin_fmaf(x1, pj, acc[1][j]);
+#pragma unroll
+            for (int t = 0; t < CPL; ++t) acc[t][j] = __builtin_fmaf(x[t], pj, acc[t][j]);
         }
     };
     const uint16_t *col = act + (col_ok ? c : 0);
     int m = m_begin + wave;
     for (; m + 12 < m_end; m += 16) {     // four rows in flight per wave
-        uint32_t v[4];
+        words_t v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint32_t *>(col + (size_t)(m + 4 * u) * C);
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const words_t *>(col + (size_t)(m + 4 * u) * C);
 #pragma unroll
         for (int u = 0; u < 4; ++u) row_fma(v[u], m + 4 * u);
     }
-    for (; m < m_end; m += 4) row_fma(*reinterpret_cast<const uint32_t *>(col + (size_t)m * C), m);
+    for (; m < m_end; m += 4) row_fma(*reinterpret_cast<const words_t *>(col + (size_t)m * C), m);
 
     if (wave > 0) {
 #pragma unroll
-        for (int j = 0; j < RP; ++j) {
-            red[wave - 1][lane][j] = acc[0][j];
-            red[wave - 1][lane][RP + j] = acc[1][j];
-        }
+        for (int t = 0; t < CPL; ++t)
+#pragma unroll
+            for (int j = 0; j < RP; ++j) red[wave - 1][lane][t * RP + j] = acc[t][j];
     }
     __syncthreads();
     if (wave != 0 || !col_ok) return;
     float *part = a.partials + (size_t)blockIdx.y * ((size_t)(a.K + a.N) * r);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < CPL; ++t) {
         float v[RP];
 #pragma unroll
         for (int j = 0; j < RP; ++j)
@@ -349,9 +360,9 @@ hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream) {
     const GradGeom g = grad_geom(a.M, a.K, a.N, a.r);
     dim3 grid(g.cols_a + g.cols_b, g.chunks, g.passes);
     prof_before("lora_grad", stream);
-    if (a.r <= 8) lora_grad_partial_kernel<8><<<grid, 256, 0, stream>>>(a, g);
-    else if (a.r <= 16) lora_grad_partial_kernel<16><<<grid, 256, 0, stream>>>(a, g);
-    else lora_grad_partial_kernel<32><<<grid, 256, 0, stream>>>(a, g);
+    if (a.r <= 8) lora_grad_partial_kernel<8, 4><<<grid, 256, 0, stream>>>(a, g);
+    else if (a.r <= 16) lora_grad_partial_kernel<16, 4><<<grid, 256, 0, stream>>>(a, g);
+    else lora_grad_partial_kernel<32, 2><<<grid, 256, 0, stream>>>(a, g);
     prof_after(stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
