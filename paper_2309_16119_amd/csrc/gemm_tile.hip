@@ -20,13 +20,15 @@
 //     that loads the words of 4 adjacent columns holds, for each k of the chunk, 4
 //     consecutive n of the MFMA operand; no transpose through LDS is needed.
 //
-// Scheduling.  One VALU instruction costs a SIMD 4 cycles and one 32x32x16 MFMA 32;
-// they overlap when they come from different waves of the same SIMD.  The large
-// variant therefore runs 8 waves (2 per SIMD) on a double-buffered LDS tile pair and
-// lets the two waves of a SIMD take the two halves of a step in opposite order: one
-// issues the MFMAs of tile t while the other dequantizes tile t+1, then they swap.
-// The mid variant runs 4 waves with one LDS buffer and relies on two workgroups per
-// CU to fill each other's gaps.
+// Scheduling.  One VALU instruction costs a SIMD about 4 cycles and one 32x32x16 MFMA 32;
+// they overlap when they come from different waves of the same SIMD, or when a wave issues
+// independent VALU work after an MFMA.  The 256x256 variant lives in gemm_big.hip.  The
+// variants of this file are: single-buffered ones (32x256 for a handful of tokens, 256x128
+// with two workgroups per CU filling each other's gaps) and pipelined ones for grids of
+// about one tile per CU, where nothing else hides latency: register stages filled several
+// tiles ahead, two LDS buffers with one barrier per tile, the dequantization of the next
+// tile issued between the MFMA steps of the current one, and optionally 8 waves that split
+// the 16-deep steps of each tile between k-groups (two waves per SIMD on a small tile).
 //
 // The steady-state loop is branch-free: rows past M and columns past the matrix are
 // clamped to valid addresses (their results are never stored), uniform address parts

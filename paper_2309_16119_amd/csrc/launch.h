@@ -107,7 +107,4 @@ size_t smallm_ws_bytes(int K, int N, int r);
 hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream);
 hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream);
 
-// dst[0..n) = 0.0f   (a fill kernel, so that callers may capture it in a HIP graph)
-hipError_t launch_fill_zero(float *dst, size_t n, hipStream_t stream);
-
 }  // namespace mlr

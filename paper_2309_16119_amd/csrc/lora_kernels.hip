@@ -373,20 +373,4 @@ hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(float *dst, size_t n) {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (; i < n; i += stride) dst[i] = 0.f;
-}
-
-hipError_t launch_fill_zero(float *dst, size_t n, hipStream_t stream) {
-    if (n == 0) return hipSuccess;
-    size_t blocks = (n + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    prof_before("fill_zero", stream);
-    fill_zero_kernel<<<(unsigned)blocks, 256, 0, stream>>>(dst, n);
-    prof_after(stream);
-    return hipGetLastError();
-}
-
 }  // namespace mlr
