@@ -248,6 +248,14 @@ __device__ __forceinline__ void ald_lds(const void *gbase_uniform, uint32_t voff
                  : "s"(lds_base_uniform), "v"(voff_bytes), "s"(gbase_uniform)
                  : "memory");
 }
+// the same with a full per-lane address; earlier LDS reads of the wave are awaited first, so
+// that the incoming data cannot overtake a read of the slot it replaces
+__device__ __forceinline__ void ald_lds64(const void *gaddr_lane, uint32_t lds_base_uniform) {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base_uniform), "v"(gaddr_lane)
+                 : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vm() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
@@ -540,11 +548,13 @@ struct SmallBwdDev {
     uint16_t *dX;           // [M][K]
     float *T_out;           // dYBt [M][r] or NULL
     float *acc;             // [nsplit][16][K] fp32 partial tiles
+    int slice_bytes;        // LDS bytes reserved for the dY slice (and, later, the wave reduction)
 };
 
 namespace smb {
 constexpr int KT = 128;      // output columns per workgroup: four 32-code blocks
 constexpr int NSTEP = 32;    // contraction elements per step (8 per lane group)
+constexpr int MAX_STEPS = 32; // steps of one slice of N: 32 KB of dY in LDS
 }
 
 // adapter term and bfloat16 store of 8 adjacent outputs dX[m][k0 .. k0+7]
@@ -607,43 +617,56 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
         row1 = b * 3 + (lo + 1 > 2 ? 2 : lo + 1);
         bitsh = (24u * u) & 31u;
     }
-    const uint32_t voff0 = (uint32_t)(((size_t)row0 * N + 8 * j) * 4);
-    const uint32_t voff1 = (uint32_t)(((size_t)row1 * N + 8 * j) * 4);
-    const uint32_t s_voff = 16u * j, z_voff = 8u * j;
     const uint32_t *wtile = d.w.qweight + (size_t)(kt / 32) * BITS * N;
     const uint16_t *stile = d.w.scales + (size_t)g * N;
     const uint8_t *ztile = d.w.zeros + (size_t)g * N;
 
+    // The packed words, scales and zeros of a step (32 n) travel global -> LDS without passing
+    // through registers: every lane moves one 16-byte piece per load, so a whole stage is NI
+    // fully coalesced loads (128 contiguous bytes per word row).  Piece p of word row `row` sits
+    // at LDS piece p ^ (row & 7) of that row: the later 16-byte reads of 16 different rows then
+    // spread over the banks.  Each wave owns DEPTH private stages behind the workgroup's dY slice.
+    constexpr int WR = 4 * BITS;                       // word rows of the 128-column tile
+    constexpr int W_PIECES = WR * 8, S_PIECE0 = W_PIECES, Z_PIECE0 = W_PIECES + 4, N_PIECES = W_PIECES + 6;
+    constexpr int NI = (N_PIECES + 63) / 64;           // loads per stage
+    constexpr int STAGE_BYTES = NI * 1024;
     constexpr int DEPTH = 4;
-    constexpr int SL = NROWS * 2 + 2;               // loads per stage
-    struct Stage {
-        sm::u32x4 w[NROWS][2];   // 8 adjacent n of each word row
-        sm::u32x4 sc;            // 8 binary16 scales
-        sm::u32x2 z;             // 8 zero points
-    };
-    Stage st[DEPTH];
-    auto issue = [&](Stage &sd, int step) {         // step: any step of the workgroup's slice
-        const uint32_t *wbase = wtile + (size_t)step * smb::NSTEP;
-        sm::ald(sd.w[0][0], wbase, voff0);
-        sm::ald(sd.w[0][1], wbase + 4, voff0);
-        if (NROWS == 2) {
-            sm::ald(sd.w[NROWS - 1][0], wbase, voff1);
-            sm::ald(sd.w[NROWS - 1][1], wbase + 4, voff1);
+    const char *gaddr[NI];                             // this lane's piece of load q, at step 0 of the matrix
+    uint32_t gstr[NI];                                 // ... and its advance per step
+#pragma unroll
+    for (int q = 0; q < NI; ++q) {
+        const int pc = q * 64 + lane;                  // lanes past N_PIECES sit out the last load
+        if (pc < W_PIECES) {
+            const int row = pc >> 3, pp = (pc & 7) ^ (row & 7);
+            gaddr[q] = reinterpret_cast<const char *>(wtile) + ((size_t)row * N + pp * 4) * 4;
+            gstr[q] = smb::NSTEP * 4;
+        } else if (pc < Z_PIECE0) {
+            gaddr[q] = reinterpret_cast<const char *>(stile) + (pc - S_PIECE0) * 16;
+            gstr[q] = smb::NSTEP * 2;
+        } else {
+            gaddr[q] = reinterpret_cast<const char *>(ztile) + (pc < N_PIECES ? pc - Z_PIECE0 : 0) * 16;
+            gstr[q] = smb::NSTEP;
         }
-        sm::ald(sd.sc, stile + (size_t)step * smb::NSTEP, s_voff);
-        sm::ald(sd.z, ztile + (size_t)step * smb::NSTEP, z_voff);
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)ys;
+    const uint32_t stage0 = (uint32_t)d.slice_bytes + (uint32_t)wave * (DEPTH * STAGE_BYTES);   // offset of the wave's stages
+    auto issue = [&](int slot, int step) {             // step: any step of the workgroup's slice
+#pragma unroll
+        for (int q = 0; q < NI; ++q) {
+            if ((q + 1) * 64 <= N_PIECES || q * 64 + lane < N_PIECES)
+                sm::ald_lds64(gaddr[q] + (size_t)step * gstr[q], lds0 + stage0 + (uint32_t)slot * STAGE_BYTES + q * 1024);
+        }
     };
     auto clamp_step = [&](int s) { return s < S1 ? s : S1 - 1; };
 
     // the slice of dY goes straight into LDS, 1 KB (one step) per wave and load
     {
         const char *src = reinterpret_cast<const char *>(d.dYp) + (size_t)S0 * 1024;
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)ys;
         for (int q = wave; q < S1 - S0; q += sm::WG_WAVES) sm::ald_lds(src + (size_t)q * 1024, (uint32_t)lane * 16u, lds0 + (uint32_t)q * 1024u);
     }
 #pragma unroll
-    for (int dd = 0; dd < DEPTH; ++dd) issue(st[dd], clamp_step(W0 + dd));
-    sm::wait_vm<DEPTH * SL>();
+    for (int dd = 0; dd < DEPTH; ++dd) issue(dd, clamp_step(W0 + dd));
+    sm::wait_vm<DEPTH * NI>();
     __syncthreads();
 
     f32x4 acc[8], accz, accs;
@@ -659,7 +682,22 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     const uint32_t fmask = sm::opaque_sgpr(BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x00070007u));
     const uint32_t magic = sm::opaque_vgpr(sm::MAGIC);
 
-    auto compute = [&](Stage &sd, int srel) {       // srel: step relative to S0
+    struct Stage {
+        sm::u32x4 w[NROWS][2];   // 8 adjacent n of each word row
+        sm::u32x4 sc;            // 8 binary16 scales
+        sm::u32x2 z;             // 8 zero points
+    };
+    auto compute = [&](int slot, int srel) {        // srel: step relative to S0
+        const unsigned char *sb = reinterpret_cast<const unsigned char *>(ys) + stage0 + slot * STAGE_BYTES;
+        Stage sd;
+        sd.w[0][0] = *reinterpret_cast<const sm::u32x4 *>(sb + row0 * 128 + (((2 * j) ^ (row0 & 7)) << 4));
+        sd.w[0][1] = *reinterpret_cast<const sm::u32x4 *>(sb + row0 * 128 + (((2 * j + 1) ^ (row0 & 7)) << 4));
+        if (NROWS == 2) {
+            sd.w[NROWS - 1][0] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j) ^ (row1 & 7)) << 4));
+            sd.w[NROWS - 1][1] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j + 1) ^ (row1 & 7)) << 4));
+        }
+        sd.sc = *reinterpret_cast<const sm::u32x4 *>(sb + S_PIECE0 * 16 + 16 * j);
+        sd.z = *reinterpret_cast<const sm::u32x2 *>(sb + Z_PIECE0 * 16 + 8 * j);
         // A operand: dY[i][8 n] * scale[g][8 n], rounded to bfloat16
         const uint4 yv = ys[((size_t)srel * 4 + j) * 16 + i];
         const uint32_t yw[4] = {yv.x, yv.y, yv.z, yv.w};
@@ -717,26 +755,14 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
 #pragma unroll
         for (int dd = 0; dd < DEPTH; ++dd) {
             if (s + dd < W1) {
-                sm::wait_vm<(DEPTH - 1) * SL>();
-#pragma unroll
-                for (int rr = 0; rr < NROWS; ++rr) { sm::tie(st[dd].w[rr][0]); sm::tie(st[dd].w[rr][1]); }
-                sm::tie(st[dd].sc);
-                sm::tie(st[dd].z);
-                compute(st[dd], s + dd - S0);
-                issue(st[dd], clamp_step(s + dd + DEPTH));
+                sm::wait_vm<(DEPTH - 1) * NI>();     // this wave's stage dd has landed; DEPTH - 1 younger ones in flight
+                compute(dd, s + dd - S0);
+                issue(dd, clamp_step(s + dd + DEPTH));
             }
         }
     }
-    // loads past the end of the slice are still in flight: keep their registers allocated
-    // until they have landed (see the forward kernel)
+    // loads past the end of the slice are still in flight towards this workgroup's LDS
     sm::wait_vm<0>();
-#pragma unroll
-    for (int dd = 0; dd < DEPTH; ++dd) {
-#pragma unroll
-        for (int rr = 0; rr < NROWS; ++rr) { sm::tie(st[dd].w[rr][0]); sm::tie(st[dd].w[rr][1]); }
-        sm::tie(st[dd].sc);
-        sm::tie(st[dd].z);
-    }
     __syncthreads();                                 // every wave is done with the dY slice
 
     // the four waves' tiles meet in LDS: red[wave][c * 4 + v][lane]
@@ -816,7 +842,7 @@ int ksplit_bound(int Kc, int Nout) {
 int pick_nsplit(int N, int K) {
     const int n_steps = N / smb::NSTEP;
     const int k_blocks = K / smb::KT;
-    const int max_steps = sm::MAX_RANGE / smb::NSTEP;          // steps of one slice that fit the LDS
+    const int max_steps = smb::MAX_STEPS;                      // steps of one slice that fit the LDS
     const int need = (n_steps + max_steps - 1) / max_steps;
     int nsplit = (512 + k_blocks - 1) / k_blocks;
     if (nsplit < need) nsplit = need;
@@ -927,7 +953,7 @@ template <int BITS>
 static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, size_t lds_bytes, hipStream_t stream) {
     auto kern = smallm_bwd_kernel<BITS>;
     static bool configured[64] = {};
-    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)80 * 1024, configured);
     if (e != hipSuccess) return e;
     kern<<<k_blocks * d.nsplit + 1, sm::WG_THREADS, lds_bytes, stream>>>(d);   // + the reducer block
     return hipGetLastError();
@@ -966,10 +992,10 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     d.dX = a.out;
     d.T_out = a.P_out;
     d.acc = reinterpret_cast<float *>(ws + l.yacc);
-    // LDS: the largest slice of dY (1 KB per step), and at least the 32 KB of the wave reduction
-    const int n_steps = N / smb::NSTEP;
-    size_t lds_bytes = (size_t)((n_steps + nsplit - 1) / nsplit) * 1024;
-    if (lds_bytes < 32 * 1024) lds_bytes = 32 * 1024;
+    // LDS: the largest slice of dY (1 KB per step; at least the 32 KB of the wave reduction), then
+    // 4 waves x 4 stages of packed words (3 KB per stage for 4-bit, 2 KB otherwise)
+    d.slice_bytes = 32 * 1024;
+    const size_t lds_bytes = (size_t)d.slice_bytes + 16 * (size_t)(a.w.bits == 4 ? 3072 : 2048);
     prof_before("stream_bwd", stream);
     switch (a.w.bits) {
         case 2: e = launch_bwd_bits<2>(d, k_blocks, lds_bytes, stream); break;
