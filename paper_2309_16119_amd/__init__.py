@@ -10,11 +10,14 @@ _BINDING_NAMES = (
     "modulora_dequant", "modulora_fwd", "modulora_bwd_input", "modulora_bwd_lora",
     "modulora_profile_begin", "modulora_profile_end", "lib", "LIB_PATH",
 )
-__all__ = list(_BINDING_NAMES)
+__all__ = list(_BINDING_NAMES) + ["ModuLoRALinear", "LPLoRAFunction"]
 
 
 def __getattr__(name):
     if name in _BINDING_NAMES:
         from . import binding
         return getattr(binding, name)
+    if name in ("ModuLoRALinear", "LPLoRAFunction"):
+        from . import nn
+        return getattr(nn, name)
     raise AttributeError(name)

@@ -1,0 +1,67 @@
+"""The layer as a torch module: autograd glue over the C-ABI calls, nothing else.
+
+`LPLoRAFunction` is Figure 1 of the ModuLoRA paper with the three library calls in place of
+its PyTorch lines: forward = modulora_fwd, backward = modulora_bwd_input (the weight is
+re-materialized from the codes, nothing but codes, scales and zeros is kept) plus
+modulora_bwd_lora for the adapter factors.  `ModuLoRALinear` holds the frozen quantized
+weight and the trainable adapter (A [d_in][r], B [r][d_out], fp32; the paper's B and A^T).
+All arithmetic runs in the HIP kernels; this file only reshapes, keeps tensors alive for the
+backward pass and hands pointers over.
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional
+
+import torch
+
+from . import binding as b
+
+
+class LPLoRAFunction(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x: torch.Tensor, A: Optional[torch.Tensor], B: Optional[torch.Tensor], w: b.QWeight,
+                lora_scale: float):
+        x2 = x.reshape(-1, w.d_in)
+        if not x2.is_contiguous():
+            x2 = x2.contiguous()
+        y, xa = b.modulora_fwd(w, x2, A, B, lora_scale)
+        ctx.w, ctx.lora_scale, ctx.x_shape = w, lora_scale, x.shape
+        ctx.save_for_backward(x2, A, B, xa)       # activations and adapter only: no weight copy
+        return y.view(*x.shape[:-1], w.d_out)
+
+    @staticmethod
+    def backward(ctx, grad_y: torch.Tensor):
+        x2, A, B, xa = ctx.saved_tensors
+        w, s = ctx.w, ctx.lora_scale
+        dy = grad_y.reshape(-1, w.d_out)
+        if dy.dtype != torch.bfloat16:
+            dy = dy.to(torch.bfloat16)
+        if not dy.is_contiguous():
+            dy = dy.contiguous()
+        dx, t = b.modulora_bwd_input(w, dy, A, B, s)
+        dA = dB = None
+        if A is not None and (ctx.needs_input_grad[1] or ctx.needs_input_grad[2]):
+            dA, dB = b.modulora_bwd_lora(x2, dy, A, B, s, XA=xa, dYBt=t)
+        return dx.view(ctx.x_shape), dA, dB, None, None
+
+
+class ModuLoRALinear(torch.nn.Module):
+    """y = x What^T + (alpha / r) (x A) B with What frozen in 2/3/4-bit group-quantized form."""
+
+    def __init__(self, w: b.QWeight, r: int = 8, alpha: float = 16.0, device: str = "cuda"):
+        super().__init__()
+        self.w = w
+        self.r = r
+        self.lora_scale = float(alpha) / r if r else 0.0
+        if r:
+            # the usual LoRA start: the factor next to the output is zero, so the layer starts
+            # as the plain quantized one (Section 3.1: the adapter then learns the correction)
+            self.A = torch.nn.Parameter(torch.randn(w.d_in, r, device=device) / math.sqrt(w.d_in))
+            self.B = torch.nn.Parameter(torch.zeros(r, w.d_out, device=device))
+        else:
+            self.register_parameter("A", None)
+            self.register_parameter("B", None)
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        return LPLoRAFunction.apply(x, self.A, self.B, self.w, self.lora_scale)

@@ -1,0 +1,75 @@
+"""The torch module over the C-ABI: autograd must deliver exactly what the three library
+calls return, and those are checked against the oracle here once more through the module."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2309_16119_amd import synth
+from paper_2309_16119_amd.nn import ModuLoRALinear
+
+from gpu_util import assert_bar, assert_tight, f64, oracle_args, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("bits,K,N,batch,seq,r,group", [(4, 512, 768, 2, 40, 8, 128), (3, 1024, 384, 1, 9, 16, 128),
+                                                       (2, 512, 520, 3, 50, 0, 64)])
+def test_module_forward_backward_match_the_oracle(bits, K, N, batch, seq, r, group):
+    M = batch * seq
+    cfg = synth.LayerConfig(name="t", K=K, N=N, bits=bits, group=group, M=M, r=r, seed=3)
+    L = synth.make_layer(cfg)
+    D = to_device(L)
+    layer = ModuLoRALinear(D["w"], r=r, alpha=2.0 * r if r else 0.0)
+    if r:
+        with torch.no_grad():
+            layer.A.copy_(D["Ad"])
+            layer.B.copy_(D["Bd"])
+    x = D["Xd"].view(batch, seq, K).clone().requires_grad_(True)
+    y = layer(x)
+    assert y.shape == (batch, seq, N) and y.dtype == torch.bfloat16
+    y.backward(D["dYd"].view(batch, seq, N))
+
+    s = 2.0
+    A, B = (L["A"], L["B"]) if r else (None, None)
+    Yr, _ = oracle.fwd(*oracle_args(L), L["X"], A, B, s)
+    dXr, _ = oracle.bwd_input(*oracle_args(L), L["dY"], A, B, s)
+    extra_Y = extra_dX = 0.0
+    if M <= 16:
+        Wabs = np.abs(oracle.dequant_f32(*oracle_args(L)).astype(np.float64))
+        extra_Y = 2.0 ** -8 * (np.abs(synth.bf16_bits_to_f64(L["X"])) @ Wabs.T)
+        extra_dX = 2.0 ** -7 * (np.abs(synth.bf16_bits_to_f64(L["dY"])) @ Wabs)
+    assert_bar("Y", f64(y).reshape(M, N), Yr)
+    assert_tight("Y", f64(y).reshape(M, N), Yr, True, K, extra_Y)
+    assert_bar("dX", f64(x.grad).reshape(M, K), dXr)
+    assert_tight("dX", f64(x.grad).reshape(M, K), dXr, True, N, extra_dX)
+    if r:
+        dAr, dBr = oracle.bwd_lora(K, N, L["X"], L["dY"], L["A"], L["B"], s)
+        assert_tight("dA", f64(layer.A.grad), dAr, False, M * N)
+        assert_tight("dB", f64(layer.B.grad), dBr, False, M * K)
+    else:
+        assert layer.A is None and layer.B is None
+
+
+def test_module_starts_as_the_plain_quantized_layer_and_trains():
+    cfg = synth.LayerConfig(name="t", K=256, N=256, bits=4, group=64, M=32, r=8, seed=4)
+    L = synth.make_layer(cfg)
+    D = to_device(L)
+    layer = ModuLoRALinear(D["w"], r=8, alpha=16.0)
+    x = D["Xd"]
+    y0 = layer(x)
+    Yr, _ = oracle.fwd(*oracle_args(L), L["X"], None, None, 0.0)
+    assert_bar("Y (B = 0)", f64(y0), Yr)          # B = 0: the adapter contributes nothing yet
+    # a few SGD steps on the adapter towards a shifted target must reduce the loss
+    target = (y0.float() + 0.1).detach()
+    opt = torch.optim.SGD(layer.parameters(), lr=1e-2)
+    losses = []
+    for _ in range(5):
+        opt.zero_grad()
+        out = layer(x).float()
+        loss = ((out - target) ** 2).mean()
+        loss.backward()
+        opt.step()
+        losses.append(float(loss.detach()))
+    assert losses[-1] < losses[0]
+    assert layer.B.grad is not None and layer.A.grad is not None
