@@ -1,0 +1,24 @@
+"""bench.py contract checks that need no GPU."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_roofline_kernel_name_mapping_covers_every_profiled_kernel():
+    sys.path.insert(0, ROOT)
+    import bench
+
+    for name in ("gemm_fwd_256x256", "gemm_bwd_256x256", "gemm_fwd_128x64k", "gemm_bwd_64x128", "stream_fwd",
+                 "stream_bwd", "stream_fwd_finish", "stream_bwd_finish", "smallm_prep_fwd", "smallm_prep_bwd",
+                 "lora_down", "lora_grad", "lora_grad_reduce"):
+        pat = bench.rocprof_kernel_pattern(name)
+        assert "kernel" in pat, (name, pat)
