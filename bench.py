@@ -231,6 +231,9 @@ def pmc_child_run(counter: str, workload_args: list) -> dict:
     exe = shutil.which("rocprofv3")
     if exe is None:
         return {}
+    # never nest profilers: when this process already runs under one, report no traffic
+    if any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ) or "rocprof" in os.environ.get("LD_PRELOAD", ""):
+        return {}
     out = tempfile.mkdtemp(prefix="modulora_pmc_", dir="/tmp")
     env = dict(os.environ, TMPDIR="/tmp")
     cmd = [exe, "--pmc", counter, "--output-format", "csv", "-d", out, "-o", "pmc", "--", sys.executable,
