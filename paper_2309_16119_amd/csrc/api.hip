@@ -104,21 +104,18 @@ std::vector<ProfRecord> g_prof;
 
 namespace mlr {
 
-void prof_before(const char *kernel_name, hipStream_t stream) {
-    if (!g_prof_on) return;
+bool prof_events(const char *kernel_name, hipEvent_t *start, hipEvent_t *stop) {
+    if (!g_prof_on) return false;
     ProfRecord rec{kernel_name, nullptr, nullptr};
-    if (hipEventCreate(&rec.start) != hipSuccess) return;
+    if (hipEventCreate(&rec.start) != hipSuccess) return false;
     if (hipEventCreate(&rec.stop) != hipSuccess) {
         (void)hipEventDestroy(rec.start);
-        return;
+        return false;
     }
-    (void)hipEventRecord(rec.start, stream);
     g_prof.push_back(rec);
-}
-
-void prof_after(hipStream_t stream) {
-    if (!g_prof_on || g_prof.empty()) return;
-    (void)hipEventRecord(g_prof.back().stop, stream);
+    *start = rec.start;
+    *stop = rec.stop;
+    return true;
 }
 
 }  // namespace mlr

@@ -31,13 +31,11 @@ __global__ __launch_bounds__(256) void dequant_kernel(LayerView w, uint16_t *__r
 
 hipError_t launch_dequant(const LayerView &w, uint16_t *What, hipStream_t stream) {
     dim3 grid((w.N + 255) / 256, w.K / 32);
-    prof_before("dequant", stream);
     switch (w.bits) {
-        case 2: dequant_kernel<2><<<grid, 256, 0, stream>>>(w, What); break;
-        case 3: dequant_kernel<3><<<grid, 256, 0, stream>>>(w, What); break;
-        default: dequant_kernel<4><<<grid, 256, 0, stream>>>(w, What); break;
+        case 2: launch_kernel("dequant", dequant_kernel<2>, grid, 256, 0, stream, w, What); break;
+        case 3: launch_kernel("dequant", dequant_kernel<3>, grid, 256, 0, stream, w, What); break;
+        default: launch_kernel("dequant", dequant_kernel<4>, grid, 256, 0, stream, w, What); break;
     }
-    prof_after(stream);
     return hipGetLastError();
 }
 

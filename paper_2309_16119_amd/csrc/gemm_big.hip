@@ -417,9 +417,7 @@ static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
     if (e != hipSuccess) return e;
-    prof_before(BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", stream);
-    kern<<<blocks, big::THREADS, lds_bytes, stream>>>(d);
-    prof_after(stream);
+    launch_kernel(BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", kern, blocks, big::THREADS, lds_bytes, stream, d);
     return hipGetLastError();
 }
 

@@ -627,9 +627,7 @@ static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
     if (e != hipSuccess) return e;
-    prof_before(name, stream);
-    kern<<<blocks, THREADS, lds_bytes, stream>>>(d);
-    prof_after(stream);
+    launch_kernel(name, kern, blocks, THREADS, lds_bytes, stream, d);
     return hipGetLastError();
 }
 

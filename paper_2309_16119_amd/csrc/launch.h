@@ -2,6 +2,7 @@
 // translation units.  Not installed; nothing outside csrc/ includes it.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace mlr {
@@ -19,11 +20,23 @@ struct LayerView {
 // the MFMA K-step of 16.
 inline int lora_ext_len(int r) { return r > 0 ? ((3 * r + 15) / 16) * 16 : 0; }
 
-// ---- profiling hook (api.hip owns the state) -------------------------------
-// launch wrappers call these around every kernel launch; they are no-ops unless
-// modulora_profile_begin() is active.
-void prof_before(const char *kernel_name, hipStream_t stream);
-void prof_after(hipStream_t stream);
+// ---- kernel launches and the profiling hook (api.hip owns the state) ---------------
+// While modulora_profile_begin() is active, prof_events() hands out a fresh pair of events
+// for one launch and returns true.
+bool prof_events(const char *kernel_name, hipEvent_t *start, hipEvent_t *stop);
+
+// Every kernel launch of the library goes through here.  Normally a plain launch; while
+// profiling, the two events are attached to the dispatch itself, so they time the kernel
+// alone (not the launch path around it).
+template <typename... KArgs, typename... Args>
+inline void launch_kernel(const char *name, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes,
+                          hipStream_t stream, Args... args) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (prof_events(name, &e0, &e1))
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, e0, e1, 0u, static_cast<KArgs>(args)...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, static_cast<KArgs>(args)...);
+}
 
 // ---- dequant_kernel.hip ------------------------------------------------------
 hipError_t launch_dequant(const LayerView &w, uint16_t *What, hipStream_t stream);

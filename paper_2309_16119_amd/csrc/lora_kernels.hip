@@ -193,12 +193,10 @@ static hipError_t launch_down_rg(const DownArgs &a, hipStream_t stream) {
         if (w_blocks < 1) w_blocks = 1;
     }
     const size_t lds = (size_t)(nwaves * RG * ROWT * 256 + ROWS * 16 * RG) * sizeof(float);
-    prof_before("lora_down", stream);
     if (a.f_is_A)
-        lora_down_kernel<RG, ROWT, true><<<row_blocks + w_blocks, nthreads, lds, stream>>>(a, row_blocks);
+        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, true>, row_blocks + w_blocks, nthreads, lds, stream, a, row_blocks);
     else
-        lora_down_kernel<RG, ROWT, false><<<row_blocks + w_blocks, nthreads, lds, stream>>>(a, row_blocks);
-    prof_after(stream);
+        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, false>, row_blocks + w_blocks, nthreads, lds, stream, a, row_blocks);
     return hipGetLastError();
 }
 
@@ -359,17 +357,13 @@ __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(GradPairArgs a, i
 hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream) {
     const GradGeom g = grad_geom(a.M, a.K, a.N, a.r);
     dim3 grid(g.cols_a + g.cols_b, g.chunks, g.passes);
-    prof_before("lora_grad", stream);
-    if (a.r <= 8) lora_grad_partial_kernel<8, 4><<<grid, 256, 0, stream>>>(a, g);
-    else if (a.r <= 16) lora_grad_partial_kernel<16, 4><<<grid, 256, 0, stream>>>(a, g);
-    else lora_grad_partial_kernel<32, 2><<<grid, 256, 0, stream>>>(a, g);
-    prof_after(stream);
+    if (a.r <= 8) launch_kernel("lora_grad", lora_grad_partial_kernel<8, 4>, grid, 256, 0, stream, a, g);
+    else if (a.r <= 16) launch_kernel("lora_grad", lora_grad_partial_kernel<16, 4>, grid, 256, 0, stream, a, g);
+    else launch_kernel("lora_grad", lora_grad_partial_kernel<32, 2>, grid, 256, 0, stream, a, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t n = (size_t)(a.K + a.N) * a.r;
-    prof_before("lora_grad_reduce", stream);
-    lora_grad_reduce_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, stream>>>(a, g.chunks);
-    prof_after(stream);
+    launch_kernel("lora_grad_reduce", lora_grad_reduce_kernel, (unsigned)((n / 4 + 255) / 256), 256, 0, stream, a, g.chunks);
     return hipGetLastError();
 }
 

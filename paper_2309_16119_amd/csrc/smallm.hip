@@ -891,7 +891,7 @@ static hipError_t launch_fwd_bits(const SmallFwdDev &d, int col_blocks, size_t l
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
     if (e != hipSuccess) return e;
-    kern<<<col_blocks * d.ksplit + 1, sm::WG_THREADS, lds_bytes, stream>>>(d);   // + the reducer block
+    launch_kernel("stream_fwd", kern, col_blocks * d.ksplit + 1, sm::WG_THREADS, lds_bytes, stream, d);   // + the reducer block
     return hipGetLastError();
 }
 
@@ -907,14 +907,8 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     const int ksplit = pick_ksplit(K, N, a.w.group);
     if (ksplit < 1) return hipErrorInvalidValue;     // callers check smallm_fwd_supported first
 
-    prof_before("smallm_prep_fwd", stream);
-    if (a.r <= 8)
-        smallm_prep_fwd_kernel<8><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart, n_kparts);
-    else if (a.r <= 16)
-        smallm_prep_fwd_kernel<16><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart, n_kparts);
-    else
-        smallm_prep_fwd_kernel<64><<<n_kparts, 256, 0, stream>>>(a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart, n_kparts);
-    prof_after(stream);
+    auto prep = a.r <= 8 ? smallm_prep_fwd_kernel<8> : (a.r <= 16 ? smallm_prep_fwd_kernel<16> : smallm_prep_fwd_kernel<64>);
+    launch_kernel("smallm_prep_fwd", prep, n_kparts, 256, 0, stream, a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart, n_kparts);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -935,17 +929,13 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     // LDS for the largest slice: ceil(groups / ksplit) groups of 32 bytes per contraction element
     const int n_groups = K / a.w.group;
     const size_t lds_bytes = (size_t)((n_groups + ksplit - 1) / ksplit) * a.w.group * 32;
-    prof_before("stream_fwd", stream);
     switch (a.w.bits) {
         case 2: e = launch_fwd_bits<2>(d, col_blocks, lds_bytes, stream); break;
         case 3: e = launch_fwd_bits<3>(d, col_blocks, lds_bytes, stream); break;
         default: e = launch_fwd_bits<4>(d, col_blocks, lds_bytes, stream); break;
     }
-    prof_after(stream);
     if (e != hipSuccess) return e;
-    prof_before("stream_fwd_finish", stream);
-    smallm_fwd_finish_kernel<<<(N + 63) / 64, sm::WG_THREADS, 0, stream>>>(d);
-    prof_after(stream);
+    launch_kernel("stream_fwd_finish", smallm_fwd_finish_kernel, (N + 63) / 64, sm::WG_THREADS, 0, stream, d);
     return hipGetLastError();
 }
 
@@ -955,7 +945,7 @@ static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, size_t lds
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)80 * 1024, configured);
     if (e != hipSuccess) return e;
-    kern<<<k_blocks * d.nsplit + 1, sm::WG_THREADS, lds_bytes, stream>>>(d);   // + the reducer block
+    launch_kernel("stream_bwd", kern, k_blocks * d.nsplit + 1, sm::WG_THREADS, lds_bytes, stream, d);   // + the reducer block
     return hipGetLastError();
 }
 
@@ -970,11 +960,8 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     const int nsplit = pick_nsplit(N, K);
     if (nsplit < 1) return hipErrorInvalidValue;     // callers check smallm_bwd_supported first
 
-    prof_before("smallm_prep_bwd", stream);
-    if (a.r <= 8) smallm_prep_bwd_kernel<8><<<n_parts, 256, 0, stream>>>(a.act, a.M, N, a.B, a.r, dYp, Tpart);
-    else if (a.r <= 16) smallm_prep_bwd_kernel<16><<<n_parts, 256, 0, stream>>>(a.act, a.M, N, a.B, a.r, dYp, Tpart);
-    else smallm_prep_bwd_kernel<64><<<n_parts, 256, 0, stream>>>(a.act, a.M, N, a.B, a.r, dYp, Tpart);
-    prof_after(stream);
+    auto prep = a.r <= 8 ? smallm_prep_bwd_kernel<8> : (a.r <= 16 ? smallm_prep_bwd_kernel<16> : smallm_prep_bwd_kernel<64>);
+    launch_kernel("smallm_prep_bwd", prep, n_parts, 256, 0, stream, a.act, a.M, N, a.B, a.r, dYp, Tpart);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
@@ -996,17 +983,13 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     // 4 waves x 4 stages of packed words (3 KB per stage for 4-bit, 2 KB otherwise)
     d.slice_bytes = 32 * 1024;
     const size_t lds_bytes = (size_t)d.slice_bytes + 16 * (size_t)(a.w.bits == 4 ? 3072 : 2048);
-    prof_before("stream_bwd", stream);
     switch (a.w.bits) {
         case 2: e = launch_bwd_bits<2>(d, k_blocks, lds_bytes, stream); break;
         case 3: e = launch_bwd_bits<3>(d, k_blocks, lds_bytes, stream); break;
         default: e = launch_bwd_bits<4>(d, k_blocks, lds_bytes, stream); break;
     }
-    prof_after(stream);
     if (e != hipSuccess) return e;
-    prof_before("stream_bwd_finish", stream);
-    smallm_bwd_finish_kernel<<<k_blocks, sm::WG_THREADS, 0, stream>>>(d);
-    prof_after(stream);
+    launch_kernel("stream_bwd_finish", smallm_bwd_finish_kernel, k_blocks, sm::WG_THREADS, 0, stream, d);
     return hipGetLastError();
 }
 
