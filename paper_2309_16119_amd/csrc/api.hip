@@ -60,7 +60,7 @@ mlr::LayerView view_of(const modulora_qweight *w) {
 
 // Workspace carving, shared by the size query and the entry points.
 struct WsLayout {
-    size_t act_ext, w_ext, p0, p1, gpart, total;
+    size_t act_ext, w_ext, p0, p1, gpart, gemm_part, total;
 };
 
 WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
@@ -68,8 +68,11 @@ WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     // the M <= 16 streaming kernels keep a re-ordered copy of the activations and the
     // adapter partial sums in the workspace (also when r == 0)
     const size_t small = M <= 16 ? mlr::smallm_ws_bytes(K, N, r) : 0;
+    // fp32 partial tiles of the split contraction of the 256 x 256 kernel (also when r == 0)
+    const size_t part = align256(mlr::gemm_partial_bytes(M, K, N));
     if (r <= 0) {
-        l.total = small;
+        l.gemm_part = 0;
+        l.total = small > part ? small : part;
         return l;
     }
     const size_t RE = (size_t)mlr::lora_ext_len(r);
@@ -80,6 +83,7 @@ WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     l.p0 = off;      off += align256((size_t)M * r * 4);
     l.p1 = off;      off += align256((size_t)M * r * 4);
     l.gpart = off;   off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
+    l.gemm_part = off; off += part;
     l.total = off > small ? off : small;
     return l;
 }
@@ -179,6 +183,7 @@ int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M, const 
     g.act = X;
     g.M = M;
     g.out = Y;
+    g.partials = reinterpret_cast<float *>(ws + l.gemm_part);
     if (r > 0) {
         mlr::DownArgs d{};
         d.act = X; d.M = M; d.C = w->d_in; d.r = r;
@@ -225,6 +230,7 @@ int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M,
     g.act = dY;
     g.M = M;
     g.out = dX;
+    g.partials = reinterpret_cast<float *>(ws + l.gemm_part);
     if (r > 0) {
         mlr::DownArgs d{};
         d.act = dY; d.M = M; d.C = w->d_out; d.r = r;

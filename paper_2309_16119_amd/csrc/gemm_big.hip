@@ -18,6 +18,11 @@
 //   - The direct loads are issued from inline assembly and awaited with an explicit
 //     s_waitcnt before the step's barrier; the compiler's own (in-order) vmcnt
 //     bookkeeping for the weight-word loads stays valid, only more conservative.
+//   - 256 x 256 tiles rarely come in multiples of the 256 compute units.  The tiles beyond
+//     the last full round are cut into slices of the contraction (BigPlan): every slice is
+//     a workgroup that leaves its fp32 accumulators, in register order, in a scratch buffer,
+//     and gemm_big_fixup_kernel adds the slices of a tile in a fixed order and runs the same
+//     epilogue.  No atomics and no fences, so results do not depend on timing.
 #include "gemm_common.h"
 
 namespace mlr {
@@ -72,16 +77,82 @@ __device__ __forceinline__ void aload_b128(u32x4 &dst, const void *base, uint32_
     asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
 }
 
+// What a workgroup works on: a whole tile (slice < 0) or slice `slice` of `split` of a tile.
+// Workgroup ids go round-robin over the 8 XCDs; every XCD gets a contiguous run of the whole
+// tiles first (walked row-block-fastest, so neighbours share the weight tile in its L2) and
+// then a contiguous run of the slices.
+struct BigItem {
+    int tile, slice;
+};
+__device__ __forceinline__ BigItem big_item_of_block(int bid, const BigPlan &p) {
+    BigItem it;
+    const int x = bid & 7, q = bid >> 3;
+    const int whole = p.split > 1 ? p.full : p.full + p.tail;
+    const int whole_per_xcd = (whole + 7) >> 3;
+    it.slice = -1;
+    if (q < whole_per_xcd) {
+        it.tile = x * whole_per_xcd + q;
+        if (it.tile >= whole) it.tile = -1;
+        return it;
+    }
+    const int slices = p.split > 1 ? p.tail * p.split : 0;
+    const int slices_per_xcd = (slices + 7) >> 3;
+    const int j = x * slices_per_xcd + (q - whole_per_xcd);
+    if (q - whole_per_xcd >= slices_per_xcd || j >= slices) {
+        it.tile = -1;
+        return it;
+    }
+    it.tile = p.full + j / p.split;
+    it.slice = j % p.split;
+    return it;
+}
+
+// Epilogue of one wave for its i-th block of 32 rows: one RNE to bfloat16; the 32 x 64 patch
+// goes through LDS so that the global stores are 16 bytes per lane and 128 contiguous bytes
+// per row.
+__device__ __forceinline__ void big_epilogue_rows(const f32x16 (&acc_i)[big::TJ], int i, unsigned char *smem, uint16_t *out,
+                                                  int M, int Cout, int m0, int c0, int wave, int lane) {
+    using namespace big;
+    const int wm = wave >> 2, wn = wave & 3;
+    uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + wave * (32 * PATCH_ROW);
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+            patch[prow * PATCH_ROW + j * 32 + (lane & 31)] = float_to_bf16_bits(acc_i[j][v]);
+        }
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the patch is private to the wave
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int idx = lane + q * 64;    // 256 chunks of 16 bytes: 32 rows x 8
+        const int prow = idx / 8, ch = idx % 8;
+        const uint4 v = *reinterpret_cast<const uint4 *>(patch + prow * PATCH_ROW + ch * 8);
+        const int row = m0 + wm * WM + i * 32 + prow;
+        const int col = c0 + wn * WN + ch * 8;
+        if (row < M && col < Cout) *reinterpret_cast<uint4 *>(out + (size_t)row * Cout + col) = v;
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Partial tiles: slice j of the plan owns 256 x 256 floats, stored as 32 float4 per thread
+// in register order ([float4 index][thread]), so writes and reads are fully coalesced.
+__device__ __forceinline__ float4 *big_partial_of(float *partials, int tail_tile, int slice, int split) {
+    return reinterpret_cast<float4 *>(partials) + ((size_t)tail_tile * split + slice) * (size_t)(big::THREADS * 32);
+}
+
 template <int BITS, bool BWD>
-__global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d) {
+__global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, BigPlan plan) {
     using namespace big;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const GemmArgs &a = d.a;
-    const TileCoord tcoord = tile_of_block(blockIdx.x, d.tiles_m, d.tiles_c);
-    if (tcoord.tm < 0) return;   // grid padded to a multiple of 8
+    const BigItem item = big_item_of_block(blockIdx.x, plan);
+    if (item.tile < 0) return;   // grid padded to a multiple of 8
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
-    const int m0 = tcoord.tm * MT, c0 = tcoord.tc * CT;
+    const int m0 = (item.tile % d.tiles_m) * MT, c0 = (item.tile / d.tiles_m) * CT;
     const int K = a.w.K, N = a.w.N;
     const int C = BWD ? N : K;
     const int Cout = BWD ? K : N;
@@ -89,6 +160,11 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d) {
     const int n_main = (C + RT - 1) / RT;
     const int n_ext = (a.RE + RT - 1) / RT;
     const int n_tiles = n_main + n_ext;
+    // this workgroup's share of the full main tiles; the last slice also takes the ragged
+    // tile and the adapter extension
+    const int t0 = item.slice < 0 ? 0 : (int)((long)n_full * item.slice / plan.split);
+    const int t1 = item.slice < 0 ? n_full : (int)((long)n_full * (item.slice + 1) / plan.split);
+    const bool takes_tail = item.slice < 0 || item.slice == plan.split - 1;
     // LDS byte address of the dynamic segment (what M0 wants)
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
@@ -270,17 +346,17 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d) {
     };
 
     // ---- steady state: full main tiles -------------------------------------------
-    if (n_full > 0) {
-        issue_a(0, 0);
-        load_w(0);
+    if (t1 > t0) {
+        issue_a(t0, 0);
+        load_w(t0);
         wait_loads();
         store_w(0);
         __syncthreads();
         if (wave < NWAVES / 2) {
             // this half of the waves: fetch t+1, MFMA tile t, then dequantize t+1
-            for (int t = 0; t < n_full; ++t) {
-                const int cur = t & 1, nxt = cur ^ 1;
-                const int tn = t + 1 < n_full ? t + 1 : n_full - 1;   // clamped repeat, never consumed
+            for (int t = t0; t < t1; ++t) {
+                const int cur = (t - t0) & 1, nxt = cur ^ 1;
+                const int tn = t + 1 < t1 ? t + 1 : t1 - 1;   // clamped repeat, never consumed
                 issue_a(tn, nxt);
                 load_w(tn);
                 mfma_full(smem + cur * BUF_BYTES);
@@ -290,13 +366,13 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d) {
             }
         } else {
             // the other half: dequantize t+1 (fetched a step earlier), fetch t+2, MFMA tile t
-            load_w(n_full > 1 ? 1 : 0);
+            load_w(t0 + 1 < t1 ? t0 + 1 : t0);
             wait_loads();
-            for (int t = 0; t < n_full; ++t) {
-                const int cur = t & 1, nxt = cur ^ 1;
-                issue_a(t + 1 < n_full ? t + 1 : n_full - 1, nxt);
+            for (int t = t0; t < t1; ++t) {
+                const int cur = (t - t0) & 1, nxt = cur ^ 1;
+                issue_a(t + 1 < t1 ? t + 1 : t1 - 1, nxt);
                 store_w(nxt);
-                load_w(t + 2 < n_full ? t + 2 : n_full - 1);
+                load_w(t + 2 < t1 ? t + 2 : t1 - 1);
                 mfma_full(smem + cur * BUF_BYTES);
                 wait_loads();
                 __syncthreads();
@@ -306,7 +382,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d) {
 
     // ---- tail: ragged last main tile and the adapter extension, one at a time, through
     // registers into buffer 0 (predicated; a handful of tiles at most) ---------------
-    for (int t = n_full; t < n_tiles; ++t) {
+    for (int t = takes_tail ? n_full : n_tiles; t < n_tiles; ++t) {
         const bool ext = t >= n_main;
         const int r0 = ext ? (t - n_main) * RT : t * RT;
         const int ld = ext ? a.RE : C;
@@ -380,44 +456,70 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d) {
         __syncthreads();
     }
 
-    // ---- epilogue: one RNE to bfloat16; 32x64 patches go through LDS so that the global
-    // stores are 16 bytes per lane and 128 contiguous bytes per row ---------------------
-    uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + wave * (32 * PATCH_ROW);
+    if (item.slice >= 0) {
+        // a slice: leave the raw accumulators for gemm_big_fixup_kernel
+        float4 *part = big_partial_of(a.partials, item.tile - plan.full, item.slice, plan.split) + tid;
 #pragma unroll
-    for (int i = 0; i < TI; ++i) {
+        for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < TJ; ++j)
+            for (int j = 0; j < TJ; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-                patch[prow * PATCH_ROW + j * 32 + (lane & 31)] = float_to_bf16_bits(acc[i][j][v]);
-            }
-        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the patch is private to the wave
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int idx = lane + q * 64;    // 256 chunks of 16 bytes: 32 rows x 8
-            const int prow = idx / 8, ch = idx % 8;
-            const uint4 v = *reinterpret_cast<const uint4 *>(patch + prow * PATCH_ROW + ch * 8);
-            const int row = m0 + wm * WM + i * 32 + prow;
-            const int col = c0 + wn * WN + ch * 8;
-            if (row < a.M && col < Cout) *reinterpret_cast<uint4 *>(a.out + (size_t)row * Cout + col) = v;
-        }
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_wave_barrier();
+                for (int q = 0; q < 4; ++q)
+                    part[(size_t)(((i * TJ + j) * 4 + q) * THREADS)] =
+                        make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        return;
     }
+#pragma unroll
+    for (int i = 0; i < TI; ++i) big_epilogue_rows(acc[i], i, smem, a.out, a.M, Cout, m0, c0, wave, lane);
+}
+
+// TI workgroups per split tile (workgroup y takes the y-th block of 32 rows of every wave):
+// add the slices in slice order, then the common epilogue.
+__global__ __launch_bounds__(big::THREADS) void gemm_big_fixup_kernel(GemmDev d, BigPlan plan) {
+    using namespace big;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[NWAVES * 32 * PATCH_ROW * 2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
+    const int tile = plan.full + blockIdx.x, i = blockIdx.y;
+    const int m0 = (tile % d.tiles_m) * MT, c0 = (tile / d.tiles_m) * CT;
+    const int Cout = d.a.backward ? d.a.w.K : d.a.w.N;
+    f32x16 acc[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+    for (int sl = 0; sl < plan.split; ++sl) {
+        const float4 *part = big_partial_of(d.a.partials, blockIdx.x, sl, plan.split) + tid;
+        float4 v[TJ * 4];
+#pragma unroll
+        for (int e = 0; e < TJ * 4; ++e) v[e] = part[(size_t)((i * TJ * 4 + e) * THREADS)];
+#pragma unroll
+        for (int e = 0; e < TJ * 4; ++e) {
+            acc[e / 4][4 * (e % 4)] += v[e].x;
+            acc[e / 4][4 * (e % 4) + 1] += v[e].y;
+            acc[e / 4][4 * (e % 4) + 2] += v[e].z;
+            acc[e / 4][4 * (e % 4) + 3] += v[e].w;
+        }
+    }
+    big_epilogue_rows(acc, i, smem, d.a.out, d.a.M, Cout, m0, c0, wave, lane);
 }
 
 template <int BITS, bool BWD>
 static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
     const GemmDev d = make_gemm_dev(a, big::MT, big::CT);
-    const int blocks = (d.tiles_m * d.tiles_c + 7) / 8 * 8;
+    const BigPlan plan = big_plan(a.M, BWD ? a.w.N : a.w.K, BWD ? a.w.K : a.w.N);
+    const int whole = plan.split > 1 ? plan.full : plan.full + plan.tail;
+    const int slices = plan.split > 1 ? plan.tail * plan.split : 0;
+    const int blocks = ((whole + 7) / 8 + (slices + 7) / 8) * 8;
     const size_t lds_bytes = 2 * (size_t)big::BUF_BYTES;
     auto kern = gemm_big_kernel<BITS, BWD>;
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
     if (e != hipSuccess) return e;
-    launch_kernel(BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", kern, blocks, big::THREADS, lds_bytes, stream, d);
+    launch_kernel(BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", kern, blocks, big::THREADS, lds_bytes, stream, d, plan);
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || plan.split <= 1) return err;
+    launch_kernel(BWD ? "gemm_bwd_256x256_fixup" : "gemm_fwd_256x256_fixup", gemm_big_fixup_kernel, dim3(plan.tail, big::TI), big::THREADS, 0,
+                  stream, d, plan);
     return hipGetLastError();
 }
 

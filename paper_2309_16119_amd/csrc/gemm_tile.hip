@@ -661,20 +661,27 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
     if (pick == PICK_AUTO) {
         if (a.M <= 32) pick = PICK_SMALL;
         else {
-            // Cost of one 64-deep contraction step of the whole grid, in microseconds, from
-            // measured per-step times of each variant: alone on a CU (t1) and sharing it with a
-            // second workgroup (t2).  rounds = how often the 256 CUs (x occupancy) are refilled.
+            // Estimated time of the whole grid in microseconds, from measured times of one 64-deep
+            // contraction step of each variant: alone on a CU (t1) and sharing it with a second
+            // workgroup (t2), times how often the 256 CUs (x occupancy) are refilled.  The 256 x 256
+            // kernel cuts the tiles of its last, partial round into slices of the contraction
+            // (BigPlan); that round then costs 1/split of a round plus the traffic of the partial
+            // tiles (written once, read once) and one more launch.
             struct Variant { TilePick pick; int mt, ct, occ; double t1, t2; };
-            const Variant vs[6] = {{PICK_BIG, 256, 256, 1, 1.83, 1.83},
-                                   {PICK_MID, 256, 128, 2, 1.46, 1.95},
+            const Variant vs[5] = {{PICK_MID, 256, 128, 2, 1.46, 1.95},
                                    {PICK_M128, 128, 128, 2, 0.97, 1.40},
                                    {PICK_M64, 64, 128, 2, 0.75, 1.10},
                                    {PICK_M64K, 64, 128, 1, 0.62, 0.62},
                                    {PICK_T128K, 128, 64, 1, 0.57, 0.57}};
-            double best = 1e30;
+            const int C = BWD ? a.w.N : a.w.K;
+            const double steps = (double)C / 64.0;
+            const BigPlan bp = big_plan(a.M, C, Cout);
+            double best = ((double)(bp.full / 256) + (bp.tail ? 1.0 / bp.split : 0.0)) * 1.83 * steps;
+            if (bp.split > 1) best += 4.0 + (double)bp.partial_bytes() / 3.0e6;
+            pick = PICK_BIG;
             for (const Variant &v : vs) {
                 const long tiles = (long)((a.M + v.mt - 1) / v.mt) * ((Cout + v.ct - 1) / v.ct);
-                const double cost = tiles <= 256 ? v.t1 : (double)((tiles + 256 * v.occ - 1) / (256 * v.occ)) * v.t2;
+                const double cost = steps * (tiles <= 256 ? v.t1 : (double)((tiles + 256 * v.occ - 1) / (256 * v.occ)) * v.t2);
                 if (cost < best) { best = cost; pick = v.pick; }
             }
         }

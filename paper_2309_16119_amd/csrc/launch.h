@@ -54,8 +54,37 @@ struct GemmArgs {
     const uint16_t *act_ext;  // bf16 [M][RE]    (NULL when RE == 0)
     const uint16_t *w_ext;    // bf16 [Cout][RE] (NULL when RE == 0)
     int RE;                   // multiple of 16
+    float *partials;          // scratch of gemm_partial_bytes() bytes (split contraction)
 };
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
+
+// How the 256 x 256 kernel fills 256 compute units when the tile count is not a multiple of
+// 256: the first `full` tiles run whole; each of the `tail` remaining ones is cut into
+// `split` slices of the contraction, one workgroup each, which leave fp32 partial tiles
+// that a second small kernel adds up.  split == 1: nothing is cut.
+struct BigPlan {
+    int full, tail, split;
+    size_t partial_bytes() const { return split > 1 ? (size_t)tail * split * (256u * 256u * 4u) : 0; }
+};
+inline BigPlan big_plan(int M, int C, int Cout) {
+    BigPlan p;
+    const long tiles = (long)((M + 255) / 256) * ((Cout + 255) / 256);
+    p.full = (int)(tiles / 256 * 256);
+    p.tail = (int)(tiles - p.full);
+    p.split = 1;
+    if (p.tail > 0 && M > 32) {
+        int s = 256 / p.tail;                 // slices that still fit one round
+        const int by_depth = (C / 64) / 8;    // at least 8 steps of 64 per slice
+        if (s > by_depth) s = by_depth;
+        if (s > 8) s = 8;
+        if (s > 1) p.split = s;
+    }
+    return p;
+}
+inline size_t gemm_partial_bytes(int M, int K, int N) {
+    const size_t f = big_plan(M, K, N).partial_bytes(), b = big_plan(M, N, K).partial_bytes();
+    return f > b ? f : b;
+}
 
 // ---- lora_kernels.hip ----------------------------------------------------------
 // P[m][j] = sum_c act[m][c] * F(c, j)  and the extended operands for launch_gemm.

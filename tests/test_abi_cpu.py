@@ -105,7 +105,10 @@ def test_rejections_bwd_lora():
 
 def test_workspace_bytes():
     w = qw()
-    assert b.lib.modulora_workspace_bytes(ctypes.byref(w), 512, 0) == 0       # r = 0 needs none
+    assert b.lib.modulora_workspace_bytes(ctypes.byref(w), 32, 0) == 0        # r = 0, tile kernels: none
+    # r = 0 at M = 512: 2 x 16 tiles of 256 x 256, each cut into 8 slices of the contraction
+    # that leave fp32 partial tiles
+    assert b.lib.modulora_workspace_bytes(ctypes.byref(w), 512, 0) == 32 * 8 * 256 * 256 * 4
     n8 = b.lib.modulora_workspace_bytes(ctypes.byref(w), 512, 8)
     n16 = b.lib.modulora_workspace_bytes(ctypes.byref(w), 512, 16)
     assert 0 < n8 < n16 and n8 % 256 == 0

@@ -88,6 +88,11 @@ SHAPES = [
     (4, 1152, 640, 13, 40, 128),
     (4, 512, 2304, 1, 16, 512),
     (2, 768, 128, 16, 0, 768),
+    # few 256 x 256 tiles and a deep contraction: the tiles are cut into slices of the
+    # contraction whose partial tiles a second kernel adds (ragged M, N and last 64-deep step)
+    (3, 8224, 328, 200, 8, 32),      # forward: 2 tiles x 8 slices
+    (4, 320, 8232, 300, 16, 64),     # backward: 4 tiles x 8 slices
+    (2, 8192, 512, 256, 0, 128),     # no adapter: the partial tiles are the only scratch
 ]
 
 
