@@ -54,7 +54,8 @@ typedef enum {
     MODULORA_ERR_ALIGN = 5,     /* a pointer is not 16-byte aligned                    */
     MODULORA_ERR_RANK = 6,      /* r < 0, r > 64, or r > 0 with A or B NULL            */
     MODULORA_ERR_WORKSPACE = 7, /* workspace NULL, misaligned or too small             */
-    MODULORA_ERR_HIP = 8        /* a HIP call failed (launch error, wrong device, ...) */
+    MODULORA_ERR_HIP = 8,       /* a HIP call failed (launch error, wrong device, ...) */
+    MODULORA_ERR_HYPER = 9      /* optimizer step or hyper-parameter out of range      */
 } modulora_status;
 
 /*
@@ -141,8 +142,8 @@ int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M,
  *       (X, A) or (dY, B).
  *   dA [d_in][r], dB [r][d_out] float32.  accumulate == 0 overwrites them,
  *       accumulate != 0 adds to their current contents (gradient accumulation over
- *       micro-batches).  The reduction over tokens uses fp32 atomic adds, so the
- *       low-order bits may differ from run to run.
+ *       micro-batches).  The reduction over tokens adds per-chunk partial sums in a
+ *       fixed order (no atomics): results are identical from run to run.
  * r must be >= 1.
  */
 int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float lora_scale,
@@ -150,6 +151,26 @@ int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float l
                       const float *XA, const float *dYBt,
                       float *dA, float *dB, int32_t accumulate,
                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One AdamW step on a flat float32 buffer, in place (the optimizer the paper trains the
+ * adapter factors with, Appendix hyper-parameter tables; Adam with decoupled weight
+ * decay, the decay scaled by the learning rate):
+ *     m <- beta1 m + (1 - beta1) g            v <- beta2 v + (1 - beta2) g^2
+ *     p <- p (1 - lr weight_decay) - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ * Meant for all adapter factors of a model (or of a layer) laid out back to back in
+ * one allocation, so that one launch updates them all.
+ *   param, exp_avg (m), exp_avg_sq (v)  [n] float32 device pointers, updated in place.
+ *   grad                                [n] float32 device pointer, read only.
+ *   step >= 1 is the number of this update (1 for the first).
+ * fp32 arithmetic throughout; beta^step is evaluated on the host in double.
+ * Errors: MODULORA_ERR_NULL, MODULORA_ERR_ALIGN (16-byte), MODULORA_ERR_SHAPE (n == 0),
+ * MODULORA_ERR_HYPER (step < 1, lr < 0, beta outside [0, 1), eps <= 0, weight_decay < 0,
+ * or a non-finite value).  Needs no workspace.
+ */
+int modulora_adamw(float *param, const float *grad, float *exp_avg, float *exp_avg_sq, size_t n,
+                   float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
+                   void *stream);
 
 /*
  * Per-kernel timing for benchmarks.  Between modulora_profile_begin() and

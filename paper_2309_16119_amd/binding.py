@@ -23,7 +23,7 @@ OK = 0
 STATUS_NAMES = {
     0: "MODULORA_OK", 1: "MODULORA_ERR_NULL", 2: "MODULORA_ERR_SHAPE", 3: "MODULORA_ERR_BITS",
     4: "MODULORA_ERR_GROUP", 5: "MODULORA_ERR_ALIGN", 6: "MODULORA_ERR_RANK",
-    7: "MODULORA_ERR_WORKSPACE", 8: "MODULORA_ERR_HIP",
+    7: "MODULORA_ERR_WORKSPACE", 8: "MODULORA_ERR_HIP", 9: "MODULORA_ERR_HYPER",
 }
 
 
@@ -65,6 +65,8 @@ def _load() -> ctypes.CDLL:
     lib.modulora_bwd_input.argtypes = [qp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]
     lib.modulora_bwd_lora.restype = ctypes.c_int
     lib.modulora_bwd_lora.argtypes = [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.modulora_adamw.restype = ctypes.c_int
+    lib.modulora_adamw.argtypes = [vp, vp, vp, vp, sz, f32, f32, f32, f32, f32, i32, vp]
     lib.modulora_profile_begin.restype = ctypes.c_int
     lib.modulora_profile_begin.argtypes = []
     lib.modulora_profile_end.restype = ctypes.c_int
@@ -223,6 +225,16 @@ def modulora_bwd_lora(X: torch.Tensor, dY: torch.Tensor, A: torch.Tensor, B: tor
                                  _ptr(XA), _ptr(dYBt), _ptr(dA), _ptr(dB), 1 if accumulate else 0,
                                  _ptr(ws), nbytes, _stream()), "modulora_bwd_lora")
     return dA, dB
+
+
+def modulora_adamw(param: torch.Tensor, grad: torch.Tensor, exp_avg: torch.Tensor, exp_avg_sq: torch.Tensor,
+                   lr: float, beta1: float, beta2: float, eps: float, weight_decay: float, step: int) -> None:
+    """One AdamW step, in place, on flat float32 buffers of equal length."""
+    n = param.numel()
+    for t in (param, grad, exp_avg, exp_avg_sq):
+        assert t.dtype == torch.float32 and t.numel() == n and t.device == param.device
+    _check(lib.modulora_adamw(_ptr(param), _ptr(grad), _ptr(exp_avg), _ptr(exp_avg_sq), n, float(lr), float(beta1),
+                              float(beta2), float(eps), float(weight_decay), int(step), _stream()), "modulora_adamw")
 
 
 def modulora_profile_begin() -> None:

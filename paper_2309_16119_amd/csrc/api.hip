@@ -7,6 +7,7 @@
 
 #include <cstring>
 #include <string>
+#include <cmath>
 #include <vector>
 
 #include "launch.h"
@@ -137,6 +138,7 @@ const char *modulora_status_string(int status) {
         case MODULORA_ERR_RANK: return "LoRA rank out of range, or A/B missing";
         case MODULORA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case MODULORA_ERR_HIP: return "a HIP call failed";
+        case MODULORA_ERR_HYPER: return "optimizer step or hyper-parameter out of range";
         default: return "unknown status";
     }
 }
@@ -289,6 +291,29 @@ int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float l
     ga.dA = dA; ga.dB = dB; ga.accumulate = accumulate ? 1 : 0;
     ga.partials = reinterpret_cast<float *>(ws + l.gpart);
     return hip_status(mlr::launch_lora_grad_pair(ga, st));
+}
+
+int modulora_adamw(float *param, const float *grad, float *exp_avg, float *exp_avg_sq, size_t n,
+                   float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
+                   void *stream) {
+    if (!param || !grad || !exp_avg || !exp_avg_sq) return MODULORA_ERR_NULL;
+    if (!aligned16(param) || !aligned16(grad) || !aligned16(exp_avg) || !aligned16(exp_avg_sq)) return MODULORA_ERR_ALIGN;
+    if (n == 0) return MODULORA_ERR_SHAPE;
+    const bool finite = std::isfinite(lr) && std::isfinite(beta1) && std::isfinite(beta2) && std::isfinite(eps) &&
+                        std::isfinite(weight_decay);
+    if (!finite || step < 1 || lr < 0.f || beta1 < 0.f || beta1 >= 1.f || beta2 < 0.f || beta2 >= 1.f || eps <= 0.f ||
+        weight_decay < 0.f)
+        return MODULORA_ERR_HYPER;
+    mlr::AdamWArgs a{};
+    a.p = param; a.g = grad; a.m = exp_avg; a.v = exp_avg_sq; a.n = n;
+    a.beta1 = beta1; a.beta2 = beta2;
+    a.one_minus_beta1 = (float)(1.0 - (double)beta1);
+    a.one_minus_beta2 = (float)(1.0 - (double)beta2);
+    a.decay = (float)(1.0 - (double)lr * (double)weight_decay);
+    a.step_size = (float)((double)lr / (1.0 - std::pow((double)beta1, (double)step)));
+    a.inv_sqrt_bc2 = (float)(1.0 / std::sqrt(1.0 - std::pow((double)beta2, (double)step)));
+    a.eps = eps;
+    return hip_status(mlr::launch_adamw(a, static_cast<hipStream_t>(stream)));
 }
 
 int modulora_profile_begin(void) {

@@ -131,6 +131,19 @@ struct GradGeom {
 GradGeom grad_geom(int M, int K, int N, int r);
 hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream);
 
+// ---- optim.hip: AdamW on a flat fp32 buffer ---------------------------------------
+struct AdamWArgs {
+    float *p, *m, *v;
+    const float *g;
+    size_t n;
+    float beta1, beta2, one_minus_beta1, one_minus_beta2;
+    float decay;          // 1 - lr * weight_decay
+    float step_size;      // lr / (1 - beta1^step)
+    float inv_sqrt_bc2;   // 1 / sqrt(1 - beta2^step)
+    float eps;
+};
+hipError_t launch_adamw(const AdamWArgs &a, hipStream_t stream);
+
 // ---- smallm.hip: M <= 16 streaming kernels ------------------------------------
 struct SmallArgs {
     LayerView w;

@@ -47,7 +47,7 @@ def bwd(w, dY=FAKE, M=16, A=FAKE, B=FAKE, r=8, dX=FAKE, T=0, ws=FAKE, wsb=1 << 3
 
 
 def test_status_strings():
-    for code in range(0, 9):
+    for code in range(0, 10):
         assert b.modulora_status_string(code)
     assert "unknown" in b.modulora_status_string(99)
 
@@ -101,6 +101,16 @@ def test_rejections_bwd_lora():
     assert call(A=0) == 6
     assert call(ws=0) == 7
     assert call(wsb=100) == 7
+
+
+def test_rejections_adamw():
+    def call(p=FAKE, g=FAKE, m=FAKE, v=FAKE, n=1024, lr=1e-3, b1=0.9, b2=0.999, eps=1e-8, wd=0.01, step=1):
+        return b.lib.modulora_adamw(p, g, m, v, n, lr, b1, b2, eps, wd, step, None)
+    assert call(p=0) == 1 and call(g=0) == 1 and call(m=0) == 1 and call(v=0) == 1
+    assert call(p=ODD) == 5 and call(v=ODD) == 5
+    assert call(n=0) == 2
+    assert call(step=0) == 9 and call(lr=-1.0) == 9 and call(b1=1.0) == 9 and call(b2=-0.1) == 9
+    assert call(eps=0.0) == 9 and call(wd=-1.0) == 9 and call(lr=float("nan")) == 9 and call(lr=float("inf")) == 9
 
 
 def test_workspace_bytes():
