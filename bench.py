@@ -109,7 +109,80 @@ class Workload:
             raise RuntimeError("library call failed with status %d" % rc)
 
 
-def time_steps(wl: Workload, steps: int, warmup: int, use_graph: bool) -> float:
+class DecoderLayerWorkload:
+    """The seven quantized-LoRA linears of one LLaMA-65B decoder layer (q, k, v, o 8192 x 8192;
+    gate, up 8192 -> 22016; down 22016 -> 8192; 3-bit, group 128, r = 8) run forward in order,
+    backward in reverse order (modulora_bwd_input + modulora_bwd_lora each), then ONE fused AdamW
+    launch over all fourteen adapter factors, which live back to back in one buffer (so do their
+    gradients, which modulora_bwd_lora writes in place).  Attention, norms and activation
+    functions are not part of the method and not run; every linear gets its own activations of
+    the right shape.  Packed weights: 0.30 GB per layer, more than the last-level cache."""
+
+    SHAPES = [("q", 8192, 8192), ("k", 8192, 8192), ("v", 8192, 8192), ("o", 8192, 8192),
+              ("gate", 8192, 22016), ("up", 8192, 22016), ("down", 22016, 8192)]
+
+    def __init__(self, M: int, bits: int = 3, group: int = 128, r: int = 8):
+        import torch
+        from paper_2309_16119_amd import binding as b
+        from paper_2309_16119_amd import synth as synth_mod
+
+        self.b, self.torch, self.M, self.r = b, torch, M, r
+        self.cfgs = [synth_mod.LayerConfig("dec_" + n, K, N, bits, group, M, r) for n, K, N in self.SHAPES]
+        n_flat = sum((K + N) * r for _, K, N in self.SHAPES)
+        self.flat = torch.empty(n_flat, dtype=torch.float32, device="cuda")
+        self.flat_grad = torch.zeros_like(self.flat)
+        self.exp_avg = torch.zeros_like(self.flat)
+        self.exp_avg_sq = torch.zeros_like(self.flat)
+        acts = {}
+        self.layers = []
+        off = 0
+        ws_bytes = 0
+        for i, cfg in enumerate(self.cfgs):
+            L = synth_mod.make_layer_torch(cfg, "cuda", seed=100 + i)
+            w = b.QWeight(L["qweight"], L["scales"], L["zeros"], cfg.K, cfg.N, cfg.bits, cfg.group)
+            for dim, key in ((cfg.K, "X"), (cfg.N, "dY")):
+                acts.setdefault((key, dim), L[key])
+            nA, nB = cfg.K * r, r * cfg.N
+            A, dA = self.flat[off:off + nA].view(cfg.K, r), self.flat_grad[off:off + nA].view(cfg.K, r)
+            B, dB = self.flat[off + nA:off + nA + nB].view(r, cfg.N), self.flat_grad[off + nA:off + nA + nB].view(r, cfg.N)
+            off += nA + nB
+            A.copy_(L["A"])
+            B.copy_(L["B"])
+            ws_bytes = max(ws_bytes, b.modulora_workspace_bytes(w, M, r))
+            self.layers.append(dict(cfg=cfg, w=w, st=w.c_struct(), X=acts[("X", cfg.K)], dY=acts[("dY", cfg.N)],
+                                    A=A, B=B, dA=dA, dB=dB,
+                                    Y=torch.empty((M, cfg.N), dtype=torch.bfloat16, device="cuda"),
+                                    dX=torch.empty((M, cfg.K), dtype=torch.bfloat16, device="cuda"),
+                                    XA=torch.empty((M, r), dtype=torch.float32, device="cuda"),
+                                    dYBt=torch.empty((M, r), dtype=torch.float32, device="cuda")))
+        self.ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.ws_bytes = ws_bytes
+        self.flops = sum(c.flops_fwd_bwd for c in self.cfgs)
+        self.opt_steps = 0
+
+    def step(self, i: int):
+        b, M, r = self.b, self.M, self.r
+        stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
+        p = lambda t: ctypes.c_void_p(t.data_ptr())
+        rc = 0
+        for l in self.layers:
+            rc |= b.lib.modulora_fwd(ctypes.byref(l["st"]), p(l["X"]), M, p(l["A"]), p(l["B"]), r, 2.0, p(l["Y"]),
+                                     p(l["XA"]), p(self.ws), self.ws_bytes, stream)
+        for l in reversed(self.layers):
+            c = l["cfg"]
+            rc |= b.lib.modulora_bwd_input(ctypes.byref(l["st"]), p(l["dY"]), M, p(l["A"]), p(l["B"]), r, 2.0,
+                                           p(l["dX"]), p(l["dYBt"]), p(self.ws), self.ws_bytes, stream)
+            rc |= b.lib.modulora_bwd_lora(c.K, c.N, M, r, 2.0, p(l["X"]), p(l["dY"]), p(l["A"]), p(l["B"]),
+                                          p(l["XA"]), p(l["dYBt"]), p(l["dA"]), p(l["dB"]), 0, p(self.ws),
+                                          self.ws_bytes, stream)
+        self.opt_steps += 1
+        rc |= b.lib.modulora_adamw(p(self.flat), p(self.flat_grad), p(self.exp_avg), p(self.exp_avg_sq),
+                                   self.flat.numel(), 1e-4, 0.9, 0.999, 1e-8, 0.0, self.opt_steps, stream)
+        if rc != 0:
+            raise RuntimeError("library call failed with status %d" % rc)
+
+
+def time_steps(wl, steps: int, warmup: int, use_graph: bool) -> float:
     """Milliseconds per step over exactly `steps` steps (after `warmup` untimed ones)."""
     torch = wl.torch
     for i in range(warmup):
@@ -138,7 +211,7 @@ def time_steps(wl: Workload, steps: int, warmup: int, use_graph: bool) -> float:
     return (t1 - t0) * 1e3 / steps
 
 
-def kernel_profile(wl: Workload, steps: int) -> dict:
+def kernel_profile(wl, steps: int) -> dict:
     """{kernel: (launches, total_ms)} over `steps` eager steps, from HIP events recorded by the
     library around each of its kernel launches (on the stream they are launched on)."""
     b, torch = wl.b, wl.torch
@@ -358,6 +431,20 @@ def main():
                     k: round(ocfg.packed_weight_bytes / (v[1] / v[0] * 1e-3) / 1e9, 1) for k, v in gemm.items()}
             extra.append(entry)
             del w2
+            torch.cuda.empty_cache()
+        # NEXT step of the method: the seven linears of a decoder layer back to back + fused AdamW
+        for M_dec in (2048, 128):
+            dl = DecoderLayerWorkload(M_dec)
+            steps = 5
+            ms3 = time_steps(dl, steps, 2, use_graph)
+            prof3 = kernel_profile(dl, steps)
+            by_family = {}
+            for name, (launches, total_ms) in prof3.items():
+                by_family[name] = round(total_ms / steps * 1e3, 1)       # microseconds per step, all launches
+            extra.append({"workload": "decoder_layer_65b_M%d: 7 linears fwd+bwd + fused AdamW, 3-bit group 128 r=8" % M_dec,
+                          "ms_per_step": round(ms3, 5), "tflops": round(dl.flops / (ms3 * 1e-3) / 1e12, 3),
+                          "tokens_per_s": round(M_dec / (ms3 * 1e-3), 1), "us_per_step_by_kernel": by_family})
+            del dl
             torch.cuda.empty_cache()
         line["extra"] = extra
     print(json.dumps(line))

@@ -7,17 +7,17 @@ so that `paper_2309_16119_amd.synth` (input generators) can be imported on its o
 """
 _BINDING_NAMES = (
     "QWeight", "ModuloraError", "modulora_status_string", "modulora_workspace_bytes",
-    "modulora_dequant", "modulora_fwd", "modulora_bwd_input", "modulora_bwd_lora",
+    "modulora_dequant", "modulora_fwd", "modulora_bwd_input", "modulora_bwd_lora", "modulora_adamw",
     "modulora_profile_begin", "modulora_profile_end", "lib", "LIB_PATH",
 )
-__all__ = list(_BINDING_NAMES) + ["ModuLoRALinear", "LPLoRAFunction"]
+__all__ = list(_BINDING_NAMES) + ["ModuLoRALinear", "LPLoRAFunction", "FusedAdapterAdamW"]
 
 
 def __getattr__(name):
     if name in _BINDING_NAMES:
         from . import binding
         return getattr(binding, name)
-    if name in ("ModuLoRALinear", "LPLoRAFunction"):
+    if name in ("ModuLoRALinear", "LPLoRAFunction", "FusedAdapterAdamW"):
         from . import nn
         return getattr(nn, name)
     raise AttributeError(name)

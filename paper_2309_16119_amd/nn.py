@@ -65,3 +65,45 @@ class ModuLoRALinear(torch.nn.Module):
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         return LPLoRAFunction.apply(x, self.A, self.B, self.w, self.lora_scale)
+
+
+class FusedAdapterAdamW:
+    """AdamW (the optimizer of the paper's Appendix hyper-parameter tables) over the adapter
+    factors of many `ModuLoRALinear` modules with one kernel launch per step.
+
+    All A and B are moved into one flat float32 buffer (each starting on a 16-byte boundary) and
+    become views of it; their `.grad` become views of a second flat buffer, into which autograd
+    accumulates in place.  `step()` is a single `modulora_adamw` call over the whole buffer;
+    `zero_grad()` clears the flat gradient (never sets `.grad` to None, which would detach it).
+    """
+
+    def __init__(self, modules, lr: float = 3e-4, betas=(0.9, 0.999), eps: float = 1e-8, weight_decay: float = 0.0):
+        params = [p for m in modules for p in (m.A, m.B) if p is not None]
+        assert params, "no trainable adapter factors"
+        dev = params[0].device
+        offsets, total = [], 0
+        for p in params:
+            assert p.dtype == torch.float32 and p.device == dev
+            offsets.append(total)
+            total += (p.numel() + 3) // 4 * 4
+        self.flat = torch.zeros(total, dtype=torch.float32, device=dev)
+        self.flat_grad = torch.zeros_like(self.flat)
+        self.exp_avg = torch.zeros_like(self.flat)
+        self.exp_avg_sq = torch.zeros_like(self.flat)
+        with torch.no_grad():
+            for p, off in zip(params, offsets):
+                view = self.flat[off:off + p.numel()].view(p.shape)
+                view.copy_(p.data)
+                p.data = view
+                p.grad = self.flat_grad[off:off + p.numel()].view(p.shape)
+        self.params = params
+        self.lr, self.betas, self.eps, self.weight_decay = lr, betas, eps, weight_decay
+        self.steps = 0
+
+    def zero_grad(self) -> None:
+        self.flat_grad.zero_()
+
+    def step(self) -> None:
+        self.steps += 1
+        b.modulora_adamw(self.flat, self.flat_grad, self.exp_avg, self.exp_avg_sq, self.lr, self.betas[0],
+                         self.betas[1], self.eps, self.weight_decay, self.steps)

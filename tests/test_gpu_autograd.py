@@ -73,3 +73,49 @@ def test_module_starts_as_the_plain_quantized_layer_and_trains():
         losses.append(float(loss.detach()))
     assert losses[-1] < losses[0]
     assert layer.B.grad is not None and layer.A.grad is not None
+
+
+def test_fused_adamw_over_two_modules_matches_the_oracle():
+    """Two layers of different shape in one flat buffer.  (a) autograd accumulates into the flat
+    gradient in place; (b) with seeded gradients written into it, three optimizer steps leave
+    every factor equal to the float64 AdamW oracle applied to that factor alone."""
+    from oracle import optim as oracle_optim
+    from paper_2309_16119_amd.nn import FusedAdapterAdamW
+
+    cfg1 = synth.LayerConfig(name="t1", K=256, N=384, bits=4, group=64, M=48, r=8, seed=5)
+    cfg2 = synth.LayerConfig(name="t2", K=384, N=264, bits=3, group=128, M=48, r=5, seed=6)   # 5 * 264: not a multiple of 4
+    D1, D2 = to_device(synth.make_layer(cfg1)), to_device(synth.make_layer(cfg2))
+    l1, l2 = ModuLoRALinear(D1["w"], r=8, alpha=16.0), ModuLoRALinear(D2["w"], r=5, alpha=10.0)
+    with torch.no_grad():
+        l1.B.copy_(D1["Bd"])
+        l2.B.copy_(D2["Bd"])
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+    hp = {k: float(np.float32(v)) for k, v in hp.items()}
+    opt = FusedAdapterAdamW([l1, l2], lr=hp["lr"], betas=(hp["beta1"], hp["beta2"]), eps=hp["eps"],
+                            weight_decay=hp["weight_decay"])
+    params = [l1.A, l1.B, l2.A, l2.B]
+
+    # (a) backward through both layers lands in the flat gradient buffer
+    grad_ptrs = [p.grad.data_ptr() for p in params]
+    opt.zero_grad()
+    l2(l1(D1["Xd"])).float().square().mean().backward()
+    assert [p.grad.data_ptr() for p in params] == grad_ptrs
+    assert all(bool(torch.any(p.grad != 0)) for p in params)
+    assert int(torch.count_nonzero(opt.flat_grad)) == sum(int(torch.count_nonzero(p.grad)) for p in params)
+
+    # (b) seeded gradients, three steps
+    rng = np.random.default_rng(7)
+    state = [(f64(p.detach()), np.zeros(p.shape), np.zeros(p.shape)) for p in params]
+    for step in range(1, 4):
+        grads = [rng.normal(size=tuple(p.shape)).astype(np.float32) * 0.1 for p in params]
+        opt.zero_grad()
+        with torch.no_grad():
+            for p, g in zip(params, grads):
+                p.grad.copy_(torch.from_numpy(g))
+        opt.step()
+        for i, p in enumerate(params):
+            assert opt.flat.data_ptr() <= p.data_ptr() < opt.flat.data_ptr() + opt.flat.numel() * 4
+            pr, mr, vr = oracle_optim.adamw_step(state[i][0], grads[i], state[i][1], state[i][2], step=step, **hp)
+            tol = step * 2.0 ** -23 * np.abs(pr) + 32 * 2.0 ** -24 * hp["lr"] * step
+            assert np.all(np.abs(f64(p.detach()) - pr) <= tol), (step, i)
+            state[i] = (pr, mr, vr)
