@@ -61,7 +61,7 @@ mlr::LayerView view_of(const modulora_qweight *w) {
 
 // Workspace carving, shared by the size query and the entry points.
 struct WsLayout {
-    size_t act_ext, w_ext, p0, p1, gpart, gemm_part, total;
+    size_t act_ext, w_ext, p0, p1, gpart, gemm_part, dpart, total;
 };
 
 WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
@@ -85,6 +85,7 @@ WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     l.p1 = off;      off += align256((size_t)M * r * 4);
     l.gpart = off;   off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
     l.gemm_part = off; off += part;
+    l.dpart = off;   off += align256(mlr::lora_down_partial_bytes(M, K, N, r));
     l.total = off > small ? off : small;
     return l;
 }
@@ -196,6 +197,7 @@ int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M, const 
         d.RE = mlr::lora_ext_len(r);
         d.w_ext = reinterpret_cast<uint16_t *>(ws + l.w_ext);
         d.Wsrc = B; d.w_from_A = false; d.Cw = w->d_out;
+        d.partials = reinterpret_cast<float *>(ws + l.dpart);
         if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
         g.act_ext = d.act_ext;
         g.w_ext = d.w_ext;
@@ -243,6 +245,7 @@ int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M,
         d.RE = mlr::lora_ext_len(r);
         d.w_ext = reinterpret_cast<uint16_t *>(ws + l.w_ext);
         d.Wsrc = A; d.w_from_A = true; d.Cw = w->d_in;
+        d.partials = reinterpret_cast<float *>(ws + l.dpart);
         if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
         g.act_ext = d.act_ext;
         g.w_ext = d.w_ext;
@@ -274,6 +277,7 @@ int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float l
         d.act = X; d.M = M; d.C = d_in; d.r = r; d.Fm = A; d.f_is_A = true;
         d.P = reinterpret_cast<float *>(ws + l.p0);
         d.lora_scale = lora_scale;
+        d.partials = reinterpret_cast<float *>(ws + l.dpart);
         if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
         XA = d.P;
     }
@@ -282,6 +286,7 @@ int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float l
         d.act = dY; d.M = M; d.C = d_out; d.r = r; d.Fm = B; d.f_is_A = false;
         d.P = reinterpret_cast<float *>(ws + l.p1);
         d.lora_scale = lora_scale;
+        d.partials = reinterpret_cast<float *>(ws + l.dpart);
         if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
         dYBt = d.P;
     }

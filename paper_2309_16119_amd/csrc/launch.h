@@ -107,7 +107,27 @@ struct DownArgs {
     const float *Wsrc;
     bool w_from_A;
     int Cw;
+    float *partials;      // scratch of lora_down_partial_bytes() bytes (few rows: split contraction)
 };
+// Few rows give few workgroups: the contraction is then also split over `lora_down_split()`
+// workgroups per 16 rows, whose partial tiles a second small kernel adds.
+inline int lora_down_split(int M, int C) {
+    const int row_blocks = (M + 15) / 16;
+    if (row_blocks * 16 >= 1024) return 1;            // 16 waves per workgroup fill the chip already
+    int split = (2048 + row_blocks * 16 - 1) / (row_blocks * 16);
+    const int by_depth = C / (32 * 16 * 4);           // at least 4 steps of 32 per wave
+    if (split > by_depth) split = by_depth;
+    if (split > 16) split = 16;
+    return split < 2 ? 1 : split;
+}
+inline size_t lora_down_partial_bytes(int M, int K, int N, int r) {
+    if (r <= 0) return 0;
+    const int sk = lora_down_split(M, K), sn = lora_down_split(M, N);
+    const int split = sk > sn ? sk : sn;
+    if (split <= 1) return 0;
+    const size_t rg = (size_t)(r + 15) / 16;
+    return (size_t)split * (size_t)((M + 15) / 16) * 256u * rg * sizeof(float);
+}
 hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream);
 
 // dA[k][j] (+)= lora_scale * sum_m X[m][k] dYBt[m][j]   and

@@ -51,7 +51,7 @@ __device__ __forceinline__ bf16x8 regs_to_bf16x8(const uint32_t r[4]) {
 // ROWT: 16-row tiles per workgroup (they share every factor operand); UNR: steps whose loads
 // are issued together before any of them is used.
 template <int RG, int ROWT, bool F_IS_A>
-__global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blocks) {
+__global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blocks, int split) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];   // [waves][ROWT][RG][256] partial tiles, then Ps
     constexpr int UNR = RG == 1 ? 4 : (RG == 2 ? 2 : 1);
     constexpr int ROWS = 16 * ROWT;
@@ -59,6 +59,7 @@ __global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blo
     const int r = a.r;
 
     if ((int)blockIdx.x >= row_blocks) {
+        if (blockIdx.y != 0) return;
         // weight-side extension: w_ext[c][e]
         const size_t total = (size_t)a.Cw * a.RE;
         size_t idx = (size_t)(blockIdx.x - row_blocks) * nthreads + tid;
@@ -86,8 +87,10 @@ __global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blo
         if (row > a.M - 1) row = a.M - 1;
         arow[t] = a.act + (size_t)row * a.C;
     }
+    // the contraction is cut over (blockIdx.y, wave)
     const int steps = (a.C + 31) / 32;
-    const int s_begin = (int)((long)steps * wave / nwaves), s_end = (int)((long)steps * (wave + 1) / nwaves);
+    const long part = (long)blockIdx.y * nwaves + wave, parts = (long)split * nwaves;
+    const int s_begin = (int)(steps * part / parts), s_end = (int)(steps * (part + 1) / parts);
 
     f32x4 acc[ROWT][RG];
 #pragma unroll
@@ -160,11 +163,41 @@ __global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blo
         for (int w = 0; w < nwaves; ++w) sum += lds_f[((w * TILES + tile) * 4 + v) * 64 + l];
         const int prow = 16 * (tile / RG) + 4 * (l >> 4) + v, j = (tile % RG) * 16 + (l & 15);
         Ps[prow * (16 * RG) + j] = sum;
+        if (split > 1)   // a slice of the contraction: leave the tile for lora_down_finish_kernel
+            a.partials[((size_t)blockIdx.y * row_blocks + blockIdx.x) * (TILES * 256) + prow * (16 * RG) + j] = sum;
+        else if (m0 + prow < a.M && j < r)
+            a.P[(size_t)(m0 + prow) * r + j] = sum;
+    }
+    if (a.act_ext == nullptr || split > 1) return;
+    __syncthreads();
+    for (int x = tid; x < ROWS * a.RE; x += nthreads) {
+        const int pr = x / a.RE, e = x % a.RE;
+        if (m0 + pr >= a.M) continue;
+        uint16_t v = 0;
+        if (e < 3 * r) {
+            const int seg = e / r, j = e % r;
+            v = split_part(a.lora_scale * Ps[pr * (16 * RG) + j], seg == 2);
+        }
+        a.act_ext[(size_t)(m0 + pr) * a.RE + e] = v;
+    }
+}
+
+// Second stage when the contraction was split over workgroups: add the slices' tiles of 16 rows
+// in slice order, write P and the activation-side extension.
+template <int RG>
+__global__ __launch_bounds__(256) void lora_down_finish_kernel(DownArgs a, int row_blocks, int split) {
+    __shared__ float Ps[16 * 16 * RG];
+    const int tid = threadIdx.x, r = a.r, m0 = blockIdx.x * 16;
+    for (int x = tid; x < 256 * RG; x += 256) {
+        float sum = 0.f;
+        for (int y = 0; y < split; ++y) sum += a.partials[((size_t)y * row_blocks + blockIdx.x) * (256 * RG) + x];
+        Ps[x] = sum;
+        const int prow = x / (16 * RG), j = x % (16 * RG);
         if (m0 + prow < a.M && j < r) a.P[(size_t)(m0 + prow) * r + j] = sum;
     }
     if (a.act_ext == nullptr) return;
     __syncthreads();
-    for (int x = tid; x < ROWS * a.RE; x += nthreads) {
+    for (int x = tid; x < 16 * a.RE; x += 256) {
         const int pr = x / a.RE, e = x % a.RE;
         if (m0 + pr >= a.M) continue;
         uint16_t v = 0;
@@ -193,10 +226,16 @@ static hipError_t launch_down_rg(const DownArgs &a, hipStream_t stream) {
         if (w_blocks < 1) w_blocks = 1;
     }
     const size_t lds = (size_t)(nwaves * RG * ROWT * 256 + ROWS * 16 * RG) * sizeof(float);
+    static_assert(ROWT == 1, "the split path stores one 16-row tile per workgroup");
+    const int split = lora_down_split(a.M, a.C);
+    const dim3 grid(row_blocks + w_blocks, split);
     if (a.f_is_A)
-        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, true>, row_blocks + w_blocks, nthreads, lds, stream, a, row_blocks);
+        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, true>, grid, nthreads, lds, stream, a, row_blocks, split);
     else
-        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, false>, row_blocks + w_blocks, nthreads, lds, stream, a, row_blocks);
+        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, false>, grid, nthreads, lds, stream, a, row_blocks, split);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || split <= 1) return e;
+    launch_kernel("lora_down_finish", lora_down_finish_kernel<RG>, row_blocks, 256, 0, stream, a, row_blocks, split);
     return hipGetLastError();
 }
 

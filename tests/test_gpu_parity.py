@@ -93,6 +93,9 @@ SHAPES = [
     (3, 8224, 328, 200, 8, 32),      # forward: 2 tiles x 8 slices
     (4, 320, 8232, 300, 16, 64),     # backward: 4 tiles x 8 slices
     (2, 8192, 512, 256, 0, 128),     # no adapter: the partial tiles are the only scratch
+    # few rows and a deep contraction: the rank-r projection is split over workgroups too
+    (3, 4096, 264, 40, 40, 128),
+    (4, 256, 6144, 100, 64, 32),
 ]
 
 
