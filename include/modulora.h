@@ -153,6 +153,26 @@ int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float l
                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Round-to-nearest group quantizer and packer (the quantizer Q of Section 2.2 in its
+ * simplest form, the round-to-nearest baseline of the paper's quantizer ablation): turns a
+ * float32 weight into the modulora_qweight storage format.
+ *   W [d_out][d_in] float32 device pointer, d_in contiguous (finite values; per group,
+ *     (max - min) / (2^bits - 1) must not exceed 65504, the largest binary16).
+ *   qweight, scales, zeros: device output buffers of the shapes given at
+ *     modulora_qweight, fully overwritten.
+ * Per group of group_size inputs of an output column, all in IEEE float32 with round
+ * half to even (so the result is defined bit for bit):
+ *     lo = min(group, 0),  hi = max(group, 0)
+ *     scale = the smallest binary16 >= max((hi - lo) / (2^bits - 1), 2^-14)
+ *     zero  = clamp(rne(-lo / scale), 0, 2^bits - 1)
+ *     q     = clamp(rne(w / scale) + zero, 0, 2^bits - 1)
+ * which gives |w - (q - zero) scale| <= scale (1/2 + 2^-20).
+ * Same shape requirements and error codes as a modulora_qweight; needs no workspace.
+ */
+int modulora_quantize_rtn(const float *W, int32_t d_in, int32_t d_out, int32_t bits, int32_t group_size,
+                          uint32_t *qweight, uint16_t *scales, uint8_t *zeros, void *stream);
+
+/*
  * One AdamW step on a flat float32 buffer, in place (the optimizer the paper trains the
  * adapter factors with, Appendix hyper-parameter tables; Adam with decoupled weight
  * decay, the decay scaled by the learning rate):

@@ -7,7 +7,7 @@ so that `paper_2309_16119_amd.synth` (input generators) can be imported on its o
 """
 _BINDING_NAMES = (
     "QWeight", "ModuloraError", "modulora_status_string", "modulora_workspace_bytes",
-    "modulora_dequant", "modulora_fwd", "modulora_bwd_input", "modulora_bwd_lora", "modulora_adamw",
+    "modulora_dequant", "modulora_fwd", "modulora_bwd_input", "modulora_bwd_lora", "modulora_adamw", "modulora_quantize_rtn",
     "modulora_profile_begin", "modulora_profile_end", "lib", "LIB_PATH",
 )
 __all__ = list(_BINDING_NAMES) + ["ModuLoRALinear", "LPLoRAFunction", "FusedAdapterAdamW"]

@@ -65,6 +65,8 @@ def _load() -> ctypes.CDLL:
     lib.modulora_bwd_input.argtypes = [qp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]
     lib.modulora_bwd_lora.restype = ctypes.c_int
     lib.modulora_bwd_lora.argtypes = [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.modulora_quantize_rtn.restype = ctypes.c_int
+    lib.modulora_quantize_rtn.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.modulora_adamw.restype = ctypes.c_int
     lib.modulora_adamw.argtypes = [vp, vp, vp, vp, sz, f32, f32, f32, f32, f32, i32, vp]
     lib.modulora_profile_begin.restype = ctypes.c_int
@@ -225,6 +227,27 @@ def modulora_bwd_lora(X: torch.Tensor, dY: torch.Tensor, A: torch.Tensor, B: tor
                                  _ptr(XA), _ptr(dYBt), _ptr(dA), _ptr(dB), 1 if accumulate else 0,
                                  _ptr(ws), nbytes, _stream()), "modulora_bwd_lora")
     return dA, dB
+
+
+def modulora_quantize_rtn(W: torch.Tensor, bits: int, group_size: int) -> "QWeight":
+    """Round-to-nearest group quantization of W float32 [d_out][d_in] into a QWeight."""
+    assert W.dtype == torch.float32 and W.dim() == 2
+    d_out, d_in = W.shape
+    W = W.contiguous()
+    # an invalid shape: let the library name the error (it validates on the host before touching
+    # any pointer), instead of sizing allocations by it
+    probe = modulora_qweight(d_in, d_out, bits, group_size, 0, 0, 0)
+    if lib.modulora_workspace_bytes(ctypes.byref(probe), 1, 1) == 0:
+        _check(lib.modulora_quantize_rtn(_ptr(W), d_in, d_out, bits, group_size, 0, 0, 0, _stream()),
+               "modulora_quantize_rtn")
+        raise AssertionError("unreachable: invalid shape accepted")
+    G = d_in // group_size
+    q = torch.empty((d_in * bits // 32, d_out), dtype=torch.int32, device=W.device)
+    sc = torch.empty((G, d_out), dtype=torch.float16, device=W.device)
+    z = torch.empty((G, d_out), dtype=torch.uint8, device=W.device)
+    _check(lib.modulora_quantize_rtn(_ptr(W), d_in, d_out, bits, group_size, _ptr(q), _ptr(sc), _ptr(z), _stream()),
+           "modulora_quantize_rtn")
+    return QWeight(q, sc, z, d_in, d_out, bits, group_size)
 
 
 def modulora_adamw(param: torch.Tensor, grad: torch.Tensor, exp_avg: torch.Tensor, exp_avg_sq: torch.Tensor,

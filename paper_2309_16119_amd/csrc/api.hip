@@ -298,6 +298,17 @@ int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float l
     return hip_status(mlr::launch_lora_grad_pair(ga, st));
 }
 
+int modulora_quantize_rtn(const float *W, int32_t d_in, int32_t d_out, int32_t bits, int32_t group_size,
+                          uint32_t *qweight, uint16_t *scales, uint8_t *zeros, void *stream) {
+    modulora_qweight shape{d_in, d_out, bits, group_size, qweight, scales, zeros};
+    const int s = check_layer(&shape);
+    if (s != MODULORA_OK) return s;
+    if (!W) return MODULORA_ERR_NULL;
+    if (!aligned16(W)) return MODULORA_ERR_ALIGN;
+    mlr::QuantArgs q{W, d_in, d_out, bits, group_size, qweight, scales, zeros};
+    return hip_status(mlr::launch_quantize_rtn(q, static_cast<hipStream_t>(stream)));
+}
+
 int modulora_adamw(float *param, const float *grad, float *exp_avg, float *exp_avg_sq, size_t n,
                    float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
                    void *stream) {

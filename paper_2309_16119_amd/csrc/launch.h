@@ -151,6 +151,16 @@ struct GradGeom {
 GradGeom grad_geom(int M, int K, int N, int r);
 hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream);
 
+// ---- quantize.hip: round-to-nearest group quantizer + packer -------------------------
+struct QuantArgs {
+    const float *W;       // fp32 [N][K]
+    int K, N, bits, group;
+    uint32_t *qweight;    // [K*bits/32][N]
+    uint16_t *scales;     // binary16 [K/group][N]
+    uint8_t *zeros;       // [K/group][N]
+};
+hipError_t launch_quantize_rtn(const QuantArgs &a, hipStream_t stream);
+
 // ---- optim.hip: AdamW on a flat fp32 buffer ---------------------------------------
 struct AdamWArgs {
     float *p, *m, *v;

@@ -103,6 +103,15 @@ def test_rejections_bwd_lora():
     assert call(wsb=100) == 7
 
 
+def test_rejections_quantize_rtn():
+    def call(W=FAKE, d_in=4096, d_out=4096, bits=3, group=128, q=FAKE, s=FAKE, z=FAKE):
+        return b.lib.modulora_quantize_rtn(W, d_in, d_out, bits, group, q, s, z, None)
+    assert call(W=0) == 1 and call(q=0) == 1 and call(s=0) == 1 and call(z=0) == 1
+    assert call(W=ODD) == 5 and call(q=ODD) == 5
+    assert call(bits=5) == 3 and call(group=48) == 4 and call(group=96) == 4
+    assert call(d_in=100) == 2 and call(d_out=12) == 2
+
+
 def test_rejections_adamw():
     def call(p=FAKE, g=FAKE, m=FAKE, v=FAKE, n=1024, lr=1e-3, b1=0.9, b2=0.999, eps=1e-8, wd=0.01, step=1):
         return b.lib.modulora_adamw(p, g, m, v, n, lr, b1, b2, eps, wd, step, None)
