@@ -446,6 +446,20 @@ def main():
                           "tokens_per_s": round(M_dec / (ms3 * 1e-3), 1), "us_per_step_by_kernel": by_family})
             del dl
             torch.cuda.empty_cache()
+        # the round-to-nearest quantizer + packer on the largest layer shape
+        Wq = torch.randn((22016, 8192), device="cuda") * 0.02
+        b_mod = __import__("paper_2309_16119_amd.binding", fromlist=["binding"])
+        b_mod.modulora_quantize_rtn(Wq, 3, 128)
+        torch.cuda.synchronize()
+        b_mod.modulora_profile_begin()
+        for _ in range(5):
+            b_mod.modulora_quantize_rtn(Wq, 3, 128)
+        profq = b_mod.modulora_profile_end()
+        us = {k: round(v[1] / v[0] * 1e3, 1) for k, v in profq.items()}
+        extra.append({"workload": "rtn_quantize 22016 x 8192 fp32 -> 3-bit group 128", "kernel_us": us,
+                      "GBps_of_fp32_weight_read": {k: round(Wq.numel() * 4 / (v * 1e-6) / 1e9, 1) for k, v in us.items()}})
+        del Wq
+        torch.cuda.empty_cache()
         line["extra"] = extra
     print(json.dumps(line))
 
