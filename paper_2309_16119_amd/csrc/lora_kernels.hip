@@ -337,29 +337,44 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(GradPairArgs a, 
     }
     __syncthreads();
     if (wave != 0 || !col_ok) return;
+    // a single row chunk is the whole sum: finish here (scale, accumulate flag) in the outputs
+    // themselves, which have the layout of a partial, and skip stage 2
+    const bool direct = g.chunks == 1;
     float *part = a.partials + (size_t)blockIdx.y * ((size_t)(a.K + a.N) * r);
+    float *base_a = direct ? a.dA : part;
+    float *base_b = direct ? a.dB : part + (size_t)a.K * r;
+    const bool add_old = direct && a.accumulate;
 #pragma unroll
     for (int t = 0; t < CPL; ++t) {
         float v[RP];
 #pragma unroll
-        for (int j = 0; j < RP; ++j)
+        for (int j = 0; j < RP; ++j) {
             v[j] = acc[t][j] + red[0][lane][t * RP + j] + red[1][lane][t * RP + j] + red[2][lane][t * RP + j];
+            if (direct) v[j] *= a.lora_scale;
+        }
         if (is_a) {
-            float *dst = part + (size_t)(c + t) * r + j0;
+            float *dst = base_a + (size_t)(c + t) * r + j0;
             if ((r & 3) == 0) {
 #pragma unroll
                 for (int j = 0; j < RP; j += 4)
-                    if (j0 + j < r) *reinterpret_cast<float4 *>(dst + j) = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+                    if (j0 + j < r) {
+                        float4 o = make_float4(v[j], v[j + 1], v[j + 2], v[j + 3]);
+                        if (add_old) {
+                            const float4 old = *reinterpret_cast<const float4 *>(dst + j);
+                            o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+                        }
+                        *reinterpret_cast<float4 *>(dst + j) = o;
+                    }
             } else {
 #pragma unroll
                 for (int j = 0; j < RP; ++j)
-                    if (j0 + j < r) dst[j] = v[j];
+                    if (j0 + j < r) dst[j] = add_old ? dst[j] + v[j] : v[j];
             }
         } else {
-            float *dst = part + (size_t)a.K * r + (size_t)j0 * a.N + (c + t);
+            float *dst = base_b + (size_t)j0 * a.N + (c + t);
 #pragma unroll
             for (int j = 0; j < RP; ++j)
-                if (j0 + j < r) dst[(size_t)j * a.N] = v[j];
+                if (j0 + j < r) dst[(size_t)j * a.N] = add_old ? dst[(size_t)j * a.N] + v[j] : v[j];
         }
     }
 }
@@ -400,7 +415,7 @@ hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream) {
     else if (a.r <= 16) launch_kernel("lora_grad", lora_grad_partial_kernel<16, 4>, grid, 256, 0, stream, a, g);
     else launch_kernel("lora_grad", lora_grad_partial_kernel<32, 2>, grid, 256, 0, stream, a, g);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || g.chunks == 1) return e;
     const size_t n = (size_t)(a.K + a.N) * a.r;
     launch_kernel("lora_grad_reduce", lora_grad_reduce_kernel, (unsigned)((n / 4 + 255) / 256), 256, 0, stream, a, g.chunks);
     return hipGetLastError();
