@@ -137,4 +137,19 @@ __device__ __forceinline__ void dequant_block(const uint32_t *w, const DqConst &
     }
 }
 
+// Exact three-way split of eight fp32 values into bfloat16 pairs: hi + mid + lo carry all 24
+// significand bits, so three bf16 MFMAs against them reproduce the fp32 products.
+__device__ __forceinline__ void split3(const float x[8], uint32_t hi[4], uint32_t mid[4], uint32_t lo[4]) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const float x0 = x[2 * p], x1 = x[2 * p + 1];
+        hi[p] = pack_bf16x2(x0, x1);
+        const float r0 = x0 - __uint_as_float(hi[p] << 16), r1 = x1 - __uint_as_float(hi[p] & 0xFFFF0000u);
+        mid[p] = pack_bf16x2(r0, r1);
+        const float s0 = r0 - __uint_as_float(mid[p] << 16), s1 = r1 - __uint_as_float(mid[p] & 0xFFFF0000u);
+        lo[p] = pack_bf16x2(s0, s1);
+    }
+}
+
+
 }  // namespace mlr

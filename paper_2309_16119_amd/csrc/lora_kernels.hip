@@ -30,18 +30,6 @@ __device__ __forceinline__ uint16_t split_part(float v, bool want_lo) {
 // Lane l = 16 cs + i: activation row i / factor column i, contraction elements 8 cs .. 8 cs + 7
 // of the step.  Extra workgroups (blockIdx.x >= row blocks) write the weight-side extension.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void split3(const float x[8], uint32_t hi[4], uint32_t mid[4], uint32_t lo[4]) {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const float x0 = x[2 * p], x1 = x[2 * p + 1];
-        hi[p] = pack_bf16x2(x0, x1);
-        const float r0 = x0 - __uint_as_float(hi[p] << 16), r1 = x1 - __uint_as_float(hi[p] & 0xFFFF0000u);
-        mid[p] = pack_bf16x2(r0, r1);
-        const float s0 = r0 - __uint_as_float(mid[p] << 16), s1 = r1 - __uint_as_float(mid[p] & 0xFFFF0000u);
-        lo[p] = pack_bf16x2(s0, s1);
-    }
-}
-
 __device__ __forceinline__ bf16x8 regs_to_bf16x8(const uint32_t r[4]) {
     bf16x8 v;
     __builtin_memcpy(&v, r, 16);

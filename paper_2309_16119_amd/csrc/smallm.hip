@@ -21,8 +21,8 @@
 // is two bfloat16 operands (128 + q_a, 128 + q_b) at once.  The +128 is removed with the
 // help of one extra MFMA per step against a vector of ones (it yields sum_k X[m][k], which
 // the zero point needs anyway).  Which two codes share a register is fixed by the bit
-// layout, so the X operand is pre-permuted to the same order by a small prep kernel
-// (which also forms the partial sums of X A for the adapter term).  For 3-bit codes the
+// layout, so every workgroup re-orders its slice of X to the same order on its way into LDS.
+// For 3-bit codes the
 // low field of a register lands four bits high (128 + 16q), compensated by the matching X
 // element divided by 16 -- a power of two, exact.
 #include "device_common.h"
@@ -33,7 +33,7 @@ namespace mlr {
 
 namespace sm {
 constexpr int WG_WAVES = 4, WG_THREADS = WG_WAVES * 64;
-constexpr int PREP_K = 128;            // contraction elements per prep workgroup
+constexpr int PREP_K = 128;            // the contraction length must be a multiple of this
 constexpr int MAX_KSPLIT = 32;         // workgroups that may share a column block
 constexpr uint32_t MAGIC = 0x43004300u;   // two bfloat16 128.0
 constexpr uint32_t ONES = 0x3F803F80u;    // two bfloat16 1.0
@@ -113,94 +113,101 @@ __device__ __forceinline__ void codes_to_operand(const uint32_t *w, int c, const
     }
 }
 
-// Source position (inside its permutation unit) and scale of permuted element `pos`.
-// Unit = 8 codes (3- and 4-bit) or 16 codes (2-bit).
-__device__ __forceinline__ int perm_src(int bits, int pos, float *scale) {
-    *scale = 1.0f;
-    if (bits == 4) return (pos >> 1) + 4 * (pos & 1);
-    if (bits == 2) {
-        const int c = pos >> 3, p = (pos >> 1) & 3, h = pos & 1;
-        return 4 * c + p + 8 * h;
-    }
-    // 3-bit: (X0/16, X4, X1/16, X5, X2/16, X6, X3/16, X7)
-    if ((pos & 1) == 0) *scale = 0.0625f;
-    return (pos >> 1) + 4 * (pos & 1);
-}
 }  // namespace sm
 
 // ---------------------------------------------------------------------------------
-// prep (forward): Xp = X in operand order, stored [K/8][16][8] (rows >= M zero), and per-128-k partial sums of
-// XA = X A.  One workgroup per 128 contraction elements; thread (m, chunk of 8).
+// The rank-r projection of the (at most 16) activation rows, XA = X A or dYBt = dY B^T, for
+// the adapter term: done by the first `nblk` workgroups of a stream kernel beside the
+// streaming ones, on the matrix cores (16x16x32 bf16 MFMA; the fp32 factor split exactly
+// into three bfloat16 terms).  The waves of those workgroups split the contraction; each
+// workgroup leaves one partial [16][r] and the finish kernel adds the nblk of them.
+// Lane l = 16 cs + i: activation row i (rows >= M repeat row M - 1; their results are never
+// used), factor column 16 g + i, contraction elements 8 cs .. 8 cs + 7 of a step of 32.
 // ---------------------------------------------------------------------------------
-template <int RP>
-__global__ __launch_bounds__(256) void smallm_prep_fwd_kernel(const uint16_t *__restrict__ X, int M, int K, int bits,
-                                                              const float *__restrict__ A, int r,
-                                                              uint16_t *__restrict__ Xp, float *__restrict__ Upart,
-                                                              int n_kparts) {
-    __shared__ uint16_t Xs[16][sm::PREP_K + 8];
-    const int t = threadIdx.x, m = t >> 4, ch = t & 15;
-    const int k0 = blockIdx.x * sm::PREP_K;
-    const int kc = k0 + ch * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (m < M && kc < K) v = *reinterpret_cast<const uint4 *>(X + (size_t)m * K + kc);
-    *reinterpret_cast<uint4 *>(&Xs[m][ch * 8]) = v;
-
-    // adapter partial sums over this thread's 8 elements
-    if (r > 0) {
-        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-        float acc[RP];
+template <bool F_IS_A>
+__device__ __forceinline__ void smallm_project(const uint16_t *act, int M, int C, const float *F, int r, int blk,
+                                               int nblk, float *parts, float *red /* LDS, 4 * 4 * 256 floats */) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 15, cs = lane >> 4;
+    const uint16_t *arow = act + (size_t)(i < M ? i : M - 1) * C;
+    const int steps = C / 32;
+    const long part = (long)blk * sm::WG_WAVES + wave, nparts = (long)nblk * sm::WG_WAVES;
+    const int s0 = (int)(steps * part / nparts), s1 = (int)(steps * (part + 1) / nparts);
+    const int RG = (r + 15) >> 4;
+    f32x4 acc[4];
 #pragma unroll
-        for (int j = 0; j < RP; ++j) acc[j] = 0.f;
-        if (kc < K) {
+    for (int g = 0; g < 4; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int st = s0; st < s1; st += 2) {
+        uint4 av[2];
+        bool ok[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float x = (e & 1) ? __uint_as_float(u[e >> 1] & 0xFFFF0000u) : __uint_as_float(u[e >> 1] << 16);
-                const float *arow = A + (size_t)(kc + e) * r;
-                if (r == RP) {
+        for (int q = 0; q < 2; ++q) {
+            ok[q] = st + q < s1;
+            av[q] = make_uint4(0, 0, 0, 0);
+            if (ok[q]) av[q] = *reinterpret_cast<const uint4 *>(arow + (st + q) * 32 + cs * 8);
+        }
 #pragma unroll
-                    for (int j = 0; j < RP; j += 4) {
-                        const float4 q = *reinterpret_cast<const float4 *>(arow + j);
-                        acc[j] = __builtin_fmaf(x, q.x, acc[j]);
-                        acc[j + 1] = __builtin_fmaf(x, q.y, acc[j + 1]);
-                        acc[j + 2] = __builtin_fmaf(x, q.z, acc[j + 2]);
-                        acc[j + 3] = __builtin_fmaf(x, q.w, acc[j + 3]);
+        for (int g = 0; g < 4; ++g) {
+            if (g >= RG) break;
+            const int j = g * 16 + i;
+            float f[2][8];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int c = (st + q) * 32 + cs * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[q][e] = 0.f;
+                if (ok[q] && j < r) {
+                    if (F_IS_A) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) f[q][e] = F[(size_t)(c + e) * r + j];
+                    } else {
+                        const float4 q0 = *reinterpret_cast<const float4 *>(F + (size_t)j * C + c);
+                        const float4 q1 = *reinterpret_cast<const float4 *>(F + (size_t)j * C + c + 4);
+                        f[q][0] = q0.x; f[q][1] = q0.y; f[q][2] = q0.z; f[q][3] = q0.w;
+                        f[q][4] = q1.x; f[q][5] = q1.y; f[q][6] = q1.z; f[q][7] = q1.w;
                     }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < RP; ++j)
-                        if (j < r) acc[j] = __builtin_fmaf(x, arow[j], acc[j]);
                 }
             }
-        }
 #pragma unroll
-        for (int j = 0; j < RP; ++j) {
-            float s = acc[j];
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-            if (ch == 0 && j < r) Upart[((size_t)blockIdx.x * 16 + m) * r + j] = s;
+            for (int q = 0; q < 2; ++q) {
+                uint32_t hi[4], mid[4], lo[4];
+                split3(f[q], hi, mid, lo);
+                const bf16x8 a = sm::as_bf16x8(av[q]);
+                acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(hi), acc[g], 0, 0, 0);
+                acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(mid), acc[g], 0, 0, 0);
+                acc[g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(lo), acc[g], 0, 0, 0);
+            }
         }
+    }
+    // D register v of lane (i, cs): row 4 cs + v, column 16 g + i
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[((wave * 4 + g) * 4 + v) * 64 + lane] = acc[g][v];
+    __syncthreads();
+    float *mine = parts + (size_t)blk * 16 * r;
+    for (int x = tid; x < RG * 256; x += sm::WG_THREADS) {
+        const int g = x >> 8, v = (x >> 6) & 3, l = x & 63;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < sm::WG_WAVES; ++w) sum += red[((w * 4 + g) * 4 + v) * 64 + l];
+        const int prow = 4 * (l >> 4) + v, j = g * 16 + (l & 15);
+        if (j < r) mine[prow * r + j] = sum;
+    }
+}
+
+// Sum of the projection workgroups' partials into Us (16 x r floats in LDS).
+__device__ __forceinline__ void smallm_sum_parts(const float *parts, int n_parts, int r, float *Us) {
+    for (int t = threadIdx.x; t < 16 * r; t += sm::WG_THREADS) {
+        float v[16];                           // n_parts <= 16: all loads in flight together
+#pragma unroll
+        for (int b = 0; b < 16; ++b) v[b] = b < n_parts ? parts[(size_t)b * 16 * r + t] : 0.f;
+        float sum = 0.f;
+#pragma unroll
+        for (int b = 0; b < 16; ++b) sum += v[b];
+        Us[t] = sum;
     }
     __syncthreads();
-    if (kc >= K) return;
-    // permuted (and for 3-bit partly scaled) copy of this thread's chunk
-    const int unit = bits == 2 ? 16 : 8;
-    uint16_t o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int pos = (ch * 8 + e) % unit, ubase = (ch * 8 + e) - pos;
-        float sc;
-        const int src = sm::perm_src(bits, pos, &sc);
-        const uint16_t xb = Xs[m][ubase + src];
-        o[e] = sc == 1.0f ? xb : float_to_bf16_bits(bf16_bits_to_float(xb) * sc);
-    }
-    uint4 ov;
-    ov.x = o[0] | ((uint32_t)o[1] << 16);
-    ov.y = o[2] | ((uint32_t)o[3] << 16);
-    ov.z = o[4] | ((uint32_t)o[5] << 16);
-    ov.w = o[6] | ((uint32_t)o[7] << 16);
-    // operand layout [chunk of 8][row m][8]: the 16 rows of one chunk are 256 contiguous bytes,
-    // which is what the 16 lanes of a lane group fetch together
-    *reinterpret_cast<uint4 *>(Xp + ((size_t)(kc >> 3) * 16 + m) * 8) = ov;
 }
 
 // ---------------------------------------------------------------------------------
@@ -216,11 +223,11 @@ __global__ __launch_bounds__(256) void smallm_prep_fwd_kernel(const uint16_t *__
 // ---------------------------------------------------------------------------------
 struct SmallFwdDev {
     LayerView w;
-    const uint16_t *Xp;     // [K/8][16][8] operand order
-    const float *Upart;     // [K/128][16][r]
-    float *Ufinal;          // [16][r]: XA, summed by the reducer block of the stream kernel
+    const uint16_t *X;      // [M][K]
+    const float *A;         // [K][r]
+    float *Upart;           // [n_proj][16][r]: partials of XA = X A, left by the projection workgroups
     const float *B;         // [r][N]
-    int M, r, n_kparts;
+    int M, r, n_proj;       // n_proj: workgroups of the stream kernel that do the projection
     int ksplit;             // workgroups that share one column block (split of the groups along K)
     float lora_scale;
     uint16_t *Y;            // [M][N]
@@ -233,6 +240,10 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void ald(u32x4 &dst, const void *base, uint32_t voff) {
     asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
+}
+// the same without the non-temporal hint, for data that other workgroups read again
+__device__ __forceinline__ void ald_cached(u32x4 &dst, const void *gaddr_lane) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(gaddr_lane) : "memory");
 }
 __device__ __forceinline__ void ald(u32x2 &dst, const void *base, uint32_t voff) {
     asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
@@ -261,6 +272,20 @@ __device__ __forceinline__ void wait_vm() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
+// wait_vm<BASE + extra>() for 0 <= extra < 8 known after unrolling
+template <int BASE>
+__device__ __forceinline__ void wait_vm_plus(int extra) {
+    switch (extra) {
+        case 0: wait_vm<BASE>(); break;
+        case 1: wait_vm<BASE + 1>(); break;
+        case 2: wait_vm<BASE + 2>(); break;
+        case 3: wait_vm<BASE + 3>(); break;
+        case 4: wait_vm<BASE + 4>(); break;
+        case 5: wait_vm<BASE + 5>(); break;
+        case 6: wait_vm<BASE + 6>(); break;
+        default: wait_vm<BASE + 7>(); break;
+    }
+}
 template <typename T>
 __device__ __forceinline__ void tie(T &x) {
     asm volatile("" : "+v"(x)::"memory");
@@ -269,31 +294,6 @@ constexpr int WCOLS = 64;                 // columns per wave (4 per lane of a 1
 constexpr int BCOLS = WG_WAVES * WCOLS;   // columns per workgroup
 constexpr int MAX_RANGE = 2048;           // contraction elements of one K slice (64 KB of LDS)
 }  // namespace sm
-
-// Sum of a prep kernel's partials [n_parts][16][r] into Us (16 x r floats in LDS): element t of the tile
-// is summed by WG_THREADS / (16 r) threads over interleaved slices of the partials, eight
-// independent loads at a time, and the slices meet through LDS atomics.
-__device__ __forceinline__ void smallm_gather_parts(const float *parts, int n_parts, int r, float *Us) {
-    const int tid = threadIdx.x;
-    const int ur = 16 * r;
-    for (int t = tid; t < ur; t += sm::WG_THREADS) Us[t] = 0.f;
-    __syncthreads();
-    if (r > 0) {
-        const int slices = sm::WG_THREADS >= ur ? sm::WG_THREADS / ur : 1;
-        for (int t = tid; t < slices * ur; t += sm::WG_THREADS) {
-            const int mj = t % ur, slice = t / ur;
-            float acc8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            int kb = slice;
-            for (; kb + 7 * slices < n_parts; kb += 8 * slices) {
-#pragma unroll
-                for (int u = 0; u < 8; ++u) acc8[u] += parts[(size_t)(kb + u * slices) * ur + mj];
-            }
-            for (; kb < n_parts; kb += slices) acc8[0] += parts[(size_t)kb * ur + mj];
-            atomicAdd(&Us[mj], ((acc8[0] + acc8[1]) + (acc8[2] + acc8[3])) + ((acc8[4] + acc8[5]) + (acc8[6] + acc8[7])));
-        }
-    }
-    __syncthreads();
-}
 
 // Adds the adapter term to the four adjacent outputs y[0..3] of row m, columns col..col+3
 // (col a multiple of 4, col + 3 < N) and stores them as bfloat16.
@@ -317,18 +317,14 @@ template <int BITS>
 __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdDev d) {
     using G = sm::Geo<BITS>;
     extern __shared__ __attribute__((aligned(16))) uint4 xs[];   // [chunks of the slice][16 rows]
-    __shared__ float Us[16 * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if (blockIdx.x == 0) {
-        // reducer block: XA = sum of the prep kernel's partials, for the finish kernel and the
-        // caller; it runs beside the streaming blocks, so its latency-bound gather costs nothing
-        smallm_gather_parts(d.Upart, d.n_kparts, d.r, Us);
-        for (int t = tid; t < 16 * d.r; t += sm::WG_THREADS) d.Ufinal[t] = Us[t];
-        if (d.XA != nullptr)
-            for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
+    if ((int)blockIdx.x < d.n_proj) {
+        // projection workgroups: partials of XA = X A for the finish kernel; they run beside the
+        // streaming ones and are done long before them
+        smallm_project<true>(d.X, d.M, d.w.K, d.A, d.r, blockIdx.x, d.n_proj, d.Upart, reinterpret_cast<float *>(xs));
         return;
     }
-    const int bid = blockIdx.x - 1;
+    const int bid = blockIdx.x - d.n_proj;
     const int i = lane & 15, j = lane >> 4;
     const int N = d.w.N, group = d.w.group;
     const int cb = bid / d.ksplit, ks = bid % d.ksplit;   // column block, K slice
@@ -363,20 +359,86 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdD
         sm::ald(sd.sc, d.w.scales + (size_t)g * N, s_voff);
         sm::ald(sd.z, d.w.zeros + (size_t)g * N, z_voff);
     };
-    // The slice of the re-ordered activations, a contiguous run of 16-byte operand rows, goes
-    // straight from global memory into LDS: 1 KB per wave and load, the waves take turns.
-    // (A slice is a multiple of 32 contraction elements, i.e. of 1 KB.)  These loads are
-    // issued first, so they are the oldest ones in flight.
+    // The workgroup's slice of X goes into LDS in operand order: chunk c of 8 contraction
+    // elements, row m at xs[16 c + m].  Inside a chunk the elements are re-ordered to the pairing
+    // the code registers have (4- and 3-bit: (0,4,1,5,2,6,3,7); 2-bit: over two chunks,
+    // (0,8,1,9,2,10,3,11) and (4,12,5,13,6,14,7,15)), and for 3-bit the even positions are
+    // divided by 16.  Thread t takes row t % 16 of chunk t / 16 (+ 16 per pass): 64 contiguous
+    // bytes per row and wave, conflict-free 16-byte LDS stores.  Rows >= M are zero.
+    // The loads of the first pass (up to 1024 contraction elements, the usual slice) are issued
+    // from assembly BEFORE the weight stages, so they return first and the re-ordering runs
+    // while the weights are in flight; every lane issues all of them (clamped addresses, masked
+    // afterwards), which keeps the load count the waits rely on.  Later passes use ordinary
+    // loads (they wait for the stages issued before them).
     {
-        const char *src = reinterpret_cast<const char *>(d.Xp) + (size_t)s_begin * (G::KSTEP / 8) * 256;
-        const int n_kb = (s_end - s_begin) * (G::KSTEP / 8) / 4;          // 1 KB units
-        const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)xs;
-        for (int u = wave; u < n_kb; u += sm::WG_WAVES) sm::ald_lds(src + (size_t)u * 1024, (uint32_t)lane * 16u, lds0 + (uint32_t)u * 1024u);
-    }
+        const int k_begin = s_begin * G::KSTEP, n_chunks = (s_end - s_begin) * (G::KSTEP / 8);
+        const int m = tid & 15;
+        const uint16_t *xrow = d.X + (size_t)(m < d.M ? m : 0) * d.w.K + k_begin;
+        constexpr int BATCH = 8;
+        static_assert(DEPTH * SL + BATCH - 1 < 64, "vmcnt is a 6-bit counter");
+        sm::u32x4 first[BATCH];
 #pragma unroll
-    for (int dd = 0; dd < DEPTH; ++dd) issue(st[dd], s_begin + dd < s_end ? s_begin + dd : s_end - 1);
-    // everything older than the DEPTH stages has landed: this wave's part of the slice is in LDS
-    sm::wait_vm<DEPTH * SL>();
+        for (int u = 0; u < BATCH; ++u) {
+            const int c = (tid >> 4) + 16 * u;
+            sm::ald_cached(first[u], xrow + 8 * (c < n_chunks ? c : n_chunks - 1));
+        }
+#pragma unroll
+        for (int dd = 0; dd < DEPTH; ++dd) issue(st[dd], s_begin + dd < s_end ? s_begin + dd : s_end - 1);
+        // re-order one chunk (all lanes of the wave call this together) and store it
+        auto reorder_store = [&](const uint4 &raw, int c) {
+            uint32_t ow[4];
+            if (BITS == 2) {
+                // the partner chunk c ^ 1 is held by lane ^ 16 (n_chunks is even: both or neither in range)
+                uint4 pr;
+                pr.x = __shfl_xor(raw.x, 16, 64);
+                pr.y = __shfl_xor(raw.y, 16, 64);
+                pr.z = __shfl_xor(raw.z, 16, 64);
+                pr.w = __shfl_xor(raw.w, 16, 64);
+                const bool odd = (c & 1) != 0;
+                const uint32_t a0 = odd ? pr.z : raw.x, a1 = odd ? pr.w : raw.y;      // elements 4h .. 4h+3 of the unit
+                const uint32_t b0 = odd ? raw.z : pr.x, b1 = odd ? raw.w : pr.y;      // elements 8 + 4h .. 8 + 4h+3
+                ow[0] = __builtin_amdgcn_perm(b0, a0, 0x05040100u);
+                ow[1] = __builtin_amdgcn_perm(b0, a0, 0x07060302u);
+                ow[2] = __builtin_amdgcn_perm(b1, a1, 0x05040100u);
+                ow[3] = __builtin_amdgcn_perm(b1, a1, 0x07060302u);
+            } else {
+                ow[0] = __builtin_amdgcn_perm(raw.z, raw.x, 0x05040100u);   // (x0, x4)
+                ow[1] = __builtin_amdgcn_perm(raw.z, raw.x, 0x07060302u);   // (x1, x5)
+                ow[2] = __builtin_amdgcn_perm(raw.w, raw.y, 0x05040100u);   // (x2, x6)
+                ow[3] = __builtin_amdgcn_perm(raw.w, raw.y, 0x07060302u);   // (x3, x7)
+                if (BITS == 3) {
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const uint32_t scaled = float_to_bf16_bits(__uint_as_float(ow[p] << 16) * 0.0625f);
+                        ow[p] = (ow[p] & 0xFFFF0000u) | scaled;
+                    }
+                }
+            }
+            if (c < n_chunks) xs[(size_t)c * 16 + m] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        };
+        // first pass: every thread waits for and ties every one of its loads, in range or not
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int c = (tid >> 4) + 16 * u;
+            // the weight stages and the BATCH - 1 - u younger loads of this pass stay in flight
+            sm::wait_vm_plus<DEPTH * SL>(BATCH - 1 - u);
+            sm::tie(first[u]);
+            const bool in = c < n_chunks && m < d.M;
+            reorder_store(make_uint4(in ? first[u][0] : 0u, in ? first[u][1] : 0u, in ? first[u][2] : 0u, in ? first[u][3] : 0u), c);
+        }
+        // later passes (slices of more than 1024 contraction elements); uniform trip count per wave pair
+        for (int c0 = 16 * BATCH; c0 < n_chunks; c0 += 16 * BATCH) {
+            uint4 raw[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int c = c0 + (tid >> 4) + 16 * u;
+                raw[u] = make_uint4(0, 0, 0, 0);
+                if (c < n_chunks && m < d.M) raw[u] = *reinterpret_cast<const uint4 *>(xrow + 8 * c);
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) reorder_store(raw[u], c0 + (tid >> 4) + 16 * u);
+        }
+    }
     __syncthreads();
 
     f32x4 yacc[4], tmp[4], s1, s2;
@@ -486,8 +548,9 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
             y[0] += v.x; y[1] += v.y; y[2] += v.z; y[3] += v.w;
         }
     }
-    for (int t = tid; t < 16 * d.r; t += sm::WG_THREADS) Us[t] = d.Ufinal[t];
-    __syncthreads();
+    smallm_sum_parts(d.Upart, d.n_proj, d.r, Us);
+    if (blockIdx.x == 0 && d.XA != nullptr)
+        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
     if (m < d.M && col < N) smallm_store4(d, Us, m, col, y);
 }
 
@@ -505,44 +568,16 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
 // Rounding dY * scale to bfloat16 moves the result by at most 2^-9 sum_n |dY| |What|, the
 // same size as the rounding of What in the materialized form.
 //
-// prep: dYp = dY stored [N/8][16][8] (rows >= M zero) and per-128-n partial sums of
-// dYBt = dY B^T.  One workgroup per 128 contraction elements; thread (m, chunk of 8).
+// The workgroup's slice of dY sits in LDS as [chunks of 8 n][16 rows][8] (copied there directly
+// from dY, 64 contiguous bytes per row and load).
 // ---------------------------------------------------------------------------------
-template <int RP>
-__global__ __launch_bounds__(256) void smallm_prep_bwd_kernel(const uint16_t *__restrict__ dY, int M, int N,
-                                                              const float *__restrict__ B, int r,
-                                                              uint16_t *__restrict__ dYp, float *__restrict__ Tpart) {
-    const int t = threadIdx.x, m = t >> 4, ch = t & 15;
-    const int nc = blockIdx.x * sm::PREP_K + ch * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (m < M) v = *reinterpret_cast<const uint4 *>(dY + (size_t)m * N + nc);
-    *reinterpret_cast<uint4 *>(dYp + ((size_t)(nc >> 3) * 16 + m) * 8) = v;
-    if (r <= 0) return;
-    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-    float x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = (e & 1) ? __uint_as_float(u[e >> 1] & 0xFFFF0000u) : __uint_as_float(u[e >> 1] << 16);
-#pragma unroll
-    for (int jj = 0; jj < RP; ++jj) {
-        float s = 0.f;
-        if (jj < r) {
-            const float4 b0 = *reinterpret_cast<const float4 *>(B + (size_t)jj * N + nc);
-            const float4 b1 = *reinterpret_cast<const float4 *>(B + (size_t)jj * N + nc + 4);
-            s = x[0] * b0.x + x[1] * b0.y + x[2] * b0.z + x[3] * b0.w + x[4] * b1.x + x[5] * b1.y + x[6] * b1.z + x[7] * b1.w;
-        }
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-        if (ch == 0 && jj < r) Tpart[((size_t)blockIdx.x * 16 + m) * r + jj] = s;
-    }
-}
-
 struct SmallBwdDev {
     LayerView w;
-    const uint16_t *dYp;    // [N/8][16][8]
-    const float *Tpart;     // [N/128][16][r]
-    float *Tfinal;          // [16][r]: dYBt, summed by the reducer block of the stream kernel
+    const uint16_t *dY;     // [M][N]
+    const float *B;         // [r][N]
+    float *Tpart;           // [n_proj][16][r]: partials of dYBt = dY B^T, left by the projection workgroups
     const float *A;         // [K][r]
-    int M, r, n_parts;
+    int M, r, n_proj;       // n_proj: workgroups of the stream kernel that do the projection
     int nsplit;             // workgroups that share one 128-column tile (split of N)
     float lora_scale;
     uint16_t *dX;           // [M][K]
@@ -584,17 +619,13 @@ __device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const fl
 template <int BITS>
 __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdDev d) {
     extern __shared__ __attribute__((aligned(16))) uint4 ys[];   // [chunks of 8 n of the slice][16 rows]
-    __shared__ float Ts[16 * 64];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if (blockIdx.x == 0) {
-        // reducer block: dYBt = sum of the prep kernel's partials (see the forward kernel)
-        smallm_gather_parts(d.Tpart, d.n_parts, d.r, Ts);
-        for (int t = tid; t < 16 * d.r; t += sm::WG_THREADS) d.Tfinal[t] = Ts[t];
-        if (d.T_out != nullptr)
-            for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.T_out[t] = Ts[t];
+    if ((int)blockIdx.x < d.n_proj) {
+        // projection workgroups: partials of dYBt = dY B^T (see the forward kernel)
+        smallm_project<false>(d.dY, d.M, d.w.N, d.B, d.r, blockIdx.x, d.n_proj, d.Tpart, reinterpret_cast<float *>(ys));
         return;
     }
-    const int bid = blockIdx.x - 1;
+    const int bid = blockIdx.x - d.n_proj;
     const int i = lane & 15, j = lane >> 4, b = i & 3, u = i >> 2;
     const int N = d.w.N, K = d.w.K;
     const int kb = bid / d.nsplit, ns = bid % d.nsplit;
@@ -659,10 +690,13 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     };
     auto clamp_step = [&](int s) { return s < S1 ? s : S1 - 1; };
 
-    // the slice of dY goes straight into LDS, 1 KB (one step) per wave and load
+    // the slice of dY goes straight into LDS, 1 KB (one step: 4 chunks of 8 n x 16 rows) per wave
+    // and load: lane l fetches row l % 16 (rows >= M repeat row M - 1; their results are never
+    // stored), chunk l / 16 of the step, and lands at byte 16 l of the step's 1 KB
     {
-        const char *src = reinterpret_cast<const char *>(d.dYp) + (size_t)S0 * 1024;
-        for (int q = wave; q < S1 - S0; q += sm::WG_WAVES) sm::ald_lds(src + (size_t)q * 1024, (uint32_t)lane * 16u, lds0 + (uint32_t)q * 1024u);
+        const int row = (lane & 15) < d.M ? (lane & 15) : d.M - 1;
+        const char *src = reinterpret_cast<const char *>(d.dY + (size_t)row * N + (size_t)S0 * smb::NSTEP + (lane >> 4) * 8);
+        for (int q = wave; q < S1 - S0; q += sm::WG_WAVES) sm::ald_lds64(src + (size_t)q * (smb::NSTEP * 2), lds0 + (uint32_t)q * 1024u);
     }
 #pragma unroll
     for (int dd = 0; dd < DEPTH; ++dd) issue(dd, clamp_step(W0 + dd));
@@ -805,8 +839,9 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(Small
             y[4] += v1.x; y[5] += v1.y; y[6] += v1.z; y[7] += v1.w;
         }
     }
-    for (int t = tid; t < 16 * d.r; t += sm::WG_THREADS) Ts[t] = d.Tfinal[t];
-    __syncthreads();
+    smallm_sum_parts(d.Tpart, d.n_proj, d.r, Ts);
+    if (blockIdx.x == 0 && d.T_out != nullptr)
+        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.T_out[t] = Ts[t];
     if (m < d.M) smallm_bwd_store8(d, Ts, m, k0, y);
 }
 
@@ -866,16 +901,22 @@ bool smallm_fwd_supported(const LayerView &w, int M) {
 
 namespace {
 struct SmallWs {
-    size_t xp, upart, ufinal, yacc, total;
+    size_t upart, yacc, total;
 };
+// workgroups that do the rank-r projection beside the streaming ones: one per 512 contraction
+// elements (four steps of 32 per wave), at most 16
+int n_proj_blocks(int C, int r) {
+    if (r <= 0) return 0;
+    int n = C / 512;
+    return n < 1 ? 1 : (n > 16 ? 16 : n);
+}
 SmallWs small_ws(int K, int N, int r) {
     const size_t kmax = (size_t)(K > N ? K : N);
     auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
     SmallWs l;
     size_t off = 0;
-    l.xp = off;      off += al((size_t)16 * kmax * 2);
-    l.upart = off;   off += al(((kmax + sm::PREP_K - 1) / sm::PREP_K) * 16 * (size_t)(r > 0 ? r : 1) * 4);
-    l.ufinal = off;  off += al((size_t)16 * 64 * 4);
+    (void)kmax;
+    l.upart = off;   off += al((size_t)16 * 16 * (size_t)(r > 0 ? r : 1) * 4);
     const size_t yf = (size_t)ksplit_bound(K, N) * 16 * N, yb = (size_t)sm::MAX_KSPLIT * 16 * K;
     l.yacc = off;    off += al((yf > yb ? yf : yb) * 4);
     l.total = off;
@@ -891,7 +932,7 @@ static hipError_t launch_fwd_bits(const SmallFwdDev &d, int col_blocks, size_t l
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
     if (e != hipSuccess) return e;
-    launch_kernel("stream_fwd", kern, col_blocks * d.ksplit + 1, sm::WG_THREADS, lds_bytes, stream, d);   // + the reducer block
+    launch_kernel("stream_fwd", kern, col_blocks * d.ksplit + d.n_proj, sm::WG_THREADS, lds_bytes, stream, d);
     return hipGetLastError();
 }
 
@@ -899,28 +940,22 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     const int K = a.w.K, N = a.w.N;
     const SmallWs l = small_ws(K, N, a.r);
     char *ws = static_cast<char *>(a.ws);
-    uint16_t *Xp = reinterpret_cast<uint16_t *>(ws + l.xp);
     float *Upart = reinterpret_cast<float *>(ws + l.upart);
     float *Yacc = reinterpret_cast<float *>(ws + l.yacc);
-    const int n_kparts = K / sm::PREP_K;
     const int col_blocks = (N + sm::BCOLS - 1) / sm::BCOLS;
     const int ksplit = pick_ksplit(K, N, a.w.group);
     if (ksplit < 1) return hipErrorInvalidValue;     // callers check smallm_fwd_supported first
 
-    auto prep = a.r <= 8 ? smallm_prep_fwd_kernel<8> : (a.r <= 16 ? smallm_prep_fwd_kernel<16> : smallm_prep_fwd_kernel<64>);
-    launch_kernel("smallm_prep_fwd", prep, n_kparts, 256, 0, stream, a.act, a.M, K, a.w.bits, a.A, a.r, Xp, Upart, n_kparts);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-
+    hipError_t e;
     SmallFwdDev d;
     d.w = a.w;
-    d.Xp = Xp;
+    d.X = a.act;
+    d.A = a.A;
     d.Upart = Upart;
-    d.Ufinal = reinterpret_cast<float *>(ws + l.ufinal);
     d.B = a.B;
     d.M = a.M;
     d.r = a.r;
-    d.n_kparts = n_kparts;
+    d.n_proj = n_proj_blocks(K, a.r);
     d.ksplit = ksplit;
     d.lora_scale = a.lora_scale;
     d.Y = a.out;
@@ -928,7 +963,8 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     d.Yacc = Yacc;
     // LDS for the largest slice: ceil(groups / ksplit) groups of 32 bytes per contraction element
     const int n_groups = K / a.w.group;
-    const size_t lds_bytes = (size_t)((n_groups + ksplit - 1) / ksplit) * a.w.group * 32;
+    size_t lds_bytes = (size_t)((n_groups + ksplit - 1) / ksplit) * a.w.group * 32;
+    if (lds_bytes < 16 * 1024) lds_bytes = 16 * 1024;      // the projection workgroups' wave reduction
     switch (a.w.bits) {
         case 2: e = launch_fwd_bits<2>(d, col_blocks, lds_bytes, stream); break;
         case 3: e = launch_fwd_bits<3>(d, col_blocks, lds_bytes, stream); break;
@@ -945,7 +981,7 @@ static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, size_t lds
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)80 * 1024, configured);
     if (e != hipSuccess) return e;
-    launch_kernel("stream_bwd", kern, k_blocks * d.nsplit + 1, sm::WG_THREADS, lds_bytes, stream, d);   // + the reducer block
+    launch_kernel("stream_bwd", kern, k_blocks * d.nsplit + d.n_proj, sm::WG_THREADS, lds_bytes, stream, d);
     return hipGetLastError();
 }
 
@@ -953,27 +989,21 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     const int K = a.w.K, N = a.w.N;
     const SmallWs l = small_ws(K, N, a.r);
     char *ws = static_cast<char *>(a.ws);
-    uint16_t *dYp = reinterpret_cast<uint16_t *>(ws + l.xp);
     float *Tpart = reinterpret_cast<float *>(ws + l.upart);
-    const int n_parts = N / sm::PREP_K;
     const int k_blocks = K / smb::KT;
     const int nsplit = pick_nsplit(N, K);
     if (nsplit < 1) return hipErrorInvalidValue;     // callers check smallm_bwd_supported first
 
-    auto prep = a.r <= 8 ? smallm_prep_bwd_kernel<8> : (a.r <= 16 ? smallm_prep_bwd_kernel<16> : smallm_prep_bwd_kernel<64>);
-    launch_kernel("smallm_prep_bwd", prep, n_parts, 256, 0, stream, a.act, a.M, N, a.B, a.r, dYp, Tpart);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-
+    hipError_t e;
     SmallBwdDev d;
     d.w = a.w;
-    d.dYp = dYp;
+    d.dY = a.act;
+    d.B = a.B;
     d.Tpart = Tpart;
-    d.Tfinal = reinterpret_cast<float *>(ws + l.ufinal);
     d.A = a.A;
     d.M = a.M;
     d.r = a.r;
-    d.n_parts = n_parts;
+    d.n_proj = n_proj_blocks(N, a.r);
     d.nsplit = nsplit;
     d.lora_scale = a.lora_scale;
     d.dX = a.out;
