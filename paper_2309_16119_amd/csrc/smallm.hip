@@ -543,9 +543,16 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
     const int m = tid >> 4, col = blockIdx.x * 64 + 4 * (tid & 15);
     float y[4] = {0.f, 0.f, 0.f, 0.f};
     if (m < d.M && col < N) {
-        for (int q = 0; q < d.ksplit; ++q) {
-            const float4 v = *reinterpret_cast<const float4 *>(d.Yacc + ((size_t)q * 16 + m) * N + col);
-            y[0] += v.x; y[1] += v.y; y[2] += v.z; y[3] += v.w;
+        // eight slices' loads in flight at a time (the sum is latency-bound otherwise)
+        for (int q0 = 0; q0 < d.ksplit; q0 += 8) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (q0 + u < d.ksplit) v[u] = *reinterpret_cast<const float4 *>(d.Yacc + ((size_t)(q0 + u) * 16 + m) * N + col);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { y[0] += v[u].x; y[1] += v[u].y; y[2] += v[u].z; y[3] += v[u].w; }
         }
     }
     smallm_sum_parts(d.Upart, d.n_proj, d.r, Us);
@@ -832,11 +839,24 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(Small
     const int m = tid >> 4, k0 = blockIdx.x * 128 + 8 * (tid & 15);
     float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (m < d.M) {
-        for (int q = 0; q < d.nsplit; ++q) {
-            const float *src = d.acc + ((size_t)q * 16 + m) * K + k0;
-            const float4 v0 = *reinterpret_cast<const float4 *>(src), v1 = *reinterpret_cast<const float4 *>(src + 4);
-            y[0] += v0.x; y[1] += v0.y; y[2] += v0.z; y[3] += v0.w;
-            y[4] += v1.x; y[5] += v1.y; y[6] += v1.z; y[7] += v1.w;
+        // four slices' loads (two 16-byte loads each) in flight at a time
+        for (int q0 = 0; q0 < d.nsplit; q0 += 4) {
+            float4 v0[4], v1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                v0[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                v1[u] = v0[u];
+                if (q0 + u < d.nsplit) {
+                    const float *src = d.acc + ((size_t)(q0 + u) * 16 + m) * K + k0;
+                    v0[u] = *reinterpret_cast<const float4 *>(src);
+                    v1[u] = *reinterpret_cast<const float4 *>(src + 4);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                y[0] += v0[u].x; y[1] += v0[u].y; y[2] += v0[u].z; y[3] += v0[u].w;
+                y[4] += v1[u].x; y[5] += v1[u].y; y[6] += v1[u].z; y[7] += v1[u].w;
+            }
         }
     }
     smallm_sum_parts(d.Tpart, d.n_proj, d.r, Ts);
