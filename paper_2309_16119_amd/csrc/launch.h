@@ -115,7 +115,7 @@ inline int lora_down_split(int M, int C) {
     const int row_blocks = (M + 15) / 16;
     if (row_blocks * 16 >= 1024) return 1;            // 16 waves per workgroup fill the chip already
     int split = (2048 + row_blocks * 16 - 1) / (row_blocks * 16);
-    const int by_depth = C / (32 * 16 * 4);           // at least 4 steps of 32 per wave
+    const int by_depth = C / (32 * 16 * 2);           // at least 2 steps of 32 per wave
     if (split > by_depth) split = by_depth;
     if (split > 16) split = 16;
     return split < 2 ? 1 : split;
