@@ -92,19 +92,23 @@ class Workload:
         self.ws_bytes = nbytes
         self.structs = [w.c_struct() for w in self.weights]
 
-    def step(self, i: int):
+    def step(self, i: int, calls=("fwd", "bwd_input", "bwd_lora")):
         b, cfg = self.b, self.cfg
         st = ctypes.byref(self.structs[i % self.n_copies])
         stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
         p = lambda t: ctypes.c_void_p(t.data_ptr())
         s = float(cfg.lora_scale)
-        rc = b.lib.modulora_fwd(st, p(self.X), cfg.M, p(self.A), p(self.B), cfg.r, s, p(self.Y), p(self.XA),
-                                p(self.ws), self.ws_bytes, stream)
-        rc |= b.lib.modulora_bwd_input(st, p(self.dY), cfg.M, p(self.A), p(self.B), cfg.r, s, p(self.dX),
-                                       p(self.dYBt), p(self.ws), self.ws_bytes, stream)
-        rc |= b.lib.modulora_bwd_lora(cfg.K, cfg.N, cfg.M, cfg.r, s, p(self.X), p(self.dY), p(self.A), p(self.B),
-                                      p(self.XA), p(self.dYBt), p(self.dA), p(self.dB), 0, p(self.ws),
-                                      self.ws_bytes, stream)
+        rc = 0
+        if "fwd" in calls:
+            rc |= b.lib.modulora_fwd(st, p(self.X), cfg.M, p(self.A), p(self.B), cfg.r, s, p(self.Y), p(self.XA),
+                                     p(self.ws), self.ws_bytes, stream)
+        if "bwd_input" in calls:
+            rc |= b.lib.modulora_bwd_input(st, p(self.dY), cfg.M, p(self.A), p(self.B), cfg.r, s, p(self.dX),
+                                           p(self.dYBt), p(self.ws), self.ws_bytes, stream)
+        if "bwd_lora" in calls:
+            rc |= b.lib.modulora_bwd_lora(cfg.K, cfg.N, cfg.M, cfg.r, s, p(self.X), p(self.dY), p(self.A), p(self.B),
+                                          p(self.XA), p(self.dYBt), p(self.dA), p(self.dB), 0, p(self.ws),
+                                          self.ws_bytes, stream)
         if rc != 0:
             raise RuntimeError("library call failed with status %d" % rc)
 
@@ -182,9 +186,13 @@ class DecoderLayerWorkload:
             raise RuntimeError("library call failed with status %d" % rc)
 
 
-def time_steps(wl, steps: int, warmup: int, use_graph: bool) -> float:
-    """Milliseconds per step over exactly `steps` steps (after `warmup` untimed ones)."""
+def time_steps(wl, steps: int, warmup: int, use_graph: bool, calls=None) -> float:
+    """Milliseconds per step over exactly `steps` steps (after `warmup` untimed ones).  `calls`
+    restricts a step to some of the three library calls (per-call times)."""
     torch = wl.torch
+    if calls is not None:
+        full_step = wl.step
+        wl = type("OneCall", (), {"torch": torch, "step": staticmethod(lambda i: full_step(i, calls))})
     for i in range(warmup):
         wl.step(i)
     torch.cuda.synchronize()
@@ -258,20 +266,64 @@ def per_call_ms(prof: dict) -> dict:
     return out
 
 
-def cpu_baseline(host_layer, cfg) -> dict:
-    """The oracle, as it stands, timed on the host cores on one full step of the workload."""
+def cpu_baseline(host_layer, cfg, wl=None):
+    """The oracle, as it stands, timed on the host cores on one full step of the workload.
+    With `wl` (the GPU workload built from the same host layer) also returns the parity of the
+    GPU outputs against the oracle's: max |gpu - ref| / max |ref| per output tensor."""
+    import numpy as np
     import oracle
 
     L = host_layer
     args = (L["qweight"], L["scales"], L["zeros"], L["K"], L["N"], L["bits"], L["group"])
     t0 = time.perf_counter()
-    oracle.fwd(*args, L["X"], L["A"], L["B"], L["lora_scale"])
-    oracle.bwd_input(*args, L["dY"], L["A"], L["B"], L["lora_scale"])
-    oracle.bwd_lora(L["K"], L["N"], L["X"], L["dY"], L["A"], L["B"], L["lora_scale"])
+    Yr, _ = oracle.fwd(*args, L["X"], L["A"], L["B"], L["lora_scale"])
+    dXr, _ = oracle.bwd_input(*args, L["dY"], L["A"], L["B"], L["lora_scale"])
+    dAr, dBr = oracle.bwd_lora(L["K"], L["N"], L["X"], L["dY"], L["A"], L["B"], L["lora_scale"])
     dt = time.perf_counter() - t0
-    return {"value": round(cfg.flops_fwd_bwd / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+    base = {"value": round(cfg.flops_fwd_bwd / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(dt, 3),
             "sample": "one full step (fwd + bwd_input + bwd_lora) of %s, all %d tokens" % (cfg.name, cfg.M)}
+    if wl is None:
+        return base, None
+    wl.step(0)                      # weight copy 0 is the host layer's
+    wl.torch.cuda.synchronize()
+    rel = lambda got, ref: float(np.max(np.abs(got.double().cpu().numpy() - ref)) / np.max(np.abs(ref)))
+    What = wl.b.modulora_dequant(wl.weights[0]).cpu().view(wl.torch.int16).numpy().view(np.uint16)
+    parity = {"rel_max_err": {"Y": rel(wl.Y, Yr), "dX": rel(wl.dX, dXr), "dA": rel(wl.dA, dAr), "dB": rel(wl.dB, dBr)},
+              "bar": 2e-2, "dequant_bit_exact": bool(np.array_equal(What, oracle.dequant_bf16(*args)))}
+    parity["rel_max_err"] = {k: float("%.3g" % v) for k, v in parity["rel_max_err"].items()}
+    return base, parity
+
+
+def measured_context(cfg, torch) -> dict:
+    """Context numbers measured on this machine (not targets): a streaming read of 2 GiB by a plain
+    reduction kernel, and a dense bfloat16 torch.matmul of the workload's M x K x N."""
+    out = {}
+    buf = torch.ones(1 << 29, dtype=torch.float32, device="cuda")        # 2 GiB
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    buf.sum(); torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        buf.sum()
+    e1.record(); torch.cuda.synchronize()
+    out["stream_read_GBps"] = round(5 * buf.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+    out["stream_read_kernel"] = "torch.sum over 2 GiB of float32"
+    del buf
+    torch.cuda.empty_cache()
+    a = torch.randn((cfg.M, cfg.K), device="cuda").to(torch.bfloat16)
+    w = torch.randn((cfg.N, cfg.K), device="cuda").to(torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(a, w.t())
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(20):
+        torch.matmul(a, w.t())
+    e1.record(); torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 20
+    out["dense_bf16_matmul_us"] = round(ms * 1e3, 2)
+    out["dense_bf16_matmul_TFLOPs"] = round(2.0 * cfg.M * cfg.K * cfg.N / (ms * 1e-3) / 1e12, 1)
+    out["dense_bf16_matmul_note"] = "torch.matmul [M,K] x [K,N] on a resident bf16 weight, same M, K, N (one product)"
+    return out
 
 
 def rocprof_kernel_pattern(lib_name: str) -> str:
@@ -405,8 +457,11 @@ def main():
     if fetch and write:
         pat = rocprof_kernel_pattern(line["roofline"]["kernel"])
         line["roofline"]["traffic"] = traffic_of(pat % cfg.bits if "%d" in pat else pat, fetch, write)
+    line["per_call_us"] = {c: round(time_steps(wl, args.steps, 2, use_graph, calls=(c,)) * 1e3, 2)
+                           for c in ("fwd", "bwd_input", "bwd_lora")}
+    line["measured_context"] = measured_context(cfg, torch)
     if not args.no_cpu:
-        line["cpu_baseline"] = cpu_baseline(host_layer, cfg)
+        line["cpu_baseline"], line["parity_vs_oracle"] = cpu_baseline(host_layer, cfg, wl)
     del wl, host_layer
     torch.cuda.empty_cache()
 
@@ -425,6 +480,9 @@ def main():
             entry = {"workload": ocfg.name, "ms_per_step": round(ms2, 5),
                      "tflops": round(ocfg.flops_fwd_bwd / (ms2 * 1e-3) / 1e12, 3),
                      "roofline": roofline_of(ocfg, prof2), "kernel_us": per_call_ms(prof2)}
+            if ocfg.M > 16:
+                ctx = measured_context(ocfg, torch)
+                entry["dense_bf16_matmul_TFLOPs"] = ctx["dense_bf16_matmul_TFLOPs"]     # context: one product, no dequantization
             if ocfg.M <= 16:
                 gemm = {k: v for k, v in prof2.items() if k.startswith("gemm_") or k in ("stream_fwd", "stream_bwd")}
                 entry["packed_weight_GBps"] = {
@@ -432,6 +490,28 @@ def main():
             extra.append(entry)
             del w2
             torch.cuda.empty_cache()
+        # config 5 as a sweep: the three distinct matrices of a LLaMA-65B decoder layer at four
+        # token counts; per call and summed, and the per-decoder-layer sum (4 x attn + 2 x up + down)
+        sweep = []
+        for M5 in (1, 16, 256, 4096):
+            row = {"M": M5}
+            layer_ms = 0.0
+            for name, mult in (("c5_65b_attn", 4), ("c5_65b_up", 2), ("c5_65b_down", 1)):
+                c5 = synth.CONFIGS[name].with_M(M5)
+                w5 = Workload(c5)
+                steps = 10 if M5 >= 256 else 20
+                ms5 = time_steps(w5, steps, 3, use_graph)
+                calls = {c: round(time_steps(w5, steps, 2, use_graph, calls=(c,)) * 1e3, 2)
+                         for c in ("fwd", "bwd_input", "bwd_lora")}
+                row[name.replace("c5_65b_", "")] = {"step_us": round(ms5 * 1e3, 2), "calls_us": calls,
+                                                   "tflops": round(c5.flops_fwd_bwd / (ms5 * 1e-3) / 1e12, 2)}
+                layer_ms += mult * ms5
+                del w5
+                torch.cuda.empty_cache()
+            row["decoder_layer_sum_ms"] = round(layer_ms, 4)
+            sweep.append(row)
+        extra.append({"workload": "c5 sweep: 8192x8192 (x4), 8192->22016 (x2), 22016->8192 (x1), 3-bit group 128 r=8",
+                      "rows": sweep})
         # NEXT step of the method: the seven linears of a decoder layer back to back + fused AdamW
         for M_dec in (2048, 128):
             dl = DecoderLayerWorkload(M_dec)
