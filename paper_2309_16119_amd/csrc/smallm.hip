@@ -23,8 +23,9 @@
 // the zero point needs anyway).  Which two codes share a register is fixed by the bit
 // layout, so every workgroup re-orders its slice of X to the same order on its way into LDS.
 // For 3-bit codes the
-// low field of a register lands four bits high (128 + 16q), compensated by the matching X
-// element divided by 16 -- a power of two, exact.
+// low field of a register lands four bits high; there the field is OR-ed into bfloat16 8.0
+// (0x4100) instead, whose mantissa bit 4 has weight one: 8 + q.  The offsets (8 or 128 times
+// X) are removed by one MFMA against the vector of the offsets themselves.
 #include "device_common.h"
 #include "gemm_common.h"
 #include "launch.h"
@@ -32,10 +33,12 @@
 namespace mlr {
 
 namespace sm {
-constexpr int WG_WAVES = 4, WG_THREADS = WG_WAVES * 64;
+constexpr int WG_WAVES = 4, WG_THREADS = WG_WAVES * 64;      // backward stream and finish kernels
+constexpr int FWD_WAVES = 8, FWD_THREADS = FWD_WAVES * 64;  // forward stream kernel: one workgroup per compute unit
 constexpr int PREP_K = 128;            // the contraction length must be a multiple of this
 constexpr int MAX_KSPLIT = 32;         // workgroups that may share a column block
 constexpr uint32_t MAGIC = 0x43004300u;   // two bfloat16 128.0
+constexpr uint32_t MAGIC3 = 0x43004100u;  // bfloat16 (8.0, 128.0): 3-bit, forward (low field at bits 4-6)
 constexpr uint32_t ONES = 0x3F803F80u;    // two bfloat16 1.0
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint32_t r[4]) {
@@ -80,7 +83,7 @@ template <int BITS>
 __device__ __forceinline__ CodeMasks make_masks() {
     CodeMasks m;
     m.field = opaque_sgpr(BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x00070070u));
-    m.magic = opaque_vgpr(MAGIC);
+    m.magic = opaque_vgpr(BITS == 3 ? MAGIC3 : MAGIC);
     return m;
 }
 
@@ -96,7 +99,7 @@ __device__ __forceinline__ void codes_to_operand(const uint32_t *w, int c, const
 #pragma unroll
         for (int p = 0; p < 4; ++p) o[p] = and_or(w[0] >> (2 * (4 * c + p)), m.field, m.magic);
     } else {
-        // 24-bit chunk c of the 96-bit block (stream bits 24c .. 24c+23); reg p = (16 * code p,
+        // 24-bit chunk c of the 96-bit block (stream bits 24c .. 24c+23); reg p = (code p,
         // code p+4): code p must land at bits 4-6, i.e. the chunk shifted right by 3p - 4, and
         // code p+4 (12 bits further up) then sits at bits 16-18.  The shift is folded into the
         // extraction of the chunk from the words (one funnel shift or plain shift per register).
@@ -124,14 +127,14 @@ __device__ __forceinline__ void codes_to_operand(const uint32_t *w, int c, const
 // Lane l = 16 cs + i: activation row i (rows >= M repeat row M - 1; their results are never
 // used), factor column 16 g + i, contraction elements 8 cs .. 8 cs + 7 of a step of 32.
 // ---------------------------------------------------------------------------------
-template <bool F_IS_A>
+template <bool F_IS_A, int NWAVES>
 __device__ __forceinline__ void smallm_project(const uint16_t *act, int M, int C, const float *F, int r, int blk,
-                                               int nblk, float *parts, float *red /* LDS, 4 * 4 * 256 floats */) {
+                                               int nblk, float *parts, float *red /* LDS, NWAVES * 4 * 256 floats */) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i = lane & 15, cs = lane >> 4;
     const uint16_t *arow = act + (size_t)(i < M ? i : M - 1) * C;
     const int steps = C / 32;
-    const long part = (long)blk * sm::WG_WAVES + wave, nparts = (long)nblk * sm::WG_WAVES;
+    const long part = (long)blk * NWAVES + wave, nparts = (long)nblk * NWAVES;
     const int s0 = (int)(steps * part / nparts), s1 = (int)(steps * (part + 1) / nparts);
     const int RG = (r + 15) >> 4;
     f32x4 acc[4];
@@ -186,11 +189,11 @@ __device__ __forceinline__ void smallm_project(const uint16_t *act, int M, int C
         for (int v = 0; v < 4; ++v) red[((wave * 4 + g) * 4 + v) * 64 + lane] = acc[g][v];
     __syncthreads();
     float *mine = parts + (size_t)blk * 16 * r;
-    for (int x = tid; x < RG * 256; x += sm::WG_THREADS) {
+    for (int x = tid; x < RG * 256; x += NWAVES * 64) {
         const int g = x >> 8, v = (x >> 6) & 3, l = x & 63;
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < sm::WG_WAVES; ++w) sum += red[((w * 4 + g) * 4 + v) * 64 + l];
+        for (int w = 0; w < NWAVES; ++w) sum += red[((w * 4 + g) * 4 + v) * 64 + l];
         const int prow = 4 * (l >> 4) + v, j = g * 16 + (l & 15);
         if (j < r) mine[prow * r + j] = sum;
     }
@@ -198,7 +201,7 @@ __device__ __forceinline__ void smallm_project(const uint16_t *act, int M, int C
 
 // Sum of the projection workgroups' partials into Us (16 x r floats in LDS).
 __device__ __forceinline__ void smallm_sum_parts(const float *parts, int n_parts, int r, float *Us) {
-    for (int t = threadIdx.x; t < 16 * r; t += sm::WG_THREADS) {
+    for (int t = threadIdx.x; t < 16 * r; t += blockDim.x) {
         float v[16];                           // n_parts <= 16: all loads in flight together
 #pragma unroll
         for (int b = 0; b < 16; ++b) v[b] = b < n_parts ? parts[(size_t)b * 16 * r + t] : 0.f;
@@ -211,9 +214,10 @@ __device__ __forceinline__ void smallm_sum_parts(const float *parts, int n_parts
 }
 
 // ---------------------------------------------------------------------------------
-// forward stream kernel.  A workgroup of 4 waves owns 256 output columns and one slice of K
+// forward stream kernel.  A workgroup of 8 waves owns 512 output columns and one slice of K
 // (a run of whole quantization groups); each wave owns 64 of the columns.  The slice of the
-// re-ordered activations sits in LDS, shared by the four waves.  Inside a wave, lane
+// re-ordered activations sits in LDS, shared by the eight waves (one workgroup per compute
+// unit: all its waves get their activations, and start on the weights, together).  Inside a wave, lane
 // l = 16 j + i holds columns n0 + 4i .. 4i+3 (one 16-byte load per packed word row, 256
 // contiguous bytes per 16-lane group) and the k-slice j of each MFMA call.  Packed words,
 // scales and zeros are loaded DEPTH steps ahead by loads issued from assembly and awaited
@@ -272,7 +276,7 @@ __device__ __forceinline__ void wait_vm() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
-// wait_vm<BASE + extra>() for 0 <= extra < 8 known after unrolling
+// wait_vm<BASE + extra>() for 0 <= extra < 16 known after unrolling
 template <int BASE>
 __device__ __forceinline__ void wait_vm_plus(int extra) {
     switch (extra) {
@@ -283,7 +287,15 @@ __device__ __forceinline__ void wait_vm_plus(int extra) {
         case 4: wait_vm<BASE + 4>(); break;
         case 5: wait_vm<BASE + 5>(); break;
         case 6: wait_vm<BASE + 6>(); break;
-        default: wait_vm<BASE + 7>(); break;
+        case 7: wait_vm<BASE + 7>(); break;
+        case 8: wait_vm<BASE + 8>(); break;
+        case 9: wait_vm<BASE + 9>(); break;
+        case 10: wait_vm<BASE + 10>(); break;
+        case 11: wait_vm<BASE + 11>(); break;
+        case 12: wait_vm<BASE + 12>(); break;
+        case 13: wait_vm<BASE + 13>(); break;
+        case 14: wait_vm<BASE + 14>(); break;
+        default: wait_vm<BASE + 15>(); break;
     }
 }
 template <typename T>
@@ -291,7 +303,7 @@ __device__ __forceinline__ void tie(T &x) {
     asm volatile("" : "+v"(x)::"memory");
 }
 constexpr int WCOLS = 64;                 // columns per wave (4 per lane of a 16-lane group)
-constexpr int BCOLS = WG_WAVES * WCOLS;   // columns per workgroup
+constexpr int BCOLS = FWD_WAVES * WCOLS;  // columns per workgroup
 constexpr int MAX_RANGE = 2048;           // contraction elements of one K slice (64 KB of LDS)
 }  // namespace sm
 
@@ -313,15 +325,17 @@ __device__ __forceinline__ void smallm_store4(const SmallFwdDev &d, const float 
     *reinterpret_cast<uint2 *>(d.Y + (size_t)m * d.w.N + col) = o;
 }
 
-template <int BITS>
-__global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdDev d) {
+// SPG1: a quantization group is exactly one step (KSTEP codes), so every step starts its
+// sums from zero (the first MFMA of a step takes a zero C operand) and ends with the affine part.
+template <int BITS, bool SPG1>
+__global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwdDev d) {
     using G = sm::Geo<BITS>;
     extern __shared__ __attribute__((aligned(16))) uint4 xs[];   // [chunks of the slice][16 rows]
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if ((int)blockIdx.x < d.n_proj) {
         // projection workgroups: partials of XA = X A for the finish kernel; they run beside the
         // streaming ones and are done long before them
-        smallm_project<true>(d.X, d.M, d.w.K, d.A, d.r, blockIdx.x, d.n_proj, d.Upart, reinterpret_cast<float *>(xs));
+        smallm_project<true, sm::FWD_WAVES>(d.X, d.M, d.w.K, d.A, d.r, blockIdx.x, d.n_proj, d.Upart, reinterpret_cast<float *>(xs));
         return;
     }
     const int bid = blockIdx.x - d.n_proj;
@@ -340,7 +354,7 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdD
     const int spg = group / G::KSTEP;               // steps per group
     const int s_begin = g_begin * spg, s_end = g_end * spg;
 
-    constexpr int DEPTH = BITS == 3 ? 4 : 8;
+    constexpr int DEPTH = BITS == 3 ? 3 : 8;
     constexpr int SL = G::WORDS + 2;                // loads per stage
     struct Stage {
         sm::u32x4 w[G::WORDS];
@@ -362,24 +376,24 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdD
     // The workgroup's slice of X goes into LDS in operand order: chunk c of 8 contraction
     // elements, row m at xs[16 c + m].  Inside a chunk the elements are re-ordered to the pairing
     // the code registers have (4- and 3-bit: (0,4,1,5,2,6,3,7); 2-bit: over two chunks,
-    // (0,8,1,9,2,10,3,11) and (4,12,5,13,6,14,7,15)), and for 3-bit the even positions are
-    // divided by 16.  Thread t takes row t % 16 of chunk t / 16 (+ 16 per pass): 64 contiguous
-    // bytes per row and wave, conflict-free 16-byte LDS stores.  Rows >= M are zero.
-    // The loads of the first pass (up to 1024 contraction elements, the usual slice) are issued
-    // from assembly BEFORE the weight stages, so they return first and the re-ordering runs
-    // while the weights are in flight; every lane issues all of them (clamped addresses, masked
-    // afterwards), which keeps the load count the waits rely on.  Later passes use ordinary
-    // loads (they wait for the stages issued before them).
+    // (0,8,1,9,2,10,3,11) and (4,12,5,13,6,14,7,15)).  Thread t takes row t % 16 of chunk
+    // t / 16 (+ 16 per pass): 64 contiguous bytes per row and wave, conflict-free 16-byte LDS
+    // stores.  Rows >= M are zero.
+    // The loads of the whole slice (at most MAX_RANGE contraction elements) are issued from
+    // assembly BEFORE the weight stages, so they return first and the re-ordering runs while the
+    // weights are in flight; every lane issues all of them (clamped addresses, masked
+    // afterwards), which keeps the load count the waits rely on.
     {
         const int k_begin = s_begin * G::KSTEP, n_chunks = (s_end - s_begin) * (G::KSTEP / 8);
         const int m = tid & 15;
         const uint16_t *xrow = d.X + (size_t)(m < d.M ? m : 0) * d.w.K + k_begin;
-        constexpr int BATCH = 8;
+        constexpr int CPP = sm::FWD_THREADS / 16;         // chunks per pass of the workgroup
+        constexpr int BATCH = sm::MAX_RANGE / 8 / CPP;
         static_assert(DEPTH * SL + BATCH - 1 < 64, "vmcnt is a 6-bit counter");
         sm::u32x4 first[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
-            const int c = (tid >> 4) + 16 * u;
+            const int c = (tid >> 4) + CPP * u;
             sm::ald_cached(first[u], xrow + 8 * (c < n_chunks ? c : n_chunks - 1));
         }
 #pragma unroll
@@ -406,37 +420,22 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdD
                 ow[1] = __builtin_amdgcn_perm(raw.z, raw.x, 0x07060302u);   // (x1, x5)
                 ow[2] = __builtin_amdgcn_perm(raw.w, raw.y, 0x05040100u);   // (x2, x6)
                 ow[3] = __builtin_amdgcn_perm(raw.w, raw.y, 0x07060302u);   // (x3, x7)
-                if (BITS == 3) {
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {
-                        const uint32_t scaled = float_to_bf16_bits(__uint_as_float(ow[p] << 16) * 0.0625f);
-                        ow[p] = (ow[p] & 0xFFFF0000u) | scaled;
-                    }
-                }
             }
             if (c < n_chunks) xs[(size_t)c * 16 + m] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
         };
-        // first pass: every thread waits for and ties every one of its loads, in range or not
+        // every thread waits for and ties every one of its loads, in range or not; chunks past the
+        // end of the slice (n_chunks is a multiple of 16 and a wave's four chunks lie inside one
+        // block of 16: the same answer for all lanes of a wave) are skipped
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
-            const int c = (tid >> 4) + 16 * u;
+            const int c = (tid >> 4) + CPP * u;
             // the weight stages and the BATCH - 1 - u younger loads of this pass stay in flight
             sm::wait_vm_plus<DEPTH * SL>(BATCH - 1 - u);
             sm::tie(first[u]);
-            const bool in = c < n_chunks && m < d.M;
-            reorder_store(make_uint4(in ? first[u][0] : 0u, in ? first[u][1] : 0u, in ? first[u][2] : 0u, in ? first[u][3] : 0u), c);
-        }
-        // later passes (slices of more than 1024 contraction elements); uniform trip count per wave pair
-        for (int c0 = 16 * BATCH; c0 < n_chunks; c0 += 16 * BATCH) {
-            uint4 raw[BATCH];
-#pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const int c = c0 + (tid >> 4) + 16 * u;
-                raw[u] = make_uint4(0, 0, 0, 0);
-                if (c < n_chunks && m < d.M) raw[u] = *reinterpret_cast<const uint4 *>(xrow + 8 * c);
+            if (4 * wave + CPP * u < n_chunks) {
+                const bool in = m < d.M;
+                reorder_store(make_uint4(in ? first[u][0] : 0u, in ? first[u][1] : 0u, in ? first[u][2] : 0u, in ? first[u][3] : 0u), c);
             }
-#pragma unroll
-            for (int u = 0; u < BATCH; ++u) reorder_store(raw[u], c0 + (tid >> 4) + 16 * u);
         }
     }
     __syncthreads();
@@ -449,8 +448,8 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdD
         s1[v] = 0.f; s2[v] = 0.f;
     }
     const uint32_t ones4[4] = {sm::ONES, sm::ONES, sm::ONES, sm::ONES};
-    const uint32_t invf4[4] = {0x3F804180u, 0x3F804180u, 0x3F804180u, 0x3F804180u};   // (16, 1) pairs
-    const bf16x8 ones = sm::as_bf16x8(ones4), invf = sm::as_bf16x8(invf4);
+    const uint32_t offs4[4] = {sm::MAGIC3, sm::MAGIC3, sm::MAGIC3, sm::MAGIC3};   // 3-bit: the (8, 128) offsets
+    const bf16x8 ones = sm::as_bf16x8(ones4), offs = sm::as_bf16x8(offs4);
     const sm::CodeMasks masks = sm::make_masks<BITS>();
 
     auto compute = [&](Stage &sd, int srel, bool group_ends) {
@@ -459,23 +458,25 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdD
         uint4 xa[G::NC];
 #pragma unroll
         for (int c = 0; c < G::NC; ++c) xa[c] = xrow[c * 16];
+        const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < G::NC; ++c) {
             const bf16x8 a = sm::as_bf16x8(xa[c]);
+            const bool fresh = SPG1 && c == 0;       // first call of a one-step group: C = 0
 #pragma unroll
             for (int cs = 0; cs < 4; ++cs) {
                 uint32_t wq[G::WORDS], o[4];
 #pragma unroll
                 for (int q = 0; q < G::WORDS; ++q) wq[q] = sd.w[q][cs];
                 sm::codes_to_operand<BITS>(wq, c, masks, o);
-                tmp[cs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), tmp[cs], 0, 0, 0);
+                tmp[cs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), fresh ? zero4 : tmp[cs], 0, 0, 0);
             }
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, s1, 0, 0, 0);
-            if (BITS == 3) s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, invf, s2, 0, 0, 0);
+            // 4- and 2-bit: s1 = sum X.  3-bit: s1 = sum offset * X, s2 = sum X.
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, BITS == 3 ? offs : ones, fresh ? zero4 : s1, 0, 0, 0);
+            if (BITS == 3) s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, fresh ? zero4 : s2, 0, 0, 0);
         }
-        if (!group_ends) return;
-        // end of a group: tmp = sum a (128 + q/f);  s1 = sum a;  s2 = sum a/f = sum X
-        // (f == 1 unless 3-bit)
+        if (!SPG1 && !group_ends) return;
+        // end of a group: tmp = sum X (offset + q); remove the offsets, apply zero point and scale
 #pragma unroll
         for (int cs = 0; cs < 4; ++cs) {
             const float scale = half_bits_to_float((uint16_t)(sd.sc[cs >> 1] >> (16 * (cs & 1))));
@@ -483,13 +484,15 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_fwd_kernel(SmallFwdD
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float xsum = BITS == 3 ? s2[v] : s1[v];
-                const float qx = __builtin_fmaf(-128.0f, s1[v], tmp[cs][v]);       // sum X q
+                const float qx = BITS == 3 ? tmp[cs][v] - s1[v] : __builtin_fmaf(-128.0f, s1[v], tmp[cs][v]);   // sum X q
                 yacc[cs][v] = __builtin_fmaf(scale, __builtin_fmaf(-zero, xsum, qx), yacc[cs][v]);
-                tmp[cs][v] = 0.f;
+                if (!SPG1) tmp[cs][v] = 0.f;
             }
         }
+        if (!SPG1) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) { s1[v] = 0.f; s2[v] = 0.f; }
+            for (int v = 0; v < 4; ++v) { s1[v] = 0.f; s2[v] = 0.f; }
+        }
     };
 
     int cp = 0;   // position of the next step inside its group
@@ -575,8 +578,9 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
 // Rounding dY * scale to bfloat16 moves the result by at most 2^-9 sum_n |dY| |What|, the
 // same size as the rounding of What in the materialized form.
 //
-// The workgroup's slice of dY sits in LDS as [chunks of 8 n][16 rows][8] (copied there directly
-// from dY, 64 contiguous bytes per row and load).
+// Nothing of dY is staged per workgroup: the 16 x 32 piece of dY that a step needs travels with
+// the step's packed words (1 KB, 64 contiguous bytes per row), so a workgroup's slice of N can
+// be of any length and the grid is sized to the chip, not to the LDS.
 // ---------------------------------------------------------------------------------
 struct SmallBwdDev {
     LayerView w;
@@ -590,13 +594,12 @@ struct SmallBwdDev {
     uint16_t *dX;           // [M][K]
     float *T_out;           // dYBt [M][r] or NULL
     float *acc;             // [nsplit][16][K] fp32 partial tiles
-    int slice_bytes;        // LDS bytes reserved for the dY slice (and, later, the wave reduction)
 };
 
 namespace smb {
 constexpr int KT = 128;      // output columns per workgroup: four 32-code blocks
 constexpr int NSTEP = 32;    // contraction elements per step (8 per lane group)
-constexpr int MAX_STEPS = 32; // steps of one slice of N: 32 KB of dY in LDS
+constexpr int RED_BYTES = sm::WG_WAVES * 32 * 64 * 4;   // the waves' tiles meeting in LDS
 }
 
 // adapter term and bfloat16 store of 8 adjacent outputs dX[m][k0 .. k0+7]
@@ -618,18 +621,42 @@ __device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const fl
 }
 
 // A workgroup owns 128 output columns k (one quantization group's scales and zeros) and a
-// slice of N; its four waves split the slice and add their results through LDS.  Lane
-// l = 16 j + i: i = 4 u + b picks the 32-code block b of the tile and the 8 codes 8u .. 8u+7
-// of it (MFMA call c handles code 8u + c, so the lane's outputs are 8 adjacent k), j picks
-// 8 adjacent n of the step.  A lane therefore loads, per step, the packed words that hold
-// its 8 codes for 8 adjacent n (32 contiguous bytes per word row).
+// slice of N; its four waves take the steps of the slice in turn (wave w: steps w, w + 4, ...,
+// so the workgroup reads 512 contiguous bytes of every word row at a time) and add their
+// results through LDS at the end.  Lane l = 16 j + i: i = 4 u + b picks the 32-code block b of
+// the tile and the 8 codes 8u .. 8u+7 of it (MFMA call c handles code 8u + c, so the lane's
+// outputs are 8 adjacent k), j picks 8 adjacent n of the step.
+template <int BITS>
+struct BwdGeo {
+    static constexpr int WR = 4 * BITS;                // word rows of the 128-column tile
+    // 16-byte pieces of one stage: word rows (8 per row), scales (4), zeros (2), dY (16 rows x 4)
+    static constexpr int W_PIECES = WR * 8, S_PIECE0 = W_PIECES, Z_PIECE0 = W_PIECES + 4, Y_PIECE0 = W_PIECES + 6;
+    static constexpr int N_PIECES = Y_PIECE0 + 64;
+    static constexpr int NI = (N_PIECES + 63) / 64;    // loads per stage
+    static constexpr int STAGE_BYTES = NI * 1024;
+    static constexpr int DEPTH = 4;                    // stages per wave (even: two register sets alternate)
+    static constexpr int LDS_BYTES = sm::WG_WAVES * DEPTH * STAGE_BYTES;
+    static_assert(LDS_BYTES >= smb::RED_BYTES, "the wave reduction re-uses the stages");
+    static_assert(DEPTH * NI < 64, "vmcnt is a 6-bit counter");
+    // XOR swizzle of a word row's eight 16-byte pieces.  Eight consecutive lanes read one piece
+    // each of up to eight different rows at a time (lane 4u + b: 4-bit row 4b + u; 3-bit rows
+    // 3b + {0,0,1,2}[u] and 3b + {1,1,2,2}[u]; 2-bit row 2b + u / 2, u in {0,1} or {2,3}); the
+    // rows that meet must get different values.
+    __device__ static __forceinline__ int swz(int row) {
+        if (BITS == 4) return (row >> 2) | ((row & 1) << 2);
+        if (BITS == 2) return row & 7;
+        return row < 8 ? row : ((0x6310 >> (4 * (row - 8))) & 7);     // rows 8..11 -> 0, 1, 3, 6
+    }
+};
+
 template <int BITS>
 __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdDev d) {
-    extern __shared__ __attribute__((aligned(16))) uint4 ys[];   // [chunks of 8 n of the slice][16 rows]
+    using BG = BwdGeo<BITS>;
+    extern __shared__ __attribute__((aligned(16))) uint4 ys[];   // [wave][stage] private stages, later the reduction
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if ((int)blockIdx.x < d.n_proj) {
         // projection workgroups: partials of dYBt = dY B^T (see the forward kernel)
-        smallm_project<false>(d.dY, d.M, d.w.N, d.B, d.r, blockIdx.x, d.n_proj, d.Tpart, reinterpret_cast<float *>(ys));
+        smallm_project<false, sm::WG_WAVES>(d.dY, d.M, d.w.N, d.B, d.r, blockIdx.x, d.n_proj, d.Tpart, reinterpret_cast<float *>(ys));
         return;
     }
     const int bid = blockIdx.x - d.n_proj;
@@ -639,8 +666,8 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     const int kt = kb * smb::KT;
     const int n_steps = N / smb::NSTEP;
     const int S0 = (int)((long)n_steps * ns / d.nsplit), S1 = (int)((long)n_steps * (ns + 1) / d.nsplit);
-    const int W0 = S0 + (int)((long)(S1 - S0) * wave / sm::WG_WAVES);
-    const int W1 = S0 + (int)((long)(S1 - S0) * (wave + 1) / sm::WG_WAVES);
+    // this wave's steps: S0 + wave + 4 t, t = 0 .. nw - 1
+    const int nw = S1 - S0 > wave ? (S1 - S0 - wave + sm::WG_WAVES - 1) / sm::WG_WAVES : 0;
     const int g = kt / d.w.group;
 
     // word rows of this lane, relative to the first word row of the tile
@@ -659,56 +686,48 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     const uint16_t *stile = d.w.scales + (size_t)g * N;
     const uint8_t *ztile = d.w.zeros + (size_t)g * N;
 
-    // The packed words, scales and zeros of a step (32 n) travel global -> LDS without passing
-    // through registers: every lane moves one 16-byte piece per load, so a whole stage is NI
-    // fully coalesced loads (128 contiguous bytes per word row).  Piece p of word row `row` sits
-    // at LDS piece p ^ (row & 7) of that row: the later 16-byte reads of 16 different rows then
-    // spread over the banks.  Each wave owns DEPTH private stages behind the workgroup's dY slice.
-    constexpr int WR = 4 * BITS;                       // word rows of the 128-column tile
-    constexpr int W_PIECES = WR * 8, S_PIECE0 = W_PIECES, Z_PIECE0 = W_PIECES + 4, N_PIECES = W_PIECES + 6;
-    constexpr int NI = (N_PIECES + 63) / 64;           // loads per stage
-    constexpr int STAGE_BYTES = NI * 1024;
-    constexpr int DEPTH = 4;
+    // The packed words, scales, zeros and the dY piece of a step (32 n) travel global -> LDS
+    // without passing through registers: every lane moves one 16-byte piece per load, so a whole
+    // stage is NI fully coalesced loads (128 contiguous bytes per word row, 64 per dY row).  Piece p
+    // of word row `row` sits at LDS piece p ^ swz(row) of that row: the later 16-byte reads of 16
+    // different rows then spread over the banks.  dY piece 16 c + m is row m (rows >= M repeat row
+    // M - 1; their results are never stored), elements 8 c .. 8 c + 7 of the step.
+    constexpr int NI = BG::NI, DEPTH = BG::DEPTH, STAGE_BYTES = BG::STAGE_BYTES;
     const char *gaddr[NI];                             // this lane's piece of load q, at step 0 of the matrix
     uint32_t gstr[NI];                                 // ... and its advance per step
 #pragma unroll
     for (int q = 0; q < NI; ++q) {
         const int pc = q * 64 + lane;                  // lanes past N_PIECES sit out the last load
-        if (pc < W_PIECES) {
-            const int row = pc >> 3, pp = (pc & 7) ^ (row & 7);
+        if (pc < BG::W_PIECES) {
+            const int row = pc >> 3, pp = (pc & 7) ^ BG::swz(row);
             gaddr[q] = reinterpret_cast<const char *>(wtile) + ((size_t)row * N + pp * 4) * 4;
             gstr[q] = smb::NSTEP * 4;
-        } else if (pc < Z_PIECE0) {
-            gaddr[q] = reinterpret_cast<const char *>(stile) + (pc - S_PIECE0) * 16;
+        } else if (pc < BG::Z_PIECE0) {
+            gaddr[q] = reinterpret_cast<const char *>(stile) + (pc - BG::S_PIECE0) * 16;
             gstr[q] = smb::NSTEP * 2;
-        } else {
-            gaddr[q] = reinterpret_cast<const char *>(ztile) + (pc < N_PIECES ? pc - Z_PIECE0 : 0) * 16;
+        } else if (pc < BG::Y_PIECE0) {
+            gaddr[q] = reinterpret_cast<const char *>(ztile) + (pc - BG::Z_PIECE0) * 16;
             gstr[q] = smb::NSTEP;
+        } else {
+            const int yp = pc < BG::N_PIECES ? pc - BG::Y_PIECE0 : 0;
+            const int m = (yp & 15) < d.M ? (yp & 15) : d.M - 1;
+            gaddr[q] = reinterpret_cast<const char *>(d.dY + (size_t)m * N + (yp >> 4) * 8);
+            gstr[q] = smb::NSTEP * 2;
         }
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)ys;
-    const uint32_t stage0 = (uint32_t)d.slice_bytes + (uint32_t)wave * (DEPTH * STAGE_BYTES);   // offset of the wave's stages
+    const uint32_t stage0 = (uint32_t)wave * (DEPTH * STAGE_BYTES);   // offset of the wave's stages
     auto issue = [&](int slot, int step) {             // step: any step of the workgroup's slice
 #pragma unroll
         for (int q = 0; q < NI; ++q) {
-            if ((q + 1) * 64 <= N_PIECES || q * 64 + lane < N_PIECES)
+            if ((q + 1) * 64 <= BG::N_PIECES || q * 64 + lane < BG::N_PIECES)
                 sm::ald_lds64(gaddr[q] + (size_t)step * gstr[q], lds0 + stage0 + (uint32_t)slot * STAGE_BYTES + q * 1024);
         }
     };
-    auto clamp_step = [&](int s) { return s < S1 ? s : S1 - 1; };
-
-    // the slice of dY goes straight into LDS, 1 KB (one step: 4 chunks of 8 n x 16 rows) per wave
-    // and load: lane l fetches row l % 16 (rows >= M repeat row M - 1; their results are never
-    // stored), chunk l / 16 of the step, and lands at byte 16 l of the step's 1 KB
-    {
-        const int row = (lane & 15) < d.M ? (lane & 15) : d.M - 1;
-        const char *src = reinterpret_cast<const char *>(d.dY + (size_t)row * N + (size_t)S0 * smb::NSTEP + (lane >> 4) * 8);
-        for (int q = wave; q < S1 - S0; q += sm::WG_WAVES) sm::ald_lds64(src + (size_t)q * (smb::NSTEP * 2), lds0 + (uint32_t)q * 1024u);
-    }
+    // step t of this wave, clamped into the slice (a clamped stage is loaded and never used)
+    auto wave_step = [&](int t) { const int st = S0 + wave + sm::WG_WAVES * t; return st < S1 ? st : S1 - 1; };
 #pragma unroll
-    for (int dd = 0; dd < DEPTH; ++dd) issue(dd, clamp_step(W0 + dd));
-    sm::wait_vm<DEPTH * NI>();
-    __syncthreads();
+    for (int dd = 0; dd < DEPTH; ++dd) issue(dd, wave_step(dd));
 
     f32x4 acc[8], accz, accs;
 #pragma unroll
@@ -727,21 +746,37 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
         sm::u32x4 w[NROWS][2];   // 8 adjacent n of each word row
         sm::u32x4 sc;            // 8 binary16 scales
         sm::u32x2 z;             // 8 zero points
+        sm::u32x4 y;             // dY[i][8 n]
     };
-    auto compute = [&](int slot, int srel) {        // srel: step relative to S0
-        const unsigned char *sb = reinterpret_cast<const unsigned char *>(ys) + stage0 + slot * STAGE_BYTES;
-        Stage sd;
-        sd.w[0][0] = *reinterpret_cast<const sm::u32x4 *>(sb + row0 * 128 + (((2 * j) ^ (row0 & 7)) << 4));
-        sd.w[0][1] = *reinterpret_cast<const sm::u32x4 *>(sb + row0 * 128 + (((2 * j + 1) ^ (row0 & 7)) << 4));
+    // marks a register set as complete (call after a wait for the LDS reads that fill it), so
+    // that the compiler does not add a wait of its own that would also cover younger reads
+    auto settled = [&](Stage &sd) {
+        sm::tie(sd.w[0][0]);
+        sm::tie(sd.w[0][1]);
         if (NROWS == 2) {
-            sd.w[NROWS - 1][0] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j) ^ (row1 & 7)) << 4));
-            sd.w[NROWS - 1][1] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j + 1) ^ (row1 & 7)) << 4));
+            sm::tie(sd.w[NROWS - 1][0]);
+            sm::tie(sd.w[NROWS - 1][1]);
         }
-        sd.sc = *reinterpret_cast<const sm::u32x4 *>(sb + S_PIECE0 * 16 + 16 * j);
-        sd.z = *reinterpret_cast<const sm::u32x2 *>(sb + Z_PIECE0 * 16 + 8 * j);
+        sm::tie(sd.sc);
+        sm::tie(sd.z);
+        sm::tie(sd.y);
+    };
+    // a landed stage, LDS -> registers
+    auto fetch = [&](Stage &sd, int slot) {
+        const unsigned char *sb = reinterpret_cast<const unsigned char *>(ys) + stage0 + slot * STAGE_BYTES;
+        sd.w[0][0] = *reinterpret_cast<const sm::u32x4 *>(sb + row0 * 128 + (((2 * j) ^ BG::swz(row0)) << 4));
+        sd.w[0][1] = *reinterpret_cast<const sm::u32x4 *>(sb + row0 * 128 + (((2 * j + 1) ^ BG::swz(row0)) << 4));
+        if (NROWS == 2) {
+            sd.w[NROWS - 1][0] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j) ^ BG::swz(row1)) << 4));
+            sd.w[NROWS - 1][1] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j + 1) ^ BG::swz(row1)) << 4));
+        }
+        sd.sc = *reinterpret_cast<const sm::u32x4 *>(sb + BG::S_PIECE0 * 16 + 16 * j);
+        sd.z = *reinterpret_cast<const sm::u32x2 *>(sb + BG::Z_PIECE0 * 16 + 8 * j);
+        sd.y = *reinterpret_cast<const sm::u32x4 *>(sb + (BG::Y_PIECE0 + 16 * j + i) * 16);
+    };
+    auto compute = [&](const Stage &sd) {
         // A operand: dY[i][8 n] * scale[g][8 n], rounded to bfloat16
-        const uint4 yv = ys[((size_t)srel * 4 + j) * 16 + i];
-        const uint32_t yw[4] = {yv.x, yv.y, yv.z, yv.w};
+        const uint32_t yw[4] = {sd.y[0], sd.y[1], sd.y[2], sd.y[3]};
         uint32_t areg[4];
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
@@ -792,19 +827,38 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
         accs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, accs, 0, 0, 0);
     };
 
-    for (int s = W0; s < W1; s += DEPTH) {
+    // Two workgroups share a compute unit and the instruction arbiter favours the older wave, so
+    // one would run ahead and leave the other to finish alone on a half-empty SIMD.  A wave's
+    // priority falls with its progress (3 in the first quarter of its steps ... 0 in the last), which
+    // lets the wave that lags behind issue first.
+    const int q1 = nw / 4, q2 = nw / 2, q3 = nw - nw / 4;
+    __builtin_amdgcn_s_setprio(3);
+    // Step t: its stage is already in registers (read from LDS during step t - 1); refill the
+    // slot for step t + DEPTH, read stage t + 1 into the other register set, then compute -- the
+    // LDS reads of the next step run under the arithmetic of this one.
+    Stage regs[2];
+    sm::wait_vm<(DEPTH - 1) * NI>();                 // stage 0 has landed
+    fetch(regs[0], 0);
+    for (int t = 0; t < nw; t += DEPTH) {
 #pragma unroll
         for (int dd = 0; dd < DEPTH; ++dd) {
-            if (s + dd < W1) {
-                sm::wait_vm<(DEPTH - 1) * NI>();     // this wave's stage dd has landed; DEPTH - 1 younger ones in flight
-                compute(dd, s + dd - S0);
-                issue(dd, clamp_step(s + dd + DEPTH));
+            if (t + dd < nw) {
+                if (t + dd == q3) __builtin_amdgcn_s_setprio(0);
+                else if (t + dd == q2) __builtin_amdgcn_s_setprio(1);
+                else if (t + dd == q1) __builtin_amdgcn_s_setprio(2);
+                issue(dd, wave_step(t + dd + DEPTH));   // waits for the LDS reads of slot dd first
+                settled(regs[dd & 1]);
+                sm::wait_vm<(DEPTH - 1) * NI>();     // the next stage has landed; DEPTH - 1 younger ones in flight
+                fetch(regs[(dd + 1) & 1], (dd + 1) % DEPTH);
+                __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads ahead of the arithmetic
+                compute(regs[dd & 1]);
             }
         }
     }
+    __builtin_amdgcn_s_setprio(0);
     // loads past the end of the slice are still in flight towards this workgroup's LDS
     sm::wait_vm<0>();
-    __syncthreads();                                 // every wave is done with the dY slice
+    __syncthreads();                                 // every wave is done with its stages
 
     // the four waves' tiles meet in LDS: red[wave][c * 4 + v][lane]
     float *red = reinterpret_cast<float *>(ys);
@@ -867,44 +921,58 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(Small
 
 namespace {
 // K slices for a product with contraction length Kc (groups of `group`) and Nout outputs:
-// enough workgroups to fill the chip, slices of whole groups that fit the LDS, at most
-// MAX_KSPLIT.  Returns 0 when no such split exists.
+// slices of whole groups that fit the LDS, at most MAX_KSPLIT, about one (8-wave) workgroup
+// per compute unit.  The stream is bound by instruction issue, so the time is set by the
+// fullest unit: workgroups per unit x groups per slice; a grid a little over 256 workgroups
+// (43 column blocks x 6 = 258) would leave a few units with two.  Returns 0 when no split exists.
 int pick_ksplit(int Kc, int Nout, int group) {
     if (group > sm::MAX_RANGE) return 0;
     const int n_groups = Kc / group;
     const int gmax = sm::MAX_RANGE / group;                    // groups per slice that fit the LDS
     const int need = (n_groups + gmax - 1) / gmax;
     const int col_blocks = (Nout + sm::BCOLS - 1) / sm::BCOLS;
-    int ksplit = (512 + col_blocks - 1) / col_blocks;
-    if (ksplit < need) ksplit = need;
-    if (ksplit > n_groups) ksplit = n_groups;
-    if (ksplit > sm::MAX_KSPLIT) ksplit = sm::MAX_KSPLIT;
-    if (ksplit < need) return 0;
-    // every slice holds at most ceil(n_groups / ksplit) groups
-    if ((long)((n_groups + ksplit - 1) / ksplit) * group > sm::MAX_RANGE) return 0;
-    return ksplit;
+    const int cap = n_groups < sm::MAX_KSPLIT ? n_groups : sm::MAX_KSPLIT;
+    if (need > cap) return 0;
+    int lo = (192 + col_blocks - 1) / col_blocks;
+    if (lo < need) lo = need;
+    if (lo > cap) lo = cap;
+    int best = 0;
+    double best_cost = 1e30;
+    for (int ks = lo; ks <= cap; ++ks) {
+        const int gps = (n_groups + ks - 1) / ks;              // groups of the longest slice
+        if ((long)gps * group > sm::MAX_RANGE) continue;
+        const int wgs = col_blocks * ks, per_cu = (wgs + 255) / 256;
+        const double cost = (double)per_cu * gps + (wgs > 256 ? 3.0 : 0.0) + 0.1 * ks;
+        if (cost < best_cost) { best_cost = cost; best = ks; }
+    }
+    return best;
 }
 // upper bound of pick_ksplit over all group sizes (for the workspace query)
-int ksplit_bound(int Kc, int Nout) {
-    const int col_blocks = (Nout + sm::BCOLS - 1) / sm::BCOLS;
-    int b = (512 + col_blocks - 1) / col_blocks;
-    const int need = (Kc + 1023) / 1024;
-    if (b < need) b = need;
-    if (b > sm::MAX_KSPLIT) b = sm::MAX_KSPLIT;
-    return b;
-}
-// N slices of the backward product (contraction length N, K outputs in tiles of 128)
+int ksplit_bound(int, int) { return sm::MAX_KSPLIT; }
+// N slices of the backward product (contraction length N, K outputs in tiles of 128).  Every
+// workgroup of the grid is resident at once (up to 3 per compute unit); the time is set by the
+// fullest unit, rounds x slice length, so take the split that makes that product smallest, and
+// among equals the smallest one (fewer partial tiles).  A wave keeps at least two steps.
 int pick_nsplit(int N, int K) {
     const int n_steps = N / smb::NSTEP;
     const int k_blocks = K / smb::KT;
-    const int max_steps = smb::MAX_STEPS;                      // steps of one slice that fit the LDS
-    const int need = (n_steps + max_steps - 1) / max_steps;
-    int nsplit = (512 + k_blocks - 1) / k_blocks;
-    if (nsplit < need) nsplit = need;
-    if (nsplit > n_steps) nsplit = n_steps;
-    if (nsplit > sm::MAX_KSPLIT) nsplit = sm::MAX_KSPLIT;
-    if (nsplit < need || nsplit < 1) return 0;
-    return nsplit;
+    if (n_steps < 1 || k_blocks < 1) return 0;
+    // largest admissible split: two steps per wave, at most 768 workgroups
+    int cap = 1;
+    while (cap < sm::MAX_KSPLIT && n_steps / (cap + 1) >= 2 * sm::WG_WAVES && (long)k_blocks * (cap + 1) <= 768) ++cap;
+    // two workgroups per compute unit where the shape allows (a second wave per SIMD hides the
+    // first one's waits)
+    int lo = (512 + k_blocks - 1) / k_blocks;
+    if (lo > cap) lo = cap;
+    int best = lo;
+    double best_cost = 1e30;
+    for (int ns = lo; ns <= cap; ++ns) {
+        const int per_cu = (k_blocks * ns + 255) / 256;
+        // steps the fullest unit runs, a fixed cost per workgroup, the partial tiles
+        const double cost = (double)per_cu * ((n_steps + ns - 1) / ns) + 8.0 * per_cu + 0.5 * ns;
+        if (cost < best_cost) { best_cost = cost; best = ns; }
+    }
+    return best;
 }
 }  // namespace
 
@@ -946,13 +1014,13 @@ SmallWs small_ws(int K, int N, int r) {
 
 size_t smallm_ws_bytes(int K, int N, int r) { return small_ws(K, N, r).total; }
 
-template <int BITS>
+template <int BITS, bool SPG1>
 static hipError_t launch_fwd_bits(const SmallFwdDev &d, int col_blocks, size_t lds_bytes, hipStream_t stream) {
-    auto kern = smallm_fwd_kernel<BITS>;
+    auto kern = smallm_fwd_kernel<BITS, SPG1>;
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
     if (e != hipSuccess) return e;
-    launch_kernel("stream_fwd", kern, col_blocks * d.ksplit + d.n_proj, sm::WG_THREADS, lds_bytes, stream, d);
+    launch_kernel("stream_fwd", kern, col_blocks * d.ksplit + d.n_proj, sm::FWD_THREADS, lds_bytes, stream, d);
     return hipGetLastError();
 }
 
@@ -984,11 +1052,13 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     // LDS for the largest slice: ceil(groups / ksplit) groups of 32 bytes per contraction element
     const int n_groups = K / a.w.group;
     size_t lds_bytes = (size_t)((n_groups + ksplit - 1) / ksplit) * a.w.group * 32;
-    if (lds_bytes < 16 * 1024) lds_bytes = 16 * 1024;      // the projection workgroups' wave reduction
+    if (lds_bytes < 32 * 1024) lds_bytes = 32 * 1024;      // the projection workgroups' wave reduction
+    const int kstep = a.w.bits == 4 ? 32 : (a.w.bits == 2 ? 64 : 128);
+    const bool spg1 = a.w.group == kstep;             // one step per quantization group
     switch (a.w.bits) {
-        case 2: e = launch_fwd_bits<2>(d, col_blocks, lds_bytes, stream); break;
-        case 3: e = launch_fwd_bits<3>(d, col_blocks, lds_bytes, stream); break;
-        default: e = launch_fwd_bits<4>(d, col_blocks, lds_bytes, stream); break;
+        case 2: e = spg1 ? launch_fwd_bits<2, true>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<2, false>(d, col_blocks, lds_bytes, stream); break;
+        case 3: e = spg1 ? launch_fwd_bits<3, true>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<3, false>(d, col_blocks, lds_bytes, stream); break;
+        default: e = spg1 ? launch_fwd_bits<4, true>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<4, false>(d, col_blocks, lds_bytes, stream); break;
     }
     if (e != hipSuccess) return e;
     launch_kernel("stream_fwd_finish", smallm_fwd_finish_kernel, (N + 63) / 64, sm::WG_THREADS, 0, stream, d);
@@ -996,12 +1066,12 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
 }
 
 template <int BITS>
-static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, size_t lds_bytes, hipStream_t stream) {
+static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, hipStream_t stream) {
     auto kern = smallm_bwd_kernel<BITS>;
     static bool configured[64] = {};
-    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)80 * 1024, configured);
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)BwdGeo<BITS>::LDS_BYTES, configured);
     if (e != hipSuccess) return e;
-    launch_kernel("stream_bwd", kern, k_blocks * d.nsplit + d.n_proj, sm::WG_THREADS, lds_bytes, stream, d);
+    launch_kernel("stream_bwd", kern, k_blocks * d.nsplit + d.n_proj, sm::WG_THREADS, (size_t)BwdGeo<BITS>::LDS_BYTES, stream, d);
     return hipGetLastError();
 }
 
@@ -1029,14 +1099,10 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     d.dX = a.out;
     d.T_out = a.P_out;
     d.acc = reinterpret_cast<float *>(ws + l.yacc);
-    // LDS: the largest slice of dY (1 KB per step; at least the 32 KB of the wave reduction), then
-    // 4 waves x 4 stages of packed words (3 KB per stage for 4-bit, 2 KB otherwise)
-    d.slice_bytes = 32 * 1024;
-    const size_t lds_bytes = (size_t)d.slice_bytes + 16 * (size_t)(a.w.bits == 4 ? 3072 : 2048);
     switch (a.w.bits) {
-        case 2: e = launch_bwd_bits<2>(d, k_blocks, lds_bytes, stream); break;
-        case 3: e = launch_bwd_bits<3>(d, k_blocks, lds_bytes, stream); break;
-        default: e = launch_bwd_bits<4>(d, k_blocks, lds_bytes, stream); break;
+        case 2: e = launch_bwd_bits<2>(d, k_blocks, stream); break;
+        case 3: e = launch_bwd_bits<3>(d, k_blocks, stream); break;
+        default: e = launch_bwd_bits<4>(d, k_blocks, stream); break;
     }
     if (e != hipSuccess) return e;
     launch_kernel("stream_bwd_finish", smallm_bwd_finish_kernel, k_blocks, sm::WG_THREADS, 0, stream, d);

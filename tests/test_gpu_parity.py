@@ -88,6 +88,10 @@ SHAPES = [
     (4, 1152, 640, 13, 40, 128),
     (4, 512, 2304, 1, 16, 512),
     (2, 768, 128, 16, 0, 768),
+    # ... with N split over several workgroups whose waves get unequal numbers of steps
+    (3, 1024, 2176, 11, 8, 128),
+    (4, 512, 2176, 16, 4, 128),
+    (2, 1024, 2176, 2, 8, 256),
     # few 256 x 256 tiles and a deep contraction: the tiles are cut into slices of the
     # contraction whose partial tiles a second kernel adds (ragged M, N and last 64-deep step)
     (3, 8224, 328, 200, 8, 32),      # forward: 2 tiles x 8 slices
