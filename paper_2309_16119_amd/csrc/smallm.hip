@@ -264,12 +264,20 @@ __device__ __forceinline__ void ald_lds(const void *gbase_uniform, uint32_t voff
                  : "memory");
 }
 // the same with a full per-lane address; earlier LDS reads of the wave are awaited first, so
-// that the incoming data cannot overtake a read of the slot it replaces
+// that the incoming data cannot overtake a read of the slot it replaces.  STREAM: data that is
+// read once (non-temporal hint).
+template <bool STREAM>
 __device__ __forceinline__ void ald_lds64(const void *gaddr_lane, uint32_t lds_base_uniform) {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_base_uniform), "v"(gaddr_lane)
-                 : "memory");
+    if (STREAM)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt"
+                     :
+                     : "s"(lds_base_uniform), "v"(gaddr_lane)
+                     : "memory");
+    else
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                     :
+                     : "s"(lds_base_uniform), "v"(gaddr_lane)
+                     : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
@@ -297,6 +305,13 @@ __device__ __forceinline__ void wait_vm_plus(int extra) {
         case 14: wait_vm<BASE + 14>(); break;
         default: wait_vm<BASE + 15>(); break;
     }
+}
+// 16-byte store of a partial tile: written once, read once by the next launch (non-temporal,
+// so the lines leave the L2 as they fill instead of waiting for the end-of-kernel write-back)
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_stream(float *dst, float a, float b, float c, float d) {
+    f32x4v v = {a, b, c, d};
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4v *>(dst));
 }
 template <typename T>
 __device__ __forceinline__ void tie(T &x) {
@@ -533,8 +548,7 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
 #pragma unroll
         for (int v = 0; v < 4; ++v)
             if (4 * j + v < d.M)
-                *reinterpret_cast<float4 *>(mine + (size_t)(4 * j + v) * N + n) =
-                    make_float4(yacc[0][v], yacc[1][v], yacc[2][v], yacc[3][v]);
+                sm::store_stream(mine + (size_t)(4 * j + v) * N + n, yacc[0][v], yacc[1][v], yacc[2][v], yacc[3][v]);
     }
 }
 
@@ -638,6 +652,10 @@ struct BwdGeo {
     static constexpr int LDS_BYTES = sm::WG_WAVES * DEPTH * STAGE_BYTES;
     static_assert(LDS_BYTES >= smb::RED_BYTES, "the wave reduction re-uses the stages");
     static_assert(DEPTH * NI < 64, "vmcnt is a 6-bit counter");
+    // mantissa bit at which code c of a lane's 8 codes is left by the shifted view it is taken from
+    __host__ __device__ static constexpr int field_pos(int c) {
+        return BITS == 4 ? 0 : (BITS == 2 ? 2 * (c % 3) : (c < 5 ? 3 * (c % 2) : (c == 6 ? 3 : 0)));
+    }
     // XOR swizzle of a word row's eight 16-byte pieces.  Eight consecutive lanes read one piece
     // each of up to eight different rows at a time (lane 4u + b: 4-bit row 4b + u; 3-bit rows
     // 3b + {0,0,1,2}[u] and 3b + {1,1,2,2}[u]; 2-bit row 2b + u / 2, u in {0,1} or {2,3}); the
@@ -720,8 +738,11 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     auto issue = [&](int slot, int step) {             // step: any step of the workgroup's slice
 #pragma unroll
         for (int q = 0; q < NI; ++q) {
-            if ((q + 1) * 64 <= BG::N_PIECES || q * 64 + lane < BG::N_PIECES)
-                sm::ald_lds64(gaddr[q] + (size_t)step * gstr[q], lds0 + stage0 + (uint32_t)slot * STAGE_BYTES + q * 1024);
+            // loads made of packed words only are read once: non-temporal
+            if ((q + 1) * 64 <= BG::W_PIECES)
+                sm::ald_lds64<true>(gaddr[q] + (size_t)step * gstr[q], lds0 + stage0 + (uint32_t)slot * STAGE_BYTES + q * 1024);
+            else if ((q + 1) * 64 <= BG::N_PIECES || q * 64 + lane < BG::N_PIECES)
+                sm::ald_lds64<false>(gaddr[q] + (size_t)step * gstr[q], lds0 + stage0 + (uint32_t)slot * STAGE_BYTES + q * 1024);
         }
     };
     // step t of this wave, clamped into the slice (a clamped stage is loaded and never used)
@@ -739,7 +760,9 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     }
     const uint32_t ones4[4] = {sm::ONES, sm::ONES, sm::ONES, sm::ONES};
     const bf16x8 ones = sm::as_bf16x8(ones4);
-    const uint32_t fmask = sm::opaque_sgpr(BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x00070007u));
+    // field masks at the positions field_pos() can return (multiples of BITS)
+    constexpr uint32_t FM = BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x00070007u);
+    const uint32_t fmask[3] = {sm::opaque_sgpr(FM), sm::opaque_sgpr(FM << BITS), sm::opaque_sgpr(FM << (2 * BITS))};
     const uint32_t magic = sm::opaque_vgpr(sm::MAGIC);
 
     struct Stage {
@@ -803,6 +826,9 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
             else if (BITS == 3) phi[p] = __builtin_amdgcn_perm(ch[2 * p + 1], ch[2 * p], 0x06050201u);   // bits 8-23
             else phi[p] = 0;
         }
+        // Code c of a pair register: shifted views put 3- and 2-bit fields at mantissa bit 0, 3
+        // (3-bit) or 0, 2, 4 (2-bit); a field at bit s enters the product as 128 + 2^s q, and the
+        // column's factor 2^s is divided out when the tile is finished.
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             uint32_t o[4];
@@ -810,9 +836,9 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
             for (int p = 0; p < 4; ++p) {
                 uint32_t x;
                 if (BITS == 4) x = c < 4 ? plo[p] >> (4 * c) : phi[p] >> (4 * (c - 4));
-                else if (BITS == 2) x = plo[p] >> (2 * c);
-                else x = c < 5 ? plo[p] >> (3 * c) : phi[p] >> (3 * c - 8);
-                o[p] = sm::and_or(x, fmask, magic);
+                else if (BITS == 2) x = plo[p] >> (6 * (c / 3));
+                else x = c < 5 ? plo[p] >> (6 * (c / 2)) : phi[p] >> (c < 7 ? 7 : 13);
+                o[p] = sm::and_or(x, fmask[BG::field_pos(c) / BITS], magic);
             }
             acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), acc[c], 0, 0, 0);
         }
@@ -866,7 +892,8 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     for (int c = 0; c < 8; ++c)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
-            red[(wave * 32 + c * 4 + v) * 64 + lane] = acc[c][v] - 128.0f * accs[v] - accz[v];
+            red[(wave * 32 + c * 4 + v) * 64 + lane] =
+                (acc[c][v] - 128.0f * accs[v]) * (1.0f / (float)(1 << BG::field_pos(c))) - accz[v];
     __syncthreads();
     // thread (wave, lane) finishes D register v = wave of lane's position: row 4j + wave, 8 adjacent k
     float y[8];
@@ -880,8 +907,8 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     const int m = 4 * j + wave, k0 = kt + 32 * b + 8 * u;
     if (m < d.M) {
         float *dst = d.acc + ((size_t)ns * 16 + m) * K + k0;
-        *reinterpret_cast<float4 *>(dst) = make_float4(y[0], y[1], y[2], y[3]);
-        *reinterpret_cast<float4 *>(dst + 4) = make_float4(y[4], y[5], y[6], y[7]);
+        sm::store_stream(dst, y[0], y[1], y[2], y[3]);
+        sm::store_stream(dst + 4, y[4], y[5], y[6], y[7]);
     }
 }
 
