@@ -31,6 +31,7 @@ namespace mlr {
 
 namespace big {
 constexpr int THREADS = 512, NWAVES = 8;
+constexpr int BAND = 4;                  // row blocks per band of the tile walk
 constexpr int MT = 256, CT = 256, WM = 128, WN = 64, RT = 64;
 constexpr int TI = WM / 32, TJ = WN / 32;
 constexpr int ROW_BYTES = RT * 2;                 // 128
@@ -81,8 +82,8 @@ __device__ __forceinline__ void aload_b128(u32x4 &dst, const void *base, uint32_
 
 // What a workgroup works on: a whole tile (slice < 0) or slice `slice` of `split` of a tile.
 // Workgroup ids go round-robin over the 8 XCDs; every XCD gets a contiguous run of the whole
-// tiles first (walked row-block-fastest, so neighbours share the weight tile in its L2) and
-// then a contiguous run of the slices.
+// tiles first (walked in bands of BAND row blocks, see banded_tile()) and then a contiguous
+// run of the slices.
 struct BigItem {
     int tile, slice;
 };
@@ -154,7 +155,8 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
     const BigItem item = big_item_of_block(blockIdx.x, plan);
     if (item.tile < 0) return;   // grid padded to a multiple of 8
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
-    const int m0 = (item.tile % d.tiles_m) * MT, c0 = (item.tile / d.tiles_m) * CT;
+    const TileCoord tco = banded_tile<big::BAND>(item.tile, d.tiles_m, d.tiles_c);
+    const int m0 = tco.tm * MT, c0 = tco.tc * CT;
     const int K = a.w.K, N = a.w.N;
     const int C = BWD ? N : K;
     const int Cout = BWD ? K : N;
@@ -333,6 +335,9 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
     auto mfma_full = [&](const unsigned char *buf) {
         Frags f[2];
         load_frags(f[0], buf, 0);
+        // the wave that feeds the matrix cores issues ahead of its SIMD neighbour, which is
+        // dequantizing the next tile at that time
+        __builtin_amdgcn_s_setprio(2);
 #pragma unroll
         for (int ks = 0; ks < RT / 16; ++ks) {
             // fetch the next step's fragments first, then run this step's 8 MFMAs over them
@@ -341,6 +346,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
             mfma_frags(f[ks & 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
+        __builtin_amdgcn_s_setprio(0);
     };
     auto wait_direct_loads_and_sync = [&]() {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -482,7 +488,8 @@ __global__ __launch_bounds__(big::THREADS) void gemm_big_fixup_kernel(GemmDev d,
     __shared__ __attribute__((aligned(16))) unsigned char smem[NWAVES * 32 * PATCH_ROW * 2];
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int tile = plan.full + blockIdx.x, i = blockIdx.y;
-    const int m0 = (tile % d.tiles_m) * MT, c0 = (tile / d.tiles_m) * CT;
+    const TileCoord tco = banded_tile<big::BAND>(tile, d.tiles_m, d.tiles_c);
+    const int m0 = tco.tm * MT, c0 = tco.tc * CT;
     const int Cout = d.a.backward ? d.a.w.K : d.a.w.N;
     f32x16 acc[TJ];
 #pragma unroll

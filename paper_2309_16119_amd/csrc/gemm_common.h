@@ -24,6 +24,28 @@ __device__ __forceinline__ TileCoord tile_of_block(int bid, int tiles_m, int til
     return tc;
 }
 
+// Row block and column block of a linear tile index when the tiles are walked in bands of
+// BAND row blocks, row-block-fastest inside a band: the ~32 tiles of consecutive index that
+// one XCD runs at a time then span BAND activation panels and 32 / BAND weight panels.  An
+// activation panel is 16 / bits times the bytes of a weight panel, so few rows and many
+// columns keep the bytes that XCD pulls through its L2 lowest (2 rows: about a third of what
+// a whole column of 16 row blocks costs).
+template <int BAND>
+__device__ __forceinline__ TileCoord banded_tile(int tile, int tiles_m, int tiles_c) {
+    const int full = (tiles_m / BAND) * BAND * tiles_c;     // tiles in whole bands
+    TileCoord tc;
+    if (tile < full) {
+        const int band = tile / (BAND * tiles_c), r = tile - band * (BAND * tiles_c);
+        tc.tc = r / BAND;
+        tc.tm = band * BAND + r % BAND;
+    } else {
+        const int rows = tiles_m % BAND, r = tile - full;   // the last, narrower band
+        tc.tc = r / rows;
+        tc.tm = (tiles_m / BAND) * BAND + r % rows;
+    }
+    return tc;
+}
+
 struct GemmDev {
     GemmArgs a;
     int tiles_m, tiles_c;
