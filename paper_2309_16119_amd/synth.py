@@ -70,7 +70,7 @@ CONFIGS = {
 C5_M_SWEEP = (1, 16, 256, 4096)
 
 # one independent random stream per tensor, keyed by these ids
-_STREAM = {"codes": 1, "zeros": 2, "scales": 3, "X": 4, "dY": 5, "A": 6, "B": 7}
+_STREAM = {"codes": 1, "zeros": 2, "scales": 3, "X": 4, "dY": 5, "A": 6, "B": 7, "zeros_f16": 8, "bias": 9}
 
 
 def _rng(seed: int, what: str) -> np.random.Generator:
@@ -135,6 +135,26 @@ def make_layer(cfg: LayerConfig, *, zero_B: bool = False, zero_A: bool = False) 
         codes=codes, qweight=pack_codes(codes, b), zeros=zeros, scales=scales,
         X=X, dY=dY, A=np.ascontiguousarray(A), B=np.ascontiguousarray(B),
     )
+
+
+def make_layer_f16(cfg: LayerConfig, *, with_bias: bool = True) -> dict:
+    """Inputs of the layer in the paper's own storage convention: the same codes, scales, A and B
+    as make_layer(), a binary16 additive zero point per group, U[-(2^b - 1) * scale_hi, 0] (the
+    range the integer zero points times the scales cover), binary16 activations N(0, 1) and a
+    binary16 bias N(0, 0.1)."""
+    L = make_layer(cfg)
+    G = cfg.K // cfg.group
+    span = ((1 << cfg.bits) - 1) * cfg.scale_hi
+    z32 = _rng(cfg.seed, "zeros_f16").uniform(-span, 0.0, size=(G, cfg.N)).astype(np.float32)
+    L["zeros_f16"] = z32.astype(np.float16).view(np.uint16)
+    L["X"] = _rng(cfg.seed, "X").standard_normal((cfg.M, cfg.K), dtype=np.float32).astype(np.float16).view(np.uint16)
+    L["dY"] = _rng(cfg.seed, "dY").standard_normal((cfg.M, cfg.N), dtype=np.float32).astype(np.float16).view(np.uint16)
+    L["bias"] = None
+    if with_bias:
+        b32 = (0.1 * _rng(cfg.seed, "bias").standard_normal(cfg.N, dtype=np.float32)).astype(np.float32)
+        L["bias"] = b32.astype(np.float16).view(np.uint16)
+    del L["zeros"]
+    return L
 
 
 def make_layer_torch(cfg: LayerConfig, device: str = "cuda", seed: int = 0) -> dict:
