@@ -201,6 +201,65 @@ int modulora_adamw(float *param, const float *grad, float *exp_avg, float *exp_a
  * records) and stores the number of records in *count.  Not thread-safe; meant for
  * a benchmark's timed loop, not for production use.
  */
+/* ------------------------------------------------------------------------------------
+ * The layer in the paper's own storage convention (Section 2.2 eq. (2): What = s (.) Wq + z
+ * with a FLOATING zero point z; Section 3.2: z, s and the materialized What in a 16-bit
+ * float; Figure 1 / eq. (3): a bias on the adapted layer):
+ *
+ *     What[n][k] = binary16( binary32( q[n][k] * scales[g][n] + zeros[g][n] ) ),  g = k / group_size
+ *     Y  = X What^T + bias + lora_scale (X A) B
+ *     dX = dY What + lora_scale (dY B^T) A^T         dA, dB as in modulora_bwd_lora
+ *
+ * q: the same LSB-first bitstream as modulora_qweight.qweight.  scales, zeros: IEEE binary16 bit
+ * patterns, [d_in / group_size][d_out]; the zero point is ADDED (eq. (2)); group_size = d_in is
+ * the paper's one (scale, zero) pair per output row.  The affine value is rounded once to binary32
+ * (a fused multiply-add) and then to nearest even to binary16; finite, normal-or-zero scales and
+ * zero points are the contract.  bias: binary16 [d_out] or NULL; it enters the forward pass only
+ * (Figure 1: the frozen parts get no gradient).  X, dY, Y, dX: binary16 bit patterns, row-major.
+ * A, B, XA, dYBt, dA, dB: float32 as in the calls above.  All pointers are DEVICE pointers,
+ * borrowed, 16-byte aligned; the workspace is the caller's (256-byte aligned, at least
+ * modulora_f16_workspace_bytes()).  Shape rules, rank rules, the stream argument, ownership and
+ * error behaviour are those of the calls above: every argument error is found on the host
+ * before any HIP call and returned as a modulora_status; nothing is allocated or synchronized.
+ * ------------------------------------------------------------------------------------ */
+typedef struct {
+    int32_t d_in;
+    int32_t d_out;
+    int32_t bits;              /* 2, 3 or 4 */
+    int32_t group_size;        /* multiple of 32 that divides d_in */
+    const uint32_t *qweight;   /* [d_in * bits / 32][d_out] */
+    const uint16_t *scales;    /* binary16 [d_in / group_size][d_out] */
+    const uint16_t *zeros;     /* binary16 [d_in / group_size][d_out], added */
+    const uint16_t *bias;      /* binary16 [d_out], or NULL */
+} modulora_qweight_f16;
+
+/* Bytes of workspace the three calls below need for (w, M, r); 0 for invalid shapes. */
+size_t modulora_f16_workspace_bytes(const modulora_qweight_f16 *w, int32_t M, int32_t r);
+
+/* Testing only: What as binary16 bit patterns, [d_out][d_in] (eq. (2), rounding as above). */
+int modulora_f16_dequant(const modulora_qweight_f16 *w, uint16_t *What_f16, void *stream);
+
+/* Forward pass of Figure 1 (eq. (3)).  Y [M][d_out] binary16 is overwritten; XA [M][r] (may be
+ * NULL) receives X A.  r == 0 is the plain low-precision linear layer (A, B ignored). */
+int modulora_f16_fwd(const modulora_qweight_f16 *w, const uint16_t *X, int32_t M,
+                     const float *A, const float *B, int32_t r, float lora_scale,
+                     uint16_t *Y, float *XA,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* Input gradient (Figure 1, LPLinear.backward: What is re-materialized, Section 3.1.1).
+ * dX [M][d_in] binary16 is overwritten; dYBt [M][r] (may be NULL) receives dY B^T. */
+int modulora_f16_bwd_input(const modulora_qweight_f16 *w, const uint16_t *dY, int32_t M,
+                           const float *A, const float *B, int32_t r, float lora_scale,
+                           uint16_t *dX, float *dYBt,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* Adapter gradients (Section 3.1.1) from binary16 X and dY; arguments as modulora_bwd_lora. */
+int modulora_f16_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float lora_scale,
+                          const uint16_t *X, const uint16_t *dY, const float *A, const float *B,
+                          const float *XA, const float *dYBt,
+                          float *dA, float *dB, int32_t accumulate,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
 typedef struct {
     char name[64];      /* kernel family and tile variant, NUL-terminated */
     int32_t launches;   /* launches seen since modulora_profile_begin()   */

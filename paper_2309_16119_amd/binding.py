@@ -35,6 +35,14 @@ class modulora_qweight(ctypes.Structure):
     ]
 
 
+class modulora_qweight_f16(ctypes.Structure):
+    _fields_ = [
+        ("d_in", ctypes.c_int32), ("d_out", ctypes.c_int32),
+        ("bits", ctypes.c_int32), ("group_size", ctypes.c_int32),
+        ("qweight", ctypes.c_void_p), ("scales", ctypes.c_void_p), ("zeros", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+    ]
+
+
 class modulora_kernel_time(ctypes.Structure):
     _fields_ = [("name", ctypes.c_char * 64), ("launches", ctypes.c_int32), ("total_ms", ctypes.c_float)]
 
@@ -65,6 +73,17 @@ def _load() -> ctypes.CDLL:
     lib.modulora_bwd_input.argtypes = [qp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]
     lib.modulora_bwd_lora.restype = ctypes.c_int
     lib.modulora_bwd_lora.argtypes = [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
+    qh = ctypes.POINTER(modulora_qweight_f16)
+    lib.modulora_f16_workspace_bytes.restype = sz
+    lib.modulora_f16_workspace_bytes.argtypes = [qh, i32, i32]
+    lib.modulora_f16_dequant.restype = ctypes.c_int
+    lib.modulora_f16_dequant.argtypes = [qh, vp, vp]
+    lib.modulora_f16_fwd.restype = ctypes.c_int
+    lib.modulora_f16_fwd.argtypes = [qh, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]
+    lib.modulora_f16_bwd_input.restype = ctypes.c_int
+    lib.modulora_f16_bwd_input.argtypes = [qh, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]
+    lib.modulora_f16_bwd_lora.restype = ctypes.c_int
+    lib.modulora_f16_bwd_lora.argtypes = [i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.modulora_quantize_rtn.restype = ctypes.c_int
     lib.modulora_quantize_rtn.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.modulora_adamw.restype = ctypes.c_int
@@ -226,6 +245,105 @@ def modulora_bwd_lora(X: torch.Tensor, dY: torch.Tensor, A: torch.Tensor, B: tor
     _check(lib.modulora_bwd_lora(d_in, d_out, M, r, float(lora_scale), _ptr(X), _ptr(dY), _ptr(A), _ptr(B),
                                  _ptr(XA), _ptr(dYBt), _ptr(dA), _ptr(dB), 1 if accumulate else 0,
                                  _ptr(ws), nbytes, _stream()), "modulora_bwd_lora")
+    return dA, dB
+
+
+# ----------------------------------------------------------------------------- paper-literal variant
+class QWeightF16:
+    """The frozen weight in the paper's own convention (eq. (2)): packed codes, binary16 scales,
+    binary16 zero points that are added, optional binary16 bias [d_out]."""
+
+    def __init__(self, qweight: torch.Tensor, scales: torch.Tensor, zeros: torch.Tensor, bias: Optional[torch.Tensor],
+                 d_in: int, d_out: int, bits: int, group_size: int):
+        assert qweight.dtype == torch.int32 and scales.dtype == torch.float16 and zeros.dtype == torch.float16
+        assert bias is None or bias.dtype == torch.float16
+        self.qweight, self.scales, self.zeros, self.bias = qweight, scales, zeros, bias
+        self.d_in, self.d_out, self.bits, self.group_size = d_in, d_out, bits, group_size
+
+    @classmethod
+    def from_numpy(cls, qweight_u32, scales_u16, zeros_u16, bias_u16, d_in, d_out, bits, group_size, device="cuda"):
+        import numpy as np
+        q = torch.from_numpy(np.ascontiguousarray(qweight_u32).view(np.int32)).to(device)
+        s = torch.from_numpy(np.ascontiguousarray(scales_u16).view(np.float16)).to(device)
+        z = torch.from_numpy(np.ascontiguousarray(zeros_u16).view(np.float16)).to(device)
+        b = None if bias_u16 is None else torch.from_numpy(np.ascontiguousarray(bias_u16).view(np.float16)).to(device)
+        return cls(q, s, z, b, d_in, d_out, bits, group_size)
+
+    def c_struct(self) -> modulora_qweight_f16:
+        return modulora_qweight_f16(self.d_in, self.d_out, self.bits, self.group_size, self.qweight.data_ptr(),
+                                    self.scales.data_ptr(), self.zeros.data_ptr(),
+                                    0 if self.bias is None else self.bias.data_ptr())
+
+    @property
+    def device(self):
+        return self.qweight.device
+
+
+def modulora_f16_workspace_bytes(w: QWeightF16, M: int, r: int) -> int:
+    st = w.c_struct()
+    return int(lib.modulora_f16_workspace_bytes(ctypes.byref(st), M, r))
+
+
+def modulora_f16_dequant(w: QWeightF16, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """What [d_out][d_in] float16 (test-only weight materialization)."""
+    if out is None:
+        out = torch.empty((w.d_out, w.d_in), dtype=torch.float16, device=w.device)
+    st = w.c_struct()
+    _check(lib.modulora_f16_dequant(ctypes.byref(st), _ptr(out), _stream()), "modulora_f16_dequant")
+    return out
+
+
+def _f16_call(fn, name, w: QWeightF16, act: torch.Tensor, width_in: int, width_out: int, A, B, lora_scale, out, P, want_P):
+    assert act.dtype == torch.float16 and act.dim() == 2 and act.shape[1] == width_in
+    M = act.shape[0]
+    r = 0 if A is None else A.shape[1]
+    if r:
+        assert A.dtype == torch.float32 and B.dtype == torch.float32
+        assert tuple(A.shape) == (w.d_in, r) and tuple(B.shape) == (r, w.d_out)
+    if out is None:
+        out = torch.empty((M, width_out), dtype=torch.float16, device=act.device)
+    if P is None and want_P and r:
+        P = torch.empty((M, r), dtype=torch.float32, device=act.device)
+    nbytes = modulora_f16_workspace_bytes(w, M, r)
+    ws = _workspace(act.device, nbytes)
+    st = w.c_struct()
+    _check(fn(ctypes.byref(st), _ptr(act), M, _ptr(A), _ptr(B), r, float(lora_scale), _ptr(out), _ptr(P), _ptr(ws), nbytes,
+              _stream()), name)
+    return out, P
+
+
+def modulora_f16_fwd(w: QWeightF16, X, A, B, lora_scale: float, Y=None, XA=None, want_XA: bool = True):
+    """Y = X What^T + bias + lora_scale (X A) B.  Returns (Y fp16 [M][d_out], XA fp32 [M][r] or None)."""
+    return _f16_call(lib.modulora_f16_fwd, "modulora_f16_fwd", w, X, w.d_in, w.d_out, A, B, lora_scale, Y, XA, want_XA)
+
+
+def modulora_f16_bwd_input(w: QWeightF16, dY, A, B, lora_scale: float, dX=None, dYBt=None, want_dYBt: bool = True):
+    """dX = dY What + lora_scale (dY B^T) A^T.  Returns (dX fp16 [M][d_in], dYBt fp32 [M][r] or None)."""
+    return _f16_call(lib.modulora_f16_bwd_input, "modulora_f16_bwd_input", w, dY, w.d_out, w.d_in, A, B, lora_scale, dX, dYBt,
+                     want_dYBt)
+
+
+def modulora_f16_bwd_lora(X: torch.Tensor, dY: torch.Tensor, A: torch.Tensor, B: torch.Tensor, lora_scale: float,
+                          XA: Optional[torch.Tensor] = None, dYBt: Optional[torch.Tensor] = None,
+                          dA: Optional[torch.Tensor] = None, dB: Optional[torch.Tensor] = None, accumulate: bool = False):
+    """dA = s X^T (dY B^T), dB = s (X A)^T dY from float16 X, dY."""
+    M, d_in = X.shape
+    d_out = dY.shape[1]
+    r = A.shape[1]
+    assert X.dtype == torch.float16 and dY.dtype == torch.float16 and dY.shape[0] == M
+    assert tuple(A.shape) == (d_in, r) and tuple(B.shape) == (r, d_out)
+    if dA is None:
+        assert not accumulate
+        dA = torch.empty((d_in, r), dtype=torch.float32, device=X.device)
+    if dB is None:
+        assert not accumulate
+        dB = torch.empty((r, d_out), dtype=torch.float32, device=X.device)
+    shape = modulora_qweight_f16(d_in, d_out, 4, 32, 0, 0, 0, 0)
+    nbytes = int(lib.modulora_f16_workspace_bytes(ctypes.byref(shape), M, r))
+    ws = _workspace(X.device, nbytes)
+    _check(lib.modulora_f16_bwd_lora(d_in, d_out, M, r, float(lora_scale), _ptr(X), _ptr(dY), _ptr(A), _ptr(B),
+                                     _ptr(XA), _ptr(dYBt), _ptr(dA), _ptr(dB), 1 if accumulate else 0,
+                                     _ptr(ws), nbytes, _stream()), "modulora_f16_bwd_lora")
     return dA, dB
 
 

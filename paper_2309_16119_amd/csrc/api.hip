@@ -298,6 +298,131 @@ int modulora_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float l
     return hip_status(mlr::launch_lora_grad_pair(ga, st));
 }
 
+// ---- the paper-literal variant (float zero point, binary16, bias) ---------------------------
+namespace {
+int check_layer_f16(const modulora_qweight_f16 *w, bool pointers) {
+    if (!w) return MODULORA_ERR_NULL;
+    modulora_qweight shape{w->d_in, w->d_out, w->bits, w->group_size, nullptr, nullptr, nullptr};
+    const int s = check_layer_shape(&shape);
+    if (s != MODULORA_OK || !pointers) return s;
+    if (!w->qweight || !w->scales || !w->zeros) return MODULORA_ERR_NULL;
+    if (!aligned16(w->qweight) || !aligned16(w->scales) || !aligned16(w->zeros) || (w->bias && !aligned16(w->bias)))
+        return MODULORA_ERR_ALIGN;
+    return MODULORA_OK;
+}
+mlr::F16Layer view_of(const modulora_qweight_f16 *w) {
+    return mlr::F16Layer{w->d_in, w->d_out, w->bits, w->group_size, w->qweight, w->scales, w->zeros, w->bias};
+}
+struct F16Ws {
+    size_t p0, p1, gpart, total;
+};
+F16Ws f16_ws(int32_t K, int32_t N, int32_t M, int32_t r) {
+    F16Ws l{};
+    if (r <= 0) return l;
+    size_t off = 0;
+    l.p0 = off;    off += align256((size_t)M * r * 4);
+    l.p1 = off;    off += align256((size_t)M * r * 4);
+    l.gpart = off; off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
+    l.total = off;
+    return l;
+}
+int check_ws_f16(const F16Ws &l, const void *ws, size_t bytes) {
+    if (l.total == 0) return MODULORA_OK;
+    if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || bytes < l.total) return MODULORA_ERR_WORKSPACE;
+    return MODULORA_OK;
+}
+}  // namespace
+
+size_t modulora_f16_workspace_bytes(const modulora_qweight_f16 *w, int32_t M, int32_t r) {
+    if (check_layer_f16(w, false) != MODULORA_OK) return 0;
+    if (M < 1 || M > kMaxTokens || r < 0 || r > kMaxRank) return 0;
+    return f16_ws(w->d_in, w->d_out, M, r).total;
+}
+
+int modulora_f16_dequant(const modulora_qweight_f16 *w, uint16_t *What_f16, void *stream) {
+    const int s = check_layer_f16(w, true);
+    if (s != MODULORA_OK) return s;
+    if (!What_f16) return MODULORA_ERR_NULL;
+    if (!aligned16(What_f16)) return MODULORA_ERR_ALIGN;
+    return hip_status(mlr::launch_f16_dequant(view_of(w), What_f16, static_cast<hipStream_t>(stream)));
+}
+
+int modulora_f16_fwd(const modulora_qweight_f16 *w, const uint16_t *X, int32_t M, const float *A, const float *B,
+                     int32_t r, float lora_scale, uint16_t *Y, float *XA, void *workspace, size_t workspace_bytes,
+                     void *stream) {
+    int s = check_layer_f16(w, true);
+    if (s != MODULORA_OK) return s;
+    if (!X || !Y) return MODULORA_ERR_NULL;
+    if (M < 1 || M > kMaxTokens) return MODULORA_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Y) || (XA && !aligned16(XA))) return MODULORA_ERR_ALIGN;
+    if ((s = check_rank(r, A, B, true)) != MODULORA_OK) return s;
+    const F16Ws l = f16_ws(w->d_in, w->d_out, M, r);
+    if ((s = check_ws_f16(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *P = nullptr;
+    if (r > 0) {
+        P = XA ? XA : reinterpret_cast<float *>(static_cast<char *>(workspace) + l.p0);
+        if ((s = hip_status(mlr::launch_f16_proj(X, M, w->d_in, A, true, r, P, st))) != MODULORA_OK) return s;
+    }
+    return hip_status(mlr::launch_f16_gemm(view_of(w), false, X, M, Y, P, B, r, lora_scale, st));
+}
+
+int modulora_f16_bwd_input(const modulora_qweight_f16 *w, const uint16_t *dY, int32_t M, const float *A, const float *B,
+                           int32_t r, float lora_scale, uint16_t *dX, float *dYBt, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+    int s = check_layer_f16(w, true);
+    if (s != MODULORA_OK) return s;
+    if (!dY || !dX) return MODULORA_ERR_NULL;
+    if (M < 1 || M > kMaxTokens) return MODULORA_ERR_SHAPE;
+    if (!aligned16(dY) || !aligned16(dX) || (dYBt && !aligned16(dYBt))) return MODULORA_ERR_ALIGN;
+    if ((s = check_rank(r, A, B, true)) != MODULORA_OK) return s;
+    const F16Ws l = f16_ws(w->d_in, w->d_out, M, r);
+    if ((s = check_ws_f16(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float *P = nullptr;
+    if (r > 0) {
+        P = dYBt ? dYBt : reinterpret_cast<float *>(static_cast<char *>(workspace) + l.p0);
+        if ((s = hip_status(mlr::launch_f16_proj(dY, M, w->d_out, B, false, r, P, st))) != MODULORA_OK) return s;
+    }
+    return hip_status(mlr::launch_f16_gemm(view_of(w), true, dY, M, dX, P, A, r, lora_scale, st));
+}
+
+int modulora_f16_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float lora_scale, const uint16_t *X,
+                          const uint16_t *dY, const float *A, const float *B, const float *XA, const float *dYBt,
+                          float *dA, float *dB, int32_t accumulate, void *workspace, size_t workspace_bytes,
+                          void *stream) {
+    if (d_in < 32 || d_in > kMaxDim || d_out < 8 || d_out > kMaxDim || d_in % 32 != 0 || d_out % 8 != 0)
+        return MODULORA_ERR_SHAPE;
+    if (M < 1 || M > kMaxTokens) return MODULORA_ERR_SHAPE;
+    if (!X || !dY || !dA || !dB) return MODULORA_ERR_NULL;
+    int s = check_rank(r, A, B, false);
+    if (s != MODULORA_OK) return s;
+    if (!aligned16(X) || !aligned16(dY) || !aligned16(dA) || !aligned16(dB) || (XA && !aligned16(XA)) ||
+        (dYBt && !aligned16(dYBt)))
+        return MODULORA_ERR_ALIGN;
+    const F16Ws l = f16_ws(d_in, d_out, M, r);
+    if ((s = check_ws_f16(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    if (!XA) {
+        float *P = reinterpret_cast<float *>(ws + l.p0);
+        if ((s = hip_status(mlr::launch_f16_proj(X, M, d_in, A, true, r, P, st))) != MODULORA_OK) return s;
+        XA = P;
+    }
+    if (!dYBt) {
+        float *P = reinterpret_cast<float *>(ws + l.p1);
+        if ((s = hip_status(mlr::launch_f16_proj(dY, M, d_out, B, false, r, P, st))) != MODULORA_OK) return s;
+        dYBt = P;
+    }
+    mlr::GradPairArgs ga{};
+    ga.X = X; ga.dY = dY; ga.M = M; ga.K = d_in; ga.N = d_out; ga.r = r;
+    ga.XA = XA; ga.dYBt = dYBt; ga.lora_scale = lora_scale;
+    ga.dA = dA; ga.dB = dB; ga.accumulate = accumulate ? 1 : 0;
+    ga.partials = reinterpret_cast<float *>(ws + l.gpart);
+    ga.f16 = 1;
+    return hip_status(mlr::launch_lora_grad_pair(ga, st));
+}
+
 int modulora_quantize_rtn(const float *W, int32_t d_in, int32_t d_out, int32_t bits, int32_t group_size,
                           uint32_t *qweight, uint16_t *scales, uint8_t *zeros, void *stream) {
     modulora_qweight shape{d_in, d_out, bits, group_size, qweight, scales, zeros};

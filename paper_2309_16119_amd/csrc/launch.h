@@ -140,6 +140,7 @@ struct GradPairArgs {
     float *dA, *dB;              // fp32 [K][r], [r][N]
     int accumulate;              // 0: overwrite, 1: add onto the outputs
     float *partials;             // scratch, grad_geom().partial_floats floats
+    int f16;                     // X, dY are binary16 instead of bfloat16 (the paper-literal path)
 };
 struct GradGeom {
     int cpl;                     // columns per lane (2 or 4)
@@ -150,6 +151,22 @@ struct GradGeom {
 };
 GradGeom grad_geom(int M, int K, int N, int r);
 hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream);
+
+// ---- f16_path.hip: the layer in the paper's own storage convention ---------------------
+// (float zero point that is added, binary16 scales / zero points / activations / outputs, bias)
+struct F16Layer {
+    int K, N, bits, group;
+    const uint32_t *qweight;
+    const uint16_t *scales;   // binary16 [K/group][N]
+    const uint16_t *zeros;    // binary16 [K/group][N], added
+    const uint16_t *bias;     // binary16 [N] or NULL
+};
+hipError_t launch_f16_dequant(const F16Layer &w, uint16_t *What, hipStream_t stream);
+// P[M][r] = act[M][C] F, F = A [C][r] (f_is_A) or B^T with B [r][C]
+hipError_t launch_f16_proj(const uint16_t *act, int M, int C, const float *F, bool f_is_A, int r, float *P, hipStream_t stream);
+// forward: out[M][N] = act What^T + bias + s P B; backward: out[M][K] = act What + s P A^T
+hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act, int M, uint16_t *out, const float *P,
+                           const float *Fm, int r, float lora_scale, hipStream_t stream);
 
 // ---- quantize.hip: round-to-nearest group quantizer + packer -------------------------
 struct QuantArgs {

@@ -266,7 +266,8 @@ GradGeom grad_geom(int M, int K, int N, int r) {
     return g;
 }
 
-template <int RP, int CPL>
+// F16: the activations are binary16 (paper-literal path) instead of bfloat16.
+template <int RP, int CPL, bool F16>
 __global__ __launch_bounds__(256) void lora_grad_partial_kernel(GradPairArgs a, GradGeom g) {
     __shared__ float red[3][64][CPL * RP + 1];
     const int lane = threadIdx.x & 63;
@@ -295,8 +296,8 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(GradPairArgs a, 
         for (int q = 0; q < CPL / 2; ++q) {
             uint32_t wq;
             wq = v[q];
-            x[2 * q] = __uint_as_float(wq << 16);
-            x[2 * q + 1] = __uint_as_float(wq & 0xFFFF0000u);
+            x[2 * q] = F16 ? half_bits_to_float((uint16_t)(wq & 0xFFFFu)) : __uint_as_float(wq << 16);
+            x[2 * q + 1] = F16 ? half_bits_to_float((uint16_t)(wq >> 16)) : __uint_as_float(wq & 0xFFFF0000u);
         }
         const float *p = P + (size_t)m * r + j0;
 #pragma unroll
@@ -399,9 +400,15 @@ __global__ __launch_bounds__(256) void lora_grad_reduce_kernel(GradPairArgs a, i
 hipError_t launch_lora_grad_pair(const GradPairArgs &a, hipStream_t stream) {
     const GradGeom g = grad_geom(a.M, a.K, a.N, a.r);
     dim3 grid(g.cols_a + g.cols_b, g.chunks, g.passes);
-    if (a.r <= 8) launch_kernel("lora_grad", lora_grad_partial_kernel<8, 4>, grid, 256, 0, stream, a, g);
-    else if (a.r <= 16) launch_kernel("lora_grad", lora_grad_partial_kernel<16, 4>, grid, 256, 0, stream, a, g);
-    else launch_kernel("lora_grad", lora_grad_partial_kernel<32, 2>, grid, 256, 0, stream, a, g);
+    if (a.f16) {
+        if (a.r <= 8) launch_kernel("lora_grad", lora_grad_partial_kernel<8, 4, true>, grid, 256, 0, stream, a, g);
+        else if (a.r <= 16) launch_kernel("lora_grad", lora_grad_partial_kernel<16, 4, true>, grid, 256, 0, stream, a, g);
+        else launch_kernel("lora_grad", lora_grad_partial_kernel<32, 2, true>, grid, 256, 0, stream, a, g);
+    } else {
+        if (a.r <= 8) launch_kernel("lora_grad", lora_grad_partial_kernel<8, 4, false>, grid, 256, 0, stream, a, g);
+        else if (a.r <= 16) launch_kernel("lora_grad", lora_grad_partial_kernel<16, 4, false>, grid, 256, 0, stream, a, g);
+        else launch_kernel("lora_grad", lora_grad_partial_kernel<32, 2, false>, grid, 256, 0, stream, a, g);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || g.chunks == 1) return e;
     const size_t n = (size_t)(a.K + a.N) * a.r;

@@ -139,3 +139,48 @@ def test_workspace_bytes():
 def test_profile_api_without_launches():
     b.modulora_profile_begin()
     assert b.modulora_profile_end() == {}
+
+
+# ---- the paper-literal variant (binary16 zero points and activations, bias) ----------------
+def qh(d_in=4096, d_out=4096, bits=3, group=128, q=FAKE, s=FAKE, z=FAKE, bias=0):
+    return b.modulora_qweight_f16(d_in, d_out, bits, group, q, s, z, bias)
+
+
+def f16_fwd(w, X=FAKE, M=16, A=FAKE, B=FAKE, r=8, Y=FAKE, XA=0, ws=FAKE, wsb=1 << 30):
+    return b.lib.modulora_f16_fwd(ctypes.byref(w), X, M, A, B, r, 2.0, Y, XA, ws, wsb, None)
+
+
+def f16_bwd(w, dY=FAKE, M=16, A=FAKE, B=FAKE, r=8, dX=FAKE, T=0, ws=FAKE, wsb=1 << 30):
+    return b.lib.modulora_f16_bwd_input(ctypes.byref(w), dY, M, A, B, r, 2.0, dX, T, ws, wsb, None)
+
+
+@pytest.mark.parametrize("call", [f16_fwd, f16_bwd])
+def test_rejections_of_the_f16_calls(call):
+    assert call(qh(bits=5)) == 3
+    assert call(qh(group=100)) == 4
+    assert call(qh(d_in=4100)) == 2
+    assert call(qh(d_out=4100)) == 2
+    assert call(qh(q=0)) == 1
+    assert call(qh(z=ODD)) == 5
+    assert call(qh(bias=ODD)) == 5
+    assert call(qh(), M=0) == 2
+    assert call(qh(), r=65) == 6
+    assert call(qh(), A=0) == 6
+    assert call(qh(), ws=0) == 7
+    assert call(qh(), wsb=16) == 7
+    assert call(qh(), ws=FAKE + 16) == 7
+    assert call(qh(), r=0, A=0, B=0, ws=0, wsb=0) in (0, 8)   # valid; no GPU here, so the launch itself may fail
+
+
+def test_f16_workspace_query_and_dequant_rejections():
+    w = qh()
+    assert b.lib.modulora_f16_workspace_bytes(ctypes.byref(w), 512, 8) > 0
+    assert b.lib.modulora_f16_workspace_bytes(ctypes.byref(w), 512, 0) == 0
+    assert b.lib.modulora_f16_workspace_bytes(ctypes.byref(qh(bits=7)), 512, 8) == 0
+    assert b.lib.modulora_f16_dequant(ctypes.byref(w), 0, None) == 1
+    assert b.lib.modulora_f16_dequant(ctypes.byref(w), ODD, None) == 5
+    bl = b.lib.modulora_f16_bwd_lora
+    assert bl(4096, 4096, 16, 0, 2.0, FAKE, FAKE, FAKE, FAKE, 0, 0, FAKE, FAKE, 0, FAKE, 1 << 30, None) == 6
+    assert bl(4096, 4100, 16, 8, 2.0, FAKE, FAKE, FAKE, FAKE, 0, 0, FAKE, FAKE, 0, FAKE, 1 << 30, None) == 2
+    assert bl(4096, 4096, 16, 8, 2.0, FAKE, 0, FAKE, FAKE, 0, 0, FAKE, FAKE, 0, FAKE, 1 << 30, None) == 1
+    assert bl(4096, 4096, 16, 8, 2.0, FAKE, FAKE, FAKE, FAKE, 0, 0, FAKE, FAKE, 0, 0, 0, None) == 7
