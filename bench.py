@@ -113,6 +113,63 @@ class Workload:
             raise RuntimeError("library call failed with status %d" % rc)
 
 
+class WorkloadF16:
+    """One layer in the paper's own storage convention (float zero point that is added, binary16
+    everywhere, bias): device-drawn inputs with the distributions of synth.make_layer_f16."""
+
+    def __init__(self, cfg, seed=0):
+        import torch
+        from paper_2309_16119_amd import binding as b
+
+        self.cfg, self.b, self.torch = cfg, b, torch
+        K, N, M, r, bits, g = cfg.K, cfg.N, cfg.M, cfg.r, cfg.bits, cfg.group
+        G = K // g
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(seed + 77)
+        self.n_copies = max(1, math.ceil(ROTATE_BYTES / cfg.packed_weight_bytes))
+        self.weights = []
+        span = ((1 << bits) - 1) * cfg.scale_hi
+        for _ in range(self.n_copies):
+            q = torch.randint(-2 ** 31, 2 ** 31 - 1, (K * bits // 32, N), dtype=torch.int32, device="cuda", generator=gen)
+            sc = (torch.rand((G, N), device="cuda", generator=gen) * (cfg.scale_hi - cfg.scale_lo) + cfg.scale_lo).to(torch.float16)
+            z = (-torch.rand((G, N), device="cuda", generator=gen) * span).to(torch.float16)
+            bias = (0.1 * torch.randn((N,), device="cuda", generator=gen)).to(torch.float16)
+            self.weights.append(b.QWeightF16(q, sc, z, bias, K, N, bits, g))
+        self.X = torch.randn((M, K), device="cuda", generator=gen).to(torch.float16)
+        self.dY = torch.randn((M, N), device="cuda", generator=gen).to(torch.float16)
+        self.A = 0.02 * torch.randn((K, r), device="cuda", generator=gen)
+        self.B = 0.02 * torch.randn((r, N), device="cuda", generator=gen)
+        self.Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+        self.dX = torch.empty((M, K), dtype=torch.float16, device="cuda")
+        self.XA = torch.empty((M, r), dtype=torch.float32, device="cuda")
+        self.dYBt = torch.empty((M, r), dtype=torch.float32, device="cuda")
+        self.dA = torch.empty((K, r), dtype=torch.float32, device="cuda")
+        self.dB = torch.empty((r, N), dtype=torch.float32, device="cuda")
+        self.ws_bytes = b.modulora_f16_workspace_bytes(self.weights[0], M, r)
+        self.ws = torch.empty(max(self.ws_bytes, 256), dtype=torch.uint8, device="cuda")
+        self.structs = [w.c_struct() for w in self.weights]
+
+    def step(self, i: int, calls=("fwd", "bwd_input", "bwd_lora")):
+        b, cfg = self.b, self.cfg
+        st = ctypes.byref(self.structs[i % self.n_copies])
+        stream = ctypes.c_void_p(self.torch.cuda.current_stream().cuda_stream)
+        p = lambda t: ctypes.c_void_p(t.data_ptr())
+        s = float(cfg.lora_scale)
+        rc = 0
+        if "fwd" in calls:
+            rc |= b.lib.modulora_f16_fwd(st, p(self.X), cfg.M, p(self.A), p(self.B), cfg.r, s, p(self.Y), p(self.XA),
+                                         p(self.ws), self.ws_bytes, stream)
+        if "bwd_input" in calls:
+            rc |= b.lib.modulora_f16_bwd_input(st, p(self.dY), cfg.M, p(self.A), p(self.B), cfg.r, s, p(self.dX),
+                                               p(self.dYBt), p(self.ws), self.ws_bytes, stream)
+        if "bwd_lora" in calls:
+            rc |= b.lib.modulora_f16_bwd_lora(cfg.K, cfg.N, cfg.M, cfg.r, s, p(self.X), p(self.dY), p(self.A), p(self.B),
+                                              p(self.XA), p(self.dYBt), p(self.dA), p(self.dB), 0, p(self.ws),
+                                              self.ws_bytes, stream)
+        if rc != 0:
+            raise RuntimeError("library call failed with status %d" % rc)
+
+
 class DecoderLayerWorkload:
     """The seven quantized-LoRA linears of one LLaMA-65B decoder layer (q, k, v, o 8192 x 8192;
     gate, up 8192 -> 22016; down 22016 -> 8192; 3-bit, group 128, r = 8) run forward in order,
@@ -525,6 +582,22 @@ def main():
                           "ms_per_step": round(ms3, 5), "tflops": round(dl.flops / (ms3 * 1e-3) / 1e12, 3),
                           "tokens_per_s": round(M_dec / (ms3 * 1e-3), 1), "us_per_step_by_kernel": by_family})
             del dl
+            torch.cuda.empty_cache()
+        # the paper-literal variant (float zero point, binary16, bias) on the headline shape and a large one
+        for cfg_h in (synth.CONFIGS["c2_7b_attn"], synth.CONFIGS["c5_65b_attn"].with_M(4096)):
+            wh = WorkloadF16(cfg_h)
+            msh = time_steps(wh, steps, args.warmup, use_graph)
+            profh = kernel_profile(wh, min(steps, 10))
+            ush = per_call_ms(profh)
+            gname = "f16_gemm_fwd"
+            flops_g = 2.0 * cfg_h.M * cfg_h.K * cfg_h.N
+            ach = flops_g / (ush[gname] * 1e-6) / 1e12
+            extra.append({"workload": "paper-literal f16 variant, %s" % cfg_h.name, "ms_per_step": round(msh, 5),
+                          "tflops": round(cfg_h.flops_fwd_bwd / (msh * 1e-3) / 1e12, 3), "kernel_us": ush,
+                          "roofline": {"kernel": gname, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                                       "avg_kernel_us": ush[gname], "launches": profh[gname][0]}})
+            del wh
             torch.cuda.empty_cache()
         # the round-to-nearest quantizer + packer on the largest layer shape
         Wq = torch.randn((22016, 8192), device="cuda") * 0.02

@@ -25,17 +25,16 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 namespace hf {
 
 constexpr int THREADS = 256;
-constexpr int MT = 128, CT = 128, RT = 64;     // output tile, contraction elements per step
+constexpr int CT = 128, RT = 64;               // output columns of a tile, contraction elements per step
 constexpr int LROW = RT + 8;                   // LDS row stride in elements (144 B: conflict-free 16-byte accesses)
-constexpr int TI = 2, TJ = 2;                  // 32 x 32 MFMA tiles of a wave's 64 x 64 tile
 
 // two floats -> two binary16 (round to nearest even), `lo` in bits 0..15
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-    const _Float16 a = (_Float16)lo, b = (_Float16)hi;
-    uint16_t ua, ub;
-    __builtin_memcpy(&ua, &a, 2);
-    __builtin_memcpy(&ub, &b, 2);
-    return (uint32_t)ua | ((uint32_t)ub << 16);
+    const f16x2 v = {(_Float16)lo, (_Float16)hi};        // v_fma_mixlo_f16 / v_fma_mixhi_f16 when fed by an fma
+    uint32_t u;
+    __builtin_memcpy(&u, &v, 4);
+    return u;
 }
 __device__ __forceinline__ uint16_t to_bits(float v) { return (uint16_t)(pack2(v, 0.f) & 0xFFFFu); }
 
@@ -88,13 +87,13 @@ hipError_t launch_f16_dequant(const F16Layer &w, uint16_t *What, hipStream_t str
 
 // ---------------------------------------------------------------------------------
 // P[m][j] = sum_c act[m][c] F(c, j):  F = A [C][r] (F_IS_A) or B^T with B [r][C].
-// A workgroup owns 4 rows; every thread walks the contraction in chunks of 8 elements
+// A workgroup owns RB = 4 rows (2 when there are few rows); every thread walks the contraction in chunks of 8 elements
 // (16-byte activation loads), keeps 4 x 8 fp32 sums per pass of 8 rank columns, and the 256
 // threads' sums meet through wave shuffles and LDS.
 // ---------------------------------------------------------------------------------
-template <bool F_IS_A>
+template <bool F_IS_A, int RB>
 __global__ __launch_bounds__(256) void f16_proj_kernel(const uint16_t *act, int M, int C, const float *F, int r, float *P) {
-    constexpr int RB = 4, RJ = 8;
+    constexpr int RJ = 8;
     __shared__ float red[4][RB * RJ];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m0 = blockIdx.x * RB;
@@ -158,9 +157,15 @@ __global__ __launch_bounds__(256) void f16_proj_kernel(const uint16_t *act, int 
 }
 
 hipError_t launch_f16_proj(const uint16_t *act, int M, int C, const float *F, bool f_is_A, int r, float *P, hipStream_t stream) {
-    const int blocks = (M + 3) / 4;
-    if (f_is_A) launch_kernel("f16_proj", f16_proj_kernel<true>, blocks, 256, 0, stream, act, M, C, F, r, P);
-    else launch_kernel("f16_proj", f16_proj_kernel<false>, blocks, 256, 0, stream, act, M, C, F, r, P);
+    if (M <= 1024) {
+        const int blocks = (M + 1) / 2;
+        if (f_is_A) launch_kernel("f16_proj", f16_proj_kernel<true, 2>, blocks, 256, 0, stream, act, M, C, F, r, P);
+        else launch_kernel("f16_proj", f16_proj_kernel<false, 2>, blocks, 256, 0, stream, act, M, C, F, r, P);
+    } else {
+        const int blocks = (M + 3) / 4;
+        if (f_is_A) launch_kernel("f16_proj", f16_proj_kernel<true, 4>, blocks, 256, 0, stream, act, M, C, F, r, P);
+        else launch_kernel("f16_proj", f16_proj_kernel<false, 4>, blocks, 256, 0, stream, act, M, C, F, r, P);
+    }
     return hipGetLastError();
 }
 
@@ -168,10 +173,11 @@ hipError_t launch_f16_proj(const uint16_t *act, int M, int C, const float *F, bo
 // out[M][Cout] = act[M][C] (x) What (+ bias) + s P F':
 //   forward : C = K, Cout = N, out[m][n] = sum_k act[m][k] What[n][k] + bias[n] + s sum_j P[m][j] B[j][n]
 //   backward: C = N, Cout = K, out[m][k] = sum_n act[m][n] What[n][k]           + s sum_j P[m][j] A[k][j]
-// 256 threads, 128 x 128 output tile, four waves of 64 x 64; per step of 64 contraction elements
-// the activation tile and the dequantized weight tile go through LDS ([row][contraction],
-// padded rows); the next step's global data is fetched into registers while the MFMAs of
-// the current one run.  Weight staging units, one per thread and step: forward (column, 32-code
+// 256 threads, MT x 128 output tile (MT = 128: four waves of 64 x 64; MT = 64, for shapes
+// with few tiles: four waves of 64 x 32); per step of 64 contraction elements the activation
+// tile and the dequantized weight tile go through LDS ([row][contraction], padded rows, two
+// buffers): the next step's global data is fetched into registers before the MFMAs of the
+// current step are issued and dequantized into the other buffer behind them, one barrier per step.  Weight staging units, one per thread and step: forward (column, 32-code
 // block); backward (n, 32-code block of k), whose 32 values go to 32 LDS rows.
 // ---------------------------------------------------------------------------------
 struct F16GemmArgs {
@@ -186,11 +192,14 @@ struct F16GemmArgs {
     int tiles_m, tiles_c;
 };
 
-template <int BITS, bool BWD>
+template <int BITS, bool BWD, int MT>
 __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
     using namespace hf;
-    __shared__ __attribute__((aligned(16))) uint16_t smem[(MT + CT) * LROW];   // 36 KB
-    uint16_t *As = smem, *Ws = smem + MT * LROW;
+    constexpr int WAVES_M = MT / 64, WAVES_N = 4 / WAVES_M;        // wave grid over the tile
+    constexpr int TI = 2, TJ = CT / WAVES_N / 32;                  // 32 x 32 MFMA tiles of a wave: 2 x 2 or 2 x 1
+    constexpr int A_CH = MT * (RT / 8) / THREADS;                  // 16-byte activation chunks per thread
+    constexpr int BUF = (MT + CT) * LROW;                          // elements of one buffer (A tile, then W tile)
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];   // two buffers
     const TileCoord tcoord = tile_of_block(blockIdx.x, a.tiles_m, a.tiles_c);
     if (tcoord.tm < 0) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
@@ -199,11 +208,11 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
     const int C = BWD ? N : K, Cout = BWD ? K : N;
     const int n_steps = (C + RT - 1) / RT;
 
-    // activation chunks of this thread: 4 x 16 bytes, chunk idx = tid + 256 i -> row idx / 8, piece idx % 8
-    const uint16_t *a_src[4];
-    int a_col[4];
+    // activation chunks of this thread: A_CH x 16 bytes, chunk idx = tid + 256 i -> row idx / 8, piece idx % 8
+    const uint16_t *a_src[A_CH];
+    int a_col[A_CH];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < A_CH; ++i) {
         const int idx = tid + i * THREADS, row = idx >> 3, ch = idx & 7;
         const int m = m0 + row < a.M ? m0 + row : a.M - 1;
         a_src[i] = a.act + (size_t)m * C + ch * 8;
@@ -212,54 +221,73 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
     // weight unit of this thread
     const int u_lo = BWD ? (tid & 63) : (tid & 127);     // forward: column of the tile; backward: n of the step
     const int u_kb = BWD ? (tid >> 6) : (tid >> 7);      // forward: block of the step (0, 1); backward: k block of the tile (0..3)
-    int w_col = 0, kblk = 0, grp_fixed = 0;
+    // Running pointers instead of per-step index arithmetic: fetch(step) is called with step =
+    // 0, 1, 2, ... in order, and every call advances them by one step.
+    const uint32_t *wp;                  // word 0 of this thread's block at the current step
+    const uint16_t *sp, *zp;             // its scale and zero point
+    int blk_in_group = 0;                // forward: 32-code block index inside the quantization group
+    const int bpg = a.w.group / 32;      // blocks per group
     if (!BWD) {
-        w_col = c0 + u_lo < N ? c0 + u_lo : N - 1;       // clamped; never stored
+        const int w_col = c0 + u_lo < N ? c0 + u_lo : N - 1;       // clamped; never stored
+        wp = a.w.qweight + (size_t)u_kb * BITS * N + w_col;
+        const int g0 = (u_kb * 32) / a.w.group;
+        blk_in_group = u_kb - g0 * bpg;
+        sp = a.w.scales + (size_t)g0 * N + w_col;
+        zp = a.w.zeros + (size_t)g0 * N + w_col;
     } else {
         const int k = c0 + u_kb * 32 < K ? c0 + u_kb * 32 : K - 32;
-        kblk = k >> 5;
-        grp_fixed = k / a.w.group;
+        const int g = k / a.w.group;
+        wp = a.w.qweight + (size_t)(k >> 5) * BITS * N + u_lo;
+        sp = a.w.scales + (size_t)g * N + u_lo;
+        zp = a.w.zeros + (size_t)g * N + u_lo;
     }
 
-    uint4 a_reg[4];
-    uint32_t w_reg[BITS];
-    uint32_t sc_reg = 0, z_reg = 0;
-    bool w_ok = false;
-    auto fetch = [&](int step) {
+    // two register sets: the data of step s + 2 is fetched during step s and staged during step s + 1
+    struct Fetched {
+        uint4 a[A_CH];
+        uint32_t w[BITS];
+        uint32_t sc, z;
+        bool ok;
+    };
+    Fetched R[2];
+    auto fetch = [&](int step, Fetched &f) {
         const int r0 = step * RT;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a_reg[i] = make_uint4(0, 0, 0, 0);
-            if (r0 + a_col[i] < C) a_reg[i] = *reinterpret_cast<const uint4 *>(a_src[i] + r0);
+        for (int i = 0; i < A_CH; ++i) {
+            f.a[i] = make_uint4(0, 0, 0, 0);
+            if (r0 + a_col[i] < C) f.a[i] = *reinterpret_cast<const uint4 *>(a_src[i] + r0);
+        }
+        // forward: contraction element r0 + 32 u_kb of column w_col; backward: n = r0 + u_lo
+        f.ok = (BWD ? r0 + u_lo : r0 + u_kb * 32) < C;
+        f.sc = 0; f.z = 0;
+#pragma unroll
+        for (int q = 0; q < BITS; ++q) f.w[q] = 0;
+        if (f.ok) {
+#pragma unroll
+            for (int q = 0; q < BITS; ++q) f.w[q] = wp[(size_t)q * N];
+            f.sc = *sp;
+            f.z = *zp;
         }
         if (!BWD) {
-            const int k = r0 + u_kb * 32;
-            w_ok = k < K;
-            const int kb = w_ok ? (k >> 5) : 0;
+            wp += (size_t)2 * BITS * N;          // two blocks per step
+            blk_in_group += 2;
 #pragma unroll
-            for (int q = 0; q < BITS; ++q) w_reg[q] = a.w.qweight[((size_t)kb * BITS + q) * N + w_col];
-            const int g = (kb * 32) / a.w.group;
-            sc_reg = a.w.scales[(size_t)g * N + w_col];
-            z_reg = a.w.zeros[(size_t)g * N + w_col];
+            for (int t = 0; t < 2; ++t)
+                if (blk_in_group >= bpg) { blk_in_group -= bpg; sp += N; zp += N; }
         } else {
-            const int n = r0 + u_lo;
-            w_ok = n < N;
-            const int nc = w_ok ? n : N - 1;
-#pragma unroll
-            for (int q = 0; q < BITS; ++q) w_reg[q] = a.w.qweight[((size_t)kblk * BITS + q) * N + nc];
-            sc_reg = a.w.scales[(size_t)grp_fixed * N + nc];
-            z_reg = a.w.zeros[(size_t)grp_fixed * N + nc];
+            wp += RT; sp += RT; zp += RT;
         }
     };
-    auto stage = [&]() {
+    auto stage = [&](int buf, const Fetched &f) {
+        uint16_t *As = smem + buf * BUF, *Ws = As + MT * LROW;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < A_CH; ++i) {
             const int idx = tid + i * THREADS, row = idx >> 3;
-            *reinterpret_cast<uint4 *>(As + row * LROW + a_col[i]) = a_reg[i];
+            *reinterpret_cast<uint4 *>(As + row * LROW + a_col[i]) = f.a[i];
         }
         uint32_t o[16];
-        dequant32<BITS>(w_reg, half_bits_to_float((uint16_t)sc_reg), half_bits_to_float((uint16_t)z_reg), o);
-        if (!w_ok) {
+        dequant32<BITS>(f.w, half_bits_to_float((uint16_t)f.sc), half_bits_to_float((uint16_t)f.z), o);
+        if (!f.ok) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[e] = 0;
         }
@@ -284,15 +312,18 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
         for (int j = 0; j < TJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int a_frag = (wm * 64 + (lane & 31)) * LROW + 8 * (lane >> 5);
-    const int w_frag = (wn * 64 + (lane & 31)) * LROW + 8 * (lane >> 5);
+    const int w_frag = MT * LROW + (wn * (32 * TJ) + (lane & 31)) * LROW + 8 * (lane >> 5);
 
-    fetch(0);
-    for (int step = 0; step < n_steps; ++step) {
-        stage();
-        __syncthreads();
-        if (step + 1 < n_steps) fetch(step + 1);
+    fetch(0, R[0]);
+    stage(0, R[0]);
+    if (n_steps > 1) fetch(1, R[1]);
+    __syncthreads();
+    // the loop body for one parity of the step (register sets and LDS buffers alternate)
+    auto one_step = [&](int step, Fetched &mine, Fetched &other) {
+        const uint16_t *As = smem + (step & 1) * BUF, *Ws = As;     // fragment offsets include the W tile's base
+        if (step + 2 < n_steps) fetch(step + 2, mine);              // `mine` was staged during the previous step
 #pragma unroll
         for (int ks = 0; ks < RT / 16; ++ks) {
             f16x8 af[TI], bf[TJ];
@@ -305,12 +336,18 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
 #pragma unroll
                 for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
         }
+        // the other buffer was last read before the previous barrier
+        if (step + 1 < n_steps) stage((step + 1) & 1, other);
         __syncthreads();
+    };
+    for (int step = 0; step < n_steps; step += 2) {
+        one_step(step, R[0], R[1]);
+        if (step + 1 < n_steps) one_step(step + 1, R[1], R[0]);
     }
 
     // ---- epilogue: adapter term (P tile through LDS), bias, one rounding to binary16 -------------
-    static_assert((MT + CT) * LROW * 2 >= MT * 64 * 4, "the P tile fits the tile buffers");
-    float *Ps = reinterpret_cast<float *>(smem);         // [MT][r], r <= 64: at most 32 KB of the 36 KB
+    static_assert(2 * BUF * 2 >= MT * 64 * 4, "the P tile fits the tile buffers");
+    float *Ps = reinterpret_cast<float *>(smem);         // [MT][r], r <= 64: at most 32 KB
     const int r = a.r;
     if (r > 0) {
         for (int x = tid; x < MT * r; x += THREADS) {
@@ -322,7 +359,7 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
     }
 #pragma unroll
     for (int j = 0; j < TJ; ++j) {
-        const int col = c0 + wn * 64 + j * 32 + (lane & 31);
+        const int col = c0 + wn * (32 * TJ) + j * 32 + (lane & 31);
         const bool col_ok = col < Cout;
         const int cc = col_ok ? col : Cout - 1;
         float lora[TI][16];
@@ -352,21 +389,36 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
     }
 }
 
+template <int BITS, bool BWD, int MT>
+static hipError_t launch_f16_gemm_variant(F16GemmArgs &a, hipStream_t stream) {
+    auto kern = f16_gemm_kernel<BITS, BWD, MT>;
+    const size_t lds_bytes = 2 * (size_t)(MT + hf::CT) * hf::LROW * 2;
+    static bool configured[64] = {};
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
+    if (e != hipSuccess) return e;
+    const int Cout = BWD ? a.w.K : a.w.N;
+    a.tiles_m = (a.M + MT - 1) / MT;
+    a.tiles_c = (Cout + hf::CT - 1) / hf::CT;
+    const int blocks = ((a.tiles_m * a.tiles_c + 7) / 8) * 8;
+    launch_kernel(BWD ? "f16_gemm_bwd" : "f16_gemm_fwd", kern, blocks, hf::THREADS, lds_bytes, stream, a);
+    return hipGetLastError();
+}
+
 template <int BITS>
 static hipError_t launch_f16_gemm_bits(F16GemmArgs &a, bool backward, hipStream_t stream) {
-    const int blocks = ((a.tiles_m * a.tiles_c + 7) / 8) * 8;
-    if (backward) launch_kernel("f16_gemm_bwd", f16_gemm_kernel<BITS, true>, blocks, hf::THREADS, 0, stream, a);
-    else launch_kernel("f16_gemm_fwd", f16_gemm_kernel<BITS, false>, blocks, hf::THREADS, 0, stream, a);
-    return hipGetLastError();
+    // 128-row tiles unless they would leave most of the 256 compute units without one
+    const int Cout = backward ? a.w.K : a.w.N;
+    const long tiles128 = (long)((a.M + 127) / 128) * ((Cout + hf::CT - 1) / hf::CT);
+    const bool small = tiles128 < 256;
+    if (backward) return small ? launch_f16_gemm_variant<BITS, true, 64>(a, stream) : launch_f16_gemm_variant<BITS, true, 128>(a, stream);
+    return small ? launch_f16_gemm_variant<BITS, false, 64>(a, stream) : launch_f16_gemm_variant<BITS, false, 128>(a, stream);
 }
 
 hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act, int M, uint16_t *out, const float *P,
                            const float *Fm, int r, float lora_scale, hipStream_t stream) {
     F16GemmArgs a;
     a.w = w; a.act = act; a.M = M; a.out = out; a.P = P; a.Fm = Fm; a.r = r; a.lora_scale = lora_scale;
-    const int Cout = backward ? w.K : w.N;
-    a.tiles_m = (M + hf::MT - 1) / hf::MT;
-    a.tiles_c = (Cout + hf::CT - 1) / hf::CT;
+    a.tiles_m = a.tiles_c = 0;
     switch (w.bits) {
         case 2: return launch_f16_gemm_bits<2>(a, backward, stream);
         case 3: return launch_f16_gemm_bits<3>(a, backward, stream);
