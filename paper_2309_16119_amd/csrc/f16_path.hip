@@ -38,6 +38,30 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 }
 __device__ __forceinline__ uint16_t to_bits(float v) { return (uint16_t)(pack2(v, 0.f) & 0xFFFFu); }
 
+// Loads issued from inline assembly (full per-lane address).  The compiler does not track
+// them: a consumer sits behind wait_vm<N>() followed by tie() of every destination register.
+// Loads return in order, so waiting until at most N remain outstanding completes everything
+// issued before the N most recent ones.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void ld128(u32x4 &dst, const void *p) {
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void ld32(uint32_t &dst, const void *p) {
+    asm volatile("global_load_dword %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void ld16(uint32_t &dst, const void *p) {
+    asm volatile("global_load_ushort %0, %1, off" : "=v"(dst) : "v"(p) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <typename T>
+__device__ __forceinline__ void tie(T &x) {
+    asm volatile("" : "+v"(x)::"memory");
+}
+
 // one code: a single rounding to binary32 inside the fma, then one to binary16
 __device__ __forceinline__ float affine(uint32_t q, float scale, float z) { return __builtin_fmaf((float)q, scale, z); }
 
@@ -242,32 +266,33 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
         zp = a.w.zeros + (size_t)g * N + u_lo;
     }
 
-    // two register sets: the data of step s + 2 is fetched during step s and staged during step s + 1
+    // two register sets: the data of step s + 2 is fetched during step s and staged during step s + 1.
+    // Every fetch issues the same LPF loads (addresses past the end are replaced by the step-0
+    // ones and the values dropped), so that the waits can count.
+    constexpr int LPF = A_CH + BITS + 2;
     struct Fetched {
-        uint4 a[A_CH];
+        u32x4 a[A_CH];
         uint32_t w[BITS];
         uint32_t sc, z;
-        bool ok;
+        bool a_ok[A_CH], ok;
     };
     Fetched R[2];
+    const uint32_t *wp0 = wp;
+    const uint16_t *sp0 = sp, *zp0 = zp;
     auto fetch = [&](int step, Fetched &f) {
         const int r0 = step * RT;
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
-            f.a[i] = make_uint4(0, 0, 0, 0);
-            if (r0 + a_col[i] < C) f.a[i] = *reinterpret_cast<const uint4 *>(a_src[i] + r0);
+            f.a_ok[i] = r0 + a_col[i] < C;
+            ld128(f.a[i], a_src[i] + (f.a_ok[i] ? r0 : 0));
         }
         // forward: contraction element r0 + 32 u_kb of column w_col; backward: n = r0 + u_lo
         f.ok = (BWD ? r0 + u_lo : r0 + u_kb * 32) < C;
-        f.sc = 0; f.z = 0;
+        const uint32_t *wq = f.ok ? wp : wp0;
 #pragma unroll
-        for (int q = 0; q < BITS; ++q) f.w[q] = 0;
-        if (f.ok) {
-#pragma unroll
-            for (int q = 0; q < BITS; ++q) f.w[q] = wp[(size_t)q * N];
-            f.sc = *sp;
-            f.z = *zp;
-        }
+        for (int q = 0; q < BITS; ++q) ld32(f.w[q], wq + (size_t)q * N);
+        ld16(f.sc, f.ok ? sp : sp0);
+        ld16(f.z, f.ok ? zp : zp0);
         if (!BWD) {
             wp += (size_t)2 * BITS * N;          // two blocks per step
             blk_in_group += 2;
@@ -278,12 +303,22 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
             wp += RT; sp += RT; zp += RT;
         }
     };
+    auto landed = [&](Fetched &f) {          // after the wait that covers f's loads
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) tie(f.a[i]);
+#pragma unroll
+        for (int q = 0; q < BITS; ++q) tie(f.w[q]);
+        tie(f.sc);
+        tie(f.z);
+    };
     auto stage = [&](int buf, const Fetched &f) {
         uint16_t *As = smem + buf * BUF, *Ws = As + MT * LROW;
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int idx = tid + i * THREADS, row = idx >> 3;
-            *reinterpret_cast<uint4 *>(As + row * LROW + a_col[i]) = f.a[i];
+            const bool k = f.a_ok[i];
+            *reinterpret_cast<uint4 *>(As + row * LROW + a_col[i]) =
+                make_uint4(k ? f.a[i][0] : 0u, k ? f.a[i][1] : 0u, k ? f.a[i][2] : 0u, k ? f.a[i][3] : 0u);
         }
         uint32_t o[16];
         dequant32<BITS>(f.w, half_bits_to_float((uint16_t)f.sc), half_bits_to_float((uint16_t)f.z), o);
@@ -317,13 +352,20 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
     const int w_frag = MT * LROW + (wn * (32 * TJ) + (lane & 31)) * LROW + 8 * (lane >> 5);
 
     fetch(0, R[0]);
+    if (n_steps > 1) {
+        fetch(1, R[1]);
+        wait_vm<LPF>();
+    } else {
+        wait_vm<0>();
+    }
+    landed(R[0]);
     stage(0, R[0]);
-    if (n_steps > 1) fetch(1, R[1]);
     __syncthreads();
     // the loop body for one parity of the step (register sets and LDS buffers alternate)
     auto one_step = [&](int step, Fetched &mine, Fetched &other) {
         const uint16_t *As = smem + (step & 1) * BUF, *Ws = As;     // fragment offsets include the W tile's base
-        if (step + 2 < n_steps) fetch(step + 2, mine);              // `mine` was staged during the previous step
+        const bool more = step + 2 < n_steps;
+        if (more) fetch(step + 2, mine);                            // `mine` was staged during the previous step
 #pragma unroll
         for (int ks = 0; ks < RT / 16; ++ks) {
             f16x8 af[TI], bf[TJ];
@@ -336,8 +378,13 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
 #pragma unroll
                 for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bf[j], acc[i][j], 0, 0, 0);
         }
-        // the other buffer was last read before the previous barrier
-        if (step + 1 < n_steps) stage((step + 1) & 1, other);
+        // the other buffer was last read before the previous barrier; the loads of `other` are the
+        // ones before this step's fetch
+        if (step + 1 < n_steps) {
+            if (more) wait_vm<LPF>(); else wait_vm<0>();
+            landed(other);
+            stage((step + 1) & 1, other);
+        }
         __syncthreads();
     };
     for (int step = 0; step < n_steps; step += 2) {

@@ -1,9 +1,9 @@
-"""Host-side check of the compiled stream kernels' register allocation.
+"""Host-side check of the register allocation of the kernels that count their loads.
 
-The M <= 16 stream kernels issue their loads from assembly and wait for them with exact
-`vmcnt` counts.  A register spill would add scratch loads and stores that the counts do not
-know about, so the build must not spill in these kernels (and the gfx950 code object must
-not contain scratch accesses at all in that file).
+The M <= 16 stream kernels and the paper-literal tile kernel issue their loads from assembly
+and wait for them with exact `vmcnt` counts.  A register spill would add scratch loads and
+stores that the counts do not know about, so the build must not spill in these kernels (and
+the gfx950 code objects of those files must not contain scratch accesses at all).
 """
 import os
 import re
@@ -45,3 +45,18 @@ def test_stream_kernels_do_not_spill(tmp_path):
     for name, c in counts.items():
         if "smallm_fwd_kernel" in name:
             assert int(c) <= 128, (name, c)
+
+
+@pytest.mark.skipif(_hipcc() is None, reason="hipcc not available")
+def test_f16_tile_kernels_do_not_spill(tmp_path):
+    out = tmp_path / "f16_path.s"
+    cmd = [_hipcc(), *build.HIPCC_FLAGS, "-S", "--cuda-device-only", os.path.join(build.CSRC, "f16_path.hip"), "-o", str(out)]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    text = out.read_text()
+    names = re.findall(r"^\s*\.name:\s+(\S+)", text, flags=re.M)
+    spills = re.findall(r"^\s*\.vgpr_spill_count:\s+(\d+)", text, flags=re.M)
+    assert sum("f16_gemm_kernel" in n for n in names) == 12       # 3 bit widths x forward / backward x 2 tile heights
+    for name, v in zip(names, spills):
+        assert int(v) == 0, "%s spills %s vector registers" % (name, v)
+    assert "scratch_load" not in text and "scratch_store" not in text
