@@ -18,14 +18,21 @@ import torch
 from . import binding as b
 
 
+def _calls(w):
+    """(forward, input gradient, adapter gradients, activation dtype) for the kind of frozen weight:
+    the bfloat16 integer-zero-point layer or the paper-literal binary16 one (b.QWeightF16)."""
+    if isinstance(w, b.QWeightF16):
+        return b.modulora_f16_fwd, b.modulora_f16_bwd_input, b.modulora_f16_bwd_lora, torch.float16
+    return b.modulora_fwd, b.modulora_bwd_input, b.modulora_bwd_lora, torch.bfloat16
+
+
 class LPLoRAFunction(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x: torch.Tensor, A: Optional[torch.Tensor], B: Optional[torch.Tensor], w: b.QWeight,
-                lora_scale: float):
+    def forward(ctx, x: torch.Tensor, A: Optional[torch.Tensor], B: Optional[torch.Tensor], w, lora_scale: float):
         x2 = x.reshape(-1, w.d_in)
         if not x2.is_contiguous():
             x2 = x2.contiguous()
-        y, xa = b.modulora_fwd(w, x2, A, B, lora_scale)
+        y, xa = _calls(w)[0](w, x2, A, B, lora_scale)
         ctx.w, ctx.lora_scale, ctx.x_shape = w, lora_scale, x.shape
         ctx.save_for_backward(x2, A, B, xa)       # activations and adapter only: no weight copy
         return y.view(*x.shape[:-1], w.d_out)
@@ -34,22 +41,25 @@ class LPLoRAFunction(torch.autograd.Function):
     def backward(ctx, grad_y: torch.Tensor):
         x2, A, B, xa = ctx.saved_tensors
         w, s = ctx.w, ctx.lora_scale
+        _, bwd_input, bwd_lora, act_dtype = _calls(w)
         dy = grad_y.reshape(-1, w.d_out)
-        if dy.dtype != torch.bfloat16:
-            dy = dy.to(torch.bfloat16)
+        if dy.dtype != act_dtype:
+            dy = dy.to(act_dtype)
         if not dy.is_contiguous():
             dy = dy.contiguous()
-        dx, t = b.modulora_bwd_input(w, dy, A, B, s)
+        dx, t = bwd_input(w, dy, A, B, s)
         dA = dB = None
         if A is not None and (ctx.needs_input_grad[1] or ctx.needs_input_grad[2]):
-            dA, dB = b.modulora_bwd_lora(x2, dy, A, B, s, XA=xa, dYBt=t)
+            dA, dB = bwd_lora(x2, dy, A, B, s, XA=xa, dYBt=t)
         return dx.view(ctx.x_shape), dA, dB, None, None
 
 
 class ModuLoRALinear(torch.nn.Module):
-    """y = x What^T + (alpha / r) (x A) B with What frozen in 2/3/4-bit group-quantized form."""
+    """y = x What^T + (alpha / r) (x A) B with What frozen in 2/3/4-bit group-quantized form.
+    `w` is a b.QWeight (bfloat16 activations, integer zero points) or a b.QWeightF16 (the paper's
+    own convention: binary16 activations, added float zero point, bias inside `w`)."""
 
-    def __init__(self, w: b.QWeight, r: int = 8, alpha: float = 16.0, device: str = "cuda"):
+    def __init__(self, w, r: int = 8, alpha: float = 16.0, device: str = "cuda"):
         super().__init__()
         self.w = w
         self.r = r

@@ -51,6 +51,36 @@ def test_module_forward_backward_match_the_oracle(bits, K, N, batch, seq, r, gro
         assert layer.A is None and layer.B is None
 
 
+def test_module_over_the_paper_literal_weight():
+    """The same module over a QWeightF16: float16 activations, bias inside the frozen weight."""
+    from oracle import paper_literal as pl
+    from paper_2309_16119_amd import binding as b
+
+    K, N, batch, seq, r = 512, 520, 2, 33, 8
+    M = batch * seq
+    cfg = synth.LayerConfig(name="t", K=K, N=N, bits=3, group=128, M=M, r=r, seed=6)
+    L = synth.make_layer_f16(cfg)
+    w = b.QWeightF16.from_numpy(L["qweight"], L["scales"], L["zeros_f16"], L["bias"], K, N, 3, 128)
+    layer = ModuLoRALinear(w, r=r, alpha=2.0 * r)
+    with torch.no_grad():
+        layer.A.copy_(torch.from_numpy(L["A"]).cuda())
+        layer.B.copy_(torch.from_numpy(L["B"]).cuda())
+    h = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+    x = h(L["X"]).view(batch, seq, K).clone().requires_grad_(True)
+    y = layer(x)
+    assert y.shape == (batch, seq, N) and y.dtype == torch.float16
+    y.backward(h(L["dY"]).view(batch, seq, N))
+    args = (L["qweight"], L["scales"], L["zeros_f16"], K, N, 3, 128)
+    Yr, _ = pl.fwd(*args, L["X"], L["A"], L["B"], 2.0, L["bias"])
+    dXr, _ = pl.bwd_input(*args, L["dY"], L["A"], L["B"], 2.0)
+    dAr, dBr = pl.bwd_lora(L["X"], L["dY"], L["A"], L["B"], 2.0)
+    assert_bar("Y", f64(y).reshape(M, N), Yr)
+    assert_bar("dX", f64(x.grad).reshape(M, K), dXr)
+    assert_bar("dA", f64(layer.A.grad), dAr)
+    assert_bar("dB", f64(layer.B.grad), dBr)
+    assert np.abs(f64(y).reshape(M, N) - Yr).max() <= 2.0 ** -10 * np.abs(Yr).max() + 1e-4
+
+
 def test_module_starts_as_the_plain_quantized_layer_and_trains():
     cfg = synth.LayerConfig(name="t", K=256, N=256, bits=4, group=64, M=32, r=8, seed=4)
     L = synth.make_layer(cfg)
