@@ -38,6 +38,8 @@ def parse_args():
     p.add_argument("--warmup", type=int, default=10)
     p.add_argument("--workload", default="c2_7b_attn")
     p.add_argument("--M", type=int, default=None, help="override the token count of the workload")
+    p.add_argument("--variant", choices=("bf16", "f16"), default="bf16",
+                   help="f16: the layer in the paper's own storage convention (float zero point, binary16, bias)")
     p.add_argument("--no-extra", action="store_true", help="skip the additional workloads")
     p.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -117,7 +119,8 @@ class WorkloadF16:
     """One layer in the paper's own storage convention (float zero point that is added, binary16
     everywhere, bias): device-drawn inputs with the distributions of synth.make_layer_f16."""
 
-    def __init__(self, cfg, seed=0):
+    def __init__(self, cfg, host_layer=None, seed=0):
+        import numpy as np
         import torch
         from paper_2309_16119_amd import binding as b
 
@@ -139,6 +142,12 @@ class WorkloadF16:
         self.dY = torch.randn((M, N), device="cuda", generator=gen).to(torch.float16)
         self.A = 0.02 * torch.randn((K, r), device="cuda", generator=gen)
         self.B = 0.02 * torch.randn((r, N), device="cuda", generator=gen)
+        if host_layer is not None:      # weight copy 0 and the activations are the host layer's (parity against the oracle)
+            L = host_layer
+            self.weights[0] = b.QWeightF16.from_numpy(L["qweight"], L["scales"], L["zeros_f16"], L["bias"], K, N, bits, g)
+            h16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+            self.X, self.dY = h16(L["X"]), h16(L["dY"])
+            self.A, self.B = torch.from_numpy(L["A"]).cuda(), torch.from_numpy(L["B"]).cuda()
         self.Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
         self.dX = torch.empty((M, K), dtype=torch.float16, device="cuda")
         self.XA = torch.empty((M, r), dtype=torch.float32, device="cuda")
@@ -294,7 +303,7 @@ def roofline_of(cfg, prof: dict) -> dict:
     name, (launches, total_ms) = max(prof.items(), key=lambda kv: kv[1][1])
     avg_s = total_ms / launches * 1e-3
     K, N, M, r = cfg.K, cfg.N, cfg.M, cfg.r
-    if name.startswith("gemm_") and M > 16:
+    if "gemm_" in name and M > 16:
         # one product with the frozen weight plus the rank-r up-projection it carries
         cout = N if "fwd" in name else K
         flops = 2.0 * M * K * N + 2.0 * M * r * cout
@@ -331,6 +340,8 @@ def cpu_baseline(host_layer, cfg, wl=None):
     import oracle
 
     L = host_layer
+    if "zeros_f16" in L:
+        return cpu_baseline_f16(L, cfg, wl)
     args = (L["qweight"], L["scales"], L["zeros"], L["K"], L["N"], L["bits"], L["group"])
     t0 = time.perf_counter()
     Yr, _ = oracle.fwd(*args, L["X"], L["A"], L["B"], L["lora_scale"])
@@ -349,6 +360,29 @@ def cpu_baseline(host_layer, cfg, wl=None):
     parity = {"rel_max_err": {"Y": rel(wl.Y, Yr), "dX": rel(wl.dX, dXr), "dA": rel(wl.dA, dAr), "dB": rel(wl.dB, dBr)},
               "bar": 2e-2, "dequant_bit_exact": bool(np.array_equal(What, oracle.dequant_bf16(*args)))}
     parity["rel_max_err"] = {k: float("%.3g" % v) for k, v in parity["rel_max_err"].items()}
+    return base, parity
+
+
+def cpu_baseline_f16(L, cfg, wl):
+    """The paper-literal oracle (numpy float64) timed on one full step, and the GPU outputs against it."""
+    import numpy as np
+    from oracle import paper_literal as pl
+
+    args = (L["qweight"], L["scales"], L["zeros_f16"], L["K"], L["N"], L["bits"], L["group"])
+    t0 = time.perf_counter()
+    Yr, _ = pl.fwd(*args, L["X"], L["A"], L["B"], L["lora_scale"], L["bias"])
+    dXr, _ = pl.bwd_input(*args, L["dY"], L["A"], L["B"], L["lora_scale"])
+    dAr, dBr = pl.bwd_lora(L["X"], L["dY"], L["A"], L["B"], L["lora_scale"])
+    dt = time.perf_counter() - t0
+    base = {"value": round(cfg.flops_fwd_bwd / dt / 1e12, 6), "unit": "TFLOP/s", "cores": os.cpu_count(),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": "one full step (fwd + bwd_input + bwd_lora) of %s, all %d tokens, numpy float64" % (cfg.name, cfg.M)}
+    wl.step(0)
+    wl.torch.cuda.synchronize()
+    rel = lambda got, ref: float("%.3g" % (np.max(np.abs(got.double().cpu().numpy() - ref)) / np.max(np.abs(ref))))
+    What = wl.b.modulora_f16_dequant(wl.weights[0]).cpu().view(wl.torch.int16).numpy().view(np.uint16)
+    parity = {"rel_max_err": {"Y": rel(wl.Y, Yr), "dX": rel(wl.dX, dXr), "dA": rel(wl.dA, dAr), "dB": rel(wl.dB, dBr)},
+              "bar": 2e-2, "dequant_bit_exact": bool(np.array_equal(What, pl.dequant_f16(*args)))}
     return base, parity
 
 
@@ -462,6 +496,8 @@ def main():
               "Run with --gpus 1." % args.gpus, file=sys.stderr)
         sys.exit(2)
     fetch = write = {}
+    if args.variant == "f16":
+        args.no_traffic = True          # the counter child runs replay the default variant
     if not (args.no_traffic or args.pmc_child):
         # before this process touches the GPU: two counter runs in child processes
         wargs = ["--workload", args.workload] + (["--M", str(args.M)] if args.M is not None else [])
@@ -494,8 +530,9 @@ def main():
         torch.cuda.synchronize()
         return
 
-    host_layer = synth.make_layer(cfg)
-    wl = Workload(cfg, host_layer)
+    f16 = args.variant == "f16"
+    host_layer = synth.make_layer_f16(cfg) if f16 else synth.make_layer(cfg)
+    wl = WorkloadF16(cfg, host_layer) if f16 else Workload(cfg, host_layer)
     ms = time_steps(wl, args.steps, args.warmup, use_graph)
     prof = kernel_profile(wl, args.steps)
     tflops = cfg.flops_fwd_bwd / (ms * 1e-3) / 1e12
@@ -504,9 +541,10 @@ def main():
         "metric": "fwd+bwd TFLOP/s per quantized LoRA layer",
         "value": round(tflops, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: d_in=%d d_out=%d %d-bit group %d, M=%d tokens, r=%d, lora_scale=%g" % (
-            cfg.name, cfg.K, cfg.N, cfg.bits, cfg.group, cfg.M, cfg.r, cfg.lora_scale),
+        "dtype": "f16" if f16 else "bf16", "data": "synthetic",
+        "config": {"workload": "%s%s: d_in=%d d_out=%d %d-bit group %d, M=%d tokens, r=%d, lora_scale=%g" % (
+            cfg.name, " (paper-literal f16 variant: float zero point, bias)" if f16 else "", cfg.K, cfg.N, cfg.bits, cfg.group,
+            cfg.M, cfg.r, cfg.lora_scale),
             "weight_copies_rotated": wl.n_copies, "hip_graph": use_graph},
         "roofline": roofline_of(cfg, prof),
         "kernel_us": per_call_ms(prof),
@@ -522,6 +560,8 @@ def main():
     del wl, host_layer
     torch.cuda.empty_cache()
 
+    if f16:
+        args.no_extra = True            # the extra workloads belong to the default variant's line
     if not args.no_extra:
         extra = []
         others = [synth.CONFIGS["c3_7b_gate_up"], synth.CONFIGS["c5_65b_up"].with_M(4096),
