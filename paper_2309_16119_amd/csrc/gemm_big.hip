@@ -342,8 +342,16 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         for (int ks = 0; ks < RT / 16; ++ks) {
             // fetch the next step's fragments first, then run this step's 8 MFMAs over them
             if (ks + 1 < RT / 16) load_frags(f[(ks + 1) & 1], buf, ks + 1);
-            __builtin_amdgcn_sched_barrier(0);
             mfma_frags(f[ks & 1]);
+            if (ks + 1 < RT / 16) {
+                // one LDS read behind each of the first six MFMAs, the last two MFMAs behind them
+#pragma unroll
+                for (int q = 0; q < TI + TJ; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, TI * TJ - (TI + TJ), 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         __builtin_amdgcn_s_setprio(0);
