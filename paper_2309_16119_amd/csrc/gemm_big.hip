@@ -1,30 +1,37 @@
 // The large-M variant of the fused dequantize + bf16 MFMA tile kernel: a 256 x 256
-// output tile per workgroup, 8 waves (two per SIMD) of 128 x 64 each, 64-deep steps on
-// two LDS buffers.  Same mathematics as gemm_tile.hip (ModuLoRA Figure 1: forward
-// X What^T and backward dY What with What re-materialized from the packed codes, plus
-// the adapter term of eq. (3) as an extended contraction); what differs is the data path,
-// chosen from what was measured on MI355X:
+// output tile per workgroup, 8 waves (two per SIMD) of 128 x 64 each, 64-deep steps.
+// Same mathematics as gemm_tile.hip (ModuLoRA Figure 1: forward X What^T and backward
+// dY What with What re-materialized from the packed codes, plus the adapter term of eq. (3)
+// as an extended contraction); what differs is the data path, chosen from what was measured
+// on MI355X:
 //
 //   - LDS stores from registers (ds_write_b128) sustain only ~70 B/clk per CU while
 //     LDS reads sustain ~200: the activation tile therefore never passes through
 //     registers -- it is fetched with direct global->LDS loads (16 B per lane), and only
 //     the dequantized weight tile is written with ds_write.
 //   - Direct loads place lane i's 16 bytes at LDS base + 16 i, so rows cannot be padded.
-//     Rows are 128 B and the 16-byte chunk index is XOR-swizzled with row & 7: 8 lanes
-//     with consecutive rows and the same logical chunk fall on 8 different 16-byte bank
-//     groups.  Measured: operand reads run at the same rate as with (row >> 1) & 7
-//     (~240 B/ns per CU), the 16-byte stores of the forward weight tile (a lane per row)
-//     at 179 instead of 152 B/ns per CU (the other swizzle gave them two-way conflicts).
-//   - The two waves of a SIMD run the halves of a step in opposite order (MFMA of tile t
-//     first / dequantization of tile t+1 first), so that VALU and MFMA overlap.
-//   - The direct loads are issued from inline assembly and awaited with an explicit
-//     s_waitcnt before the step's barrier; the compiler's own (in-order) vmcnt
-//     bookkeeping for the weight-word loads stays valid, only more conservative.
+//     Rows are 128 B and the 16-byte chunk index is XOR-swizzled with (row >> 1) & 7.  The
+//     LDS has 64 banks, so two rows share a bank line: 16 consecutive rows at one logical
+//     chunk (a quarter of a 16-byte fragment read, or of a forward weight-tile store) then
+//     cover all 16 bank groups.  SQ_LDS_BANK_CONFLICT of the backward kernel fell from 40 % of
+//     its active LDS cycles (with row & 7) to nothing.
+//   - All of a CU's 160 KB of LDS: a ring of three activation tiles and two weight tiles.
+//     Every wave runs the same step: the MFMAs of tile t with, between them, its share of
+//     the dequantization of weight tile t + 1 (from registers staged a step earlier) and the
+//     fetches of what comes after -- the packed words of tile t + 2 and, a quarter per
+//     16-deep step, the direct loads of activation tile t + 2.  Stamps written by an
+//     instrumented build showed why: with all fetches at the top of a step the eight waves
+//     queue at the memory pipeline for 500-800 cycles while the matrix cores idle, and loads
+//     issued one step ahead arrive ~300 cycles after the step's MFMAs are done.
+//   - The loads are issued from inline assembly and awaited with an explicit s_waitcnt vmcnt
+//     that leaves exactly the step's four direct loads in flight (loads return in order).
 //   - 256 x 256 tiles rarely come in multiples of the 256 compute units.  The tiles beyond
 //     the last full round are cut into slices of the contraction (BigPlan): every slice is
 //     a workgroup that leaves its fp32 accumulators, in register order, in a scratch buffer,
 //     and gemm_big_fixup_kernel adds the slices of a tile in a fixed order and runs the same
 //     epilogue.  No atomics and no fences, so results do not depend on timing.
+#include <type_traits>
+
 #include "gemm_common.h"
 
 namespace mlr {
@@ -35,15 +42,22 @@ constexpr int BAND = 4;                  // row blocks per band of the tile walk
 constexpr int MT = 256, CT = 256, WM = 128, WN = 64, RT = 64;
 constexpr int TI = WM / 32, TJ = WN / 32;
 constexpr int ROW_BYTES = RT * 2;                 // 128
-constexpr int A_BYTES = MT * ROW_BYTES;           // 32 KB
-constexpr int BUF_BYTES = (MT + CT) * ROW_BYTES;  // 64 KB
+constexpr int A_BYTES = MT * ROW_BYTES;           // 32 KB: one activation tile
+constexpr int W_BYTES = CT * ROW_BYTES;           // 32 KB: one weight tile
+constexpr int A_SLOTS = 3, W_SLOTS = 2;           // activation ring (filled two steps ahead), weight tiles
+constexpr int W_BASE = A_SLOTS * A_BYTES;
+constexpr int LDS_BYTES = A_SLOTS * A_BYTES + W_SLOTS * W_BYTES;   // 160 KB, all of a CU's LDS
 constexpr int A_CH = MT * 8 / THREADS;            // 16-byte activation chunks per thread = 4
 constexpr int W_CH = CT * 8 / THREADS;            // 16-byte chunks of an extension W tile per thread
 constexpr int FW_UNITS = CT * 2 / THREADS;        // (column, 32-code block) units per thread = 1
 constexpr int BW_UNITS = (CT / 8) * (RT / 4) / THREADS;   // (4 n, 8 k) units per thread = 1
+static_assert(A_CH == RT / 16, "one quarter of the activation tile per 16-deep step");
 constexpr int PATCH_ROW = 72;                     // epilogue patch row stride (elements)
 
-__device__ __forceinline__ int swz(int row) { return row & 7; }
+// XOR swizzle of a row's eight 16-byte chunks.  Rows are 128 bytes and the LDS has 64 banks
+// (256 bytes per cycle, 16 lanes of a 16-byte access), so two rows share a bank line: the even
+// rows of 16 consecutive ones need eight different values, and so do the odd ones.
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 // byte offset of logical 16-byte chunk `c` of row `row` inside a tile
 __device__ __forceinline__ int tile_off(int row, int c) { return row * ROW_BYTES + ((c ^ swz(row)) << 4); }
 }  // namespace big
@@ -146,6 +160,26 @@ __device__ __forceinline__ float4 *big_partial_of(float *partials, int tail_tile
     return reinterpret_cast<float4 *>(partials) + ((size_t)tail_tile * split + slice) * (size_t)(big::THREADS * 32);
 }
 
+// Quarter j (0..3) of a 32-code block held in BITS words: its 8 codes dequantized with one
+// (scale, bias) into 8 bfloat16, code 8 j in the low half of out[0].
+template <int BITS>
+__device__ __forceinline__ void dequant_quarter(const uint32_t *w, int j, const DqConst &c, uint32_t out[4]) {
+    if (BITS == 4) {
+        const uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)   // codes 2i (byte i of lo) and 2i+1 (byte i of hi)
+            out[i] = pack_bf16x2(dq_value((lo >> (8 * i)) & 0xFFu, c), dq_value((hi >> (8 * i)) & 0xFFu, c));
+    } else if (BITS == 2) {
+        const uint32_t h = w[j >> 1] >> (16 * (j & 1));   // 8 codes in the low 16 bits
+        const uint32_t even = h & 0x3333u, odd = (h >> 2) & 0x3333u;   // nibble n: code 2n / 2n+1
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            out[i] = pack_bf16x2(dq_value((even >> (4 * i)) & 0xFu, c), dq_value((odd >> (4 * i)) & 0xFu, c));
+    } else {
+        dequant_chunk<BITS>(block_chunk<BITS>(w, j), c, out);
+    }
+}
+
 template <int BITS, bool BWD>
 __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, BigPlan plan) {
     using namespace big;
@@ -185,11 +219,13 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         a_voff[i] = (uint32_t)(((size_t)(m - m0) * C + lc * 8) * 2);
     }
     const uint16_t *act_rowblock = a.act + (size_t)m0 * C;
-    auto issue_a = [&](int t, int buf) {
-        const uint16_t *g = act_rowblock + (size_t)t * RT;
+    // quarter i of activation tile t -> ring slot at byte a_slot (wave-uniform)
+    auto issue_a_part = [&](int t, int a_slot, int i) {
+        load_to_lds_16(act_rowblock + (size_t)t * RT, a_voff[i], lds0 + a_slot + i * (THREADS * 16) + wave * 1024);
+    };
+    auto issue_a = [&](int t, int a_slot) {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i)
-            load_to_lds_16(g, a_voff[i], lds0 + buf * BUF_BYTES + i * (THREADS * 16) + wave * 1024);
+        for (int i = 0; i < A_CH; ++i) issue_a_part(t, a_slot, i);
     };
 
     // ---- weight units -------------------------------------------------------------
@@ -220,77 +256,104 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         bw_soff = (uint32_t)((size_t)((int)d.group_of_block((uint32_t)(k >> 5)) - bw_g0) * N + no * 4);
     }
 
-    // staging registers of the asm loads
-    uint32_t fw_words[BITS] = {};
-    uint32_t fw_scale = 0, fw_zero = 0;
-    u32x4 bw_lo = {0, 0, 0, 0}, bw_hi = {0, 0, 0, 0};
-    u32x2 bw_scale = {0, 0};
-    uint32_t bw_zero = 0;
+    // staging registers of the asm loads: two sets, tile t0 + i goes through set i & 1
+    struct WStage {
+        uint32_t fw_words[BITS];
+        uint32_t fw_scale, fw_zero;
+        u32x4 bw_lo, bw_hi;
+        u32x2 bw_scale;
+        uint32_t bw_zero;
+    };
+    WStage wst[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) wst[i].fw_words[j] = 0;
+        wst[i].fw_scale = wst[i].fw_zero = wst[i].bw_zero = 0;
+        wst[i].bw_lo = wst[i].bw_hi = u32x4{0, 0, 0, 0};
+        wst[i].bw_scale = u32x2{0, 0};
+    }
 
-    auto load_w = [&](int t) {     // raw words, scales and zeros of full main tile t -> registers (async)
+    auto load_w = [&](WStage &st, int t) {     // raw words, scales and zeros of full main tile t -> registers (async)
         if (!BWD) {
             const int blk = t * 2 + fw_kb;
             const uint32_t *wbase = a.w.qweight + (size_t)blk * BITS * N;
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) aload_b32(fw_words[j], wbase + (size_t)j * N, fw_off);
+            for (int j = 0; j < BITS; ++j) aload_b32(st.fw_words[j], wbase + (size_t)j * N, fw_off);
             const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
-            aload_u16(fw_scale, a.w.scales + grow, fw_n * 2);
-            aload_u8(fw_zero, a.w.zeros + grow, fw_n);
+            aload_u16(st.fw_scale, a.w.scales + grow, fw_n * 2);
+            aload_u8(st.fw_zero, a.w.zeros + grow, fw_n);
         } else {
             const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
-            aload_b128(bw_lo, wbase, bw_off);
-            if (BITS == 3) aload_b128(bw_hi, wbase, bw_offhi);
-            aload_b64(bw_scale, a.w.scales + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff * 2);
-            aload_b32(bw_zero, a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff);
+            aload_b128(st.bw_lo, wbase, bw_off);
+            if (BITS == 3) aload_b128(st.bw_hi, wbase, bw_offhi);
+            aload_b64(st.bw_scale, a.w.scales + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff * 2);
+            aload_b32(st.bw_zero, a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff);
         }
     };
     // wait for every outstanding load of this wave (direct and staged) and pin the staged
-    // registers behind the wait
-    auto wait_loads = [&]() {
+    // registers of one set behind the wait
+    // Loads return in order: waiting until at most KEEP remain outstanding completes everything
+    // issued before the KEEP most recent ones.
+    auto wait_loads = [&](WStage &st, auto keep) {
+        constexpr int KEEP = decltype(keep)::value;
         if (!BWD) {
             if (BITS == 2)
-                asm volatile("s_waitcnt vmcnt(0)" : "+v"(fw_words[0]), "+v"(fw_words[1]), "+v"(fw_scale), "+v"(fw_zero)::"memory");
+                asm volatile("s_waitcnt vmcnt(%4)" : "+v"(st.fw_words[0]), "+v"(st.fw_words[1]), "+v"(st.fw_scale), "+v"(st.fw_zero) : "n"(KEEP) : "memory");
             else if (BITS == 3)
-                asm volatile("s_waitcnt vmcnt(0)" : "+v"(fw_words[0]), "+v"(fw_words[1]), "+v"(fw_words[2 % BITS]), "+v"(fw_scale), "+v"(fw_zero)::"memory");
+                asm volatile("s_waitcnt vmcnt(%5)" : "+v"(st.fw_words[0]), "+v"(st.fw_words[1]), "+v"(st.fw_words[2 % BITS]), "+v"(st.fw_scale), "+v"(st.fw_zero) : "n"(KEEP) : "memory");
             else
-                asm volatile("s_waitcnt vmcnt(0)" : "+v"(fw_words[0]), "+v"(fw_words[1]), "+v"(fw_words[2 % BITS]), "+v"(fw_words[3 % BITS]), "+v"(fw_scale), "+v"(fw_zero)::"memory");
+                asm volatile("s_waitcnt vmcnt(%6)" : "+v"(st.fw_words[0]), "+v"(st.fw_words[1]), "+v"(st.fw_words[2 % BITS]), "+v"(st.fw_words[3 % BITS]), "+v"(st.fw_scale), "+v"(st.fw_zero) : "n"(KEEP) : "memory");
         } else {
-            asm volatile("s_waitcnt vmcnt(0)" : "+v"(bw_lo), "+v"(bw_hi), "+v"(bw_scale), "+v"(bw_zero)::"memory");
+            if (BITS == 3) {
+                asm volatile("s_waitcnt vmcnt(%4)" : "+v"(st.bw_lo), "+v"(st.bw_hi), "+v"(st.bw_scale), "+v"(st.bw_zero) : "n"(KEEP) : "memory");
+                // the 8-code chunks straddle two words: join them now, so that a landed set is 4 registers
+#pragma unroll
+                for (int i = 0; i < 4; ++i) st.bw_lo[i] = __builtin_amdgcn_alignbit(st.bw_hi[i], st.bw_lo[i], bw_shift);
+            } else {
+                asm volatile("s_waitcnt vmcnt(%3)" : "+v"(st.bw_lo), "+v"(st.bw_scale), "+v"(st.bw_zero) : "n"(KEEP) : "memory");
+            }
         }
     };
 
-    auto store_w = [&](int buf) {  // dequantize the staged words into the W tile of buffer buf
-        unsigned char *Ws = smem + buf * BUF_BYTES + A_BYTES;
+    // dequantize the staged words of one set into the W tile of buffer buf: quarter `part`
+    // (0..3) of the thread's share, or all of it (part < 0)
+    auto store_w = [&](int buf, const WStage &st, int part) {
+        unsigned char *Ws = smem + W_BASE + buf * W_BYTES;
         if (!BWD) {
             const int nl = tid & (CT - 1);
-            const DqConst dq = make_dq((uint16_t)fw_scale, (uint8_t)fw_zero);
-            uint32_t o[16];
-            dequant_block<BITS>(fw_words, dq, o);
+            const DqConst dq = make_dq((uint16_t)st.fw_scale, (uint8_t)st.fw_zero);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<uint4 *>(Ws + tile_off(nl, fw_kb * 4 + j)) =
-                    make_uint4(o[4 * j], o[4 * j + 1], o[4 * j + 2], o[4 * j + 3]);
+            for (int j = 0; j < 4; ++j) {
+                if (part >= 0 && j != part) continue;
+                uint32_t o[4];
+                dequant_quarter<BITS>(st.fw_words, j, dq, o);
+                *reinterpret_cast<uint4 *>(Ws + tile_off(nl, fw_kb * 4 + j)) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
         } else {
             const int no = tid & 15, ko = tid >> 4;
-            const uint32_t lo[4] = {bw_lo[0], bw_lo[1], bw_lo[2], bw_lo[3]};
-            const uint32_t hi[4] = {bw_hi[0], bw_hi[1], bw_hi[2], bw_hi[3]};
-            const uint32_t sc[2] = {bw_scale[0], bw_scale[1]};
+            const uint32_t sc[2] = {st.bw_scale[0], st.bw_scale[1]};
             uint32_t chunk[4];
             DqConst dq[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                chunk[i] = BITS == 3 ? __builtin_amdgcn_alignbit(hi[i], lo[i], bw_shift) : lo[i] >> bw_shift;
+                chunk[i] = BITS == 3 ? st.bw_lo[i] : st.bw_lo[i] >> bw_shift;   // 3-bit: joined by wait_loads()
                 const uint16_t sb = bw_kok ? (uint16_t)(sc[i >> 1] >> ((i & 1) * 16)) : (uint16_t)0;
-                dq[i] = make_dq(sb, (uint8_t)(bw_zero >> (i * 8)));
+                dq[i] = make_dq(sb, (uint8_t)(st.bw_zero >> (i * 8)));
             }
+            // a 16-lane group fills one row per store; neighbouring groups take their eight rows in
+            // opposite order of parity, so that the two rows of a 32-lane store fall into different
+            // halves of the banks
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
+                if (part >= 0 && kk / 2 != part) continue;
+                const int kq = kk ^ (ko & 1);
                 uint32_t o[2];
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    o[i] = pack_bf16x2(dq_value(chunk_code<BITS>(chunk[2 * i], kk), dq[2 * i]),
-                                       dq_value(chunk_code<BITS>(chunk[2 * i + 1], kk), dq[2 * i + 1]));
-                *reinterpret_cast<uint2 *>(Ws + tile_off(ko * 8 + kk, no >> 1) + (no & 1) * 8) = make_uint2(o[0], o[1]);
+                    o[i] = pack_bf16x2(dq_value(chunk_code<BITS>(chunk[2 * i], kq), dq[2 * i]),
+                                       dq_value(chunk_code<BITS>(chunk[2 * i + 1], kq), dq[2 * i + 1]));
+                *reinterpret_cast<uint2 *>(Ws + tile_off(ko * 8 + kq, no >> 1) + (no & 1) * 8) = make_uint2(o[0], o[1]);
             }
         }
     };
@@ -306,24 +369,23 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
 
     const int wm = wave >> 2, wn = wave & 3;
     const int rowA = wm * WM + (lane & 31), rowW = wn * WN + (lane & 31);
-    // +32 rows leaves the swizzle unchanged, so one offset per 16-deep step serves all i / j
-    int offA[RT / 16], offW[RT / 16];
-#pragma unroll
-    for (int ks = 0; ks < RT / 16; ++ks) {
-        offA[ks] = tile_off(rowA, 2 * ks + (lane >> 5));
-        offW[ks] = A_BYTES + tile_off(rowW, 2 * ks + (lane >> 5));
-    }
+    // +32 rows leaves the swizzle unchanged, so one offset serves all i / j; 16-deep step ks reads
+    // logical chunks 2 ks and 2 ks + 1, and (2 ks + h) ^ z = (2 ks) ^ (h ^ z): its offset is that of
+    // step 0 with ks XOR-ed into bits 5-6 (one VALU operation instead of a register per step)
+    const int offA0 = tile_off(rowA, lane >> 5);
+    const int offW0 = W_BASE + tile_off(rowW, lane >> 5);
 
     struct Frags {
         bf16x8 af[TI], bf[TJ];
     };
-    auto load_frags = [&](Frags &f, const unsigned char *buf, int ks) {
+    // oa: offA0 plus the ring slot's byte offset; wbuf: which weight tile
+    auto load_frags = [&](Frags &f, int oa, int wbuf, int ks) {
 #pragma unroll
         for (int i = 0; i < TI; ++i)
-            f.af[i] = *reinterpret_cast<const bf16x8 *>(buf + offA[ks] + i * 32 * ROW_BYTES);
+            f.af[i] = *reinterpret_cast<const bf16x8 *>(smem + (oa ^ (ks << 5)) + i * 32 * ROW_BYTES);
 #pragma unroll
         for (int j = 0; j < TJ; ++j)
-            f.bf[j] = *reinterpret_cast<const bf16x8 *>(buf + offW[ks] + j * 32 * ROW_BYTES);
+            f.bf[j] = *reinterpret_cast<const bf16x8 *>(smem + (offW0 ^ (ks << 5)) + wbuf * W_BYTES + j * 32 * ROW_BYTES);
     };
     auto mfma_frags = [&](const Frags &f) {
 #pragma unroll
@@ -332,68 +394,56 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
             for (int j = 0; j < TJ; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
     };
-    auto mfma_full = [&](const unsigned char *buf) {
-        Frags f[2];
-        load_frags(f[0], buf, 0);
-        // the wave that feeds the matrix cores issues ahead of its SIMD neighbour, which is
-        // dequantizing the next tile at that time
-        __builtin_amdgcn_s_setprio(2);
+    // ---- steady state: full main tiles -------------------------------------------
+    // Step i works on tile t0 + i: activations in ring slot i % 3, weights in tile buffer i & 1.
+    // Between its MFMAs a wave dequantizes its share of weight tile i + 1 (staged set (i + 1) & 1,
+    // landed before the barrier that ended step i - 1) into the other tile buffer, and issues what
+    // comes later: the words of tile i + 2 into set i & 1 and, one quarter per 16-deep step so that
+    // the waves of a CU do not queue at the memory pipeline all at once, the direct loads of
+    // activation tile i + 2 into the slot that every wave left at the last barrier.  The wait that
+    // ends a step leaves exactly those four direct loads in flight: they have a whole further step
+    // to land.
+    if (t1 > t0) {
+        const int last = t1 - 1;   // past the last tile the fetches repeat it; what they bring is never consumed
+        issue_a(t0, 0);
+        issue_a(t0 + 1 < t1 ? t0 + 1 : last, A_BYTES);
+        load_w(wst[0], t0);
+        wait_loads(wst[0], std::integral_constant<int, 0>());
+        store_w(0, wst[0], -1);
+        load_w(wst[1], t0 + 1 < t1 ? t0 + 1 : last);
+        wait_loads(wst[1], std::integral_constant<int, 0>());
+        __syncthreads();
+        int a_cur = 0, a_nxt = A_BYTES, a_fill = 2 * A_BYTES;   // ring slots (byte offsets, wave-uniform)
+        for (int t = t0; t < t1; t += 2) {
 #pragma unroll
-        for (int ks = 0; ks < RT / 16; ++ks) {
-            // fetch the next step's fragments first, then run this step's 8 MFMAs over them
-            if (ks + 1 < RT / 16) load_frags(f[(ks + 1) & 1], buf, ks + 1);
-            mfma_frags(f[ks & 1]);
-            if (ks + 1 < RT / 16) {
-                // one LDS read behind each of the first six MFMAs, the last two MFMAs behind them
+            for (int u = 0; u < 2; ++u) {
+                const int tt = t + u;
+                if (tt < t1) {
+                    const int ta = tt + 2 < t1 ? tt + 2 : last;
+                    const int oa = offA0 + a_cur;
+                    Frags f[2];
+                    load_frags(f[0], oa, u, 0);
+                    load_w(wst[u], ta);
 #pragma unroll
-                for (int q = 0; q < TI + TJ; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    for (int ks = 0; ks < RT / 16; ++ks) {
+                        issue_a_part(ta, a_fill, ks);
+                        if (ks + 1 < RT / 16) load_frags(f[(ks + 1) & 1], oa, u, ks + 1);
+                        mfma_frags(f[ks & 1]);
+                        store_w(u ^ 1, wst[u ^ 1], ks);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    wait_loads(wst[u], std::integral_constant<int, A_CH>());
+                    __syncthreads();
+                    const int freed = a_cur;
+                    a_cur = a_nxt;
+                    a_nxt = a_fill;
+                    a_fill = freed;
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, TI * TJ - (TI + TJ), 0);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_s_setprio(0);
-    };
-    auto wait_direct_loads_and_sync = [&]() {
+        // the repeated fetches of the last steps still write into the ring
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-    };
-
-    // ---- steady state: full main tiles -------------------------------------------
-    if (t1 > t0) {
-        issue_a(t0, 0);
-        load_w(t0);
-        wait_loads();
-        store_w(0);
-        __syncthreads();
-        if (wave < NWAVES / 2) {
-            // this half of the waves: fetch t+1, MFMA tile t, then dequantize t+1
-            for (int t = t0; t < t1; ++t) {
-                const int cur = (t - t0) & 1, nxt = cur ^ 1;
-                const int tn = t + 1 < t1 ? t + 1 : t1 - 1;   // clamped repeat, never consumed
-                issue_a(tn, nxt);
-                load_w(tn);
-                mfma_full(smem + cur * BUF_BYTES);
-                wait_loads();
-                store_w(nxt);
-                __syncthreads();
-            }
-        } else {
-            // the other half: dequantize t+1 (fetched a step earlier), fetch t+2, MFMA tile t
-            load_w(t0 + 1 < t1 ? t0 + 1 : t0);
-            wait_loads();
-            for (int t = t0; t < t1; ++t) {
-                const int cur = (t - t0) & 1, nxt = cur ^ 1;
-                issue_a(t + 1 < t1 ? t + 1 : t1 - 1, nxt);
-                store_w(nxt);
-                load_w(t + 2 < t1 ? t + 2 : t1 - 1);
-                mfma_full(smem + cur * BUF_BYTES);
-                wait_loads();
-                __syncthreads();
-            }
-        }
     }
 
     // ---- tail: ragged last main tile and the adapter extension, one at a time, through
@@ -403,7 +453,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         const int r0 = ext ? (t - n_main) * RT : t * RT;
         const int ld = ext ? a.RE : C;
         const uint16_t *abase = (ext ? a.act_ext + (size_t)m0 * ld : act_rowblock) + r0;
-        unsigned char *As = smem, *Ws = smem + A_BYTES;
+        unsigned char *As = smem, *Ws = smem + W_BASE;
 #pragma unroll
         for (int i = 0; i < A_CH; ++i) {
             const int idx = i * THREADS + tid;
@@ -431,25 +481,30 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
             const int blk_c = ok ? blk : 0;
             const uint32_t *wbase = a.w.qweight + (size_t)blk_c * BITS * N;
 #pragma unroll
-            for (int j = 0; j < BITS; ++j) fw_words[j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off);
+            for (int j = 0; j < BITS; ++j) wst[0].fw_words[j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off);
             const size_t grow = (size_t)d.group_of_block((uint32_t)blk_c) * N;
-            fw_scale = ok ? (uint32_t)load_at<uint16_t>(a.w.scales + grow, fw_n * 2) : 0u;   // 0 -> weights +0
-            fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
-            store_w(0);
+            wst[0].fw_scale = ok ? (uint32_t)load_at<uint16_t>(a.w.scales + grow, fw_n * 2) : 0u;   // 0 -> weights +0
+            wst[0].fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
+            store_w(0, wst[0], -1);
         } else {
             const bool ok = r0 + (tid & 15) * 4 < N;
-            bw_lo = u32x4{0, 0, 0, 0};
-            bw_hi = u32x4{0, 0, 0, 0};
-            bw_scale = u32x2{0, 0};
-            bw_zero = 0;
+            WStage &st = wst[0];
+            st.bw_lo = u32x4{0, 0, 0, 0};
+            st.bw_hi = u32x4{0, 0, 0, 0};
+            st.bw_scale = u32x2{0, 0};
+            st.bw_zero = 0;
             if (ok) {
                 const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + r0;
-                bw_lo = load_at<u32x4>(wbase, bw_off);
-                if (BITS == 3) bw_hi = load_at<u32x4>(wbase, bw_offhi);
-                bw_scale = load_at<u32x2>(a.w.scales + (size_t)bw_g0 * N + r0, bw_soff * 2);
-                bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
+                st.bw_lo = load_at<u32x4>(wbase, bw_off);
+                if (BITS == 3) {
+                    st.bw_hi = load_at<u32x4>(wbase, bw_offhi);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) st.bw_lo[i] = __builtin_amdgcn_alignbit(st.bw_hi[i], st.bw_lo[i], bw_shift);
+                }
+                st.bw_scale = load_at<u32x2>(a.w.scales + (size_t)bw_g0 * N + r0, bw_soff * 2);
+                st.bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
             }
-            store_w(0);
+            store_w(0, st, -1);
         }
         __syncthreads();
         int ksteps = RT / 16;
@@ -459,14 +514,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         }
         for (int ks = 0; ks < ksteps; ++ks) {
             Frags f;
-            // offA/offW are indexed with a runtime step here: recompute instead
-            const int c = 2 * ks + (lane >> 5);
-#pragma unroll
-            for (int i = 0; i < TI; ++i)
-                f.af[i] = *reinterpret_cast<const bf16x8 *>(smem + tile_off(rowA, c) + i * 32 * ROW_BYTES);
-#pragma unroll
-            for (int j = 0; j < TJ; ++j)
-                f.bf[j] = *reinterpret_cast<const bf16x8 *>(smem + A_BYTES + tile_off(rowW, c) + j * 32 * ROW_BYTES);
+            load_frags(f, offA0, 0, ks);
             mfma_frags(f);
         }
         __syncthreads();
@@ -527,7 +575,7 @@ static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
     const int whole = plan.split > 1 ? plan.full : plan.full + plan.tail;
     const int slices = plan.split > 1 ? plan.tail * plan.split : 0;
     const int blocks = ((whole + 7) / 8 + (slices + 7) / 8) * 8;
-    const size_t lds_bytes = 2 * (size_t)big::BUF_BYTES;
+    const size_t lds_bytes = big::LDS_BYTES;
     auto kern = gemm_big_kernel<BITS, BWD>;
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);

@@ -1,6 +1,6 @@
 """Host-side check of the register allocation of the kernels that count their loads.
 
-The M <= 16 stream kernels and the paper-literal tile kernel issue their loads from assembly
+The M <= 16 stream kernels, the paper-literal tile kernel and the 256 x 256 tile kernel issue their loads from assembly
 and wait for them with exact `vmcnt` counts.  A register spill would add scratch loads and
 stores that the counts do not know about, so the build must not spill in these kernels (and
 the gfx950 code objects of those files must not contain scratch accesses at all).
@@ -57,6 +57,23 @@ def test_f16_tile_kernels_do_not_spill(tmp_path):
     names = re.findall(r"^\s*\.name:\s+(\S+)", text, flags=re.M)
     spills = re.findall(r"^\s*\.vgpr_spill_count:\s+(\d+)", text, flags=re.M)
     assert sum("f16_gemm_kernel" in n for n in names) == 12       # 3 bit widths x forward / backward x 2 tile heights
+    for name, v in zip(names, spills):
+        assert int(v) == 0, "%s spills %s vector registers" % (name, v)
+    assert "scratch_load" not in text and "scratch_store" not in text
+
+
+@pytest.mark.skipif(_hipcc() is None, reason="hipcc not available")
+def test_large_m_tile_kernel_does_not_spill(tmp_path):
+    """The 256 x 256 kernel waits for its assembly-issued loads by count and keeps staged registers
+    untouched while their loads are in flight: no spills, no scratch accesses."""
+    out = tmp_path / "gemm_big.s"
+    cmd = [_hipcc(), *build.HIPCC_FLAGS, "-S", "--cuda-device-only", os.path.join(build.CSRC, "gemm_big.hip"), "-o", str(out)]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    text = out.read_text()
+    names = re.findall(r"^\s*\.name:\s+(\S+)", text, flags=re.M)
+    spills = re.findall(r"^\s*\.vgpr_spill_count:\s+(\d+)", text, flags=re.M)
+    assert sum("gemm_big_kernel" in n for n in names) == 6        # 3 bit widths x forward / backward
     for name, v in zip(names, spills):
         assert int(v) == 0, "%s spills %s vector registers" % (name, v)
     assert "scratch_load" not in text and "scratch_store" not in text
