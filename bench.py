@@ -423,6 +423,10 @@ def rocprof_kernel_pattern(lib_name: str) -> str:
         return "gemm_big_kernel<%d, false"
     if lib_name.startswith("gemm_bwd_256x256"):
         return "gemm_big_kernel<%d, true"
+    if lib_name.startswith("gemm_fwd_128x64s"):
+        return "gemm_mid_kernel<%d, false"
+    if lib_name.startswith("gemm_bwd_128x64s"):
+        return "gemm_mid_kernel<%d, true"
     if lib_name.startswith("gemm_fwd"):
         return "gemm_tile_kernel<%d, false"
     if lib_name.startswith("gemm_bwd"):

@@ -62,38 +62,6 @@ __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 __device__ __forceinline__ int tile_off(int row, int c) { return row * ROW_BYTES + ((c ^ swz(row)) << 4); }
 }  // namespace big
 
-// One direct global->LDS load of 16 bytes per lane: lane i's data lands at
-// lds_base + 16 i (lds_base wave-uniform, in M0).
-__device__ __forceinline__ void load_to_lds_16(const void *gbase_uniform, uint32_t voff_bytes, uint32_t lds_base_uniform) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_base_uniform), "v"(voff_bytes), "s"(gbase_uniform)
-                 : "memory");
-}
-
-// Register loads issued from inline assembly (uniform base + per-lane byte offset).  The
-// compiler does not know that they are in flight: every consumer must sit behind
-// wait_loads(), which also ties the destination registers so that no use can be moved
-// ahead of the wait.  This keeps the compiler from sprinkling conservative vmcnt waits
-// (which would also wait for the direct loads) through the MFMA phase.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ void aload_b32(uint32_t &dst, const void *base, uint32_t voff) {
-    asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
-}
-__device__ __forceinline__ void aload_u16(uint32_t &dst, const void *base, uint32_t voff) {
-    asm volatile("global_load_ushort %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
-}
-__device__ __forceinline__ void aload_u8(uint32_t &dst, const void *base, uint32_t voff) {
-    asm volatile("global_load_ubyte %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
-}
-__device__ __forceinline__ void aload_b64(u32x2 &dst, const void *base, uint32_t voff) {
-    asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
-}
-__device__ __forceinline__ void aload_b128(u32x4 &dst, const void *base, uint32_t voff) {
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
-}
-
 // What a workgroup works on: a whole tile (slice < 0) or slice `slice` of `split` of a tile.
 // Workgroup ids go round-robin over the 8 XCDs; every XCD gets a contiguous run of the whole
 // tiles first (walked in bands of BAND row blocks, see banded_tile()) and then a contiguous
@@ -158,26 +126,6 @@ __device__ __forceinline__ void big_epilogue_rows(const f32x16 (&acc_i)[big::TJ]
 // in register order ([float4 index][thread]), so writes and reads are fully coalesced.
 __device__ __forceinline__ float4 *big_partial_of(float *partials, int tail_tile, int slice, int split) {
     return reinterpret_cast<float4 *>(partials) + ((size_t)tail_tile * split + slice) * (size_t)(big::THREADS * 32);
-}
-
-// Quarter j (0..3) of a 32-code block held in BITS words: its 8 codes dequantized with one
-// (scale, bias) into 8 bfloat16, code 8 j in the low half of out[0].
-template <int BITS>
-__device__ __forceinline__ void dequant_quarter(const uint32_t *w, int j, const DqConst &c, uint32_t out[4]) {
-    if (BITS == 4) {
-        const uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)   // codes 2i (byte i of lo) and 2i+1 (byte i of hi)
-            out[i] = pack_bf16x2(dq_value((lo >> (8 * i)) & 0xFFu, c), dq_value((hi >> (8 * i)) & 0xFFu, c));
-    } else if (BITS == 2) {
-        const uint32_t h = w[j >> 1] >> (16 * (j & 1));   // 8 codes in the low 16 bits
-        const uint32_t even = h & 0x3333u, odd = (h >> 2) & 0x3333u;   // nibble n: code 2n / 2n+1
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            out[i] = pack_bf16x2(dq_value((even >> (4 * i)) & 0xFu, c), dq_value((odd >> (4 * i)) & 0xFu, c));
-    } else {
-        dequant_chunk<BITS>(block_chunk<BITS>(w, j), c, out);
-    }
 }
 
 template <int BITS, bool BWD>

@@ -1,0 +1,500 @@
+// The fused dequantize + bf16 MFMA tile kernel for grids of about one 128 x 64 tile per
+// compute unit (a few hundred tokens against a 4096-wide layer).  Same mathematics as
+// gemm_tile.hip (ModuLoRA Figure 1: forward X What^T and backward dY What with What
+// re-materialized from the packed codes, plus the adapter term of eq. (3) as an extended
+// contraction).
+//
+// With one small tile per CU every 128-deep step holds only 16 MFMAs per SIMD, and in a
+// kernel where every wave fetches, dequantizes, stores, synchronizes and multiplies in
+// turn the costs of a step add up instead of overlapping (measured on the 8-wave k-group
+// variant of gemm_tile.hip: taking out the activation stores, the dequantization or the
+// loads each shortened the kernel by its own share, taking out the MFMAs changed nothing).
+// Here the waves are specialized instead:
+//
+//   - waves 0-3, one per SIMD, are consumers: each owns the whole 128 x 64 tile for a
+//     quarter of every 128-deep step (two 16-deep MFMA steps), reads its fragments and
+//     issues MFMAs, nothing else.  Their four partial tiles are added through LDS at the end.
+//   - waves 4-7, one per SIMD, are producers: they issue the direct global->LDS loads of the
+//     activation tile two steps ahead (ring of three tiles), fetch the packed words one step
+//     ahead into registers and dequantize them into the weight tile of the next step.
+//   - one barrier per step hands the buffers over.  LDS rows are 256 bytes (one line of the
+//     64 banks) with the 16-byte chunk index XOR-ed with row & 15: fragment reads, weight
+//     stores and direct loads are all conflict-free.
+#include <type_traits>
+
+#include "gemm_common.h"
+
+namespace mlr {
+
+namespace mid {
+constexpr int THREADS = 512, CWAVES = 4, PTHREADS = 256;
+constexpr int MT = 128, CT = 64, RT = 128;
+constexpr int TI = MT / 32, TJ = CT / 32;
+constexpr int ROW_BYTES = RT * 2;                 // 256
+constexpr int A_BYTES = MT * ROW_BYTES;           // 32 KB
+constexpr int W_BYTES = CT * ROW_BYTES;           // 16 KB
+constexpr int A_SLOTS = 4, W_SLOTS = 2;
+constexpr int W_BASE = A_SLOTS * A_BYTES;         // 128 KB
+constexpr int LDS_BYTES = W_BASE + W_SLOTS * W_BYTES;   // 160 KB, all of a CU's LDS
+constexpr int W_SETS = 3;                         // staged register sets of packed words
+constexpr int A_CH = MT * 16 / PTHREADS;          // direct loads per producer thread and tile = 8
+constexpr int PATCH_ROW = 72;                     // epilogue patch row stride (elements)
+static_assert((CWAVES - 1) * MT * CT * 4 <= W_BASE, "the partial tiles of three consumers fit the activation ring");
+static_assert(A_SLOTS == 4 && W_SETS == 3, "the steady state below fetches three tiles ahead");
+
+__device__ __forceinline__ int swz(int row) { return row & 15; }
+// byte offset of logical 16-byte chunk `c` (0..15) of row `row` inside a tile
+__device__ __forceinline__ int tile_off(int row, int c) { return row * ROW_BYTES + ((c ^ swz(row)) << 4); }
+}  // namespace mid
+
+template <int BITS, bool BWD>
+__global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
+    using namespace mid;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+    const GemmArgs &a = d.a;
+    const TileCoord tco = tile_of_block(blockIdx.x, d.tiles_m, d.tiles_c);
+    if (tco.tm < 0) return;   // grid padded to a multiple of 8
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
+    const bool producer = wave >= CWAVES;
+    const int ptid = tid & (PTHREADS - 1), pwave = wave & 3;
+    const int m0 = tco.tm * MT, c0 = tco.tc * CT;
+    const int K = a.w.K, N = a.w.N;
+    const int C = BWD ? N : K;
+    const int Cout = BWD ? K : N;
+    const int n_full = C / RT;
+    const int n_main = (C + RT - 1) / RT;
+    const int n_ext = (a.RE + RT - 1) / RT;
+    const int n_tiles = n_main + n_ext;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const uint16_t *act_rowblock = a.act + (size_t)m0 * C;
+
+    // ---- producers: activation tile by direct loads --------------------------------
+    // chunk idx = i*256 + ptid sits at byte 16*idx of the tile: row idx/16, physical chunk
+    // idx%16, which holds logical chunk (idx%16) ^ swz(row).
+    uint32_t a_voff[A_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+        const int idx = i * PTHREADS + ptid;
+        const int row = idx >> 4, lc = (idx & 15) ^ swz(row);
+        int m = m0 + row;
+        if (m > a.M - 1) m = a.M - 1;
+        a_voff[i] = (uint32_t)(((size_t)(m - m0) * C + lc * 8) * 2);
+    }
+    auto issue_a_part = [&](int t, int a_slot, int i) {
+        load_to_lds_16(act_rowblock + (size_t)t * RT, a_voff[i], lds0 + a_slot + i * (PTHREADS * 16) + pwave * 1024);
+    };
+
+    // ---- producers: weight units ------------------------------------------------------
+    // forward: one (column, 32-code block) per thread; backward: one (4 n, 8 k) unit per thread
+    uint32_t fw_off = 0, fw_n = 0;
+    uint32_t bw_off = 0, bw_offhi = 0, bw_soff = 0;
+    int bw_shift = 0, bw_row0 = 0, bw_g0 = 0;
+    bool bw_kok = true;
+    if (!BWD) {
+        int n = c0 + (ptid & (CT - 1));
+        if (n > N - 1) n = N - 1;
+        fw_n = (uint32_t)n;
+        fw_off = (uint32_t)n * 4u;
+    } else {
+        bw_row0 = (c0 * BITS) >> 5;
+        bw_g0 = (int)d.group_of_block((uint32_t)(c0 >> 5));
+        const int last_row = K * BITS / 32 - 1;
+        const int no = ptid & 31, ko = ptid >> 5;
+        int k = c0 + ko * 8;
+        bw_kok = k < K;
+        if (k > K - 8) k = K - 8;
+        const int bit = k * BITS, row = bit >> 5;
+        const int row_hi = row + 1 > last_row ? last_row : row + 1;
+        bw_shift = bit & 31;
+        bw_off = (uint32_t)(((size_t)(row - bw_row0) * N + no * 4) * 4);
+        bw_offhi = (uint32_t)(((size_t)(row_hi - bw_row0) * N + no * 4) * 4);
+        bw_soff = (uint32_t)((size_t)((int)d.group_of_block((uint32_t)(k >> 5)) - bw_g0) * N + no * 4);
+    }
+
+    // staging registers of the asm loads: three sets, main tile i goes through set i % 3
+    struct WStage {
+        uint32_t fw_words[BITS];
+        uint32_t fw_scale, fw_zero;
+        u32x4 bw_lo, bw_hi;
+        u32x2 bw_scale;
+        uint32_t bw_zero;
+    };
+    WStage wst[W_SETS];
+#pragma unroll
+    for (int i = 0; i < W_SETS; ++i) {
+#pragma unroll
+        for (int j = 0; j < BITS; ++j) wst[i].fw_words[j] = 0;
+        wst[i].fw_scale = wst[i].fw_zero = wst[i].bw_zero = 0;
+        wst[i].bw_lo = wst[i].bw_hi = u32x4{0, 0, 0, 0};
+        wst[i].bw_scale = u32x2{0, 0};
+    }
+    auto load_w = [&](WStage &st, int t) {     // raw words, scales and zeros of full main tile t -> registers (async)
+        if (!BWD) {
+            const int blk = t * (RT / 32) + pwave;
+            const uint32_t *wbase = a.w.qweight + (size_t)blk * BITS * N;
+#pragma unroll
+            for (int j = 0; j < BITS; ++j) aload_b32(st.fw_words[j], wbase + (size_t)j * N, fw_off);
+            const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
+            aload_u16(st.fw_scale, a.w.scales + grow, fw_n * 2);
+            aload_u8(st.fw_zero, a.w.zeros + grow, fw_n);
+        } else {
+            const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
+            aload_b128(st.bw_lo, wbase, bw_off);
+            if (BITS == 3) aload_b128(st.bw_hi, wbase, bw_offhi);
+            aload_b64(st.bw_scale, a.w.scales + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff * 2);
+            aload_b32(st.bw_zero, a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff);
+        }
+    };
+    // Loads return in order: waiting until at most KEEP remain outstanding completes everything
+    // issued before the KEEP most recent ones.  The staged registers of the set are pinned behind
+    // the wait.
+    auto wait_loads = [&](WStage &st, auto keep) {
+        constexpr int KEEP = decltype(keep)::value;
+        if (!BWD) {
+            if (BITS == 2)
+                asm volatile("s_waitcnt vmcnt(%4)" : "+v"(st.fw_words[0]), "+v"(st.fw_words[1]), "+v"(st.fw_scale), "+v"(st.fw_zero) : "n"(KEEP) : "memory");
+            else if (BITS == 3)
+                asm volatile("s_waitcnt vmcnt(%5)" : "+v"(st.fw_words[0]), "+v"(st.fw_words[1]), "+v"(st.fw_words[2 % BITS]), "+v"(st.fw_scale), "+v"(st.fw_zero) : "n"(KEEP) : "memory");
+            else
+                asm volatile("s_waitcnt vmcnt(%6)" : "+v"(st.fw_words[0]), "+v"(st.fw_words[1]), "+v"(st.fw_words[2 % BITS]), "+v"(st.fw_words[3 % BITS]), "+v"(st.fw_scale), "+v"(st.fw_zero) : "n"(KEEP) : "memory");
+        } else {
+            if (BITS == 3) {
+                asm volatile("s_waitcnt vmcnt(%4)" : "+v"(st.bw_lo), "+v"(st.bw_hi), "+v"(st.bw_scale), "+v"(st.bw_zero) : "n"(KEEP) : "memory");
+                // the 8-code chunks straddle two words: join them now
+#pragma unroll
+                for (int i = 0; i < 4; ++i) st.bw_lo[i] = __builtin_amdgcn_alignbit(st.bw_hi[i], st.bw_lo[i], bw_shift);
+            } else {
+                asm volatile("s_waitcnt vmcnt(%3)" : "+v"(st.bw_lo), "+v"(st.bw_scale), "+v"(st.bw_zero) : "n"(KEEP) : "memory");
+            }
+        }
+    };
+    // dequantize the staged words of one set into weight tile `buf`: quarter `part` (0..3) of
+    // the thread's share, or all of it (part < 0)
+    auto store_w = [&](int buf, const WStage &st, int part) {
+        unsigned char *Ws = smem + W_BASE + buf * W_BYTES;
+        if (!BWD) {
+            const int nl = ptid & (CT - 1);
+            const DqConst dq = make_dq((uint16_t)st.fw_scale, (uint8_t)st.fw_zero);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (part >= 0 && j != part) continue;
+                uint32_t o[4];
+                dequant_quarter<BITS>(st.fw_words, j, dq, o);
+                *reinterpret_cast<uint4 *>(Ws + tile_off(nl, pwave * 4 + j)) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+        } else {
+            const int no = ptid & 31, ko = ptid >> 5;
+            const uint32_t sc[2] = {st.bw_scale[0], st.bw_scale[1]};
+            uint32_t chunk[4];
+            DqConst dq[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                chunk[i] = BITS == 3 ? st.bw_lo[i] : st.bw_lo[i] >> bw_shift;   // 3-bit: joined by wait_loads()
+                const uint16_t sb = bw_kok ? (uint16_t)(sc[i >> 1] >> ((i & 1) * 16)) : (uint16_t)0;
+                dq[i] = make_dq(sb, (uint8_t)(st.bw_zero >> (i * 8)));
+            }
+            // 32 lanes fill one whole row per store
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                if (part >= 0 && kk / 2 != part) continue;
+                uint32_t o[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    o[i] = pack_bf16x2(dq_value(chunk_code<BITS>(chunk[2 * i], kk), dq[2 * i]),
+                                       dq_value(chunk_code<BITS>(chunk[2 * i + 1], kk), dq[2 * i + 1]));
+                *reinterpret_cast<uint2 *>(Ws + tile_off(ko * 8 + kk, no >> 1) + (no & 1) * 8) = make_uint2(o[0], o[1]);
+            }
+        }
+    };
+
+    // ---- tail tiles (ragged last main tile, adapter extension): staged one at a time through
+    // registers into slot 0 / weight tile 0 by all waves (predicated; a handful of tiles at most)
+    auto tail_geometry = [&](int t, bool &ext, int &r0, int &ksteps) {
+        ext = t >= n_main;
+        r0 = ext ? (t - n_main) * RT : t * RT;
+        ksteps = RT / 16;
+        if (ext) {
+            ksteps = (a.RE - r0) / 16;
+            if (ksteps > RT / 16) ksteps = RT / 16;
+        }
+    };
+    auto stage_tail_tile = [&](int t, bool is_producer) {
+        bool ext;
+        int r0, ksteps;
+        tail_geometry(t, ext, r0, ksteps);
+        const int ld = ext ? a.RE : C;
+        const uint16_t *abase = (ext ? a.act_ext + (size_t)m0 * ld : act_rowblock) + r0;
+        unsigned char *As = smem, *Ws = smem + W_BASE;
+#pragma unroll
+        for (int i = 0; i < MT * 16 / THREADS; ++i) {
+            const int idx = i * THREADS + tid;
+            const int row = idx >> 4, ch = idx & 15;
+            int m = m0 + row;
+            if (m > a.M - 1) m = a.M - 1;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (r0 + ch * 8 < ld) v = load_at<uint4>(abase, (uint32_t)(((size_t)(m - m0) * ld + ch * 8) * 2));
+            *reinterpret_cast<uint4 *>(As + tile_off(row, ch)) = v;
+        }
+        if (ext) {
+#pragma unroll
+            for (int i = 0; i < CT * 16 / THREADS; ++i) {
+                const int idx = i * THREADS + tid;
+                const int row = idx >> 4, ch = idx & 15;
+                int c = c0 + row;
+                if (c > Cout - 1) c = Cout - 1;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (r0 + ch * 8 < a.RE) v = *reinterpret_cast<const uint4 *>(a.w_ext + (size_t)c * a.RE + r0 + ch * 8);
+                *reinterpret_cast<uint4 *>(Ws + tile_off(row, ch)) = v;
+            }
+        } else if (is_producer) {
+            WStage &st = wst[0];
+            if (!BWD) {
+                const int blk = t * (RT / 32) + pwave;
+                const bool ok = blk * 32 < K;
+                const int blk_c = ok ? blk : 0;
+                const uint32_t *wbase = a.w.qweight + (size_t)blk_c * BITS * N;
+#pragma unroll
+                for (int j = 0; j < BITS; ++j) st.fw_words[j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off);
+                const size_t grow = (size_t)d.group_of_block((uint32_t)blk_c) * N;
+                st.fw_scale = ok ? (uint32_t)load_at<uint16_t>(a.w.scales + grow, fw_n * 2) : 0u;   // 0 -> weights +0
+                st.fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
+            } else {
+                const bool ok = r0 + (ptid & 31) * 4 < N;
+                st.bw_lo = u32x4{0, 0, 0, 0};
+                st.bw_hi = u32x4{0, 0, 0, 0};
+                st.bw_scale = u32x2{0, 0};
+                st.bw_zero = 0;
+                if (ok) {
+                    const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + r0;
+                    st.bw_lo = load_at<u32x4>(wbase, bw_off);
+                    if (BITS == 3) {
+                        st.bw_hi = load_at<u32x4>(wbase, bw_offhi);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) st.bw_lo[i] = __builtin_amdgcn_alignbit(st.bw_hi[i], st.bw_lo[i], bw_shift);
+                    }
+                    st.bw_scale = load_at<u32x2>(a.w.scales + (size_t)bw_g0 * N + r0, bw_soff * 2);
+                    st.bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
+                }
+            }
+            store_w(0, st, -1);
+        }
+    };
+
+    // Producers and consumers run separate loops that meet at the same barriers (every wave of the
+    // workgroup executes the same number of them).
+    //
+    // Step i of the steady state (full main tiles): consumers work on activation slot i % 4 and
+    // weight tile i & 1, and send the direct loads of activation tile i + 3 into the slot they left
+    // at the last barrier.  Producers dequantize weight tile i + 1 from staged set (i + 1) % 3 and
+    // then refill that set with the words of tile i + 4.  A step is shorter than a trip to memory,
+    // hence the distances.  Loads return in order, so "at most n still in flight" completes all
+    // but the n most recent: a producer opens step i with the words of tiles i + 2 and i + 3 still
+    // allowed in flight, a consumer ends it with the direct loads of tiles i + 2 and i + 3.
+    // The memory pipeline of a CU accepts about 64 bytes per clock, which the 32 KB of an
+    // activation tile fill for most of a step: the producers' few loads are issued last in a step,
+    // where they do not queue behind the direct loads with the dequantization still ahead of them.
+    constexpr int W_LOADS = BWD ? (BITS == 3 ? 4 : 3) : BITS + 2;   // load instructions of one load_w()
+    const int last = n_full - 1;   // past the last tile the fetches repeat it; what they bring is never consumed
+    if (producer) {
+        if (n_full > 0) {
+            load_w(wst[0], 0);
+            load_w(wst[1], last < 1 ? last : 1);
+            load_w(wst[2], last < 2 ? last : 2);
+            // everything has landed after this wait; sets 1 and 2 are pinned (and, for 3-bit backward,
+            // joined) by the waits that open steps 0 and 1, the only ones they pass through
+            wait_loads(wst[0], std::integral_constant<int, 0>());
+            store_w(0, wst[0], -1);
+            load_w(wst[0], last < 3 ? last : 3);
+            __syncthreads();
+            for (int t = 0; t < n_full; t += 3) {
+#pragma unroll
+                for (int u = 0; u < 3; ++u) {
+                    const int tt = t + u;
+                    if (tt < n_full) {
+                        WStage &st = wst[(u + 1) % 3];          // words of tile tt + 1
+                        const int wbuf = (tt + 1) & 1;
+                        wait_loads(st, std::integral_constant<int, 2 * W_LOADS>());
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            store_w(wbuf, st, q);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        // the set is free again: fetch tile tt + 4 now, when the consumers' direct
+                        // loads of this step are through the memory pipeline
+                        load_w(st, tt + 4 < n_full ? tt + 4 : last);
+                        __syncthreads();
+                    }
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+        for (int t = n_full; t < n_tiles; ++t) {
+            stage_tail_tile(t, true);
+            __syncthreads();
+            __syncthreads();
+        }
+        __syncthreads();   // the consumers' two barriers around their sum
+        __syncthreads();
+        return;
+    }
+
+    // ---- consumers ------------------------------------------------------------------------
+    f32x16 acc[TI][TJ];
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // consumer `wave` takes the 16-deep steps 2 wave and 2 wave + 1 of a tile: logical chunks
+    // 4 wave + 2 s + h for its step s and lane half h.  +32 rows leaves the swizzle unchanged, and
+    // s only flips bit 5 of the offset.
+    const int off0 = tile_off(lane & 31, 4 * wave + (lane >> 5));
+    struct Frags {
+        bf16x8 af[TI], bf[TJ];
+    };
+    auto load_frags = [&](Frags &f, int a_slot, int wbuf, int s) {
+        const int o = off0 ^ (s << 5);
+#pragma unroll
+        for (int i = 0; i < TI; ++i) f.af[i] = *reinterpret_cast<const bf16x8 *>(smem + a_slot + o + i * 32 * ROW_BYTES);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+            f.bf[j] = *reinterpret_cast<const bf16x8 *>(smem + W_BASE + wbuf * W_BYTES + o + j * 32 * ROW_BYTES);
+    };
+    auto mfma_frags = [&](const Frags &f) {
+#pragma unroll
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
+    };
+
+    if (n_full > 0) {
+#pragma unroll
+        for (int sl = 0; sl < 3; ++sl)
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i) issue_a_part(last < sl ? last : sl, sl * A_BYTES, i);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        int a_cur = 0, a_fill = 3 * A_BYTES;   // ring slots (byte offsets, wave-uniform)
+        for (int t = 0; t < n_full; t += 2) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int tt = t + u;
+                if (tt < n_full) {
+                    const int ta = tt + 3 < n_full ? tt + 3 : last;
+                    Frags f[2];
+                    load_frags(f[0], a_cur, u, 0);
+                    load_frags(f[1], a_cur, u, 1);
+#pragma unroll
+                    for (int i = 0; i < A_CH / 2; ++i) issue_a_part(ta, a_fill, i);
+                    mfma_frags(f[0]);
+#pragma unroll
+                    for (int i = A_CH / 2; i < A_CH; ++i) issue_a_part(ta, a_fill, i);
+                    mfma_frags(f[1]);
+                    // activation tile tt + 1 (sent two steps ago) has landed once only the direct loads of
+                    // this step and the last remain in flight
+                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * A_CH) : "memory");
+                    __syncthreads();
+                    a_cur = a_cur == 3 * A_BYTES ? 0 : a_cur + A_BYTES;
+                    a_fill = a_fill == 3 * A_BYTES ? 0 : a_fill + A_BYTES;
+                }
+            }
+        }
+        // the repeated fetches of the last steps still write into the ring
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+    for (int t = n_full; t < n_tiles; ++t) {
+        bool ext;
+        int r0, ksteps;
+        tail_geometry(t, ext, r0, ksteps);
+        stage_tail_tile(t, false);
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            if (2 * wave + s < ksteps) {
+                Frags f;
+                load_frags(f, 0, 0, s);
+                mfma_frags(f);
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- the four consumers' partial tiles meet in LDS: consumer i ends up with rows
+    // [32 i, 32 i + 32) of the tile, summed in a fixed order --------------------------------
+    float *red = reinterpret_cast<float *>(smem);   // [owner i][slot 0..2][j][v][lane]
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+        if (i == wave) continue;
+        const int slot = (wave - i - 1) & 3;     // 0..2
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[(((i * 3 + slot) * TJ + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+    }
+    __syncthreads();
+    f32x16 fin[TJ];
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+        if (i != wave) continue;
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float x = acc[i][j][v];
+#pragma unroll
+                for (int slot = 0; slot < 3; ++slot) x += red[(((i * 3 + slot) * TJ + j) * 16 + v) * 64 + lane];
+                fin[j][v] = x;
+            }
+    }
+    __syncthreads();
+
+    // ---- epilogue of consumer `wave`: its 32 x 64 block, one RNE to bfloat16, through an LDS
+    // patch so that the global stores are 16 bytes per lane and 128 contiguous bytes per row ----
+    uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + wave * (32 * PATCH_ROW);
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+            patch[prow * PATCH_ROW + j * 32 + (lane & 31)] = float_to_bf16_bits(fin[j][v]);
+        }
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the patch is private to the wave
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int idx = lane + q * 64;    // 256 chunks of 16 bytes: 32 rows x 8
+        const int prow = idx / 8, ch = idx % 8;
+        const uint4 v = *reinterpret_cast<const uint4 *>(patch + prow * PATCH_ROW + ch * 8);
+        const int row = m0 + wave * 32 + prow;
+        const int col = c0 + ch * 8;
+        if (row < a.M && col < Cout) *reinterpret_cast<uint4 *>(a.out + (size_t)row * Cout + col) = v;
+    }
+}
+
+template <int BITS, bool BWD>
+static hipError_t launch_mid(const GemmArgs &a, hipStream_t stream) {
+    const GemmDev d = make_gemm_dev(a, mid::MT, mid::CT);
+    const int blocks = (d.tiles_m * d.tiles_c + 7) / 8 * 8;
+    auto kern = gemm_mid_kernel<BITS, BWD>;
+    static bool configured[64] = {};
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), mid::LDS_BYTES, configured);
+    if (e != hipSuccess) return e;
+    launch_kernel(BWD ? "gemm_bwd_128x64s" : "gemm_fwd_128x64s", kern, blocks, mid::THREADS, mid::LDS_BYTES, stream, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_mid(const GemmArgs &a, hipStream_t stream) {
+    switch (a.w.bits) {
+        case 2: return a.backward ? launch_mid<2, true>(a, stream) : launch_mid<2, false>(a, stream);
+        case 3: return a.backward ? launch_mid<3, true>(a, stream) : launch_mid<3, false>(a, stream);
+        default: return a.backward ? launch_mid<4, true>(a, stream) : launch_mid<4, false>(a, stream);
+    }
+}
+
+}  // namespace mlr

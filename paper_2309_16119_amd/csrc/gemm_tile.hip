@@ -632,8 +632,8 @@ static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_
 }
 
 // Tile variants.  `pick` may be forced with the environment variable MODULORA_TILE
-// (big | mid | m128 | m64 | small), a tuning knob for benchmarks.
-enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128, PICK_T128K, PICK_SMALL };
+// (big | mid | m128 | m64 | m64k | t128 | t128k | t128s | small), a tuning knob for benchmarks.
+enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128, PICK_T128K, PICK_T128S, PICK_SMALL };
 
 static TilePick forced_pick() {
     static int cached = -1;
@@ -648,6 +648,7 @@ static TilePick forced_pick() {
             else if (!std::strcmp(e, "m64k")) cached = PICK_M64K;
             else if (!std::strcmp(e, "t128")) cached = PICK_T128;
             else if (!std::strcmp(e, "t128k")) cached = PICK_T128K;
+            else if (!std::strcmp(e, "t128s")) cached = PICK_T128S;
             else if (!std::strcmp(e, "small")) cached = PICK_SMALL;
         }
     }
@@ -672,7 +673,7 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
                                    {PICK_M128, 128, 128, 2, 0.97, 1.40},
                                    {PICK_M64, 64, 128, 2, 0.75, 1.10},
                                    {PICK_M64K, 64, 128, 1, 0.62, 0.62},
-                                   {PICK_T128K, 128, 64, 1, 0.57, 0.57}};
+                                   {PICK_T128S, 128, 64, 1, 0.48, 0.48}};   // gemm_mid.hip (t128k, its predecessor here: 0.57)
             const int C = BWD ? a.w.N : a.w.K;
             const double steps = (double)C / 64.0;
             const BigPlan bp = big_plan(a.M, C, Cout);
@@ -705,6 +706,8 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
         case PICK_T128:   // tall tile: half the dequantization work per output of the 64-row tile
             return launch_variant<BITS, BWD, 256, 128, 64, 32, 64, 1, 2, 128, 1>(
                 a, BWD ? "gemm_bwd_128x64" : "gemm_fwd_128x64", stream);
+        case PICK_T128S:  // 8 waves: four consumers (k-groups of one 128x64 wave tile) and four producers
+            return launch_gemm_mid(a, stream);
         case PICK_T128K:  // 8 waves: four k-groups of two 64x64 wave tiles
             return launch_variant<BITS, BWD, 512, 128, 64, 64, 64, 1, 3, 128, 4>(
                 a, BWD ? "gemm_bwd_128x64k" : "gemm_fwd_128x64k", stream);

@@ -100,7 +100,24 @@ SHAPES = [
     # few rows and a deep contraction: the rank-r projection is split over workgroups too
     (3, 4096, 264, 40, 40, 128),
     (4, 256, 6144, 100, 64, 32),
+    # about a hundred 128 x 64 tiles: the producer / consumer kernel, with a ragged row tile, a
+    # ragged column tile, a ragged last 128-deep step in both directions and 16-deep adapter steps
+    (3, 2112, 2136, 300, 8, 64),
+    (4, 2144, 2080, 300, 16, 32),
+    (2, 2048, 2176, 384, 40, 2048),
 ]
+
+
+def test_mid_size_shapes_run_the_producer_consumer_kernel():
+    """The shapes above that are meant for the 128 x 64 producer / consumer kernel do reach it."""
+    L = layer(3, 2112, 2136, 300, 8, 64, seed=2)
+    D = to_device(L)
+    b.modulora_profile_begin()
+    b.modulora_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], L["lora_scale"])
+    b.modulora_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], L["lora_scale"])
+    torch.cuda.synchronize()
+    names = set(b.modulora_profile_end())
+    assert {"gemm_fwd_128x64s", "gemm_bwd_128x64s"} <= names, names
 
 
 @pytest.mark.parametrize("bits,K,N,M,r,group", SHAPES)

@@ -77,3 +77,19 @@ def test_large_m_tile_kernel_does_not_spill(tmp_path):
     for name, v in zip(names, spills):
         assert int(v) == 0, "%s spills %s vector registers" % (name, v)
     assert "scratch_load" not in text and "scratch_store" not in text
+
+
+@pytest.mark.skipif(_hipcc() is None, reason="hipcc not available")
+def test_producer_consumer_tile_kernel_does_not_spill(tmp_path):
+    """The 128 x 64 producer / consumer kernel counts its assembly-issued loads in both roles."""
+    out = tmp_path / "gemm_mid.s"
+    cmd = [_hipcc(), *build.HIPCC_FLAGS, "-S", "--cuda-device-only", os.path.join(build.CSRC, "gemm_mid.hip"), "-o", str(out)]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-2000:]
+    text = out.read_text()
+    names = re.findall(r"^\s*\.name:\s+(\S+)", text, flags=re.M)
+    spills = re.findall(r"^\s*\.vgpr_spill_count:\s+(\d+)", text, flags=re.M)
+    assert sum("gemm_mid_kernel" in n for n in names) == 6        # 3 bit widths x forward / backward
+    for name, v in zip(names, spills):
+        assert int(v) == 0, "%s spills %s vector registers" % (name, v)
+    assert "scratch_load" not in text and "scratch_store" not in text
