@@ -9,17 +9,23 @@
 // turn the costs of a step add up instead of overlapping (measured on the 8-wave k-group
 // variant of gemm_tile.hip: taking out the activation stores, the dequantization or the
 // loads each shortened the kernel by its own share, taking out the MFMAs changed nothing).
-// Here the waves are specialized instead:
+// Here the waves are specialized instead (12 waves, three per SIMD):
 //
-//   - waves 0-3, one per SIMD, are consumers: each owns the whole 128 x 64 tile for a
-//     quarter of every 128-deep step (two 16-deep MFMA steps), reads its fragments and
-//     issues MFMAs, nothing else.  Their four partial tiles are added through LDS at the end.
-//   - waves 4-7, one per SIMD, are producers: they issue the direct global->LDS loads of the
-//     activation tile two steps ahead (ring of three tiles), fetch the packed words one step
-//     ahead into registers and dequantize them into the weight tile of the next step.
+//   - waves 0-3, one per SIMD, are consumers: each owns half of the tile's rows (64 x 64) for
+//     half of every 128-deep step (four 16-deep MFMA steps); they read fragments and issue
+//     MFMAs, nothing else.  The two halves of the contraction are added through LDS at the end.
+//   - waves 4-11, two per SIMD, are producers: they dequantize the weight tile of the next step
+//     (half a 32-code unit per thread), send the direct global->LDS loads of the activation tile
+//     three steps ahead (ring of four tiles) and fetch the packed words four steps ahead into
+//     registers.  A step is shorter than a trip to memory, hence the distances.
 //   - one barrier per step hands the buffers over.  LDS rows are 256 bytes (one line of the
 //     64 banks) with the 16-byte chunk index XOR-ed with row & 15: fragment reads, weight
 //     stores and direct loads are all conflict-free.
+//   - measured with stamps from an instrumented build (8-wave predecessor, four producers): a
+//     consumer needs ~860 cycles per step (300 until its fragments are there, 560 for 16 MFMAs),
+//     a producer wave ~1100 (120 VALU instructions, 4 LDS stores, its share of the loads), and a
+//     CU's memory pipeline takes ~16 cycles per 1 KB load instruction, i.e. ~600 per step: loads
+//     issued right after the barrier, ahead of other work of the same wave, held that wave up.
 #include <type_traits>
 
 #include "gemm_common.h"
@@ -27,9 +33,10 @@
 namespace mlr {
 
 namespace mid {
-constexpr int THREADS = 512, CWAVES = 4, PTHREADS = 256;
+constexpr int THREADS = 768, CWAVES = 4, PTHREADS = 512;
 constexpr int MT = 128, CT = 64, RT = 128;
-constexpr int TI = MT / 32, TJ = CT / 32;
+constexpr int TI = 2, TJ = CT / 32;               // a consumer's wave tile: 64 x 64
+constexpr int KS = RT / 16 / 2;                   // 16-deep steps of a consumer per tile = 4
 constexpr int ROW_BYTES = RT * 2;                 // 256
 constexpr int A_BYTES = MT * ROW_BYTES;           // 32 KB
 constexpr int W_BYTES = CT * ROW_BYTES;           // 16 KB
@@ -37,10 +44,9 @@ constexpr int A_SLOTS = 4, W_SLOTS = 2;
 constexpr int W_BASE = A_SLOTS * A_BYTES;         // 128 KB
 constexpr int LDS_BYTES = W_BASE + W_SLOTS * W_BYTES;   // 160 KB, all of a CU's LDS
 constexpr int W_SETS = 3;                         // staged register sets of packed words
-constexpr int A_CH = MT * 16 / PTHREADS;          // direct loads per producer thread and tile = 8
+constexpr int A_CH = MT * 16 / PTHREADS;          // direct loads per producer thread and tile = 4
 constexpr int PATCH_ROW = 72;                     // epilogue patch row stride (elements)
-static_assert((CWAVES - 1) * MT * CT * 4 <= W_BASE, "the partial tiles of three consumers fit the activation ring");
-static_assert(A_SLOTS == 4 && W_SETS == 3, "the steady state below fetches three tiles ahead");
+static_assert(A_SLOTS == 4 && W_SETS == 3, "the steady state below fetches three and four tiles ahead");
 
 __device__ __forceinline__ int swz(int row) { return row & 15; }
 // byte offset of logical 16-byte chunk `c` (0..15) of row `row` inside a tile
@@ -48,7 +54,7 @@ __device__ __forceinline__ int tile_off(int row, int c) { return row * ROW_BYTES
 }  // namespace mid
 
 template <int BITS, bool BWD>
-__global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
+__global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
     using namespace mid;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -57,7 +63,9 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
     if (tco.tm < 0) return;   // grid padded to a multiple of 8
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const bool producer = wave >= CWAVES;
-    const int ptid = tid & (PTHREADS - 1), pwave = wave & 3;
+    // producers: thread 0..511; its weight unit 0..255 and which half of the unit it dequantizes
+    const int ptid = (tid - CWAVES * 64) & (PTHREADS - 1), pwave = (wave - CWAVES) & 7;
+    const int unit = ptid & 255, half = uniform(pwave >> 2), ukb = uniform(pwave & 3);
     const int m0 = tco.tm * MT, c0 = tco.tc * CT;
     const int K = a.w.K, N = a.w.N;
     const int C = BWD ? N : K;
@@ -70,7 +78,7 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
     const uint16_t *act_rowblock = a.act + (size_t)m0 * C;
 
     // ---- producers: activation tile by direct loads --------------------------------
-    // chunk idx = i*256 + ptid sits at byte 16*idx of the tile: row idx/16, physical chunk
+    // chunk idx = i*512 + ptid sits at byte 16*idx of the tile: row idx/16, physical chunk
     // idx%16, which holds logical chunk (idx%16) ^ swz(row).
     uint32_t a_voff[A_CH];
 #pragma unroll
@@ -92,7 +100,7 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
     int bw_shift = 0, bw_row0 = 0, bw_g0 = 0;
     bool bw_kok = true;
     if (!BWD) {
-        int n = c0 + (ptid & (CT - 1));
+        int n = c0 + (unit & (CT - 1));
         if (n > N - 1) n = N - 1;
         fw_n = (uint32_t)n;
         fw_off = (uint32_t)n * 4u;
@@ -100,7 +108,7 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
         bw_row0 = (c0 * BITS) >> 5;
         bw_g0 = (int)d.group_of_block((uint32_t)(c0 >> 5));
         const int last_row = K * BITS / 32 - 1;
-        const int no = ptid & 31, ko = ptid >> 5;
+        const int no = unit & 31, ko = unit >> 5;
         int k = c0 + ko * 8;
         bw_kok = k < K;
         if (k > K - 8) k = K - 8;
@@ -131,7 +139,7 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
     }
     auto load_w = [&](WStage &st, int t) {     // raw words, scales and zeros of full main tile t -> registers (async)
         if (!BWD) {
-            const int blk = t * (RT / 32) + pwave;
+            const int blk = t * (RT / 32) + ukb;
             const uint32_t *wbase = a.w.qweight + (size_t)blk * BITS * N;
 #pragma unroll
             for (int j = 0; j < BITS; ++j) aload_b32(st.fw_words[j], wbase + (size_t)j * N, fw_off);
@@ -169,22 +177,22 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
             }
         }
     };
-    // dequantize the staged words of one set into weight tile `buf`: quarter `part` (0..3) of
-    // the thread's share, or all of it (part < 0)
+    // dequantize quarter `part` (0..3) of the unit whose words are staged in `st` into weight tile
+    // `buf`; a thread's share of a unit is quarters 2 half and 2 half + 1
     auto store_w = [&](int buf, const WStage &st, int part) {
         unsigned char *Ws = smem + W_BASE + buf * W_BYTES;
         if (!BWD) {
-            const int nl = ptid & (CT - 1);
+            const int nl = unit & (CT - 1);
             const DqConst dq = make_dq((uint16_t)st.fw_scale, (uint8_t)st.fw_zero);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (part >= 0 && j != part) continue;
+                if (j != part) continue;
                 uint32_t o[4];
                 dequant_quarter<BITS>(st.fw_words, j, dq, o);
-                *reinterpret_cast<uint4 *>(Ws + tile_off(nl, pwave * 4 + j)) = make_uint4(o[0], o[1], o[2], o[3]);
+                *reinterpret_cast<uint4 *>(Ws + tile_off(nl, ukb * 4 + j)) = make_uint4(o[0], o[1], o[2], o[3]);
             }
         } else {
-            const int no = ptid & 31, ko = ptid >> 5;
+            const int no = unit & 31, ko = unit >> 5;
             const uint32_t sc[2] = {st.bw_scale[0], st.bw_scale[1]};
             uint32_t chunk[4];
             DqConst dq[4];
@@ -197,7 +205,7 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
             // 32 lanes fill one whole row per store
 #pragma unroll
             for (int kk = 0; kk < 8; ++kk) {
-                if (part >= 0 && kk / 2 != part) continue;
+                if (kk / 2 != part) continue;
                 uint32_t o[2];
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
@@ -227,30 +235,34 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
         const uint16_t *abase = (ext ? a.act_ext + (size_t)m0 * ld : act_rowblock) + r0;
         unsigned char *As = smem, *Ws = smem + W_BASE;
 #pragma unroll
-        for (int i = 0; i < MT * 16 / THREADS; ++i) {
+        for (int i = 0; i < (MT * 16 + THREADS - 1) / THREADS; ++i) {
             const int idx = i * THREADS + tid;
-            const int row = idx >> 4, ch = idx & 15;
-            int m = m0 + row;
-            if (m > a.M - 1) m = a.M - 1;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (r0 + ch * 8 < ld) v = load_at<uint4>(abase, (uint32_t)(((size_t)(m - m0) * ld + ch * 8) * 2));
-            *reinterpret_cast<uint4 *>(As + tile_off(row, ch)) = v;
+            if (idx < MT * 16) {
+                const int row = idx >> 4, ch = idx & 15;
+                int m = m0 + row;
+                if (m > a.M - 1) m = a.M - 1;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (r0 + ch * 8 < ld) v = load_at<uint4>(abase, (uint32_t)(((size_t)(m - m0) * ld + ch * 8) * 2));
+                *reinterpret_cast<uint4 *>(As + tile_off(row, ch)) = v;
+            }
         }
         if (ext) {
 #pragma unroll
-            for (int i = 0; i < CT * 16 / THREADS; ++i) {
+            for (int i = 0; i < (CT * 16 + THREADS - 1) / THREADS; ++i) {
                 const int idx = i * THREADS + tid;
-                const int row = idx >> 4, ch = idx & 15;
-                int c = c0 + row;
-                if (c > Cout - 1) c = Cout - 1;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (r0 + ch * 8 < a.RE) v = *reinterpret_cast<const uint4 *>(a.w_ext + (size_t)c * a.RE + r0 + ch * 8);
-                *reinterpret_cast<uint4 *>(Ws + tile_off(row, ch)) = v;
+                if (idx < CT * 16) {
+                    const int row = idx >> 4, ch = idx & 15;
+                    int c = c0 + row;
+                    if (c > Cout - 1) c = Cout - 1;
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (r0 + ch * 8 < a.RE) v = *reinterpret_cast<const uint4 *>(a.w_ext + (size_t)c * a.RE + r0 + ch * 8);
+                    *reinterpret_cast<uint4 *>(Ws + tile_off(row, ch)) = v;
+                }
             }
         } else if (is_producer) {
             WStage &st = wst[0];
             if (!BWD) {
-                const int blk = t * (RT / 32) + pwave;
+                const int blk = t * (RT / 32) + ukb;
                 const bool ok = blk * 32 < K;
                 const int blk_c = ok ? blk : 0;
                 const uint32_t *wbase = a.w.qweight + (size_t)blk_c * BITS * N;
@@ -260,7 +272,7 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
                 st.fw_scale = ok ? (uint32_t)load_at<uint16_t>(a.w.scales + grow, fw_n * 2) : 0u;   // 0 -> weights +0
                 st.fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
             } else {
-                const bool ok = r0 + (ptid & 31) * 4 < N;
+                const bool ok = r0 + (unit & 31) * 4 < N;
                 st.bw_lo = u32x4{0, 0, 0, 0};
                 st.bw_hi = u32x4{0, 0, 0, 0};
                 st.bw_scale = u32x2{0, 0};
@@ -277,7 +289,8 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
                     st.bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
                 }
             }
-            store_w(0, st, -1);
+            store_w(0, st, 2 * half);
+            store_w(0, st, 2 * half + 1);
         }
     };
 
@@ -285,28 +298,33 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
     // workgroup executes the same number of them).
     //
     // Step i of the steady state (full main tiles): consumers work on activation slot i % 4 and
-    // weight tile i & 1, and send the direct loads of activation tile i + 3 into the slot they left
-    // at the last barrier.  Producers dequantize weight tile i + 1 from staged set (i + 1) % 3 and
-    // then refill that set with the words of tile i + 4.  A step is shorter than a trip to memory,
-    // hence the distances.  Loads return in order, so "at most n still in flight" completes all
-    // but the n most recent: a producer opens step i with the words of tiles i + 2 and i + 3 still
-    // allowed in flight, a consumer ends it with the direct loads of tiles i + 2 and i + 3.
-    // The memory pipeline of a CU accepts about 64 bytes per clock, which the 32 KB of an
-    // activation tile fill for most of a step: the producers' few loads are issued last in a step,
-    // where they do not queue behind the direct loads with the dequantization still ahead of them.
+    // weight tile i & 1.  Producers dequantize weight tile i + 1 from staged set (i + 1) % 3, send
+    // the direct loads of activation tile i + 3 into the slot the consumers left at the last
+    // barrier and refill the set with the words of tile i + 4.  Loads return in order, so "at most
+    // n still in flight" completes all but the n most recent: the wait that ends step i asks for
+    // the words of tile i + 2 (needed when step i + 1 opens), which also completes the direct
+    // loads of tile i + 1 issued before them, and leaves in flight the direct loads of tiles
+    // i + 2 and i + 3 and the words of tiles i + 3 and i + 4.
     constexpr int W_LOADS = BWD ? (BITS == 3 ? 4 : 3) : BITS + 2;   // load instructions of one load_w()
     const int last = n_full - 1;   // past the last tile the fetches repeat it; what they bring is never consumed
     if (producer) {
         if (n_full > 0) {
+#pragma unroll
+            for (int sl = 0; sl < 3; ++sl)
+#pragma unroll
+                for (int i = 0; i < A_CH; ++i) issue_a_part(last < sl ? last : sl, sl * A_BYTES, i);
             load_w(wst[0], 0);
             load_w(wst[1], last < 1 ? last : 1);
             load_w(wst[2], last < 2 ? last : 2);
-            // everything has landed after this wait; sets 1 and 2 are pinned (and, for 3-bit backward,
-            // joined) by the waits that open steps 0 and 1, the only ones they pass through
+            // everything has landed after the first wait; set 2 is pinned (and, for 3-bit backward,
+            // joined) by the wait that ends step 0, the only one it passes through
             wait_loads(wst[0], std::integral_constant<int, 0>());
-            store_w(0, wst[0], -1);
+            wait_loads(wst[1], std::integral_constant<int, 0>());
+            store_w(0, wst[0], 2 * half);
+            store_w(0, wst[0], 2 * half + 1);
             load_w(wst[0], last < 3 ? last : 3);
             __syncthreads();
+            int a_fill = 3 * A_BYTES;   // ring slot being filled (byte offset, wave-uniform)
             for (int t = 0; t < n_full; t += 3) {
 #pragma unroll
                 for (int u = 0; u < 3; ++u) {
@@ -314,16 +332,18 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
                     if (tt < n_full) {
                         WStage &st = wst[(u + 1) % 3];          // words of tile tt + 1
                         const int wbuf = (tt + 1) & 1;
-                        wait_loads(st, std::integral_constant<int, 2 * W_LOADS>());
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            store_w(wbuf, st, q);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                        // the set is free again: fetch tile tt + 4 now, when the consumers' direct
-                        // loads of this step are through the memory pipeline
+                        const int ta = tt + 3 < n_full ? tt + 3 : last;
+                        store_w(wbuf, st, 2 * half);
+                        issue_a_part(ta, a_fill, 0);
+                        issue_a_part(ta, a_fill, 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                        store_w(wbuf, st, 2 * half + 1);
+                        issue_a_part(ta, a_fill, 2);
+                        issue_a_part(ta, a_fill, 3);
                         load_w(st, tt + 4 < n_full ? tt + 4 : last);
+                        wait_loads(wst[(u + 2) % 3], std::integral_constant<int, 2 * A_CH + 2 * W_LOADS>());
                         __syncthreads();
+                        a_fill = a_fill == 3 * A_BYTES ? 0 : a_fill + A_BYTES;
                     }
                 }
             }
@@ -341,6 +361,7 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
     }
 
     // ---- consumers ------------------------------------------------------------------------
+    const int wm = wave & 1, kg = wave >> 1;   // row half of the tile, half of each 128-deep step
     f32x16 acc[TI][TJ];
 #pragma unroll
     for (int i = 0; i < TI; ++i)
@@ -349,20 +370,21 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // consumer `wave` takes the 16-deep steps 2 wave and 2 wave + 1 of a tile: logical chunks
-    // 4 wave + 2 s + h for its step s and lane half h.  +32 rows leaves the swizzle unchanged, and
-    // s only flips bit 5 of the offset.
-    const int off0 = tile_off(lane & 31, 4 * wave + (lane >> 5));
+    // the consumer's 16-deep step s (0..3) of a tile is step 4 kg + s: logical chunks
+    // 8 kg + 2 s + h for lane half h.  +32 rows leaves the swizzle unchanged, and s only flips
+    // bits 5-6 of the offset.
+    const int offA0 = tile_off(wm * 64 + (lane & 31), 8 * kg + (lane >> 5));
+    const int offW0 = W_BASE + tile_off(lane & 31, 8 * kg + (lane >> 5));
     struct Frags {
         bf16x8 af[TI], bf[TJ];
     };
-    auto load_frags = [&](Frags &f, int a_slot, int wbuf, int s) {
-        const int o = off0 ^ (s << 5);
+    auto load_frags = [&](Frags &f, int a_slot, int wbuf, int sidx) {
 #pragma unroll
-        for (int i = 0; i < TI; ++i) f.af[i] = *reinterpret_cast<const bf16x8 *>(smem + a_slot + o + i * 32 * ROW_BYTES);
+        for (int i = 0; i < TI; ++i)
+            f.af[i] = *reinterpret_cast<const bf16x8 *>(smem + a_slot + (offA0 ^ (sidx << 5)) + i * 32 * ROW_BYTES);
 #pragma unroll
         for (int j = 0; j < TJ; ++j)
-            f.bf[j] = *reinterpret_cast<const bf16x8 *>(smem + W_BASE + wbuf * W_BYTES + o + j * 32 * ROW_BYTES);
+            f.bf[j] = *reinterpret_cast<const bf16x8 *>(smem + wbuf * W_BYTES + (offW0 ^ (sidx << 5)) + j * 32 * ROW_BYTES);
     };
     auto mfma_frags = [&](const Frags &f) {
 #pragma unroll
@@ -373,39 +395,22 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
     };
 
     if (n_full > 0) {
-#pragma unroll
-        for (int sl = 0; sl < 3; ++sl)
-#pragma unroll
-            for (int i = 0; i < A_CH; ++i) issue_a_part(last < sl ? last : sl, sl * A_BYTES, i);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        int a_cur = 0, a_fill = 3 * A_BYTES;   // ring slots (byte offsets, wave-uniform)
+        int a_cur = 0;
         for (int t = 0; t < n_full; t += 2) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const int tt = t + u;
-                if (tt < n_full) {
-                    const int ta = tt + 3 < n_full ? tt + 3 : last;
-                    Frags f[2];
-                    load_frags(f[0], a_cur, u, 0);
-                    load_frags(f[1], a_cur, u, 1);
+                if (t + u < n_full) {
+                    Frags f[KS];
 #pragma unroll
-                    for (int i = 0; i < A_CH / 2; ++i) issue_a_part(ta, a_fill, i);
-                    mfma_frags(f[0]);
+                    for (int sidx = 0; sidx < KS; ++sidx) load_frags(f[sidx], a_cur, u, sidx);
 #pragma unroll
-                    for (int i = A_CH / 2; i < A_CH; ++i) issue_a_part(ta, a_fill, i);
-                    mfma_frags(f[1]);
-                    // activation tile tt + 1 (sent two steps ago) has landed once only the direct loads of
-                    // this step and the last remain in flight
-                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * A_CH) : "memory");
+                    for (int sidx = 0; sidx < KS; ++sidx) mfma_frags(f[sidx]);
                     __syncthreads();
                     a_cur = a_cur == 3 * A_BYTES ? 0 : a_cur + A_BYTES;
-                    a_fill = a_fill == 3 * A_BYTES ? 0 : a_fill + A_BYTES;
                 }
             }
         }
-        // the repeated fetches of the last steps still write into the ring
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
     }
     for (int t = n_full; t < n_tiles; ++t) {
@@ -415,47 +420,46 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
         stage_tail_tile(t, false);
         __syncthreads();
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            if (2 * wave + s < ksteps) {
+        for (int sidx = 0; sidx < KS; ++sidx) {
+            if (KS * kg + sidx < ksteps) {
                 Frags f;
-                load_frags(f, 0, 0, s);
+                load_frags(f, 0, 0, sidx);
                 mfma_frags(f);
             }
         }
         __syncthreads();
     }
 
-    // ---- the four consumers' partial tiles meet in LDS: consumer i ends up with rows
-    // [32 i, 32 i + 32) of the tile, summed in a fixed order --------------------------------
-    float *red = reinterpret_cast<float *>(smem);   // [owner i][slot 0..2][j][v][lane]
+    // ---- the two halves of the contraction meet in LDS: of its 64 rows a consumer keeps block kg
+    // (32 rows) and hands the other block to its partner
+    float *red = reinterpret_cast<float *>(smem);   // [receiving wave][j][v][lane]
+    {
+        const int partner = wave ^ 2;
 #pragma unroll
-    for (int i = 0; i < TI; ++i) {
-        if (i == wave) continue;
-        const int slot = (wave - i - 1) & 3;     // 0..2
+        for (int i = 0; i < TI; ++i) {
+            if (i == kg) continue;
 #pragma unroll
-        for (int j = 0; j < TJ; ++j)
+            for (int j = 0; j < TJ; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) red[(((i * 3 + slot) * TJ + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+                for (int v = 0; v < 16; ++v) red[((partner * TJ + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+        }
     }
     __syncthreads();
     f32x16 fin[TJ];
 #pragma unroll
     for (int i = 0; i < TI; ++i) {
-        if (i != wave) continue;
+        if (i != kg) continue;
 #pragma unroll
         for (int j = 0; j < TJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                float x = acc[i][j][v];
-#pragma unroll
-                for (int slot = 0; slot < 3; ++slot) x += red[(((i * 3 + slot) * TJ + j) * 16 + v) * 64 + lane];
-                fin[j][v] = x;
+                fin[j][v] = acc[i][j][v] + red[((wave * TJ + j) * 16 + v) * 64 + lane];
             }
     }
     __syncthreads();
 
-    // ---- epilogue of consumer `wave`: its 32 x 64 block, one RNE to bfloat16, through an LDS
-    // patch so that the global stores are 16 bytes per lane and 128 contiguous bytes per row ----
+    // ---- epilogue of a consumer: its 32 x 64 block, one RNE to bfloat16, through an LDS patch
+    // so that the global stores are 16 bytes per lane and 128 contiguous bytes per row ----------
     uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + wave * (32 * PATCH_ROW);
 #pragma unroll
     for (int j = 0; j < TJ; ++j)
@@ -471,7 +475,7 @@ __global__ __launch_bounds__(mid::THREADS, 2) void gemm_mid_kernel(GemmDev d) {
         const int idx = lane + q * 64;    // 256 chunks of 16 bytes: 32 rows x 8
         const int prow = idx / 8, ch = idx % 8;
         const uint4 v = *reinterpret_cast<const uint4 *>(patch + prow * PATCH_ROW + ch * 8);
-        const int row = m0 + wave * 32 + prow;
+        const int row = m0 + wm * 64 + kg * 32 + prow;
         const int col = c0 + ch * 8;
         if (row < a.M && col < Cout) *reinterpret_cast<uint4 *>(a.out + (size_t)row * Cout + col) = v;
     }
