@@ -9,23 +9,27 @@
 // turn the costs of a step add up instead of overlapping (measured on the 8-wave k-group
 // variant of gemm_tile.hip: taking out the activation stores, the dequantization or the
 // loads each shortened the kernel by its own share, taking out the MFMAs changed nothing).
-// Here the waves are specialized instead (12 waves, three per SIMD):
+// Here the waves are specialized instead (12 waves, three per SIMD, one of each kind):
 //
-//   - waves 0-3, one per SIMD, are consumers: each owns half of the tile's rows (64 x 64) for
-//     half of every 128-deep step (four 16-deep MFMA steps); they read fragments and issue
-//     MFMAs, nothing else.  The two halves of the contraction are added through LDS at the end.
-//   - waves 4-11, two per SIMD, are producers: they dequantize the weight tile of the next step
-//     (half a 32-code unit per thread), send the direct global->LDS loads of the activation tile
-//     three steps ahead (ring of four tiles) and fetch the packed words four steps ahead into
-//     registers.  A step is shorter than a trip to memory, hence the distances.
+//   - waves 0-3 are consumers: each owns half of the tile's rows (64 x 64) for half of every
+//     128-deep step (four 16-deep MFMA steps); they read fragments and issue MFMAs, nothing
+//     else.  The two halves of the contraction are added through LDS at the end.
+//   - waves 4-7 dequantize: a thread fetches the packed words, scale and zero point of one
+//     32-code unit four steps ahead into registers (three sets) and writes the unit's 32
+//     bfloat16 into the weight tile of the next step.
+//   - waves 8-11 only send the direct global->LDS loads of the activation tile, three steps
+//     ahead into a ring of four tiles.  A step is shorter than a trip to memory, hence the
+//     distances.
 //   - one barrier per step hands the buffers over.  LDS rows are 256 bytes (one line of the
 //     64 banks) with the 16-byte chunk index XOR-ed with row & 15: fragment reads, weight
 //     stores and direct loads are all conflict-free.
-//   - measured with stamps from an instrumented build (8-wave predecessor, four producers): a
-//     consumer needs ~860 cycles per step (300 until its fragments are there, 560 for 16 MFMAs),
-//     a producer wave ~1100 (120 VALU instructions, 4 LDS stores, its share of the loads), and a
-//     CU's memory pipeline takes ~16 cycles per 1 KB load instruction, i.e. ~600 per step: loads
-//     issued right after the barrier, ahead of other work of the same wave, held that wave up.
+//   - measured with stamps from instrumented builds: a consumer needs ~900 cycles per step (300
+//     until its fragments are there, 560 for 16 MFMAs), a dequantizing wave ~900 (120 VALU
+//     instructions, 4 LDS stores) plus ~250 to get its five loads accepted; loads issued right
+//     after the barrier, ahead of other work of the same wave, held that wave up for 600 cycles.
+//     Fetching the raw weight data with a handful of wide direct loads into an LDS staging ring
+//     (instead of 20 narrow register loads per step) was slower, not faster: the dequantization
+//     then starts with a round trip to LDS after every barrier.
 #include <type_traits>
 
 #include "gemm_common.h"
@@ -44,7 +48,7 @@ constexpr int A_SLOTS = 4, W_SLOTS = 2;
 constexpr int W_BASE = A_SLOTS * A_BYTES;         // 128 KB
 constexpr int LDS_BYTES = W_BASE + W_SLOTS * W_BYTES;   // 160 KB, all of a CU's LDS
 constexpr int W_SETS = 3;                         // staged register sets of packed words
-constexpr int A_CH = MT * 16 / PTHREADS;          // direct loads per producer thread and tile = 4
+constexpr int A_CH = MT * 16 / 256;               // direct loads per loader thread and tile = 8
 constexpr int PATCH_ROW = 72;                     // epilogue patch row stride (elements)
 static_assert(A_SLOTS == 4 && W_SETS == 3, "the steady state below fetches three and four tiles ahead");
 
@@ -63,9 +67,10 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
     if (tco.tm < 0) return;   // grid padded to a multiple of 8
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const bool producer = wave >= CWAVES;
-    // producers: thread 0..511; its weight unit 0..255 and which half of the unit it dequantizes
+    // waves 4-7 dequantize (thread -> weight unit 0..255), waves 8-11 only send direct loads
     const int ptid = (tid - CWAVES * 64) & (PTHREADS - 1), pwave = (wave - CWAVES) & 7;
-    const int unit = ptid & 255, half = uniform(pwave >> 2), ukb = uniform(pwave & 3);
+    const bool loader = pwave >= 4;
+    const int unit = ptid & 255, ukb = uniform(pwave & 3);
     const int m0 = tco.tm * MT, c0 = tco.tc * CT;
     const int K = a.w.K, N = a.w.N;
     const int C = BWD ? N : K;
@@ -78,19 +83,19 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
     const uint16_t *act_rowblock = a.act + (size_t)m0 * C;
 
     // ---- producers: activation tile by direct loads --------------------------------
-    // chunk idx = i*512 + ptid sits at byte 16*idx of the tile: row idx/16, physical chunk
+    // chunk idx = i*256 + unit sits at byte 16*idx of the tile: row idx/16, physical chunk
     // idx%16, which holds logical chunk (idx%16) ^ swz(row).
     uint32_t a_voff[A_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) {
-        const int idx = i * PTHREADS + ptid;
+        const int idx = i * 256 + unit;
         const int row = idx >> 4, lc = (idx & 15) ^ swz(row);
         int m = m0 + row;
         if (m > a.M - 1) m = a.M - 1;
         a_voff[i] = (uint32_t)(((size_t)(m - m0) * C + lc * 8) * 2);
     }
     auto issue_a_part = [&](int t, int a_slot, int i) {
-        load_to_lds_16(act_rowblock + (size_t)t * RT, a_voff[i], lds0 + a_slot + i * (PTHREADS * 16) + pwave * 1024);
+        load_to_lds_16(act_rowblock + (size_t)t * RT, a_voff[i], lds0 + a_slot + i * (256 * 16) + ukb * 1024);
     };
 
     // ---- producers: weight units ------------------------------------------------------
@@ -177,8 +182,7 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
             }
         }
     };
-    // dequantize quarter `part` (0..3) of the unit whose words are staged in `st` into weight tile
-    // `buf`; a thread's share of a unit is quarters 2 half and 2 half + 1
+    // dequantize quarter `part` (0..3) of the unit whose words are staged in `st` into weight tile `buf`
     auto store_w = [&](int buf, const WStage &st, int part) {
         unsigned char *Ws = smem + W_BASE + buf * W_BYTES;
         if (!BWD) {
@@ -259,7 +263,7 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
                     *reinterpret_cast<uint4 *>(Ws + tile_off(row, ch)) = v;
                 }
             }
-        } else if (is_producer) {
+        } else if (is_producer && !loader) {
             WStage &st = wst[0];
             if (!BWD) {
                 const int blk = t * (RT / 32) + ukb;
@@ -289,8 +293,8 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
                     st.bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
                 }
             }
-            store_w(0, st, 2 * half);
-            store_w(0, st, 2 * half + 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) store_w(0, st, q);
         }
     };
 
@@ -308,23 +312,37 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
     constexpr int W_LOADS = BWD ? (BITS == 3 ? 4 : 3) : BITS + 2;   // load instructions of one load_w()
     const int last = n_full - 1;   // past the last tile the fetches repeat it; what they bring is never consumed
     if (producer) {
-        if (n_full > 0) {
+        if (n_full > 0 && loader) {
+            // activation tiles three steps ahead; the wait leaves the loads of two steps in flight
 #pragma unroll
             for (int sl = 0; sl < 3; ++sl)
 #pragma unroll
                 for (int i = 0; i < A_CH; ++i) issue_a_part(last < sl ? last : sl, sl * A_BYTES, i);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            int a_fill = 3 * A_BYTES;   // ring slot being filled (byte offset, wave-uniform)
+            for (int tt = 0; tt < n_full; ++tt) {
+                const int ta = tt + 3 < n_full ? tt + 3 : last;
+#pragma unroll
+                for (int i = 0; i < A_CH; ++i) issue_a_part(ta, a_fill, i);
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * A_CH) : "memory");
+                __syncthreads();
+                a_fill = a_fill == 3 * A_BYTES ? 0 : a_fill + A_BYTES;
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        } else if (n_full > 0) {
             load_w(wst[0], 0);
             load_w(wst[1], last < 1 ? last : 1);
             load_w(wst[2], last < 2 ? last : 2);
             // everything has landed after the first wait; set 2 is pinned (and, for 3-bit backward,
-            // joined) by the wait that ends step 0, the only one it passes through
+            // joined) by the wait that opens step 1, the only one it passes through
             wait_loads(wst[0], std::integral_constant<int, 0>());
             wait_loads(wst[1], std::integral_constant<int, 0>());
-            store_w(0, wst[0], 2 * half);
-            store_w(0, wst[0], 2 * half + 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) store_w(0, wst[0], q);
             load_w(wst[0], last < 3 ? last : 3);
             __syncthreads();
-            int a_fill = 3 * A_BYTES;   // ring slot being filled (byte offset, wave-uniform)
             for (int t = 0; t < n_full; t += 3) {
 #pragma unroll
                 for (int u = 0; u < 3; ++u) {
@@ -332,18 +350,15 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
                     if (tt < n_full) {
                         WStage &st = wst[(u + 1) % 3];          // words of tile tt + 1
                         const int wbuf = (tt + 1) & 1;
-                        const int ta = tt + 3 < n_full ? tt + 3 : last;
-                        store_w(wbuf, st, 2 * half);
-                        issue_a_part(ta, a_fill, 0);
-                        issue_a_part(ta, a_fill, 1);
-                        __builtin_amdgcn_sched_barrier(0);
-                        store_w(wbuf, st, 2 * half + 1);
-                        issue_a_part(ta, a_fill, 2);
-                        issue_a_part(ta, a_fill, 3);
+                        // in flight at most: the words of tiles tt + 2 and tt + 3
+                        if (tt > 0) wait_loads(st, std::integral_constant<int, 2 * W_LOADS>());
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            store_w(wbuf, st, q);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
                         load_w(st, tt + 4 < n_full ? tt + 4 : last);
-                        wait_loads(wst[(u + 2) % 3], std::integral_constant<int, 2 * A_CH + 2 * W_LOADS>());
                         __syncthreads();
-                        a_fill = a_fill == 3 * A_BYTES ? 0 : a_fill + A_BYTES;
                     }
                 }
             }
