@@ -30,6 +30,12 @@
 //     Fetching the raw weight data with a handful of wide direct loads into an LDS staging ring
 //     (instead of 20 narrow register loads per step) was slower, not faster: the dequantization
 //     then starts with a round trip to LDS after every barrier.
+//   - what bounds a step now is LDS store bandwidth: stores reach LDS at ~80 bytes per clock and
+//     CU whatever their width (direct loads included; reads get ~240), and a step stores 48 KB
+//     and reads 64 KB.  Issuing every direct load twice lengthened the kernel by exactly what
+//     removing them saves.  Loading the activation fragments from global memory straight into
+//     MFMA registers (16x16x32, 64-byte pieces of a row per four lanes) avoided those stores and
+//     was a third slower.
 #include <type_traits>
 
 #include "gemm_common.h"
