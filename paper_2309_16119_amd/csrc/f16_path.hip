@@ -16,6 +16,8 @@
 // The adapter gradients reuse lora_grad_partial_kernel with a binary16 element conversion.
 #include "device_common.h"
 #include "gemm_common.h"
+#include <cstdlib>
+
 #include "launch.h"
 
 namespace mlr {
@@ -492,6 +494,24 @@ static hipError_t launch_f16_gemm_bits(F16GemmArgs &a, bool backward, hipStream_
 
 hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act, int M, uint16_t *out, const float *P,
                            const float *Fm, int r, float lora_scale, hipStream_t stream) {
+    // About one 128 x 64 tile per compute unit (half a round to a round and a quarter of the 256):
+    // the producer / consumer kernel of the bfloat16 path, instantiated for this storage convention
+    // (its loads, LDS layout and wave roles are the same; dequantization, MFMA type and epilogue
+    // differ).  Measured: 33 against 64-69 us at 512 x 4096 x 4096; with many rounds of such small
+    // tiles (4096 x 8192 x 8192) the kernel below is the faster one, 826 against 1197 us.
+    {
+        const int Cout = backward ? w.K : w.N;
+        const long tiles = (long)((M + 127) / 128) * ((Cout + 63) / 64);
+        if (M > 32 && tiles >= 128 && tiles <= 320 && std::getenv("MODULORA_F16_PLAIN") == nullptr) {
+            GemmArgs g{};
+            g.w.K = w.K; g.w.N = w.N; g.w.bits = w.bits; g.w.group = w.group;
+            g.w.qweight = w.qweight; g.w.scales = w.scales; g.w.zeros = nullptr;
+            g.backward = backward; g.act = act; g.M = M; g.out = out;
+            g.zeros16 = w.zeros; g.bias16 = w.bias;
+            g.ep_P = r > 0 ? P : nullptr; g.ep_F = Fm; g.ep_r = r; g.ep_scale = lora_scale;
+            return launch_gemm_mid_f16(g, stream);
+        }
+    }
     F16GemmArgs a;
     a.w = w; a.act = act; a.M = M; a.out = out; a.P = P; a.Fm = Fm; a.r = r; a.lora_scale = lora_scale;
     a.tiles_m = a.tiles_c = 0;

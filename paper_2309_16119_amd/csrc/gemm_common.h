@@ -116,23 +116,38 @@ __device__ __forceinline__ void aload_b128(u32x4 &dst, const void *base, uint32_
     asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(voff), "s"(base) : "memory");
 }
 
+// Two fp32 values rounded to nearest even into a pair of 16-bit floats, `lo` in the low half:
+// bfloat16, or binary16 for the layer in the paper's own storage convention.
+typedef _Float16 half16x2 __attribute__((ext_vector_type(2)));
+template <bool F16>
+__device__ __forceinline__ uint32_t pack_pair(float lo, float hi) {
+    if (!F16) return pack_bf16x2(lo, hi);
+    const half16x2 v = {(_Float16)lo, (_Float16)hi};
+    uint32_t u;
+    __builtin_memcpy(&u, &v, sizeof u);
+    return u;
+}
+
 // Quarter j (0..3) of a 32-code block held in BITS words: its 8 codes dequantized with one
-// (scale, bias) into 8 bfloat16, code 8 j in the low half of out[0].
-template <int BITS>
+// (scale, bias) into 8 bfloat16 (or binary16), code 8 j in the low half of out[0].
+template <int BITS, bool F16 = false>
 __device__ __forceinline__ void dequant_quarter(const uint32_t *w, int j, const DqConst &c, uint32_t out[4]) {
     if (BITS == 4) {
         const uint32_t lo = w[j] & 0x0F0F0F0Fu, hi = (w[j] >> 4) & 0x0F0F0F0Fu;
 #pragma unroll
         for (int i = 0; i < 4; ++i)   // codes 2i (byte i of lo) and 2i+1 (byte i of hi)
-            out[i] = pack_bf16x2(dq_value((lo >> (8 * i)) & 0xFFu, c), dq_value((hi >> (8 * i)) & 0xFFu, c));
+            out[i] = pack_pair<F16>(dq_value((lo >> (8 * i)) & 0xFFu, c), dq_value((hi >> (8 * i)) & 0xFFu, c));
     } else if (BITS == 2) {
         const uint32_t h = w[j >> 1] >> (16 * (j & 1));   // 8 codes in the low 16 bits
         const uint32_t even = h & 0x3333u, odd = (h >> 2) & 0x3333u;   // nibble n: code 2n / 2n+1
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            out[i] = pack_bf16x2(dq_value((even >> (4 * i)) & 0xFu, c), dq_value((odd >> (4 * i)) & 0xFu, c));
+            out[i] = pack_pair<F16>(dq_value((even >> (4 * i)) & 0xFu, c), dq_value((odd >> (4 * i)) & 0xFu, c));
     } else {
-        dequant_chunk<BITS>(block_chunk<BITS>(w, j), c, out);
+        const uint32_t chunk = block_chunk<BITS>(w, j);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            out[i] = pack_pair<F16>(dq_value(chunk_code<BITS>(chunk, 2 * i), c), dq_value(chunk_code<BITS>(chunk, 2 * i + 1), c));
     }
 }
 

@@ -2,7 +2,9 @@
 // compute unit (a few hundred tokens against a 4096-wide layer).  Same mathematics as
 // gemm_tile.hip (ModuLoRA Figure 1: forward X What^T and backward dY What with What
 // re-materialized from the packed codes, plus the adapter term of eq. (3) as an extended
-// contraction).
+// contraction).  A second instantiation (F16) serves the layer in the paper's own storage
+// convention: binary16 activations and outputs, What = binary16(fma(q, scale, z)) with a binary16
+// zero point that is added, f16 MFMAs, and the adapter term and the bias added in the epilogue.
 //
 // With one small tile per CU every 128-deep step holds only 16 MFMAs per SIMD, and in a
 // kernel where every wave fetches, dequantizes, stores, synchronizes and multiplies in
@@ -43,6 +45,7 @@
 namespace mlr {
 
 namespace mid {
+typedef _Float16 half16x8 __attribute__((ext_vector_type(8)));
 constexpr int THREADS = 768, CWAVES = 4, PTHREADS = 512;
 constexpr int MT = 128, CT = 64, RT = 128;
 constexpr int TI = 2, TJ = CT / 32;               // a consumer's wave tile: 64 x 64
@@ -63,7 +66,7 @@ __device__ __forceinline__ int swz(int row) { return row & 15; }
 __device__ __forceinline__ int tile_off(int row, int c) { return row * ROW_BYTES + ((c ^ swz(row)) << 4); }
 }  // namespace mid
 
-template <int BITS, bool BWD>
+template <int BITS, bool BWD, bool F16>
 __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
     using namespace mid;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -137,7 +140,8 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
         uint32_t fw_scale, fw_zero;
         u32x4 bw_lo, bw_hi;
         u32x2 bw_scale;
-        uint32_t bw_zero;
+        uint32_t bw_zero;     // four 8-bit zero points
+        u32x2 bw_zero16;      // F16: four binary16 zero points
     };
     WStage wst[W_SETS];
 #pragma unroll
@@ -146,7 +150,7 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
         for (int j = 0; j < BITS; ++j) wst[i].fw_words[j] = 0;
         wst[i].fw_scale = wst[i].fw_zero = wst[i].bw_zero = 0;
         wst[i].bw_lo = wst[i].bw_hi = u32x4{0, 0, 0, 0};
-        wst[i].bw_scale = u32x2{0, 0};
+        wst[i].bw_scale = wst[i].bw_zero16 = u32x2{0, 0};
     }
     auto load_w = [&](WStage &st, int t) {     // raw words, scales and zeros of full main tile t -> registers (async)
         if (!BWD) {
@@ -156,13 +160,15 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
             for (int j = 0; j < BITS; ++j) aload_b32(st.fw_words[j], wbase + (size_t)j * N, fw_off);
             const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
             aload_u16(st.fw_scale, a.w.scales + grow, fw_n * 2);
-            aload_u8(st.fw_zero, a.w.zeros + grow, fw_n);
+            if (F16) aload_u16(st.fw_zero, a.zeros16 + grow, fw_n * 2);
+            else aload_u8(st.fw_zero, a.w.zeros + grow, fw_n);
         } else {
             const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
             aload_b128(st.bw_lo, wbase, bw_off);
             if (BITS == 3) aload_b128(st.bw_hi, wbase, bw_offhi);
             aload_b64(st.bw_scale, a.w.scales + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff * 2);
-            aload_b32(st.bw_zero, a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff);
+            if (F16) aload_b64(st.bw_zero16, a.zeros16 + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff * 2);
+            else aload_b32(st.bw_zero, a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff);
         }
     };
     // Loads return in order: waiting until at most KEEP remain outstanding completes everything
@@ -186,19 +192,29 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
             } else {
                 asm volatile("s_waitcnt vmcnt(%3)" : "+v"(st.bw_lo), "+v"(st.bw_scale), "+v"(st.bw_zero) : "n"(KEEP) : "memory");
             }
+            if (F16) asm volatile("" : "+v"(st.bw_zero16)::"memory");   // stays behind the wait: volatile asms keep their order
         }
+    };
+    // w = fma(q, scale, bias): bias = -zero * scale for an integer zero point, or the binary16 zero
+    // point itself where it is one that is added (Section 2.2 eq. (2) as printed)
+    auto dq_of = [](uint16_t scale_bits, uint32_t zero_bits) {
+        if (!F16) return make_dq(scale_bits, (uint8_t)zero_bits);
+        DqConst c;
+        c.scale = half_bits_to_float(scale_bits);
+        c.bias = half_bits_to_float((uint16_t)zero_bits);
+        return c;
     };
     // dequantize quarter `part` (0..3) of the unit whose words are staged in `st` into weight tile `buf`
     auto store_w = [&](int buf, const WStage &st, int part) {
         unsigned char *Ws = smem + W_BASE + buf * W_BYTES;
         if (!BWD) {
             const int nl = unit & (CT - 1);
-            const DqConst dq = make_dq((uint16_t)st.fw_scale, (uint8_t)st.fw_zero);
+            const DqConst dq = dq_of((uint16_t)st.fw_scale, st.fw_zero);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (j != part) continue;
                 uint32_t o[4];
-                dequant_quarter<BITS>(st.fw_words, j, dq, o);
+                dequant_quarter<BITS, F16>(st.fw_words, j, dq, o);
                 *reinterpret_cast<uint4 *>(Ws + tile_off(nl, ukb * 4 + j)) = make_uint4(o[0], o[1], o[2], o[3]);
             }
         } else {
@@ -210,7 +226,8 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
             for (int i = 0; i < 4; ++i) {
                 chunk[i] = BITS == 3 ? st.bw_lo[i] : st.bw_lo[i] >> bw_shift;   // 3-bit: joined by wait_loads()
                 const uint16_t sb = bw_kok ? (uint16_t)(sc[i >> 1] >> ((i & 1) * 16)) : (uint16_t)0;
-                dq[i] = make_dq(sb, (uint8_t)(st.bw_zero >> (i * 8)));
+                const uint32_t zb = F16 ? (bw_kok ? (st.bw_zero16[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu : 0u) : (st.bw_zero >> (i * 8)) & 0xFFu;
+                dq[i] = dq_of(sb, zb);
             }
             // 32 lanes fill one whole row per store
 #pragma unroll
@@ -219,8 +236,8 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
                 uint32_t o[2];
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    o[i] = pack_bf16x2(dq_value(chunk_code<BITS>(chunk[2 * i], kk), dq[2 * i]),
-                                       dq_value(chunk_code<BITS>(chunk[2 * i + 1], kk), dq[2 * i + 1]));
+                    o[i] = pack_pair<F16>(dq_value(chunk_code<BITS>(chunk[2 * i], kk), dq[2 * i]),
+                                          dq_value(chunk_code<BITS>(chunk[2 * i + 1], kk), dq[2 * i + 1]));
                 *reinterpret_cast<uint2 *>(Ws + tile_off(ko * 8 + kk, no >> 1) + (no & 1) * 8) = make_uint2(o[0], o[1]);
             }
         }
@@ -280,12 +297,13 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
                 for (int j = 0; j < BITS; ++j) st.fw_words[j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off);
                 const size_t grow = (size_t)d.group_of_block((uint32_t)blk_c) * N;
                 st.fw_scale = ok ? (uint32_t)load_at<uint16_t>(a.w.scales + grow, fw_n * 2) : 0u;   // 0 -> weights +0
-                st.fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
+                if (F16) st.fw_zero = ok ? (uint32_t)load_at<uint16_t>(a.zeros16 + grow, fw_n * 2) : 0u;
+                else st.fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
             } else {
                 const bool ok = r0 + (unit & 31) * 4 < N;
                 st.bw_lo = u32x4{0, 0, 0, 0};
                 st.bw_hi = u32x4{0, 0, 0, 0};
-                st.bw_scale = u32x2{0, 0};
+                st.bw_scale = st.bw_zero16 = u32x2{0, 0};
                 st.bw_zero = 0;
                 if (ok) {
                     const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + r0;
@@ -296,7 +314,8 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
                         for (int i = 0; i < 4; ++i) st.bw_lo[i] = __builtin_amdgcn_alignbit(st.bw_hi[i], st.bw_lo[i], bw_shift);
                     }
                     st.bw_scale = load_at<u32x2>(a.w.scales + (size_t)bw_g0 * N + r0, bw_soff * 2);
-                    st.bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
+                    if (F16) st.bw_zero16 = load_at<u32x2>(a.zeros16 + (size_t)bw_g0 * N + r0, bw_soff * 2);
+                    else st.bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
                 }
             }
 #pragma unroll
@@ -412,7 +431,14 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
         for (int i = 0; i < TI; ++i)
 #pragma unroll
             for (int j = 0; j < TJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
+                if (F16) {
+                    half16x8 x, y;
+                    __builtin_memcpy(&x, &f.af[i], sizeof x);
+                    __builtin_memcpy(&y, &f.bf[j], sizeof y);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, y, acc[i][j], 0, 0, 0);
+                } else {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
+                }
     };
 
     if (n_full > 0) {
@@ -479,15 +505,52 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
     }
     __syncthreads();
 
-    // ---- epilogue of a consumer: its 32 x 64 block, one RNE to bfloat16, through an LDS patch
-    // so that the global stores are 16 bytes per lane and 128 contiguous bytes per row ----------
+    // ---- F16: the adapter term s P F and the bias join here, before the one rounding
+    // (Figure 1 / eq. (3); the bias belongs to the frozen layer and enters the forward pass only) ----
+    if (F16) {
+        const int r = a.ep_r;
+        float *Ps = reinterpret_cast<float *>(smem + 32768) + wave * (32 * 64);   // this wave's 32 rows of P
+        if (r > 0) {
+            for (int x = lane; x < 32 * r; x += 64) {
+                const int prow = x / r, jj = x - prow * r;
+                int m = m0 + wm * 64 + kg * 32 + prow;
+                if (m > a.M - 1) m = a.M - 1;
+                Ps[x] = a.ep_P[(size_t)m * r + jj];
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            const int col = c0 + j * 32 + (lane & 31);
+            const int cc = col < Cout ? col : Cout - 1;
+            float lora[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) lora[v] = 0.f;
+            for (int jj = 0; jj < r; ++jj) {
+                const float f = BWD ? a.ep_F[(size_t)cc * r + jj] : a.ep_F[(size_t)jj * N + cc];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+                    lora[v] = __builtin_fmaf(Ps[prow * r + jj], f, lora[v]);
+                }
+            }
+            float bias = 0.f;
+            if (!BWD && a.bias16 != nullptr) bias = half_bits_to_float(a.bias16[cc]);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) fin[j][v] = __builtin_fmaf(a.ep_scale, lora[v], fin[j][v] + bias);
+        }
+    }
+
+    // ---- epilogue of a consumer: its 32 x 64 block, one RNE to bfloat16 (binary16), through an LDS
+    // patch so that the global stores are 16 bytes per lane and 128 contiguous bytes per row ------
     uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + wave * (32 * PATCH_ROW);
 #pragma unroll
     for (int j = 0; j < TJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-            patch[prow * PATCH_ROW + j * 32 + (lane & 31)] = float_to_bf16_bits(fin[j][v]);
+            patch[prow * PATCH_ROW + j * 32 + (lane & 31)] = (uint16_t)(pack_pair<F16>(fin[j][v], 0.f) & 0xFFFFu);
         }
     __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the patch is private to the wave
     __builtin_amdgcn_wave_barrier();
@@ -502,15 +565,16 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
     }
 }
 
-template <int BITS, bool BWD>
+template <int BITS, bool BWD, bool F16 = false>
 static hipError_t launch_mid(const GemmArgs &a, hipStream_t stream) {
     const GemmDev d = make_gemm_dev(a, mid::MT, mid::CT);
     const int blocks = (d.tiles_m * d.tiles_c + 7) / 8 * 8;
-    auto kern = gemm_mid_kernel<BITS, BWD>;
+    auto kern = gemm_mid_kernel<BITS, BWD, F16>;
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), mid::LDS_BYTES, configured);
     if (e != hipSuccess) return e;
-    launch_kernel(BWD ? "gemm_bwd_128x64s" : "gemm_fwd_128x64s", kern, blocks, mid::THREADS, mid::LDS_BYTES, stream, d);
+    launch_kernel(F16 ? (BWD ? "f16_gemm_bwd" : "f16_gemm_fwd") : (BWD ? "gemm_bwd_128x64s" : "gemm_fwd_128x64s"), kern,
+                  blocks, mid::THREADS, mid::LDS_BYTES, stream, d);
     return hipGetLastError();
 }
 
@@ -519,6 +583,14 @@ hipError_t launch_gemm_mid(const GemmArgs &a, hipStream_t stream) {
         case 2: return a.backward ? launch_mid<2, true>(a, stream) : launch_mid<2, false>(a, stream);
         case 3: return a.backward ? launch_mid<3, true>(a, stream) : launch_mid<3, false>(a, stream);
         default: return a.backward ? launch_mid<4, true>(a, stream) : launch_mid<4, false>(a, stream);
+    }
+}
+
+hipError_t launch_gemm_mid_f16(const GemmArgs &a, hipStream_t stream) {
+    switch (a.w.bits) {
+        case 2: return a.backward ? launch_mid<2, true, true>(a, stream) : launch_mid<2, false, true>(a, stream);
+        case 3: return a.backward ? launch_mid<3, true, true>(a, stream) : launch_mid<3, false, true>(a, stream);
+        default: return a.backward ? launch_mid<4, true, true>(a, stream) : launch_mid<4, false, true>(a, stream);
     }
 }
 

@@ -55,8 +55,21 @@ struct GemmArgs {
     const uint16_t *w_ext;    // bf16 [Cout][RE] (NULL when RE == 0)
     int RE;                   // multiple of 16
     float *partials;          // scratch of gemm_partial_bytes() bytes (split contraction)
+    // The layer in the paper's own storage convention (launch_gemm_mid_f16 only): binary16
+    // activations and outputs, binary16 zero points that are added (w.zeros unused), an optional
+    // binary16 bias (forward), and the adapter term s P F in the epilogue instead of the extended
+    // contraction (act_ext, w_ext, RE unused).
+    const uint16_t *zeros16;  // binary16 [K/group][N]
+    const uint16_t *bias16;   // binary16 [N] or NULL
+    const float *ep_P;        // fp32 [M][ep_r] or NULL
+    const float *ep_F;        // forward B [r][N], backward A [K][r]
+    int ep_r;
+    float ep_scale;
 };
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
+// gemm_mid.hip, binary16 instantiation: the 128 x 64 producer / consumer kernel for the layer in
+// the paper's own storage convention (GemmArgs::zeros16, bias16, ep_*).
+hipError_t launch_gemm_mid_f16(const GemmArgs &a, hipStream_t stream);
 
 // How the 256 x 256 kernel fills 256 compute units when the tile count is not a multiple of
 // 256: the first `full` tiles run whole; each of the `tail` remaining ones is cut into

@@ -58,6 +58,11 @@ SHAPES = [
     (2, 512, 2056, 515, 5, 128, True),
     (4, 2048, 512, 64, 0, 128, True),        # no adapter
     (3, 4096, 4096, 512, 8, 128, True),      # the headline shape
+    # 128 tiles of 128 x 64 or more: the producer / consumer kernel, with a ragged row tile, ragged
+    # column tiles and a ragged last 128-deep step in both directions
+    (3, 2848, 2776, 300, 8, 32, True),
+    (4, 2816, 2776, 300, 16, 2816, False),   # one (scale, zero) pair per row
+    (2, 2944, 2752, 260, 40, 64, True),
 ]
 
 
@@ -99,6 +104,20 @@ def test_one_hot_activations_pick_out_single_weights():
     eyeN = torch.eye(264, dtype=torch.float16, device="cuda")
     dX, _ = b.modulora_f16_bwd_input(D["w"], eyeN[100:101].contiguous(), None, None, 1.0)
     assert np.array_equal(dX.view(torch.int16).cpu().numpy().view(np.uint16), What[100:101])
+
+
+def test_one_hot_activations_through_the_producer_consumer_kernel():
+    """The same observation of the dequantization inside the kernel at a size that takes the
+    128 x 64 producer / consumer kernel (300 one-hot rows, 132 tiles in both directions)."""
+    K, N = 2816, 2776
+    D = layer(3, K, N, 1, 0, 128, with_bias=False)
+    What = pl.dequant_f16(*oargs(D))
+    eyeK = torch.eye(K, dtype=torch.float16, device="cuda")
+    Y, _ = b.modulora_f16_fwd(D["w"], eyeK[100:400].contiguous(), None, None, 1.0)
+    assert np.array_equal(Y.view(torch.int16).cpu().numpy().view(np.uint16), What.T[100:400])
+    eyeN = torch.eye(N, dtype=torch.float16, device="cuda")
+    dX, _ = b.modulora_f16_bwd_input(D["w"], eyeN[200:500].contiguous(), None, None, 1.0)
+    assert np.array_equal(dX.view(torch.int16).cpu().numpy().view(np.uint16), What[200:500])
 
 
 def test_outputs_do_not_depend_on_stale_memory():
