@@ -502,14 +502,19 @@ hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act
     {
         const int Cout = backward ? w.K : w.N;
         const long tiles = (long)((M + 127) / 128) * ((Cout + 63) / 64);
-        if (M > 32 && tiles >= 128 && tiles <= 320 && std::getenv("MODULORA_F16_PLAIN") == nullptr) {
+        const long tiles256 = (long)((M + 255) / 256) * ((Cout + 255) / 256);
+        const bool use_mid = tiles >= 128 && tiles <= 320;
+        // several rounds' worth of 256 x 256 tiles: that kernel (whole tiles; a last round at least
+        // three quarters full, or many rounds)
+        const bool use_big = !use_mid && tiles256 >= 192 && (tiles256 % 256 == 0 || tiles256 % 256 >= 192 || tiles256 >= 1024);
+        if (M > 32 && (use_mid || use_big) && std::getenv("MODULORA_F16_PLAIN") == nullptr) {
             GemmArgs g{};
             g.w.K = w.K; g.w.N = w.N; g.w.bits = w.bits; g.w.group = w.group;
             g.w.qweight = w.qweight; g.w.scales = w.scales; g.w.zeros = nullptr;
             g.backward = backward; g.act = act; g.M = M; g.out = out;
             g.zeros16 = w.zeros; g.bias16 = w.bias;
             g.ep_P = r > 0 ? P : nullptr; g.ep_F = Fm; g.ep_r = r; g.ep_scale = lora_scale;
-            return launch_gemm_mid_f16(g, stream);
+            return use_mid ? launch_gemm_mid_f16(g, stream) : launch_gemm_big_f16(g, stream);
         }
     }
     F16GemmArgs a;

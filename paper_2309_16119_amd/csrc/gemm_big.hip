@@ -37,6 +37,7 @@
 namespace mlr {
 
 namespace big {
+typedef _Float16 half16x8 __attribute__((ext_vector_type(8)));
 constexpr int THREADS = 512, NWAVES = 8;
 constexpr int BAND = 4;                  // row blocks per band of the tile walk
 constexpr int MT = 256, CT = 256, WM = 128, WN = 64, RT = 64;
@@ -92,20 +93,63 @@ __device__ __forceinline__ BigItem big_item_of_block(int bid, const BigPlan &p) 
     return it;
 }
 
-// Epilogue of one wave for its i-th block of 32 rows: one RNE to bfloat16; the 32 x 64 patch
-// goes through LDS so that the global stores are 16 bytes per lane and 128 contiguous bytes
-// per row.
-__device__ __forceinline__ void big_epilogue_rows(const f32x16 (&acc_i)[big::TJ], int i, unsigned char *smem, uint16_t *out,
-                                                  int M, int Cout, int m0, int c0, int wave, int lane) {
+// Epilogue of one wave for its i-th block of 32 rows: one RNE to bfloat16 (binary16); the
+// 32 x 64 patch goes through LDS so that the global stores are 16 bytes per lane and 128
+// contiguous bytes per row.  F16 (the layer in the paper's own storage convention): the adapter
+// term s P F and the bias join here, before the rounding (Figure 1 / eq. (3); the bias belongs
+// to the frozen layer and enters the forward pass only); P's 32 rows pass through LDS behind
+// the patches.
+template <bool F16>
+__device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int i, unsigned char *smem, const GemmArgs &a, int Cout,
+                                                  int m0, int c0, int wave, int lane) {
     using namespace big;
     const int wm = wave >> 2, wn = wave & 3;
+    uint16_t *out = a.out;
+    const int M = a.M;
+    if (F16) {
+        const int r = a.ep_r, N = a.w.N;
+        const bool bwd = a.backward;
+        float *Ps = reinterpret_cast<float *>(smem + 40960) + wave * (32 * 64);
+        if (r > 0) {
+            for (int x = lane; x < 32 * r; x += 64) {
+                const int prow = x / r, jj = x - prow * r;
+                int m = m0 + wm * WM + i * 32 + prow;
+                if (m > M - 1) m = M - 1;
+                Ps[x] = a.ep_P[(size_t)m * r + jj];
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+        }
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) {
+            const int col = c0 + wn * WN + j * 32 + (lane & 31);
+            const int cc = col < Cout ? col : Cout - 1;
+            float lora[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) lora[v] = 0.f;
+            for (int jj = 0; jj < r; ++jj) {
+                const float f = bwd ? a.ep_F[(size_t)cc * r + jj] : a.ep_F[(size_t)jj * N + cc];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+                    lora[v] = __builtin_fmaf(Ps[prow * r + jj], f, lora[v]);
+                }
+            }
+            float bias = 0.f;
+            if (!bwd && a.bias16 != nullptr) bias = half_bits_to_float(a.bias16[cc]);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc_i[j][v] = __builtin_fmaf(a.ep_scale, lora[v], acc_i[j][v] + bias);
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // the next block of rows overwrites Ps
+        __builtin_amdgcn_wave_barrier();
+    }
     uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + wave * (32 * PATCH_ROW);
 #pragma unroll
     for (int j = 0; j < TJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-            patch[prow * PATCH_ROW + j * 32 + (lane & 31)] = float_to_bf16_bits(acc_i[j][v]);
+            patch[prow * PATCH_ROW + j * 32 + (lane & 31)] = (uint16_t)(pack_pair<F16>(acc_i[j][v], 0.f) & 0xFFFFu);
         }
     __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the patch is private to the wave
     __builtin_amdgcn_wave_barrier();
@@ -128,7 +172,7 @@ __device__ __forceinline__ float4 *big_partial_of(float *partials, int tail_tile
     return reinterpret_cast<float4 *>(partials) + ((size_t)tail_tile * split + slice) * (size_t)(big::THREADS * 32);
 }
 
-template <int BITS, bool BWD>
+template <int BITS, bool BWD, bool F16>
 __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, BigPlan plan) {
     using namespace big;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -210,7 +254,8 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         uint32_t fw_scale, fw_zero;
         u32x4 bw_lo, bw_hi;
         u32x2 bw_scale;
-        uint32_t bw_zero;
+        uint32_t bw_zero;     // four 8-bit zero points
+        u32x2 bw_zero16;      // F16: four binary16 zero points
     };
     WStage wst[2];
 #pragma unroll
@@ -219,7 +264,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         for (int j = 0; j < BITS; ++j) wst[i].fw_words[j] = 0;
         wst[i].fw_scale = wst[i].fw_zero = wst[i].bw_zero = 0;
         wst[i].bw_lo = wst[i].bw_hi = u32x4{0, 0, 0, 0};
-        wst[i].bw_scale = u32x2{0, 0};
+        wst[i].bw_scale = wst[i].bw_zero16 = u32x2{0, 0};
     }
 
     auto load_w = [&](WStage &st, int t) {     // raw words, scales and zeros of full main tile t -> registers (async)
@@ -230,13 +275,15 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
             for (int j = 0; j < BITS; ++j) aload_b32(st.fw_words[j], wbase + (size_t)j * N, fw_off);
             const size_t grow = (size_t)d.group_of_block((uint32_t)blk) * N;
             aload_u16(st.fw_scale, a.w.scales + grow, fw_n * 2);
-            aload_u8(st.fw_zero, a.w.zeros + grow, fw_n);
+            if (F16) aload_u16(st.fw_zero, a.zeros16 + grow, fw_n * 2);
+            else aload_u8(st.fw_zero, a.w.zeros + grow, fw_n);
         } else {
             const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + (size_t)t * RT;
             aload_b128(st.bw_lo, wbase, bw_off);
             if (BITS == 3) aload_b128(st.bw_hi, wbase, bw_offhi);
             aload_b64(st.bw_scale, a.w.scales + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff * 2);
-            aload_b32(st.bw_zero, a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff);
+            if (F16) aload_b64(st.bw_zero16, a.zeros16 + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff * 2);
+            else aload_b32(st.bw_zero, a.w.zeros + (size_t)bw_g0 * N + (size_t)t * RT, bw_soff);
         }
     };
     // wait for every outstanding load of this wave (direct and staged) and pin the staged
@@ -261,21 +308,31 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
             } else {
                 asm volatile("s_waitcnt vmcnt(%3)" : "+v"(st.bw_lo), "+v"(st.bw_scale), "+v"(st.bw_zero) : "n"(KEEP) : "memory");
             }
+            if (F16) asm volatile("" : "+v"(st.bw_zero16)::"memory");   // stays behind the wait: volatile asms keep their order
         }
     };
 
+    // w = fma(q, scale, bias): bias = -zero * scale for an integer zero point, or the binary16 zero
+    // point itself where it is one that is added (Section 2.2 eq. (2) as printed)
+    auto dq_of = [](uint16_t scale_bits, uint32_t zero_bits) {
+        if (!F16) return make_dq(scale_bits, (uint8_t)zero_bits);
+        DqConst c;
+        c.scale = half_bits_to_float(scale_bits);
+        c.bias = half_bits_to_float((uint16_t)zero_bits);
+        return c;
+    };
     // dequantize the staged words of one set into the W tile of buffer buf: quarter `part`
     // (0..3) of the thread's share, or all of it (part < 0)
     auto store_w = [&](int buf, const WStage &st, int part) {
         unsigned char *Ws = smem + W_BASE + buf * W_BYTES;
         if (!BWD) {
             const int nl = tid & (CT - 1);
-            const DqConst dq = make_dq((uint16_t)st.fw_scale, (uint8_t)st.fw_zero);
+            const DqConst dq = dq_of((uint16_t)st.fw_scale, st.fw_zero);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (part >= 0 && j != part) continue;
                 uint32_t o[4];
-                dequant_quarter<BITS>(st.fw_words, j, dq, o);
+                dequant_quarter<BITS, F16>(st.fw_words, j, dq, o);
                 *reinterpret_cast<uint4 *>(Ws + tile_off(nl, fw_kb * 4 + j)) = make_uint4(o[0], o[1], o[2], o[3]);
             }
         } else {
@@ -287,7 +344,8 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
             for (int i = 0; i < 4; ++i) {
                 chunk[i] = BITS == 3 ? st.bw_lo[i] : st.bw_lo[i] >> bw_shift;   // 3-bit: joined by wait_loads()
                 const uint16_t sb = bw_kok ? (uint16_t)(sc[i >> 1] >> ((i & 1) * 16)) : (uint16_t)0;
-                dq[i] = make_dq(sb, (uint8_t)(st.bw_zero >> (i * 8)));
+                const uint32_t zb = F16 ? (bw_kok ? (st.bw_zero16[i >> 1] >> ((i & 1) * 16)) & 0xFFFFu : 0u) : (st.bw_zero >> (i * 8)) & 0xFFu;
+                dq[i] = dq_of(sb, zb);
             }
             // a 16-lane group fills one row per store; neighbouring groups take their eight rows in
             // opposite order of parity, so that the two rows of a 32-lane store fall into different
@@ -299,8 +357,8 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
                 uint32_t o[2];
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    o[i] = pack_bf16x2(dq_value(chunk_code<BITS>(chunk[2 * i], kq), dq[2 * i]),
-                                       dq_value(chunk_code<BITS>(chunk[2 * i + 1], kq), dq[2 * i + 1]));
+                    o[i] = pack_pair<F16>(dq_value(chunk_code<BITS>(chunk[2 * i], kq), dq[2 * i]),
+                                          dq_value(chunk_code<BITS>(chunk[2 * i + 1], kq), dq[2 * i + 1]));
                 *reinterpret_cast<uint2 *>(Ws + tile_off(ko * 8 + kq, no >> 1) + (no & 1) * 8) = make_uint2(o[0], o[1]);
             }
         }
@@ -340,7 +398,14 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         for (int i = 0; i < TI; ++i)
 #pragma unroll
             for (int j = 0; j < TJ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
+                if (F16) {
+                    half16x8 x, y;
+                    __builtin_memcpy(&x, &f.af[i], sizeof x);
+                    __builtin_memcpy(&y, &f.bf[j], sizeof y);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(x, y, acc[i][j], 0, 0, 0);
+                } else {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.af[i], f.bf[j], acc[i][j], 0, 0, 0);
+                }
     };
     // ---- steady state: full main tiles -------------------------------------------
     // Step i works on tile t0 + i: activations in ring slot i % 3, weights in tile buffer i & 1.
@@ -432,7 +497,8 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
             for (int j = 0; j < BITS; ++j) wst[0].fw_words[j] = load_at<uint32_t>(wbase + (size_t)j * N, fw_off);
             const size_t grow = (size_t)d.group_of_block((uint32_t)blk_c) * N;
             wst[0].fw_scale = ok ? (uint32_t)load_at<uint16_t>(a.w.scales + grow, fw_n * 2) : 0u;   // 0 -> weights +0
-            wst[0].fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
+            if (F16) wst[0].fw_zero = ok ? (uint32_t)load_at<uint16_t>(a.zeros16 + grow, fw_n * 2) : 0u;
+            else wst[0].fw_zero = load_at<uint8_t>(a.w.zeros + grow, fw_n);
             store_w(0, wst[0], -1);
         } else {
             const bool ok = r0 + (tid & 15) * 4 < N;
@@ -441,6 +507,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
             st.bw_hi = u32x4{0, 0, 0, 0};
             st.bw_scale = u32x2{0, 0};
             st.bw_zero = 0;
+            st.bw_zero16 = u32x2{0, 0};
             if (ok) {
                 const uint32_t *wbase = a.w.qweight + (size_t)bw_row0 * N + r0;
                 st.bw_lo = load_at<u32x4>(wbase, bw_off);
@@ -450,7 +517,8 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
                     for (int i = 0; i < 4; ++i) st.bw_lo[i] = __builtin_amdgcn_alignbit(st.bw_hi[i], st.bw_lo[i], bw_shift);
                 }
                 st.bw_scale = load_at<u32x2>(a.w.scales + (size_t)bw_g0 * N + r0, bw_soff * 2);
-                st.bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
+                if (F16) st.bw_zero16 = load_at<u32x2>(a.zeros16 + (size_t)bw_g0 * N + r0, bw_soff * 2);
+                else st.bw_zero = load_at<uint32_t>(a.w.zeros + (size_t)bw_g0 * N + r0, bw_soff);
             }
             store_w(0, st, -1);
         }
@@ -482,7 +550,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         return;
     }
 #pragma unroll
-    for (int i = 0; i < TI; ++i) big_epilogue_rows(acc[i], i, smem, a.out, a.M, Cout, m0, c0, wave, lane);
+    for (int i = 0; i < TI; ++i) big_epilogue_rows<F16>(acc[i], i, smem, a, Cout, m0, c0, wave, lane);
 }
 
 // TI workgroups per split tile (workgroup y takes the y-th block of 32 rows of every wave):
@@ -513,22 +581,24 @@ __global__ __launch_bounds__(big::THREADS) void gemm_big_fixup_kernel(GemmDev d,
             acc[e / 4][4 * (e % 4) + 3] += v[e].w;
         }
     }
-    big_epilogue_rows(acc, i, smem, d.a.out, d.a.M, Cout, m0, c0, wave, lane);
+    big_epilogue_rows<false>(acc, i, smem, d.a, Cout, m0, c0, wave, lane);
 }
 
-template <int BITS, bool BWD>
+template <int BITS, bool BWD, bool F16 = false>
 static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
     const GemmDev d = make_gemm_dev(a, big::MT, big::CT);
-    const BigPlan plan = big_plan(a.M, BWD ? a.w.N : a.w.K, BWD ? a.w.K : a.w.N);
+    BigPlan plan = big_plan(a.M, BWD ? a.w.N : a.w.K, BWD ? a.w.K : a.w.N);
+    if (F16) plan.split = 1;   // whole tiles only: that path has no scratch for partial tiles
     const int whole = plan.split > 1 ? plan.full : plan.full + plan.tail;
     const int slices = plan.split > 1 ? plan.tail * plan.split : 0;
     const int blocks = ((whole + 7) / 8 + (slices + 7) / 8) * 8;
     const size_t lds_bytes = big::LDS_BYTES;
-    auto kern = gemm_big_kernel<BITS, BWD>;
+    auto kern = gemm_big_kernel<BITS, BWD, F16>;
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
     if (e != hipSuccess) return e;
-    launch_kernel(BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256", kern, blocks, big::THREADS, lds_bytes, stream, d, plan);
+    launch_kernel(F16 ? (BWD ? "f16_gemm_bwd" : "f16_gemm_fwd") : (BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256"), kern, blocks, big::THREADS,
+                  lds_bytes, stream, d, plan);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || plan.split <= 1) return err;
     launch_kernel(BWD ? "gemm_bwd_256x256_fixup" : "gemm_fwd_256x256_fixup", gemm_big_fixup_kernel, dim3(plan.tail, big::TI), big::THREADS, 0,
@@ -541,6 +611,14 @@ hipError_t launch_gemm_big(const GemmArgs &a, hipStream_t stream) {
         case 2: return a.backward ? launch_big<2, true>(a, stream) : launch_big<2, false>(a, stream);
         case 3: return a.backward ? launch_big<3, true>(a, stream) : launch_big<3, false>(a, stream);
         default: return a.backward ? launch_big<4, true>(a, stream) : launch_big<4, false>(a, stream);
+    }
+}
+
+hipError_t launch_gemm_big_f16(const GemmArgs &a, hipStream_t stream) {
+    switch (a.w.bits) {
+        case 2: return a.backward ? launch_big<2, true, true>(a, stream) : launch_big<2, false, true>(a, stream);
+        case 3: return a.backward ? launch_big<3, true, true>(a, stream) : launch_big<3, false, true>(a, stream);
+        default: return a.backward ? launch_big<4, true, true>(a, stream) : launch_big<4, false, true>(a, stream);
     }
 }
 

@@ -70,6 +70,8 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
 // gemm_mid.hip, binary16 instantiation: the 128 x 64 producer / consumer kernel for the layer in
 // the paper's own storage convention (GemmArgs::zeros16, bias16, ep_*).
 hipError_t launch_gemm_mid_f16(const GemmArgs &a, hipStream_t stream);
+// gemm_big.hip, binary16 instantiation: the 256 x 256 kernel, whole tiles only.
+hipError_t launch_gemm_big_f16(const GemmArgs &a, hipStream_t stream);
 
 // How the 256 x 256 kernel fills 256 compute units when the tile count is not a multiple of
 // 256: the first `full` tiles run whole; each of the `tail` remaining ones is cut into

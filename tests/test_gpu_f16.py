@@ -120,6 +120,38 @@ def test_one_hot_activations_through_the_producer_consumer_kernel():
     assert np.array_equal(dX.view(torch.int16).cpu().numpy().view(np.uint16), What[200:500])
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_large_shape_on_sampled_rows_and_one_hot(bits):
+    """Close to 200 tiles of 256 x 256 in both directions: the 256 x 256 kernel's binary16
+    instantiation (ragged last row tile).  The oracle's cost is linear in the token count, so Y
+    and dX are checked on sampled token rows (a row of Y / dX depends only on the same row of
+    X / dY); one-hot activations make the dequantization inside the kernel observable bit for bit."""
+    K, N, M, r, group = 4096, 3584, 3500, 8, 128
+    D = layer(bits, K, N, M, r, group, seed=9, with_bias=True)
+    s = D["lora_scale"]
+    Y, XA = b.modulora_f16_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], s)
+    dX, T = b.modulora_f16_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], s)
+    rows = np.unique(np.concatenate(([0, M - 1, 3327, 3328], np.random.default_rng(3).integers(0, M, 8))))
+    Yr, XAr = pl.fwd(*oargs(D), np.ascontiguousarray(D["X"][rows]), D["A"], D["B"], s, D["bias"])
+    dXr, Tr = pl.bwd_input(*oargs(D), np.ascontiguousarray(D["dY"][rows]), D["A"], D["B"], s)
+    assert_bar("Y", f64(Y)[rows], Yr)
+    assert_bar("dX", f64(dX)[rows], dXr)
+    tight("Y", f64(Y)[rows], Yr, K + r)
+    tight("dX", f64(dX)[rows], dXr, N + r)
+    tight("XA", f64(XA)[rows], XAr, K, out_f16=False)
+    tight("dYBt", f64(T)[rows], Tr, N, out_f16=False)
+
+    E = layer(bits, K, N, 1, 0, group, seed=9, with_bias=False)
+    What = pl.dequant_f16(*oargs(E))
+    eyeK = torch.eye(K, dtype=torch.float16, device="cuda")
+    Y1, _ = b.modulora_f16_fwd(E["w"], eyeK[300:300 + M].contiguous(), None, None, 1.0)
+    assert np.array_equal(Y1.view(torch.int16).cpu().numpy().view(np.uint16), What.T[300:300 + M])
+    del eyeK, Y1
+    eyeN = torch.eye(N, dtype=torch.float16, device="cuda")
+    dX1, _ = b.modulora_f16_bwd_input(E["w"], eyeN[:M].contiguous(), None, None, 1.0)
+    assert np.array_equal(dX1.view(torch.int16).cpu().numpy().view(np.uint16), What[:M])
+
+
 def test_outputs_do_not_depend_on_stale_memory():
     D = layer(4, 512, 520, 40, 8, 64)
     s = D["lora_scale"]
