@@ -314,15 +314,17 @@ mlr::F16Layer view_of(const modulora_qweight_f16 *w) {
     return mlr::F16Layer{w->d_in, w->d_out, w->bits, w->group_size, w->qweight, w->scales, w->zeros, w->bias};
 }
 struct F16Ws {
-    size_t p0, p1, gpart, total;
+    size_t p0, p1, gpart, gemm_part, total;
 };
 F16Ws f16_ws(int32_t K, int32_t N, int32_t M, int32_t r) {
     F16Ws l{};
-    if (r <= 0) return l;
     size_t off = 0;
-    l.p0 = off;    off += align256((size_t)M * r * 4);
-    l.p1 = off;    off += align256((size_t)M * r * 4);
-    l.gpart = off; off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
+    if (r > 0) {
+        l.p0 = off;    off += align256((size_t)M * r * 4);
+        l.p1 = off;    off += align256((size_t)M * r * 4);
+        l.gpart = off; off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
+    }
+    l.gemm_part = off; off += align256(mlr::gemm_partial_bytes(M, K, N));   // partial tiles of the 256 x 256 kernel
     l.total = off;
     return l;
 }
@@ -364,7 +366,8 @@ int modulora_f16_fwd(const modulora_qweight_f16 *w, const uint16_t *X, int32_t M
         P = XA ? XA : reinterpret_cast<float *>(static_cast<char *>(workspace) + l.p0);
         if ((s = hip_status(mlr::launch_f16_proj(X, M, w->d_in, A, true, r, P, st))) != MODULORA_OK) return s;
     }
-    return hip_status(mlr::launch_f16_gemm(view_of(w), false, X, M, Y, P, B, r, lora_scale, st));
+    float *parts = l.total > 0 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + l.gemm_part) : nullptr;
+    return hip_status(mlr::launch_f16_gemm(view_of(w), false, X, M, Y, P, B, r, lora_scale, parts, st));
 }
 
 int modulora_f16_bwd_input(const modulora_qweight_f16 *w, const uint16_t *dY, int32_t M, const float *A, const float *B,
@@ -384,7 +387,8 @@ int modulora_f16_bwd_input(const modulora_qweight_f16 *w, const uint16_t *dY, in
         P = dYBt ? dYBt : reinterpret_cast<float *>(static_cast<char *>(workspace) + l.p0);
         if ((s = hip_status(mlr::launch_f16_proj(dY, M, w->d_out, B, false, r, P, st))) != MODULORA_OK) return s;
     }
-    return hip_status(mlr::launch_f16_gemm(view_of(w), true, dY, M, dX, P, A, r, lora_scale, st));
+    float *parts = l.total > 0 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + l.gemm_part) : nullptr;
+    return hip_status(mlr::launch_f16_gemm(view_of(w), true, dY, M, dX, P, A, r, lora_scale, parts, st));
 }
 
 int modulora_f16_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, float lora_scale, const uint16_t *X,

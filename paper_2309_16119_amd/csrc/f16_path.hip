@@ -493,7 +493,7 @@ static hipError_t launch_f16_gemm_bits(F16GemmArgs &a, bool backward, hipStream_
 }
 
 hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act, int M, uint16_t *out, const float *P,
-                           const float *Fm, int r, float lora_scale, hipStream_t stream) {
+                           const float *Fm, int r, float lora_scale, float *partials, hipStream_t stream) {
     // About one 128 x 64 tile per compute unit (half a round to a round and a quarter of the 256):
     // the producer / consumer kernel of the bfloat16 path, instantiated for this storage convention
     // (its loads, LDS layout and wave roles are the same; dequantization, MFMA type and epilogue
@@ -504,9 +504,9 @@ hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act
         const long tiles = (long)((M + 127) / 128) * ((Cout + 63) / 64);
         const long tiles256 = (long)((M + 255) / 256) * ((Cout + 255) / 256);
         const bool use_mid = tiles >= 128 && tiles <= 320;
-        // several rounds' worth of 256 x 256 tiles: that kernel (whole tiles; a last round at least
-        // three quarters full, or many rounds)
-        const bool use_big = !use_mid && tiles256 >= 192 && (tiles256 % 256 == 0 || tiles256 % 256 >= 192 || tiles256 >= 1024);
+        // a few dozen 256 x 256 tiles or more: that kernel (the tiles of a partial last round are cut
+        // into slices of the contraction, as on the bfloat16 path)
+        const bool use_big = !use_mid && tiles256 >= 24;
         if (M > 32 && (use_mid || use_big) && std::getenv("MODULORA_F16_PLAIN") == nullptr) {
             GemmArgs g{};
             g.w.K = w.K; g.w.N = w.N; g.w.bits = w.bits; g.w.group = w.group;
@@ -514,6 +514,7 @@ hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act
             g.backward = backward; g.act = act; g.M = M; g.out = out;
             g.zeros16 = w.zeros; g.bias16 = w.bias;
             g.ep_P = r > 0 ? P : nullptr; g.ep_F = Fm; g.ep_r = r; g.ep_scale = lora_scale;
+            g.partials = partials;
             return use_mid ? launch_gemm_mid_f16(g, stream) : launch_gemm_big_f16(g, stream);
         }
     }

@@ -109,10 +109,10 @@ __device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int 
     if (F16) {
         const int r = a.ep_r, N = a.w.N;
         const bool bwd = a.backward;
-        float *Ps = reinterpret_cast<float *>(smem + 40960) + wave * (32 * 64);
+        float *Ps = reinterpret_cast<float *>(smem + 40960) + wave * (32 * 64);   // [jj][32 rows]
         if (r > 0) {
             for (int x = lane; x < 32 * r; x += 64) {
-                const int prow = x / r, jj = x - prow * r;
+                const int prow = x & 31, jj = x >> 5;
                 int m = m0 + wm * WM + i * 32 + prow;
                 if (m > M - 1) m = M - 1;
                 Ps[x] = a.ep_P[(size_t)m * r + jj];
@@ -120,25 +120,36 @@ __device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int 
             __builtin_amdgcn_s_waitcnt(0xc07f);
             __builtin_amdgcn_wave_barrier();
         }
+        int cc[TJ];
+        float lora[TJ][16];
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
             const int col = c0 + wn * WN + j * 32 + (lane & 31);
-            const int cc = col < Cout ? col : Cout - 1;
-            float lora[16];
+            cc[j] = col < Cout ? col : Cout - 1;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) lora[v] = 0.f;
-            for (int jj = 0; jj < r; ++jj) {
-                const float f = bwd ? a.ep_F[(size_t)cc * r + jj] : a.ep_F[(size_t)jj * N + cc];
+            for (int v = 0; v < 16; ++v) lora[j][v] = 0.f;
+        }
+        for (int jj = 0; jj < r; ++jj) {
+            float f[TJ];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int prow = 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-                    lora[v] = __builtin_fmaf(Ps[prow * r + jj], f, lora[v]);
-                }
+            for (int j = 0; j < TJ; ++j) f[j] = bwd ? a.ep_F[(size_t)cc[j] * r + jj] : a.ep_F[(size_t)jj * N + cc[j]];
+            // accumulator register v belongs to row 8 (v / 4) + 4 (lane / 32) + v % 4: four float4
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 p = *reinterpret_cast<const float4 *>(Ps + jj * 32 + 8 * q + 4 * (lane >> 5));
+                const float pv[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+                for (int z = 0; z < 4; ++z)
+#pragma unroll
+                    for (int j = 0; j < TJ; ++j) lora[j][4 * q + z] = __builtin_fmaf(pv[z], f[j], lora[j][4 * q + z]);
             }
-            float bias = 0.f;
-            if (!bwd && a.bias16 != nullptr) bias = half_bits_to_float(a.bias16[cc]);
+        }
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc_i[j][v] = __builtin_fmaf(a.ep_scale, lora[v], acc_i[j][v] + bias);
+        for (int j = 0; j < TJ; ++j) {
+            float bias = 0.f;
+            if (!bwd && a.bias16 != nullptr) bias = half_bits_to_float(a.bias16[cc[j]]);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc_i[j][v] = __builtin_fmaf(a.ep_scale, lora[j][v], acc_i[j][v] + bias);
         }
         __builtin_amdgcn_s_waitcnt(0xc07f);   // the next block of rows overwrites Ps
         __builtin_amdgcn_wave_barrier();
@@ -555,9 +566,10 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
 
 // TI workgroups per split tile (workgroup y takes the y-th block of 32 rows of every wave):
 // add the slices in slice order, then the common epilogue.
+template <bool F16>
 __global__ __launch_bounds__(big::THREADS) void gemm_big_fixup_kernel(GemmDev d, BigPlan plan) {
     using namespace big;
-    __shared__ __attribute__((aligned(16))) unsigned char smem[NWAVES * 32 * PATCH_ROW * 2];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // FIXUP_LDS bytes
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int tile = plan.full + blockIdx.x, i = blockIdx.y;
     const TileCoord tco = banded_tile<big::BAND>(tile, d.tiles_m, d.tiles_c);
@@ -581,14 +593,14 @@ __global__ __launch_bounds__(big::THREADS) void gemm_big_fixup_kernel(GemmDev d,
             acc[e / 4][4 * (e % 4) + 3] += v[e].w;
         }
     }
-    big_epilogue_rows<false>(acc, i, smem, d.a, Cout, m0, c0, wave, lane);
+    big_epilogue_rows<F16>(acc, i, smem, d.a, Cout, m0, c0, wave, lane);
 }
 
 template <int BITS, bool BWD, bool F16 = false>
 static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
     const GemmDev d = make_gemm_dev(a, big::MT, big::CT);
     BigPlan plan = big_plan(a.M, BWD ? a.w.N : a.w.K, BWD ? a.w.K : a.w.N);
-    if (F16) plan.split = 1;   // whole tiles only: that path has no scratch for partial tiles
+    if (a.partials == nullptr) plan.split = 1;   // no scratch for partial tiles: whole tiles only
     const int whole = plan.split > 1 ? plan.full : plan.full + plan.tail;
     const int slices = plan.split > 1 ? plan.tail * plan.split : 0;
     const int blocks = ((whole + 7) / 8 + (slices + 7) / 8) * 8;
@@ -601,8 +613,14 @@ static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
                   lds_bytes, stream, d, plan);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || plan.split <= 1) return err;
-    launch_kernel(BWD ? "gemm_bwd_256x256_fixup" : "gemm_fwd_256x256_fixup", gemm_big_fixup_kernel, dim3(plan.tail, big::TI), big::THREADS, 0,
-                  stream, d, plan);
+    // the patches, and behind them (F16) 32 rows of P per wave
+    constexpr size_t FIXUP_LDS = F16 ? 40960 + big::NWAVES * 32 * 64 * 4 : big::NWAVES * 32 * big::PATCH_ROW * 2;
+    auto fix = gemm_big_fixup_kernel<F16>;
+    static bool fix_configured[64] = {};
+    const hipError_t e2 = ensure_lds_limit(reinterpret_cast<const void *>(fix), FIXUP_LDS, fix_configured);
+    if (e2 != hipSuccess) return e2;
+    launch_kernel(F16 ? (BWD ? "f16_gemm_bwd_fixup" : "f16_gemm_fwd_fixup") : (BWD ? "gemm_bwd_256x256_fixup" : "gemm_fwd_256x256_fixup"), fix,
+                  dim3(plan.tail, big::TI), big::THREADS, FIXUP_LDS, stream, d, plan);
     return hipGetLastError();
 }
 

@@ -70,7 +70,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t stream);
 // gemm_mid.hip, binary16 instantiation: the 128 x 64 producer / consumer kernel for the layer in
 // the paper's own storage convention (GemmArgs::zeros16, bias16, ep_*).
 hipError_t launch_gemm_mid_f16(const GemmArgs &a, hipStream_t stream);
-// gemm_big.hip, binary16 instantiation: the 256 x 256 kernel, whole tiles only.
+// gemm_big.hip, binary16 instantiation: the 256 x 256 kernel (whole tiles only when GemmArgs::partials is NULL).
 hipError_t launch_gemm_big_f16(const GemmArgs &a, hipStream_t stream);
 
 // How the 256 x 256 kernel fills 256 compute units when the tile count is not a multiple of
@@ -180,8 +180,9 @@ hipError_t launch_f16_dequant(const F16Layer &w, uint16_t *What, hipStream_t str
 // P[M][r] = act[M][C] F, F = A [C][r] (f_is_A) or B^T with B [r][C]
 hipError_t launch_f16_proj(const uint16_t *act, int M, int C, const float *F, bool f_is_A, int r, float *P, hipStream_t stream);
 // forward: out[M][N] = act What^T + bias + s P B; backward: out[M][K] = act What + s P A^T
+// partials: scratch of gemm_partial_bytes(M, K, N) bytes for the 256 x 256 kernel's split contraction, or NULL
 hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act, int M, uint16_t *out, const float *P,
-                           const float *Fm, int r, float lora_scale, hipStream_t stream);
+                           const float *Fm, int r, float lora_scale, float *partials, hipStream_t stream);
 
 // ---- quantize.hip: round-to-nearest group quantizer + packer -------------------------
 struct QuantArgs {

@@ -63,6 +63,10 @@ SHAPES = [
     (3, 2848, 2776, 300, 8, 32, True),
     (4, 2816, 2776, 300, 16, 2816, False),   # one (scale, zero) pair per row
     (2, 2944, 2752, 260, 40, 64, True),
+    # about fifty 256 x 256 tiles in both directions: the 256 x 256 kernel with every tile cut into
+    # slices of the contraction, whose partial tiles a second launch adds (ragged M and N)
+    (3, 2816, 2456, 1100, 8, 128, True),
+    (4, 2816, 2456, 1100, 0, 64, False),
 ]
 
 
