@@ -27,6 +27,13 @@ CASES = [
     ("c5_65b_attn", 4096),
     ("c5_65b_up", 16),
     ("c5_65b_down", 16),
+    ("c4_30b_up", None),
+    ("c4_30b_down", None),
+    ("c5_65b_up", 1),
+    ("c5_65b_up", 256),
+    ("c5_65b_up", 4096),
+    ("c5_65b_down", 256),
+    ("c5_65b_down", 4096),
 ]
 
 
