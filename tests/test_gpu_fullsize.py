@@ -92,3 +92,64 @@ def test_full_size_layer_against_oracle(name, M):
     rhs = float((dX.double() * L["X"].double()).sum())
     mag = float((L["dY"].double().abs() * Y.double().abs()).sum())
     assert abs(lhs - rhs) <= 2.0 ** -9 * mag, (lhs, rhs, mag)
+
+
+def test_operands_beyond_four_gib():
+    """More tokens than 32-bit byte offsets can address: X, dY, Y and dX are 4.5 GB each, so
+    the rows past index 2^20 lie beyond 4 GiB from the start of their matrices.  Only a few
+    thousand rows, spread over the whole range and dense at its very end, are non-zero; the
+    oracle sees just those rows (every sum over tokens skips zero rows, every output row
+    depends on its own input row alone).  An address that wrapped at 4 GiB would read a zero
+    row in place of a populated one, or write into a row that must stay zero."""
+    K = N = 2048
+    bits, group, r, s = 3, 128, 8, 2.0
+    M = (1 << 20) + (1 << 16) + 3
+    n_live = 4096
+    small = synth.LayerConfig("beyond_4gib", K, N, bits, group, n_live, r)
+    L = synth.make_layer_torch(small, "cuda", seed=23)
+    rng = np.random.default_rng(9)
+    live = np.unique(np.concatenate((rng.integers(0, M, n_live - 200), np.arange(M - 150, M), [0, 1 << 20, (1 << 20) + 1])))
+    n_live = live.size
+    live_t = torch.from_numpy(live).cuda()
+    X = torch.zeros((M, K), dtype=torch.bfloat16, device="cuda")
+    dY = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda")
+    X[live_t] = L["X"][:n_live]
+    dY[live_t] = L["dY"][:n_live]
+    assert X.numel() * 2 > (1 << 32) and int(live[-1]) * K * 2 > (1 << 32)
+
+    w = b.QWeight(L["qweight"], L["scales"], L["zeros"], K, N, bits, group)
+    Y, XA = b.modulora_fwd(w, X, L["A"], L["B"], s)
+    dX, T = b.modulora_bwd_input(w, dY, L["A"], L["B"], s)
+    dA, dB = b.modulora_bwd_lora(X, dY, L["A"], L["B"], s, XA=XA, dYBt=T)
+    torch.cuda.synchronize()
+
+    # rows that must be zero are zero, and no populated row came out empty
+    is_live = torch.zeros(M, dtype=torch.bool, device="cuda")
+    is_live[live_t] = True
+    for name, out in (("Y", Y), ("dX", dX), ("XA", XA), ("dYBt", T)):
+        nonzero_rows = out.ne(0).any(dim=1)
+        assert torch.equal(nonzero_rows, is_live), name
+
+    qw = L["qweight"].cpu().numpy().view(np.uint32)
+    sc = host16(L["scales"])
+    zz = L["zeros"].cpu().numpy()
+    Ah, Bh = L["A"].cpu().numpy(), L["B"].cpu().numpy()
+    wargs = (qw, sc, zz, K, N, bits, group)
+    Xl, dYl = host16(L["X"][:n_live]), host16(L["dY"][:n_live])
+    # Y and dX on the populated rows from the far end and a sample of the others
+    pick = np.unique(np.concatenate((np.arange(n_live - 24, n_live), rng.integers(0, n_live, 24))))
+    pick_t = live_t[torch.from_numpy(pick).cuda()]
+    Yr, Ur = oracle.fwd(*wargs, np.ascontiguousarray(Xl[pick]), Ah, Bh, s)
+    dXr, Tr = oracle.bwd_input(*wargs, np.ascontiguousarray(dYl[pick]), Ah, Bh, s)
+    assert_bar("Y", f64(Y[pick_t]), Yr)
+    assert_tight("Y", f64(Y[pick_t]), Yr, True, K)
+    assert_bar("dX", f64(dX[pick_t]), dXr)
+    assert_tight("dX", f64(dX[pick_t]), dXr, True, N)
+    assert_tight("XA", f64(XA[pick_t]), Ur, False, K)
+    assert_tight("dYBt", f64(T[pick_t]), Tr, False, N)
+    # the adapter gradients: sums over all tokens = sums over the populated rows
+    dAr, dBr = oracle.bwd_lora(K, N, Xl, dYl, Ah, Bh, s)
+    assert_bar("dA", f64(dA), dAr)
+    assert_bar("dB", f64(dB), dBr)
+    assert_tight("dA", f64(dA), dAr, False, n_live * N)
+    assert_tight("dB", f64(dB), dBr, False, n_live * K)
