@@ -164,3 +164,53 @@ def test_outputs_do_not_depend_on_stale_memory():
     b._workspaces.clear()
     b.modulora_f16_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], s, Y=Y1)
     assert torch.equal(Y0.view(torch.int16), Y1.view(torch.int16))
+
+
+def test_operands_beyond_four_gib():
+    """A million tokens: X, dY, Y and dX are 4.5 GB each, so rows past index 2^20 lie beyond
+    4 GiB from the start of their matrices.  A few thousand rows, spread over the range and
+    dense at its end, are populated; the others are zero, so their outputs must be exactly the
+    bias (Y) or zero (dX), and the sums over tokens reduce to the populated rows, which is all
+    the oracle is given."""
+    K = N = 2048
+    bits, group, r = 3, 128, 8
+    M = (1 << 20) + (1 << 16) + 3
+    rng = np.random.default_rng(9)
+    live = np.unique(np.concatenate((rng.integers(0, M, 3800), np.arange(M - 150, M), [0, 1 << 20, (1 << 20) + 1])))
+    n_live = live.size
+    D = layer(bits, K, N, n_live, r, group, seed=13, with_bias=True)
+    s = D["lora_scale"]
+    live_t = torch.from_numpy(live).cuda()
+    X = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+    dY = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    X[live_t] = D["Xd"]
+    dY[live_t] = D["dYd"]
+    assert int(live[-1]) * K * 2 > (1 << 32)
+
+    Y, XA = b.modulora_f16_fwd(D["w"], X, D["Ad"], D["Bd"], s)
+    dX, T = b.modulora_f16_bwd_input(D["w"], dY, D["Ad"], D["Bd"], s)
+    dA, dB = b.modulora_f16_bwd_lora(X, dY, D["Ad"], D["Bd"], s, XA=XA, dYBt=T)
+    torch.cuda.synchronize()
+
+    is_live = torch.zeros(M, dtype=torch.bool, device="cuda")
+    is_live[live_t] = True
+    bias_d = f16_dev(D["bias"])
+    assert torch.equal(Y.ne(bias_d).any(dim=1), is_live), "Y"
+    for name, out in (("dX", dX), ("XA", XA), ("dYBt", T)):
+        assert torch.equal(out.ne(0).any(dim=1), is_live), name
+
+    pick = np.unique(np.concatenate((np.arange(n_live - 24, n_live), rng.integers(0, n_live, 24))))
+    pick_t = live_t[torch.from_numpy(pick).cuda()]
+    Yr, XAr = pl.fwd(*oargs(D), np.ascontiguousarray(D["X"][pick]), D["A"], D["B"], s, D["bias"])
+    dXr, Tr = pl.bwd_input(*oargs(D), np.ascontiguousarray(D["dY"][pick]), D["A"], D["B"], s)
+    assert_bar("Y", f64(Y[pick_t]), Yr)
+    assert_bar("dX", f64(dX[pick_t]), dXr)
+    tight("Y", f64(Y[pick_t]), Yr, K + r)
+    tight("dX", f64(dX[pick_t]), dXr, N + r)
+    tight("XA", f64(XA[pick_t]), XAr, K, out_f16=False)
+    tight("dYBt", f64(T[pick_t]), Tr, N, out_f16=False)
+    dAr, dBr = pl.bwd_lora(D["X"], D["dY"], D["A"], D["B"], s)
+    assert_bar("dA", f64(dA), dAr)
+    assert_bar("dB", f64(dB), dBr)
+    tight("dA", f64(dA), dAr, n_live * N, out_f16=False)
+    tight("dB", f64(dB), dBr, n_live * K, out_f16=False)
