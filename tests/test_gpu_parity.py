@@ -105,6 +105,9 @@ SHAPES = [
     (3, 2112, 2136, 300, 8, 64),
     (4, 2144, 2080, 300, 16, 32),
     (2, 2048, 2176, 384, 40, 2048),
+    # either side of the token count at which the streaming kernels hand over to the tile kernels
+    (3, 1024, 768, 17, 8, 128),
+    (4, 512, 520, 32, 8, 64),
 ]
 
 
