@@ -97,8 +97,8 @@ size_t modulora_workspace_bytes(const modulora_qweight *w, int32_t M, int32_t r)
 
 /*
  * Test-only: materialize the whole weight, What[n][k] as defined above, into
- * What_bf16 [d_out][d_in] (bfloat16 bits, d_in contiguous).  This is the paper's
- * "weight materialization" (Figure 1, hatW = dequantize(hatWq, z, s)); the product
+ * What_bf16 [d_out][d_in] (bfloat16 bits, d_in contiguous).  This is the weight
+ * materialization step of Figure 1 (LPLinear.forward, before the product); the product
  * path never calls it -- it exists so that unpacking and dequantization can be
  * checked bit for bit.
  */
@@ -112,6 +112,14 @@ int modulora_dequant(const modulora_qweight *w, uint16_t *What_bf16, void *strea
  *   Y  [M][d_out] bfloat16 (out)   XA [M][r] float32 (out, may be NULL)
  * r == 0 (A, B ignored) is the plain low-precision linear map LPLinear.forward.
  * fp32 accumulation; one round-to-nearest-even to bfloat16 at the end.
+ * Arithmetic by token count.  M > 16: What is materialized tile by tile exactly as defined
+ * above (rounded to bfloat16) and multiplied.  M <= 16 (when the shape allows: d_in a
+ * multiple of 128, group_size a multiple of 32 / 64 / 128 for 4 / 2 / 3 bits): the direct
+ * product with the quantized matrix of Section 3.1.2 -- the codes are multiplied as they are
+ * and scale and zero point are applied to per-group sums, so What is NOT rounded to bfloat16
+ * first.  The result then differs from the materialized form by at most
+ * 2^-8 sum_k |X[m][k]| |What[n][k]| (closer to the exact product); the same input row can
+ * therefore give results that differ by this much at M = 16 and at M = 17.
  */
 int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M,
                  const float *A, const float *B, int32_t r, float lora_scale,
@@ -127,6 +135,10 @@ int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M,
  *   dY [M][d_out] bfloat16          dX [M][d_in] bfloat16 (out)
  *   dYBt [M][r] float32 (out, may be NULL)
  * No gradient flows to qweight, scales or zeros.
+ * Arithmetic by token count, as for modulora_fwd: at M <= 16 (when d_out is a multiple of
+ * 128 and group_size a multiple of 128) the codes are multiplied directly and the scaled
+ * activation dY[m][n] * scales[g][n] is rounded to bfloat16 before the product; the result
+ * differs from the materialized form by at most 2^-7 sum_n |dY[m][n]| |What[n][k]|.
  */
 int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M,
                        const float *A, const float *B, int32_t r, float lora_scale,
@@ -192,15 +204,6 @@ int modulora_adamw(float *param, const float *grad, float *exp_avg, float *exp_a
                    float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step,
                    void *stream);
 
-/*
- * Per-kernel timing for benchmarks.  Between modulora_profile_begin() and
- * modulora_profile_end() every kernel the library launches is bracketed by HIP
- * events on the stream it is launched on.  modulora_profile_end() waits for those
- * events (it synchronizes with the device -- the only call that does), writes one
- * record per distinct kernel name into `out` (host memory, at most `capacity`
- * records) and stores the number of records in *count.  Not thread-safe; meant for
- * a benchmark's timed loop, not for production use.
- */
 /* ------------------------------------------------------------------------------------
  * The layer in the paper's own storage convention (Section 2.2 eq. (2): What = s (.) Wq + z
  * with a FLOATING zero point z; Section 3.2: z, s and the materialized What in a 16-bit
@@ -260,6 +263,16 @@ int modulora_f16_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, flo
                           float *dA, float *dB, int32_t accumulate,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Per-kernel timing for benchmarks and tests (no operation of the paper).  Between
+ * modulora_profile_begin() and modulora_profile_end() every kernel the library launches is
+ * bracketed by a fresh pair of HIP events on the stream it is launched on.
+ * modulora_profile_end() waits for those events (it synchronizes with the device -- the only
+ * call that does), writes one record per distinct kernel name into `out` (host memory, at most
+ * `capacity` records) and stores the number of records in *count.  While profiling is active
+ * the launch path creates events, so calls made then must NOT be recorded into a HIP graph.
+ * Not thread-safe; not for production use.
+ */
 typedef struct {
     char name[64];      /* kernel family and tile variant, NUL-terminated */
     int32_t launches;   /* launches seen since modulora_profile_begin()   */

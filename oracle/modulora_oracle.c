@@ -154,7 +154,7 @@ int oracle_dequant_bf16(const uint32_t *qweight, const uint16_t *scales,
 
 /* The materialized weight What[n][k], held as float32 [N][K] (every
  * bfloat16 value is a float32 value, so nothing is lost).  Figure 1 of the
- * paper: hatW = dequantize(hatWq, z, s), then the matrix product.
+ * paper (LPLinear.forward): the weight is materialized first, then multiplied.
  * k_major only chooses the storage order of the copy (so that the loop that
  * consumes it walks memory forwards); the values are the same.
  * Returns NULL when out of memory; the caller frees it. */

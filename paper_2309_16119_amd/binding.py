@@ -145,14 +145,24 @@ _workspaces: dict = {}
 
 
 def _workspace(device, nbytes: int) -> Optional[torch.Tensor]:
-    """A cached scratch tensor per device (grown on demand); torch memory is 256-byte aligned."""
+    """Scratch memory for one call: a cached tensor per (device, current stream), so that calls
+    sharing a buffer are ordered on one stream as the library requires.  A request larger than
+    the cached buffer gets a new one; the old ones stay alive until the process ends, because a
+    HIP graph captured earlier may still hold their addresses.  torch memory is 256-byte aligned.
+    Callers that capture graphs can size the buffer first with reserve_workspace()."""
     if nbytes == 0:
         return None
-    ws = _workspaces.get(device)
-    if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
-        _workspaces[device] = ws
-    return ws
+    key = (torch.device(device), torch.cuda.current_stream(device).cuda_stream)
+    held = _workspaces.setdefault(key, [])
+    if not held or held[-1].numel() < nbytes:
+        held.append(torch.empty(nbytes, dtype=torch.uint8, device=device))
+    return held[-1]
+
+
+def reserve_workspace(device, nbytes: int) -> None:
+    """Make the cached scratch buffer of (device, current stream) at least `nbytes` large now, e.g.
+    before a HIP graph capture (allocating during capture would tie the buffer to the graph's pool)."""
+    _workspace(device, int(nbytes))
 
 
 def _check(status: int, where: str):

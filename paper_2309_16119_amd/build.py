@@ -24,9 +24,6 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    # fp32 atomic adds as the hardware instruction (not a compare-and-swap loop); valid for
-    # ordinary (coarse-grained) device allocations, which is all this library is given
-    "-munsafe-fp-atomics",
     "-Wall", "-Wno-unused-variable", "-Wno-unused-but-set-variable",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

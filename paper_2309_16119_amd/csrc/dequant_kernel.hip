@@ -1,5 +1,5 @@
 // Standalone weight materialization (test-only entry point modulora_dequant):
-// the paper's "weight materialization" of Figure 1, hatW = dequantize(hatWq, z, s),
+// the weight materialization step of Figure 1 (LPLinear.forward, before the product),
 // written out to HBM as bfloat16 [N][K].  It exists so that unpacking and
 // dequantization -- the same device functions the fused kernels use -- can be
 // compared with the oracle bit for bit.

@@ -507,7 +507,9 @@ hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act
         // a few dozen 256 x 256 tiles or more: that kernel (the tiles of a partial last round are cut
         // into slices of the contraction, as on the bfloat16 path)
         const bool use_big = !use_mid && tiles256 >= 24;
-        if (M > 32 && (use_mid || use_big) && std::getenv("MODULORA_F16_PLAIN") == nullptr) {
+        // MODULORA_F16_PLAIN (read once per process) keeps every shape on the plain kernel, for comparisons
+        static const bool force_plain = std::getenv("MODULORA_F16_PLAIN") != nullptr;
+        if (M > 32 && (use_mid || use_big) && !force_plain) {
             GemmArgs g{};
             g.w.K = w.K; g.w.N = w.N; g.w.bits = w.bits; g.w.group = w.group;
             g.w.qweight = w.qweight; g.w.scales = w.scales; g.w.zeros = nullptr;

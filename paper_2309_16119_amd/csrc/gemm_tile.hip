@@ -87,7 +87,7 @@ __global__ __launch_bounds__(THREADS, OCC) void gemm_tile_kernel(GemmDev d) {
     constexpr int GWAVES = NWAVES / KG;      // waves of one k-group: they tile the MT x CT output
     static_assert((MT / WM) * (CT / WN) == GWAVES && GWAVES * KG == NWAVES, "wave grid covers the tile");
     constexpr int KS_LOCAL = (RT / 16) / KG;   // 16-deep steps of a tile that one wave takes: ks = i * KG + kg
-    static_assert((KG == 1 || KG == 2 || KG == 4) && (RT / 16) % KG == 0 && (KS_LOCAL == 2 || KS_LOCAL == 4 || KS_LOCAL == 8),
+    static_assert((KG == 1 || KG == 2) && (RT / 16) % KG == 0 && (KS_LOCAL == 2 || KS_LOCAL == 4 || KS_LOCAL == 8),
                   "k-steps divide between the groups");
     static_assert(WM % 32 == 0 && WN == 64, "wave tile: rows in 32s, two 32-column MFMA tiles");
     extern __shared__ __attribute__((aligned(16))) uint16_t lds[];
@@ -632,8 +632,9 @@ static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_
 }
 
 // Tile variants.  `pick` may be forced with the environment variable MODULORA_TILE
-// (big | mid | m128 | m64 | m64k | t128 | t128k | t128s | small), a tuning knob for benchmarks.
-enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128, PICK_T128K, PICK_T128S, PICK_SMALL };
+// (big | mid | m128 | m64 | m64k | t128s | small), a tuning knob for benchmarks.  Every variant
+// listed is one the automatic choice below can reach.
+enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128S, PICK_SMALL };
 
 static TilePick forced_pick() {
     static int cached = -1;
@@ -646,8 +647,6 @@ static TilePick forced_pick() {
             else if (!std::strcmp(e, "m128")) cached = PICK_M128;
             else if (!std::strcmp(e, "m64")) cached = PICK_M64;
             else if (!std::strcmp(e, "m64k")) cached = PICK_M64K;
-            else if (!std::strcmp(e, "t128")) cached = PICK_T128;
-            else if (!std::strcmp(e, "t128k")) cached = PICK_T128K;
             else if (!std::strcmp(e, "t128s")) cached = PICK_T128S;
             else if (!std::strcmp(e, "small")) cached = PICK_SMALL;
         }
@@ -673,7 +672,7 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
                                    {PICK_M128, 128, 128, 2, 0.97, 1.40},
                                    {PICK_M64, 64, 128, 2, 0.75, 1.10},
                                    {PICK_M64K, 64, 128, 1, 0.62, 0.62},
-                                   {PICK_T128S, 128, 64, 1, 0.48, 0.48}};   // gemm_mid.hip (t128k, its predecessor here: 0.57)
+                                   {PICK_T128S, 128, 64, 1, 0.48, 0.48}};   // gemm_mid.hip
             const int C = BWD ? a.w.N : a.w.K;
             const double steps = (double)C / 64.0;
             const BigPlan bp = big_plan(a.M, C, Cout);
@@ -703,14 +702,8 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
         case PICK_M64K:   // 8 waves: two k-groups of 4 share every 128-deep tile
             return launch_variant<BITS, BWD, 512, 64, 128, 32, 64, 1, 3, 128, 2>(
                 a, BWD ? "gemm_bwd_64x128k" : "gemm_fwd_64x128k", stream);
-        case PICK_T128:   // tall tile: half the dequantization work per output of the 64-row tile
-            return launch_variant<BITS, BWD, 256, 128, 64, 32, 64, 1, 2, 128, 1>(
-                a, BWD ? "gemm_bwd_128x64" : "gemm_fwd_128x64", stream);
         case PICK_T128S:  // 8 waves: four consumers (k-groups of one 128x64 wave tile) and four producers
             return launch_gemm_mid(a, stream);
-        case PICK_T128K:  // 8 waves: four k-groups of two 64x64 wave tiles
-            return launch_variant<BITS, BWD, 512, 128, 64, 64, 64, 1, 3, 128, 4>(
-                a, BWD ? "gemm_bwd_128x64k" : "gemm_fwd_128x64k", stream);
         default:
             return launch_gemm_big(a, stream);
     }

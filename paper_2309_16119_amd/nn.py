@@ -76,6 +76,12 @@ class ModuLoRALinear(torch.nn.Module):
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         return LPLoRAFunction.apply(x, self.A, self.B, self.w, self.lora_scale)
 
+    def reserve_workspace(self, tokens: int) -> None:
+        """Size the binding's cached scratch buffer of the current stream for `tokens` rows now, so
+        that no allocation happens later (call it on the capture stream before a HIP graph capture)."""
+        query = b.modulora_f16_workspace_bytes if isinstance(self.w, b.QWeightF16) else b.modulora_workspace_bytes
+        b.reserve_workspace(self.w.device, query(self.w, int(tokens), self.r))
+
 
 class FusedAdapterAdamW:
     """AdamW (the optimizer of the paper's Appendix hyper-parameter tables) over the adapter

@@ -41,9 +41,10 @@ def test_graph_replays_equal_eager_steps(bits, K, N, M, r, group):
         b.modulora_bwd_input(D["w"], dY, D["Ad"], D["Bd"], s, dX=out["dX"], dYBt=out["T"])
         b.modulora_bwd_lora(X, dY, D["Ad"], D["Bd"], s, XA=out["XA"], dYBt=out["T"], dA=out["dA"], dB=out["dB"])
 
-    step()                       # eager first: kernel attributes and the cached workspace exist before the capture
-    torch.cuda.synchronize()
     side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()                   # eager first, on the capture stream: kernel attributes and that stream's
+    torch.cuda.synchronize()     # cached workspace exist before the capture
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
