@@ -1,15 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the quantized-LoRA linear layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-extra]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--M TOKENS] [--no-extra]
 
 A "step" is one pass of the whole hot path over one batch of synthetic tokens:
 modulora_fwd + modulora_bwd_input + modulora_bwd_lora of one layer, inputs already
-resident in HBM.  The headline workload is the LLaMA-7B attention projection
-(4096x4096, 3-bit, group 128, M = 512, r = 8); `--workload` picks another one.
-The timed region replays the K steps from one HIP graph (no host launch overhead);
-weights rotate over enough distinct copies (>= 512 MB) that no step finds its
-packed weights in the last-level cache.  Prints ONE JSON line.
+resident in HBM.  The headline workload is the largest single-GPU configuration of the
+benchmark: the LLaMA-65B up projection (8192 -> 22016, 3-bit, group 128, r = 8) at
+M = 4096 tokens; `--workload` / `--M` pick another one.  The timed region replays the K
+steps from one HIP graph (no host launch overhead), REPEATS times, and the median replay
+is reported; weights rotate over enough distinct copies (>= 512 MB) that no step finds its
+packed weights in the last-level cache.  Prints ONE JSON line, which also carries the
+second half of the metric -- the packed-weight GB/s of the M <= 16 streaming passes
+(`packed_weight_GBps`) -- the roofline of the dominant kernel and of the whole layer, the
+CPU oracle timed on a bounded sample, and the other benchmark configurations (`extra`).
 """
 from __future__ import annotations
 
@@ -18,6 +22,7 @@ import ctypes
 import json
 import math
 import os
+import statistics
 import sys
 import time
 
@@ -29,18 +34,22 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor peak
 ROTATE_BYTES = 512 << 20        # distinct packed weights touched before one is reused
 COPY_CAL_BYTES = 1 << 30        # size of the copy that calibrates the rocprofv3 byte counters
+REPEATS = 5                     # timed replays of the K steps; the median is reported
+HEADLINE = ("c5_65b_up", 4096)  # the largest single-GPU configuration
+ORACLE_ROWS = 64                # token rows the CPU oracle computes where a full step would take minutes
 
 
 def parse_args():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=50)
-    p.add_argument("--warmup", type=int, default=10)
-    p.add_argument("--workload", default="c2_7b_attn")
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--workload", default=None, help="a name from synth.CONFIGS (default: %s at M = %d)" % HEADLINE)
     p.add_argument("--M", type=int, default=None, help="override the token count of the workload")
     p.add_argument("--variant", choices=("bf16", "f16"), default="bf16",
                    help="f16: the layer in the paper's own storage convention (float zero point, binary16, bias)")
     p.add_argument("--no-extra", action="store_true", help="skip the additional workloads")
+    p.add_argument("--no-small", action="store_true", help="skip the M <= 16 packed-weight block")
     p.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     p.add_argument("--no-traffic", action="store_true",
@@ -142,6 +151,7 @@ class WorkloadF16:
         self.dY = torch.randn((M, N), device="cuda", generator=gen).to(torch.float16)
         self.A = 0.02 * torch.randn((K, r), device="cuda", generator=gen)
         self.B = 0.02 * torch.randn((r, N), device="cuda", generator=gen)
+        self.host_layer = host_layer
         if host_layer is not None:      # weight copy 0 and the activations are the host layer's (parity against the oracle)
             L = host_layer
             self.weights[0] = b.QWeightF16.from_numpy(L["qweight"], L["scales"], L["zeros_f16"], L["bias"], K, N, bits, g)
@@ -252,9 +262,9 @@ class DecoderLayerWorkload:
             raise RuntimeError("library call failed with status %d" % rc)
 
 
-def time_steps(wl, steps: int, warmup: int, use_graph: bool, calls=None) -> float:
-    """Milliseconds per step over exactly `steps` steps (after `warmup` untimed ones).  `calls`
-    restricts a step to some of the three library calls (per-call times)."""
+def time_steps(wl, steps: int, warmup: int, use_graph: bool, calls=None, repeats: int = REPEATS):
+    """(median, all) milliseconds per step over `repeats` timed runs of exactly `steps` steps each
+    (after `warmup` untimed steps).  `calls` restricts a step to some of the three library calls."""
     torch = wl.torch
     if calls is not None:
         full_step = wl.step
@@ -262,6 +272,7 @@ def time_steps(wl, steps: int, warmup: int, use_graph: bool, calls=None) -> floa
     for i in range(warmup):
         wl.step(i)
     torch.cuda.synchronize()
+    runs = []
     if use_graph:
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
@@ -272,30 +283,46 @@ def time_steps(wl, steps: int, warmup: int, use_graph: bool, calls=None) -> floa
         torch.cuda.synchronize()
         graph.replay()          # untimed: uploads the graph
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        graph.replay()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
+        for _ in range(repeats):
+            t0 = time.perf_counter()
+            graph.replay()
+            torch.cuda.synchronize()
+            runs.append((time.perf_counter() - t0) * 1e3 / steps)
     else:
-        t0 = time.perf_counter()
-        for i in range(steps):
-            wl.step(i)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    return (t1 - t0) * 1e3 / steps
+        for _ in range(repeats):
+            t0 = time.perf_counter()
+            for i in range(steps):
+                wl.step(i)
+            torch.cuda.synchronize()
+            runs.append((time.perf_counter() - t0) * 1e3 / steps)
+    return statistics.median(runs), runs
 
 
-def kernel_profile(wl, steps: int) -> dict:
-    """{kernel: (launches, total_ms)} over `steps` eager steps, from HIP events recorded by the
-    library around each of its kernel launches (on the stream they are launched on)."""
+def kernel_profile(wl, steps: int, calls=None) -> dict:
+    """{kernel: (launches, total_ms)} over `steps` eager steps, from HIP events that the library
+    attaches to each of its kernel dispatches (on the stream they are launched on)."""
     b, torch = wl.b, wl.torch
     torch.cuda.synchronize()
     b.modulora_profile_begin()
     for i in range(steps):
-        wl.step(i)
+        if calls is None:
+            wl.step(i)
+        else:
+            wl.step(i, calls)
     prof = b.modulora_profile_end(capacity=64)
     torch.cuda.synchronize()
     return prof
+
+
+def gemm_flops(cfg, name: str) -> float:
+    """Algorithmic flop of one launch of a product kernel with the frozen weight: the product
+    plus the rank-r up-projection it carries in its contraction."""
+    cout = cfg.N if "fwd" in name else cfg.K
+    return 2.0 * cfg.M * cfg.K * cfg.N + 2.0 * cfg.M * cfg.r * cout
+
+
+def is_product_kernel(name: str) -> bool:
+    return name.startswith(("gemm_fwd", "gemm_bwd", "f16_gemm")) and "fixup" not in name
 
 
 def roofline_of(cfg, prof: dict) -> dict:
@@ -303,26 +330,47 @@ def roofline_of(cfg, prof: dict) -> dict:
     name, (launches, total_ms) = max(prof.items(), key=lambda kv: kv[1][1])
     avg_s = total_ms / launches * 1e-3
     K, N, M, r = cfg.K, cfg.N, cfg.M, cfg.r
-    if "gemm_" in name and M > 16:
-        # one product with the frozen weight plus the rank-r up-projection it carries
-        cout = N if "fwd" in name else K
-        flops = 2.0 * M * K * N + 2.0 * M * r * cout
-        ach = flops / avg_s / 1e12
+    if is_product_kernel(name) and M > 16:
+        ach = gemm_flops(cfg, name) / avg_s / 1e12
         return {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
                 "avg_kernel_us": round(avg_s * 1e6, 2), "launches": launches}
     if name.startswith("gemm_") or name in ("stream_fwd", "stream_bwd"):
         nbytes = float(cfg.packed_weight_bytes)            # one pass over codes + scales + zeros
     elif name.startswith("stream_"):
-        # finish kernels: the partial tiles (not known here) -- report against the output only
         nbytes = 2.0 * M * max(K, N)
     else:
-        # adapter kernels stream the activations once
-        nbytes = 2.0 * M * (K if ("down" in name) else max(K, N))
+        nbytes = 2.0 * M * (K if ("down" in name) else max(K, N))   # adapter kernels stream the activations once
     ach = nbytes / avg_s / 1e9
     return {"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(ach / HBM_PEAK_GBPS, 4), "traffic": None, "avg_kernel_us": round(avg_s * 1e6, 2),
             "launches": launches}
+
+
+def product_kernels(cfg, prof: dict) -> dict:
+    """Per product kernel (forward, backward): average duration, TFLOP/s and fraction of the MFMA peak,
+    alone and with the second launch (`*_fixup`) that a split last round of tiles needs."""
+    out = {}
+    for name, (launches, total_ms) in prof.items():
+        if not is_product_kernel(name):
+            continue
+        us = total_ms / launches * 1e3
+        fix = [v for k, v in prof.items() if "fixup" in k and ("fwd" in k) == ("fwd" in name)]
+        fix_us = sum(t / n * 1e3 for n, t in fix)
+        fl = gemm_flops(cfg, name)
+        e = {"avg_us": round(us, 2), "TFLOPs": round(fl / us / 1e6, 1), "frac": round(fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
+        if fix_us:
+            e["fixup_us"] = round(fix_us, 2)
+            e["frac_with_fixup"] = round(fl / (us + fix_us) / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)
+        out[name] = e
+    return out
+
+
+def layer_roofline(cfg, ms: float) -> dict:
+    """The whole fwd+bwd layer against the MFMA peak: 4MKN + 6Mr(K+N) flop over the step time."""
+    ach = cfg.flops_fwd_bwd / (ms * 1e-3) / 1e12
+    return {"flops": cfg.flops_fwd_bwd, "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4)}
 
 
 def per_call_ms(prof: dict) -> dict:
@@ -332,42 +380,65 @@ def per_call_ms(prof: dict) -> dict:
     return out
 
 
-def cpu_baseline(host_layer, cfg, wl=None):
-    """The oracle, as it stands, timed on the host cores on one full step of the workload.
-    With `wl` (the GPU workload built from the same host layer) also returns the parity of the
-    GPU outputs against the oracle's: max |gpu - ref| / max |ref| per output tensor."""
+def host16(t):
+    """A device tensor of 16-bit floats as host bit patterns."""
+    import numpy as np
+    import torch
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def cpu_baseline(cfg, wl):
+    """The oracle, as it stands, timed on the host cores on the workload's own inputs (weight copy
+    0 and the activations, copied to the host), and the parity of the GPU outputs against it.
+    Where a full step is cheap (4MKN <= 1e11) the oracle computes all of it; otherwise it computes
+    Y and dX for ORACLE_ROWS sampled token rows and dA, dB in full (they need only rank-r
+    products), and the full-step time is extrapolated: rows' seconds x M / rows + adapter seconds
+    (the oracle's cost is linear in the token count)."""
     import numpy as np
     import oracle
 
-    L = host_layer
-    if "zeros_f16" in L:
-        return cpu_baseline_f16(L, cfg, wl)
-    args = (L["qweight"], L["scales"], L["zeros"], L["K"], L["N"], L["bits"], L["group"])
+    torch = wl.torch
+    if isinstance(wl, WorkloadF16):
+        return cpu_baseline_f16(cfg, wl)
+    K, N, M, r, s = cfg.K, cfg.N, cfg.M, cfg.r, float(cfg.lora_scale)
+    w0 = wl.weights[0]
+    args = (w0.qweight.cpu().numpy().view(np.uint32), host16(w0.scales), w0.zeros.cpu().numpy(), K, N, cfg.bits, cfg.group)
+    Xh, dYh = host16(wl.X), host16(wl.dY)
+    Ah, Bh = wl.A.cpu().numpy(), wl.B.cpu().numpy()
+    full = 4.0 * M * K * N <= 1e11 or M <= ORACLE_ROWS
+    rows = np.arange(M) if full else np.sort(np.random.default_rng(0).choice(M, ORACLE_ROWS, replace=False))
+    Xs, dYs = np.ascontiguousarray(Xh[rows]), np.ascontiguousarray(dYh[rows])
     t0 = time.perf_counter()
-    Yr, _ = oracle.fwd(*args, L["X"], L["A"], L["B"], L["lora_scale"])
-    dXr, _ = oracle.bwd_input(*args, L["dY"], L["A"], L["B"], L["lora_scale"])
-    dAr, dBr = oracle.bwd_lora(L["K"], L["N"], L["X"], L["dY"], L["A"], L["B"], L["lora_scale"])
-    dt = time.perf_counter() - t0
-    base = {"value": round(cfg.flops_fwd_bwd / dt / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds": round(dt, 3),
-            "sample": "one full step (fwd + bwd_input + bwd_lora) of %s, all %d tokens" % (cfg.name, cfg.M)}
-    if wl is None:
-        return base, None
-    wl.step(0)                      # weight copy 0 is the host layer's
-    wl.torch.cuda.synchronize()
-    rel = lambda got, ref: float(np.max(np.abs(got.double().cpu().numpy() - ref)) / np.max(np.abs(ref)))
-    What = wl.b.modulora_dequant(wl.weights[0]).cpu().view(wl.torch.int16).numpy().view(np.uint16)
-    parity = {"rel_max_err": {"Y": rel(wl.Y, Yr), "dX": rel(wl.dX, dXr), "dA": rel(wl.dA, dAr), "dB": rel(wl.dB, dBr)},
-              "bar": 2e-2, "dequant_bit_exact": bool(np.array_equal(What, oracle.dequant_bf16(*args)))}
-    parity["rel_max_err"] = {k: float("%.3g" % v) for k, v in parity["rel_max_err"].items()}
+    Yr, _ = oracle.fwd(*args, Xs, Ah, Bh, s)
+    dXr, _ = oracle.bwd_input(*args, dYs, Ah, Bh, s)
+    t_rows = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    dAr, dBr = oracle.bwd_lora(K, N, Xh, dYh, Ah, Bh, s)
+    t_lora = time.perf_counter() - t0
+    seconds = t_rows * (M / len(rows)) + t_lora
+    base = {"value": round(cfg.flops_fwd_bwd / seconds / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds_measured": round(t_rows + t_lora, 3), "seconds_full_step": round(seconds, 3),
+            "extrapolated": not full,
+            "sample": ("one full step (fwd + bwd_input + bwd_lora) of %s, all %d tokens" % (cfg.name, M)) if full else
+                      ("%s: Y and dX of %d sampled token rows (%.2f s) + dA, dB in full (%.2f s); full-step time "
+                       "extrapolated as rows' seconds x %d/%d + adapter seconds" % (cfg.name, len(rows), t_rows, t_lora, M, len(rows)))}
+    wl.step(0)                      # weight copy 0
+    torch.cuda.synchronize()
+    rows_t = torch.from_numpy(rows).cuda()
+    rel = lambda got, ref: float("%.3g" % (np.max(np.abs(got.double().cpu().numpy() - ref)) / np.max(np.abs(ref))))
+    What = host16(wl.b.modulora_dequant(w0))
+    parity = {"rel_max_err": {"Y": rel(wl.Y[rows_t], Yr), "dX": rel(wl.dX[rows_t], dXr), "dA": rel(wl.dA, dAr), "dB": rel(wl.dB, dBr)},
+              "rows_checked": int(len(rows)), "bar": 2e-2,
+              "dequant_bit_exact": bool(np.array_equal(What, oracle.dequant_bf16(*args)))}
     return base, parity
 
 
-def cpu_baseline_f16(L, cfg, wl):
+def cpu_baseline_f16(cfg, wl):
     """The paper-literal oracle (numpy float64) timed on one full step, and the GPU outputs against it."""
     import numpy as np
     from oracle import paper_literal as pl
 
+    L = wl.host_layer
     args = (L["qweight"], L["scales"], L["zeros_f16"], L["K"], L["N"], L["bits"], L["group"])
     t0 = time.perf_counter()
     Yr, _ = pl.fwd(*args, L["X"], L["A"], L["B"], L["lora_scale"], L["bias"])
@@ -375,7 +446,7 @@ def cpu_baseline_f16(L, cfg, wl):
     dAr, dBr = pl.bwd_lora(L["X"], L["dY"], L["A"], L["B"], L["lora_scale"])
     dt = time.perf_counter() - t0
     base = {"value": round(cfg.flops_fwd_bwd / dt / 1e12, 6), "unit": "TFLOP/s", "cores": os.cpu_count(),
-            "kind": "oracle", "seconds": round(dt, 3),
+            "kind": "oracle", "seconds_measured": round(dt, 3), "seconds_full_step": round(dt, 3), "extrapolated": False,
             "sample": "one full step (fwd + bwd_input + bwd_lora) of %s, all %d tokens, numpy float64" % (cfg.name, cfg.M)}
     wl.step(0)
     wl.torch.cuda.synchronize()
@@ -386,31 +457,73 @@ def cpu_baseline_f16(L, cfg, wl):
     return base, parity
 
 
+def read_rate(b, torch, nbytes: int, use_graph: bool) -> dict:
+    """GB/s of the library's plain hand-written streaming read (modulora_bench_read) over `nbytes`
+    bytes: the kernel alone (HIP events on its dispatch) and as a launch of its own replayed from
+    a HIP graph like the layer's calls.  The buffer rotates over >= 512 MB so that no read finds its
+    data in the last-level cache."""
+    n_copies = max(2, math.ceil(ROTATE_BYTES / nbytes))
+    bufs = [torch.randint(0, 1 << 30, (nbytes // 4,), dtype=torch.int32, device="cuda") for _ in range(n_copies)]
+    sink = torch.empty(b.BENCH_READ_SINK_WORDS, dtype=torch.int32, device="cuda")
+
+    class W:
+        pass
+    w = W()
+    w.torch, w.b = torch, b
+    w.step = lambda i, calls=None: b.modulora_bench_read(bufs[i % n_copies], sink)
+    ms, _ = time_steps(w, 20, 3, use_graph)
+    prof = kernel_profile(w, 20)
+    k_us = prof["bench_read"][1] / prof["bench_read"][0] * 1e3
+    return {"bytes": nbytes, "kernel_us": round(k_us, 2), "kernel_GBps": round(nbytes / k_us / 1e3, 1),
+            "call_us": round(ms * 1e3, 2), "call_GBps": round(nbytes / ms / 1e6, 1)}
+
+
+def small_m_block(synth, torch, use_graph: bool) -> dict:
+    """The second half of the metric: packed-weight HBM GB/s of the M <= 16 passes.  Per workload
+    and pass (fwd, bwd_input): the whole library call as replayed from a HIP graph (every launch
+    of the pass), the streaming kernel alone (HIP events on its dispatch), both as GB/s of the
+    packed weight (codes + scales + zeros, one pass) and as a fraction of the 8 TB/s peak, beside
+    the plain hand-written read of the same number of bytes measured the same two ways."""
+    from paper_2309_16119_amd import binding as b
+    rows = []
+    for name, M in (("c5_65b_up", 16), ("c5_65b_down", 16), ("c5_65b_attn", 16), ("c5_65b_up", 1), ("c5_65b_attn", 1)):
+        cfg = synth.CONFIGS[name].with_M(M)
+        wl = Workload(cfg)
+        W = float(cfg.packed_weight_bytes)
+        entry = {"workload": cfg.name, "packed_weight_bytes": int(W)}
+        for call, stream_kernel in (("fwd", "stream_fwd"), ("bwd_input", "stream_bwd")):
+            ms, _ = time_steps(wl, 20, 3, use_graph, calls=(call,))
+            prof = kernel_profile(wl, 20, calls=(call,))
+            us = {k: round(v[1] / v[0] * 1e3, 2) for k, v in prof.items()}
+            e = {"call_us": round(ms * 1e3, 2), "call_GBps": round(W / ms / 1e6, 1),
+                 "call_frac_of_peak": round(W / ms / 1e6 / HBM_PEAK_GBPS, 4), "kernels_us": us}
+            if stream_kernel in us:
+                e["stream_kernel_GBps"] = round(W / us[stream_kernel] / 1e3, 1)
+                e["stream_kernel_frac_of_peak"] = round(W / us[stream_kernel] / 1e3 / HBM_PEAK_GBPS, 4)
+            entry[call] = e
+        entry["plain_read_same_bytes"] = read_rate(b, torch, int(W) // 16 * 16, use_graph)
+        rows.append(entry)
+        del wl
+        torch.cuda.empty_cache()
+    return {"peak_GBps": HBM_PEAK_GBPS, "unit": "GB/s", "target_frac": 0.70, "workloads": rows,
+            "plain_read_2GiB": read_rate(b, torch, 1 << 31, use_graph)}
+
+
 def measured_context(cfg, torch) -> dict:
-    """Context numbers measured on this machine (not targets): a streaming read of 2 GiB by a plain
-    reduction kernel, and a dense bfloat16 torch.matmul of the workload's M x K x N."""
+    """Context measured on this machine (not a target): a dense bfloat16 torch.matmul of the workload's
+    M x K x N (resident bf16 weight, no dequantization, one product)."""
     out = {}
-    buf = torch.ones(1 << 29, dtype=torch.float32, device="cuda")        # 2 GiB
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    buf.sum(); torch.cuda.synchronize()
-    e0.record()
-    for _ in range(5):
-        buf.sum()
-    e1.record(); torch.cuda.synchronize()
-    out["stream_read_GBps"] = round(5 * buf.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
-    out["stream_read_kernel"] = "torch.sum over 2 GiB of float32"
-    del buf
-    torch.cuda.empty_cache()
     a = torch.randn((cfg.M, cfg.K), device="cuda").to(torch.bfloat16)
     w = torch.randn((cfg.N, cfg.K), device="cuda").to(torch.bfloat16)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for _ in range(3):
         torch.matmul(a, w.t())
     torch.cuda.synchronize()
     e0.record()
-    for _ in range(20):
+    for _ in range(10):
         torch.matmul(a, w.t())
     e1.record(); torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / 20
+    ms = e0.elapsed_time(e1) / 10
     out["dense_bf16_matmul_us"] = round(ms * 1e3, 2)
     out["dense_bf16_matmul_TFLOPs"] = round(2.0 * cfg.M * cfg.K * cfg.N / (ms * 1e-3) / 1e12, 1)
     out["dense_bf16_matmul_note"] = "torch.matmul [M,K] x [K,N] on a resident bf16 weight, same M, K, N (one product)"
@@ -493,12 +606,34 @@ def traffic_of(kernel_pattern: str, fetch: dict, write: dict):
             "copy_kernel_scale": {"FETCH_SIZE_per_GiB": round(cal_f, 1), "WRITE_SIZE_per_GiB": round(cal_w, 1)}}
 
 
+def workload_entry(cfg, wl, steps: int, use_graph: bool, torch, dense: bool = True) -> dict:
+    """One extra workload: median step time, layer-level and per-kernel roofline figures."""
+    ms, runs = time_steps(wl, steps, 3, use_graph)
+    prof = kernel_profile(wl, steps)
+    entry = {"workload": cfg.name, "shape": "d_in=%d d_out=%d %d-bit group %d M=%d r=%d" % (cfg.K, cfg.N, cfg.bits, cfg.group, cfg.M, cfg.r),
+             "ms_per_step": round(ms, 5), "tflops": round(cfg.flops_fwd_bwd / (ms * 1e-3) / 1e12, 3),
+             "roofline": roofline_of(cfg, prof), "kernel_us": per_call_ms(prof)}
+    if cfg.M > 16:
+        entry["layer_roofline"] = layer_roofline(cfg, ms)
+        entry["product_kernels"] = product_kernels(cfg, prof)
+        if dense:
+            entry["dense_bf16_matmul_TFLOPs"] = measured_context(cfg, torch)["dense_bf16_matmul_TFLOPs"]   # context only
+    return entry
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding). "
               "Run with --gpus 1." % args.gpus, file=sys.stderr)
         sys.exit(2)
+    if args.workload is None:
+        if args.variant == "f16":       # its oracle is numpy: a shape it finishes in seconds
+            args.workload = "c2_7b_attn"
+        else:
+            args.workload = HEADLINE[0]
+            if args.M is None:
+                args.M = HEADLINE[1]
     fetch = write = {}
     if args.variant == "f16":
         args.no_traffic = True          # the counter child runs replay the default variant
@@ -528,67 +663,63 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
-        wl = Workload(cfg, synth.make_layer(cfg))
+        wl = Workload(cfg)
         for i in range(args.warmup + args.steps):
             wl.step(i)
         torch.cuda.synchronize()
         return
 
     f16 = args.variant == "f16"
-    host_layer = synth.make_layer_f16(cfg) if f16 else synth.make_layer(cfg)
-    wl = WorkloadF16(cfg, host_layer) if f16 else Workload(cfg, host_layer)
-    ms = time_steps(wl, args.steps, args.warmup, use_graph)
+    wl = WorkloadF16(cfg, synth.make_layer_f16(cfg)) if f16 else Workload(cfg)
+    ms, runs = time_steps(wl, args.steps, args.warmup, use_graph)
     prof = kernel_profile(wl, args.steps)
     tflops = cfg.flops_fwd_bwd / (ms * 1e-3) / 1e12
 
     line = {
-        "metric": "fwd+bwd TFLOP/s per quantized LoRA layer",
+        "metric": "fwd+bwd TFLOP/s per quantized LoRA layer; packed-weight HBM GB/s at M<=16",
         "value": round(tflops, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if f16 else "bf16", "data": "synthetic",
         "config": {"workload": "%s%s: d_in=%d d_out=%d %d-bit group %d, M=%d tokens, r=%d, lora_scale=%g" % (
             cfg.name, " (paper-literal f16 variant: float zero point, bias)" if f16 else "", cfg.K, cfg.N, cfg.bits, cfg.group,
             cfg.M, cfg.r, cfg.lora_scale),
-            "weight_copies_rotated": wl.n_copies, "hip_graph": use_graph},
+            "weight_copies_rotated": wl.n_copies, "hip_graph": use_graph,
+            "timing": "median of %d replays of %d steps each" % (REPEATS, args.steps)},
+        "ms_per_step_replays": [round(x, 5) for x in runs],
         "roofline": roofline_of(cfg, prof),
         "kernel_us": per_call_ms(prof),
     }
+    if cfg.M > 16:
+        line["roofline"]["layer"] = layer_roofline(cfg, ms)
+        line["roofline"]["product_kernels"] = product_kernels(cfg, prof)
     if fetch and write:
         pat = rocprof_kernel_pattern(line["roofline"]["kernel"])
         line["roofline"]["traffic"] = traffic_of(pat % cfg.bits if "%d" in pat else pat, fetch, write)
-    line["per_call_us"] = {c: round(time_steps(wl, args.steps, 2, use_graph, calls=(c,)) * 1e3, 2)
+    line["per_call_us"] = {c: round(time_steps(wl, args.steps, 2, use_graph, calls=(c,))[0] * 1e3, 2)
                            for c in ("fwd", "bwd_input", "bwd_lora")}
-    line["measured_context"] = measured_context(cfg, torch)
+    if cfg.M > 16:
+        line["measured_context"] = measured_context(cfg, torch)
     if not args.no_cpu:
-        line["cpu_baseline"], line["parity_vs_oracle"] = cpu_baseline(host_layer, cfg, wl)
-    del wl, host_layer
+        line["cpu_baseline"], line["parity_vs_oracle"] = cpu_baseline(cfg, wl)
+    del wl
     torch.cuda.empty_cache()
 
     if f16:
-        args.no_extra = True            # the extra workloads belong to the default variant's line
+        args.no_extra = args.no_small = True     # those blocks belong to the default variant's line
+    if not args.no_small:
+        line["packed_weight_GBps"] = small_m_block(synth, torch, use_graph)
     if not args.no_extra:
         extra = []
-        others = [synth.CONFIGS["c3_7b_gate_up"], synth.CONFIGS["c5_65b_up"].with_M(4096),
-                  synth.CONFIGS["c5_65b_attn"].with_M(16), synth.CONFIGS["c5_65b_up"].with_M(16),
-                  synth.CONFIGS["c5_65b_attn"].with_M(1)]
+        steps_x = max(5, min(args.steps, 20))
+        # the other benchmark configurations, each at its own token count
+        others = [synth.CONFIGS["c2_7b_attn"], synth.CONFIGS["c3_7b_gate_up"], synth.CONFIGS["c3_7b_down"],
+                  synth.CONFIGS["c4_30b_attn"], synth.CONFIGS["c4_30b_up"], synth.CONFIGS["c4_30b_down"],
+                  synth.CONFIGS["c5_65b_up"].with_M(4096)]
         for ocfg in others:
             if ocfg.name == cfg.name:
                 continue
             w2 = Workload(ocfg)
-            steps = max(5, min(args.steps, 20))
-            ms2 = time_steps(w2, steps, 3, use_graph)
-            prof2 = kernel_profile(w2, steps)
-            entry = {"workload": ocfg.name, "ms_per_step": round(ms2, 5),
-                     "tflops": round(ocfg.flops_fwd_bwd / (ms2 * 1e-3) / 1e12, 3),
-                     "roofline": roofline_of(ocfg, prof2), "kernel_us": per_call_ms(prof2)}
-            if ocfg.M > 16:
-                ctx = measured_context(ocfg, torch)
-                entry["dense_bf16_matmul_TFLOPs"] = ctx["dense_bf16_matmul_TFLOPs"]     # context: one product, no dequantization
-            if ocfg.M <= 16:
-                gemm = {k: v for k, v in prof2.items() if k.startswith("gemm_") or k in ("stream_fwd", "stream_bwd")}
-                entry["packed_weight_GBps"] = {
-                    k: round(ocfg.packed_weight_bytes / (v[1] / v[0] * 1e-3) / 1e9, 1) for k, v in gemm.items()}
-            extra.append(entry)
+            extra.append(workload_entry(ocfg, w2, steps_x, use_graph, torch))
             del w2
             torch.cuda.empty_cache()
         # config 5 as a sweep: the three distinct matrices of a LLaMA-65B decoder layer at four
@@ -601,11 +732,15 @@ def main():
                 c5 = synth.CONFIGS[name].with_M(M5)
                 w5 = Workload(c5)
                 steps = 10 if M5 >= 256 else 20
-                ms5 = time_steps(w5, steps, 3, use_graph)
-                calls = {c: round(time_steps(w5, steps, 2, use_graph, calls=(c,)) * 1e3, 2)
+                ms5, _ = time_steps(w5, steps, 3, use_graph)
+                calls = {c: round(time_steps(w5, steps, 2, use_graph, calls=(c,), repeats=3)[0] * 1e3, 2)
                          for c in ("fwd", "bwd_input", "bwd_lora")}
-                row[name.replace("c5_65b_", "")] = {"step_us": round(ms5 * 1e3, 2), "calls_us": calls,
-                                                   "tflops": round(c5.flops_fwd_bwd / (ms5 * 1e-3) / 1e12, 2)}
+                e5 = {"step_us": round(ms5 * 1e3, 2), "calls_us": calls,
+                      "tflops": round(c5.flops_fwd_bwd / (ms5 * 1e-3) / 1e12, 2)}
+                if M5 >= 256:
+                    e5["layer_frac_of_mfma_peak"] = layer_roofline(c5, ms5)["frac"]
+                    e5["product_kernels"] = product_kernels(c5, kernel_profile(w5, 5))
+                row[name.replace("c5_65b_", "")] = e5
                 layer_ms += mult * ms5
                 del w5
                 torch.cuda.empty_cache()
@@ -617,30 +752,23 @@ def main():
         for M_dec in (2048, 128):
             dl = DecoderLayerWorkload(M_dec)
             steps = 5
-            ms3 = time_steps(dl, steps, 2, use_graph)
+            ms3, _ = time_steps(dl, steps, 2, use_graph)
             prof3 = kernel_profile(dl, steps)
             by_family = {}
             for name, (launches, total_ms) in prof3.items():
                 by_family[name] = round(total_ms / steps * 1e3, 1)       # microseconds per step, all launches
             extra.append({"workload": "decoder_layer_65b_M%d: 7 linears fwd+bwd + fused AdamW, 3-bit group 128 r=8" % M_dec,
                           "ms_per_step": round(ms3, 5), "tflops": round(dl.flops / (ms3 * 1e-3) / 1e12, 3),
+                          "layer_frac_of_mfma_peak": round(dl.flops / (ms3 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                           "tokens_per_s": round(M_dec / (ms3 * 1e-3), 1), "us_per_step_by_kernel": by_family})
             del dl
             torch.cuda.empty_cache()
-        # the paper-literal variant (float zero point, binary16, bias) on the headline shape and a large one
+        # the paper-literal variant (float zero point, binary16, bias) on a mid-size and a large shape
         for cfg_h in (synth.CONFIGS["c2_7b_attn"], synth.CONFIGS["c5_65b_attn"].with_M(4096)):
             wh = WorkloadF16(cfg_h)
-            msh = time_steps(wh, steps, args.warmup, use_graph)
-            profh = kernel_profile(wh, min(steps, 10))
-            ush = per_call_ms(profh)
-            gname = "f16_gemm_fwd"
-            flops_g = 2.0 * cfg_h.M * cfg_h.K * cfg_h.N
-            ach = flops_g / (ush[gname] * 1e-6) / 1e12
-            extra.append({"workload": "paper-literal f16 variant, %s" % cfg_h.name, "ms_per_step": round(msh, 5),
-                          "tflops": round(cfg_h.flops_fwd_bwd / (msh * 1e-3) / 1e12, 3), "kernel_us": ush,
-                          "roofline": {"kernel": gname, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                                       "unit": "TFLOP/s", "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                                       "avg_kernel_us": ush[gname], "launches": profh[gname][0]}})
+            e = workload_entry(cfg_h, wh, steps_x, use_graph, torch, dense=False)
+            e["workload"] = "paper-literal f16 variant, %s" % cfg_h.name
+            extra.append(e)
             del wh
             torch.cuda.empty_cache()
         # the round-to-nearest quantizer + packer on the largest layer shape

@@ -282,6 +282,19 @@ typedef struct {
 int modulora_profile_begin(void);
 int modulora_profile_end(modulora_kernel_time *out, int32_t capacity, int32_t *count);
 
+/*
+ * Benchmark hook (no operation of the paper): one plain streaming read of `bytes` bytes of device
+ * memory at `buf` (16-byte aligned, bytes a positive multiple of 16) by a hand-written kernel
+ * with 16-byte non-temporal loads -- the measured read rate that the packed-weight GB/s of the
+ * M <= 16 streaming kernels is reported beside.  `sink` is a device buffer of
+ * MODULORA_BENCH_READ_SINK_WORDS uint32 that receives one checksum word per workgroup (so the
+ * reads cannot be optimized away).  Enqueued on `stream`; timed by the caller or through
+ * modulora_profile_begin/_end under the name "bench_read".
+ * Errors: MODULORA_ERR_NULL, MODULORA_ERR_ALIGN, MODULORA_ERR_SHAPE, MODULORA_ERR_HIP.
+ */
+#define MODULORA_BENCH_READ_SINK_WORDS 2048
+int modulora_bench_read(const void *buf, size_t bytes, uint32_t *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

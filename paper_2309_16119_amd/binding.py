@@ -88,6 +88,8 @@ def _load() -> ctypes.CDLL:
     lib.modulora_quantize_rtn.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.modulora_adamw.restype = ctypes.c_int
     lib.modulora_adamw.argtypes = [vp, vp, vp, vp, sz, f32, f32, f32, f32, f32, i32, vp]
+    lib.modulora_bench_read.restype = ctypes.c_int
+    lib.modulora_bench_read.argtypes = [vp, sz, vp, vp]
     lib.modulora_profile_begin.restype = ctypes.c_int
     lib.modulora_profile_begin.argtypes = []
     lib.modulora_profile_end.restype = ctypes.c_int
@@ -386,6 +388,19 @@ def modulora_adamw(param: torch.Tensor, grad: torch.Tensor, exp_avg: torch.Tenso
         assert t.dtype == torch.float32 and t.numel() == n and t.device == param.device
     _check(lib.modulora_adamw(_ptr(param), _ptr(grad), _ptr(exp_avg), _ptr(exp_avg_sq), n, float(lr), float(beta1),
                               float(beta2), float(eps), float(weight_decay), int(step), _stream()), "modulora_adamw")
+
+
+BENCH_READ_SINK_WORDS = 2048
+
+
+def modulora_bench_read(buf: torch.Tensor, sink: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One plain streaming read of `buf` by the library's hand-written read kernel (benchmark hook)."""
+    if sink is None:
+        sink = torch.empty(BENCH_READ_SINK_WORDS, dtype=torch.int32, device=buf.device)
+    assert sink.numel() >= BENCH_READ_SINK_WORDS and sink.dtype == torch.int32
+    _check(lib.modulora_bench_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), _stream()),
+           "modulora_bench_read")
+    return sink
 
 
 def modulora_profile_begin() -> None:

@@ -18,7 +18,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libmodulora.so")
 
-SOURCES = ["api.hip", "dequant_kernel.hip", "gemm_tile.hip", "gemm_big.hip", "gemm_mid.hip", "lora_kernels.hip", "smallm.hip", "optim.hip", "quantize.hip", "f16_path.hip"]
+SOURCES = ["api.hip", "dequant_kernel.hip", "gemm_tile.hip", "gemm_big.hip", "gemm_mid.hip", "lora_kernels.hip", "smallm.hip", "optim.hip", "quantize.hip", "f16_path.hip", "bench_hooks.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

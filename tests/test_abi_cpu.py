@@ -186,3 +186,13 @@ def test_f16_workspace_query_and_dequant_rejections():
     assert bl(4096, 4100, 16, 8, 2.0, FAKE, FAKE, FAKE, FAKE, 0, 0, FAKE, FAKE, 0, FAKE, 1 << 30, None) == 2
     assert bl(4096, 4096, 16, 8, 2.0, FAKE, 0, FAKE, FAKE, 0, 0, FAKE, FAKE, 0, FAKE, 1 << 30, None) == 1
     assert bl(4096, 4096, 16, 8, 2.0, FAKE, FAKE, FAKE, FAKE, 0, 0, FAKE, FAKE, 0, 0, 0, None) == 7
+
+
+def test_bench_read_hook_rejections():
+    f = b.lib.modulora_bench_read
+    assert f(0, 1024, FAKE, None) == 1
+    assert f(FAKE, 1024, 0, None) == 1
+    assert f(ODD, 1024, FAKE, None) == 5
+    assert f(FAKE, 0, FAKE, None) == 2
+    assert f(FAKE, 1000, FAKE, None) == 2        # not a multiple of 16
+
