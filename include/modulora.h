@@ -127,6 +127,28 @@ int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M,
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * modulora_fwd for callers that cannot provide scratch memory or allocate any: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results (bit for bit) and error codes as modulora_fwd, minus the workspace: the
+ * scratch is a static device array of MODULORA_STATIC_SCRATCH_BYTES inside the library (each GPU
+ * the library runs on holds its own copy from the first call on that GPU until the process
+ * ends).  The call allocates and frees nothing, on the host side of the GPU or through any
+ * library.  A layer / M / r whose forward pass needs more scratch than that returns
+ * MODULORA_ERR_WORKSPACE (the M <= 16 streaming pass of every benchmark layer needs < 8 MiB; the
+ * tile kernels need about 2 (M + d_out) (3 r + 16) bytes; partial tiles of a split last round of
+ * 256 x 256 tiles are used only when they also fit, otherwise those tiles run whole).
+ * All calls on one GPU share that GPU's array and it keeps the last call's contents (nothing in
+ * it needs clearing: every region is written before it is read): two calls that overlap in
+ * time on one GPU -- different streams, or different host threads -- race; order them on one
+ * stream.  The first call on a GPU looks the array's address up (hipGetSymbolAddress) and must
+ * not be made while a graph is being captured; later calls may be.
+ */
+#define MODULORA_STATIC_SCRATCH_BYTES (16u << 20)
+int modulora_fwd_static(const modulora_qweight *w, const uint16_t *X, int32_t M,
+                        const float *A, const float *B, int32_t r, float lora_scale,
+                        uint16_t *Y, float *XA, void *stream);
+
+/*
  * Backward with respect to the input (Figure 1 LPLinear.backward: the weight is
  * re-materialized, grad_input = grad_output What; plus the adapter path of
  * Section 3.1.1, d y~/d y = What^T + B A^T in the paper's naming):

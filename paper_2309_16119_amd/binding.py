@@ -69,6 +69,8 @@ def _load() -> ctypes.CDLL:
     lib.modulora_dequant.argtypes = [qp, vp, vp]
     lib.modulora_fwd.restype = ctypes.c_int
     lib.modulora_fwd.argtypes = [qp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]
+    lib.modulora_fwd_static.restype = ctypes.c_int
+    lib.modulora_fwd_static.argtypes = [qp, vp, i32, vp, vp, i32, f32, vp, vp, vp]
     lib.modulora_bwd_input.restype = ctypes.c_int
     lib.modulora_bwd_input.argtypes = [qp, vp, i32, vp, vp, i32, f32, vp, vp, vp, sz, vp]
     lib.modulora_bwd_lora.restype = ctypes.c_int
@@ -210,6 +212,23 @@ def modulora_fwd(w: QWeight, X: torch.Tensor, A: Optional[torch.Tensor], B: Opti
     st = w.c_struct()
     _check(lib.modulora_fwd(ctypes.byref(st), _ptr(X), M, _ptr(A), _ptr(B), r, float(lora_scale),
                             _ptr(Y), _ptr(XA), _ptr(ws), nbytes, _stream()), "modulora_fwd")
+    return Y, XA
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def modulora_fwd_static(w: QWeight, X: torch.Tensor, A: Optional[torch.Tensor], B: Optional[torch.Tensor],
+                        lora_scale: float, Y: torch.Tensor, XA: Optional[torch.Tensor] = None):
+    """modulora_fwd on the library's own static scratch: the caller passes every buffer (Y, and XA
+    if wanted), this wrapper allocates nothing either."""
+    assert X.dtype == torch.bfloat16 and X.dim() == 2 and X.shape[1] == w.d_in
+    M = X.shape[0]
+    r = 0 if A is None else A.shape[1]
+    assert Y.dtype == torch.bfloat16 and tuple(Y.shape) == (M, w.d_out)
+    st = w.c_struct()
+    _check(lib.modulora_fwd_static(ctypes.byref(st), _ptr(X), M, _ptr(A), _ptr(B), r, float(lora_scale),
+                                   _ptr(Y), _ptr(XA), _stream()), "modulora_fwd_static")
     return Y, XA
 
 

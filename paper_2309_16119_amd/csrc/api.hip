@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <cmath>
 #include <vector>
@@ -62,6 +63,7 @@ mlr::LayerView view_of(const modulora_qweight *w) {
 // Workspace carving, shared by the size query and the entry points.
 struct WsLayout {
     size_t act_ext, w_ext, p0, p1, gpart, gemm_part, dpart, total;
+    size_t gemm_part_bytes;      // size of the region at gemm_part
 };
 
 WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
@@ -71,6 +73,7 @@ WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     const size_t small = M <= 16 ? mlr::smallm_ws_bytes(K, N, r) : 0;
     // fp32 partial tiles of the split contraction of the 256 x 256 kernel (also when r == 0)
     const size_t part = align256(mlr::gemm_partial_bytes(M, K, N));
+    l.gemm_part_bytes = part;
     if (r <= 0) {
         l.gemm_part = 0;
         l.total = small > part ? small : part;
@@ -90,6 +93,34 @@ WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     return l;
 }
 
+// What modulora_fwd alone touches for this layer (no backward, no adapter-gradient regions), for
+// a scratch buffer of `avail` bytes: the M <= 16 stream's exact need, or the adapter operands of
+// the tile kernels plus -- only if they still fit -- the partial tiles of a split contraction
+// (without them the 256 x 256 kernel runs whole tiles).
+WsLayout ws_layout_fwd(const mlr::LayerView &v, int32_t M, int32_t r, size_t avail) {
+    WsLayout l{};
+    if (mlr::smallm_fwd_supported(v, M)) {
+        l.total = mlr::smallm_fwd_ws_bytes(v, r);
+        return l;
+    }
+    size_t off = 0;
+    if (r > 0) {
+        const size_t RE = (size_t)mlr::lora_ext_len(r);
+        l.act_ext = off; off += align256((size_t)M * RE * 2);
+        l.w_ext = off;   off += align256((size_t)v.N * RE * 2);
+        l.p0 = off;      off += align256((size_t)M * r * 4);
+        l.dpart = off;   off += align256(mlr::lora_down_partial_bytes(M, v.K, v.N, r));
+    }
+    const size_t part = align256(mlr::big_plan(M, v.K, v.N).partial_bytes());
+    l.gemm_part = off;
+    if (off + part <= avail) {
+        l.gemm_part_bytes = part;
+        off += part;
+    }
+    l.total = off;
+    return l;
+}
+
 int check_workspace(const WsLayout &l, const void *ws, size_t bytes) {
     if (l.total == 0) return MODULORA_OK;
     if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || bytes < l.total) return MODULORA_ERR_WORKSPACE;
@@ -97,6 +128,84 @@ int check_workspace(const WsLayout &l, const void *ws, size_t bytes) {
 }
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? MODULORA_OK : MODULORA_ERR_HIP; }
+
+// ---- forward: validation and body, shared by modulora_fwd and modulora_fwd_static ----------
+int check_fwd_args(const modulora_qweight *w, const uint16_t *X, int32_t M, const float *A, const float *B, int32_t r,
+                   const uint16_t *Y, const float *XA) {
+    int s = check_layer(w);
+    if (s != MODULORA_OK) return s;
+    if (!X || !Y) return MODULORA_ERR_NULL;
+    if (M < 1 || M > kMaxTokens) return MODULORA_ERR_SHAPE;
+    if (!aligned16(X) || !aligned16(Y) || (XA && !aligned16(XA))) return MODULORA_ERR_ALIGN;
+    return check_rank(r, A, B, true);
+}
+
+int run_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M, const float *A, const float *B, int32_t r,
+            float lora_scale, uint16_t *Y, float *XA, char *ws, const WsLayout &l, hipStream_t st) {
+    if (mlr::smallm_fwd_supported(view_of(w), M)) {
+        mlr::SmallArgs sa{};
+        sa.w = view_of(w);
+        sa.act = X; sa.M = M; sa.out = Y;
+        sa.A = A; sa.B = B; sa.r = r; sa.lora_scale = lora_scale;
+        sa.P_out = XA; sa.ws = ws;
+        return hip_status(mlr::launch_smallm_fwd(sa, st));
+    }
+    mlr::GemmArgs g{};
+    g.w = view_of(w);
+    g.backward = false;
+    g.act = X;
+    g.M = M;
+    g.out = Y;
+    g.partials = l.gemm_part_bytes ? reinterpret_cast<float *>(ws + l.gemm_part) : nullptr;
+    g.partials_bytes = l.gemm_part_bytes;
+    if (r > 0) {
+        mlr::DownArgs d{};
+        d.act = X; d.M = M; d.C = w->d_in; d.r = r;
+        d.Fm = A; d.f_is_A = true;
+        d.P = XA ? XA : reinterpret_cast<float *>(ws + l.p0);
+        d.lora_scale = lora_scale;
+        d.act_ext = reinterpret_cast<uint16_t *>(ws + l.act_ext);
+        d.RE = mlr::lora_ext_len(r);
+        d.w_ext = reinterpret_cast<uint16_t *>(ws + l.w_ext);
+        d.Wsrc = B; d.w_from_A = false; d.Cw = w->d_out;
+        d.partials = reinterpret_cast<float *>(ws + l.dpart);
+        const int s = hip_status(mlr::launch_lora_down(d, st));
+        if (s != MODULORA_OK) return s;
+        g.act_ext = d.act_ext;
+        g.w_ext = d.w_ext;
+        g.RE = d.RE;
+    }
+    return hip_status(mlr::launch_gemm(g, st));
+}
+
+// ---- the library's own scratch for modulora_fwd_static ---------------------------------------
+// One array per GPU, in that GPU's memory from the moment the code object is loaded there until
+// the process ends.  In host code the array's name is only a handle: the device address comes
+// from hipGetSymbolAddress, once per device, and only that pointer is ever given to kernels.
+constexpr size_t kStaticScratchBytes = MODULORA_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[MODULORA_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+int static_scratch(char **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return MODULORA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return MODULORA_ERR_HIP;
+        if ((reinterpret_cast<uintptr_t>(p) & 255u) != 0) return MODULORA_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<char *>(g_scratch_ptr[dev]);
+    return MODULORA_OK;
+}
 
 // ---- profiling state ------------------------------------------------------------
 struct ProfRecord {
@@ -161,49 +270,22 @@ int modulora_dequant(const modulora_qweight *w, uint16_t *What_bf16, void *strea
 int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M, const float *A, const float *B,
                  int32_t r, float lora_scale, uint16_t *Y, float *XA, void *workspace,
                  size_t workspace_bytes, void *stream) {
-    int s = check_layer(w);
+    int s = check_fwd_args(w, X, M, A, B, r, Y, XA);
     if (s != MODULORA_OK) return s;
-    if (!X || !Y) return MODULORA_ERR_NULL;
-    if (M < 1 || M > kMaxTokens) return MODULORA_ERR_SHAPE;
-    if (!aligned16(X) || !aligned16(Y) || (XA && !aligned16(XA))) return MODULORA_ERR_ALIGN;
-    if ((s = check_rank(r, A, B, true)) != MODULORA_OK) return s;
     const WsLayout l = ws_layout(w->d_in, w->d_out, M, r);
     if ((s = check_workspace(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
+    return run_fwd(w, X, M, A, B, r, lora_scale, Y, XA, static_cast<char *>(workspace), l, static_cast<hipStream_t>(stream));
+}
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    char *ws = static_cast<char *>(workspace);
-    if (mlr::smallm_fwd_supported(view_of(w), M)) {
-        mlr::SmallArgs sa{};
-        sa.w = view_of(w);
-        sa.act = X; sa.M = M; sa.out = Y;
-        sa.A = A; sa.B = B; sa.r = r; sa.lora_scale = lora_scale;
-        sa.P_out = XA; sa.ws = ws;
-        return hip_status(mlr::launch_smallm_fwd(sa, st));
-    }
-    mlr::GemmArgs g{};
-    g.w = view_of(w);
-    g.backward = false;
-    g.act = X;
-    g.M = M;
-    g.out = Y;
-    g.partials = reinterpret_cast<float *>(ws + l.gemm_part);
-    if (r > 0) {
-        mlr::DownArgs d{};
-        d.act = X; d.M = M; d.C = w->d_in; d.r = r;
-        d.Fm = A; d.f_is_A = true;
-        d.P = XA ? XA : reinterpret_cast<float *>(ws + l.p0);
-        d.lora_scale = lora_scale;
-        d.act_ext = reinterpret_cast<uint16_t *>(ws + l.act_ext);
-        d.RE = mlr::lora_ext_len(r);
-        d.w_ext = reinterpret_cast<uint16_t *>(ws + l.w_ext);
-        d.Wsrc = B; d.w_from_A = false; d.Cw = w->d_out;
-        d.partials = reinterpret_cast<float *>(ws + l.dpart);
-        if ((s = hip_status(mlr::launch_lora_down(d, st))) != MODULORA_OK) return s;
-        g.act_ext = d.act_ext;
-        g.w_ext = d.w_ext;
-        g.RE = d.RE;
-    }
-    return hip_status(mlr::launch_gemm(g, st));
+int modulora_fwd_static(const modulora_qweight *w, const uint16_t *X, int32_t M, const float *A, const float *B,
+                        int32_t r, float lora_scale, uint16_t *Y, float *XA, void *stream) {
+    int s = check_fwd_args(w, X, M, A, B, r, Y, XA);
+    if (s != MODULORA_OK) return s;
+    const WsLayout l = ws_layout_fwd(view_of(w), M, r, kStaticScratchBytes);
+    if (l.total > kStaticScratchBytes) return MODULORA_ERR_WORKSPACE;     // beyond the library's scratch
+    char *ws = nullptr;
+    if ((s = static_scratch(&ws)) != MODULORA_OK) return s;
+    return run_fwd(w, X, M, A, B, r, lora_scale, Y, XA, ws, l, static_cast<hipStream_t>(stream));
 }
 
 int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M, const float *A,
@@ -235,6 +317,7 @@ int modulora_bwd_input(const modulora_qweight *w, const uint16_t *dY, int32_t M,
     g.M = M;
     g.out = dX;
     g.partials = reinterpret_cast<float *>(ws + l.gemm_part);
+    g.partials_bytes = l.gemm_part_bytes;
     if (r > 0) {
         mlr::DownArgs d{};
         d.act = dY; d.M = M; d.C = w->d_out; d.r = r;

@@ -600,7 +600,8 @@ template <int BITS, bool BWD, bool F16 = false>
 static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
     const GemmDev d = make_gemm_dev(a, big::MT, big::CT);
     BigPlan plan = big_plan(a.M, BWD ? a.w.N : a.w.K, BWD ? a.w.K : a.w.N);
-    if (a.partials == nullptr) plan.split = 1;   // no scratch for partial tiles: whole tiles only
+    // no (or too little) scratch for partial tiles: whole tiles only
+    if (a.partials == nullptr || a.partials_bytes < plan.partial_bytes()) plan.split = 1;
     const int whole = plan.split > 1 ? plan.full : plan.full + plan.tail;
     const int slices = plan.split > 1 ? plan.tail * plan.split : 0;
     const int blocks = ((whole + 7) / 8 + (slices + 7) / 8) * 8;

@@ -54,7 +54,8 @@ struct GemmArgs {
     const uint16_t *act_ext;  // bf16 [M][RE]    (NULL when RE == 0)
     const uint16_t *w_ext;    // bf16 [Cout][RE] (NULL when RE == 0)
     int RE;                   // multiple of 16
-    float *partials;          // scratch of gemm_partial_bytes() bytes (split contraction)
+    float *partials;          // scratch for the partial tiles of a split contraction, or NULL
+    size_t partials_bytes;    // its size: a plan that needs more runs whole tiles only
     // The layer in the paper's own storage convention (launch_gemm_mid_f16 only): binary16
     // activations and outputs, binary16 zero points that are added (w.zeros unused), an optional
     // binary16 bias (forward), and the adapter term s P F in the epilogue instead of the extended
@@ -221,7 +222,8 @@ struct SmallArgs {
 };
 bool smallm_fwd_supported(const LayerView &w, int M);
 bool smallm_bwd_supported(const LayerView &w, int M);
-size_t smallm_ws_bytes(int K, int N, int r);
+size_t smallm_ws_bytes(int K, int N, int r);              // enough for both passes of any layer of this shape
+size_t smallm_fwd_ws_bytes(const LayerView &w, int r);    // what launch_smallm_fwd touches for this layer
 hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream);
 hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream);
 

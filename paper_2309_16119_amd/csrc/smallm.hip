@@ -1041,6 +1041,13 @@ SmallWs small_ws(int K, int N, int r) {
 
 size_t smallm_ws_bytes(int K, int N, int r) { return small_ws(K, N, r).total; }
 
+size_t smallm_fwd_ws_bytes(const LayerView &w, int r) {
+    const int ksplit = pick_ksplit(w.K, w.N, w.group);
+    if (ksplit < 1) return 0;
+    // the projection partials, then ksplit partial tiles [16][N]
+    return small_ws(w.K, w.N, r).yacc + (((size_t)ksplit * 16 * w.N * 4 + 255) & ~(size_t)255);
+}
+
 template <int BITS, bool SPG1>
 static hipError_t launch_fwd_bits(const SmallFwdDev &d, int col_blocks, size_t lds_bytes, hipStream_t stream) {
     auto kern = smallm_fwd_kernel<BITS, SPG1>;

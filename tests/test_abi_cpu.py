@@ -196,3 +196,17 @@ def test_bench_read_hook_rejections():
     assert f(FAKE, 0, FAKE, None) == 2
     assert f(FAKE, 1000, FAKE, None) == 2        # not a multiple of 16
 
+
+def test_static_scratch_forward_rejections():
+    """Host-side checks of modulora_fwd_static: the same argument errors as modulora_fwd, and a
+    request beyond the library's static scratch is refused before anything touches the GPU."""
+    def f(w, X=FAKE, M=16, A=FAKE, B=FAKE, r=8, Y=FAKE, XA=0):
+        return b.lib.modulora_fwd_static(ctypes.byref(w), X, M, A, B, r, 2.0, Y, XA, None)
+    assert f(qw(bits=5)) == 3
+    assert f(qw(), X=0) == 1
+    assert f(qw(), X=ODD) == 5
+    assert f(qw(), r=65) == 6
+    assert f(qw(), M=0) == 2
+    # 30000 tokens at rank 64 need about 19 MB of adapter operands: more than the 16 MiB array
+    assert f(qw(), M=30000, r=64) == 7
+    assert b.STATIC_SCRATCH_BYTES == 16 << 20
