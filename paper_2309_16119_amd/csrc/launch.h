@@ -123,26 +123,60 @@ struct DownArgs {
     const float *Wsrc;
     bool w_from_A;
     int Cw;
-    float *partials;      // scratch of lora_down_partial_bytes() bytes (few rows: split contraction)
+    float *partials;      // scratch of lora_down_partial_bytes() bytes (split contraction)
 };
-// Few rows give few workgroups: the contraction is then also split over `lora_down_split()`
-// workgroups per 16 rows, whose partial tiles a second small kernel adds.
-inline int lora_down_split(int M, int C) {
-    const int row_blocks = (M + 15) / 16;
-    if (row_blocks * 16 >= 1024) return 1;            // 16 waves per workgroup fill the chip already
-    int split = (2048 + row_blocks * 16 - 1) / (row_blocks * 16);
-    const int by_depth = C / (32 * 16 * 2);           // at least 2 steps of 32 per wave
-    if (split > by_depth) split = by_depth;
-    if (split > 16) split = 16;
-    return split < 2 ? 1 : split;
+// How launch_lora_down covers act [M][C]: a workgroup of `nwaves` waves owns `rowt` tiles of 16 rows
+// (they share every factor operand: the fp32 factor is fetched and split once per workgroup and
+// step, not once per 16 rows) and one of `split` slices of the contraction, which its waves
+// divide again.  With split > 1 the slices leave partial tiles that a second small kernel adds.
+// Many tokens take rowt = 4 and as many slices as give the chip about two workgroups per compute
+// unit; few tokens keep one tile per workgroup and split only a deep contraction.
+struct DownPlan {
+    int rowt, nwaves, split;
+};
+inline DownPlan lora_down_plan(int M, int C, int r) {
+    DownPlan p;
+    const int rg = (r + 15) / 16;
+    const int tiles16 = (M + 15) / 16;
+    // (a contraction under ~6000 is too short to split further: there one tile per workgroup and no
+    // second launch is quicker)
+    p.rowt = (tiles16 >= 64 && rg <= 2 && C >= 6144) ? 4 : 1;
+    const int row_blocks = (tiles16 + p.rowt - 1) / p.rowt;
+    const int steps = (C + 31) / 32;
+    if (p.rowt == 4) {
+        p.nwaves = rg == 1 ? 8 : 4;                      // at most 32 partial tiles meet in a workgroup's LDS
+        int split = (512 + row_blocks - 1) / row_blocks;
+        const int by_depth = steps / (2 * p.nwaves);     // at least 2 steps of 32 per wave
+        if (split > by_depth) split = by_depth;
+        if (split > 16) split = 16;
+        p.split = split < 2 ? 1 : split;
+        return p;
+    }
+    int nwaves = 4;
+    while (nwaves < 16 && row_blocks * nwaves < 2048 && nwaves * 2 * rg <= 32) nwaves *= 2;
+    p.nwaves = nwaves;
+    p.split = 1;
+    if (row_blocks * 16 < 1024) {                        // 16 waves per workgroup do not fill the chip yet
+        int split = (2048 + row_blocks * 16 - 1) / (row_blocks * 16);
+        const int by_depth = C / (32 * 16 * 2);
+        if (split > by_depth) split = by_depth;
+        if (split > 16) split = 16;
+        if (split >= 2) p.split = split;
+    }
+    return p;
 }
 inline size_t lora_down_partial_bytes(int M, int K, int N, int r) {
     if (r <= 0) return 0;
-    const int sk = lora_down_split(M, K), sn = lora_down_split(M, N);
-    const int split = sk > sn ? sk : sn;
-    if (split <= 1) return 0;
-    const size_t rg = (size_t)(r + 15) / 16;
-    return (size_t)split * (size_t)((M + 15) / 16) * 256u * rg * sizeof(float);
+    size_t most = 0;
+    for (int C : {K, N}) {
+        const DownPlan p = lora_down_plan(M, C, r);
+        if (p.split <= 1) continue;
+        const size_t rg = (size_t)(r + 15) / 16;
+        const size_t row_blocks = (size_t)(((M + 15) / 16) + p.rowt - 1) / p.rowt;
+        const size_t b = (size_t)p.split * row_blocks * (size_t)p.rowt * 256u * rg * sizeof(float);
+        if (b > most) most = b;
+    }
+    return most;
 }
 hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream);
 

@@ -36,32 +36,48 @@ __device__ __forceinline__ bf16x8 regs_to_bf16x8(const uint32_t r[4]) {
     return v;
 }
 
+// Eight consecutive elements (one 16-byte store) of the weight-side extension w_ext [Cw][RE]:
+// row c holds the segments (hi, lo, hi) of the r factor values of that row and zero padding.
+// Unit u = c * (RE / 8) + chunk, consecutive threads take consecutive units: the stores are
+// contiguous, and the loads of a wave touch a few dozen adjacent rows c (from B [r][Cw]: runs of
+// adjacent floats in up to eight rows j; from A [Cw][r]: adjacent floats of a row).
+__device__ __forceinline__ void write_w_ext_unit(const DownArgs &a, size_t u) {
+    const int r = a.r, per_row = a.RE >> 3;
+    const int c = (int)(u / per_row), e0 = (int)(u % per_row) * 8;
+    float src[8];
+    int seg[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        const int e = e0 + q;
+        seg[q] = e / r;
+        const int j = e - seg[q] * r;
+        src[q] = seg[q] < 3 ? (a.w_from_A ? a.Wsrc[(size_t)c * r + j] : a.Wsrc[(size_t)j * a.Cw + c]) : 0.f;
+    }
+    uint32_t o[4];
+#pragma unroll
+    for (int q = 0; q < 8; q += 2) {
+        const uint32_t lo16 = seg[q] < 3 ? split_part(src[q], seg[q] == 1) : 0u;
+        const uint32_t hi16 = seg[q + 1] < 3 ? split_part(src[q + 1], seg[q + 1] == 1) : 0u;
+        o[q >> 1] = lo16 | (hi16 << 16);
+    }
+    *reinterpret_cast<uint4 *>(a.w_ext + u * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 // ROWT: 16-row tiles per workgroup (they share every factor operand); UNR: steps whose loads
 // are issued together before any of them is used.
 template <int RG, int ROWT, bool F_IS_A>
 __global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blocks, int split) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];   // [waves][ROWT][RG][256] partial tiles, then Ps
-    constexpr int UNR = RG == 1 ? 4 : (RG == 2 ? 2 : 1);
+    constexpr int UNR = ROWT > 1 ? 2 : (RG == 1 ? 4 : (RG == 2 ? 2 : 1));
     constexpr int ROWS = 16 * ROWT;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const int r = a.r;
 
     if ((int)blockIdx.x >= row_blocks) {
         if (blockIdx.y != 0) return;
-        // weight-side extension: w_ext[c][e]
-        const size_t total = (size_t)a.Cw * a.RE;
-        size_t idx = (size_t)(blockIdx.x - row_blocks) * nthreads + tid;
-        const size_t stride = (size_t)(gridDim.x - row_blocks) * nthreads;
-        for (; idx < total; idx += stride) {
-            const int c = (int)(idx / a.RE), e = (int)(idx % a.RE);
-            uint16_t v = 0;
-            if (e < 3 * r) {
-                const int seg = e / r, j = e % r;
-                const float src = a.w_from_A ? a.Wsrc[(size_t)c * r + j] : a.Wsrc[(size_t)j * a.Cw + c];
-                v = split_part(src, seg == 1);
-            }
-            a.w_ext[idx] = v;
-        }
+        // weight-side extension, one 16-byte unit per thread
+        const size_t u = (size_t)(blockIdx.x - row_blocks) * nthreads + tid;
+        if (u < (size_t)a.Cw * (a.RE >> 3)) write_w_ext_unit(a, u);
         return;
     }
 
@@ -171,14 +187,25 @@ __global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blo
 }
 
 // Second stage when the contraction was split over workgroups: add the slices' tiles of 16 rows
-// in slice order, write P and the activation-side extension.
+// in slice order, write P and the activation-side extension.  One workgroup per 16 rows; the
+// partials of a first-stage workgroup hold its ROWT tiles one after the other.
 template <int RG>
-__global__ __launch_bounds__(256) void lora_down_finish_kernel(DownArgs a, int row_blocks, int split) {
+__global__ __launch_bounds__(256) void lora_down_finish_kernel(DownArgs a, int row_blocks, int split, int rowt) {
     __shared__ float Ps[16 * 16 * RG];
     const int tid = threadIdx.x, r = a.r, m0 = blockIdx.x * 16;
+    const int rb = blockIdx.x / rowt, tile = blockIdx.x % rowt;
+    const size_t wg_floats = (size_t)rowt * 256 * RG;
     for (int x = tid; x < 256 * RG; x += 256) {
+        const float *src = a.partials + (size_t)rb * wg_floats + (size_t)tile * (256 * RG) + x;
         float sum = 0.f;
-        for (int y = 0; y < split; ++y) sum += a.partials[((size_t)y * row_blocks + blockIdx.x) * (256 * RG) + x];
+        int y = 0;
+        for (; y + 4 <= split; y += 4) {      // four slices' loads in flight
+            float v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = src[(size_t)(y + u) * row_blocks * wg_floats];
+            sum += v[0]; sum += v[1]; sum += v[2]; sum += v[3];
+        }
+        for (; y < split; ++y) sum += src[(size_t)y * row_blocks * wg_floats];
         Ps[x] = sum;
         const int prow = x / (16 * RG), j = x % (16 * RG);
         if (m0 + prow < a.M && j < r) a.P[(size_t)(m0 + prow) * r + j] = sum;
@@ -198,24 +225,12 @@ __global__ __launch_bounds__(256) void lora_down_finish_kernel(DownArgs a, int r
 }
 
 template <int RG, int ROWT>
-static hipError_t launch_down_rg(const DownArgs &a, hipStream_t stream) {
+static hipError_t launch_down_rg(const DownArgs &a, const DownPlan &plan, hipStream_t stream) {
     constexpr int ROWS = 16 * ROWT;
     const int row_blocks = (a.M + ROWS - 1) / ROWS;
-    // enough waves to fill the chip (~2048: the loads are 64-byte pieces of 16 rows, so it takes
-    // many waves to keep HBM busy), at most 32 partial tiles per workgroup
-    int nwaves = 4;
-    while (nwaves < 16 && row_blocks * nwaves < 2048 && nwaves * 2 * RG * ROWT <= 32) nwaves *= 2;
-    const int nthreads = nwaves * 64;
-    int w_blocks = 0;
-    if (a.w_ext) {
-        const size_t total = (size_t)a.Cw * a.RE;
-        w_blocks = (int)((total + (size_t)nthreads * 8 - 1) / ((size_t)nthreads * 8));
-        if (w_blocks > 512) w_blocks = 512;
-        if (w_blocks < 1) w_blocks = 1;
-    }
+    const int nwaves = plan.nwaves, nthreads = nwaves * 64, split = plan.split;
+    const int w_blocks = a.w_ext ? (int)(((size_t)a.Cw * (a.RE / 8) + nthreads - 1) / nthreads) : 0;
     const size_t lds = (size_t)(nwaves * RG * ROWT * 256 + ROWS * 16 * RG) * sizeof(float);
-    static_assert(ROWT == 1, "the split path stores one 16-row tile per workgroup");
-    const int split = lora_down_split(a.M, a.C);
     const dim3 grid(row_blocks + w_blocks, split);
     if (a.f_is_A)
         launch_kernel("lora_down", lora_down_kernel<RG, ROWT, true>, grid, nthreads, lds, stream, a, row_blocks, split);
@@ -223,16 +238,20 @@ static hipError_t launch_down_rg(const DownArgs &a, hipStream_t stream) {
         launch_kernel("lora_down", lora_down_kernel<RG, ROWT, false>, grid, nthreads, lds, stream, a, row_blocks, split);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split <= 1) return e;
-    launch_kernel("lora_down_finish", lora_down_finish_kernel<RG>, row_blocks, 256, 0, stream, a, row_blocks, split);
+    launch_kernel("lora_down_finish", lora_down_finish_kernel<RG>, (a.M + 15) / 16, 256, 0, stream, a, row_blocks, split, ROWT);
     return hipGetLastError();
 }
 
 hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream) {
-    // many tokens: four row tiles per workgroup share each split factor operand
-    if (a.r <= 16) return launch_down_rg<1, 1>(a, stream);
-    if (a.r <= 32) return launch_down_rg<2, 1>(a, stream);
-    if (a.r <= 48) return launch_down_rg<3, 1>(a, stream);
-    return launch_down_rg<4, 1>(a, stream);
+    const DownPlan plan = lora_down_plan(a.M, a.C, a.r);
+    if (plan.rowt == 4) {
+        if (a.r <= 16) return launch_down_rg<1, 4>(a, plan, stream);
+        return launch_down_rg<2, 4>(a, plan, stream);
+    }
+    if (a.r <= 16) return launch_down_rg<1, 1>(a, plan, stream);
+    if (a.r <= 32) return launch_down_rg<2, 1>(a, plan, stream);
+    if (a.r <= 48) return launch_down_rg<3, 1>(a, plan, stream);
+    return launch_down_rg<4, 1>(a, plan, stream);
 }
 
 // ---------------------------------------------------------------------------
@@ -269,12 +288,17 @@ GradGeom grad_geom(int M, int K, int N, int r) {
 // F16: the activations are binary16 (paper-literal path) instead of bfloat16.
 template <int RP, int CPL, bool F16>
 __global__ __launch_bounds__(256) void lora_grad_partial_kernel(GradPairArgs a, GradGeom g) {
-    __shared__ float red[3][64][CPL * RP + 1];
+    // one LDS buffer, used first for pieces of P and then for the waves' sums
+    constexpr int PROWS = 128, RED_ROW = CPL * RP + 1;
+    constexpr int LDS_FLOATS = 3 * 64 * RED_ROW > PROWS * RP ? 3 * 64 * RED_ROW : PROWS * RP;
+    __shared__ __attribute__((aligned(16))) float lds_buf[LDS_FLOATS];
+    float (*red)[64][RED_ROW] = reinterpret_cast<float (*)[64][RED_ROW]>(lds_buf);
+    float (*Ps)[RP] = reinterpret_cast<float (*)[RP]>(lds_buf);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const bool is_a = (int)blockIdx.x < g.cols_a;
-    const uint16_t *act = is_a ? a.X : a.dY;
-    const float *P = is_a ? a.dYBt : a.XA;
+    const uint16_t *__restrict__ act = is_a ? a.X : a.dY;
+    const float *__restrict__ P = is_a ? a.dYBt : a.XA;   // [M][r]: a row is the same for every lane (scalar loads)
     const int C = is_a ? a.K : a.N;
     const int c = (is_a ? blockIdx.x : blockIdx.x - g.cols_a) * (64 * CPL) + CPL * lane;
     const int r = a.r, j0 = blockIdx.z * RP;
@@ -289,8 +313,12 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(GradPairArgs a, 
 #pragma unroll
         for (int j = 0; j < RP; ++j) acc[t][j] = 0.f;
 
+    // The rows of P that the workgroup needs pass through LDS, a piece of PROWS rows at a time:
+    // every lane of a wave needs the same RP values of a row, and reading them from LDS (one
+    // address for the whole wave: a broadcast) costs RP / 4 instructions per row, where loads from
+    // global memory with a wave-uniform address would cost RP.
     typedef uint32_t words_t __attribute__((ext_vector_type(CPL / 2)));
-    auto row_fma = [&](words_t v, int m) {
+    auto row_fma = [&](words_t v, int prow) {
         float x[CPL];
 #pragma unroll
         for (int q = 0; q < CPL / 2; ++q) {
@@ -299,24 +327,54 @@ __global__ __launch_bounds__(256) void lora_grad_partial_kernel(GradPairArgs a, 
             x[2 * q] = F16 ? half_bits_to_float((uint16_t)(wq & 0xFFFFu)) : __uint_as_float(wq << 16);
             x[2 * q + 1] = F16 ? half_bits_to_float((uint16_t)(wq >> 16)) : __uint_as_float(wq & 0xFFFF0000u);
         }
-        const float *p = P + (size_t)m * r + j0;
 #pragma unroll
-        for (int j = 0; j < RP; ++j) {
-            const float pj = j0 + j < r ? p[j] : 0.f;
+        for (int j = 0; j < RP; j += 4) {
+            const float4 pj = *reinterpret_cast<const float4 *>(&Ps[prow][j]);
+            const float pv[4] = {pj.x, pj.y, pj.z, pj.w};
 #pragma unroll
-            for (int t = 0; t < CPL; ++t) acc[t][j] = __builtin_fmaf(x[t], pj, acc[t][j]);
+            for (int z = 0; z < 4; ++z)
+#pragma unroll
+                for (int t = 0; t < CPL; ++t) acc[t][j + z] = __builtin_fmaf(x[t], pv[z], acc[t][j + z]);
         }
     };
     const uint16_t *col = act + (col_ok ? c : 0);
-    int m = m_begin + wave;
-    for (; m + 12 < m_end; m += 16) {     // four rows in flight per wave
-        words_t v[4];
+    for (int mb = m_begin; mb < m_end; mb += PROWS) {
+        const int me = mb + PROWS < m_end ? mb + PROWS : m_end;
+        __syncthreads();                              // the previous piece has been consumed
+        for (int x = threadIdx.x; x < (me - mb) * RP; x += 256) {
+            const int prow = x / RP, j = x % RP;
+            Ps[prow][j] = j0 + j < r ? P[(size_t)(mb + prow) * r + j0 + j] : 0.f;
+        }
+        __syncthreads();
+        // groups of four rows per wave (rows m, m + 4, m + 8, m + 12); the loads of the next group
+        // are issued before the arithmetic of the current one, so a wave always has a group in flight
+        int m = mb + wave;
+        bool have = m + 12 < me;
+        words_t cur[4];
+        if (have) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const words_t *>(col + (size_t)(m + 4 * u) * C);
+            for (int u = 0; u < 4; ++u) cur[u] = *reinterpret_cast<const words_t *>(col + (size_t)(m + 4 * u) * C);
+        }
+        while (have) {
+            const int mn = m + 16;
+            const bool have_next = mn + 12 < me;
+            words_t nxt[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) row_fma(v[u], m + 4 * u);
+            for (int u = 0; u < 4; ++u) nxt[u] = cur[u];
+            if (have_next) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) nxt[u] = *reinterpret_cast<const words_t *>(col + (size_t)(mn + 4 * u) * C);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) row_fma(cur[u], m + 4 * u - mb);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
+            m = mn;
+            have = have_next;
+        }
+        for (; m < me; m += 4) row_fma(*reinterpret_cast<const words_t *>(col + (size_t)m * C), m - mb);
     }
-    for (; m < m_end; m += 4) row_fma(*reinterpret_cast<const words_t *>(col + (size_t)m * C), m);
+    __syncthreads();                                  // every wave is done with the last piece of P
 
     if (wave > 0) {
 #pragma unroll
