@@ -246,6 +246,11 @@ int modulora_adamw(float *param, const float *grad, float *exp_avg, float *exp_a
  * modulora_f16_workspace_bytes()).  Shape rules, rank rules, the stream argument, ownership and
  * error behaviour are those of the calls above: every argument error is found on the host
  * before any HIP call and returned as a modulora_status; nothing is allocated or synchronized.
+ * Arithmetic by token count, as for modulora_fwd / modulora_bwd_input: at M <= 16 (same shape
+ * conditions) the codes are multiplied directly (Section 3.1.2) and scale and zero point are
+ * applied to per-group sums, so What is not rounded to binary16 first; forward results differ from
+ * the materialized form by at most 2^-11 sum_k |X| |What|, input gradients (where dY * scale is
+ * rounded to binary16) by at most 2^-10 sum_n |dY| |What|.
  * ------------------------------------------------------------------------------------ */
 typedef struct {
     int32_t d_in;

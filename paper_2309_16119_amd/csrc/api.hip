@@ -409,7 +409,19 @@ F16Ws f16_ws(int32_t K, int32_t N, int32_t M, int32_t r) {
     }
     l.gemm_part = off; off += align256(mlr::gemm_partial_bytes(M, K, N));   // partial tiles of the 256 x 256 kernel
     l.total = off;
+    // the M <= 16 streaming kernels lay out their own scratch from the start of the workspace
+    if (M <= 16) {
+        const size_t small = mlr::smallm_ws_bytes(K, N, r);
+        if (small > l.total) l.total = small;
+    }
     return l;
+}
+// the codes and scales of the layer as the streaming kernels take them (zero points travel separately)
+mlr::LayerView stream_view_of(const modulora_qweight_f16 *w) {
+    mlr::LayerView v;
+    v.K = w->d_in; v.N = w->d_out; v.bits = w->bits; v.group = w->group_size;
+    v.qweight = w->qweight; v.scales = w->scales; v.zeros = nullptr;
+    return v;
 }
 int check_ws_f16(const F16Ws &l, const void *ws, size_t bytes) {
     if (l.total == 0) return MODULORA_OK;
@@ -444,6 +456,16 @@ int modulora_f16_fwd(const modulora_qweight_f16 *w, const uint16_t *X, int32_t M
     const F16Ws l = f16_ws(w->d_in, w->d_out, M, r);
     if ((s = check_ws_f16(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (mlr::smallm_fwd_supported(stream_view_of(w), M)) {
+        // a handful of tokens: the direct product with the quantized matrix (Section 3.1.2)
+        mlr::SmallArgs sa{};
+        sa.w = stream_view_of(w);
+        sa.act = X; sa.M = M; sa.out = Y;
+        sa.A = A; sa.B = B; sa.r = r; sa.lora_scale = lora_scale;
+        sa.P_out = XA; sa.ws = workspace;
+        sa.f16 = true; sa.zeros16 = w->zeros; sa.bias16 = w->bias;
+        return hip_status(mlr::launch_smallm_fwd(sa, st));
+    }
     float *P = nullptr;
     if (r > 0) {
         P = XA ? XA : reinterpret_cast<float *>(static_cast<char *>(workspace) + l.p0);
@@ -465,6 +487,15 @@ int modulora_f16_bwd_input(const modulora_qweight_f16 *w, const uint16_t *dY, in
     const F16Ws l = f16_ws(w->d_in, w->d_out, M, r);
     if ((s = check_ws_f16(l, workspace, workspace_bytes)) != MODULORA_OK) return s;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (mlr::smallm_bwd_supported(stream_view_of(w), M)) {
+        mlr::SmallArgs sa{};
+        sa.w = stream_view_of(w);
+        sa.act = dY; sa.M = M; sa.out = dX;
+        sa.A = A; sa.B = B; sa.r = r; sa.lora_scale = lora_scale;
+        sa.P_out = dYBt; sa.ws = workspace;
+        sa.f16 = true; sa.zeros16 = w->zeros; sa.bias16 = nullptr;
+        return hip_status(mlr::launch_smallm_bwd(sa, st));
+    }
     float *P = nullptr;
     if (r > 0) {
         P = dYBt ? dYBt : reinterpret_cast<float *>(static_cast<char *>(workspace) + l.p0);

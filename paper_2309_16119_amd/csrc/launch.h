@@ -253,6 +253,11 @@ struct SmallArgs {
     float lora_scale;
     float *P_out;         // XA / dYBt hand-off [M][r], may be NULL
     void *ws;             // at least smallm_ws_bytes() bytes
+    // The layer in the paper's own storage convention: binary16 activations and outputs, binary16
+    // zero points [K/group][N] that are added (w.zeros unused), optional binary16 bias [N] (forward).
+    bool f16;
+    const uint16_t *zeros16;
+    const uint16_t *bias16;
 };
 bool smallm_fwd_supported(const LayerView &w, int M);
 bool smallm_bwd_supported(const LayerView &w, int M);

@@ -37,9 +37,43 @@ constexpr int WG_WAVES = 4, WG_THREADS = WG_WAVES * 64;      // backward stream 
 constexpr int FWD_WAVES = 8, FWD_THREADS = FWD_WAVES * 64;  // forward stream kernel: one workgroup per compute unit
 constexpr int PREP_K = 128;            // the contraction length must be a multiple of this
 constexpr int MAX_KSPLIT = 32;         // workgroups that may share a column block
-constexpr uint32_t MAGIC = 0x43004300u;   // two bfloat16 128.0
-constexpr uint32_t MAGIC3 = 0x43004100u;  // bfloat16 (8.0, 128.0): 3-bit, forward (low field at bits 4-6)
-constexpr uint32_t ONES = 0x3F803F80u;    // two bfloat16 1.0
+// Number format of the activations and of the operands built from the codes: bfloat16, or binary16
+// for the layer in the paper's own storage convention (F16).  A b-bit field OR-ed into the mantissa
+// of a power of two whose unit in the last place is one gives that power of two plus the code:
+// bfloat16 128.0 (7 mantissa bits), binary16 1024.0 (10 mantissa bits); with the field four bits up,
+// bfloat16 8.0 or binary16 64.0.
+template <bool F16> struct Num {
+    static constexpr uint32_t MAGIC = F16 ? 0x64006400u : 0x43004300u;    // two 1024.0 / two 128.0
+    static constexpr uint32_t MAGIC3 = F16 ? 0x64005400u : 0x43004100u;   // (64.0, 1024.0) / (8.0, 128.0): 3-bit forward, low field at bits 4-6
+    static constexpr uint32_t ONES = F16 ? 0x3C003C00u : 0x3F803F80u;     // two 1.0
+    static constexpr float OFFSET = F16 ? 1024.0f : 128.0f;
+};
+constexpr uint32_t MAGIC = Num<false>::MAGIC;
+constexpr uint32_t MAGIC3 = Num<false>::MAGIC3;
+constexpr uint32_t ONES = Num<false>::ONES;
+typedef _Float16 half16x8 __attribute__((ext_vector_type(8)));
+
+// D = A B + C on a 16 x 16 x 32 tile, operands given as four registers of 16-bit pairs
+template <bool F16>
+__device__ __forceinline__ f32x4 mma(const bf16x8 &a, const bf16x8 &b, const f32x4 &c) {
+    if (F16) {
+        half16x8 x, y;
+        __builtin_memcpy(&x, &a, 16);
+        __builtin_memcpy(&y, &b, 16);
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(x, y, c, 0, 0, 0);
+    }
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// two fp32 -> a pair of 16-bit floats (round to nearest even), `lo` in the low half
+template <bool F16>
+__device__ __forceinline__ uint32_t pack16(float lo, float hi) {
+    return pack_pair<F16>(lo, hi);
+}
+// a stored 16-bit float -> fp32 (exact)
+template <bool F16>
+__device__ __forceinline__ float widen16(uint32_t bits16) {
+    return F16 ? half_bits_to_float((uint16_t)bits16) : __uint_as_float(bits16 << 16);
+}
 
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint32_t r[4]) {
     bf16x8 v;
@@ -79,11 +113,11 @@ template <int BITS> struct Geo {
     static constexpr int KSTEP = 32 * NC;                             // codes per wave step
 };
 
-template <int BITS>
+template <int BITS, bool F16>
 __device__ __forceinline__ CodeMasks make_masks() {
     CodeMasks m;
     m.field = opaque_sgpr(BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x00070070u));
-    m.magic = opaque_vgpr(BITS == 3 ? MAGIC3 : MAGIC);
+    m.magic = opaque_vgpr(BITS == 3 ? Num<F16>::MAGIC3 : Num<F16>::MAGIC);
     return m;
 }
 
@@ -199,6 +233,41 @@ __device__ __forceinline__ void smallm_project(const uint16_t *act, int M, int C
     }
 }
 
+// The same projection for binary16 activations (the layer in the paper's own storage convention),
+// in plain fp32 on the vector ALUs: a binary16 activation does not fit a bfloat16 operand, and at
+// most 16 rows by a few thousand contraction elements per workgroup are too little work to matter.
+// Thread t: row t % 16, contraction elements (t / 16) + k * (threads / 16) of the workgroup's range;
+// the threads' sums meet in LDS.  Same partial layout as above: one [16][r] per workgroup.
+template <bool F_IS_A, int NWAVES>
+__device__ __forceinline__ void smallm_project_f16(const uint16_t *act, int M, int C, const float *F, int r, int blk,
+                                                   int nblk, float *parts, float *red /* LDS, NWAVES * 64 * 16 floats */) {
+    constexpr int NT = NWAVES * 64, KL = NT / 16;
+    const int tid = threadIdx.x, m = tid & 15, kl = tid >> 4;
+    const int c0 = (int)((long)C * blk / nblk), c1 = (int)((long)C * (blk + 1) / nblk);
+    const uint16_t *arow = act + (size_t)(m < M ? m : M - 1) * C;
+    float *mine = parts + (size_t)blk * 16 * r;
+    for (int j0 = 0; j0 < r; j0 += 16) {
+        float acc[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+        for (int c = c0 + kl; c < c1; c += KL) {
+            const float x = half_bits_to_float(arow[c]);
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (j0 + j < r) acc[j] = __builtin_fmaf(x, F_IS_A ? F[(size_t)c * r + j0 + j] : F[(size_t)(j0 + j) * C + c], acc[j]);
+        }
+        __syncthreads();                         // the previous pass has been read
+#pragma unroll
+        for (int j = 0; j < 16; ++j) red[(kl * 16 + m) * 16 + j] = acc[j];
+        __syncthreads();
+        if (tid < 256) {                         // (row, column) = (tid / 16, tid % 16)
+            float sum = 0.f;
+            for (int q = 0; q < KL; ++q) sum += red[(q * 16 + (tid >> 4)) * 16 + (tid & 15)];
+            if (j0 + (tid & 15) < r) mine[(tid >> 4) * r + j0 + (tid & 15)] = sum;
+        }
+    }
+}
+
 // Sum of the projection workgroups' partials into Us (16 x r floats in LDS).
 __device__ __forceinline__ void smallm_sum_parts(const float *parts, int n_parts, int r, float *Us) {
     for (int t = threadIdx.x; t < 16 * r; t += blockDim.x) {
@@ -237,6 +306,9 @@ struct SmallFwdDev {
     uint16_t *Y;            // [M][N]
     float *XA;              // [M][r] or NULL
     float *Yacc;            // [ksplit][16][N] fp32 partial tiles
+    // the layer in the paper's own storage convention (F16 kernels only; w.zeros unused there)
+    const uint16_t *zeros16;   // binary16 [K/group][N], added
+    const uint16_t *bias16;    // binary16 [N] or NULL
 };
 
 namespace sm {
@@ -324,6 +396,7 @@ constexpr int MAX_RANGE = 2048;           // contraction elements of one K slice
 
 // Adds the adapter term to the four adjacent outputs y[0..3] of row m, columns col..col+3
 // (col a multiple of 4, col + 3 < N) and stores them as bfloat16.
+template <bool F16>
 __device__ __forceinline__ void smallm_store4(const SmallFwdDev &d, const float *Us, int m, int col, const float y[4]) {
     float l[4] = {0.f, 0.f, 0.f, 0.f};
     for (int jj = 0; jj < d.r; ++jj) {
@@ -334,15 +407,21 @@ __device__ __forceinline__ void smallm_store4(const SmallFwdDev &d, const float 
         l[2] = __builtin_fmaf(u, b.z, l[2]);
         l[3] = __builtin_fmaf(u, b.w, l[3]);
     }
+    float b[4] = {0.f, 0.f, 0.f, 0.f};
+    if (F16 && d.bias16 != nullptr) {          // the bias of Figure 1 / eq. (3): part of the frozen layer
+        const uint2 bw = *reinterpret_cast<const uint2 *>(d.bias16 + col);
+        b[0] = half_bits_to_float((uint16_t)(bw.x & 0xFFFFu)); b[1] = half_bits_to_float((uint16_t)(bw.x >> 16));
+        b[2] = half_bits_to_float((uint16_t)(bw.y & 0xFFFFu)); b[3] = half_bits_to_float((uint16_t)(bw.y >> 16));
+    }
     uint2 o;
-    o.x = pack_bf16x2(__builtin_fmaf(d.lora_scale, l[0], y[0]), __builtin_fmaf(d.lora_scale, l[1], y[1]));
-    o.y = pack_bf16x2(__builtin_fmaf(d.lora_scale, l[2], y[2]), __builtin_fmaf(d.lora_scale, l[3], y[3]));
+    o.x = sm::pack16<F16>(__builtin_fmaf(d.lora_scale, l[0], y[0] + b[0]), __builtin_fmaf(d.lora_scale, l[1], y[1] + b[1]));
+    o.y = sm::pack16<F16>(__builtin_fmaf(d.lora_scale, l[2], y[2] + b[2]), __builtin_fmaf(d.lora_scale, l[3], y[3] + b[3]));
     *reinterpret_cast<uint2 *>(d.Y + (size_t)m * d.w.N + col) = o;
 }
 
 // SPG1: a quantization group is exactly one step (KSTEP codes), so every step starts its
 // sums from zero (the first MFMA of a step takes a zero C operand) and ends with the affine part.
-template <int BITS, bool SPG1>
+template <int BITS, bool SPG1, bool F16>
 __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwdDev d) {
     using G = sm::Geo<BITS>;
     extern __shared__ __attribute__((aligned(16))) uint4 xs[];   // [chunks of the slice][16 rows]
@@ -350,7 +429,8 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
     if ((int)blockIdx.x < d.n_proj) {
         // projection workgroups: partials of XA = X A for the finish kernel; they run beside the
         // streaming ones and are done long before them
-        smallm_project<true, sm::FWD_WAVES>(d.X, d.M, d.w.K, d.A, d.r, blockIdx.x, d.n_proj, d.Upart, reinterpret_cast<float *>(xs));
+        if (F16) smallm_project_f16<true, sm::FWD_WAVES>(d.X, d.M, d.w.K, d.A, d.r, blockIdx.x, d.n_proj, d.Upart, reinterpret_cast<float *>(xs));
+        else smallm_project<true, sm::FWD_WAVES>(d.X, d.M, d.w.K, d.A, d.r, blockIdx.x, d.n_proj, d.Upart, reinterpret_cast<float *>(xs));
         return;
     }
     const int bid = blockIdx.x - d.n_proj;
@@ -369,12 +449,15 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
     const int spg = group / G::KSTEP;               // steps per group
     const int s_begin = g_begin * spg, s_end = g_end * spg;
 
-    constexpr int DEPTH = BITS == 3 ? 3 : 8;
+    // stages in flight (the binary16 zero points take one more register per stage: one stage fewer,
+    // so that the kernel stays within 128 registers)
+    constexpr int DEPTH = BITS == 3 ? 3 : (F16 ? 7 : 8);
     constexpr int SL = G::WORDS + 2;                // loads per stage
     struct Stage {
         sm::u32x4 w[G::WORDS];
         sm::u32x2 sc;      // 4 binary16 scales
-        uint32_t z;        // 4 zero points
+        uint32_t z;        // 4 integer zero points (bfloat16 layer)
+        sm::u32x2 z16;     // 4 binary16 zero points (F16)
     };
     Stage st[DEPTH];
     // lane group j reads packed rows (4 s + j) * WORDS + q, columns n .. n + 3
@@ -386,7 +469,8 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
         for (int q = 0; q < G::WORDS; ++q) sm::ald(sd.w[q], wbase + (size_t)q * N, w_voff);
         const int g = s / spg;
         sm::ald(sd.sc, d.w.scales + (size_t)g * N, s_voff);
-        sm::ald(sd.z, d.w.zeros + (size_t)g * N, z_voff);
+        if (F16) sm::ald(sd.z16, d.zeros16 + (size_t)g * N, s_voff);
+        else sm::ald(sd.z, d.w.zeros + (size_t)g * N, z_voff);
     };
     // The workgroup's slice of X goes into LDS in operand order: chunk c of 8 contraction
     // elements, row m at xs[16 c + m].  Inside a chunk the elements are re-ordered to the pairing
@@ -462,10 +546,11 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
         for (int cs = 0; cs < 4; ++cs) { yacc[cs][v] = 0.f; tmp[cs][v] = 0.f; }
         s1[v] = 0.f; s2[v] = 0.f;
     }
-    const uint32_t ones4[4] = {sm::ONES, sm::ONES, sm::ONES, sm::ONES};
-    const uint32_t offs4[4] = {sm::MAGIC3, sm::MAGIC3, sm::MAGIC3, sm::MAGIC3};   // 3-bit: the (8, 128) offsets
+    using NF = sm::Num<F16>;
+    const uint32_t ones4[4] = {NF::ONES, NF::ONES, NF::ONES, NF::ONES};
+    const uint32_t offs4[4] = {NF::MAGIC3, NF::MAGIC3, NF::MAGIC3, NF::MAGIC3};   // 3-bit: the two offsets themselves
     const bf16x8 ones = sm::as_bf16x8(ones4), offs = sm::as_bf16x8(offs4);
-    const sm::CodeMasks masks = sm::make_masks<BITS>();
+    const sm::CodeMasks masks = sm::make_masks<BITS, F16>();
 
     auto compute = [&](Stage &sd, int srel, bool group_ends) {
         // operand chunks 4 NC srel + NC j + c of the slice, row i
@@ -484,23 +569,25 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
 #pragma unroll
                 for (int q = 0; q < G::WORDS; ++q) wq[q] = sd.w[q][cs];
                 sm::codes_to_operand<BITS>(wq, c, masks, o);
-                tmp[cs] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), fresh ? zero4 : tmp[cs], 0, 0, 0);
+                tmp[cs] = sm::mma<F16>(a, sm::as_bf16x8(o), fresh ? zero4 : tmp[cs]);
             }
             // 4- and 2-bit: s1 = sum X.  3-bit: s1 = sum offset * X, s2 = sum X.
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, BITS == 3 ? offs : ones, fresh ? zero4 : s1, 0, 0, 0);
-            if (BITS == 3) s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, fresh ? zero4 : s2, 0, 0, 0);
+            s1 = sm::mma<F16>(a, BITS == 3 ? offs : ones, fresh ? zero4 : s1);
+            if (BITS == 3) s2 = sm::mma<F16>(a, ones, fresh ? zero4 : s2);
         }
         if (!SPG1 && !group_ends) return;
         // end of a group: tmp = sum X (offset + q); remove the offsets, apply zero point and scale
 #pragma unroll
         for (int cs = 0; cs < 4; ++cs) {
             const float scale = half_bits_to_float((uint16_t)(sd.sc[cs >> 1] >> (16 * (cs & 1))));
-            const float zero = (float)((sd.z >> (8 * cs)) & 0xFFu);
+            // integer zero point: w = (q - zero) scale; binary16 zero point: w = q scale + z (eq. (2) as printed)
+            const float zero = F16 ? half_bits_to_float((uint16_t)(sd.z16[cs >> 1] >> (16 * (cs & 1)))) : (float)((sd.z >> (8 * cs)) & 0xFFu);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const float xsum = BITS == 3 ? s2[v] : s1[v];
-                const float qx = BITS == 3 ? tmp[cs][v] - s1[v] : __builtin_fmaf(-128.0f, s1[v], tmp[cs][v]);   // sum X q
-                yacc[cs][v] = __builtin_fmaf(scale, __builtin_fmaf(-zero, xsum, qx), yacc[cs][v]);
+                const float qx = BITS == 3 ? tmp[cs][v] - s1[v] : __builtin_fmaf(-NF::OFFSET, s1[v], tmp[cs][v]);   // sum X q
+                if (F16) yacc[cs][v] = __builtin_fmaf(scale, qx, __builtin_fmaf(zero, xsum, yacc[cs][v]));
+                else yacc[cs][v] = __builtin_fmaf(scale, __builtin_fmaf(-zero, xsum, qx), yacc[cs][v]);
                 if (!SPG1) tmp[cs][v] = 0.f;
             }
         }
@@ -520,7 +607,7 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
 #pragma unroll
                 for (int q = 0; q < G::WORDS; ++q) sm::tie(st[dd].w[q]);
                 sm::tie(st[dd].sc);
-                sm::tie(st[dd].z);
+                if (F16) sm::tie(st[dd].z16); else sm::tie(st[dd].z);
                 const bool ends = ++cp == spg;
                 if (ends) cp = 0;
                 compute(st[dd], s + dd - s_begin, ends);
@@ -538,7 +625,7 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
 #pragma unroll
         for (int q = 0; q < G::WORDS; ++q) sm::tie(st[dd].w[q]);
         sm::tie(st[dd].sc);
-        sm::tie(st[dd].z);
+        if (F16) sm::tie(st[dd].z16); else sm::tie(st[dd].z);
     }
 
     // D register v of lane (i, j): row 4j + v, columns n + cs.  The finish kernel (next launch
@@ -554,6 +641,7 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
 
 // Sum of the K slices' partial tiles, then the adapter term and the bfloat16 store.  One
 // workgroup per 64 columns: thread t owns row t / 16, columns 4 (t % 16) .. + 3.
+template <bool F16>
 __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(SmallFwdDev d) {
     __shared__ float Us[16 * 64];
     const int tid = threadIdx.x, N = d.w.N;
@@ -575,7 +663,7 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
     smallm_sum_parts(d.Upart, d.n_proj, d.r, Us);
     if (blockIdx.x == 0 && d.XA != nullptr)
         for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
-    if (m < d.M && col < N) smallm_store4(d, Us, m, col, y);
+    if (m < d.M && col < N) smallm_store4<F16>(d, Us, m, col, y);
 }
 
 // ---------------------------------------------------------------------------------
@@ -608,6 +696,7 @@ struct SmallBwdDev {
     uint16_t *dX;           // [M][K]
     float *T_out;           // dYBt [M][r] or NULL
     float *acc;             // [nsplit][16][K] fp32 partial tiles
+    const uint16_t *zeros16;   // F16 kernels only: binary16 zero points [K/group][N], added (w.zeros unused there)
 };
 
 namespace smb {
@@ -617,6 +706,7 @@ constexpr int RED_BYTES = sm::WG_WAVES * 32 * 64 * 4;   // the waves' tiles meet
 }
 
 // adapter term and bfloat16 store of 8 adjacent outputs dX[m][k0 .. k0+7]
+template <bool F16>
 __device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const float *Ts, int m, int k0, const float y[8]) {
     float o[8];
 #pragma unroll
@@ -627,10 +717,10 @@ __device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const fl
         o[c] = __builtin_fmaf(d.lora_scale, l, y[c]);
     }
     uint4 v;
-    v.x = pack_bf16x2(o[0], o[1]);
-    v.y = pack_bf16x2(o[2], o[3]);
-    v.z = pack_bf16x2(o[4], o[5]);
-    v.w = pack_bf16x2(o[6], o[7]);
+    v.x = sm::pack16<F16>(o[0], o[1]);
+    v.y = sm::pack16<F16>(o[2], o[3]);
+    v.z = sm::pack16<F16>(o[4], o[5]);
+    v.w = sm::pack16<F16>(o[6], o[7]);
     *reinterpret_cast<uint4 *>(d.dX + (size_t)m * d.w.K + k0) = v;
 }
 
@@ -640,11 +730,12 @@ __device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const fl
 // results through LDS at the end.  Lane l = 16 j + i: i = 4 u + b picks the 32-code block b of
 // the tile and the 8 codes 8u .. 8u+7 of it (MFMA call c handles code 8u + c, so the lane's
 // outputs are 8 adjacent k), j picks 8 adjacent n of the step.
-template <int BITS>
+template <int BITS, bool F16 = false>
 struct BwdGeo {
     static constexpr int WR = 4 * BITS;                // word rows of the 128-column tile
-    // 16-byte pieces of one stage: word rows (8 per row), scales (4), zeros (2), dY (16 rows x 4)
-    static constexpr int W_PIECES = WR * 8, S_PIECE0 = W_PIECES, Z_PIECE0 = W_PIECES + 4, Y_PIECE0 = W_PIECES + 6;
+    // 16-byte pieces of one stage: word rows (8 per row), scales (4), zeros (2 of uint8, or 4 of
+    // binary16), dY (16 rows x 4)
+    static constexpr int W_PIECES = WR * 8, S_PIECE0 = W_PIECES, Z_PIECE0 = W_PIECES + 4, Y_PIECE0 = Z_PIECE0 + (F16 ? 4 : 2);
     static constexpr int N_PIECES = Y_PIECE0 + 64;
     static constexpr int NI = (N_PIECES + 63) / 64;    // loads per stage
     static constexpr int STAGE_BYTES = NI * 1024;
@@ -667,14 +758,16 @@ struct BwdGeo {
     }
 };
 
-template <int BITS>
+template <int BITS, bool F16>
 __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdDev d) {
-    using BG = BwdGeo<BITS>;
+    using BG = BwdGeo<BITS, F16>;
+    using NF = sm::Num<F16>;
     extern __shared__ __attribute__((aligned(16))) uint4 ys[];   // [wave][stage] private stages, later the reduction
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if ((int)blockIdx.x < d.n_proj) {
         // projection workgroups: partials of dYBt = dY B^T (see the forward kernel)
-        smallm_project<false, sm::WG_WAVES>(d.dY, d.M, d.w.N, d.B, d.r, blockIdx.x, d.n_proj, d.Tpart, reinterpret_cast<float *>(ys));
+        if (F16) smallm_project_f16<false, sm::WG_WAVES>(d.dY, d.M, d.w.N, d.B, d.r, blockIdx.x, d.n_proj, d.Tpart, reinterpret_cast<float *>(ys));
+        else smallm_project<false, sm::WG_WAVES>(d.dY, d.M, d.w.N, d.B, d.r, blockIdx.x, d.n_proj, d.Tpart, reinterpret_cast<float *>(ys));
         return;
     }
     const int bid = blockIdx.x - d.n_proj;
@@ -702,7 +795,8 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     }
     const uint32_t *wtile = d.w.qweight + (size_t)(kt / 32) * BITS * N;
     const uint16_t *stile = d.w.scales + (size_t)g * N;
-    const uint8_t *ztile = d.w.zeros + (size_t)g * N;
+    // zero points of the group: one byte each, or (F16) one binary16 each
+    const char *ztile = F16 ? reinterpret_cast<const char *>(d.zeros16 + (size_t)g * N) : reinterpret_cast<const char *>(d.w.zeros + (size_t)g * N);
 
     // The packed words, scales, zeros and the dY piece of a step (32 n) travel global -> LDS
     // without passing through registers: every lane moves one 16-byte piece per load, so a whole
@@ -724,8 +818,8 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
             gaddr[q] = reinterpret_cast<const char *>(stile) + (pc - BG::S_PIECE0) * 16;
             gstr[q] = smb::NSTEP * 2;
         } else if (pc < BG::Y_PIECE0) {
-            gaddr[q] = reinterpret_cast<const char *>(ztile) + (pc - BG::Z_PIECE0) * 16;
-            gstr[q] = smb::NSTEP;
+            gaddr[q] = ztile + (pc - BG::Z_PIECE0) * 16;
+            gstr[q] = smb::NSTEP * (F16 ? 2 : 1);
         } else {
             const int yp = pc < BG::N_PIECES ? pc - BG::Y_PIECE0 : 0;
             const int m = (yp & 15) < d.M ? (yp & 15) : d.M - 1;
@@ -758,17 +852,18 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
         accz[v] = 0.f;
         accs[v] = 0.f;
     }
-    const uint32_t ones4[4] = {sm::ONES, sm::ONES, sm::ONES, sm::ONES};
+    const uint32_t ones4[4] = {NF::ONES, NF::ONES, NF::ONES, NF::ONES};
     const bf16x8 ones = sm::as_bf16x8(ones4);
     // field masks at the positions field_pos() can return (multiples of BITS)
     constexpr uint32_t FM = BITS == 4 ? 0x000F000Fu : (BITS == 2 ? 0x00030003u : 0x00070007u);
     const uint32_t fmask[3] = {sm::opaque_sgpr(FM), sm::opaque_sgpr(FM << BITS), sm::opaque_sgpr(FM << (2 * BITS))};
-    const uint32_t magic = sm::opaque_vgpr(sm::MAGIC);
+    const uint32_t magic = sm::opaque_vgpr(NF::MAGIC);
 
     struct Stage {
         sm::u32x4 w[NROWS][2];   // 8 adjacent n of each word row
         sm::u32x4 sc;            // 8 binary16 scales
-        sm::u32x2 z;             // 8 zero points
+        sm::u32x2 z;             // 8 integer zero points (bfloat16 layer)
+        sm::u32x4 z16;           // 8 binary16 zero points (F16)
         sm::u32x4 y;             // dY[i][8 n]
     };
     // marks a register set as complete (call after a wait for the LDS reads that fill it), so
@@ -781,7 +876,7 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
             sm::tie(sd.w[NROWS - 1][1]);
         }
         sm::tie(sd.sc);
-        sm::tie(sd.z);
+        if (F16) sm::tie(sd.z16); else sm::tie(sd.z);
         sm::tie(sd.y);
     };
     // a landed stage, LDS -> registers
@@ -794,18 +889,19 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
             sd.w[NROWS - 1][1] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j + 1) ^ BG::swz(row1)) << 4));
         }
         sd.sc = *reinterpret_cast<const sm::u32x4 *>(sb + BG::S_PIECE0 * 16 + 16 * j);
-        sd.z = *reinterpret_cast<const sm::u32x2 *>(sb + BG::Z_PIECE0 * 16 + 8 * j);
+        if (F16) sd.z16 = *reinterpret_cast<const sm::u32x4 *>(sb + BG::Z_PIECE0 * 16 + 16 * j);
+        else sd.z = *reinterpret_cast<const sm::u32x2 *>(sb + BG::Z_PIECE0 * 16 + 8 * j);
         sd.y = *reinterpret_cast<const sm::u32x4 *>(sb + (BG::Y_PIECE0 + 16 * j + i) * 16);
     };
     auto compute = [&](const Stage &sd) {
-        // A operand: dY[i][8 n] * scale[g][8 n], rounded to bfloat16
+        // A operand: dY[i][8 n] * scale[g][8 n], rounded to the activations' 16-bit format
         const uint32_t yw[4] = {sd.y[0], sd.y[1], sd.y[2], sd.y[3]};
         uint32_t areg[4];
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            const float y0 = __uint_as_float(yw[p] << 16), y1 = __uint_as_float(yw[p] & 0xFFFF0000u);
+            const float y0 = sm::widen16<F16>(yw[p] & 0xFFFFu), y1 = sm::widen16<F16>(yw[p] >> 16);
             const float s0 = half_bits_to_float((uint16_t)(sd.sc[p] & 0xFFFFu)), s1 = half_bits_to_float((uint16_t)(sd.sc[p] >> 16));
-            areg[p] = pack_bf16x2(y0 * s0, y1 * s1);
+            areg[p] = sm::pack16<F16>(y0 * s0, y1 * s1);
         }
         const bf16x8 a = sm::as_bf16x8(areg);
         // the lane's 8 codes of each of its 8 n, at bit 0 of ch[e]
@@ -840,17 +936,23 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
                 else x = c < 5 ? plo[p] >> (6 * (c / 2)) : phi[p] >> (c < 7 ? 7 : 13);
                 o[p] = sm::and_or(x, fmask[BG::field_pos(c) / BITS], magic);
             }
-            acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(o), acc[c], 0, 0, 0);
+            acc[c] = sm::mma<F16>(a, sm::as_bf16x8(o), acc[c]);
         }
-        // zero points as exact bfloat16
-        uint32_t zo[4];
+        if (F16) {
+            // the added zero point: sum_n dY[m][n] z[g][n], with the unscaled dY and z as stored
+            const uint32_t zo[4] = {sd.z16[0], sd.z16[1], sd.z16[2], sd.z16[3]};
+            accz = sm::mma<F16>(sm::as_bf16x8(yw), sm::as_bf16x8(zo), accz);
+        } else {
+            // integer zero points as exact bfloat16: sum_n (dY scale)[m][n] zero[g][n]
+            uint32_t zo[4];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const uint32_t zw = sd.z[p >> 1] >> (16 * (p & 1));
-            zo[p] = pack_bf16x2((float)(zw & 0xFFu), (float)((zw >> 8) & 0xFFu));
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t zw = sd.z[p >> 1] >> (16 * (p & 1));
+                zo[p] = pack_bf16x2((float)(zw & 0xFFu), (float)((zw >> 8) & 0xFFu));
+            }
+            accz = sm::mma<F16>(a, sm::as_bf16x8(zo), accz);
         }
-        accz = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, sm::as_bf16x8(zo), accz, 0, 0, 0);
-        accs = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, ones, accs, 0, 0, 0);
+        accs = sm::mma<F16>(a, ones, accs);
     };
 
     // Two workgroups share a compute unit and the instruction arbiter favours the older wave, so
@@ -893,7 +995,7 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
 #pragma unroll
         for (int v = 0; v < 4; ++v)
             red[(wave * 32 + c * 4 + v) * 64 + lane] =
-                (acc[c][v] - 128.0f * accs[v]) * (1.0f / (float)(1 << BG::field_pos(c))) - accz[v];
+                (acc[c][v] - NF::OFFSET * accs[v]) * (1.0f / (float)(1 << BG::field_pos(c))) + (F16 ? accz[v] : -accz[v]);
     __syncthreads();
     // thread (wave, lane) finishes D register v = wave of lane's position: row 4j + wave, 8 adjacent k
     float y[8];
@@ -914,6 +1016,7 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
 
 // Sum of the N slices' partial tiles, adapter term, bfloat16 store.  One workgroup per 128
 // columns: thread t owns row t / 16, columns 8 (t % 16) .. + 7.
+template <bool F16>
 __global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(SmallBwdDev d) {
     __shared__ float Ts[16 * 64];
     const int tid = threadIdx.x, K = d.w.K;
@@ -943,7 +1046,7 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(Small
     smallm_sum_parts(d.Tpart, d.n_proj, d.r, Ts);
     if (blockIdx.x == 0 && d.T_out != nullptr)
         for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.T_out[t] = Ts[t];
-    if (m < d.M) smallm_bwd_store8(d, Ts, m, k0, y);
+    if (m < d.M) smallm_bwd_store8<F16>(d, Ts, m, k0, y);
 }
 
 namespace {
@@ -1048,14 +1151,22 @@ size_t smallm_fwd_ws_bytes(const LayerView &w, int r) {
     return small_ws(w.K, w.N, r).yacc + (((size_t)ksplit * 16 * w.N * 4 + 255) & ~(size_t)255);
 }
 
-template <int BITS, bool SPG1>
+template <int BITS, bool SPG1, bool F16>
 static hipError_t launch_fwd_bits(const SmallFwdDev &d, int col_blocks, size_t lds_bytes, hipStream_t stream) {
-    auto kern = smallm_fwd_kernel<BITS, SPG1>;
+    auto kern = smallm_fwd_kernel<BITS, SPG1, F16>;
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
     if (e != hipSuccess) return e;
-    launch_kernel("stream_fwd", kern, col_blocks * d.ksplit + d.n_proj, sm::FWD_THREADS, lds_bytes, stream, d);
+    launch_kernel(F16 ? "f16_stream_fwd" : "stream_fwd", kern, col_blocks * d.ksplit + d.n_proj, sm::FWD_THREADS, lds_bytes, stream, d);
     return hipGetLastError();
+}
+template <bool F16>
+static hipError_t launch_fwd_any(const SmallFwdDev &d, int bits, bool spg1, int col_blocks, size_t lds_bytes, hipStream_t stream) {
+    switch (bits) {
+        case 2: return spg1 ? launch_fwd_bits<2, true, F16>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<2, false, F16>(d, col_blocks, lds_bytes, stream);
+        case 3: return spg1 ? launch_fwd_bits<3, true, F16>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<3, false, F16>(d, col_blocks, lds_bytes, stream);
+        default: return spg1 ? launch_fwd_bits<4, true, F16>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<4, false, F16>(d, col_blocks, lds_bytes, stream);
+    }
 }
 
 hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
@@ -1083,30 +1194,39 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     d.Y = a.out;
     d.XA = a.P_out;
     d.Yacc = Yacc;
+    d.zeros16 = a.zeros16;
+    d.bias16 = a.bias16;
     // LDS for the largest slice: ceil(groups / ksplit) groups of 32 bytes per contraction element
     const int n_groups = K / a.w.group;
     size_t lds_bytes = (size_t)((n_groups + ksplit - 1) / ksplit) * a.w.group * 32;
     if (lds_bytes < 32 * 1024) lds_bytes = 32 * 1024;      // the projection workgroups' wave reduction
     const int kstep = a.w.bits == 4 ? 32 : (a.w.bits == 2 ? 64 : 128);
     const bool spg1 = a.w.group == kstep;             // one step per quantization group
-    switch (a.w.bits) {
-        case 2: e = spg1 ? launch_fwd_bits<2, true>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<2, false>(d, col_blocks, lds_bytes, stream); break;
-        case 3: e = spg1 ? launch_fwd_bits<3, true>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<3, false>(d, col_blocks, lds_bytes, stream); break;
-        default: e = spg1 ? launch_fwd_bits<4, true>(d, col_blocks, lds_bytes, stream) : launch_fwd_bits<4, false>(d, col_blocks, lds_bytes, stream); break;
-    }
+    e = a.f16 ? launch_fwd_any<true>(d, a.w.bits, spg1, col_blocks, lds_bytes, stream)
+              : launch_fwd_any<false>(d, a.w.bits, spg1, col_blocks, lds_bytes, stream);
     if (e != hipSuccess) return e;
-    launch_kernel("stream_fwd_finish", smallm_fwd_finish_kernel, (N + 63) / 64, sm::WG_THREADS, 0, stream, d);
+    if (a.f16) launch_kernel("f16_stream_fwd_finish", smallm_fwd_finish_kernel<true>, (N + 63) / 64, sm::WG_THREADS, 0, stream, d);
+    else launch_kernel("stream_fwd_finish", smallm_fwd_finish_kernel<false>, (N + 63) / 64, sm::WG_THREADS, 0, stream, d);
     return hipGetLastError();
 }
 
-template <int BITS>
+template <int BITS, bool F16>
 static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, hipStream_t stream) {
-    auto kern = smallm_bwd_kernel<BITS>;
+    auto kern = smallm_bwd_kernel<BITS, F16>;
     static bool configured[64] = {};
-    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)BwdGeo<BITS>::LDS_BYTES, configured);
+    constexpr size_t LDS = (size_t)BwdGeo<BITS, F16>::LDS_BYTES;
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), LDS, configured);
     if (e != hipSuccess) return e;
-    launch_kernel("stream_bwd", kern, k_blocks * d.nsplit + d.n_proj, sm::WG_THREADS, (size_t)BwdGeo<BITS>::LDS_BYTES, stream, d);
+    launch_kernel(F16 ? "f16_stream_bwd" : "stream_bwd", kern, k_blocks * d.nsplit + d.n_proj, sm::WG_THREADS, LDS, stream, d);
     return hipGetLastError();
+}
+template <bool F16>
+static hipError_t launch_bwd_any(const SmallBwdDev &d, int bits, int k_blocks, hipStream_t stream) {
+    switch (bits) {
+        case 2: return launch_bwd_bits<2, F16>(d, k_blocks, stream);
+        case 3: return launch_bwd_bits<3, F16>(d, k_blocks, stream);
+        default: return launch_bwd_bits<4, F16>(d, k_blocks, stream);
+    }
 }
 
 hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
@@ -1133,13 +1253,11 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     d.dX = a.out;
     d.T_out = a.P_out;
     d.acc = reinterpret_cast<float *>(ws + l.yacc);
-    switch (a.w.bits) {
-        case 2: e = launch_bwd_bits<2>(d, k_blocks, stream); break;
-        case 3: e = launch_bwd_bits<3>(d, k_blocks, stream); break;
-        default: e = launch_bwd_bits<4>(d, k_blocks, stream); break;
-    }
+    d.zeros16 = a.zeros16;
+    e = a.f16 ? launch_bwd_any<true>(d, a.w.bits, k_blocks, stream) : launch_bwd_any<false>(d, a.w.bits, k_blocks, stream);
     if (e != hipSuccess) return e;
-    launch_kernel("stream_bwd_finish", smallm_bwd_finish_kernel, k_blocks, sm::WG_THREADS, 0, stream, d);
+    if (a.f16) launch_kernel("f16_stream_bwd_finish", smallm_bwd_finish_kernel<true>, k_blocks, sm::WG_THREADS, 0, stream, d);
+    else launch_kernel("stream_bwd_finish", smallm_bwd_finish_kernel<false>, k_blocks, sm::WG_THREADS, 0, stream, d);
     return hipGetLastError();
 }
 

@@ -32,10 +32,10 @@ def oargs(L):
     return (L["qweight"], L["scales"], L["zeros_f16"], L["K"], L["N"], L["bits"], L["group"])
 
 
-def tight(name, got, ref, n_sum, out_f16=True):
+def tight(name, got, ref, n_sum, out_f16=True, extra=0.0):
     """One binary16 rounding of the output (2^-11 relative) plus fp32 accumulation over n_sum terms."""
     scale = np.abs(ref).max()
-    tol = (2.0 ** -10 if out_f16 else 2.0 ** -20) * np.abs(ref) + (4e-7 * np.sqrt(n_sum) + 2e-5) * scale
+    tol = (2.0 ** -10 if out_f16 else 2.0 ** -20) * np.abs(ref) + (4e-7 * np.sqrt(n_sum) + 2e-5) * scale + extra
     bad = np.abs(got - ref) > tol
     assert not bad.any(), "%s: %d elements off, worst %g (scale %g)" % (name, int(bad.sum()), float(np.abs(got - ref).max()), scale)
 
@@ -70,7 +70,43 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("bits,K,N,M,r,group,bias", SHAPES)
+# M <= 16 with shapes the streaming kernels accept: forward only (ragged last column block, group
+# sizes down to one step), forward and backward (N and group multiples of 128), and N split over
+# workgroups whose waves get unequal numbers of steps
+STREAM_SHAPES = [
+    (3, 1024, 808, 16, 8, 128, True),
+    (3, 2560, 264, 3, 5, 256, False),
+    (2, 768, 296, 5, 4, 64, True),
+    (2, 1024, 1032, 16, 16, 128, True),
+    (4, 512, 1304, 1, 16, 32, True),
+    (4, 1152, 520, 13, 40, 128, False),
+    (3, 1536, 512, 9, 0, 1536, True),        # one (scale, zero) pair per row, no adapter
+    (3, 1024, 768, 16, 8, 128, True),
+    (3, 2560, 384, 3, 5, 256, True),
+    (2, 1024, 1152, 5, 16, 256, False),
+    (4, 1152, 640, 13, 40, 128, True),
+    (4, 512, 2304, 1, 16, 512, True),
+    (2, 768, 128, 16, 0, 768, False),
+    (3, 1024, 2176, 11, 8, 128, True),
+    (4, 512, 2176, 16, 4, 128, True),
+    (2, 1024, 2176, 2, 8, 256, True),
+]
+
+
+def code_domain_allowance(D, M):
+    """What the M <= 16 streaming kernels may differ by from materialize-then-multiply: they multiply
+    by the codes directly, so What is not rounded to binary16 first (2^-11 relative per weight), and
+    the backward kernel rounds dY * scale to binary16 (another 2^-11 per term; a product below the
+    normal range keeps 2^-25 absolute)."""
+    if M > 16:
+        return 0.0, 0.0
+    Wabs = np.abs(synth.f16_bits_to_f64(pl.dequant_f16(*oargs(D))))          # [N][K]
+    Xabs, dYabs = np.abs(synth.f16_bits_to_f64(D["X"])), np.abs(synth.f16_bits_to_f64(D["dY"]))
+    qmax = float((1 << D["bits"]) - 1)
+    return 2.0 ** -11 * (Xabs @ Wabs.T), 2.0 ** -10 * (dYabs @ Wabs) + 2.0 ** -25 * qmax * D["N"]
+
+
+@pytest.mark.parametrize("bits,K,N,M,r,group,bias", SHAPES + STREAM_SHAPES)
 def test_forward_backward_against_oracle(bits, K, N, M, r, group, bias):
     D = layer(bits, K, N, M, r, group, with_bias=bias)
     s = D["lora_scale"]
@@ -79,10 +115,11 @@ def test_forward_backward_against_oracle(bits, K, N, M, r, group, bias):
     dX, T = b.modulora_f16_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], s)
     Yr, XAr = pl.fwd(*oargs(D), D["X"], A, B, s, D["bias"])
     dXr, Tr = pl.bwd_input(*oargs(D), D["dY"], A, B, s)
+    extra_Y, extra_dX = code_domain_allowance(D, M)
     assert_bar("Y", f64(Y), Yr)
     assert_bar("dX", f64(dX), dXr)
-    tight("Y", f64(Y), Yr, K + r)
-    tight("dX", f64(dX), dXr, N + r)
+    tight("Y", f64(Y), Yr, K + r, extra=extra_Y)
+    tight("dX", f64(dX), dXr, N + r, extra=extra_dX)
     if r:
         tight("XA", f64(XA), XAr, K, out_f16=False)
         tight("dYBt", f64(T), Tr, N, out_f16=False)
@@ -108,6 +145,65 @@ def test_one_hot_activations_pick_out_single_weights():
     eyeN = torch.eye(264, dtype=torch.float16, device="cuda")
     dX, _ = b.modulora_f16_bwd_input(D["w"], eyeN[100:101].contiguous(), None, None, 1.0)
     assert np.array_equal(dX.view(torch.int16).cpu().numpy().view(np.uint16), What[100:101])
+
+
+def test_streaming_shapes_run_the_streaming_kernels():
+    """The M <= 16 shapes above do reach the streaming kernels (in both directions where N and the
+    group size allow)."""
+    D = layer(3, 1024, 768, 16, 8, 128)
+    b.modulora_profile_begin()
+    b.modulora_f16_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], 2.0)
+    b.modulora_f16_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], 2.0)
+    torch.cuda.synchronize()
+    names = set(b.modulora_profile_end())
+    assert {"f16_stream_fwd", "f16_stream_fwd_finish", "f16_stream_bwd", "f16_stream_bwd_finish"} <= names, names
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_streaming_kernels_pick_out_single_weights(bits):
+    """One-hot rows through the M <= 16 streaming kernels: a single nonzero term, so the direct
+    product with the codes must land on the same binary16 as the materialized weight -- in both
+    directions (a one-hot 1.0 times the scale is the scale itself, so nothing is rounded early)."""
+    K, N, group = 512, 384, 128
+    D = layer(bits, K, N, 1, 0, group, seed=6, with_bias=False)
+    What = pl.dequant_f16(*oargs(D))
+    eyeK = torch.eye(K, dtype=torch.float16, device="cuda")
+    for lo in (0, 100, 497):
+        Y, _ = b.modulora_f16_fwd(D["w"], eyeK[lo:lo + 15].contiguous(), None, None, 1.0)
+        assert np.array_equal(Y.view(torch.int16).cpu().numpy().view(np.uint16), What.T[lo:lo + 15])
+    eyeN = torch.eye(N, dtype=torch.float16, device="cuda")
+    for lo in (0, 368):
+        dX, _ = b.modulora_f16_bwd_input(D["w"], eyeN[lo:lo + 16].contiguous(), None, None, 1.0)
+        assert np.array_equal(dX.view(torch.int16).cpu().numpy().view(np.uint16), What[lo:lo + 16])
+
+
+def test_full_size_attention_projection_at_sixteen_tokens():
+    """LLaMA-65B attention projection (8192 x 8192, 3-bit, group 128) at M = 16 in the paper's storage
+    convention: the streaming kernels in the launch configuration of the full-size layer."""
+    cfg = synth.CONFIGS["c5_65b_attn"].with_M(16)
+    L = synth.make_layer_f16(cfg)
+    w = b.QWeightF16.from_numpy(L["qweight"], L["scales"], L["zeros_f16"], L["bias"], cfg.K, cfg.N, cfg.bits, cfg.group)
+    Xd, dYd = f16_dev(L["X"]), f16_dev(L["dY"])
+    Ad, Bd = torch.from_numpy(L["A"]).cuda(), torch.from_numpy(L["B"]).cuda()
+    s = L["lora_scale"]
+    b.modulora_profile_begin()
+    Y, XA = b.modulora_f16_fwd(w, Xd, Ad, Bd, s)
+    dX, T = b.modulora_f16_bwd_input(w, dYd, Ad, Bd, s)
+    torch.cuda.synchronize()
+    assert {"f16_stream_fwd", "f16_stream_bwd"} <= set(b.modulora_profile_end())
+    Yr, XAr = pl.fwd(*oargs(L), L["X"], L["A"], L["B"], s, L["bias"])
+    dXr, Tr = pl.bwd_input(*oargs(L), L["dY"], L["A"], L["B"], s)
+    extra_Y, extra_dX = code_domain_allowance(L, 16)
+    assert_bar("Y", f64(Y), Yr)
+    assert_bar("dX", f64(dX), dXr)
+    tight("Y", f64(Y), Yr, cfg.K + cfg.r, extra=extra_Y)
+    tight("dX", f64(dX), dXr, cfg.N + cfg.r, extra=extra_dX)
+    tight("XA", f64(XA), XAr, cfg.K, out_f16=False)
+    tight("dYBt", f64(T), Tr, cfg.N, out_f16=False)
+    dA, dB = b.modulora_f16_bwd_lora(Xd, dYd, Ad, Bd, s, XA=XA, dYBt=T)
+    dAr, dBr = pl.bwd_lora(L["X"], L["dY"], L["A"], L["B"], s)
+    tight("dA", f64(dA), dAr, 16 + cfg.N, out_f16=False)
+    tight("dB", f64(dB), dBr, 16 + cfg.K, out_f16=False)
 
 
 def test_one_hot_activations_through_the_producer_consumer_kernel():
