@@ -158,7 +158,7 @@ int modulora_fwd_static(const modulora_qweight *w, const uint16_t *X, int32_t M,
  *   dYBt [M][r] float32 (out, may be NULL)
  * No gradient flows to qweight, scales or zeros.
  * Arithmetic by token count, as for modulora_fwd: at M <= 16 (when d_out is a multiple of
- * 128 and group_size a multiple of 128) the codes are multiplied directly and the scaled
+ * 128, d_in a multiple of 128 and group_size 64 or a multiple of 128) the codes are multiplied directly and the scaled
  * activation dY[m][n] * scales[g][n] is rounded to bfloat16 before the product; the result
  * differs from the materialized form by at most 2^-7 sum_n |dY[m][n]| |What[n][k]|.
  */

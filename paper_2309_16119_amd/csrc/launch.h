@@ -161,6 +161,8 @@ inline DownPlan lora_down_plan(int M, int C, int r) {
         const int by_depth = C / (32 * 16 * 2);
         if (split > by_depth) split = by_depth;
         if (split > 16) split = 16;
+        // (measured at 512 tokens x 4096: one launch with 8 steps per wave takes 10-11 us, the split
+        // launch plus its finish kernel 5-6 + 4-5 us, and the whole call 3 us less)
         if (split >= 2) p.split = split;
     }
     return p;

@@ -730,12 +730,14 @@ __device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const fl
 // results through LDS at the end.  Lane l = 16 j + i: i = 4 u + b picks the 32-code block b of
 // the tile and the 8 codes 8u .. 8u+7 of it (MFMA call c handles code 8u + c, so the lane's
 // outputs are 8 adjacent k), j picks 8 adjacent n of the step.
-template <int BITS, bool F16 = false>
+// GPT: quantization groups per 128-column tile (1: group a multiple of 128; 2: group 64).
+template <int BITS, bool F16 = false, int GPT = 1>
 struct BwdGeo {
     static constexpr int WR = 4 * BITS;                // word rows of the 128-column tile
-    // 16-byte pieces of one stage: word rows (8 per row), scales (4), zeros (2 of uint8, or 4 of
-    // binary16), dY (16 rows x 4)
-    static constexpr int W_PIECES = WR * 8, S_PIECE0 = W_PIECES, Z_PIECE0 = W_PIECES + 4, Y_PIECE0 = Z_PIECE0 + (F16 ? 4 : 2);
+    // 16-byte pieces of one stage: word rows (8 per row), per group of the tile scales (4) and zeros
+    // (2 of uint8, or 4 of binary16), dY (16 rows x 4)
+    static constexpr int Z_PER_GROUP = F16 ? 4 : 2;
+    static constexpr int W_PIECES = WR * 8, S_PIECE0 = W_PIECES, Z_PIECE0 = S_PIECE0 + 4 * GPT, Y_PIECE0 = Z_PIECE0 + Z_PER_GROUP * GPT;
     static constexpr int N_PIECES = Y_PIECE0 + 64;
     static constexpr int NI = (N_PIECES + 63) / 64;    // loads per stage
     static constexpr int STAGE_BYTES = NI * 1024;
@@ -758,9 +760,9 @@ struct BwdGeo {
     }
 };
 
-template <int BITS, bool F16>
+template <int BITS, bool F16, int GPT>
 __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdDev d) {
-    using BG = BwdGeo<BITS, F16>;
+    using BG = BwdGeo<BITS, F16, GPT>;
     using NF = sm::Num<F16>;
     extern __shared__ __attribute__((aligned(16))) uint4 ys[];   // [wave][stage] private stages, later the reduction
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -779,7 +781,7 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     const int S0 = (int)((long)n_steps * ns / d.nsplit), S1 = (int)((long)n_steps * (ns + 1) / d.nsplit);
     // this wave's steps: S0 + wave + 4 t, t = 0 .. nw - 1
     const int nw = S1 - S0 > wave ? (S1 - S0 - wave + sm::WG_WAVES - 1) / sm::WG_WAVES : 0;
-    const int g = kt / d.w.group;
+    const int g = kt / d.w.group;        // first of the tile's GPT quantization groups
 
     // word rows of this lane, relative to the first word row of the tile
     constexpr int NROWS = BITS == 3 ? 2 : 1;
@@ -815,10 +817,12 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
             gaddr[q] = reinterpret_cast<const char *>(wtile) + ((size_t)row * N + pp * 4) * 4;
             gstr[q] = smb::NSTEP * 4;
         } else if (pc < BG::Z_PIECE0) {
-            gaddr[q] = reinterpret_cast<const char *>(stile) + (pc - BG::S_PIECE0) * 16;
+            const int sp = pc - BG::S_PIECE0;          // group sp / 4 of the tile, piece sp % 4 of its 64 bytes
+            gaddr[q] = reinterpret_cast<const char *>(stile) + (size_t)(sp >> 2) * N * 2 + (sp & 3) * 16;
             gstr[q] = smb::NSTEP * 2;
         } else if (pc < BG::Y_PIECE0) {
-            gaddr[q] = ztile + (pc - BG::Z_PIECE0) * 16;
+            const int zp = pc - BG::Z_PIECE0;
+            gaddr[q] = ztile + (size_t)(zp / BG::Z_PER_GROUP) * N * (F16 ? 2 : 1) + (zp % BG::Z_PER_GROUP) * 16;
             gstr[q] = smb::NSTEP * (F16 ? 2 : 1);
         } else {
             const int yp = pc < BG::N_PIECES ? pc - BG::Y_PIECE0 : 0;
@@ -844,14 +848,18 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
 #pragma unroll
     for (int dd = 0; dd < DEPTH; ++dd) issue(dd, wave_step(dd));
 
-    f32x4 acc[8], accz, accs;
+    // per quantization group of the tile: the scaled activations differ, so each group has its own
+    // products (a lane keeps the ones of the group its output columns lie in)
+    f32x4 acc[GPT][8], accz[GPT], accs[GPT];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
+    for (int gi = 0; gi < GPT; ++gi)
 #pragma unroll
-        for (int c = 0; c < 8; ++c) acc[c][v] = 0.f;
-        accz[v] = 0.f;
-        accs[v] = 0.f;
-    }
+        for (int v = 0; v < 4; ++v) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[gi][c][v] = 0.f;
+            accz[gi][v] = 0.f;
+            accs[gi][v] = 0.f;
+        }
     const uint32_t ones4[4] = {NF::ONES, NF::ONES, NF::ONES, NF::ONES};
     const bf16x8 ones = sm::as_bf16x8(ones4);
     // field masks at the positions field_pos() can return (multiples of BITS)
@@ -861,9 +869,9 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
 
     struct Stage {
         sm::u32x4 w[NROWS][2];   // 8 adjacent n of each word row
-        sm::u32x4 sc;            // 8 binary16 scales
-        sm::u32x2 z;             // 8 integer zero points (bfloat16 layer)
-        sm::u32x4 z16;           // 8 binary16 zero points (F16)
+        sm::u32x4 sc[GPT];       // 8 binary16 scales per group
+        sm::u32x2 z[GPT];        // 8 integer zero points (bfloat16 layer)
+        sm::u32x4 z16[GPT];      // 8 binary16 zero points (F16)
         sm::u32x4 y;             // dY[i][8 n]
     };
     // marks a register set as complete (call after a wait for the LDS reads that fill it), so
@@ -875,8 +883,11 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
             sm::tie(sd.w[NROWS - 1][0]);
             sm::tie(sd.w[NROWS - 1][1]);
         }
-        sm::tie(sd.sc);
-        if (F16) sm::tie(sd.z16); else sm::tie(sd.z);
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi) {
+            sm::tie(sd.sc[gi]);
+            if (F16) sm::tie(sd.z16[gi]); else sm::tie(sd.z[gi]);
+        }
         sm::tie(sd.y);
     };
     // a landed stage, LDS -> registers
@@ -888,22 +899,29 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
             sd.w[NROWS - 1][0] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j) ^ BG::swz(row1)) << 4));
             sd.w[NROWS - 1][1] = *reinterpret_cast<const sm::u32x4 *>(sb + row1 * 128 + (((2 * j + 1) ^ BG::swz(row1)) << 4));
         }
-        sd.sc = *reinterpret_cast<const sm::u32x4 *>(sb + BG::S_PIECE0 * 16 + 16 * j);
-        if (F16) sd.z16 = *reinterpret_cast<const sm::u32x4 *>(sb + BG::Z_PIECE0 * 16 + 16 * j);
-        else sd.z = *reinterpret_cast<const sm::u32x2 *>(sb + BG::Z_PIECE0 * 16 + 8 * j);
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi) {
+            sd.sc[gi] = *reinterpret_cast<const sm::u32x4 *>(sb + (BG::S_PIECE0 + 4 * gi) * 16 + 16 * j);
+            if (F16) sd.z16[gi] = *reinterpret_cast<const sm::u32x4 *>(sb + (BG::Z_PIECE0 + 4 * gi) * 16 + 16 * j);
+            else sd.z[gi] = *reinterpret_cast<const sm::u32x2 *>(sb + (BG::Z_PIECE0 + 2 * gi) * 16 + 8 * j);
+        }
         sd.y = *reinterpret_cast<const sm::u32x4 *>(sb + (BG::Y_PIECE0 + 16 * j + i) * 16);
     };
     auto compute = [&](const Stage &sd) {
-        // A operand: dY[i][8 n] * scale[g][8 n], rounded to the activations' 16-bit format
+        // A operands: dY[i][8 n] * scale[group][8 n], rounded to the activations' 16-bit format
         const uint32_t yw[4] = {sd.y[0], sd.y[1], sd.y[2], sd.y[3]};
-        uint32_t areg[4];
+        bf16x8 a[GPT];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const float y0 = sm::widen16<F16>(yw[p] & 0xFFFFu), y1 = sm::widen16<F16>(yw[p] >> 16);
-            const float s0 = half_bits_to_float((uint16_t)(sd.sc[p] & 0xFFFFu)), s1 = half_bits_to_float((uint16_t)(sd.sc[p] >> 16));
-            areg[p] = sm::pack16<F16>(y0 * s0, y1 * s1);
+        for (int gi = 0; gi < GPT; ++gi) {
+            uint32_t areg[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const float y0 = sm::widen16<F16>(yw[p] & 0xFFFFu), y1 = sm::widen16<F16>(yw[p] >> 16);
+                const float s0 = half_bits_to_float((uint16_t)(sd.sc[gi][p] & 0xFFFFu)), s1 = half_bits_to_float((uint16_t)(sd.sc[gi][p] >> 16));
+                areg[p] = sm::pack16<F16>(y0 * s0, y1 * s1);
+            }
+            a[gi] = sm::as_bf16x8(areg);
         }
-        const bf16x8 a = sm::as_bf16x8(areg);
         // the lane's 8 codes of each of its 8 n, at bit 0 of ch[e]
         uint32_t ch[8];
 #pragma unroll
@@ -936,23 +954,28 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
                 else x = c < 5 ? plo[p] >> (6 * (c / 2)) : phi[p] >> (c < 7 ? 7 : 13);
                 o[p] = sm::and_or(x, fmask[BG::field_pos(c) / BITS], magic);
             }
-            acc[c] = sm::mma<F16>(a, sm::as_bf16x8(o), acc[c]);
-        }
-        if (F16) {
-            // the added zero point: sum_n dY[m][n] z[g][n], with the unscaled dY and z as stored
-            const uint32_t zo[4] = {sd.z16[0], sd.z16[1], sd.z16[2], sd.z16[3]};
-            accz = sm::mma<F16>(sm::as_bf16x8(yw), sm::as_bf16x8(zo), accz);
-        } else {
-            // integer zero points as exact bfloat16: sum_n (dY scale)[m][n] zero[g][n]
-            uint32_t zo[4];
+            const bf16x8 ob = sm::as_bf16x8(o);
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const uint32_t zw = sd.z[p >> 1] >> (16 * (p & 1));
-                zo[p] = pack_bf16x2((float)(zw & 0xFFu), (float)((zw >> 8) & 0xFFu));
-            }
-            accz = sm::mma<F16>(a, sm::as_bf16x8(zo), accz);
+            for (int gi = 0; gi < GPT; ++gi) acc[gi][c] = sm::mma<F16>(a[gi], ob, acc[gi][c]);
         }
-        accs = sm::mma<F16>(a, ones, accs);
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi) {
+            if (F16) {
+                // the added zero point: sum_n dY[m][n] z[group][n], with the unscaled dY and z as stored
+                const uint32_t zo[4] = {sd.z16[gi][0], sd.z16[gi][1], sd.z16[gi][2], sd.z16[gi][3]};
+                accz[gi] = sm::mma<F16>(sm::as_bf16x8(yw), sm::as_bf16x8(zo), accz[gi]);
+            } else {
+                // integer zero points as exact bfloat16: sum_n (dY scale)[m][n] zero[group][n]
+                uint32_t zo[4];
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const uint32_t zw = sd.z[gi][p >> 1] >> (16 * (p & 1));
+                    zo[p] = pack_bf16x2((float)(zw & 0xFFu), (float)((zw >> 8) & 0xFFu));
+                }
+                accz[gi] = sm::mma<F16>(a[gi], sm::as_bf16x8(zo), accz[gi]);
+            }
+            accs[gi] = sm::mma<F16>(a[gi], ones, accs[gi]);
+        }
     };
 
     // Two workgroups share a compute unit and the instruction arbiter favours the older wave, so
@@ -994,8 +1017,13 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     for (int c = 0; c < 8; ++c)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
+        {
+            // the lane's output columns lie in 32-code block b of the tile: group b * GPT / 4
+            float av = acc[0][c][v], sv = accs[0][v], zv = accz[0][v];
+            if (GPT == 2 && b >= 2) { av = acc[GPT - 1][c][v]; sv = accs[GPT - 1][v]; zv = accz[GPT - 1][v]; }
             red[(wave * 32 + c * 4 + v) * 64 + lane] =
-                (acc[c][v] - NF::OFFSET * accs[v]) * (1.0f / (float)(1 << BG::field_pos(c))) + (F16 ? accz[v] : -accz[v]);
+                (av - NF::OFFSET * sv) * (1.0f / (float)(1 << BG::field_pos(c))) + (F16 ? zv : -zv);
+        }
     __syncthreads();
     // thread (wave, lane) finishes D register v = wave of lane's position: row 4j + wave, 8 adjacent k
     float y[8];
@@ -1108,7 +1136,9 @@ int pick_nsplit(int N, int K) {
 
 bool smallm_bwd_supported(const LayerView &w, int M) {
     if (M > 16) return false;
-    return w.group % smb::KT == 0 && w.N % sm::PREP_K == 0 && pick_nsplit(w.N, w.K) > 0;
+    // a 128-column tile lies inside one quantization group, or covers exactly two
+    const bool group_ok = w.group % smb::KT == 0 || w.group == smb::KT / 2;
+    return group_ok && w.K % smb::KT == 0 && w.N % sm::PREP_K == 0 && pick_nsplit(w.N, w.K) > 0;
 }
 
 bool smallm_fwd_supported(const LayerView &w, int M) {
@@ -1210,11 +1240,11 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     return hipGetLastError();
 }
 
-template <int BITS, bool F16>
+template <int BITS, bool F16, int GPT>
 static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, hipStream_t stream) {
-    auto kern = smallm_bwd_kernel<BITS, F16>;
+    auto kern = smallm_bwd_kernel<BITS, F16, GPT>;
     static bool configured[64] = {};
-    constexpr size_t LDS = (size_t)BwdGeo<BITS, F16>::LDS_BYTES;
+    constexpr size_t LDS = (size_t)BwdGeo<BITS, F16, GPT>::LDS_BYTES;
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), LDS, configured);
     if (e != hipSuccess) return e;
     launch_kernel(F16 ? "f16_stream_bwd" : "stream_bwd", kern, k_blocks * d.nsplit + d.n_proj, sm::WG_THREADS, LDS, stream, d);
@@ -1222,10 +1252,11 @@ static hipError_t launch_bwd_bits(const SmallBwdDev &d, int k_blocks, hipStream_
 }
 template <bool F16>
 static hipError_t launch_bwd_any(const SmallBwdDev &d, int bits, int k_blocks, hipStream_t stream) {
+    const bool two = d.w.group == smb::KT / 2;      // two quantization groups per 128-column tile
     switch (bits) {
-        case 2: return launch_bwd_bits<2, F16>(d, k_blocks, stream);
-        case 3: return launch_bwd_bits<3, F16>(d, k_blocks, stream);
-        default: return launch_bwd_bits<4, F16>(d, k_blocks, stream);
+        case 2: return two ? launch_bwd_bits<2, F16, 2>(d, k_blocks, stream) : launch_bwd_bits<2, F16, 1>(d, k_blocks, stream);
+        case 3: return two ? launch_bwd_bits<3, F16, 2>(d, k_blocks, stream) : launch_bwd_bits<3, F16, 1>(d, k_blocks, stream);
+        default: return two ? launch_bwd_bits<4, F16, 2>(d, k_blocks, stream) : launch_bwd_bits<4, F16, 1>(d, k_blocks, stream);
     }
 }
 

@@ -87,6 +87,9 @@ STREAM_SHAPES = [
     (4, 1152, 640, 13, 40, 128, True),
     (4, 512, 2304, 1, 16, 512, True),
     (2, 768, 128, 16, 0, 768, False),
+    (2, 768, 384, 5, 4, 64, True),           # two quantization groups per 128-column backward tile
+    (3, 1024, 2176, 11, 8, 64, False),
+    (4, 512, 640, 16, 16, 64, True),
     (3, 1024, 2176, 11, 8, 128, True),
     (4, 512, 2176, 16, 4, 128, True),
     (2, 1024, 2176, 2, 8, 256, True),
@@ -159,12 +162,13 @@ def test_streaming_shapes_run_the_streaming_kernels():
     assert {"f16_stream_fwd", "f16_stream_fwd_finish", "f16_stream_bwd", "f16_stream_bwd_finish"} <= names, names
 
 
+@pytest.mark.parametrize("group", [128, 64])
 @pytest.mark.parametrize("bits", [2, 3, 4])
-def test_streaming_kernels_pick_out_single_weights(bits):
+def test_streaming_kernels_pick_out_single_weights(bits, group):
     """One-hot rows through the M <= 16 streaming kernels: a single nonzero term, so the direct
     product with the codes must land on the same binary16 as the materialized weight -- in both
     directions (a one-hot 1.0 times the scale is the scale itself, so nothing is rounded early)."""
-    K, N, group = 512, 384, 128
+    K, N = 512, 384
     D = layer(bits, K, N, 1, 0, group, seed=6, with_bias=False)
     What = pl.dequant_f16(*oargs(D))
     eyeK = torch.eye(K, dtype=torch.float16, device="cuda")

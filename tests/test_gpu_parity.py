@@ -88,6 +88,10 @@ SHAPES = [
     (4, 1152, 640, 13, 40, 128),
     (4, 512, 2304, 1, 16, 512),
     (2, 768, 128, 16, 0, 768),
+    # ... with two quantization groups per 128-column backward tile (group 64)
+    (2, 768, 384, 5, 4, 64),
+    (3, 1024, 2176, 11, 8, 64),
+    (4, 512, 640, 16, 16, 64),
     # ... with N split over several workgroups whose waves get unequal numbers of steps
     (3, 1024, 2176, 11, 8, 128),
     (4, 512, 2176, 16, 4, 128),
@@ -167,11 +171,25 @@ def test_forward_backward_against_oracle(bits, K, N, M, r, group):
         assert_tight("dB", f64(dB), dBr, False, M * K)
 
 
+def test_small_token_counts_run_the_streaming_kernels():
+    """BASELINE config 1 (group 64) and a group-128 layer reach the streaming kernels in both directions."""
+    for bits, K, N, group in ((4, 256, 256, 64), (3, 1024, 768, 128)):
+        L = layer(bits, K, N, 16, 8, group, seed=2)
+        D = to_device(L)
+        b.modulora_profile_begin()
+        b.modulora_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], 2.0)
+        b.modulora_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], 2.0)
+        torch.cuda.synchronize()
+        names = set(b.modulora_profile_end())
+        assert {"stream_fwd", "stream_fwd_finish", "stream_bwd", "stream_bwd_finish"} <= names, (group, names)
+
+
+@pytest.mark.parametrize("group", [128, 64])
 @pytest.mark.parametrize("bits", [2, 3, 4])
-def test_streaming_kernels_pick_out_single_weights(bits):
+def test_streaming_kernels_pick_out_single_weights(bits, group):
     """One-hot rows through the M <= 16 streaming kernels: a single nonzero term, so the
     code-domain arithmetic must land on the same bfloat16 as the materialized weight."""
-    K, N, group = 512, 384, 128
+    K, N = 512, 384
     L = layer(bits, K, N, 1, 0, group, seed=6)
     D = to_device(L)
     What = oracle.dequant_bf16(*oracle_args(L))
