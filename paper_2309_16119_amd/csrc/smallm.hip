@@ -236,34 +236,57 @@ __device__ __forceinline__ void smallm_project(const uint16_t *act, int M, int C
 // The same projection for binary16 activations (the layer in the paper's own storage convention),
 // in plain fp32 on the vector ALUs: a binary16 activation does not fit a bfloat16 operand, and at
 // most 16 rows by a few thousand contraction elements per workgroup are too little work to matter.
-// Thread t: row t % 16, contraction elements (t / 16) + k * (threads / 16) of the workgroup's range;
-// the threads' sums meet in LDS.  Same partial layout as above: one [16][r] per workgroup.
+// Thread t: row t % 16, chunks of 8 contraction elements (t / 16) + k * (threads / 16) of the
+// workgroup's range (one 16-byte activation load per chunk, and every factor load of the chunk in
+// flight with it); eight rank columns per pass; the threads' sums meet in LDS.  Same partial layout
+// as above: one [16][r] per workgroup.
 template <bool F_IS_A, int NWAVES>
 __device__ __forceinline__ void smallm_project_f16(const uint16_t *act, int M, int C, const float *F, int r, int blk,
-                                                   int nblk, float *parts, float *red /* LDS, NWAVES * 64 * 16 floats */) {
+                                                   int nblk, float *parts, float *red /* LDS, NWAVES * 64 * 8 floats */) {
     constexpr int NT = NWAVES * 64, KL = NT / 16;
     const int tid = threadIdx.x, m = tid & 15, kl = tid >> 4;
-    const int c0 = (int)((long)C * blk / nblk), c1 = (int)((long)C * (blk + 1) / nblk);
+    const int chunks = C >> 3;
+    const int ch0 = (int)((long)chunks * blk / nblk), ch1 = (int)((long)chunks * (blk + 1) / nblk);
     const uint16_t *arow = act + (size_t)(m < M ? m : M - 1) * C;
     float *mine = parts + (size_t)blk * 16 * r;
-    for (int j0 = 0; j0 < r; j0 += 16) {
-        float acc[16];
+    for (int j0 = 0; j0 < r; j0 += 8) {
+        float acc[8];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc[j] = 0.f;
-        for (int c = c0 + kl; c < c1; c += KL) {
-            const float x = half_bits_to_float(arow[c]);
+        for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+        for (int ch = ch0 + kl; ch < ch1; ch += KL) {
+            const int c = ch << 3;
+            const uint4 xv = *reinterpret_cast<const uint4 *>(arow + c);
+            const uint32_t xw[4] = {xv.x, xv.y, xv.z, xv.w};
+            float x[8];
 #pragma unroll
-            for (int j = 0; j < 16; ++j)
-                if (j0 + j < r) acc[j] = __builtin_fmaf(x, F_IS_A ? F[(size_t)c * r + j0 + j] : F[(size_t)(j0 + j) * C + c], acc[j]);
+            for (int e = 0; e < 8; ++e) x[e] = half_bits_to_float((uint16_t)(xw[e >> 1] >> (16 * (e & 1))));
+            float f[8][8];       // [rank column][contraction element]
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool ok = j0 + j < r;
+                if (F_IS_A) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) f[j][e] = ok ? F[(size_t)(c + e) * r + j0 + j] : 0.f;
+                } else {
+                    const float *src = F + (size_t)(ok ? j0 + j : 0) * C + c;     // 32-byte aligned: C is a multiple of 8
+                    const float4 q0 = *reinterpret_cast<const float4 *>(src), q1 = *reinterpret_cast<const float4 *>(src + 4);
+                    f[j][0] = q0.x; f[j][1] = q0.y; f[j][2] = q0.z; f[j][3] = q0.w;
+                    f[j][4] = q1.x; f[j][5] = q1.y; f[j][6] = q1.z; f[j][7] = q1.w;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[j] = __builtin_fmaf(x[e], f[j][e], acc[j]);
         }
         __syncthreads();                         // the previous pass has been read
 #pragma unroll
-        for (int j = 0; j < 16; ++j) red[(kl * 16 + m) * 16 + j] = acc[j];
+        for (int j = 0; j < 8; ++j) red[(kl * 16 + m) * 8 + j] = acc[j];
         __syncthreads();
-        if (tid < 256) {                         // (row, column) = (tid / 16, tid % 16)
+        if (tid < 128) {                         // (row, column) = (tid / 8, tid % 8)
             float sum = 0.f;
-            for (int q = 0; q < KL; ++q) sum += red[(q * 16 + (tid >> 4)) * 16 + (tid & 15)];
-            if (j0 + (tid & 15) < r) mine[(tid >> 4) * r + j0 + (tid & 15)] = sum;
+            for (int q = 0; q < KL; ++q) sum += red[(q * 16 + (tid >> 3)) * 8 + (tid & 7)];
+            if (j0 + (tid & 7) < r) mine[(tid >> 3) * r + j0 + (tid & 7)] = sum;
         }
     }
 }
@@ -271,12 +294,14 @@ __device__ __forceinline__ void smallm_project_f16(const uint16_t *act, int M, i
 // Sum of the projection workgroups' partials into Us (16 x r floats in LDS).
 __device__ __forceinline__ void smallm_sum_parts(const float *parts, int n_parts, int r, float *Us) {
     for (int t = threadIdx.x; t < 16 * r; t += blockDim.x) {
-        float v[16];                           // n_parts <= 16: all loads in flight together
-#pragma unroll
-        for (int b = 0; b < 16; ++b) v[b] = b < n_parts ? parts[(size_t)b * 16 * r + t] : 0.f;
         float sum = 0.f;
+        for (int b0 = 0; b0 < n_parts; b0 += 16) {   // n_parts <= 32; sixteen loads in flight together
+            float v[16];
 #pragma unroll
-        for (int b = 0; b < 16; ++b) sum += v[b];
+            for (int b = 0; b < 16; ++b) v[b] = b0 + b < n_parts ? parts[(size_t)(b0 + b) * 16 * r + t] : 0.f;
+#pragma unroll
+            for (int b = 0; b < 16; ++b) sum += v[b];
+        }
         Us[t] = sum;
     }
     __syncthreads();
@@ -1152,11 +1177,14 @@ struct SmallWs {
     size_t upart, yacc, total;
 };
 // workgroups that do the rank-r projection beside the streaming ones: one per 512 contraction
-// elements (four steps of 32 per wave), at most 16
-int n_proj_blocks(int C, int r) {
+// elements (four steps of 32 per wave), at most 16 -- or, for the binary16 layer, whose projection
+// runs on the vector ALUs with one 8-element chunk per thread and pass, at most 32
+constexpr int MAX_PROJ_BLOCKS = 32;
+int n_proj_blocks(int C, int r, bool f16) {
     if (r <= 0) return 0;
+    const int cap = f16 ? MAX_PROJ_BLOCKS : 16;
     int n = C / 512;
-    return n < 1 ? 1 : (n > 16 ? 16 : n);
+    return n < 1 ? 1 : (n > cap ? cap : n);
 }
 SmallWs small_ws(int K, int N, int r) {
     const size_t kmax = (size_t)(K > N ? K : N);
@@ -1164,7 +1192,7 @@ SmallWs small_ws(int K, int N, int r) {
     SmallWs l;
     size_t off = 0;
     (void)kmax;
-    l.upart = off;   off += al((size_t)16 * 16 * (size_t)(r > 0 ? r : 1) * 4);
+    l.upart = off;   off += al((size_t)MAX_PROJ_BLOCKS * 16 * (size_t)(r > 0 ? r : 1) * 4);
     const size_t yf = (size_t)ksplit_bound(K, N) * 16 * N, yb = (size_t)sm::MAX_KSPLIT * 16 * K;
     l.yacc = off;    off += al((yf > yb ? yf : yb) * 4);
     l.total = off;
@@ -1218,7 +1246,7 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     d.B = a.B;
     d.M = a.M;
     d.r = a.r;
-    d.n_proj = n_proj_blocks(K, a.r);
+    d.n_proj = n_proj_blocks(K, a.r, a.f16);
     d.ksplit = ksplit;
     d.lora_scale = a.lora_scale;
     d.Y = a.out;
@@ -1278,7 +1306,7 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     d.A = a.A;
     d.M = a.M;
     d.r = a.r;
-    d.n_proj = n_proj_blocks(N, a.r);
+    d.n_proj = n_proj_blocks(N, a.r, a.f16);
     d.nsplit = nsplit;
     d.lora_scale = a.lora_scale;
     d.dX = a.out;
