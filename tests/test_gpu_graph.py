@@ -4,8 +4,10 @@ every replay is compared bit for bit with an eager run on the same inputs (the k
 atomics, so results do not depend on timing), with the program's own eager work and
 synchronizations between the replays and new inputs written into the captured buffers each time.
 The shapes cover the launch configurations: the 128 x 64 producer / consumer kernel, the
-streaming kernels (M <= 16), and the 256 x 256 kernel with a split contraction and its second
-launch, each with the rank-r projection and the adapter-gradient launches."""
+streaming kernels (M <= 16, one and two quantization groups per backward tile), the 256 x 256
+kernel with a split contraction and its second launch, and the projection kernel's two forms
+(one row tile per workgroup; four that share the factor, with its finish launch), each with the
+adapter-gradient launches."""
 import pytest
 import torch
 
@@ -21,6 +23,8 @@ pytestmark = pytest.mark.gpu
     (3, 2112, 2136, 300, 8, 64),
     (3, 1024, 768, 16, 8, 128),
     (4, 320, 8232, 300, 16, 64),
+    (4, 512, 640, 16, 16, 64),        # streaming kernels, two quantization groups per backward tile
+    (2, 6400, 520, 1100, 8, 64),      # projection with four row tiles per workgroup, slices of the contraction + finish
 ])
 def test_graph_replays_equal_eager_steps(bits, K, N, M, r, group):
     L = layer(bits, K, N, M, r, group, seed=4)
