@@ -42,8 +42,8 @@ ORACLE_ROWS = 64                # token rows the CPU oracle computes where a ful
 def parse_args():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=20)
-    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=10)
     p.add_argument("--workload", default=None, help="a name from synth.CONFIGS (default: %s at M = %d)" % HEADLINE)
     p.add_argument("--M", type=int, default=None, help="override the token count of the workload")
     p.add_argument("--variant", choices=("bf16", "f16"), default="bf16",
@@ -387,6 +387,17 @@ def host16(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(cfg, wl):
     """The oracle, as it stands, timed on the host cores on the workload's own inputs (weight copy
     0 and the activations, copied to the host), and the parity of the GPU outputs against it.
@@ -417,7 +428,7 @@ def cpu_baseline(cfg, wl):
     t_lora = time.perf_counter() - t0
     seconds = t_rows * (M / len(rows)) + t_lora
     base = {"value": round(cfg.flops_fwd_bwd / seconds / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
-            "kind": "oracle", "seconds_measured": round(t_rows + t_lora, 3), "seconds_full_step": round(seconds, 3),
+            "cpu_model": cpu_model(), "kind": "oracle", "seconds_measured": round(t_rows + t_lora, 3), "seconds_full_step": round(seconds, 3),
             "extrapolated": not full,
             "sample": ("one full step (fwd + bwd_input + bwd_lora) of %s, all %d tokens" % (cfg.name, M)) if full else
                       ("%s: Y and dX of %d sampled token rows (%.2f s) + dA, dB in full (%.2f s); full-step time "
