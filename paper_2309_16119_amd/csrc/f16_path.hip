@@ -270,7 +270,9 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
     for (int i = 0; i < A_CH; ++i) {
         const int idx = tid + i * THREADS, row = idx >> 3, ch = idx & 7;
         const int m = m0 + row < a.M ? m0 + row : a.M - 1;
-        a_src[i] = a.act + (size_t)m * C + ch * 8;
+        // a chunk past the end of a contraction shorter than one step is never used (a_ok below is
+        // false in every step): its loads are pointed at the row's first chunk, inside the matrix
+        a_src[i] = a.act + (size_t)m * C + (ch * 8 < C ? ch * 8 : 0);
         a_col[i] = ch * 8;
     }
     // weight unit of this thread
@@ -284,17 +286,23 @@ __global__ __launch_bounds__(hf::THREADS) void f16_gemm_kernel(F16GemmArgs a) {
     const int bpg = a.w.group / 32;      // blocks per group
     if (!BWD) {
         const int w_col = c0 + u_lo < N ? c0 + u_lo : N - 1;       // clamped; never stored
-        wp = a.w.qweight + (size_t)u_kb * BITS * N + w_col;
-        const int g0 = (u_kb * 32) / a.w.group;
-        blk_in_group = u_kb - g0 * bpg;
+        // d_in = 32: the second block of a step does not exist in any step (f.ok below is always
+        // false for it); its loads are pointed at block 0
+        const int kb0 = u_kb * 32 < K ? u_kb : 0;
+        wp = a.w.qweight + (size_t)kb0 * BITS * N + w_col;
+        const int g0 = (kb0 * 32) / a.w.group;
+        blk_in_group = kb0 - g0 * bpg;
         sp = a.w.scales + (size_t)g0 * N + w_col;
         zp = a.w.zeros + (size_t)g0 * N + w_col;
     } else {
         const int k = c0 + u_kb * 32 < K ? c0 + u_kb * 32 : K - 32;
         const int g = k / a.w.group;
-        wp = a.w.qweight + (size_t)(k >> 5) * BITS * N + u_lo;
-        sp = a.w.scales + (size_t)g * N + u_lo;
-        zp = a.w.zeros + (size_t)g * N + u_lo;
+        // d_out < 64: lanes whose n lies past the matrix in step 0 lie past it in every step (f.ok
+        // below is always false for them); their loads are pointed at the last column
+        const int n0 = u_lo < N ? u_lo : N - 1;
+        wp = a.w.qweight + (size_t)(k >> 5) * BITS * N + n0;
+        sp = a.w.scales + (size_t)g * N + n0;
+        zp = a.w.zeros + (size_t)g * N + n0;
     }
 
     // two register sets: the data of step s + 2 is fetched during step s and staged during step s + 1.

@@ -67,6 +67,12 @@ SHAPES = [
     # slices of the contraction, whose partial tiles a second launch adds (ragged M and N)
     (3, 2816, 2456, 1100, 8, 128, True),
     (4, 2816, 2456, 1100, 0, 64, False),
+    # contractions shorter than one 64-deep step of the plain tile kernel (d_in = 32 forward, d_out = 48
+    # backward) and outputs narrower than its tile: every load of the absent part stays inside its matrix
+    (2, 32, 1664, 16, 0, 32, False),
+    (4, 512, 48, 2, 8, 64, True),
+    (2, 192, 96, 324, 33, 64, True),
+    (3, 5632, 80, 12, 33, 5632, True),
 ]
 
 
