@@ -419,18 +419,38 @@ constexpr int BCOLS = FWD_WAVES * WCOLS;  // columns per workgroup
 constexpr int MAX_RANGE = 2048;           // contraction elements of one K slice (64 KB of LDS)
 }  // namespace sm
 
+// The eight rows jj0 .. jj0 + 7 of B at columns col .. col + 3, all loads issued together (rows
+// past r come back as zeros).
+__device__ __forceinline__ void smallm_load_b8(const SmallFwdDev &d, int jj0, int col, float4 b[8]) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+        b[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (jj0 + q < d.r) b[q] = *reinterpret_cast<const float4 *>(d.B + (size_t)(jj0 + q) * d.w.N + col);
+    }
+}
+
 // Adds the adapter term to the four adjacent outputs y[0..3] of row m, columns col..col+3
-// (col a multiple of 4, col + 3 < N) and stores them as bfloat16.
+// (col a multiple of 4, col + 3 < N) and stores them as 16-bit floats.  `b0`: rows 0 .. 7 of B
+// for these columns, loaded by the caller ahead of time.
 template <bool F16>
-__device__ __forceinline__ void smallm_store4(const SmallFwdDev &d, const float *Us, int m, int col, const float y[4]) {
+__device__ __forceinline__ void smallm_store4(const SmallFwdDev &d, const float *Us, int m, int col, const float y[4], const float4 b0[8]) {
     float l[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int jj = 0; jj < d.r; ++jj) {
-        const float u = Us[m * d.r + jj];
-        const float4 b = *reinterpret_cast<const float4 *>(d.B + (size_t)jj * d.w.N + col);
-        l[0] = __builtin_fmaf(u, b.x, l[0]);
-        l[1] = __builtin_fmaf(u, b.y, l[1]);
-        l[2] = __builtin_fmaf(u, b.z, l[2]);
-        l[3] = __builtin_fmaf(u, b.w, l[3]);
+    for (int jj0 = 0; jj0 < d.r; jj0 += 8) {
+        float4 b[8];
+        if (jj0 == 0) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) b[q] = b0[q];
+        } else {
+            smallm_load_b8(d, jj0, col, b);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const float u = jj0 + q < d.r ? Us[m * d.r + jj0 + q] : 0.f;
+            l[0] = __builtin_fmaf(u, b[q].x, l[0]);
+            l[1] = __builtin_fmaf(u, b[q].y, l[1]);
+            l[2] = __builtin_fmaf(u, b[q].z, l[2]);
+            l[3] = __builtin_fmaf(u, b[q].w, l[3]);
+        }
     }
     float b[4] = {0.f, 0.f, 0.f, 0.f};
     if (F16 && d.bias16 != nullptr) {          // the bias of Figure 1 / eq. (3): part of the frozen layer
@@ -672,10 +692,23 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
     const int tid = threadIdx.x, N = d.w.N;
     const int m = tid >> 4, col = blockIdx.x * 64 + 4 * (tid & 15);
     float y[4] = {0.f, 0.f, 0.f, 0.f};
-    if (m < d.M && col < N) {
-        // eight slices' loads in flight at a time (the sum is latency-bound otherwise)
-        for (int q0 = 0; q0 < d.ksplit; q0 += 8) {
-            float4 v[8];
+    const bool mine = m < d.M && col < N;
+    // The kernel is a chain of memory round trips; everything that does not depend on another
+    // load is issued first and consumed last: the first eight slices' tiles, the first eight rows
+    // of B, and (inside smallm_sum_parts) the projection partials.
+    float4 v[8], b0[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        b0[u] = v[u];
+        if (mine && u < d.ksplit) v[u] = *reinterpret_cast<const float4 *>(d.Yacc + ((size_t)u * 16 + m) * N + col);
+    }
+    if (mine) smallm_load_b8(d, 0, col, b0);
+    smallm_sum_parts(d.Upart, d.n_proj, d.r, Us);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { y[0] += v[u].x; y[1] += v[u].y; y[2] += v[u].z; y[3] += v[u].w; }
+    if (mine) {
+        for (int q0 = 8; q0 < d.ksplit; q0 += 8) {     // further slices, eight loads in flight at a time
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -685,10 +718,9 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
             for (int u = 0; u < 8; ++u) { y[0] += v[u].x; y[1] += v[u].y; y[2] += v[u].z; y[3] += v[u].w; }
         }
     }
-    smallm_sum_parts(d.Upart, d.n_proj, d.r, Us);
     if (blockIdx.x == 0 && d.XA != nullptr)
         for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
-    if (m < d.M && col < N) smallm_store4<F16>(d, Us, m, col, y);
+    if (mine) smallm_store4<F16>(d, Us, m, col, y, b0);
 }
 
 // ---------------------------------------------------------------------------------
@@ -730,17 +762,52 @@ constexpr int NSTEP = 32;    // contraction elements per step (8 per lane group)
 constexpr int RED_BYTES = sm::WG_WAVES * 32 * 64 * 4;   // the waves' tiles meeting in LDS
 }
 
-// adapter term and bfloat16 store of 8 adjacent outputs dX[m][k0 .. k0+7]
-template <bool F16>
-__device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const float *Ts, int m, int k0, const float y[8]) {
-    float o[8];
+// A[k0 + c][jj0 .. jj0 + 3] for the eight adjacent rows c, all loads issued together (columns past
+// r come back as zeros): 16-byte loads when the rows are 16-byte aligned (r a multiple of 4).
+__device__ __forceinline__ void smallm_load_a8(const SmallBwdDev &d, int k0, int jj0, float4 a[8]) {
+    const int r = d.r;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
-        float l = 0.f;
-        const float *arow = d.A + (size_t)(k0 + c) * d.r;
-        for (int jj = 0; jj < d.r; ++jj) l = __builtin_fmaf(Ts[m * d.r + jj], arow[jj], l);
-        o[c] = __builtin_fmaf(d.lora_scale, l, y[c]);
+        const float *src = d.A + (size_t)(k0 + c) * r + jj0;
+        a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if ((r & 3) == 0) {
+            if (jj0 < r) a[c] = *reinterpret_cast<const float4 *>(src);
+        } else {
+            if (jj0 < r) a[c].x = src[0];
+            if (jj0 + 1 < r) a[c].y = src[1];
+            if (jj0 + 2 < r) a[c].z = src[2];
+            if (jj0 + 3 < r) a[c].w = src[3];
+        }
     }
+}
+
+// Adapter term and 16-bit store of 8 adjacent outputs dX[m][k0 .. k0+7].  `a0`: columns 0 .. 3 of
+// the eight rows of A, loaded by the caller ahead of time.
+template <bool F16>
+__device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const float *Ts, int m, int k0, const float y[8], const float4 a0[8]) {
+    float l[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int jj0 = 0; jj0 < d.r; jj0 += 4) {
+        float4 a[8];
+        if (jj0 == 0) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) a[c] = a0[c];
+        } else {
+            smallm_load_a8(d, k0, jj0, a);
+        }
+        float t[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t[q] = jj0 + q < d.r ? Ts[m * d.r + jj0 + q] : 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            l[c] = __builtin_fmaf(t[0], a[c].x, l[c]);
+            l[c] = __builtin_fmaf(t[1], a[c].y, l[c]);
+            l[c] = __builtin_fmaf(t[2], a[c].z, l[c]);
+            l[c] = __builtin_fmaf(t[3], a[c].w, l[c]);
+        }
+    }
+    float o[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[c] = __builtin_fmaf(d.lora_scale, l[c], y[c]);
     uint4 v;
     v.x = sm::pack16<F16>(o[0], o[1]);
     v.y = sm::pack16<F16>(o[2], o[3]);
@@ -1075,31 +1142,41 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(Small
     const int tid = threadIdx.x, K = d.w.K;
     const int m = tid >> 4, k0 = blockIdx.x * 128 + 8 * (tid & 15);
     float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (m < d.M) {
-        // four slices' loads (two 16-byte loads each) in flight at a time
-        for (int q0 = 0; q0 < d.nsplit; q0 += 4) {
-            float4 v0[4], v1[4];
+    // the first columns of the eight rows of A are fetched ahead of everything that waits
+    float4 a0[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                v0[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                v1[u] = v0[u];
-                if (q0 + u < d.nsplit) {
-                    const float *src = d.acc + ((size_t)(q0 + u) * 16 + m) * K + k0;
-                    v0[u] = *reinterpret_cast<const float4 *>(src);
-                    v1[u] = *reinterpret_cast<const float4 *>(src + 4);
-                }
-            }
+    for (int c = 0; c < 8; ++c) a0[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (m < d.M && d.r > 0) smallm_load_a8(d, k0, 0, a0);
+    // four slices' loads (two 16-byte loads each) in flight at a time; the first four are issued
+    // before the projection partials are summed and consumed after
+    float4 v0[4], v1[4];
+    auto load4 = [&](int q0) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                y[0] += v0[u].x; y[1] += v0[u].y; y[2] += v0[u].z; y[3] += v0[u].w;
-                y[4] += v1[u].x; y[5] += v1[u].y; y[6] += v1[u].z; y[7] += v1[u].w;
+        for (int u = 0; u < 4; ++u) {
+            v0[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            v1[u] = v0[u];
+            if (m < d.M && q0 + u < d.nsplit) {
+                const float *src = d.acc + ((size_t)(q0 + u) * 16 + m) * K + k0;
+                v0[u] = *reinterpret_cast<const float4 *>(src);
+                v1[u] = *reinterpret_cast<const float4 *>(src + 4);
             }
         }
-    }
+    };
+    auto add4 = [&]() {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            y[0] += v0[u].x; y[1] += v0[u].y; y[2] += v0[u].z; y[3] += v0[u].w;
+            y[4] += v1[u].x; y[5] += v1[u].y; y[6] += v1[u].z; y[7] += v1[u].w;
+        }
+    };
+    load4(0);
     smallm_sum_parts(d.Tpart, d.n_proj, d.r, Ts);
+    add4();
+    if (m < d.M)
+        for (int q0 = 4; q0 < d.nsplit; q0 += 4) { load4(q0); add4(); }
     if (blockIdx.x == 0 && d.T_out != nullptr)
         for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.T_out[t] = Ts[t];
-    if (m < d.M) smallm_bwd_store8<F16>(d, Ts, m, k0, y);
+    if (m < d.M) smallm_bwd_store8<F16>(d, Ts, m, k0, y, a0);
 }
 
 namespace {
