@@ -543,9 +543,9 @@ def measured_context(cfg, torch) -> dict:
 
 def rocprof_kernel_pattern(lib_name: str) -> str:
     """Substring of the rocprofv3 kernel name that belongs to a library profile name."""
-    if lib_name.startswith("gemm_fwd_256x256"):
+    if lib_name.startswith(("gemm_fwd_256x256", "gemm_fwd_128x256")):
         return "gemm_big_kernel<%d, false"
-    if lib_name.startswith("gemm_bwd_256x256"):
+    if lib_name.startswith(("gemm_bwd_256x256", "gemm_bwd_128x256")):
         return "gemm_big_kernel<%d, true"
     if lib_name.startswith("gemm_fwd_128x64s"):
         return "gemm_mid_kernel<%d, false"

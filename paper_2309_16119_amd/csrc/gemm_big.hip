@@ -1,5 +1,7 @@
 // The large-M variant of the fused dequantize + bf16 MFMA tile kernel: a 256 x 256
 // output tile per workgroup, 8 waves (two per SIMD) of 128 x 64 each, 64-deep steps.
+// (A second instantiation with 128-row tiles, waves of 64 x 64, serves token counts whose last
+// block of 256 rows would be at most half full -- a hundred-odd tokens above all.)
 // Same mathematics as gemm_tile.hip (ModuLoRA Figure 1: forward X What^T and backward
 // dY What with What re-materialized from the packed codes, plus the adapter term of eq. (3)
 // as an extended contraction); what differs is the data path, chosen from what was measured
@@ -40,20 +42,27 @@ namespace big {
 typedef _Float16 half16x8 __attribute__((ext_vector_type(8)));
 constexpr int THREADS = 512, NWAVES = 8;
 constexpr int BAND = 4;                  // row blocks per band of the tile walk (2 measures the same, 8 is 1-2 % slower)
-constexpr int MT = 256, CT = 256, WM = 128, WN = 64, RT = 64;
-constexpr int TI = WM / 32, TJ = WN / 32;
+constexpr int CT = 256, WN = 64, RT = 64;
+constexpr int TJ = WN / 32;
 constexpr int ROW_BYTES = RT * 2;                 // 128
-constexpr int A_BYTES = MT * ROW_BYTES;           // 32 KB: one activation tile
 constexpr int W_BYTES = CT * ROW_BYTES;           // 32 KB: one weight tile
 constexpr int A_SLOTS = 3, W_SLOTS = 2;           // activation ring (filled two steps ahead), weight tiles
-constexpr int W_BASE = A_SLOTS * A_BYTES;
-constexpr int LDS_BYTES = A_SLOTS * A_BYTES + W_SLOTS * W_BYTES;   // 160 KB, all of a CU's LDS
-constexpr int A_CH = MT * 8 / THREADS;            // 16-byte activation chunks per thread = 4
 constexpr int W_CH = CT * 8 / THREADS;            // 16-byte chunks of an extension W tile per thread
 constexpr int FW_UNITS = CT * 2 / THREADS;        // (column, 32-code block) units per thread = 1
 constexpr int BW_UNITS = (CT / 8) * (RT / 4) / THREADS;   // (4 n, 8 k) units per thread = 1
-static_assert(A_CH == RT / 16, "one quarter of the activation tile per 16-deep step");
 constexpr int PATCH_ROW = 72;                     // epilogue patch row stride (elements)
+// What depends on the rows of a tile (MT = 256 or 128; two rows of four waves either way).
+template <int MT_>
+struct Geo {
+    static constexpr int MT = MT_, WM = MT / 2, TI = WM / 32;
+    static constexpr int A_BYTES = MT * ROW_BYTES;            // 32 / 16 KB: one activation tile
+    static constexpr int W_BASE = A_SLOTS * A_BYTES;
+    static constexpr int LDS_BYTES = A_SLOTS * A_BYTES + W_SLOTS * W_BYTES;   // 160 KB (all of a CU's LDS) / 112 KB
+    static constexpr int A_CH = MT * 8 / THREADS;             // 16-byte activation chunks per thread: 4 / 2
+    static constexpr int A_EVERY = (RT / 16) / A_CH;          // one of them every so many 16-deep steps
+    static constexpr int PART_F4 = THREADS * (MT / 8);        // float4 of one partial tile
+    static_assert(A_CH * A_EVERY == RT / 16, "the activation tile's chunks spread evenly over the 16-deep steps");
+};
 
 // XOR swizzle of a row's eight 16-byte chunks.  Rows are 128 bytes and the LDS has 64 banks
 // (256 bytes per cycle, 16 lanes of a 16-byte access), so two rows share a bank line: the even
@@ -99,9 +108,10 @@ __device__ __forceinline__ BigItem big_item_of_block(int bid, const BigPlan &p) 
 // term s P F and the bias join here, before the rounding (Figure 1 / eq. (3); the bias belongs
 // to the frozen layer and enters the forward pass only); P's 32 rows pass through LDS behind
 // the patches.
-template <bool F16>
+// `slot`: which of the per-wave LDS areas (patch, rows of P) this wave uses.
+template <bool F16, int WM>
 __device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int i, unsigned char *smem, const GemmArgs &a, int Cout,
-                                                  int m0, int c0, int wave, int lane) {
+                                                  int m0, int c0, int wave, int lane, int slot) {
     using namespace big;
     const int wm = wave >> 2, wn = wave & 3;
     uint16_t *out = a.out;
@@ -109,7 +119,7 @@ __device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int 
     if (F16) {
         const int r = a.ep_r, N = a.w.N;
         const bool bwd = a.backward;
-        float *Ps = reinterpret_cast<float *>(smem + 40960) + wave * (32 * 64);   // [jj][32 rows]
+        float *Ps = reinterpret_cast<float *>(smem + 40960) + slot * (32 * 64);   // [jj][32 rows]
         if (r > 0) {
             for (int x = lane; x < 32 * r; x += 64) {
                 const int prow = x & 31, jj = x >> 5;
@@ -154,7 +164,7 @@ __device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int 
         __builtin_amdgcn_s_waitcnt(0xc07f);   // the next block of rows overwrites Ps
         __builtin_amdgcn_wave_barrier();
     }
-    uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + wave * (32 * PATCH_ROW);
+    uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + slot * (32 * PATCH_ROW);
 #pragma unroll
     for (int j = 0; j < TJ; ++j)
 #pragma unroll
@@ -177,15 +187,18 @@ __device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int 
     __builtin_amdgcn_wave_barrier();
 }
 
-// Partial tiles: slice j of the plan owns 256 x 256 floats, stored as 32 float4 per thread
+// Partial tiles: slice j of the plan owns MT x 256 floats, stored as MT / 8 float4 per thread
 // in register order ([float4 index][thread]), so writes and reads are fully coalesced.
+template <int MT>
 __device__ __forceinline__ float4 *big_partial_of(float *partials, int tail_tile, int slice, int split) {
-    return reinterpret_cast<float4 *>(partials) + ((size_t)tail_tile * split + slice) * (size_t)(big::THREADS * 32);
+    return reinterpret_cast<float4 *>(partials) + ((size_t)tail_tile * split + slice) * (size_t)big::Geo<MT>::PART_F4;
 }
 
-template <int BITS, bool BWD, bool F16>
+template <int BITS, bool BWD, bool F16, int MT>
 __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, BigPlan plan) {
     using namespace big;
+    using G = Geo<MT>;
+    constexpr int WM = G::WM, TI = G::TI, A_BYTES = G::A_BYTES, W_BASE = G::W_BASE, A_CH = G::A_CH;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
     const GemmArgs &a = d.a;
@@ -450,7 +463,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
                     load_w(wst[u], ta);
 #pragma unroll
                     for (int ks = 0; ks < RT / 16; ++ks) {
-                        issue_a_part(ta, a_fill, ks);
+                        if (ks % G::A_EVERY == 0) issue_a_part(ta, a_fill, ks / G::A_EVERY);
                         if (ks + 1 < RT / 16) load_frags(f[(ks + 1) & 1], oa, u, ks + 1);
                         mfma_frags(f[ks & 1]);
                         store_w(u ^ 1, wst[u ^ 1], ks);
@@ -549,7 +562,7 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
 
     if (item.slice >= 0) {
         // a slice: leave the raw accumulators for gemm_big_fixup_kernel
-        float4 *part = big_partial_of(a.partials, item.tile - plan.full, item.slice, plan.split) + tid;
+        float4 *part = big_partial_of<MT>(a.partials, item.tile - plan.full, item.slice, plan.split) + tid;
 #pragma unroll
         for (int i = 0; i < TI; ++i)
 #pragma unroll
@@ -561,16 +574,17 @@ __global__ __launch_bounds__(big::THREADS, 2) void gemm_big_kernel(GemmDev d, Bi
         return;
     }
 #pragma unroll
-    for (int i = 0; i < TI; ++i) big_epilogue_rows<F16>(acc[i], i, smem, a, Cout, m0, c0, wave, lane);
+    for (int i = 0; i < TI; ++i) big_epilogue_rows<F16, WM>(acc[i], i, smem, a, Cout, m0, c0, wave, lane, wave);
 }
 
-// TI workgroups per split tile (workgroup y takes the y-th block of 32 rows of every wave):
-// add the slices in slice order, then the common epilogue.
-template <bool F16>
-__global__ __launch_bounds__(big::THREADS) void gemm_big_fixup_kernel(GemmDev d, BigPlan plan) {
+// 8 TI single-wave workgroups per split tile (workgroup (y, z) stands in for wave z of the tile's
+// workgroup and takes that wave's y-th block of 32 rows; whole-chip parallelism even for a few
+// deeply split tiles): add the slices in slice order, then the common epilogue.
+template <bool F16, int MT>
+__global__ __launch_bounds__(64) void gemm_big_fixup_kernel(GemmDev d, BigPlan plan) {
     using namespace big;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // FIXUP_LDS bytes
-    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
+    const int lane = threadIdx.x, wave = blockIdx.z, tid = wave * 64 + lane;
     const int tile = plan.full + blockIdx.x, i = blockIdx.y;
     const TileCoord tco = banded_tile<big::BAND>(tile, d.tiles_m, d.tiles_c);
     const int m0 = tco.tm * MT, c0 = tco.tc * CT;
@@ -580,49 +594,73 @@ __global__ __launch_bounds__(big::THREADS) void gemm_big_fixup_kernel(GemmDev d,
     for (int j = 0; j < TJ; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-    for (int sl = 0; sl < plan.split; ++sl) {
-        const float4 *part = big_partial_of(d.a.partials, blockIdx.x, sl, plan.split) + tid;
-        float4 v[TJ * 4];
+    // four slices' loads in flight at a time (a slice per round trip leaves the few workgroups of
+    // a deep split waiting on memory latency), added in slice order
+    constexpr int SB = 4;
+    for (int sl0 = 0; sl0 < plan.split; sl0 += SB) {
+        float4 v[SB][TJ * 4];
 #pragma unroll
-        for (int e = 0; e < TJ * 4; ++e) v[e] = part[(size_t)((i * TJ * 4 + e) * THREADS)];
+        for (int u = 0; u < SB; ++u) {
+            if (sl0 + u < plan.split) {
+                const float4 *part = big_partial_of<MT>(d.a.partials, blockIdx.x, sl0 + u, plan.split) + tid;
 #pragma unroll
-        for (int e = 0; e < TJ * 4; ++e) {
-            acc[e / 4][4 * (e % 4)] += v[e].x;
-            acc[e / 4][4 * (e % 4) + 1] += v[e].y;
-            acc[e / 4][4 * (e % 4) + 2] += v[e].z;
-            acc[e / 4][4 * (e % 4) + 3] += v[e].w;
+                for (int e = 0; e < TJ * 4; ++e) v[u][e] = part[(size_t)((i * TJ * 4 + e) * THREADS)];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            if (sl0 + u < plan.split) {
+#pragma unroll
+                for (int e = 0; e < TJ * 4; ++e) {
+                    acc[e / 4][4 * (e % 4)] += v[u][e].x;
+                    acc[e / 4][4 * (e % 4) + 1] += v[u][e].y;
+                    acc[e / 4][4 * (e % 4) + 2] += v[u][e].z;
+                    acc[e / 4][4 * (e % 4) + 3] += v[u][e].w;
+                }
+            }
         }
     }
-    big_epilogue_rows<F16>(acc, i, smem, d.a, Cout, m0, c0, wave, lane);
+    big_epilogue_rows<F16, MT / 2>(acc, i, smem, d.a, Cout, m0, c0, wave, lane, 0);
 }
 
-template <int BITS, bool BWD, bool F16 = false>
-static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
-    const GemmDev d = make_gemm_dev(a, big::MT, big::CT);
-    BigPlan plan = big_plan(a.M, BWD ? a.w.N : a.w.K, BWD ? a.w.K : a.w.N);
+template <int BITS, bool BWD, bool F16, int MT>
+static hipError_t launch_big_mt(const GemmArgs &a, BigPlan plan, hipStream_t stream) {
+    const GemmDev d = make_gemm_dev(a, MT, big::CT);
     // no (or too little) scratch for partial tiles: whole tiles only
     if (a.partials == nullptr || a.partials_bytes < plan.partial_bytes()) plan.split = 1;
     const int whole = plan.split > 1 ? plan.full : plan.full + plan.tail;
     const int slices = plan.split > 1 ? plan.tail * plan.split : 0;
     const int blocks = ((whole + 7) / 8 + (slices + 7) / 8) * 8;
-    const size_t lds_bytes = big::LDS_BYTES;
-    auto kern = gemm_big_kernel<BITS, BWD, F16>;
+    const size_t lds_bytes = big::Geo<MT>::LDS_BYTES;
+    auto kern = gemm_big_kernel<BITS, BWD, F16, MT>;
     static bool configured[64] = {};
     const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), lds_bytes, configured);
     if (e != hipSuccess) return e;
-    launch_kernel(F16 ? (BWD ? "f16_gemm_bwd" : "f16_gemm_fwd") : (BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256"), kern, blocks, big::THREADS,
-                  lds_bytes, stream, d, plan);
+    const char *name = F16 ? (BWD ? "f16_gemm_bwd" : "f16_gemm_fwd")
+                           : MT == 256 ? (BWD ? "gemm_bwd_256x256" : "gemm_fwd_256x256") : (BWD ? "gemm_bwd_128x256" : "gemm_fwd_128x256");
+    launch_kernel(name, kern, blocks, big::THREADS, lds_bytes, stream, d, plan);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || plan.split <= 1) return err;
-    // the patches, and behind them (F16) 32 rows of P per wave
-    constexpr size_t FIXUP_LDS = F16 ? 40960 + big::NWAVES * 32 * 64 * 4 : big::NWAVES * 32 * big::PATCH_ROW * 2;
-    auto fix = gemm_big_fixup_kernel<F16>;
+    // one wave's patch, and (F16, at the offset the epilogue expects) its 32 rows of P
+    constexpr size_t FIXUP_LDS = F16 ? 40960 + 32 * 64 * 4 : 32 * big::PATCH_ROW * 2;
+    auto fix = gemm_big_fixup_kernel<F16, MT>;
     static bool fix_configured[64] = {};
     const hipError_t e2 = ensure_lds_limit(reinterpret_cast<const void *>(fix), FIXUP_LDS, fix_configured);
     if (e2 != hipSuccess) return e2;
-    launch_kernel(F16 ? (BWD ? "f16_gemm_bwd_fixup" : "f16_gemm_fwd_fixup") : (BWD ? "gemm_bwd_256x256_fixup" : "gemm_fwd_256x256_fixup"), fix,
-                  dim3(plan.tail, big::TI), big::THREADS, FIXUP_LDS, stream, d, plan);
+    const char *fix_name = F16 ? (BWD ? "f16_gemm_bwd_fixup" : "f16_gemm_fwd_fixup")
+                               : MT == 256 ? (BWD ? "gemm_bwd_256x256_fixup" : "gemm_fwd_256x256_fixup")
+                                           : (BWD ? "gemm_bwd_128x256_fixup" : "gemm_fwd_128x256_fixup");
+    launch_kernel(fix_name, fix, dim3(plan.tail, big::Geo<MT>::TI, big::NWAVES), 64, FIXUP_LDS, stream, d, plan);
     return hipGetLastError();
+}
+
+template <int BITS, bool BWD, bool F16 = false>
+static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
+    const int C = BWD ? a.w.N : a.w.K, Cout = BWD ? a.w.K : a.w.N;
+    if (F16) return launch_big_mt<BITS, BWD, F16, 256>(a, big_plan_rows(a.M, C, Cout, 256), stream);
+    const BigPlan plan = big_plan(a.M, C, Cout);
+    if (!F16 && plan.mt == 128) return launch_big_mt<BITS, BWD, false, 128>(a, plan, stream);
+    return launch_big_mt<BITS, BWD, F16, 256>(a, plan, stream);
 }
 
 hipError_t launch_gemm_big(const GemmArgs &a, hipStream_t stream) {

@@ -77,14 +77,16 @@ hipError_t launch_gemm_big_f16(const GemmArgs &a, hipStream_t stream);
 // How the 256 x 256 kernel fills 256 compute units when the tile count is not a multiple of
 // 256: the first `full` tiles run whole; each of the `tail` remaining ones is cut into
 // `split` slices of the contraction, one workgroup each, which leave fp32 partial tiles
-// that a second small kernel adds up.  split == 1: nothing is cut.
+// that a second small kernel adds up.  split == 1: nothing is cut.  `mt`: rows of a tile,
+// 256 or (the kernel's second instantiation) 128.
 struct BigPlan {
-    int full, tail, split;
-    size_t partial_bytes() const { return split > 1 ? (size_t)tail * split * (256u * 256u * 4u) : 0; }
+    int full, tail, split, mt;
+    size_t partial_bytes() const { return split > 1 ? (size_t)tail * split * ((size_t)mt * 256u * 4u) : 0; }
 };
-inline BigPlan big_plan(int M, int C, int Cout) {
+inline BigPlan big_plan_rows(int M, int C, int Cout, int mt) {
     BigPlan p;
-    const long tiles = (long)((M + 255) / 256) * ((Cout + 255) / 256);
+    p.mt = mt;
+    const long tiles = (long)((M + mt - 1) / mt) * ((Cout + 255) / 256);
     p.full = (int)(tiles / 256 * 256);
     p.tail = (int)(tiles - p.full);
     p.split = 1;
@@ -97,9 +99,22 @@ inline BigPlan big_plan(int M, int C, int Cout) {
     }
     return p;
 }
+// 128-row tiles where the last block of 256 rows would be at most half full and the row blocks
+// are few: a step of the 128-row kernel takes 0.55 of a 256-row step, so an odd number n of
+// 128-row blocks costs 0.55 n against (n + 1) / 2.
+inline BigPlan big_plan(int M, int C, int Cout) {
+    const int n128 = (M + 127) / 128;
+    const bool half_rows = (n128 & 1) != 0 && n128 <= 5 && M > 32;
+    return big_plan_rows(M, C, Cout, half_rows ? 128 : 256);
+}
 inline size_t gemm_partial_bytes(int M, int K, int N) {
-    const size_t f = big_plan(M, K, N).partial_bytes(), b = big_plan(M, N, K).partial_bytes();
-    return f > b ? f : b;
+    size_t most = 0;
+    for (int mt = 128; mt <= 256; mt += 128) {     // the binary16 path always takes 256-row tiles
+        const size_t f = big_plan_rows(M, K, N, mt).partial_bytes(), b = big_plan_rows(M, N, K, mt).partial_bytes();
+        most = f > most ? f : most;
+        most = b > most ? b : most;
+    }
+    return most;
 }
 
 // ---- lora_kernels.hip ----------------------------------------------------------

@@ -3,7 +3,9 @@
 The library picks a tile kernel from the shape alone (a table of measured step costs).  Besides
 the 256 x 256, the 128 x 64 producer / consumer and the 32 x 256 kernels that the benchmark
 shapes land on, ordinary shapes reach four more variants of the generic tile kernel: 64 x 128
-with two k-groups (a few dozen tokens, very wide outputs), 64 x 128, 128 x 128 and 256 x 128.
+with two k-groups (a few dozen tokens, very wide outputs), 64 x 128, 128 x 128 and 256 x 128;
+and token counts whose last block of 256 rows would be at most half full take the 256 x 256
+kernel's instantiation with 128-row tiles.
 Each is driven here in both directions and at all three bit widths by a shape that the table
 routes to it -- the kernel that ran is read back through the profiling hook and asserted -- with
 a ragged row tile, a ragged column tile, a ragged last contraction step and an adapter."""
@@ -24,7 +26,9 @@ pytestmark = pytest.mark.gpu
 VARIANTS = {
     "64x128k": (50, (288, 16664, 96), (16672, 264, 32)),
     "64x128": (131, (288, 16664, 32), (16672, 264, 16672)),
-    "128x128": (257, (288, 16664, 288), (16672, 264, 32)),
+    "128x128": (200, (288, 16664, 288), (16672, 264, 32)),
+    # the 256 x 256 kernel's second instantiation; eight slices of the contraction per tile + fix-up launch
+    "128x256": (100, (4128, 1064, 96), (1056, 4104, 32)),
     "256x128": (1301, (288, 10760, 32), (10784, 264, 10784)),
 }
 
