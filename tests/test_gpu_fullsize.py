@@ -41,6 +41,10 @@ CASES = [
     ("c5_65b_up", 4096),
     ("c5_65b_down", 256),
     ("c5_65b_down", 4096),
+    # the decoder layer of the benchmark at 128 tokens: the 128-row instantiation of the large tile kernel
+    ("c5_65b_attn", 128),
+    ("c5_65b_up", 128),
+    ("c5_65b_down", 128),
 ]
 
 
@@ -50,14 +54,14 @@ def host16(t):
 
 def sample_rows(M):
     """Token rows the oracle computes: all of them up to 48; else one random row from every block
-    of 128 rows, the first and last row of every block of 256 (either side of every row-tile
-    boundary of the 256-, 128- and 64-row kernels' coarsest grid), and rows 0 and M - 1."""
+    of 128 rows, the first and last row of every block of 128 (either side of every row-tile
+    boundary of the 256- and 128-row kernels), and rows 0 and M - 1."""
     if M <= 48:
         return np.arange(M)
     rng = np.random.default_rng(5)
     starts = np.arange(0, M, 128)
     inner = starts + rng.integers(0, 128, starts.size)
-    edges = np.concatenate((np.arange(0, M, 256), np.arange(255, M, 256)))
+    edges = np.concatenate((np.arange(0, M, 128), np.arange(127, M, 128)))
     rows = np.concatenate((inner, edges, [0, M - 1]))
     return np.unique(rows[rows < M])
 

@@ -101,6 +101,11 @@ SHAPES = [
     (3, 8224, 328, 200, 8, 32),      # forward: 2 tiles x 8 slices
     (4, 320, 8232, 300, 16, 64),     # backward: 4 tiles x 8 slices
     (2, 8192, 512, 256, 0, 128),     # no adapter: the partial tiles are the only scratch
+    # a hundred-odd tokens (or that many past a multiple of 256): the same kernel with 128-row
+    # tiles -- one exactly full tile, ragged ones, an adapter wider than one 64-deep step
+    (3, 4096, 1024, 128, 8, 128),
+    (2, 4160, 1064, 97, 20, 32),
+    (4, 1056, 4136, 330, 40, 32),
     # few rows and a deep contraction: the rank-r projection is split over workgroups too
     (3, 4096, 264, 40, 40, 128),
     (4, 256, 6144, 100, 64, 32),
