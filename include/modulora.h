@@ -112,14 +112,15 @@ int modulora_dequant(const modulora_qweight *w, uint16_t *What_bf16, void *strea
  *   Y  [M][d_out] bfloat16 (out)   XA [M][r] float32 (out, may be NULL)
  * r == 0 (A, B ignored) is the plain low-precision linear map LPLinear.forward.
  * fp32 accumulation; one round-to-nearest-even to bfloat16 at the end.
- * Arithmetic by token count.  M > 16: What is materialized tile by tile exactly as defined
- * above (rounded to bfloat16) and multiplied.  M <= 16 (when the shape allows: d_in a
- * multiple of 128, group_size a multiple of 32 / 64 / 128 for 4 / 2 / 3 bits): the direct
- * product with the quantized matrix of Section 3.1.2 -- the codes are multiplied as they are
- * and scale and zero point are applied to per-group sums, so What is NOT rounded to bfloat16
- * first.  The result then differs from the materialized form by at most
+ * Arithmetic by token count.  Normally What is materialized tile by tile exactly as defined
+ * above (rounded to bfloat16) and multiplied.  A handful of tokens -- M <= 16, or M <= 32 over a
+ * weight of at least 4 MiB of codes (done as two passes of at most 16 rows) -- take, when the
+ * shape allows (d_in a multiple of 128, group_size a multiple of 32 / 64 / 128 for 4 / 2 / 3
+ * bits), the direct product with the quantized matrix of Section 3.1.2: the codes are multiplied
+ * as they are and scale and zero point are applied to per-group sums, so What is NOT rounded to
+ * bfloat16 first.  The result then differs from the materialized form by at most
  * 2^-8 sum_k |X[m][k]| |What[n][k]| (closer to the exact product); the same input row can
- * therefore give results that differ by this much at M = 16 and at M = 17.
+ * therefore give results that differ by this much on either side of that token count.
  */
 int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M,
                  const float *A, const float *B, int32_t r, float lora_scale,
@@ -134,7 +135,7 @@ int modulora_fwd(const modulora_qweight *w, const uint16_t *X, int32_t M,
  * the library runs on holds its own copy from the first call on that GPU until the process
  * ends).  The call allocates and frees nothing, on the host side of the GPU or through any
  * library.  A layer / M / r whose forward pass needs more scratch than that returns
- * MODULORA_ERR_WORKSPACE (the M <= 16 streaming pass of every benchmark layer needs < 8 MiB; the
+ * MODULORA_ERR_WORKSPACE (the streaming passes for a handful of tokens need < 8 MiB at every benchmark layer; the
  * tile kernels need about 2 (M + d_out) (3 r + 16) bytes; partial tiles of a split last round of
  * 256 x 256 tiles are used only when they also fit, otherwise those tiles run whole).
  * All calls on one GPU share that GPU's array and it keeps the last call's contents (nothing in
@@ -157,8 +158,9 @@ int modulora_fwd_static(const modulora_qweight *w, const uint16_t *X, int32_t M,
  *   dY [M][d_out] bfloat16          dX [M][d_in] bfloat16 (out)
  *   dYBt [M][r] float32 (out, may be NULL)
  * No gradient flows to qweight, scales or zeros.
- * Arithmetic by token count, as for modulora_fwd: at M <= 16 (when d_out is a multiple of
- * 128, d_in a multiple of 128 and group_size 64 or a multiple of 128) the codes are multiplied directly and the scaled
+ * Arithmetic by token count, as for modulora_fwd: for the same handful of tokens (when d_out is
+ * a multiple of 128, d_in a multiple of 128 and group_size 64 or a multiple of 128) the codes are
+ * multiplied directly and the scaled
  * activation dY[m][n] * scales[g][n] is rounded to bfloat16 before the product; the result
  * differs from the materialized form by at most 2^-7 sum_n |dY[m][n]| |What[n][k]|.
  */
@@ -246,8 +248,8 @@ int modulora_adamw(float *param, const float *grad, float *exp_avg, float *exp_a
  * modulora_f16_workspace_bytes()).  Shape rules, rank rules, the stream argument, ownership and
  * error behaviour are those of the calls above: every argument error is found on the host
  * before any HIP call and returned as a modulora_status; nothing is allocated or synchronized.
- * Arithmetic by token count, as for modulora_fwd / modulora_bwd_input: at M <= 16 (same shape
- * conditions) the codes are multiplied directly (Section 3.1.2) and scale and zero point are
+ * Arithmetic by token count, as for modulora_fwd / modulora_bwd_input: for a handful of tokens
+ * (same token counts, same shape conditions) the codes are multiplied directly (Section 3.1.2) and scale and zero point are
  * applied to per-group sums, so What is not rounded to binary16 first; forward results differ from
  * the materialized form by at most 2^-11 sum_k |X| |What|, input gradients (where dY * scale is
  * rounded to binary16) by at most 2^-10 sum_n |dY| |What|.

@@ -68,9 +68,9 @@ struct WsLayout {
 
 WsLayout ws_layout(int32_t K, int32_t N, int32_t M, int32_t r) {
     WsLayout l{};
-    // the M <= 16 streaming kernels keep a re-ordered copy of the activations and the
+    // the streaming kernels for a handful of tokens keep the slices' partial tiles and the
     // adapter partial sums in the workspace (also when r == 0)
-    const size_t small = M <= 16 ? mlr::smallm_ws_bytes(K, N, r) : 0;
+    const size_t small = M <= mlr::SMALLM_MAX_M ? mlr::smallm_ws_bytes(K, N, r) : 0;
     // fp32 partial tiles of the split contraction of the 256 x 256 kernel (also when r == 0)
     const size_t part = align256(mlr::gemm_partial_bytes(M, K, N));
     l.gemm_part_bytes = part;
@@ -407,10 +407,10 @@ F16Ws f16_ws(int32_t K, int32_t N, int32_t M, int32_t r) {
         l.p1 = off;    off += align256((size_t)M * r * 4);
         l.gpart = off; off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
     }
-    l.gemm_part = off; off += align256(mlr::gemm_partial_bytes(M, K, N));   // partial tiles of the 256 x 256 kernel
+    l.gemm_part = off; off += align256(mlr::gemm_partial_bytes(M, K, N, true));   // partial tiles of the 256 x 256 kernel
     l.total = off;
-    // the M <= 16 streaming kernels lay out their own scratch from the start of the workspace
-    if (M <= 16) {
+    // the streaming kernels for a handful of tokens lay out their own scratch from the start of the workspace
+    if (M <= mlr::SMALLM_MAX_M) {
         const size_t small = mlr::smallm_ws_bytes(K, N, r);
         if (small > l.total) l.total = small;
     }

@@ -525,7 +525,7 @@ hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act
             g.zeros16 = w.zeros; g.bias16 = w.bias;
             g.ep_P = r > 0 ? P : nullptr; g.ep_F = Fm; g.ep_r = r; g.ep_scale = lora_scale;
             g.partials = partials;
-            g.partials_bytes = partials ? gemm_partial_bytes(M, w.K, w.N) : 0;
+            g.partials_bytes = partials ? gemm_partial_bytes(M, w.K, w.N, true) : 0;
             return use_mid ? launch_gemm_mid_f16(g, stream) : launch_gemm_big_f16(g, stream);
         }
     }

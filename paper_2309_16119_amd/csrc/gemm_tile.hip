@@ -23,8 +23,8 @@
 // Scheduling.  One VALU instruction costs a SIMD about 4 cycles and one 32x32x16 MFMA 32;
 // they overlap when they come from different waves of the same SIMD, or when a wave issues
 // independent VALU work after an MFMA.  The 256x256 variant lives in gemm_big.hip.  The
-// variants of this file are: single-buffered ones (32x256 for a handful of tokens, 256x128
-// with two workgroups per CU filling each other's gaps) and pipelined ones for grids of
+// variants of this file are: a single-buffered one (256x128 with two workgroups per CU
+// filling each other's gaps) and pipelined ones for grids of
 // about one tile per CU, where nothing else hides latency: register stages filled several
 // tiles ahead, two LDS buffers with one barrier per tile, the dequantization of the next
 // tile issued between the MFMA steps of the current one, and optionally 8 waves that split
@@ -632,9 +632,9 @@ static hipError_t launch_variant(const GemmArgs &a, const char *name, hipStream_
 }
 
 // Tile variants.  `pick` may be forced with the environment variable MODULORA_TILE
-// (big | mid | m128 | m64 | m64k | t128s | small), a tuning knob for benchmarks.  Every variant
+// (big | mid | m128 | m64 | m64k | t128s), a tuning knob for benchmarks.  Every variant
 // listed is one the automatic choice below can reach.
-enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128S, PICK_SMALL };
+enum TilePick { PICK_AUTO = 0, PICK_BIG, PICK_MID, PICK_M128, PICK_M64, PICK_M64K, PICK_T128S };
 
 static TilePick forced_pick() {
     static int cached = -1;
@@ -648,7 +648,6 @@ static TilePick forced_pick() {
             else if (!std::strcmp(e, "m64")) cached = PICK_M64;
             else if (!std::strcmp(e, "m64k")) cached = PICK_M64K;
             else if (!std::strcmp(e, "t128s")) cached = PICK_T128S;
-            else if (!std::strcmp(e, "small")) cached = PICK_SMALL;
         }
     }
     return (TilePick)cached;
@@ -659,8 +658,7 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
     const int Cout = BWD ? a.w.K : a.w.N;
     TilePick pick = forced_pick();
     if (pick == PICK_AUTO) {
-        if (a.M <= 32) pick = PICK_SMALL;
-        else {
+        {   // (any token count: a 32-row tile kernel for M <= 32 measured 1.2 us per step, more than any of these)
             // Estimated time of the whole grid in microseconds, from measured times of one 64-deep
             // contraction step of each variant: alone on a CU (t1) and sharing it with a second
             // workgroup (t2), times how often the 256 CUs (x occupancy) are refilled.  The 256 x 256
@@ -687,9 +685,6 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
         }
     }
     switch (pick) {
-        case PICK_SMALL:
-            return launch_variant<BITS, BWD, 256, 32, 256, 32, 64, 1, 0>(
-                a, BWD ? "gemm_bwd_32x256" : "gemm_fwd_32x256", stream);
         case PICK_MID:
             return launch_variant<BITS, BWD, 256, 256, 128, 128, 64, 2, 0>(
                 a, BWD ? "gemm_bwd_256x128" : "gemm_fwd_256x128", stream);

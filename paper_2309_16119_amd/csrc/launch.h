@@ -90,7 +90,7 @@ inline BigPlan big_plan_rows(int M, int C, int Cout, int mt) {
     p.full = (int)(tiles / 256 * 256);
     p.tail = (int)(tiles - p.full);
     p.split = 1;
-    if (p.tail > 0 && M > 32) {
+    if (p.tail > 0) {
         int s = 256 / p.tail;                 // slices that still fit one round
         const int by_depth = (C / 64) / 8;    // at least 8 steps of 64 per slice
         if (s > by_depth) s = by_depth;
@@ -104,17 +104,14 @@ inline BigPlan big_plan_rows(int M, int C, int Cout, int mt) {
 // 128-row blocks costs 0.55 n against (n + 1) / 2.
 inline BigPlan big_plan(int M, int C, int Cout) {
     const int n128 = (M + 127) / 128;
-    const bool half_rows = (n128 & 1) != 0 && n128 <= 5 && M > 32;
+    const bool half_rows = (n128 & 1) != 0 && n128 <= 5;
     return big_plan_rows(M, C, Cout, half_rows ? 128 : 256);
 }
-inline size_t gemm_partial_bytes(int M, int K, int N) {
-    size_t most = 0;
-    for (int mt = 128; mt <= 256; mt += 128) {     // the binary16 path always takes 256-row tiles
-        const size_t f = big_plan_rows(M, K, N, mt).partial_bytes(), b = big_plan_rows(M, N, K, mt).partial_bytes();
-        most = f > most ? f : most;
-        most = b > most ? b : most;
-    }
-    return most;
+// Scratch for the partial tiles of either direction.  The binary16 path always takes 256-row tiles.
+inline size_t gemm_partial_bytes(int M, int K, int N, bool f16 = false) {
+    const size_t f = (f16 ? big_plan_rows(M, K, N, 256) : big_plan(M, K, N)).partial_bytes();
+    const size_t b = (f16 ? big_plan_rows(M, N, K, 256) : big_plan(M, N, K)).partial_bytes();
+    return f > b ? f : b;
 }
 
 // ---- lora_kernels.hip ----------------------------------------------------------
@@ -259,7 +256,12 @@ struct AdamWArgs {
 };
 hipError_t launch_adamw(const AdamWArgs &a, hipStream_t stream);
 
-// ---- smallm.hip: M <= 16 streaming kernels ------------------------------------
+// ---- smallm.hip: streaming kernels for a handful of tokens ------------------------
+// A launch of the kernels handles at most SMALLM_ROWS token rows (one MFMA tile); the launchers take
+// up to SMALLM_MAX_M rows and run that many passes over the packed weight, one after the other on
+// the stream (sharing the scratch): two passes over a weight of some megabytes still cost a
+// fraction of what a tile kernel needs for so few rows.
+constexpr int SMALLM_ROWS = 16, SMALLM_MAX_M = 32;
 struct SmallArgs {
     LayerView w;
     const uint16_t *act;  // bf16 [M][K] (forward) or [M][N] (backward)

@@ -1236,15 +1236,22 @@ int pick_nsplit(int N, int K) {
 }
 }  // namespace
 
+// More than one pass (M > SMALLM_ROWS) only over a weight of at least 4 MB of codes: below that a
+// pass is all launch latency and the tile kernels are as fast.
+static bool smallm_rows_ok(const LayerView &w, int M) {
+    if (M <= SMALLM_ROWS) return true;
+    return M <= SMALLM_MAX_M && (size_t)w.K * w.N * w.bits / 8 >= ((size_t)4 << 20);
+}
+
 bool smallm_bwd_supported(const LayerView &w, int M) {
-    if (M > 16) return false;
+    if (!smallm_rows_ok(w, M)) return false;
     // a 128-column tile lies inside one quantization group, or covers exactly two
     const bool group_ok = w.group % smb::KT == 0 || w.group == smb::KT / 2;
     return group_ok && w.K % smb::KT == 0 && w.N % sm::PREP_K == 0 && pick_nsplit(w.N, w.K) > 0;
 }
 
 bool smallm_fwd_supported(const LayerView &w, int M) {
-    if (M > 16) return false;
+    if (!smallm_rows_ok(w, M)) return false;
     const int kstep = w.bits == 4 ? 32 : (w.bits == 2 ? 64 : 128);
     return w.group % kstep == 0 && w.K % sm::PREP_K == 0 && pick_ksplit(w.K, w.N, w.group) > 0;
 }
@@ -1304,7 +1311,25 @@ static hipError_t launch_fwd_any(const SmallFwdDev &d, int bits, bool spg1, int 
     }
 }
 
+// The rows beyond the first SMALLM_ROWS of a call: the same arguments, advanced by that many rows
+// of the input (row length C), the output (row length Cout) and the projection hand-off.
+static SmallArgs rows_after_first_pass(const SmallArgs &a, int C, int Cout) {
+    SmallArgs b = a;
+    b.act = a.act + (size_t)SMALLM_ROWS * C;
+    b.out = a.out + (size_t)SMALLM_ROWS * Cout;
+    if (a.P_out) b.P_out = a.P_out + (size_t)SMALLM_ROWS * a.r;
+    b.M = a.M - SMALLM_ROWS;
+    return b;
+}
+
 hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
+    if (a.M > SMALLM_ROWS) {
+        SmallArgs first = a;
+        first.M = SMALLM_ROWS;
+        const hipError_t e1 = launch_smallm_fwd(first, stream);
+        if (e1 != hipSuccess) return e1;
+        return launch_smallm_fwd(rows_after_first_pass(a, a.w.K, a.w.N), stream);
+    }
     const int K = a.w.K, N = a.w.N;
     const SmallWs l = small_ws(K, N, a.r);
     char *ws = static_cast<char *>(a.ws);
@@ -1366,6 +1391,13 @@ static hipError_t launch_bwd_any(const SmallBwdDev &d, int bits, int k_blocks, h
 }
 
 hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
+    if (a.M > SMALLM_ROWS) {
+        SmallArgs first = a;
+        first.M = SMALLM_ROWS;
+        const hipError_t e1 = launch_smallm_bwd(first, stream);
+        if (e1 != hipSuccess) return e1;
+        return launch_smallm_bwd(rows_after_first_pass(a, a.w.N, a.w.K), stream);
+    }
     const int K = a.w.K, N = a.w.N;
     const SmallWs l = small_ws(K, N, a.r);
     char *ws = static_cast<char *>(a.ws);

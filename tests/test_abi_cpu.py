@@ -124,7 +124,9 @@ def test_rejections_adamw():
 
 def test_workspace_bytes():
     w = qw()
-    assert b.lib.modulora_workspace_bytes(ctypes.byref(w), 32, 0) == 0        # r = 0, tile kernels: none
+    # r = 0 at M = 32: 16 tiles of 128 x 256, each cut into 8 slices of the contraction (more than
+    # the streaming kernels' scratch for two passes of 16 rows)
+    assert b.lib.modulora_workspace_bytes(ctypes.byref(w), 32, 0) == 16 * 8 * 128 * 256 * 4
     # r = 0 at M = 512: 2 x 16 tiles of 256 x 256, each cut into 8 slices of the contraction
     # that leave fp32 partial tiles
     assert b.lib.modulora_workspace_bytes(ctypes.byref(w), 512, 0) == 32 * 8 * 256 * 256 * 4
@@ -169,10 +171,12 @@ def test_rejections_of_the_f16_calls(call):
     assert call(qh(), ws=0) == 7
     assert call(qh(), wsb=16) == 7
     assert call(qh(), ws=FAKE + 16) == 7
-    # 20 tokens without adapter need no scratch (valid; no GPU here, so the launch itself may fail);
-    # 16 tokens take the streaming kernels, whose slices meet in the workspace
-    assert call(qh(), M=20, r=0, A=0, B=0, ws=0, wsb=0) in (0, 8)
+    # 4096 tokens without adapter are exactly 256 whole tiles and need no scratch (valid; no GPU here,
+    # so the launch itself may fail); 16 or 20 tokens take the streaming kernels, whose slices meet
+    # in the workspace
+    assert call(qh(), M=4096, r=0, A=0, B=0, ws=0, wsb=0) in (0, 8)
     assert call(qh(), M=16, r=0, A=0, B=0, ws=0, wsb=0) == 7
+    assert call(qh(), M=20, r=0, A=0, B=0, ws=0, wsb=0) == 7
 
 
 def test_f16_workspace_query_and_dequant_rejections():

@@ -80,6 +80,8 @@ SHAPES = [
 # sizes down to one step), forward and backward (N and group multiples of 128), and N split over
 # workgroups whose waves get unequal numbers of steps
 STREAM_SHAPES = [
+    (3, 4096, 4096, 17, 8, 128, True),       # 17 .. 32 tokens over more than 4 MB of codes: two passes
+    (4, 2560, 4096, 32, 16, 64, False),
     (3, 1024, 808, 16, 8, 128, True),
     (3, 2560, 264, 3, 5, 256, False),
     (2, 768, 296, 5, 4, 64, True),
@@ -103,11 +105,11 @@ STREAM_SHAPES = [
 
 
 def code_domain_allowance(D, M):
-    """What the M <= 16 streaming kernels may differ by from materialize-then-multiply: they multiply
+    """What the streaming kernels (M <= 32) may differ by from materialize-then-multiply: they multiply
     by the codes directly, so What is not rounded to binary16 first (2^-11 relative per weight), and
     the backward kernel rounds dY * scale to binary16 (another 2^-11 per term; a product below the
     normal range keeps 2^-25 absolute)."""
-    if M > 16:
+    if M > 32:
         return 0.0, 0.0
     Wabs = np.abs(synth.f16_bits_to_f64(pl.dequant_f16(*oargs(D))))          # [N][K]
     Xabs, dYabs = np.abs(synth.f16_bits_to_f64(D["X"])), np.abs(synth.f16_bits_to_f64(D["dY"]))
@@ -159,13 +161,15 @@ def test_one_hot_activations_pick_out_single_weights():
 def test_streaming_shapes_run_the_streaming_kernels():
     """The M <= 16 shapes above do reach the streaming kernels (in both directions where N and the
     group size allow)."""
-    D = layer(3, 1024, 768, 16, 8, 128)
-    b.modulora_profile_begin()
-    b.modulora_f16_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], 2.0)
-    b.modulora_f16_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], 2.0)
-    torch.cuda.synchronize()
-    names = set(b.modulora_profile_end())
-    assert {"f16_stream_fwd", "f16_stream_fwd_finish", "f16_stream_bwd", "f16_stream_bwd_finish"} <= names, names
+    for K, N, M, passes in ((1024, 768, 16, 1), (4096, 4096, 20, 2)):
+        D = layer(3, K, N, M, 8, 128)
+        b.modulora_profile_begin()
+        b.modulora_f16_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], 2.0)
+        b.modulora_f16_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], 2.0)
+        torch.cuda.synchronize()
+        prof = b.modulora_profile_end()
+        assert {k: v[0] for k, v in prof.items()} == {k: passes for k in ("f16_stream_fwd", "f16_stream_fwd_finish", "f16_stream_bwd",
+                                                                          "f16_stream_bwd_finish")}, prof
 
 
 @pytest.mark.parametrize("group", [128, 64])

@@ -109,6 +109,10 @@ SHAPES = [
     # few rows and a deep contraction: the rank-r projection is split over workgroups too
     (3, 4096, 264, 40, 40, 128),
     (4, 256, 6144, 100, 64, 32),
+    # 17 .. 32 tokens over a weight of more than 4 MB of codes: two passes of the streaming kernels
+    (3, 4096, 4096, 17, 8, 128),
+    (4, 2560, 4096, 32, 16, 64),
+    (2, 8192, 2176, 24, 5, 128),
     # about a hundred 128 x 64 tiles: the producer / consumer kernel, with a ragged row tile, a
     # ragged column tile, a ragged last 128-deep step in both directions and 16-deep adapter steps
     (3, 2112, 2136, 300, 8, 64),
@@ -139,13 +143,13 @@ def test_forward_backward_against_oracle(bits, K, N, M, r, group):
     s = L["lora_scale"]
     A, B = (L["A"], L["B"]) if r else (None, None)
 
-    # At M <= 16 the library may multiply by the codes directly, i.e. without the oracle's
+    # For a handful of tokens (M <= 32) the library may multiply by the codes directly, i.e. without the oracle's
     # intermediate rounding of What to bfloat16 (half an ulp, at most 2^-8 relative per
     # weight): allow exactly that much, as the rigorous bound 2^-8 * |act| |What|^T.  The
     # backward kernel instead rounds dY * scale to bfloat16 (another 2^-8 per term), hence
     # 2^-7 there.
     extra_Y = extra_dX = 0.0
-    if M <= 16:
+    if M <= 32:
         Wabs = np.abs(oracle.dequant_f32(*oracle_args(L)).astype(np.float64))      # [N][K]
         extra_Y = 2.0 ** -8 * (np.abs(synth.bf16_bits_to_f64(L["X"])) @ Wabs.T)
         extra_dX = 2.0 ** -7 * (np.abs(synth.bf16_bits_to_f64(L["dY"])) @ Wabs)
@@ -177,16 +181,21 @@ def test_forward_backward_against_oracle(bits, K, N, M, r, group):
 
 
 def test_small_token_counts_run_the_streaming_kernels():
-    """BASELINE config 1 (group 64) and a group-128 layer reach the streaming kernels in both directions."""
-    for bits, K, N, group in ((4, 256, 256, 64), (3, 1024, 768, 128)):
-        L = layer(bits, K, N, 16, 8, group, seed=2)
+    """BASELINE config 1 (group 64) and a group-128 layer reach the streaming kernels in both directions;
+    so do 17 .. 32 tokens over a weight of at least 4 MB of codes (two passes: twice the launches), while
+    a smaller weight at those token counts and 33 tokens do not."""
+    for bits, K, N, M, group, passes in ((4, 256, 256, 16, 64, 1), (3, 1024, 768, 16, 128, 1), (3, 4096, 4096, 17, 128, 2),
+                                         (2, 8192, 2176, 32, 128, 2), (3, 1024, 768, 17, 128, 0), (3, 4096, 4096, 33, 128, 0)):
+        L = layer(bits, K, N, M, 8, group, seed=2)
         D = to_device(L)
         b.modulora_profile_begin()
         b.modulora_fwd(D["w"], D["Xd"], D["Ad"], D["Bd"], 2.0)
         b.modulora_bwd_input(D["w"], D["dYd"], D["Ad"], D["Bd"], 2.0)
         torch.cuda.synchronize()
-        names = set(b.modulora_profile_end())
-        assert {"stream_fwd", "stream_fwd_finish", "stream_bwd", "stream_bwd_finish"} <= names, (group, names)
+        prof = b.modulora_profile_end()
+        stream = {k: v[0] for k, v in prof.items() if k.startswith("stream_")}
+        want = {k: passes for k in ("stream_fwd", "stream_fwd_finish", "stream_bwd", "stream_bwd_finish")} if passes else {}
+        assert stream == want, (bits, K, N, M, group, prof)
 
 
 @pytest.mark.parametrize("group", [128, 64])
@@ -211,6 +220,30 @@ def test_streaming_kernels_pick_out_single_weights(bits, group):
         rows = eyeN[lo:lo + 16].contiguous()
         dX, _ = b.modulora_bwd_input(D["w"], rows, None, None, 1.0)
         assert np.all(np.abs(f64(dX) - Wf[lo:lo + 16]) <= 2.0 ** -7 * np.abs(Wf[lo:lo + 16]))
+
+
+def test_second_streaming_pass_picks_out_the_right_rows():
+    """One-hot rows 0 .. 31 through the two-pass form (17 .. 32 tokens): row m of the output is
+    column / row hot[m] of the weight, so a second pass that read or wrote at the wrong row offset
+    would put the wrong weights there."""
+    K, N = 4096, 4096
+    L = layer(3, K, N, 1, 0, 128, seed=8)
+    D = to_device(L)
+    What = oracle.dequant_bf16(*oracle_args(L))
+    hot = (np.arange(29) * 139 + 5) % K
+    rows = torch.zeros((29, K), dtype=torch.bfloat16, device="cuda")
+    rows[torch.arange(29), torch.from_numpy(hot).cuda()] = 1.0
+    b.modulora_profile_begin()
+    Y, _ = b.modulora_fwd(D["w"], rows, None, None, 1.0)
+    torch.cuda.synchronize()
+    assert b.modulora_profile_end()["stream_fwd"][0] == 2
+    assert np.array_equal(bits16(Y), What.T[hot])
+    hot = (np.arange(32) * 131 + 7) % N
+    rows = torch.zeros((32, N), dtype=torch.bfloat16, device="cuda")
+    rows[torch.arange(32), torch.from_numpy(hot).cuda()] = 1.0
+    dX, _ = b.modulora_bwd_input(D["w"], rows, None, None, 1.0)
+    Wf = synth.bf16_bits_to_f64(What)
+    assert np.all(np.abs(f64(dX) - Wf[hot]) <= 2.0 ** -7 * np.abs(Wf[hot]))
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])

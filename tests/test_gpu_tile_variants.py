@@ -1,8 +1,7 @@
 """Every tile variant the automatic choice can reach, against the oracle.
 
 The library picks a tile kernel from the shape alone (a table of measured step costs).  Besides
-the 256 x 256, the 128 x 64 producer / consumer and the 32 x 256 kernels that the benchmark
-shapes land on, ordinary shapes reach four more variants of the generic tile kernel: 64 x 128
+the 256 x 256 and the 128 x 64 producer / consumer kernels that the benchmark shapes land on, ordinary shapes reach four more variants of the generic tile kernel: 64 x 128
 with two k-groups (a few dozen tokens, very wide outputs), 64 x 128, 128 x 128 and 256 x 128;
 and token counts whose last block of 256 rows would be at most half full take the 256 x 256
 kernel's instantiation with 128-row tiles.
