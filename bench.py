@@ -36,7 +36,7 @@ ROTATE_BYTES = 512 << 20        # distinct packed weights touched before one is 
 COPY_CAL_BYTES = 1 << 30        # size of the copy that calibrates the rocprofv3 byte counters
 REPEATS = 5                     # timed replays of the K steps; the median is reported
 HEADLINE = ("c5_65b_up", 4096)  # the largest single-GPU configuration
-ORACLE_ROWS = 64                # token rows the CPU oracle computes where a full step would take minutes
+ORACLE_ROWS = 768               # token rows the CPU oracle computes where a full step would take minutes
 
 
 def parse_args():
