@@ -557,7 +557,9 @@ def rocprof_kernel_pattern(lib_name: str) -> str:
         return "gemm_tile_kernel<%d, true"
     return {"stream_fwd": "smallm_fwd_kernel<%d", "stream_bwd": "smallm_bwd_kernel<%d",
             "stream_fwd_finish": "smallm_fwd_finish_kernel", "stream_bwd_finish": "smallm_bwd_finish_kernel",
-            "smallm_prep_fwd": "smallm_prep_fwd_kernel", "smallm_prep_bwd": "smallm_prep_bwd_kernel",
+            "f16_stream_fwd": "smallm_fwd_kernel<%d", "f16_stream_bwd": "smallm_bwd_kernel<%d",
+            "f16_stream_fwd_finish": "smallm_fwd_finish_kernel", "f16_stream_bwd_finish": "smallm_bwd_finish_kernel",
+            "lora_down_finish": "lora_down_finish_kernel", "adamw": "adamw_kernel",
             "lora_down": "lora_down_kernel", "lora_grad": "lora_grad_partial_kernel",
             "lora_grad_reduce": "lora_grad_reduce_kernel"}.get(lib_name, lib_name)
 

@@ -18,7 +18,7 @@ def test_roofline_kernel_name_mapping_covers_every_profiled_kernel():
     import bench
 
     for name in ("gemm_fwd_256x256", "gemm_bwd_256x256", "gemm_fwd_128x256", "gemm_bwd_128x256", "gemm_fwd_64x128k", "gemm_fwd_128x64s", "gemm_bwd_128x64s", "gemm_bwd_64x128", "stream_fwd",
-                 "stream_bwd", "stream_fwd_finish", "stream_bwd_finish", "smallm_prep_fwd", "smallm_prep_bwd",
+                 "stream_bwd", "stream_fwd_finish", "stream_bwd_finish", "f16_stream_fwd", "f16_stream_bwd_finish", "lora_down_finish",
                  "lora_down", "lora_grad", "lora_grad_reduce"):
         pat = bench.rocprof_kernel_pattern(name)
         assert "kernel" in pat, (name, pat)

@@ -4,8 +4,8 @@ every replay is compared bit for bit with an eager run on the same inputs (the k
 atomics, so results do not depend on timing), with the program's own eager work and
 synchronizations between the replays and new inputs written into the captured buffers each time.
 The shapes cover the launch configurations: the 128 x 64 producer / consumer kernel, the
-streaming kernels (M <= 16, one and two quantization groups per backward tile), the 256 x 256
-kernel with a split contraction and its second launch, and the projection kernel's two forms
+streaming kernels (M <= 16, one and two quantization groups per backward tile; two passes for 24
+tokens), the 256 x 256 kernel and its 128-row instantiation with a split contraction and the second launch, and the projection kernel's two forms
 (one row tile per workgroup; four that share the factor, with its finish launch), each with the
 adapter-gradient launches."""
 import pytest
@@ -25,6 +25,8 @@ pytestmark = pytest.mark.gpu
     (4, 320, 8232, 300, 16, 64),
     (4, 512, 640, 16, 16, 64),        # streaming kernels, two quantization groups per backward tile
     (2, 6400, 520, 1100, 8, 64),      # projection with four row tiles per workgroup, slices of the contraction + finish
+    (3, 4096, 1024, 128, 8, 128),     # 128-row instantiation of the 256-column kernel, split contraction + fix-up
+    (3, 4096, 4096, 24, 8, 128),      # two passes of the streaming kernels that share the scratch
 ])
 def test_graph_replays_equal_eager_steps(bits, K, N, M, r, group):
     L = layer(bits, K, N, M, r, group, seed=4)
