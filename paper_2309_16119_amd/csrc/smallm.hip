@@ -292,17 +292,34 @@ __device__ __forceinline__ void smallm_project_f16(const uint16_t *act, int M, i
 }
 
 // Sum of the projection workgroups' partials into Us (16 x r floats in LDS).
+template <int EPT>
 __device__ __forceinline__ void smallm_sum_parts(const float *parts, int n_parts, int r, float *Us) {
-    for (int t = threadIdx.x; t < 16 * r; t += blockDim.x) {
-        float sum = 0.f;
-        for (int b0 = 0; b0 < n_parts; b0 += 16) {   // n_parts <= 32; sixteen loads in flight together
-            float v[16];
+    // EPT elements per thread and up to sixteen workgroups' partials of each in flight together
+    // (n_parts <= 32), so that a small workgroup and a large rank still wait for few round trips
+    const int n = 16 * r, stride = blockDim.x;
+    for (int t0 = threadIdx.x; t0 < n; t0 += EPT * stride) {
+        float sum[EPT];
 #pragma unroll
-            for (int b = 0; b < 16; ++b) v[b] = b0 + b < n_parts ? parts[(size_t)(b0 + b) * 16 * r + t] : 0.f;
+        for (int q = 0; q < EPT; ++q) sum[q] = 0.f;
+        for (int b0 = 0; b0 < n_parts; b0 += 16) {
+            float v[EPT][16];
 #pragma unroll
-            for (int b = 0; b < 16; ++b) sum += v[b];
+            for (int q = 0; q < EPT; ++q) {
+                const int t = t0 + q * stride;
+#pragma unroll
+                for (int b = 0; b < 16; ++b) {     // clamped, not predicated: past the end the last one is re-read and not added
+                    const int bb = b0 + b < n_parts ? b0 + b : n_parts - 1;
+                    v[q][b] = parts[(size_t)bb * n + (t < n ? t : n - 1)];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < EPT; ++q)
+#pragma unroll
+                for (int b = 0; b < 16; ++b) sum[q] += b0 + b < n_parts ? v[q][b] : 0.f;
         }
-        Us[t] = sum;
+#pragma unroll
+        for (int q = 0; q < EPT; ++q)
+            if (t0 + q * stride < n) Us[t0 + q * stride] = sum[q];
     }
     __syncthreads();
 }
@@ -704,7 +721,7 @@ __global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(Small
         if (mine && u < d.ksplit) v[u] = *reinterpret_cast<const float4 *>(d.Yacc + ((size_t)u * 16 + m) * N + col);
     }
     if (mine) smallm_load_b8(d, 0, col, b0);
-    smallm_sum_parts(d.Upart, d.n_proj, d.r, Us);
+    smallm_sum_parts<1>(d.Upart, d.n_proj, d.r, Us);
 #pragma unroll
     for (int u = 0; u < 8; ++u) { y[0] += v[u].x; y[1] += v[u].y; y[2] += v[u].z; y[3] += v[u].w; }
     if (mine) {
@@ -1134,48 +1151,53 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
     }
 }
 
-// Sum of the N slices' partial tiles, adapter term, bfloat16 store.  One workgroup per 128
-// columns: thread t owns row t / 16, columns 8 (t % 16) .. + 7.
+// Sum of the N slices' partial tiles, adapter term, 16-bit store.  One single-wave workgroup per 32
+// columns (a few dozen 256-thread workgroups left most of the chip idle while each waited for its
+// chain of loads): lane l owns row l / 4, columns 8 (l % 4) .. + 7.
+constexpr int BWD_FIN_COLS = 32;
 template <bool F16>
-__global__ __launch_bounds__(sm::WG_THREADS) void smallm_bwd_finish_kernel(SmallBwdDev d) {
+__global__ __launch_bounds__(64) void smallm_bwd_finish_kernel(SmallBwdDev d) {
     __shared__ float Ts[16 * 64];
     const int tid = threadIdx.x, K = d.w.K;
-    const int m = tid >> 4, k0 = blockIdx.x * 128 + 8 * (tid & 15);
+    const int m = tid >> 2, k0 = blockIdx.x * BWD_FIN_COLS + 8 * (tid & 3);
     float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // the first columns of the eight rows of A are fetched ahead of everything that waits
     float4 a0[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) a0[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (m < d.M && d.r > 0) smallm_load_a8(d, k0, 0, a0);
-    // four slices' loads (two 16-byte loads each) in flight at a time; the first four are issued
+    // eight slices' loads (two 16-byte loads each) in flight at a time; the first eight are issued
     // before the projection partials are summed and consumed after
-    float4 v0[4], v1[4];
-    auto load4 = [&](int q0) {
+    constexpr int SB = 8;
+    float4 v0[SB], v1[SB];
+    // (slices past the last one re-read the last and are not added: one predicate for all the loads
+    // of a batch instead of one per slice keeps the scalar registers within bounds)
+    const float *mine = d.acc + (size_t)(m < d.M ? m : 0) * K + k0;
+    const size_t slice_stride = (size_t)16 * K;
+    auto load_slices = [&](int q0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            v0[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            v1[u] = v0[u];
-            if (m < d.M && q0 + u < d.nsplit) {
-                const float *src = d.acc + ((size_t)(q0 + u) * 16 + m) * K + k0;
-                v0[u] = *reinterpret_cast<const float4 *>(src);
-                v1[u] = *reinterpret_cast<const float4 *>(src + 4);
+        for (int u = 0; u < SB; ++u) {
+            const int sl = q0 + u < d.nsplit ? q0 + u : d.nsplit - 1;
+            const float *src = mine + (size_t)sl * slice_stride;
+            v0[u] = *reinterpret_cast<const float4 *>(src);
+            v1[u] = *reinterpret_cast<const float4 *>(src + 4);
+        }
+    };
+    auto add_slices = [&](int q0) {
+#pragma unroll
+        for (int u = 0; u < SB; ++u) {
+            if (q0 + u < d.nsplit) {
+                y[0] += v0[u].x; y[1] += v0[u].y; y[2] += v0[u].z; y[3] += v0[u].w;
+                y[4] += v1[u].x; y[5] += v1[u].y; y[6] += v1[u].z; y[7] += v1[u].w;
             }
         }
     };
-    auto add4 = [&]() {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            y[0] += v0[u].x; y[1] += v0[u].y; y[2] += v0[u].z; y[3] += v0[u].w;
-            y[4] += v1[u].x; y[5] += v1[u].y; y[6] += v1[u].z; y[7] += v1[u].w;
-        }
-    };
-    load4(0);
-    smallm_sum_parts(d.Tpart, d.n_proj, d.r, Ts);
-    add4();
-    if (m < d.M)
-        for (int q0 = 4; q0 < d.nsplit; q0 += 4) { load4(q0); add4(); }
+    load_slices(0);
+    smallm_sum_parts<2>(d.Tpart, d.n_proj, d.r, Ts);
+    add_slices(0);
+    for (int q0 = SB; q0 < d.nsplit; q0 += SB) { load_slices(q0); add_slices(q0); }
     if (blockIdx.x == 0 && d.T_out != nullptr)
-        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.T_out[t] = Ts[t];
+        for (int t = tid; t < d.M * d.r; t += 64) d.T_out[t] = Ts[t];
     if (m < d.M) smallm_bwd_store8<F16>(d, Ts, m, k0, y, a0);
 }
 
@@ -1424,8 +1446,8 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     d.zeros16 = a.zeros16;
     e = a.f16 ? launch_bwd_any<true>(d, a.w.bits, k_blocks, stream) : launch_bwd_any<false>(d, a.w.bits, k_blocks, stream);
     if (e != hipSuccess) return e;
-    if (a.f16) launch_kernel("f16_stream_bwd_finish", smallm_bwd_finish_kernel<true>, k_blocks, sm::WG_THREADS, 0, stream, d);
-    else launch_kernel("stream_bwd_finish", smallm_bwd_finish_kernel<false>, k_blocks, sm::WG_THREADS, 0, stream, d);
+    if (a.f16) launch_kernel("f16_stream_bwd_finish", smallm_bwd_finish_kernel<true>, K / BWD_FIN_COLS, 64, 0, stream, d);
+    else launch_kernel("stream_bwd_finish", smallm_bwd_finish_kernel<false>, K / BWD_FIN_COLS, 64, 0, stream, d);
     return hipGetLastError();
 }
 
