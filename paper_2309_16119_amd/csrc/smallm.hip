@@ -601,44 +601,80 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
     }
     __syncthreads();
 
-    f32x4 yacc[4], tmp[4], s1, s2;
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-#pragma unroll
-        for (int cs = 0; cs < 4; ++cs) { yacc[cs][v] = 0.f; tmp[cs][v] = 0.f; }
-        s1[v] = 0.f; s2[v] = 0.f;
-    }
     using NF = sm::Num<F16>;
     const uint32_t ones4[4] = {NF::ONES, NF::ONES, NF::ONES, NF::ONES};
     const uint32_t offs4[4] = {NF::MAGIC3, NF::MAGIC3, NF::MAGIC3, NF::MAGIC3};   // 3-bit: the two offsets themselves
     const bf16x8 ones = sm::as_bf16x8(ones4), offs = sm::as_bf16x8(offs4);
     const sm::CodeMasks masks = sm::make_masks<BITS, F16>();
 
-    auto compute = [&](Stage &sd, int srel, bool group_ends) {
+    // What the affine part of eq. (2) needs of the activations alone, once per workgroup instead of
+    // in every wave's loop: for each quantization group of the slice and each row,
+    //   gs[g][0][m] = -sum_k offset_k X[m][k]   (what the operands' offsets 8 / 128 / 1024 add to the product)
+    //   gs[g][1][m] =  sum_k X[m][k]            (the zero point's factor)
+    // by the same MFMAs against constant vectors; wave w takes groups w, w + 8, ...  Behind the
+    // slice in LDS.
+    float *gs = reinterpret_cast<float *>(xs + (size_t)(s_end - s_begin) * (G::KSTEP / 8) * 16);
+    for (int g = wave; g < g_end - g_begin; g += sm::FWD_WAVES) {
+        f32x4 a1 = {0.f, 0.f, 0.f, 0.f}, a2 = {0.f, 0.f, 0.f, 0.f};
+        for (int srel = g * spg; srel < (g + 1) * spg; ++srel) {
+            const uint4 *xrow = xs + ((size_t)srel * 4 * G::NC + G::NC * j) * 16 + i;
+#pragma unroll
+            for (int c = 0; c < G::NC; ++c) {
+                const bf16x8 a = sm::as_bf16x8(xrow[c * 16]);
+                a1 = sm::mma<F16>(a, BITS == 3 ? offs : ones, a1);
+                if (BITS == 3) a2 = sm::mma<F16>(a, ones, a2);
+            }
+        }
+        // D register v of lane (i, j): row 4 j + v, the same value in every column i
+        if (i == 0) {
+            const f32x4 neg = BITS == 3 ? f32x4{-a1[0], -a1[1], -a1[2], -a1[3]}
+                                        : f32x4{-NF::OFFSET * a1[0], -NF::OFFSET * a1[1], -NF::OFFSET * a1[2], -NF::OFFSET * a1[3]};
+            *reinterpret_cast<f32x4 *>(gs + (g * 2 + 0) * 16 + 4 * j) = neg;
+            *reinterpret_cast<f32x4 *>(gs + (g * 2 + 1) * 16 + 4 * j) = BITS == 3 ? a2 : a1;
+        }
+    }
+    __syncthreads();
+
+    f32x4 yacc[4], tmp[4], xsum;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+#pragma unroll
+        for (int cs = 0; cs < 4; ++cs) { yacc[cs][v] = 0.f; tmp[cs][v] = 0.f; }
+        xsum[v] = 0.f;
+    }
+
+    // grel: the step's quantization group inside the slice; group_begins / group_ends: first / last step of it
+    auto compute = [&](Stage &sd, int srel, int grel, bool group_begins, bool group_ends) {
         // operand chunks 4 NC srel + NC j + c of the slice, row i
         const uint4 *xrow = xs + ((size_t)srel * 4 * G::NC + G::NC * j) * 16 + i;
         uint4 xa[G::NC];
 #pragma unroll
         for (int c = 0; c < G::NC; ++c) xa[c] = xrow[c * 16];
-        const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+        // the products start from minus the offsets' share, so that they end at sum X q
+        f32x4 start = {0.f, 0.f, 0.f, 0.f};
+        if (SPG1 || group_begins) {
+            start = *reinterpret_cast<const f32x4 *>(gs + (grel * 2 + 0) * 16 + 4 * j);
+            xsum = *reinterpret_cast<const f32x4 *>(gs + (grel * 2 + 1) * 16 + 4 * j);
+            if (!SPG1) {
+#pragma unroll
+                for (int cs = 0; cs < 4; ++cs) tmp[cs] = start;
+            }
+        }
 #pragma unroll
         for (int c = 0; c < G::NC; ++c) {
             const bf16x8 a = sm::as_bf16x8(xa[c]);
-            const bool fresh = SPG1 && c == 0;       // first call of a one-step group: C = 0
+            const bool fresh = SPG1 && c == 0;       // first call of a one-step group
 #pragma unroll
             for (int cs = 0; cs < 4; ++cs) {
                 uint32_t wq[G::WORDS], o[4];
 #pragma unroll
                 for (int q = 0; q < G::WORDS; ++q) wq[q] = sd.w[q][cs];
                 sm::codes_to_operand<BITS>(wq, c, masks, o);
-                tmp[cs] = sm::mma<F16>(a, sm::as_bf16x8(o), fresh ? zero4 : tmp[cs]);
+                tmp[cs] = sm::mma<F16>(a, sm::as_bf16x8(o), fresh ? start : tmp[cs]);
             }
-            // 4- and 2-bit: s1 = sum X.  3-bit: s1 = sum offset * X, s2 = sum X.
-            s1 = sm::mma<F16>(a, BITS == 3 ? offs : ones, fresh ? zero4 : s1);
-            if (BITS == 3) s2 = sm::mma<F16>(a, ones, fresh ? zero4 : s2);
         }
         if (!SPG1 && !group_ends) return;
-        // end of a group: tmp = sum X (offset + q); remove the offsets, apply zero point and scale
+        // end of a group: tmp = sum X q (the offsets' share was taken off at the start); apply zero point and scale
 #pragma unroll
         for (int cs = 0; cs < 4; ++cs) {
             const float scale = half_bits_to_float((uint16_t)(sd.sc[cs >> 1] >> (16 * (cs & 1))));
@@ -646,20 +682,14 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
             const float zero = F16 ? half_bits_to_float((uint16_t)(sd.z16[cs >> 1] >> (16 * (cs & 1)))) : (float)((sd.z >> (8 * cs)) & 0xFFu);
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const float xsum = BITS == 3 ? s2[v] : s1[v];
-                const float qx = BITS == 3 ? tmp[cs][v] - s1[v] : __builtin_fmaf(-NF::OFFSET, s1[v], tmp[cs][v]);   // sum X q
-                if (F16) yacc[cs][v] = __builtin_fmaf(scale, qx, __builtin_fmaf(zero, xsum, yacc[cs][v]));
-                else yacc[cs][v] = __builtin_fmaf(scale, __builtin_fmaf(-zero, xsum, qx), yacc[cs][v]);
-                if (!SPG1) tmp[cs][v] = 0.f;
+                const float qx = tmp[cs][v];                                                             // sum X q
+                if (F16) yacc[cs][v] = __builtin_fmaf(scale, qx, __builtin_fmaf(zero, xsum[v], yacc[cs][v]));
+                else yacc[cs][v] = __builtin_fmaf(scale, __builtin_fmaf(-zero, xsum[v], qx), yacc[cs][v]);
             }
-        }
-        if (!SPG1) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) { s1[v] = 0.f; s2[v] = 0.f; }
         }
     };
 
-    int cp = 0;   // position of the next step inside its group
+    int cp = 0, grel = 0;   // position of the next step inside its group; that group's index inside the slice
     for (int s = s_begin; s < s_end; s += DEPTH) {
 #pragma unroll
         for (int dd = 0; dd < DEPTH; ++dd) {
@@ -670,9 +700,10 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
                 for (int q = 0; q < G::WORDS; ++q) sm::tie(st[dd].w[q]);
                 sm::tie(st[dd].sc);
                 if (F16) sm::tie(st[dd].z16); else sm::tie(st[dd].z);
+                const bool begins = cp == 0;
                 const bool ends = ++cp == spg;
-                if (ends) cp = 0;
-                compute(st[dd], s + dd - s_begin, ends);
+                compute(st[dd], s + dd - s_begin, grel, begins, ends);
+                if (ends) { cp = 0; ++grel; }
                 const int sn = s + dd + DEPTH;
                 issue(st[dd], sn < s_end ? sn : s_end - 1);
             }
@@ -1319,7 +1350,8 @@ template <int BITS, bool SPG1, bool F16>
 static hipError_t launch_fwd_bits(const SmallFwdDev &d, int col_blocks, size_t lds_bytes, hipStream_t stream) {
     auto kern = smallm_fwd_kernel<BITS, SPG1, F16>;
     static bool configured[64] = {};
-    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32, configured);
+    // the largest slice plus its per-group sums (groups of at least 32 codes)
+    const hipError_t e = ensure_lds_limit(reinterpret_cast<const void *>(kern), (size_t)sm::MAX_RANGE * 32 + (sm::MAX_RANGE / 32) * 128, configured);
     if (e != hipSuccess) return e;
     launch_kernel(F16 ? "f16_stream_fwd" : "stream_fwd", kern, col_blocks * d.ksplit + d.n_proj, sm::FWD_THREADS, lds_bytes, stream, d);
     return hipGetLastError();
@@ -1380,7 +1412,9 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     d.bias16 = a.bias16;
     // LDS for the largest slice: ceil(groups / ksplit) groups of 32 bytes per contraction element
     const int n_groups = K / a.w.group;
-    size_t lds_bytes = (size_t)((n_groups + ksplit - 1) / ksplit) * a.w.group * 32;
+    // ... plus the per-group sums behind the slice: 2 x 16 floats per group
+    const size_t groups_per_slice = (size_t)((n_groups + ksplit - 1) / ksplit);
+    size_t lds_bytes = groups_per_slice * a.w.group * 32 + groups_per_slice * 128;
     if (lds_bytes < 32 * 1024) lds_bytes = 32 * 1024;      // the projection workgroups' wave reduction
     const int kstep = a.w.bits == 4 ? 32 : (a.w.bits == 2 ? 64 : 128);
     const bool spg1 = a.w.group == kstep;             // one step per quantization group
