@@ -19,8 +19,10 @@
 // mantissa of bfloat16 128.0 (0x4300) gives exactly 128 + q, so
 //     ((word >> s) & 0x000F000F) | 0x43004300
 // is two bfloat16 operands (128 + q_a, 128 + q_b) at once.  The +128 is removed with the
-// help of one extra MFMA per step against a vector of ones (it yields sum_k X[m][k], which
-// the zero point needs anyway).  Which two codes share a register is fixed by the bit
+// help of an MFMA against a vector of ones (it yields sum_k X[m][k], which the zero point
+// needs anyway); these sums depend on the activations only, so a workgroup computes them once
+// per quantization group of its slice, and every product starts from minus the offsets'
+// share instead of zero.  Which two codes share a register is fixed by the bit
 // layout, so every workgroup re-orders its slice of X to the same order on its way into LDS.
 // For 3-bit codes the
 // low field of a register lands four bits high; there the field is OR-ed into bfloat16 8.0
