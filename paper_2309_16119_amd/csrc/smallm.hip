@@ -438,49 +438,64 @@ constexpr int BCOLS = FWD_WAVES * WCOLS;  // columns per workgroup
 constexpr int MAX_RANGE = 2048;           // contraction elements of one K slice (64 KB of LDS)
 }  // namespace sm
 
-// The eight rows jj0 .. jj0 + 7 of B at columns col .. col + 3, all loads issued together (rows
+// The eight rows jj0 .. jj0 + 7 of B at columns col .. col + 7, all loads issued together (rows
 // past r come back as zeros).
-__device__ __forceinline__ void smallm_load_b8(const SmallFwdDev &d, int jj0, int col, float4 b[8]) {
+constexpr int FIN_BROWS = 8;
+__device__ __forceinline__ void smallm_load_b8x8(const SmallFwdDev &d, int jj0, int col, float4 b[FIN_BROWS][2]) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-        b[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (jj0 + q < d.r) b[q] = *reinterpret_cast<const float4 *>(d.B + (size_t)(jj0 + q) * d.w.N + col);
+    for (int q = 0; q < FIN_BROWS; ++q) {
+        b[q][0] = make_float4(0.f, 0.f, 0.f, 0.f);
+        b[q][1] = b[q][0];
+        if (jj0 + q < d.r) {
+            const float *src = d.B + (size_t)(jj0 + q) * d.w.N + col;
+            b[q][0] = *reinterpret_cast<const float4 *>(src);
+            b[q][1] = *reinterpret_cast<const float4 *>(src + 4);
+        }
     }
 }
 
-// Adds the adapter term to the four adjacent outputs y[0..3] of row m, columns col..col+3
-// (col a multiple of 4, col + 3 < N) and stores them as 16-bit floats.  `b0`: rows 0 .. 7 of B
-// for these columns, loaded by the caller ahead of time.
+// Adds the adapter term (and, F16, the bias) to the eight adjacent outputs y[0..7] of row m, columns
+// col .. col + 7 (col a multiple of 8, col + 7 < N) and stores them as 16-bit floats.  `b0`: rows
+// 0 .. 7 of B for these columns, loaded by the caller ahead of time.
 template <bool F16>
-__device__ __forceinline__ void smallm_store4(const SmallFwdDev &d, const float *Us, int m, int col, const float y[4], const float4 b0[8]) {
-    float l[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int jj0 = 0; jj0 < d.r; jj0 += 8) {
-        float4 b[8];
+__device__ __forceinline__ void smallm_fwd_store8(const SmallFwdDev &d, const float *Us, int m, int col, const float y[8], const float4 b0[FIN_BROWS][2]) {
+    float l[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int jj0 = 0; jj0 < d.r; jj0 += FIN_BROWS) {
+        float4 b[FIN_BROWS][2];
         if (jj0 == 0) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) b[q] = b0[q];
+            for (int q = 0; q < FIN_BROWS; ++q) { b[q][0] = b0[q][0]; b[q][1] = b0[q][1]; }
         } else {
-            smallm_load_b8(d, jj0, col, b);
+            smallm_load_b8x8(d, jj0, col, b);
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < FIN_BROWS; ++q) {
             const float u = jj0 + q < d.r ? Us[m * d.r + jj0 + q] : 0.f;
-            l[0] = __builtin_fmaf(u, b[q].x, l[0]);
-            l[1] = __builtin_fmaf(u, b[q].y, l[1]);
-            l[2] = __builtin_fmaf(u, b[q].z, l[2]);
-            l[3] = __builtin_fmaf(u, b[q].w, l[3]);
+            l[0] = __builtin_fmaf(u, b[q][0].x, l[0]); l[1] = __builtin_fmaf(u, b[q][0].y, l[1]);
+            l[2] = __builtin_fmaf(u, b[q][0].z, l[2]); l[3] = __builtin_fmaf(u, b[q][0].w, l[3]);
+            l[4] = __builtin_fmaf(u, b[q][1].x, l[4]); l[5] = __builtin_fmaf(u, b[q][1].y, l[5]);
+            l[6] = __builtin_fmaf(u, b[q][1].z, l[6]); l[7] = __builtin_fmaf(u, b[q][1].w, l[7]);
         }
     }
-    float b[4] = {0.f, 0.f, 0.f, 0.f};
+    float bias[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (F16 && d.bias16 != nullptr) {          // the bias of Figure 1 / eq. (3): part of the frozen layer
-        const uint2 bw = *reinterpret_cast<const uint2 *>(d.bias16 + col);
-        b[0] = half_bits_to_float((uint16_t)(bw.x & 0xFFFFu)); b[1] = half_bits_to_float((uint16_t)(bw.x >> 16));
-        b[2] = half_bits_to_float((uint16_t)(bw.y & 0xFFFFu)); b[3] = half_bits_to_float((uint16_t)(bw.y >> 16));
+        const uint4 bw = *reinterpret_cast<const uint4 *>(d.bias16 + col);
+        const uint32_t w4[4] = {bw.x, bw.y, bw.z, bw.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bias[2 * q] = half_bits_to_float((uint16_t)(w4[q] & 0xFFFFu));
+            bias[2 * q + 1] = half_bits_to_float((uint16_t)(w4[q] >> 16));
+        }
     }
-    uint2 o;
-    o.x = sm::pack16<F16>(__builtin_fmaf(d.lora_scale, l[0], y[0] + b[0]), __builtin_fmaf(d.lora_scale, l[1], y[1] + b[1]));
-    o.y = sm::pack16<F16>(__builtin_fmaf(d.lora_scale, l[2], y[2] + b[2]), __builtin_fmaf(d.lora_scale, l[3], y[3] + b[3]));
-    *reinterpret_cast<uint2 *>(d.Y + (size_t)m * d.w.N + col) = o;
+    float o[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[c] = __builtin_fmaf(d.lora_scale, l[c], y[c] + bias[c]);
+    uint4 v;
+    v.x = sm::pack16<F16>(o[0], o[1]);
+    v.y = sm::pack16<F16>(o[2], o[3]);
+    v.z = sm::pack16<F16>(o[4], o[5]);
+    v.w = sm::pack16<F16>(o[6], o[7]);
+    *reinterpret_cast<uint4 *>(d.Y + (size_t)m * d.w.N + col) = v;
 }
 
 // SPG1: a quantization group is exactly one step (KSTEP codes), so every step starts its
@@ -734,43 +749,72 @@ __global__ __launch_bounds__(sm::FWD_THREADS, 4) void smallm_fwd_kernel(SmallFwd
     }
 }
 
-// Sum of the K slices' partial tiles, then the adapter term and the bfloat16 store.  One
-// workgroup per 64 columns: thread t owns row t / 16, columns 4 (t % 16) .. + 3.
+// Sum of the K slices' partial tiles, then the adapter term and the 16-bit store.  One single-wave
+// workgroup per 32 columns (whole-chip parallelism also for a narrow output): lane l owns row
+// l / 4, columns 8 (l % 4) .. + 7.  The kernel is a chain of memory round trips; everything that
+// does not depend on another load is issued first and consumed last: the first sixteen slices'
+// tiles, the first rows of B, and (inside smallm_sum_parts) the projection partials.
+constexpr int FIN_COLS = 32, FIN_SLICES = 16;
 template <bool F16>
-__global__ __launch_bounds__(sm::WG_THREADS) void smallm_fwd_finish_kernel(SmallFwdDev d) {
+__global__ __launch_bounds__(64) void smallm_fwd_finish_kernel(SmallFwdDev d) {
     __shared__ float Us[16 * 64];
     const int tid = threadIdx.x, N = d.w.N;
-    const int m = tid >> 4, col = blockIdx.x * 64 + 4 * (tid & 15);
-    float y[4] = {0.f, 0.f, 0.f, 0.f};
-    const bool mine = m < d.M && col < N;
-    // The kernel is a chain of memory round trips; everything that does not depend on another
-    // load is issued first and consumed last: the first eight slices' tiles, the first eight rows
-    // of B, and (inside smallm_sum_parts) the projection partials.
-    float4 v[8], b0[8];
+    const int m = tid >> 2, col = blockIdx.x * FIN_COLS + 8 * (tid & 3);
+    const bool mine = m < d.M && col < N;          // N is a multiple of 8: all eight columns or none
+    float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float4 b0[FIN_BROWS][2];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        b0[u] = v[u];
-        if (mine && u < d.ksplit) v[u] = *reinterpret_cast<const float4 *>(d.Yacc + ((size_t)u * 16 + m) * N + col);
-    }
-    if (mine) smallm_load_b8(d, 0, col, b0);
-    smallm_sum_parts<1>(d.Upart, d.n_proj, d.r, Us);
+    for (int q = 0; q < FIN_BROWS; ++q) { b0[q][0] = make_float4(0.f, 0.f, 0.f, 0.f); b0[q][1] = b0[q][0]; }
+    if (mine) smallm_load_b8x8(d, 0, col, b0);
+    // (lanes with nothing to do read row 0, columns 0 .. 7; slices past the last one re-read the last
+    // and are not added: no predicate per load)
+    const float *base = d.Yacc + (mine ? (size_t)m * N + col : (size_t)0);
+    // (the stride lives in a vector register: with scalar address arithmetic the sixteen slice
+    // addresses of a batch are all formed up front and overflow the scalar registers)
+    const uint32_t slice_stride = sm::opaque_vgpr((uint32_t)16 * (uint32_t)N);      // floats; < 2^32 bytes checked by the launcher
+    float4 v0[FIN_SLICES], v1[FIN_SLICES];
+    // A batch is four sets of four slices; a set is skipped as a whole (one scalar branch) when it
+    // lies past the last slice, and inside a set a slice past the end re-reads the last one and is
+    // added with weight 0 (weights 1 / 0 from a vector compare: a scalar condition per slice, all
+    // held at once, overflows the scalar registers).
+    auto load_slices = [&](int q0) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) { y[0] += v[u].x; y[1] += v[u].y; y[2] += v[u].z; y[3] += v[u].w; }
-    if (mine) {
-        for (int q0 = 8; q0 < d.ksplit; q0 += 8) {     // further slices, eight loads in flight at a time
+        for (int set = 0; set < FIN_SLICES / 4; ++set) {
+            if (q0 + 4 * set < d.ksplit) {
+                const float *src = base + (size_t)(q0 + 4 * set) * slice_stride;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (q0 + u < d.ksplit) v[u] = *reinterpret_cast<const float4 *>(d.Yacc + ((size_t)(q0 + u) * 16 + m) * N + col);
+                for (int u = 4 * set; u < 4 * set + 4; ++u) {
+                    v0[u] = *reinterpret_cast<const float4 *>(src);
+                    v1[u] = *reinterpret_cast<const float4 *>(src + 4);
+                    src += q0 + u + 1 < d.ksplit ? slice_stride : 0u;
+                }
             }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) { y[0] += v[u].x; y[1] += v[u].y; y[2] += v[u].z; y[3] += v[u].w; }
         }
-    }
+    };
+    auto add_slices = [&](int q0) {
+        const int left = (int)sm::opaque_vgpr((uint32_t)(d.ksplit - q0));
+#pragma unroll
+        for (int set = 0; set < FIN_SLICES / 4; ++set) {
+            if (q0 + 4 * set < d.ksplit) {
+#pragma unroll
+                for (int u = 4 * set; u < 4 * set + 4; ++u) {
+                    const float w = u < left ? 1.f : 0.f;
+                    y[0] = __builtin_fmaf(w, v0[u].x, y[0]); y[1] = __builtin_fmaf(w, v0[u].y, y[1]);
+                    y[2] = __builtin_fmaf(w, v0[u].z, y[2]); y[3] = __builtin_fmaf(w, v0[u].w, y[3]);
+                    y[4] = __builtin_fmaf(w, v1[u].x, y[4]); y[5] = __builtin_fmaf(w, v1[u].y, y[5]);
+                    y[6] = __builtin_fmaf(w, v1[u].z, y[6]); y[7] = __builtin_fmaf(w, v1[u].w, y[7]);
+                }
+            }
+        }
+    };
+    load_slices(0);
+    if (d.r <= 8) smallm_sum_parts<2>(d.Upart, d.n_proj, d.r, Us);     // 16 r elements over 64 lanes: no more loads than needed
+    else smallm_sum_parts<4>(d.Upart, d.n_proj, d.r, Us);
+    add_slices(0);
+    for (int q0 = FIN_SLICES; q0 < d.ksplit; q0 += FIN_SLICES) { load_slices(q0); add_slices(q0); }
     if (blockIdx.x == 0 && d.XA != nullptr)
-        for (int t = tid; t < d.M * d.r; t += sm::WG_THREADS) d.XA[t] = Us[t];
-    if (mine) smallm_store4<F16>(d, Us, m, col, y, b0);
+        for (int t = tid; t < d.M * d.r; t += 64) d.XA[t] = Us[t];
+    if (mine) smallm_fwd_store8<F16>(d, Us, m, col, y, b0);
 }
 
 // ---------------------------------------------------------------------------------
@@ -812,47 +856,55 @@ constexpr int NSTEP = 32;    // contraction elements per step (8 per lane group)
 constexpr int RED_BYTES = sm::WG_WAVES * 32 * 64 * 4;   // the waves' tiles meeting in LDS
 }
 
-// A[k0 + c][jj0 .. jj0 + 3] for the eight adjacent rows c, all loads issued together (columns past
+// A[k0 + c][jj0 .. jj0 + 7] for the eight adjacent rows c, all loads issued together (columns past
 // r come back as zeros): 16-byte loads when the rows are 16-byte aligned (r a multiple of 4).
-__device__ __forceinline__ void smallm_load_a8(const SmallBwdDev &d, int k0, int jj0, float4 a[8]) {
+__device__ __forceinline__ void smallm_load_a8(const SmallBwdDev &d, int k0, int jj0, float4 a[8][2]) {
     const int r = d.r;
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
         const float *src = d.A + (size_t)(k0 + c) * r + jj0;
-        a[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if ((r & 3) == 0) {
-            if (jj0 < r) a[c] = *reinterpret_cast<const float4 *>(src);
-        } else {
-            if (jj0 < r) a[c].x = src[0];
-            if (jj0 + 1 < r) a[c].y = src[1];
-            if (jj0 + 2 < r) a[c].z = src[2];
-            if (jj0 + 3 < r) a[c].w = src[3];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            a[c][h] = make_float4(0.f, 0.f, 0.f, 0.f);
+            const int j = jj0 + 4 * h;
+            if ((r & 3) == 0) {
+                if (j < r) a[c][h] = *reinterpret_cast<const float4 *>(src + 4 * h);
+            } else {
+                if (j < r) a[c][h].x = src[4 * h];
+                if (j + 1 < r) a[c][h].y = src[4 * h + 1];
+                if (j + 2 < r) a[c][h].z = src[4 * h + 2];
+                if (j + 3 < r) a[c][h].w = src[4 * h + 3];
+            }
         }
     }
 }
 
-// Adapter term and 16-bit store of 8 adjacent outputs dX[m][k0 .. k0+7].  `a0`: columns 0 .. 3 of
+// Adapter term and 16-bit store of 8 adjacent outputs dX[m][k0 .. k0+7].  `a0`: columns 0 .. 7 of
 // the eight rows of A, loaded by the caller ahead of time.
 template <bool F16>
-__device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const float *Ts, int m, int k0, const float y[8], const float4 a0[8]) {
+__device__ __forceinline__ void smallm_bwd_store8(const SmallBwdDev &d, const float *Ts, int m, int k0, const float y[8], const float4 a0[8][2]) {
     float l[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int jj0 = 0; jj0 < d.r; jj0 += 4) {
-        float4 a[8];
+    for (int jj0 = 0; jj0 < d.r; jj0 += 8) {
+        float4 a[8][2];
         if (jj0 == 0) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) a[c] = a0[c];
+            for (int c = 0; c < 8; ++c) { a[c][0] = a0[c][0]; a[c][1] = a0[c][1]; }
         } else {
             smallm_load_a8(d, k0, jj0, a);
         }
-        float t[4];
+        float t[8];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) t[q] = jj0 + q < d.r ? Ts[m * d.r + jj0 + q] : 0.f;
+        for (int q = 0; q < 8; ++q) t[q] = jj0 + q < d.r ? Ts[m * d.r + jj0 + q] : 0.f;
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-            l[c] = __builtin_fmaf(t[0], a[c].x, l[c]);
-            l[c] = __builtin_fmaf(t[1], a[c].y, l[c]);
-            l[c] = __builtin_fmaf(t[2], a[c].z, l[c]);
-            l[c] = __builtin_fmaf(t[3], a[c].w, l[c]);
+            l[c] = __builtin_fmaf(t[0], a[c][0].x, l[c]);
+            l[c] = __builtin_fmaf(t[1], a[c][0].y, l[c]);
+            l[c] = __builtin_fmaf(t[2], a[c][0].z, l[c]);
+            l[c] = __builtin_fmaf(t[3], a[c][0].w, l[c]);
+            l[c] = __builtin_fmaf(t[4], a[c][1].x, l[c]);
+            l[c] = __builtin_fmaf(t[5], a[c][1].y, l[c]);
+            l[c] = __builtin_fmaf(t[6], a[c][1].z, l[c]);
+            l[c] = __builtin_fmaf(t[7], a[c][1].w, l[c]);
         }
     }
     float o[8];
@@ -1187,46 +1239,59 @@ __global__ __launch_bounds__(sm::WG_THREADS, 2) void smallm_bwd_kernel(SmallBwdD
 // Sum of the N slices' partial tiles, adapter term, 16-bit store.  One single-wave workgroup per 32
 // columns (a few dozen 256-thread workgroups left most of the chip idle while each waited for its
 // chain of loads): lane l owns row l / 4, columns 8 (l % 4) .. + 7.
-constexpr int BWD_FIN_COLS = 32;
 template <bool F16>
 __global__ __launch_bounds__(64) void smallm_bwd_finish_kernel(SmallBwdDev d) {
     __shared__ float Ts[16 * 64];
     const int tid = threadIdx.x, K = d.w.K;
-    const int m = tid >> 2, k0 = blockIdx.x * BWD_FIN_COLS + 8 * (tid & 3);
+    const int m = tid >> 2, k0 = blockIdx.x * FIN_COLS + 8 * (tid & 3);
     float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     // the first columns of the eight rows of A are fetched ahead of everything that waits
-    float4 a0[8];
+    float4 a0[8][2];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) a0[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < 8; ++c) { a0[c][0] = make_float4(0.f, 0.f, 0.f, 0.f); a0[c][1] = a0[c][0]; }
     if (m < d.M && d.r > 0) smallm_load_a8(d, k0, 0, a0);
-    // eight slices' loads (two 16-byte loads each) in flight at a time; the first eight are issued
+    // sixteen slices' loads (two 16-byte loads each) in flight at a time; the first sixteen are issued
     // before the projection partials are summed and consumed after
-    constexpr int SB = 8;
+    constexpr int SB = FIN_SLICES;
     float4 v0[SB], v1[SB];
     // (slices past the last one re-read the last and are not added: one predicate for all the loads
     // of a batch instead of one per slice keeps the scalar registers within bounds)
     const float *mine = d.acc + (size_t)(m < d.M ? m : 0) * K + k0;
-    const size_t slice_stride = (size_t)16 * K;
+    const uint32_t slice_stride = sm::opaque_vgpr((uint32_t)16 * (uint32_t)K);      // floats, in a vector register (see the forward kernel)
+    // four sets of four slices, as in the forward finish kernel
     auto load_slices = [&](int q0) {
 #pragma unroll
-        for (int u = 0; u < SB; ++u) {
-            const int sl = q0 + u < d.nsplit ? q0 + u : d.nsplit - 1;
-            const float *src = mine + (size_t)sl * slice_stride;
-            v0[u] = *reinterpret_cast<const float4 *>(src);
-            v1[u] = *reinterpret_cast<const float4 *>(src + 4);
+        for (int set = 0; set < SB / 4; ++set) {
+            if (q0 + 4 * set < d.nsplit) {
+                const float *src = mine + (size_t)(q0 + 4 * set) * slice_stride;
+#pragma unroll
+                for (int u = 4 * set; u < 4 * set + 4; ++u) {
+                    v0[u] = *reinterpret_cast<const float4 *>(src);
+                    v1[u] = *reinterpret_cast<const float4 *>(src + 4);
+                    src += q0 + u + 1 < d.nsplit ? slice_stride : 0u;
+                }
+            }
         }
     };
     auto add_slices = [&](int q0) {
+        const int left = (int)sm::opaque_vgpr((uint32_t)(d.nsplit - q0));
 #pragma unroll
-        for (int u = 0; u < SB; ++u) {
-            if (q0 + u < d.nsplit) {
-                y[0] += v0[u].x; y[1] += v0[u].y; y[2] += v0[u].z; y[3] += v0[u].w;
-                y[4] += v1[u].x; y[5] += v1[u].y; y[6] += v1[u].z; y[7] += v1[u].w;
+        for (int set = 0; set < SB / 4; ++set) {
+            if (q0 + 4 * set < d.nsplit) {
+#pragma unroll
+                for (int u = 4 * set; u < 4 * set + 4; ++u) {
+                    const float w = u < left ? 1.f : 0.f;
+                    y[0] = __builtin_fmaf(w, v0[u].x, y[0]); y[1] = __builtin_fmaf(w, v0[u].y, y[1]);
+                    y[2] = __builtin_fmaf(w, v0[u].z, y[2]); y[3] = __builtin_fmaf(w, v0[u].w, y[3]);
+                    y[4] = __builtin_fmaf(w, v1[u].x, y[4]); y[5] = __builtin_fmaf(w, v1[u].y, y[5]);
+                    y[6] = __builtin_fmaf(w, v1[u].z, y[6]); y[7] = __builtin_fmaf(w, v1[u].w, y[7]);
+                }
             }
         }
     };
     load_slices(0);
-    smallm_sum_parts<2>(d.Tpart, d.n_proj, d.r, Ts);
+    if (d.r <= 8) smallm_sum_parts<2>(d.Tpart, d.n_proj, d.r, Ts);     // 16 r elements over 64 lanes: no more loads than needed
+    else smallm_sum_parts<4>(d.Tpart, d.n_proj, d.r, Ts);
     add_slices(0);
     for (int q0 = SB; q0 < d.nsplit; q0 += SB) { load_slices(q0); add_slices(q0); }
     if (blockIdx.x == 0 && d.T_out != nullptr)
@@ -1423,8 +1488,8 @@ hipError_t launch_smallm_fwd(const SmallArgs &a, hipStream_t stream) {
     e = a.f16 ? launch_fwd_any<true>(d, a.w.bits, spg1, col_blocks, lds_bytes, stream)
               : launch_fwd_any<false>(d, a.w.bits, spg1, col_blocks, lds_bytes, stream);
     if (e != hipSuccess) return e;
-    if (a.f16) launch_kernel("f16_stream_fwd_finish", smallm_fwd_finish_kernel<true>, (N + 63) / 64, sm::WG_THREADS, 0, stream, d);
-    else launch_kernel("stream_fwd_finish", smallm_fwd_finish_kernel<false>, (N + 63) / 64, sm::WG_THREADS, 0, stream, d);
+    if (a.f16) launch_kernel("f16_stream_fwd_finish", smallm_fwd_finish_kernel<true>, (N + FIN_COLS - 1) / FIN_COLS, 64, 0, stream, d);
+    else launch_kernel("stream_fwd_finish", smallm_fwd_finish_kernel<false>, (N + FIN_COLS - 1) / FIN_COLS, 64, 0, stream, d);
     return hipGetLastError();
 }
 
@@ -1482,8 +1547,8 @@ hipError_t launch_smallm_bwd(const SmallArgs &a, hipStream_t stream) {
     d.zeros16 = a.zeros16;
     e = a.f16 ? launch_bwd_any<true>(d, a.w.bits, k_blocks, stream) : launch_bwd_any<false>(d, a.w.bits, k_blocks, stream);
     if (e != hipSuccess) return e;
-    if (a.f16) launch_kernel("f16_stream_bwd_finish", smallm_bwd_finish_kernel<true>, K / BWD_FIN_COLS, 64, 0, stream, d);
-    else launch_kernel("stream_bwd_finish", smallm_bwd_finish_kernel<false>, K / BWD_FIN_COLS, 64, 0, stream, d);
+    if (a.f16) launch_kernel("f16_stream_bwd_finish", smallm_bwd_finish_kernel<true>, K / FIN_COLS, 64, 0, stream, d);
+    else launch_kernel("stream_bwd_finish", smallm_bwd_finish_kernel<false>, K / FIN_COLS, 64, 0, stream, d);
     return hipGetLastError();
 }
 
