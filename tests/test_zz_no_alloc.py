@@ -47,6 +47,8 @@ _both.first = True      # the first call on the GPU loads the array's address (a
     # M <= 16 streaming kernels: slices of K meet in the scratch
     ((3, 2048, 2176, 16, 8, 128), (3, 1024, 768, 5, 8, 128)),
     ((4, 1152, 520, 13, 40, 128), (2, 768, 296, 5, 0, 64)),
+    # two passes of the streaming kernels (24 tokens over 6 MB of codes), then one pass
+    ((3, 4096, 4096, 24, 8, 128), (3, 4096, 4096, 9, 8, 128)),
     # 128 x 64 producer / consumer kernel, then a few dozen tokens: adapter operands in the scratch
     ((3, 2112, 2136, 300, 8, 64), (4, 512, 520, 32, 8, 64)),
     # 256 x 256 kernel with a split contraction whose partial tiles (4 MB) fit the scratch, then a
