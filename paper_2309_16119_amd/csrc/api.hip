@@ -407,7 +407,7 @@ F16Ws f16_ws(int32_t K, int32_t N, int32_t M, int32_t r) {
         l.p1 = off;    off += align256((size_t)M * r * 4);
         l.gpart = off; off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
     }
-    l.gemm_part = off; off += align256(mlr::gemm_partial_bytes(M, K, N, true));   // partial tiles of the 256 x 256 kernel
+    l.gemm_part = off; off += align256(mlr::gemm_partial_bytes(M, K, N));   // partial tiles of the 256 x 256 kernel
     l.total = off;
     // the streaming kernels for a handful of tokens lay out their own scratch from the start of the workspace
     if (M <= mlr::SMALLM_MAX_M) {

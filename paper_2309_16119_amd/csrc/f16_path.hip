@@ -511,10 +511,13 @@ hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act
         const int Cout = backward ? w.K : w.N;
         const long tiles = (long)((M + 127) / 128) * ((Cout + 63) / 64);
         const long tiles256 = (long)((M + 255) / 256) * ((Cout + 255) / 256);
-        const bool use_mid = tiles >= 128 && tiles <= 320;
+        // a hundred-odd tokens (the last block of 256 rows at most half full) against a large weight: the
+        // 256-column kernel with 128-row tiles, as on the bfloat16 path (27 + 7 against 49 us at 128 x 8192 x 8192)
+        const bool half_rows = big_plan(M, backward ? w.N : w.K, Cout).mt == 128 && (long)w.K * w.N >= 4096L * 4096L;
+        const bool use_mid = !half_rows && tiles >= 128 && tiles <= 320;
         // a few dozen 256 x 256 tiles or more: that kernel (the tiles of a partial last round are cut
         // into slices of the contraction, as on the bfloat16 path)
-        const bool use_big = !use_mid && tiles256 >= 24;
+        const bool use_big = half_rows || (!use_mid && tiles256 >= 24);
         // MODULORA_F16_PLAIN (read once per process) keeps every shape on the plain kernel, for comparisons
         static const bool force_plain = std::getenv("MODULORA_F16_PLAIN") != nullptr;
         if (M > 32 && (use_mid || use_big) && !force_plain) {
@@ -525,7 +528,7 @@ hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act
             g.zeros16 = w.zeros; g.bias16 = w.bias;
             g.ep_P = r > 0 ? P : nullptr; g.ep_F = Fm; g.ep_r = r; g.ep_scale = lora_scale;
             g.partials = partials;
-            g.partials_bytes = partials ? gemm_partial_bytes(M, w.K, w.N, true) : 0;
+            g.partials_bytes = partials ? gemm_partial_bytes(M, w.K, w.N) : 0;
             return use_mid ? launch_gemm_mid_f16(g, stream) : launch_gemm_big_f16(g, stream);
         }
     }

@@ -1,7 +1,8 @@
 // The large-M variant of the fused dequantize + bf16 MFMA tile kernel: a 256 x 256
 // output tile per workgroup, 8 waves (two per SIMD) of 128 x 64 each, 64-deep steps.
 // (A second instantiation with 128-row tiles, waves of 64 x 64, serves token counts whose last
-// block of 256 rows would be at most half full -- a hundred-odd tokens above all.)
+// block of 256 rows would be at most half full -- a hundred-odd tokens above all; both exist for
+// either storage convention.)
 // Same mathematics as gemm_tile.hip (ModuLoRA Figure 1: forward X What^T and backward
 // dY What with What re-materialized from the packed codes, plus the adapter term of eq. (3)
 // as an extended contraction); what differs is the data path, chosen from what was measured
@@ -657,9 +658,8 @@ static hipError_t launch_big_mt(const GemmArgs &a, BigPlan plan, hipStream_t str
 template <int BITS, bool BWD, bool F16 = false>
 static hipError_t launch_big(const GemmArgs &a, hipStream_t stream) {
     const int C = BWD ? a.w.N : a.w.K, Cout = BWD ? a.w.K : a.w.N;
-    if (F16) return launch_big_mt<BITS, BWD, F16, 256>(a, big_plan_rows(a.M, C, Cout, 256), stream);
     const BigPlan plan = big_plan(a.M, C, Cout);
-    if (!F16 && plan.mt == 128) return launch_big_mt<BITS, BWD, false, 128>(a, plan, stream);
+    if (plan.mt == 128) return launch_big_mt<BITS, BWD, F16, 128>(a, plan, stream);
     return launch_big_mt<BITS, BWD, F16, 256>(a, plan, stream);
 }
 

@@ -107,10 +107,9 @@ inline BigPlan big_plan(int M, int C, int Cout) {
     const bool half_rows = (n128 & 1) != 0 && n128 <= 5;
     return big_plan_rows(M, C, Cout, half_rows ? 128 : 256);
 }
-// Scratch for the partial tiles of either direction.  The binary16 path always takes 256-row tiles.
-inline size_t gemm_partial_bytes(int M, int K, int N, bool f16 = false) {
-    const size_t f = (f16 ? big_plan_rows(M, K, N, 256) : big_plan(M, K, N)).partial_bytes();
-    const size_t b = (f16 ? big_plan_rows(M, N, K, 256) : big_plan(M, N, K)).partial_bytes();
+// Scratch for the partial tiles of either direction.
+inline size_t gemm_partial_bytes(int M, int K, int N) {
+    const size_t f = big_plan(M, K, N).partial_bytes(), b = big_plan(M, N, K).partial_bytes();
     return f > b ? f : b;
 }
 

@@ -67,6 +67,11 @@ SHAPES = [
     # slices of the contraction, whose partial tiles a second launch adds (ragged M and N)
     (3, 2816, 2456, 1100, 8, 128, True),
     (4, 2816, 2456, 1100, 0, 64, False),
+    # a hundred-odd tokens (or that many past a multiple of 256) against a weight of 4096 x 4096 or more:
+    # the 256-column kernel with 128-row tiles, split contraction and second launch (ragged M, N, last step)
+    (3, 4096, 4104, 100, 8, 128, True),
+    (4, 4128, 4096, 128, 16, 32, False),
+    (2, 4096, 4224, 300, 40, 64, True),
     # contractions shorter than one 64-deep step of the plain tile kernel (d_in = 32 forward, d_out = 48
     # backward) and outputs narrower than its tile: every load of the absent part stays inside its matrix
     (2, 32, 1664, 16, 0, 32, False),
