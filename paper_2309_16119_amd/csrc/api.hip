@@ -397,7 +397,7 @@ mlr::F16Layer view_of(const modulora_qweight_f16 *w) {
     return mlr::F16Layer{w->d_in, w->d_out, w->bits, w->group_size, w->qweight, w->scales, w->zeros, w->bias};
 }
 struct F16Ws {
-    size_t p0, p1, gpart, gemm_part, total;
+    size_t p0, p1, gpart, dpart, gemm_part, total;
 };
 F16Ws f16_ws(int32_t K, int32_t N, int32_t M, int32_t r) {
     F16Ws l{};
@@ -406,6 +406,7 @@ F16Ws f16_ws(int32_t K, int32_t N, int32_t M, int32_t r) {
         l.p0 = off;    off += align256((size_t)M * r * 4);
         l.p1 = off;    off += align256((size_t)M * r * 4);
         l.gpart = off; off += align256(mlr::grad_geom(M, K, N, r).partial_floats * 4);
+        l.dpart = off; off += align256(mlr::lora_down_partial_bytes(M, K, N, r));   // slices of the rank-r projection
     }
     l.gemm_part = off; off += align256(mlr::gemm_partial_bytes(M, K, N));   // partial tiles of the 256 x 256 kernel
     l.total = off;
@@ -416,6 +417,20 @@ F16Ws f16_ws(int32_t K, int32_t N, int32_t M, int32_t r) {
     }
     return l;
 }
+// P = act F for binary16 activations (X A or dY B^T; fp32-exact products on the matrix cores): the
+// projection kernel of the bfloat16 path with each activation split into two bfloat16 operands.  No
+// extended-contraction operands here: this path adds the adapter term in the product kernel's epilogue.
+int f16_project(const uint16_t *act, int32_t M, int32_t C, const float *F, bool f_is_A, int32_t r, float *P, char *ws,
+                const F16Ws &l, hipStream_t st) {
+    mlr::DownArgs d{};
+    d.act = act; d.act_f16 = true; d.M = M; d.C = C; d.r = r;
+    d.Fm = F; d.f_is_A = f_is_A;
+    d.P = P; d.lora_scale = 1.0f;
+    d.act_ext = nullptr; d.RE = 0; d.w_ext = nullptr; d.Wsrc = nullptr; d.w_from_A = false; d.Cw = 0;
+    d.partials = reinterpret_cast<float *>(ws + l.dpart);
+    return hip_status(mlr::launch_lora_down(d, st));
+}
+
 // the codes and scales of the layer as the streaming kernels take them (zero points travel separately)
 mlr::LayerView stream_view_of(const modulora_qweight_f16 *w) {
     mlr::LayerView v;
@@ -469,7 +484,7 @@ int modulora_f16_fwd(const modulora_qweight_f16 *w, const uint16_t *X, int32_t M
     float *P = nullptr;
     if (r > 0) {
         P = XA ? XA : reinterpret_cast<float *>(static_cast<char *>(workspace) + l.p0);
-        if ((s = hip_status(mlr::launch_f16_proj(X, M, w->d_in, A, true, r, P, st))) != MODULORA_OK) return s;
+        if ((s = f16_project(X, M, w->d_in, A, true, r, P, static_cast<char *>(workspace), l, st)) != MODULORA_OK) return s;
     }
     float *parts = l.total > 0 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + l.gemm_part) : nullptr;
     return hip_status(mlr::launch_f16_gemm(view_of(w), false, X, M, Y, P, B, r, lora_scale, parts, st));
@@ -499,7 +514,7 @@ int modulora_f16_bwd_input(const modulora_qweight_f16 *w, const uint16_t *dY, in
     float *P = nullptr;
     if (r > 0) {
         P = dYBt ? dYBt : reinterpret_cast<float *>(static_cast<char *>(workspace) + l.p0);
-        if ((s = hip_status(mlr::launch_f16_proj(dY, M, w->d_out, B, false, r, P, st))) != MODULORA_OK) return s;
+        if ((s = f16_project(dY, M, w->d_out, B, false, r, P, static_cast<char *>(workspace), l, st)) != MODULORA_OK) return s;
     }
     float *parts = l.total > 0 ? reinterpret_cast<float *>(static_cast<char *>(workspace) + l.gemm_part) : nullptr;
     return hip_status(mlr::launch_f16_gemm(view_of(w), true, dY, M, dX, P, A, r, lora_scale, parts, st));
@@ -524,12 +539,12 @@ int modulora_f16_bwd_lora(int32_t d_in, int32_t d_out, int32_t M, int32_t r, flo
     char *ws = static_cast<char *>(workspace);
     if (!XA) {
         float *P = reinterpret_cast<float *>(ws + l.p0);
-        if ((s = hip_status(mlr::launch_f16_proj(X, M, d_in, A, true, r, P, st))) != MODULORA_OK) return s;
+        if ((s = f16_project(X, M, d_in, A, true, r, P, ws, l, st)) != MODULORA_OK) return s;
         XA = P;
     }
     if (!dYBt) {
         float *P = reinterpret_cast<float *>(ws + l.p1);
-        if ((s = hip_status(mlr::launch_f16_proj(dY, M, d_out, B, false, r, P, st))) != MODULORA_OK) return s;
+        if ((s = f16_project(dY, M, d_out, B, false, r, P, ws, l, st)) != MODULORA_OK) return s;
         dYBt = P;
     }
     mlr::GradPairArgs ga{};

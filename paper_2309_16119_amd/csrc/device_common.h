@@ -151,5 +151,18 @@ __device__ __forceinline__ void split3(const float x[8], uint32_t hi[4], uint32_
     }
 }
 
+// Exact two-way split of eight binary16 values (four registers of pairs) into bfloat16 pairs: the
+// upper 8 significand bits and the remaining (at most 3), so two bf16 MFMAs against them reproduce
+// the products with the binary16 values.  Truncation, not rounding: both parts are exact.
+__device__ __forceinline__ void split_f16x8(const uint32_t h[4], uint32_t hi[4], uint32_t lo[4]) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const float x0 = half_bits_to_float((uint16_t)(h[p] & 0xFFFFu)), x1 = half_bits_to_float((uint16_t)(h[p] >> 16));
+        const uint32_t t0 = __float_as_uint(x0) & 0xFFFF0000u, t1 = __float_as_uint(x1) & 0xFFFF0000u;
+        hi[p] = (t0 >> 16) | t1;
+        const float r0 = x0 - __uint_as_float(t0), r1 = x1 - __uint_as_float(t1);
+        lo[p] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xFFFF0000u);
+    }
+}
 
 }  // namespace mlr

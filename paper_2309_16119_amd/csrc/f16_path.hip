@@ -11,9 +11,10 @@
 //
 // This path has its own, plainer kernels (one tile shape, adapter term in the epilogue):
 //   f16_dequant_kernel   test-only materialization of What
-//   f16_proj_kernel      P = act F            (X A or dY B^T), fp32
 //   f16_gemm_kernel      the two products with What, adapter term and bias in the epilogue
-// The adapter gradients reuse lora_grad_partial_kernel with a binary16 element conversion.
+// The projections P = act F (X A or dY B^T) reuse lora_down_kernel, each binary16 activation split
+// exactly into two bfloat16 operands; the adapter gradients reuse lora_grad_partial_kernel with a
+// binary16 element conversion.
 #include "device_common.h"
 #include "gemm_common.h"
 #include <cstdlib>
@@ -107,119 +108,6 @@ hipError_t launch_f16_dequant(const F16Layer &w, uint16_t *What, hipStream_t str
         case 2: launch_kernel("f16_dequant", f16_dequant_kernel<2>, grid, 256, 0, stream, w, What); break;
         case 3: launch_kernel("f16_dequant", f16_dequant_kernel<3>, grid, 256, 0, stream, w, What); break;
         default: launch_kernel("f16_dequant", f16_dequant_kernel<4>, grid, 256, 0, stream, w, What); break;
-    }
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------
-// P[m][j] = sum_c act[m][c] F(c, j):  F = A [C][r] (F_IS_A) or B^T with B [r][C].
-// A workgroup owns RB rows (16 with many rows, so that the factor is re-read from the L2 by few
-// workgroups; 4 or 2 with few rows, for enough workgroups); every thread walks the contraction in chunks of 8 elements
-// (16-byte activation loads), keeps 4 x 8 fp32 sums per pass of 8 rank columns, and the 256
-// threads' sums meet through wave shuffles and LDS.
-// ---------------------------------------------------------------------------------
-template <bool F_IS_A, int RB>
-__global__ __launch_bounds__(256) void f16_proj_kernel(const uint16_t *act, int M, int C, const float *F, int r, float *P) {
-    constexpr int RJ = 8;
-    __shared__ float red[4][RB * RJ];
-    static_assert(RB == 2 || RB % 4 == 0, "rows go in batches of four");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m0 = blockIdx.x * RB;
-    const uint16_t *rows[RB];
-#pragma unroll
-    for (int i = 0; i < RB; ++i) rows[i] = act + (size_t)(m0 + i < M ? m0 + i : M - 1) * C;
-    for (int j0 = 0; j0 < r; j0 += RJ) {
-        float acc[RB][RJ];
-#pragma unroll
-        for (int i = 0; i < RB; ++i)
-#pragma unroll
-            for (int j = 0; j < RJ; ++j) acc[i][j] = 0.f;
-        for (int c = tid * 8; c < C; c += 256 * 8) {       // C is a multiple of 8
-            // the factor values of this chunk, f[e][j] = F(c + e, j0 + j), shared by all rows
-            float f[8][RJ];
-            if (F_IS_A) {
-                // A[c + e][j0 .. j0 + 7]: 32 contiguous bytes per contraction element when they are all there
-                const bool vec = (r & 3) == 0 && j0 + RJ <= r;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float *src = F + (size_t)(c + e) * r + j0;
-                    if (vec) {
-                        const float4 q0 = *reinterpret_cast<const float4 *>(src), q1 = *reinterpret_cast<const float4 *>(src + 4);
-                        f[e][0] = q0.x; f[e][1] = q0.y; f[e][2] = q0.z; f[e][3] = q0.w;
-                        f[e][4] = q1.x; f[e][5] = q1.y; f[e][6] = q1.z; f[e][7] = q1.w;
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < RJ; ++j) f[e][j] = j0 + j < r ? src[j] : 0.f;
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < RJ; ++j) {
-                    float4 q0 = make_float4(0.f, 0.f, 0.f, 0.f), q1 = q0;
-                    if (j0 + j < r) {
-                        q0 = *reinterpret_cast<const float4 *>(F + (size_t)(j0 + j) * C + c);
-                        q1 = *reinterpret_cast<const float4 *>(F + (size_t)(j0 + j) * C + c + 4);
-                    }
-                    f[0][j] = q0.x; f[1][j] = q0.y; f[2][j] = q0.z; f[3][j] = q0.w;
-                    f[4][j] = q1.x; f[5][j] = q1.y; f[6][j] = q1.z; f[7][j] = q1.w;
-                }
-            }
-#pragma unroll
-            for (int ib = 0; ib < RB; ib += 4) {           // four rows at a time
-                float x[4][8];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (ib + i >= RB) break;
-                    const uint4 v = *reinterpret_cast<const uint4 *>(rows[ib + i] + c);
-                    const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        x[i][2 * e] = half_bits_to_float((uint16_t)(wv[e] & 0xFFFFu));
-                        x[i][2 * e + 1] = half_bits_to_float((uint16_t)(wv[e] >> 16));
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (ib + i >= RB) break;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-#pragma unroll
-                        for (int j = 0; j < RJ; ++j) acc[ib + i][j] = __builtin_fmaf(x[i][e], f[e][j], acc[ib + i][j]);
-                }
-            }
-        }
-        // wave sums, then the four waves through LDS
-#pragma unroll
-        for (int i = 0; i < RB; ++i)
-#pragma unroll
-            for (int j = 0; j < RJ; ++j) {
-                float v = acc[i][j];
-#pragma unroll
-                for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-                if (lane == 0) red[wave][i * RJ + j] = v;
-            }
-        __syncthreads();
-        if (tid < RB * RJ) {
-            const int i = tid / RJ, j = tid % RJ;
-            if (m0 + i < M && j0 + j < r) P[(size_t)(m0 + i) * r + j0 + j] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
-        }
-        __syncthreads();
-    }
-}
-
-hipError_t launch_f16_proj(const uint16_t *act, int M, int C, const float *F, bool f_is_A, int r, float *P, hipStream_t stream) {
-    if (M <= 1024) {
-        const int blocks = (M + 1) / 2;
-        if (f_is_A) launch_kernel("f16_proj", f16_proj_kernel<true, 2>, blocks, 256, 0, stream, act, M, C, F, r, P);
-        else launch_kernel("f16_proj", f16_proj_kernel<false, 2>, blocks, 256, 0, stream, act, M, C, F, r, P);
-    } else if (M < 4096) {
-        const int blocks = (M + 3) / 4;
-        if (f_is_A) launch_kernel("f16_proj", f16_proj_kernel<true, 4>, blocks, 256, 0, stream, act, M, C, F, r, P);
-        else launch_kernel("f16_proj", f16_proj_kernel<false, 4>, blocks, 256, 0, stream, act, M, C, F, r, P);
-    } else {
-        const int blocks = (M + 15) / 16;
-        if (f_is_A) launch_kernel("f16_proj", f16_proj_kernel<true, 16>, blocks, 256, 0, stream, act, M, C, F, r, P);
-        else launch_kernel("f16_proj", f16_proj_kernel<false, 16>, blocks, 256, 0, stream, act, M, C, F, r, P);
     }
     return hipGetLastError();
 }

@@ -122,7 +122,8 @@ inline size_t gemm_partial_bytes(int M, int K, int N) {
 //   w_from_A: w_ext[c][.] from Wsrc[c * r + j] (A, for the backward pass)
 //   else    : w_ext[c][.] from Wsrc[j * Cw + c] (B, for the forward pass)
 struct DownArgs {
-    const uint16_t *act;  // bf16 [M][C]
+    const uint16_t *act;  // bf16 [M][C] (binary16 when act_f16)
+    bool act_f16;         // the layer in the paper's own storage convention: binary16 activations, P only
     int M, C, r;
     const float *Fm;
     bool f_is_A;
@@ -226,7 +227,6 @@ struct F16Layer {
 };
 hipError_t launch_f16_dequant(const F16Layer &w, uint16_t *What, hipStream_t stream);
 // P[M][r] = act[M][C] F, F = A [C][r] (f_is_A) or B^T with B [r][C]
-hipError_t launch_f16_proj(const uint16_t *act, int M, int C, const float *F, bool f_is_A, int r, float *P, hipStream_t stream);
 // forward: out[M][N] = act What^T + bias + s P B; backward: out[M][K] = act What + s P A^T
 // partials: scratch of gemm_partial_bytes(M, K, N) bytes for the 256 x 256 kernel's split contraction, or NULL
 hipError_t launch_f16_gemm(const F16Layer &w, bool backward, const uint16_t *act, int M, uint16_t *out, const float *P,

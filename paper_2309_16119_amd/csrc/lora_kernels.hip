@@ -65,7 +65,8 @@ __device__ __forceinline__ void write_w_ext_unit(const DownArgs &a, size_t u) {
 
 // ROWT: 16-row tiles per workgroup (they share every factor operand); UNR: steps whose loads
 // are issued together before any of them is used.
-template <int RG, int ROWT, bool F_IS_A>
+// ACT_F16: the activations are binary16; each operand is split exactly into two bfloat16 ones.
+template <int RG, int ROWT, bool F_IS_A, bool ACT_F16>
 __global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blocks, int split) {
     extern __shared__ __attribute__((aligned(16))) float lds_f[];   // [waves][ROWT][RG][256] partial tiles, then Ps
     constexpr int UNR = ROWT > 1 ? 2 : (RG == 1 ? 4 : (RG == 2 ? 2 : 1));
@@ -143,10 +144,22 @@ __global__ __launch_bounds__(1024) void lora_down_kernel(DownArgs a, int row_blo
 #pragma unroll
                 for (int t = 0; t < ROWT; ++t) {
                     const uint32_t ar[4] = {av[q][t].x, av[q][t].y, av[q][t].z, av[q][t].w};
-                    const bf16x8 aop = regs_to_bf16x8(ar);
-                    acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bh, acc[t][g], 0, 0, 0);
-                    acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bm, acc[t][g], 0, 0, 0);
-                    acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bl, acc[t][g], 0, 0, 0);
+                    if (ACT_F16) {
+                        uint32_t ah[4], al[4];
+                        split_f16x8(ar, ah, al);
+                        const bf16x8 aop = regs_to_bf16x8(ah), aop2 = regs_to_bf16x8(al);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bh, acc[t][g], 0, 0, 0);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bm, acc[t][g], 0, 0, 0);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bl, acc[t][g], 0, 0, 0);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop2, bh, acc[t][g], 0, 0, 0);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop2, bm, acc[t][g], 0, 0, 0);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop2, bl, acc[t][g], 0, 0, 0);
+                    } else {
+                        const bf16x8 aop = regs_to_bf16x8(ar);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bh, acc[t][g], 0, 0, 0);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bm, acc[t][g], 0, 0, 0);
+                        acc[t][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bl, acc[t][g], 0, 0, 0);
+                    }
                 }
             }
     }
@@ -232,10 +245,16 @@ static hipError_t launch_down_rg(const DownArgs &a, const DownPlan &plan, hipStr
     const int w_blocks = a.w_ext ? (int)(((size_t)a.Cw * (a.RE / 8) + nthreads - 1) / nthreads) : 0;
     const size_t lds = (size_t)(nwaves * RG * ROWT * 256 + ROWS * 16 * RG) * sizeof(float);
     const dim3 grid(row_blocks + w_blocks, split);
-    if (a.f_is_A)
-        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, true>, grid, nthreads, lds, stream, a, row_blocks, split);
-    else
-        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, false>, grid, nthreads, lds, stream, a, row_blocks, split);
+    if (a.act_f16) {
+        if (a.f_is_A)
+            launch_kernel("lora_down", lora_down_kernel<RG, ROWT, true, true>, grid, nthreads, lds, stream, a, row_blocks, split);
+        else
+            launch_kernel("lora_down", lora_down_kernel<RG, ROWT, false, true>, grid, nthreads, lds, stream, a, row_blocks, split);
+    } else if (a.f_is_A) {
+        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, true, false>, grid, nthreads, lds, stream, a, row_blocks, split);
+    } else {
+        launch_kernel("lora_down", lora_down_kernel<RG, ROWT, false, false>, grid, nthreads, lds, stream, a, row_blocks, split);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || split <= 1) return e;
     launch_kernel("lora_down_finish", lora_down_finish_kernel<RG>, (a.M + 15) / 16, 256, 0, stream, a, row_blocks, split, ROWT);
