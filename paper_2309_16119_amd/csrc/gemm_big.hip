@@ -121,40 +121,14 @@ __device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int 
         const int r = a.ep_r, N = a.w.N;
         const bool bwd = a.backward;
         float *Ps = reinterpret_cast<float *>(smem + 40960) + slot * (32 * 64);   // [jj][32 rows]
-        if (r > 0) {
-            for (int x = lane; x < 32 * r; x += 64) {
-                const int prow = x & 31, jj = x >> 5;
-                int m = m0 + wm * WM + i * 32 + prow;
-                if (m > M - 1) m = M - 1;
-                Ps[x] = a.ep_P[(size_t)m * r + jj];
-            }
-            __builtin_amdgcn_s_waitcnt(0xc07f);
-            __builtin_amdgcn_wave_barrier();
-        }
         int cc[TJ];
         float lora[TJ][16];
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
             const int col = c0 + wn * WN + j * 32 + (lane & 31);
             cc[j] = col < Cout ? col : Cout - 1;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) lora[j][v] = 0.f;
         }
-        for (int jj = 0; jj < r; ++jj) {
-            float f[TJ];
-#pragma unroll
-            for (int j = 0; j < TJ; ++j) f[j] = bwd ? a.ep_F[(size_t)cc[j] * r + jj] : a.ep_F[(size_t)jj * N + cc[j]];
-            // accumulator register v belongs to row 8 (v / 4) + 4 (lane / 32) + v % 4: four float4
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 p = *reinterpret_cast<const float4 *>(Ps + jj * 32 + 8 * q + 4 * (lane >> 5));
-                const float pv[4] = {p.x, p.y, p.z, p.w};
-#pragma unroll
-                for (int z = 0; z < 4; ++z)
-#pragma unroll
-                    for (int j = 0; j < TJ; ++j) lora[j][4 * q + z] = __builtin_fmaf(pv[z], f[j], lora[j][4 * q + z]);
-            }
-        }
+        adapter_term_32rows<TJ>(a.ep_P, a.ep_F, r, N, bwd, m0 + wm * WM + i * 32, M, cc, Ps, lane, lora);
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
             float bias = 0.f;
@@ -162,8 +136,6 @@ __device__ __forceinline__ void big_epilogue_rows(f32x16 (&acc_i)[big::TJ], int 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc_i[j][v] = __builtin_fmaf(a.ep_scale, lora[j][v], acc_i[j][v] + bias);
         }
-        __builtin_amdgcn_s_waitcnt(0xc07f);   // the next block of rows overwrites Ps
-        __builtin_amdgcn_wave_barrier();
     }
     uint16_t *patch = reinterpret_cast<uint16_t *>(smem) + slot * (32 * PATCH_ROW);
 #pragma unroll

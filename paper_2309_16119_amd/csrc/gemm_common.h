@@ -156,4 +156,64 @@ hipError_t launch_gemm_big(const GemmArgs &a, hipStream_t stream);
 // gemm_mid.hip: 128x64 tiles for grids of about one tile per CU, producer and consumer waves
 hipError_t launch_gemm_mid(const GemmArgs &a, hipStream_t stream);
 
+// The adapter term of a wave's block of 32 rows x (TJ x 32) columns in the epilogue (the layer in
+// the paper's own storage convention adds s P F there, before the one rounding):
+//   lora[j][v] = sum_jj P[row(v)][jj] F(jj, cc[j]),   row(v) = 8 (v / 4) + 4 (lane / 32) + v % 4,
+// P fp32 [M][r] (rows first_row .. first_row + 31, clamped to M - 1), F = B [r][N] (forward) or A [K][r]
+// (backward: F(jj, c) = A[c][jj]).  The block's rows of P pass through LDS (Ps: 32 x 64 floats,
+// private to the wave), [jj][32 rows].  Loads go out eight at a time before anything waits for
+// them: one round trip per eight rank columns instead of one per column.
+template <int TJ>
+__device__ __forceinline__ void adapter_term_32rows(const float *P, const float *F, int r, int N, bool bwd, int first_row, int M,
+                                                    const int (&cc)[TJ], float *Ps, int lane, float (&lora)[TJ][16]) {
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) lora[j][v] = 0.f;
+    if (r <= 0) return;
+    for (int x0 = lane; x0 < 32 * r; x0 += 8 * 64) {
+        float pv[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int x = x0 + 64 * t;
+            const int prow = x & 31, jj = x >> 5;
+            int m = first_row + prow;
+            if (m > M - 1) m = M - 1;
+            pv[t] = x < 32 * r ? P[(size_t)m * r + jj] : 0.f;
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            if (x0 + 64 * t < 32 * r) Ps[x0 + 64 * t] = pv[t];
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+    for (int jj0 = 0; jj0 < r; jj0 += 8) {
+        float f[8][TJ];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+            for (int j = 0; j < TJ; ++j) {
+                const int jj = jj0 + q;
+                f[q][j] = jj < r ? (bwd ? F[(size_t)cc[j] * r + jj] : F[(size_t)jj * N + cc[j]]) : 0.f;
+            }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            if (jj0 + q < r) {
+                // accumulator register v belongs to row 8 (v / 4) + 4 (lane / 32) + v % 4: four float4
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const float4 p = *reinterpret_cast<const float4 *>(Ps + (jj0 + q) * 32 + 8 * qq + 4 * (lane >> 5));
+                    const float p4[4] = {p.x, p.y, p.z, p.w};
+#pragma unroll
+                    for (int z = 0; z < 4; ++z)
+#pragma unroll
+                        for (int j = 0; j < TJ; ++j) lora[j][4 * qq + z] = __builtin_fmaf(p4[z], f[q][j], lora[j][4 * qq + z]);
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // the next block of rows overwrites Ps
+    __builtin_amdgcn_wave_barrier();
+}
+
 }  // namespace mlr

@@ -510,40 +510,14 @@ __global__ __launch_bounds__(mid::THREADS, 3) void gemm_mid_kernel(GemmDev d) {
     if (F16) {
         const int r = a.ep_r;
         float *Ps = reinterpret_cast<float *>(smem + 32768) + wave * (32 * 64);   // this wave's 32 rows of P, [jj][32 rows]
-        if (r > 0) {
-            for (int x = lane; x < 32 * r; x += 64) {
-                const int prow = x & 31, jj = x >> 5;
-                int m = m0 + wm * 64 + kg * 32 + prow;
-                if (m > a.M - 1) m = a.M - 1;
-                Ps[x] = a.ep_P[(size_t)m * r + jj];
-            }
-            __builtin_amdgcn_s_waitcnt(0xc07f);
-            __builtin_amdgcn_wave_barrier();
-        }
         int cc[TJ];
         float lora[TJ][16];
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
             const int col = c0 + j * 32 + (lane & 31);
             cc[j] = col < Cout ? col : Cout - 1;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) lora[j][v] = 0.f;
         }
-        for (int jj = 0; jj < r; ++jj) {
-            float f[TJ];
-#pragma unroll
-            for (int j = 0; j < TJ; ++j) f[j] = BWD ? a.ep_F[(size_t)cc[j] * r + jj] : a.ep_F[(size_t)jj * N + cc[j]];
-            // accumulator register v belongs to row 8 (v / 4) + 4 (lane / 32) + v % 4: four float4
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 p = *reinterpret_cast<const float4 *>(Ps + jj * 32 + 8 * q + 4 * (lane >> 5));
-                const float pv[4] = {p.x, p.y, p.z, p.w};
-#pragma unroll
-                for (int z = 0; z < 4; ++z)
-#pragma unroll
-                    for (int j = 0; j < TJ; ++j) lora[j][4 * q + z] = __builtin_fmaf(pv[z], f[j], lora[j][4 * q + z]);
-            }
-        }
+        adapter_term_32rows<TJ>(a.ep_P, a.ep_F, r, N, BWD, m0 + wm * 64 + kg * 32, a.M, cc, Ps, lane, lora);
 #pragma unroll
         for (int j = 0; j < TJ; ++j) {
             float bias = 0.f;
