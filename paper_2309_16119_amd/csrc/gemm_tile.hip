@@ -674,8 +674,8 @@ static hipError_t launch_bits_dir(const GemmArgs &a, hipStream_t stream) {
             const int C = BWD ? a.w.N : a.w.K;
             const double steps = (double)C / 64.0;
             const BigPlan bp = big_plan(a.M, C, Cout);
-            double best = ((double)(bp.full / 256) + (bp.tail ? 1.0 / bp.split : 0.0)) * (bp.mt == 128 ? 1.05 : 1.83) * steps;
-            if (bp.split > 1) best += (bp.mt == 128 ? 9.0 : 4.0) + (double)bp.partial_bytes() / 4.0e6;
+            double best = ((double)(bp.full / 256) + (bp.tail ? 1.0 / bp.split : 0.0)) * (bp.mt == 128 ? 1.0 : 1.83) * steps;
+            if (bp.split > 1) best += (bp.mt == 128 ? 12.0 : 9.0) + (double)bp.partial_bytes() / 4.0e6;
             pick = PICK_BIG;
             for (const Variant &v : vs) {
                 const long tiles = (long)((a.M + v.mt - 1) / v.mt) * ((Cout + v.ct - 1) / v.ct);
