@@ -283,6 +283,9 @@ hipError_t launch_lora_down(const DownArgs &a, hipStream_t stream) {
 // accumulate flag.  No atomics (device-scope fp32 atomics bypass the per-XCD L2 and are slow)
 // and no zero-fill of the outputs.
 // ---------------------------------------------------------------------------
+// Up to this many rows go in one chunk (measured per call: 5.9 - 6.5 against 7.9 - 8.1 us at 33 - 64
+// rows; at 128 rows the single launch is no quicker than the pair).
+constexpr int GRAD_ONE_CHUNK_ROWS = 64;
 GradGeom grad_geom(int M, int K, int N, int r) {
     GradGeom g;
     g.cpl = r <= 16 ? 4 : 2;                        // columns per lane (8- or 4-byte loads)
@@ -295,6 +298,7 @@ GradGeom grad_geom(int M, int K, int N, int r) {
     const int max_chunks = (M + 31) / 32;
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
+    if (M <= GRAD_ONE_CHUNK_ROWS) chunks = 1;       // few rows: one launch, no reduction launch behind it
     int rows = (M + chunks - 1) / chunks;
     rows = (rows + 3) / 4 * 4;
     g.rows_per_block = rows;
